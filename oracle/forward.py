@@ -1,0 +1,124 @@
+"""CPU oracle for the target model's batched verify forward pass.
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).  numpy, fp64 throughout, one operation
+per line of the textbook decoder; ``@`` (matmul) is the only library primitive used as a step.
+
+What it follows.  The paper (Section 2.1-2.2) says only that the target model verifies the k
+drafted tokens of each sequence in one decode-phase forward pass; the decoder itself is the
+standard pre-norm transformer the paper's models (Qwen3 / Llama class) use: RMSNorm, grouped-query
+attention with rotary position embedding, SwiGLU feed-forward, untied or tied output head.
+
+Conventions of this build (the paper does not state them):
+  * input row i of sequence b is token t[b,i] at position ctx_len[b] + i; t[b,0] is the last
+    emitted token (not yet cached), t[b,1..k] are the drafts; logits row i parameterises the
+    distribution of the token that follows t[b,i];
+  * RMSNorm: y = x / sqrt(mean(x^2) + eps) * g;
+  * rotary embedding pairs element j with j + head_dim/2 and rotates the pair by the angle
+    pos * theta^(-2j/head_dim); no long-context frequency scaling;
+  * query head j uses key/value head j // (n_q_heads // n_kv_heads);
+  * scores are scaled by 1/sqrt(head_dim); row i sees cache positions 0 .. ctx_len[b]+i;
+  * silu(z) = z / (1 + exp(-z)); all projections are bias-free, weights are [out, in].
+"""
+import numpy as np
+
+
+def rmsnorm(x, gain, eps):
+    x = np.asarray(x, dtype=np.float64)
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * np.asarray(gain, dtype=np.float64)
+
+
+def rope(x, positions, theta):
+    """x [T, H, dh], positions [T] -> rotated copy."""
+    x = np.asarray(x, dtype=np.float64)
+    dh = x.shape[-1]
+    half = dh // 2
+    j = np.arange(half, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * j / dh)
+    angle = np.asarray(positions, dtype=np.float64)[:, None] * inv_freq[None, :]      # [T, half]
+    c = np.cos(angle)[:, None, :]
+    s = np.sin(angle)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+def silu(z):
+    return z / (1.0 + np.exp(-z))
+
+
+def softmax(s):
+    e = np.exp(s - np.max(s))
+    return e / np.sum(e)
+
+
+def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len):
+    """One verify forward.
+
+    cfg      dict: n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab,
+                   rope_theta, rms_eps.
+    weights  dict: 'embed' [V,d], 'layers' (list of dicts with attn_norm [d], wq [Hq*dh,d],
+                   wk, wv [Hkv*dh,d], wo [d,Hq*dh], ffn_norm [d], wg, wu [F,d], wd [d,F]),
+                   'final_norm' [d], 'head' [V,d] or None (tied to 'embed').
+    kv_ctx   kv_ctx[layer][b] = (K [ctx_len[b], Hkv, dh], V [ctx_len[b], Hkv, dh]) cached context.
+    tokens   [B, k+1] int, ctx_len [B] int.
+
+    Returns (logits [B,k+1,V] fp64, new_kv) with new_kv[layer] = (K [B,k+1,Hkv,dh], V [...]),
+    the keys (after rotation) and values of the k+1 input positions.
+    """
+    tokens = np.asarray(tokens)
+    B, T = tokens.shape
+    Hq, Hkv, dh = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+    group = Hq // Hkv
+    eps, theta = cfg["rms_eps"], cfg["rope_theta"]
+    scale = 1.0 / np.sqrt(float(dh))
+
+    embed = np.asarray(weights["embed"], dtype=np.float64)
+    x = embed[tokens.reshape(-1)]                                   # [B*T, d]
+    pos = (np.asarray(ctx_len)[:, None] + np.arange(T)[None, :]).reshape(-1)
+
+    new_kv = []
+    for layer in range(cfg["n_layers"]):
+        w = weights["layers"][layer]
+        h = rmsnorm(x, w["attn_norm"], eps)
+        q = (h @ np.asarray(w["wq"], dtype=np.float64).T).reshape(B * T, Hq, dh)
+        kx = (h @ np.asarray(w["wk"], dtype=np.float64).T).reshape(B * T, Hkv, dh)
+        vx = (h @ np.asarray(w["wv"], dtype=np.float64).T).reshape(B * T, Hkv, dh)
+        q = rope(q, pos, theta)
+        kx = rope(kx, pos, theta)
+        new_kv.append((kx.reshape(B, T, Hkv, dh).copy(), vx.reshape(B, T, Hkv, dh).copy()))
+
+        attn = np.zeros((B * T, Hq, dh), dtype=np.float64)
+        for b in range(B):
+            Kc, Vc = kv_ctx[layer][b]
+            K_all = np.concatenate([np.asarray(Kc, dtype=np.float64).reshape(-1, Hkv, dh), kx[b * T:(b + 1) * T]])
+            V_all = np.concatenate([np.asarray(Vc, dtype=np.float64).reshape(-1, Hkv, dh), vx[b * T:(b + 1) * T]])
+            for i in range(T):
+                visible = int(ctx_len[b]) + i + 1                   # positions 0 .. ctx+i
+                for j in range(Hq):
+                    g = j // group
+                    s = (K_all[:visible, g, :] @ q[b * T + i, j, :]) * scale
+                    attn[b * T + i, j, :] = softmax(s) @ V_all[:visible, g, :]
+        x = x + attn.reshape(B * T, Hq * dh) @ np.asarray(w["wo"], dtype=np.float64).T
+
+        h = rmsnorm(x, w["ffn_norm"], eps)
+        gate = h @ np.asarray(w["wg"], dtype=np.float64).T
+        up = h @ np.asarray(w["wu"], dtype=np.float64).T
+        x = x + (silu(gate) * up) @ np.asarray(w["wd"], dtype=np.float64).T
+
+    head = weights.get("head")
+    head = embed if head is None else np.asarray(head, dtype=np.float64)
+    logits = rmsnorm(x, weights["final_norm"], eps) @ head.T
+    return logits.reshape(B, T, -1), new_kv
+
+
+def prefill(cfg, weights, tokens):
+    """Cache contents for context tokens [B, C]: a verify forward from an empty cache.
+
+    Returns kv_ctx in the form ``verify_forward`` takes.
+    """
+    tokens = np.asarray(tokens)
+    B = tokens.shape[0]
+    Hkv, dh = cfg["n_kv_heads"], cfg["head_dim"]
+    empty = [[(np.zeros((0, Hkv, dh)), np.zeros((0, Hkv, dh))) for _ in range(B)]
+             for _ in range(cfg["n_layers"])]
+    _, new_kv = verify_forward(cfg, weights, empty, tokens, np.zeros(B, dtype=np.int64))
+    return [[(new_kv[layer][0][b], new_kv[layer][1][b]) for b in range(B)] for layer in range(cfg["n_layers"])]

@@ -1,0 +1,191 @@
+"""Seeded synthetic inputs for the verify step: configurations, weights, contexts, page tables.
+
+This module serves both the HIP path and the CPU oracle and holds none of the method's
+arithmetic: it only draws random tensors of the shapes and distributions the workloads have,
+rounds them to the storage type, and moves data between the logical (per sequence) and the
+physical (paged pool) view by plain indexing.  It imports neither the oracle nor the product
+package.
+
+Recipe (all draws are functions of an integer seed through ``torch.Generator``):
+  * matrices and embedding ~ N(0, 0.02) (0.02 is the standard deviation), rounded to the
+    model's storage type; RMSNorm gains are 1;
+  * token ids uniform over the vocabulary; context lengths integer-uniform on a closed interval;
+  * cached context K and V entries ~ N(0, 1) rounded to the storage type (used where a real
+    prefill is too large for the CPU oracle);
+  * physical pages are handed out from a shuffled list (worst-case fragmentation) or in order.
+"""
+import math
+
+import numpy as np
+import torch
+
+PAGE_SIZE = 16
+DEFAULT_SEED = 20260427
+
+# name -> model description.  dtype is the storage type of weights and of the KV cache.
+MODELS = {
+    # Tiny fp32 decoder (BASELINE config 0): 2 layers, MHA, vocab 1024.
+    "tiny_fp32": dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn_dim=704,
+                      vocab=1024, rope_theta=1.0e4, rms_eps=1.0e-5, dtype="f32", tied_head=0),
+    # Small bf16 model for parity tests of the MFMA path: several tiles plus ragged tails in N and V.
+    "small_bf16": dict(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1280,
+                       vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0),
+    # Llama-3-8B-shaped (BASELINE config 1).
+    "llama8b_bf16": dict(n_layers=32, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
+                         vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0),
+}
+
+# name -> batch description of the verify step.
+WORKLOADS = {
+    "tiny_fp32_b4_ctx128_k3": dict(model="tiny_fp32", B=4, k=3, ctx_lo=128, ctx_hi=128, noise_std=0.5,
+                                   temperature=1.0),
+    "small_bf16_b5_k3": dict(model="small_bf16", B=5, k=3, ctx_lo=37, ctx_hi=700, noise_std=1.0,
+                             temperature=1.0),
+    "llama8b_b32_ctx1k-8k_k3": dict(model="llama8b_bf16", B=32, k=3, ctx_lo=1024, ctx_hi=8192, noise_std=1.0,
+                                    temperature=1.0),
+}
+
+
+def torch_dtype(name):
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+
+
+def _gen(seed, device):
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    return g
+
+
+def weight_shapes(cfg):
+    """Canonical, ordered list of (name, shape).  Matrices are [out_features, in_features]."""
+    d, Hq, Hkv, dh, F, V = (cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
+                            cfg["ffn_dim"], cfg["vocab"])
+    out = [("embed", (V, d))]
+    for l in range(cfg["n_layers"]):
+        out += [(f"l{l}.attn_norm", (d,)), (f"l{l}.wq", (Hq * dh, d)), (f"l{l}.wk", (Hkv * dh, d)),
+                (f"l{l}.wv", (Hkv * dh, d)), (f"l{l}.wo", (d, Hq * dh)), (f"l{l}.ffn_norm", (d,)),
+                (f"l{l}.wg", (F, d)), (f"l{l}.wu", (F, d)), (f"l{l}.wd", (d, F))]
+    out.append(("final_norm", (d,)))
+    if not cfg.get("tied_head", 0):
+        out.append(("head", (V, d)))
+    return out
+
+
+def make_weights(cfg, seed=DEFAULT_SEED, device="cpu", std=0.02):
+    """Ordered dict name -> tensor in the model's storage type on ``device``."""
+    g = _gen(seed, device)
+    dt = torch_dtype(cfg["dtype"])
+    weights = {}
+    for name, shape in weight_shapes(cfg):
+        if name.endswith("norm"):
+            weights[name] = torch.ones(shape, dtype=dt, device=device)
+        else:
+            weights[name] = (torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std).to(dt)
+    return weights
+
+
+def weights_for_oracle(cfg, weights):
+    """The same values as nested fp32 numpy arrays in the layout the oracle's forward takes."""
+    def f(name):
+        return weights[name].detach().to("cpu", torch.float32).numpy()
+    layers = []
+    for l in range(cfg["n_layers"]):
+        layers.append({k: f(f"l{l}.{k}") for k in
+                       ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd")})
+    return {"embed": f("embed"), "layers": layers, "final_norm": f("final_norm"),
+            "head": None if cfg.get("tied_head", 0) else f("head")}
+
+
+def make_batch(workload, seed=DEFAULT_SEED, shuffle_pages=True, extra_pages=8):
+    """Token ids, context lengths and page lists of one verify step (host side, numpy).
+
+    Returns dict: tokens0 [B] (the last emitted token of each sequence), ctx_len [B],
+    ctx_tokens (list of [ctx_len[b]] arrays), page_lists (list of int lists covering exactly the
+    context), n_pages (pool size: what the contexts need, what the step may add, plus slack).
+    """
+    cfg = MODELS[workload["model"]]
+    rng = np.random.Generator(np.random.Philox(int(seed) + 1))
+    B, k = workload["B"], workload["k"]
+    ctx_len = rng.integers(workload["ctx_lo"], workload["ctx_hi"] + 1, size=B).astype(np.int64)
+    tokens0 = rng.integers(0, cfg["vocab"], size=B).astype(np.int32)
+    ctx_tokens = [rng.integers(0, cfg["vocab"], size=int(c)).astype(np.int32) for c in ctx_len]
+    ctx_pages = [-(-int(c) // PAGE_SIZE) for c in ctx_len]
+    step_pages = [-(-(int(c) + k + 1) // PAGE_SIZE) for c in ctx_len]
+    n_pages = sum(step_pages) + extra_pages
+    order = rng.permutation(n_pages) if shuffle_pages else np.arange(n_pages)
+    page_lists, at = [], 0
+    for n in ctx_pages:
+        page_lists.append([int(p) for p in order[at:at + n]])
+        at += n
+    return dict(tokens0=tokens0, ctx_len=ctx_len, ctx_tokens=ctx_tokens, page_lists=page_lists,
+                n_pages=int(n_pages))
+
+
+def make_logical_kv(cfg, ctx_len, seed=DEFAULT_SEED, device="cpu"):
+    """Synthetic cached context: kv[layer][b] = (K, V), each [ctx_len[b], Hkv, dh] ~ N(0,1) in storage type."""
+    g = _gen(int(seed) + 2, device)
+    dt = torch_dtype(cfg["dtype"])
+    Hkv, dh = cfg["n_kv_heads"], cfg["head_dim"]
+    kv = []
+    for _ in range(cfg["n_layers"]):
+        per_seq = []
+        for c in ctx_len:
+            K = torch.randn((int(c), Hkv, dh), generator=g, device=device, dtype=torch.float32).to(dt)
+            V = torch.randn((int(c), Hkv, dh), generator=g, device=device, dtype=torch.float32).to(dt)
+            per_seq.append((K, V))
+        kv.append(per_seq)
+    return kv
+
+
+def kv_for_oracle(kv):
+    """kv[layer][b] = (K, V) tensors -> the same nesting with fp32 numpy arrays."""
+    return [[(K.detach().to("cpu", torch.float32).numpy(), V.detach().to("cpu", torch.float32).numpy())
+             for (K, V) in per_seq] for per_seq in kv]
+
+
+def round_to_storage(array, dtype_name):
+    """Round an fp64/fp32 numpy array to the storage type and return it as fp32 numpy."""
+    t = torch.from_numpy(np.ascontiguousarray(array, dtype=np.float32))
+    return t.to(torch_dtype(dtype_name)).to(torch.float32).numpy()
+
+
+def make_sampler_case(B, k, V, seed=DEFAULT_SEED, logit_std=3.0, noise_std=1.0, temperature=1.0):
+    """Free-standing sampler inputs: logits ~ N(0, logit_std), q = softmax((logits + noise)/T), drafts ~ q.
+
+    Row i of q is built from logits row i (the row that judges draft i+1).  numpy, fp32.
+    """
+    rng = np.random.Generator(np.random.Philox(int(seed) + 3))
+    logits = (rng.standard_normal((B, k + 1, V)) * logit_std).astype(np.float32)
+    noisy = (logits[:, :k, :].astype(np.float64) + rng.standard_normal((B, k, V)) * noise_std) / temperature
+    noisy -= noisy.max(axis=-1, keepdims=True)
+    q = np.exp(noisy)
+    q /= q.sum(axis=-1, keepdims=True)
+    q = q.astype(np.float32)
+    cdf = np.cumsum(q.astype(np.float64), axis=-1)
+    u = rng.random((B, k, 1)) * cdf[..., -1:]
+    draft = np.minimum((cdf < u).sum(axis=-1), V - 1).astype(np.int32)
+    return logits, q, draft
+
+
+def draw_from(prob, rng):
+    """One categorical draw per row of ``prob`` [..., V] by inverse CDF (input generation only)."""
+    cdf = np.cumsum(np.asarray(prob, dtype=np.float64), axis=-1)
+    u = rng.random(cdf.shape[:-1] + (1,)) * cdf[..., -1:]
+    return np.minimum((cdf < u).sum(axis=-1), prob.shape[-1] - 1).astype(np.int32)
+
+
+def noisy_draft_distribution(logits_row, noise, temperature):
+    """q = softmax((logits + noise) / T) in fp64, returned as fp32 (the draft model stand-in)."""
+    z = (np.asarray(logits_row, dtype=np.float64) + noise) / temperature
+    z = z - z.max(axis=-1, keepdims=True)
+    e = np.exp(z)
+    return (e / e.sum(axis=-1, keepdims=True)).astype(np.float32)
+
+
+def ceil_div(a, b):
+    return -(-a // b)
+
+
+__all__ = ["PAGE_SIZE", "DEFAULT_SEED", "MODELS", "WORKLOADS", "torch_dtype", "weight_shapes", "make_weights",
+           "weights_for_oracle", "make_batch", "make_logical_kv", "kv_for_oracle", "round_to_storage",
+           "make_sampler_case", "draw_from", "noisy_draft_distribution", "ceil_div", "math"]
