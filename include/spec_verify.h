@@ -1,0 +1,205 @@
+/*
+ * spec_verify.h - C ABI of the MI355X (gfx950) speculative-decoding verify step.
+ *
+ * The operation (paper: Introduction, paragraph introducing speculative decoding; Section 2.1,
+ * "lossless acceleration"; Section 2.2, acceptance length): a draft proposes k tokens per
+ * sequence, the target model scores all k+1 positions of every sequence in ONE decode-phase
+ * forward pass against its KV cache, a rejection procedure that preserves the target's output
+ * distribution keeps the longest valid draft prefix and draws one more token, and the cache keeps
+ * only what was accepted.  One "step" is
+ *     spec_verify_forward -> spec_reject_sample -> spec_commit_kv
+ * enqueued on one HIP stream; none of the three synchronises with the host or allocates.
+ *
+ * General rules
+ *   - Every function returns SPEC_OK (0) or a negative spec_status; nothing throws, aborts or
+ *     exits.  spec_last_error() gives a thread-local message for the last failure.
+ *   - Pointers named dev_* are device memory owned by the caller (e.g. torch.empty on the GPU);
+ *     they are only borrowed until the enqueued work has run.  Pointers named host_* are host memory.
+ *   - Opaque handles (spec_model, spec_kv) are owned by the library; release them with the
+ *     matching destroy/free.  Handles are bound to the device that was current at creation.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Arguments are validated on the host before anything is launched.
+ */
+#ifndef SPEC_VERIFY_H
+#define SPEC_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPEC_OK = 0,
+    SPEC_EINVAL = -1,        /* bad argument (null pointer, size out of range, workspace too small) */
+    SPEC_ENOMEM = -2,        /* page pool exhausted or device allocation failed */
+    SPEC_EHIP = -3,          /* a HIP call failed; message holds hipGetErrorString */
+    SPEC_ESTATE = -4,        /* call not valid in the handle's current state */
+    SPEC_EUNSUPPORTED = -5   /* shape or type outside what the kernels cover */
+} spec_status;
+
+enum { SPEC_F32 = 0, SPEC_BF16 = 1 };
+enum { SPEC_MAX_DRAFT = 15 };          /* largest k */
+enum { SPEC_PAGE_SIZE = 16 };          /* tokens per KV page */
+
+const char* spec_last_error(void);
+
+/* ---------------------------------------------------------------- model ------------------------------------ */
+
+/* Plain data, copied by spec_model_create.  Dense pre-norm decoder: RMSNorm, grouped-query attention
+ * with rotary embedding (pair j with j + head_dim/2, angle pos * rope_theta^(-2j/head_dim)), SwiGLU. */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
+    float rope_theta, rms_eps;
+    int32_t dtype;             /* SPEC_F32 or SPEC_BF16: storage type of weights and of the KV cache */
+    int32_t tied_head;         /* 1: output head = embedding matrix */
+} spec_model_desc;
+
+typedef struct spec_model spec_model;
+typedef struct spec_kv spec_kv;
+
+/* Number of weight pointers spec_model_create expects: 1 + 9*n_layers + 1 + (tied_head ? 0 : 1). */
+int32_t spec_model_weight_count(const spec_model_desc* desc);
+
+/*
+ * dev_weights[i], all in `dtype`, row-major [out_features, in_features], in this order:
+ *   embed [vocab, d_model];
+ *   per layer: attn_norm [d], wq [Hq*dh, d], wk [Hkv*dh, d], wv [Hkv*dh, d], wo [d, Hq*dh],
+ *              ffn_norm [d], wg [ffn, d], wu [ffn, d], wd [d, ffn];
+ *   final_norm [d]; head [vocab, d] unless tied_head.
+ * SPEC_F32: the pointers are borrowed for the model's lifetime (kernels read them in place).
+ * SPEC_BF16: the matrices are re-tiled once into a library-owned device buffer laid out for the
+ * MFMA kernels (one hipMalloc of about the model's size); afterwards only embed and the norm
+ * gains are still read from the caller's buffers.  BF16 needs head_dim == 128,
+ * d_model % 128 == 0, ffn_dim % 128 == 0 and n_q_heads % n_kv_heads == 0, else SPEC_EUNSUPPORTED.
+ * Synchronises the device.  (Paper: the target model of Section 2.1; its shape is the caller's.)
+ */
+spec_status spec_model_create(const spec_model_desc* desc, const void* const* dev_weights, int32_t n_weights,
+                              spec_model** out);
+spec_status spec_model_destroy(spec_model* model);
+
+/* ---------------------------------------------------------------- KV cache --------------------------------- */
+
+/*
+ * Paged KV cache (the cache the decode-phase verification of Section 2.2 runs against; paging and
+ * layout are this library's).  The pool is caller-owned device memory of spec_kv_pool_bytes():
+ *   pool[layer_pool][page][K=0|V=1][kv_head] -> one block of SPEC_PAGE_SIZE * head_dim elements,
+ * layer_pool = layer if layer_alias_mod == 0, else layer % layer_alias_mod (several layers share a
+ * pool region: a way to run a cache larger than memory through the real access pattern; each
+ * layer writes its new entries before it reads, cached context then is per region, not per layer).
+ * Inside a block, element (token t of the page, channel c) sits at spec_kv_block_offset().
+ * Page ids are 0 .. n_pages-1; slot = page * SPEC_PAGE_SIZE + t.
+ *
+ * Bookkeeping lives on the device (context length and page list per sequence, a stack of free
+ * pages) so that a step needs no host round trip.  A fresh cache's stack pops 0, 1, 2, ...
+ */
+int64_t spec_kv_pool_bytes(const spec_model* model, int64_t n_pages, int32_t layer_alias_mod);
+spec_status spec_kv_alloc(const spec_model* model, int32_t max_seqs, int32_t max_ctx_len, int64_t n_pages,
+                          void* dev_pool, int32_t layer_alias_mod, spec_kv** out);
+spec_status spec_kv_free(spec_kv* kv);
+
+/* Element offset (in elements) of (t, c) inside a K (is_v = 0) or V (is_v = 1) block; -1 on bad input. */
+int64_t spec_kv_block_offset(const spec_kv* kv, int32_t is_v, int32_t t, int32_t c);
+/* Element offset of the block of (layer, page, is_v, kv_head) from the start of the pool; -1 on bad input. */
+int64_t spec_kv_block_base(const spec_kv* kv, int32_t layer, int64_t page, int32_t is_v, int32_t kv_head);
+
+/*
+ * Host call: install sequence `seq` (0 <= seq < max_seqs) with cached length ctx_len on the given
+ * pages (exactly ceil(ctx_len / SPEC_PAGE_SIZE) distinct free page ids, possibly fragmented).  The
+ * caller fills the pages' contents itself.  Synchronises the device if steps have run since the
+ * last host call.  SPEC_EINVAL for pages in use or out of range.
+ */
+spec_status spec_kv_seq_assign(spec_kv* kv, int32_t seq, int32_t ctx_len, const int32_t* host_page_ids,
+                               int32_t n_page_ids);
+
+/*
+ * Host call (synchronises): copy the bookkeeping out.  Any pointer may be NULL.
+ *   host_ctx_len [max_seqs]; host_n_pages [max_seqs] pages held; host_page_table
+ *   [max_seqs * spec_kv_max_pages_per_seq()] (-1 padded); host_free_stack [n_pages] bottom to top,
+ *   *host_n_free entries valid.  Returns SPEC_ENOMEM if a step ran out of pages since the last
+ *   call (the affected sequences were left untouched by that step), clearing the flag.
+ */
+spec_status spec_kv_get_state(spec_kv* kv, int32_t* host_ctx_len, int32_t* host_n_pages,
+                              int32_t* host_page_table, int32_t* host_free_stack, int64_t* host_n_free);
+int32_t spec_kv_max_pages_per_seq(const spec_kv* kv);
+
+/*
+ * Roll the bookkeeping back without a host round trip (re-running a step from the same state,
+ * abandoning a speculative branch).  spec_kv_snapshot copies context lengths, page lists and
+ * the free stack into dev_buf (spec_kv_state_bytes() bytes, caller-owned); spec_kv_restore
+ * copies them back.  Page contents are not saved: positions beyond the restored lengths are
+ * dead anyway.  Both are asynchronous on `stream`; a buffer that was never the target of
+ * spec_kv_snapshot on this cache gives SPEC_ESTATE.
+ */
+size_t spec_kv_state_bytes(const spec_kv* kv);
+spec_status spec_kv_snapshot(spec_kv* kv, void* dev_buf, void* stream);
+spec_status spec_kv_restore(spec_kv* kv, const void* dev_buf, void* stream);
+
+/* ---------------------------------------------------------------- the step ---------------------------------- */
+
+/*
+ * Verify forward (Section 2.1-2.2: the target scores all drafted positions in one decode pass).
+ * Batch entry b is sequence dev_seq_ids[b] (distinct ids); its input row i (0..k) is token
+ * dev_tokens[b*(k+1)+i] at position ctx_len+i: row 0 is the last emitted token (not cached yet),
+ * rows 1..k are the drafts.  The call reserves pages for positions ctx..ctx+k, writes their K/V
+ * there, and writes dev_logits[b][i][:] (fp32, [B, k+1, vocab]) = the target's logits for the token
+ * following row i, which sees cache positions 0..ctx+i.  ctx_len is not changed (spec_commit_kv does).
+ * dev_workspace: at least spec_verify_workspace_bytes(model, kv, B, k) bytes (0 = bad arguments), 256-byte
+ * aligned; contents need not be preserved between calls.  Query the size again after spec_tune_set.
+ * Errors: SPEC_EINVAL (null, B < 1, k < 0, k > SPEC_MAX_DRAFT, workspace too small, kv of another
+ * model), SPEC_ENOMEM (the pool cannot hold k+1 more positions for every batch entry),
+ * SPEC_EHIP.  Asynchronous on `stream`.
+ */
+size_t spec_verify_workspace_bytes(const spec_model* model, const spec_kv* kv, int32_t B, int32_t k);
+spec_status spec_verify_forward(spec_model* model, spec_kv* kv, int32_t B, int32_t k,
+                                const int32_t* dev_seq_ids, const int32_t* dev_tokens, float* dev_logits,
+                                void* dev_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Lossless rejection sampling (the rejection procedure of Section 2.1; acceptance length as in
+ * Section 2.2).  p_i = softmax(dev_logits[b][i][:] / temperature).  For i = 0..k-1 in order: draft
+ * x = dev_draft_tokens[b][i] is kept iff u * q(x) < p_i(x) (u in [0,1), compared in fp64), where
+ * q = dev_q[b][i][:] are the probabilities the draft was sampled from; stop at the first failure.
+ * With n kept: if n < k the next token is drawn from norm(max(0, p_n - q_n)) (from p_n if that
+ * residual is identically zero), else from p_k (bonus).  The draw is an exponential race,
+ * argmax_v w_v / (-ln u_v), ties to the lowest v.
+ * Random numbers: Philox4x32-10, key = (seed low word, seed high word), counter =
+ * (c0, i, b, step*4 + stream); accept: stream 0, c0 = 0, u = (word0 >> 8) * 2^-24;
+ * vocabulary entry v: stream 1, c0 = v >> 2, word v & 3, u_v = ((word >> 9) + 0.5) * 2^-23.
+ * Outputs: dev_accept_len[b] = n; dev_out_tokens[b][0..k] = the n kept drafts, the drawn token,
+ * then -1.  dev_dbg [B, k, 3] fp32, may be NULL: P, Q, u of every accept test evaluated (NaN elsewhere).
+ * Needs B >= 1, 0 <= k <= SPEC_MAX_DRAFT, V >= 1, temperature > 0, step < 2^30; draft tokens
+ * outside [0, V) are treated as rejected.  dev_q and dev_draft_tokens may be NULL when k == 0.
+ * dev_workspace: at least spec_sample_workspace_bytes(B, k) bytes.  Asynchronous on `stream`.
+ */
+size_t spec_sample_workspace_bytes(int32_t B, int32_t k);
+spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
+                               const int32_t* dev_draft_tokens, float temperature, uint64_t seed, uint64_t step,
+                               int32_t* dev_accept_len, int32_t* dev_out_tokens, float* dev_dbg,
+                               void* dev_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * KV commit (keeps the accepted prefix; the paper leaves the cache handling to the serving engine).
+ * For batch entry b with n = dev_accept_len[b] (values outside 0..k are clamped): positions
+ * ctx..ctx+n stay, the new context length is ctx+n+1 (the drawn token is the next step's row 0 and
+ * has no entry yet); pages wholly beyond the new length return to the free stack, a sequence's
+ * last page first, batch entries in order.  k must be the k of the preceding spec_verify_forward.
+ * Outputs (either may be NULL): dev_new_ctx_len [B]; dev_commit_slots [B, k+1] = pool slot of each
+ * kept position, -1 for dropped ones.  Asynchronous on `stream`.
+ */
+spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                           const int32_t* dev_accept_len, int32_t* dev_new_ctx_len, int32_t* dev_commit_slots,
+                           void* stream);
+
+/* ---------------------------------------------------------------- tuning / introspection -------------------- */
+
+/* Set a launch parameter by name (split factors and the like); unknown names give SPEC_EINVAL.
+ * Results never depend on these beyond floating-point summation order. */
+spec_status spec_tune_set(const char* name, int32_t value);
+int32_t spec_tune_get(const char* name);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEC_VERIFY_H */

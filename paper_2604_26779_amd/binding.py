@@ -1,0 +1,226 @@
+"""ctypes binding of libspecverify.so: same names as the C ABI (include/spec_verify.h), argument
+marshalling only.  Device buffers are torch tensors (their ``data_ptr()`` is what crosses the
+boundary); no step of the verify path runs in Python or in torch.
+
+The library must have been built (``python -m paper_2604_26779_amd.build`` or
+``__graft_entry__.build()``); loading fails loudly otherwise, there is no fallback.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspecverify.so")
+
+SPEC_OK, SPEC_EINVAL, SPEC_ENOMEM, SPEC_EHIP, SPEC_ESTATE, SPEC_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+SPEC_F32, SPEC_BF16 = 0, 1
+SPEC_MAX_DRAFT = 15
+SPEC_PAGE_SIZE = 16
+
+EXPORTS = [
+    "spec_last_error", "spec_model_weight_count", "spec_model_create", "spec_model_destroy", "spec_kv_pool_bytes",
+    "spec_kv_alloc", "spec_kv_free", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
+    "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
+    "spec_verify_workspace_bytes", "spec_verify_forward", "spec_sample_workspace_bytes", "spec_reject_sample",
+    "spec_commit_kv", "spec_tune_set", "spec_tune_get",
+]
+
+
+class SpecError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("spec_status %d: %s" % (status, message))
+        self.status = status
+
+
+class spec_model_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim",
+                                              "ffn_dim", "vocab")] + \
+               [("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("dtype", ctypes.c_int32),
+                ("tied_head", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libspecverify.so is not built: run `python -m paper_2604_26779_amd.build` "
+                              "(there is no CPU or PyTorch fallback for the verify step)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u64, sz, f32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64,
+                                      ctypes.c_size_t, ctypes.c_float)
+        sig = {
+            "spec_last_error": (ctypes.c_char_p, []),
+            "spec_model_weight_count": (i32, [vp]),
+            "spec_model_create": (i32, [vp, vp, i32, vp]),
+            "spec_model_destroy": (i32, [vp]),
+            "spec_kv_pool_bytes": (i64, [vp, i64, i32]),
+            "spec_kv_alloc": (i32, [vp, i32, i32, i64, vp, i32, vp]),
+            "spec_kv_free": (i32, [vp]),
+            "spec_kv_block_offset": (i64, [vp, i32, i32, i32]),
+            "spec_kv_block_base": (i64, [vp, i32, i64, i32, i32]),
+            "spec_kv_seq_assign": (i32, [vp, i32, i32, vp, i32]),
+            "spec_kv_get_state": (i32, [vp, vp, vp, vp, vp, vp]),
+            "spec_kv_max_pages_per_seq": (i32, [vp]),
+            "spec_kv_state_bytes": (sz, [vp]),
+            "spec_kv_snapshot": (i32, [vp, vp, vp]),
+            "spec_kv_restore": (i32, [vp, vp, vp]),
+            "spec_verify_workspace_bytes": (sz, [vp, vp, i32, i32]),
+            "spec_verify_forward": (i32, [vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]),
+            "spec_sample_workspace_bytes": (sz, [i32, i32]),
+            "spec_reject_sample": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp, sz, vp]),
+            "spec_commit_kv": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
+            "spec_tune_set": (i32, [ctypes.c_char_p, i32]),
+            "spec_tune_get": (i32, [ctypes.c_char_p]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def spec_last_error():
+    return lib().spec_last_error().decode()
+
+
+def _check(status):
+    if status != SPEC_OK:
+        raise SpecError(status, spec_last_error())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, torch.Tensor):
+        assert t.is_contiguous()
+        return t.data_ptr()
+    return int(t)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def make_desc(cfg):
+    d = spec_model_desc()
+    for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "ffn_dim", "vocab"):
+        setattr(d, n, int(cfg[n]))
+    d.rope_theta, d.rms_eps = float(cfg["rope_theta"]), float(cfg["rms_eps"])
+    d.dtype = {"f32": SPEC_F32, "bf16": SPEC_BF16}[cfg["dtype"]]
+    d.tied_head = int(cfg.get("tied_head", 0))
+    return d
+
+
+def spec_model_weight_count(cfg):
+    d = make_desc(cfg)
+    return lib().spec_model_weight_count(ctypes.byref(d))
+
+
+def spec_model_create(cfg, weights):
+    """weights: device tensors in the header's canonical order.  Returns an opaque handle."""
+    d = make_desc(cfg)
+    arr = (ctypes.c_void_p * len(weights))(*[_ptr(w) for w in weights])
+    out = ctypes.c_void_p()
+    _check(lib().spec_model_create(ctypes.byref(d), arr, len(weights), ctypes.byref(out)))
+    return out
+
+
+def spec_model_destroy(model):
+    _check(lib().spec_model_destroy(model))
+
+
+def spec_kv_pool_bytes(model, n_pages, layer_alias_mod=0):
+    return lib().spec_kv_pool_bytes(model, n_pages, layer_alias_mod)
+
+
+def spec_kv_alloc(model, max_seqs, max_ctx_len, n_pages, pool, layer_alias_mod=0):
+    out = ctypes.c_void_p()
+    _check(lib().spec_kv_alloc(model, max_seqs, max_ctx_len, n_pages, _ptr(pool), layer_alias_mod, ctypes.byref(out)))
+    return out
+
+
+def spec_kv_free(kv):
+    _check(lib().spec_kv_free(kv))
+
+
+def spec_kv_block_offset(kv, is_v, t, c):
+    return lib().spec_kv_block_offset(kv, is_v, t, c)
+
+
+def spec_kv_block_base(kv, layer, page, is_v, kv_head):
+    return lib().spec_kv_block_base(kv, layer, page, is_v, kv_head)
+
+
+def spec_kv_seq_assign(kv, seq, ctx_len, page_ids):
+    ids = np.ascontiguousarray(page_ids, dtype=np.int32)
+    _check(lib().spec_kv_seq_assign(kv, seq, ctx_len, ids.ctypes.data, len(ids)))
+
+
+def spec_kv_max_pages_per_seq(kv):
+    return lib().spec_kv_max_pages_per_seq(kv)
+
+
+def spec_kv_get_state(kv, max_seqs, n_pages):
+    """Returns dict(ctx_len, n_pages, page_table [max_seqs, max_pages], free_stack (valid part))."""
+    mp = spec_kv_max_pages_per_seq(kv)
+    ctx = np.zeros(max_seqs, dtype=np.int32)
+    held = np.zeros(max_seqs, dtype=np.int32)
+    table = np.zeros((max_seqs, mp), dtype=np.int32)
+    stack = np.zeros(n_pages, dtype=np.int32)
+    nfree = ctypes.c_int64()
+    _check(lib().spec_kv_get_state(kv, ctx.ctypes.data, held.ctypes.data, table.ctypes.data, stack.ctypes.data,
+                                   ctypes.byref(nfree)))
+    return dict(ctx_len=ctx, n_pages=held, page_table=table, free_stack=stack[:nfree.value].copy())
+
+
+def spec_kv_state_bytes(kv):
+    return lib().spec_kv_state_bytes(kv)
+
+
+def spec_kv_snapshot(kv, buf, stream=None):
+    _check(lib().spec_kv_snapshot(kv, _ptr(buf), _stream(stream)))
+
+
+def spec_kv_restore(kv, buf, stream=None):
+    _check(lib().spec_kv_restore(kv, _ptr(buf), _stream(stream)))
+
+
+def spec_verify_workspace_bytes(model, kv, B, k):
+    return lib().spec_verify_workspace_bytes(model, kv, B, k)
+
+
+def spec_verify_forward(model, kv, B, k, seq_ids, tokens, logits, workspace, stream=None):
+    _check(lib().spec_verify_forward(model, kv, B, k, _ptr(seq_ids), _ptr(tokens), _ptr(logits), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def spec_sample_workspace_bytes(B, k):
+    return lib().spec_sample_workspace_bytes(B, k)
+
+
+def spec_reject_sample(B, k, V, logits, q, draft_tokens, temperature, seed, step, accept_len, out_tokens, dbg,
+                       workspace, stream=None):
+    _check(lib().spec_reject_sample(B, k, V, _ptr(logits), _ptr(q), _ptr(draft_tokens), float(temperature),
+                                    int(seed), int(step), _ptr(accept_len), _ptr(out_tokens), _ptr(dbg),
+                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def spec_commit_kv(kv, B, k, seq_ids, accept_len, new_ctx_len, commit_slots, stream=None):
+    _check(lib().spec_commit_kv(kv, B, k, _ptr(seq_ids), _ptr(accept_len), _ptr(new_ctx_len), _ptr(commit_slots),
+                                _stream(stream)))
+
+
+def spec_tune_set(name, value):
+    _check(lib().spec_tune_set(name.encode(), int(value)))
+
+
+def spec_tune_get(name):
+    return lib().spec_tune_get(name.encode())

@@ -1,0 +1,426 @@
+// Host side of the C ABI: handles, argument checks, cache bookkeeping mirror, dispatch to the
+// fp32 or bf16 forward.  Every kernel lives in the other translation units.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <map>
+#include <mutex>
+
+#include "common.h"
+
+namespace specv {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+}
+
+static std::mutex g_tune_mutex;
+static std::map<std::string, int>& tune_table()
+{
+    // launch parameters with their defaults; see gemm_bf16.hip / attn_bf16.hip for their meaning
+    static std::map<std::string, int> t = {
+        {"gemm_wg_target", 512},   // split K until a GEMM launches about this many workgroups
+        {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
+        {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
+        {"attn_chunk_pages", 32},  // KV pages per attention workgroup
+    };
+    return t;
+}
+
+int tune(const char* name)
+{
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    auto it = tune_table().find(name);
+    return it == tune_table().end() ? 0 : it->second;
+}
+
+}  // namespace specv
+
+using namespace specv;
+
+extern "C" const char* spec_last_error(void) { return g_error; }
+
+extern "C" spec_status spec_tune_set(const char* name, int32_t value)
+{
+    if (!name) { set_error("spec_tune_set: null name"); return SPEC_EINVAL; }
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    auto it = tune_table().find(name);
+    if (it == tune_table().end()) { set_error("spec_tune_set: unknown parameter '%s'", name); return SPEC_EINVAL; }
+    if (value < 0) { set_error("spec_tune_set: negative value"); return SPEC_EINVAL; }
+    it->second = value;
+    return SPEC_OK;
+}
+
+extern "C" int32_t spec_tune_get(const char* name)
+{
+    if (!name) return -1;
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    auto it = tune_table().find(name);
+    return it == tune_table().end() ? -1 : it->second;
+}
+
+// ------------------------------------------------------------------------------------------ model
+
+extern "C" int32_t spec_model_weight_count(const spec_model_desc* d)
+{
+    if (!d || d->n_layers < 0) return -1;
+    return 1 + 9 * d->n_layers + 1 + (d->tied_head ? 0 : 1);
+}
+
+static spec_status check_desc(const spec_model_desc& d)
+{
+    if (d.n_layers < 1 || d.d_model < 1 || d.n_q_heads < 1 || d.n_kv_heads < 1 || d.head_dim < 2 || d.ffn_dim < 1 ||
+        d.vocab < 1 || !(d.rope_theta > 0.f) || !(d.rms_eps >= 0.f)) {
+        set_error("spec_model_create: non-positive size in the description");
+        return SPEC_EINVAL;
+    }
+    if (d.n_q_heads % d.n_kv_heads) { set_error("spec_model_create: n_q_heads must be a multiple of n_kv_heads"); return SPEC_EUNSUPPORTED; }
+    if (d.dtype != SPEC_F32 && d.dtype != SPEC_BF16) { set_error("spec_model_create: unknown dtype"); return SPEC_EINVAL; }
+    if (d.dtype == SPEC_BF16) {
+        if (d.head_dim != 128 || d.d_model % 128 || d.ffn_dim % 128) {
+            set_error("spec_model_create: the bf16 path needs head_dim == 128 and d_model, ffn_dim multiples of 128");
+            return SPEC_EUNSUPPORTED;
+        }
+        int rows = d.n_q_heads / d.n_kv_heads;
+        if (rows * (SPEC_MAX_DRAFT + 1) > 256 && rows > 16) { set_error("spec_model_create: more than 16 query heads per kv head"); return SPEC_EUNSUPPORTED; }
+    }
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void* const* dev_weights, int32_t n_weights,
+                                         spec_model** out)
+{
+    if (!desc || !dev_weights || !out) { set_error("spec_model_create: null pointer"); return SPEC_EINVAL; }
+    spec_status st = check_desc(*desc);
+    if (st != SPEC_OK) return st;
+    if (n_weights != spec_model_weight_count(desc)) {
+        set_error("spec_model_create: expected %d weight pointers, got %d", spec_model_weight_count(desc), n_weights);
+        return SPEC_EINVAL;
+    }
+    for (int i = 0; i < n_weights; ++i)
+        if (!dev_weights[i]) { set_error("spec_model_create: weight pointer %d is null", i); return SPEC_EINVAL; }
+    spec_model* m = new (std::nothrow) spec_model();
+    if (!m) { set_error("spec_model_create: out of host memory"); return SPEC_ENOMEM; }
+    m->desc = *desc;
+    m->w.assign(dev_weights, dev_weights + n_weights);
+    SPEC_HIP_TRY(hipGetDevice(&m->device));
+
+    if (desc->dtype == SPEC_BF16) {
+        const spec_model_desc& d = *desc;
+        int L = d.n_layers, D = d.d_model, F = d.ffn_dim;
+        int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim;
+        size_t elems = 0;
+        elems += (size_t)L * (bf16_packed_elems(nq + 2 * nkv, D) + bf16_packed_elems(D, nq) + bf16_packed_elems(2 * F, D) +
+                              bf16_packed_elems(D, F));
+        elems += bf16_packed_elems(d.vocab, D);
+        m->arena_bytes = elems * sizeof(bf16_t);
+        hipError_t e = hipMalloc(&m->arena, m->arena_bytes);
+        if (e != hipSuccess) {
+            set_error("spec_model_create: hipMalloc of %zu bytes for the tiled weights failed: %s", m->arena_bytes, hipGetErrorString(e));
+            delete m;
+            return SPEC_ENOMEM;
+        }
+        bf16_t* at = (bf16_t*)m->arena;
+        m->wqkv.resize(L); m->wo.resize(L); m->wgu.resize(L); m->wd.resize(L);
+        auto pack = [&](std::initializer_list<const void*> parts, std::initializer_list<int> rows, int K, PackedW* pw) -> spec_status {
+            std::vector<const bf16_t*> p;
+            for (auto q : parts) p.push_back((const bf16_t*)q);
+            std::vector<int> r(rows);
+            int N = 0;
+            for (int x : r) N += x;
+            spec_status s2 = bf16_pack_matrix(p.data(), r.data(), (int)p.size(), K, at, pw, nullptr);
+            at += bf16_packed_elems(N, K);
+            return s2;
+        };
+        for (int l = 0; l < L && st == SPEC_OK; ++l) {
+            st = pack({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {nq, nkv, nkv}, D, &m->wqkv[l]);
+            if (st == SPEC_OK) st = pack({m->layer_w(l, 4)}, {D}, nq, &m->wo[l]);
+            if (st == SPEC_OK) st = pack({m->layer_w(l, 6), m->layer_w(l, 7)}, {F, F}, D, &m->wgu[l]);
+            if (st == SPEC_OK) st = pack({m->layer_w(l, 8)}, {D}, F, &m->wd[l]);
+        }
+        if (st == SPEC_OK) st = pack({m->head_w()}, {d.vocab}, D, &m->head);
+        if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }
+        if (st != SPEC_OK) { (void)hipFree(m->arena); delete m; return st; }
+    }
+    *out = m;
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_model_destroy(spec_model* m)
+{
+    if (!m) return SPEC_OK;
+    if (m->arena) (void)hipFree(m->arena);
+    delete m;
+    return SPEC_OK;
+}
+
+// ------------------------------------------------------------------------------------------ cache
+
+static int elem_bytes(int dtype) { return dtype == SPEC_F32 ? 4 : 2; }
+
+void spec_kv::recount()
+{
+    ub = Bounds();
+    for (int s = 0; s < max_seqs; ++s) {
+        if (h_ctx_len[s] > ub.max_ctx) ub.max_ctx = h_ctx_len[s];
+        ub.base_pages += h_n_held[s];
+    }
+}
+
+specv::KvView spec_kv::view() const
+{
+    KvView v;
+    v.pool = pool;
+    v.ctx_len = d_ctx_len;
+    v.n_held = d_n_held;
+    v.page_table = d_page_table;
+    v.max_pages = max_pages;
+    v.n_pages = n_pages;
+    v.n_kv_heads = model->desc.n_kv_heads;
+    v.head_dim = model->desc.head_dim;
+    v.alias_mod = alias_mod;
+    v.elem_bytes = elem_bytes(model->desc.dtype);
+    return v;
+}
+
+extern "C" int64_t spec_kv_pool_bytes(const spec_model* m, int64_t n_pages, int32_t alias)
+{
+    if (!m || n_pages < 1 || alias < 0) return -1;
+    int pools = alias > 0 ? (alias < m->desc.n_layers ? alias : m->desc.n_layers) : m->desc.n_layers;
+    return (int64_t)pools * n_pages * 2 * m->desc.n_kv_heads * SPEC_PAGE_SIZE * m->desc.head_dim * elem_bytes(m->desc.dtype);
+}
+
+extern "C" spec_status spec_kv_alloc(const spec_model* m, int32_t max_seqs, int32_t max_ctx_len, int64_t n_pages,
+                                     void* dev_pool, int32_t alias, spec_kv** out)
+{
+    if (!m || !dev_pool || !out) { set_error("spec_kv_alloc: null pointer"); return SPEC_EINVAL; }
+    if (max_seqs < 1 || max_ctx_len < 1 || n_pages < 1 || n_pages > (1 << 27) || alias < 0) {
+        set_error("spec_kv_alloc: size out of range");
+        return SPEC_EINVAL;
+    }
+    spec_kv* kv = new (std::nothrow) spec_kv();
+    if (!kv) { set_error("spec_kv_alloc: out of host memory"); return SPEC_ENOMEM; }
+    kv->model = m;
+    kv->device = m->device;
+    kv->max_seqs = max_seqs;
+    kv->max_pages = (int32_t)cdiv(max_ctx_len, SPEC_PAGE_SIZE);
+    kv->alias_mod = alias;
+    kv->n_pages = n_pages;
+    kv->pool = dev_pool;
+    kv->state_ints = (size_t)max_seqs * 2 + (size_t)max_seqs * kv->max_pages + (size_t)n_pages + 2;
+    hipError_t e = hipMalloc((void**)&kv->d_state, kv->state_ints * sizeof(int32_t));
+    if (e != hipSuccess) { set_error("spec_kv_alloc: hipMalloc failed: %s", hipGetErrorString(e)); delete kv; return SPEC_ENOMEM; }
+    int32_t* p = kv->d_state;
+    kv->d_ctx_len = p; p += max_seqs;
+    kv->d_n_held = p; p += max_seqs;
+    kv->d_page_table = p; p += (size_t)max_seqs * kv->max_pages;
+    kv->d_free_stack = p; p += n_pages;
+    kv->d_free_count = p; p += 1;
+    kv->d_error = p;
+    kv->h_ctx_len.assign(max_seqs, 0);
+    kv->h_n_held.assign(max_seqs, 0);
+    kv->h_page_table.assign((size_t)max_seqs * kv->max_pages, -1);
+    kv->h_free_stack.resize(n_pages);
+    for (int64_t i = 0; i < n_pages; ++i) kv->h_free_stack[i] = (int32_t)(n_pages - 1 - i);   // top of stack = page 0
+    kv->h_free_count = n_pages;
+    kv->device_ahead = false;
+    // upload
+    std::vector<int32_t> img(kv->state_ints, 0);
+    std::fill(img.begin() + 2 * max_seqs, img.begin() + 2 * max_seqs + (size_t)max_seqs * kv->max_pages, -1);
+    std::copy(kv->h_free_stack.begin(), kv->h_free_stack.end(), img.begin() + 2 * max_seqs + (size_t)max_seqs * kv->max_pages);
+    img[kv->state_ints - 2] = (int32_t)n_pages;
+    e = hipMemcpy(kv->d_state, img.data(), img.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { set_error("spec_kv_alloc: upload failed: %s", hipGetErrorString(e)); (void)hipFree(kv->d_state); delete kv; return SPEC_EHIP; }
+    *out = kv;
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_kv_free(spec_kv* kv)
+{
+    if (!kv) return SPEC_OK;
+    if (kv->d_state) (void)hipFree(kv->d_state);
+    delete kv;
+    return SPEC_OK;
+}
+
+extern "C" int32_t spec_kv_max_pages_per_seq(const spec_kv* kv) { return kv ? kv->max_pages : -1; }
+
+extern "C" int64_t spec_kv_block_offset(const spec_kv* kv, int32_t is_v, int32_t t, int32_t c)
+{
+    if (!kv || t < 0 || t >= SPEC_PAGE_SIZE || c < 0 || c >= kv->model->desc.head_dim || (is_v != 0 && is_v != 1)) return -1;
+    return kv_block_offset(kv->model->desc.dtype, is_v, t, c, kv->model->desc.head_dim);
+}
+
+extern "C" int64_t spec_kv_block_base(const spec_kv* kv, int32_t layer, int64_t page, int32_t is_v, int32_t h)
+{
+    if (!kv) return -1;
+    const spec_model_desc& d = kv->model->desc;
+    if (layer < 0 || layer >= d.n_layers || page < 0 || page >= kv->n_pages || (is_v != 0 && is_v != 1) || h < 0 || h >= d.n_kv_heads) return -1;
+    int lp = kv->alias_mod > 0 ? layer % kv->alias_mod : layer;
+    return ((((int64_t)lp * kv->n_pages + page) * 2 + is_v) * d.n_kv_heads + h) * SPEC_PAGE_SIZE * d.head_dim;
+}
+
+// bring the host mirror up to date with the device (synchronises)
+static spec_status kv_download(spec_kv* kv, int32_t* err_bits)
+{
+    SPEC_HIP_TRY(hipDeviceSynchronize());
+    std::vector<int32_t> img(kv->state_ints);
+    SPEC_HIP_TRY(hipMemcpy(img.data(), kv->d_state, img.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    size_t S = kv->max_seqs, PT = (size_t)kv->max_seqs * kv->max_pages;
+    std::copy(img.begin(), img.begin() + S, kv->h_ctx_len.begin());
+    std::copy(img.begin() + S, img.begin() + 2 * S, kv->h_n_held.begin());
+    std::copy(img.begin() + 2 * S, img.begin() + 2 * S + PT, kv->h_page_table.begin());
+    std::copy(img.begin() + 2 * S + PT, img.begin() + 2 * S + PT + kv->n_pages, kv->h_free_stack.begin());
+    kv->h_free_count = img[kv->state_ints - 2];
+    if (err_bits) *err_bits = img[kv->state_ints - 1];
+    if (img[kv->state_ints - 1] != 0) {
+        int32_t zero = 0;
+        SPEC_HIP_TRY(hipMemcpy(kv->d_error, &zero, sizeof(zero), hipMemcpyHostToDevice));
+    }
+    kv->device_ahead = false;
+    kv->recount();
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_kv_seq_assign(spec_kv* kv, int32_t seq, int32_t ctx_len, const int32_t* host_page_ids, int32_t n_ids)
+{
+    if (!kv) { set_error("spec_kv_seq_assign: null handle"); return SPEC_EINVAL; }
+    if (seq < 0 || seq >= kv->max_seqs || ctx_len < 0) { set_error("spec_kv_seq_assign: seq or ctx_len out of range"); return SPEC_EINVAL; }
+    int need = (int)cdiv(ctx_len, SPEC_PAGE_SIZE);
+    if (n_ids != need || need > kv->max_pages || (need > 0 && !host_page_ids)) {
+        set_error("spec_kv_seq_assign: %d page ids given, context of %d tokens needs %d (at most %d per sequence)", n_ids, ctx_len, need, kv->max_pages);
+        return SPEC_EINVAL;
+    }
+    if (kv->device_ahead) {
+        spec_status st = kv_download(kv, nullptr);
+        if (st != SPEC_OK) return st;
+    }
+    // pages the sequence held so far go back to the stack (last page first)
+    std::vector<int32_t> stack(kv->h_free_stack.begin(), kv->h_free_stack.begin() + kv->h_free_count);
+    for (int j = kv->h_n_held[seq] - 1; j >= 0; --j) stack.push_back(kv->h_page_table[(size_t)seq * kv->max_pages + j]);
+    for (int j = 0; j < need; ++j) {
+        int32_t p = host_page_ids[j];
+        auto it = std::find(stack.begin(), stack.end(), p);
+        if (p < 0 || p >= kv->n_pages || it == stack.end()) { set_error("spec_kv_seq_assign: page %d is out of range or in use", p); return SPEC_EINVAL; }
+        stack.erase(it);
+    }
+    for (int j = 0; j < kv->max_pages; ++j) kv->h_page_table[(size_t)seq * kv->max_pages + j] = j < need ? host_page_ids[j] : -1;
+    kv->h_ctx_len[seq] = ctx_len;
+    kv->h_n_held[seq] = need;
+    std::copy(stack.begin(), stack.end(), kv->h_free_stack.begin());
+    kv->h_free_count = (int64_t)stack.size();
+    // upload the touched parts
+    size_t S = kv->max_seqs;
+    SPEC_HIP_TRY(hipMemcpy(kv->d_ctx_len + seq, &kv->h_ctx_len[seq], sizeof(int32_t), hipMemcpyHostToDevice));
+    SPEC_HIP_TRY(hipMemcpy(kv->d_n_held + seq, &kv->h_n_held[seq], sizeof(int32_t), hipMemcpyHostToDevice));
+    SPEC_HIP_TRY(hipMemcpy(kv->d_page_table + (size_t)seq * kv->max_pages, &kv->h_page_table[(size_t)seq * kv->max_pages],
+                           kv->max_pages * sizeof(int32_t), hipMemcpyHostToDevice));
+    SPEC_HIP_TRY(hipMemcpy(kv->d_free_stack, kv->h_free_stack.data(), kv->n_pages * sizeof(int32_t), hipMemcpyHostToDevice));
+    int32_t fc = (int32_t)kv->h_free_count;
+    SPEC_HIP_TRY(hipMemcpy(kv->d_free_count, &fc, sizeof(int32_t), hipMemcpyHostToDevice));
+    (void)S;
+    kv->recount();
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_kv_get_state(spec_kv* kv, int32_t* host_ctx_len, int32_t* host_n_pages, int32_t* host_page_table,
+                                         int32_t* host_free_stack, int64_t* host_n_free)
+{
+    if (!kv) { set_error("spec_kv_get_state: null handle"); return SPEC_EINVAL; }
+    int32_t err = 0;
+    spec_status st = kv_download(kv, &err);
+    if (st != SPEC_OK) return st;
+    if (host_ctx_len) std::copy(kv->h_ctx_len.begin(), kv->h_ctx_len.end(), host_ctx_len);
+    if (host_n_pages) std::copy(kv->h_n_held.begin(), kv->h_n_held.end(), host_n_pages);
+    if (host_page_table) std::copy(kv->h_page_table.begin(), kv->h_page_table.end(), host_page_table);
+    if (host_free_stack) std::copy(kv->h_free_stack.begin(), kv->h_free_stack.end(), host_free_stack);
+    if (host_n_free) *host_n_free = kv->h_free_count;
+    if (err & 1) { set_error("a step ran out of KV pages; its sequences were left without new pages"); return SPEC_ENOMEM; }
+    if (err & 2) { set_error("a step was given a sequence id out of range"); return SPEC_EINVAL; }
+    if (err & 4) { set_error("a sequence outgrew max_ctx_len"); return SPEC_EINVAL; }
+    return SPEC_OK;
+}
+
+// ------------------------------------------------------------------------------------------ the step
+
+extern "C" size_t spec_verify_workspace_bytes(const spec_model* m, const spec_kv* kv, int32_t B, int32_t k)
+{
+    if (!m || !kv || kv->model != m || B < 1 || k < 0 || k > SPEC_MAX_DRAFT) return 0;
+    return m->desc.dtype == SPEC_F32 ? f32_workspace_bytes(m->desc, B, k) : bf16_workspace_bytes(m, kv, B, k);
+}
+
+extern "C" spec_status spec_verify_forward(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                           const int32_t* dev_tokens, float* dev_logits, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!m || !kv || !dev_seq_ids || !dev_tokens || !dev_logits || !ws) { set_error("spec_verify_forward: null pointer"); return SPEC_EINVAL; }
+    if (kv->model != m) { set_error("spec_verify_forward: the cache belongs to another model"); return SPEC_EINVAL; }
+    if (B < 1 || B > kv->max_seqs || k < 0 || k > SPEC_MAX_DRAFT) { set_error("spec_verify_forward: B or k out of range"); return SPEC_EINVAL; }
+    if (ws_bytes < spec_verify_workspace_bytes(m, kv, B, k)) { set_error("spec_verify_forward: workspace too small (%zu < %zu)", ws_bytes, spec_verify_workspace_bytes(m, kv, B, k)); return SPEC_EINVAL; }
+    if (((uintptr_t)ws & 255) != 0) { set_error("spec_verify_forward: workspace must be 256-byte aligned"); return SPEC_EINVAL; }
+    // page budget: every batch entry may need ceil((k+1)/P)+1 more pages than it holds at most
+    int64_t grow = (int64_t)B * (cdiv(k + 1, SPEC_PAGE_SIZE) + 1);
+    if (kv->ub.pages() + grow > kv->n_pages || kv->ub.max_ctx + k + 1 > (int64_t)kv->max_pages * SPEC_PAGE_SIZE) {
+        if (kv->device_ahead) {                           // bounds may be stale: refresh them exactly once
+            spec_status st = kv_download(kv, nullptr);
+            if (st != SPEC_OK) return st;
+        }
+        int64_t exact_grow = 0;                           // worst case over any B sequences: take the B largest needs
+        std::vector<int64_t> needs;
+        for (int s = 0; s < kv->max_seqs; ++s)
+            needs.push_back(cdiv((int64_t)kv->h_ctx_len[s] + k + 1, SPEC_PAGE_SIZE) - kv->h_n_held[s]);
+        std::sort(needs.begin(), needs.end(), [](int64_t a, int64_t b) { return a > b; });
+        for (int i = 0; i < B; ++i) exact_grow += needs[i] > 0 ? needs[i] : 0;
+        if (exact_grow > kv->h_free_count) { set_error("spec_verify_forward: the page pool cannot hold %d more positions for %d sequences", k + 1, B); return SPEC_ENOMEM; }
+        if (kv->ub.max_ctx + k + 1 > (int64_t)kv->max_pages * SPEC_PAGE_SIZE) { set_error("spec_verify_forward: a sequence would outgrow max_ctx_len"); return SPEC_EINVAL; }
+    }
+    hipStream_t s = (hipStream_t)stream;
+    spec_status st = launch_kv_reserve(kv, B, k, dev_seq_ids, s);
+    if (st != SPEC_OK) return st;
+    kv->device_ahead = true;
+    st = m->desc.dtype == SPEC_F32 ? f32_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_logits, ws, s)
+                                   : bf16_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_logits, ws, ws_bytes, s);
+    return st;
+}
+
+extern "C" spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids, const int32_t* dev_accept_len,
+                                      int32_t* dev_new_ctx_len, int32_t* dev_commit_slots, void* stream)
+{
+    if (!kv || !dev_seq_ids || !dev_accept_len) { set_error("spec_commit_kv: null pointer"); return SPEC_EINVAL; }
+    if (B < 1 || B > kv->max_seqs || k < 0 || k > SPEC_MAX_DRAFT) { set_error("spec_commit_kv: B or k out of range"); return SPEC_EINVAL; }
+    spec_status st = launch_kv_commit(kv, B, k, dev_seq_ids, dev_accept_len, dev_new_ctx_len, dev_commit_slots, (hipStream_t)stream);
+    if (st != SPEC_OK) return st;
+    kv->device_ahead = true;
+    kv->ub.max_ctx += k + 1;
+    kv->ub.added_ctx += (int64_t)B * (k + 1);
+    kv->ub.touched = std::min<int64_t>(kv->max_seqs, kv->ub.touched + B);
+    return SPEC_OK;
+}
+
+extern "C" size_t spec_kv_state_bytes(const spec_kv* kv) { return kv ? kv->state_ints * sizeof(int32_t) : 0; }
+
+extern "C" spec_status spec_kv_snapshot(spec_kv* kv, void* dev_buf, void* stream)
+{
+    if (!kv || !dev_buf) { set_error("spec_kv_snapshot: null pointer"); return SPEC_EINVAL; }
+    SPEC_HIP_TRY(hipMemcpyAsync(dev_buf, kv->d_state, kv->state_ints * sizeof(int32_t), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    kv->snapshots[dev_buf] = kv->ub;
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_kv_restore(spec_kv* kv, const void* dev_buf, void* stream)
+{
+    if (!kv || !dev_buf) { set_error("spec_kv_restore: null pointer"); return SPEC_EINVAL; }
+    auto it = kv->snapshots.find(dev_buf);
+    if (it == kv->snapshots.end()) { set_error("spec_kv_restore: this buffer holds no snapshot of this cache"); return SPEC_ESTATE; }
+    SPEC_HIP_TRY(hipMemcpyAsync(kv->d_state, dev_buf, kv->state_ints * sizeof(int32_t), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    kv->ub = it->second;
+    kv->device_ahead = true;
+    return SPEC_OK;
+}

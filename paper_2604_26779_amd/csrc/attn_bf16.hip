@@ -1,0 +1,291 @@
+// Paged multi-query causal decode attention for the verify step (bf16 cache, head_dim 128).
+//
+// All (k+1) * G query rows that share a KV head (k+1 input positions x G query heads per KV head)
+// ride on ONE pass over that head's cached keys and values: that sharing is what makes verifying
+// k drafts cost about one decode step.  The pass is split along the context so that short and
+// long sequences fill the machine evenly:
+//   attn_partial_kernel : workgroup = (chunk of ATT_CP pages, kv head, batch entry); each of its 4
+//                         wavefronts walks every 4th page of the chunk with its own online softmax,
+//                         reading K and V blocks straight into MFMA operand registers (the cache's
+//                         in-block layout is the operand order, so every load is a contiguous
+//                         1 KiB), two pages in flight per wavefront;
+//                           S^T = K Q^T   v_mfma_f32_16x16x32_bf16 (keys x queries)
+//                           O^T += V^T P^T v_mfma_f32_16x16x16_bf16 (P^T comes out of S^T's
+//                                          accumulator layout without any shuffle);
+//                         the wavefronts' results are merged through LDS and written as an
+//                         un-normalised partial (O, max, sum).
+//   attn_reduce_kernel  : merges the chunks of a (batch entry, kv head) and writes the bf16 result
+//                         in the operand order the O-projection GEMM reads.
+// Row r of a (batch entry, kv head) tile is input position r / G, query head kvh*G + r % G.
+// Row i sees cache positions 0 .. ctx+i (causal over the k+1 new positions).
+#include "common.h"
+
+namespace specv {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int ATT_CP = 32;                 // pages per workgroup
+constexpr int ATT_WAVES = 4;
+constexpr int ATT_PPW = ATT_CP / ATT_WAVES;  // pages per wavefront
+constexpr int DH = 128;
+constexpr int BLOCK_U4 = SPEC_PAGE_SIZE * DH * 2 / 16;   // 256 16-byte words per K or V block
+
+__device__ inline unsigned short f2bf(float f)
+{
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (unsigned short)((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
+    u += 0x7fffu + ((u >> 16) & 1u);           // round to nearest even
+    return (unsigned short)(u >> 16);
+}
+
+// part_o : [item][RB*16 rows][128] fp32, part_ml : [item][RB*16][2] (max in log2 domain, sum)
+// item = (b * Hkv + kvh) * max_chunks + chunk
+template <int RB>
+__global__ __launch_bounds__(256) void attn_partial_kernel(
+    const unsigned short* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
+    int layer_pool, float scale_log2, int max_chunks, float* __restrict__ part_o, float* __restrict__ part_ml)
+{
+    const int chunk = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int Hkv = gridDim.y;
+    const int seq = seq_ids[b];
+    const int ctx = kv.ctx_len[seq];
+    int total = ctx + T;
+    const int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
+    if (total > cap) total = cap;
+    const int n_pages_seq = (total + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
+    const int page0 = chunk * ATT_CP;
+    if (page0 >= n_pages_seq) return;
+    int page_end = page0 + ATT_CP;
+    if (page_end > n_pages_seq) page_end = n_pages_seq;
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int lq = lane & 15, lg = lane >> 4;
+    const int R = T * G;
+
+    // query operands: lane (row lq, group lg) holds Q[row][s*32 + lg*8 .. +8], s = 0..3
+    bf16x8_t qf[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        int r = rb * 16 + lq;
+        const unsigned short* src = q + ((int64_t)(b * T + r / G) * Hq + kvh * G + r % G) * DH + lg * 8;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (r < R) v = *(const u32x4_t*)(src + s * 32);
+            qf[rb][s] = __builtin_bit_cast(bf16x8_t, v);
+        }
+    }
+    int row_limit[RB];                       // last visible cache position of this lane's query row
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        int r = rb * 16 + lq;
+        row_limit[rb] = r < R ? ctx + r / G : -1;
+    }
+
+    // this wavefront's pages: page0 + wave, + 4, ...
+    const int32_t* pt = kv.page_table + (int64_t)seq * kv.max_pages;
+    const u32x4_t* pool = (const u32x4_t*)kv.pool;
+    const int64_t layer_base = (int64_t)layer_pool * kv.n_pages;
+    auto block_ptr = [&](int logical_page, int is_v) {
+        int64_t pid = pt[logical_page];
+        return pool + ((((layer_base + pid) * 2 + is_v) * Hkv + kvh) * BLOCK_U4) + lane;
+    };
+
+    float mrow[RB], lrow[RB];
+    f32x4_t oacc[RB][8];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        mrow[rb] = -INFINITY;
+        lrow[rb] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    u32x4_t kf[2][4], vf[2][4];
+    auto load_page = [&](int slot, int logical_page) {
+        const u32x4_t* kp = block_ptr(logical_page, 0);
+        const u32x4_t* vp = block_ptr(logical_page, 1);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) kf[slot][s] = __builtin_nontemporal_load(kp + s * 64);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) vf[slot][s] = __builtin_nontemporal_load(vp + s * 64);
+    };
+
+    auto process = [&](int slot, int logical_page) {
+        const int key0 = logical_page * SPEC_PAGE_SIZE + lg * 4;          // this lane's 4 keys: key0 .. key0+3
+        const bool need_mask = (logical_page + 1) * SPEC_PAGE_SIZE > ctx;  // page reaches into the new positions
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[slot][s]), qf[rb][s], sacc, 0, 0, 0);
+            float sv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                sv[j] = sacc[j] * scale_log2;
+                if (need_mask && key0 + j > row_limit[rb]) sv[j] = -INFINITY;
+            }
+            float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            float mnew = fmaxf(mrow[rb], mx);
+            float alpha = 1.f, p[4] = {0.f, 0.f, 0.f, 0.f};
+            if (mnew > -INFINITY) {
+                alpha = exp2f(mrow[rb] - mnew);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) p[j] = exp2f(sv[j] - mnew);
+            }
+            mrow[rb] = mnew;
+            lrow[rb] = lrow[rb] * alpha + (p[0] + p[1] + p[2] + p[3]);
+            s16x4_t pb;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pb[j] = (short)f2bf(p[j]);
+            if (alpha != 1.f) {
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] *= alpha;
+            }
+#pragma unroll
+            for (int cp = 0; cp < 4; ++cp) {
+                u32x4_t v = vf[slot][cp];
+                if (need_mask) {
+                    // slots past the end of the sequence hold whatever the pool held: 0 * NaN would poison O
+                    unsigned int m01 = (key0 + 0 < total ? 0x0000ffffu : 0u) | (key0 + 1 < total ? 0xffff0000u : 0u);
+                    unsigned int m23 = (key0 + 2 < total ? 0x0000ffffu : 0u) | (key0 + 3 < total ? 0xffff0000u : 0u);
+                    v.x &= m01; v.y &= m23; v.z &= m01; v.w &= m23;
+                }
+                s16x4_t va = __builtin_bit_cast(s16x4_t, u32x2_t{v.x, v.y});
+                s16x4_t vb = __builtin_bit_cast(s16x4_t, u32x2_t{v.z, v.w});
+                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb, oacc[rb][2 * cp], 0, 0, 0);
+                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pb, oacc[rb][2 * cp + 1], 0, 0, 0);
+            }
+        }
+    };
+
+    int pg = page0 + wave;
+    if (pg < page_end) load_page(0, pg);
+    for (int it = 0; it < ATT_PPW; it += 2) {
+        int pg0 = page0 + wave + ATT_WAVES * it, pg1 = pg0 + ATT_WAVES, pg2 = pg1 + ATT_WAVES;
+        if (pg0 >= page_end) break;
+        if (pg1 < page_end) load_page(1, pg1);
+        process(0, pg0);
+        if (pg1 >= page_end) break;
+        if (pg2 < page_end) load_page(0, pg2);
+        process(1, pg1);
+    }
+
+    // per-row sums are spread over the 4 lane groups
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        lrow[rb] += __shfl_xor(lrow[rb], 16);
+        lrow[rb] += __shfl_xor(lrow[rb], 32);
+    }
+
+    // merge the 4 wavefronts through LDS
+    __shared__ float s_o[ATT_WAVES][RB][8][64][4];
+    __shared__ float s_m[ATT_WAVES][RB][16], s_l[ATT_WAVES][RB][16];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s_o[wave][rb][cb][lane][j] = oacc[rb][cb][j];
+        if (lg == 0) { s_m[wave][rb][lq] = mrow[rb]; s_l[wave][rb][lq] = lrow[rb]; }
+    }
+    __syncthreads();
+    const int64_t item = ((int64_t)b * Hkv + kvh) * max_chunks + chunk;
+    float* po = part_o + item * (RB * 16) * DH;
+    float* pml = part_ml + item * (RB * 16) * 2;
+    // element e of the tile: (rb, cb, lane', j) -> row rb*16 + lane'%16, channel cb*16 + (lane'/16)*4 + j
+    for (int e = threadIdx.x; e < RB * 8 * 64; e += 256) {
+        int l2 = e & 63, cb = (e >> 6) & 7, rb = e >> 9;
+        int row = l2 & 15;
+        float mw[ATT_WAVES], M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; ++w) { mw[w] = s_m[w][rb][row]; M = fmaxf(M, mw[w]); }
+        float o4[4] = {0.f, 0.f, 0.f, 0.f}, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; ++w) {
+            float f = mw[w] > -INFINITY ? exp2f(mw[w] - M) : 0.f;
+            L += f * s_l[w][rb][row];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o4[j] += f * s_o[w][rb][cb][l2][j];
+        }
+        int r = rb * 16 + row, c = cb * 16 + (l2 >> 4) * 4;
+        *(float4*)(po + (int64_t)r * DH + c) = make_float4(o4[0], o4[1], o4[2], o4[3]);
+        if (cb == 0 && (l2 >> 4) == 0) { pml[r * 2] = M; pml[r * 2 + 1] = L; }
+    }
+}
+
+// one thread per (batch entry, kv head, row, 8 channels): merge chunks, normalise, write the bf16
+// operand of the O projection: xp[k-step][m-block][lane][8] with k = head*128 + channel
+__global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int B, int T,
+                                   int G, int Hkv, int RBrows, int max_chunks, const int32_t* __restrict__ seq_ids,
+                                   KvView kv, int mb_pad, uint4* __restrict__ xp)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int R = T * G;
+    int64_t total = (int64_t)B * Hkv * R * (DH / 8);
+    if (idx >= total) return;
+    int c8 = (int)(idx % (DH / 8));
+    int r = (int)((idx / (DH / 8)) % R);
+    int kvh = (int)((idx / (DH / 8) / R) % Hkv);
+    int b = (int)(idx / (DH / 8) / R / Hkv);
+    int seq = seq_ids[b];
+    int totalk = kv.ctx_len[seq] + T;
+    int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
+    if (totalk > cap) totalk = cap;
+    int n_chunks = ((totalk + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE + ATT_CP - 1) / ATT_CP;
+    int64_t item0 = ((int64_t)b * Hkv + kvh) * max_chunks;
+    float M = -INFINITY;
+    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part_ml[((item0 + c) * RBrows + r) * 2]);
+    float L = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < n_chunks; ++c) {
+        float mc = part_ml[((item0 + c) * RBrows + r) * 2];
+        if (!(mc > -INFINITY)) continue;
+        float f = exp2f(mc - M);
+        L += f * part_ml[((item0 + c) * RBrows + r) * 2 + 1];
+        const float4* src = (const float4*)(part_o + ((item0 + c) * RBrows + r) * DH + c8 * 8);
+        float4 a = src[0], d = src[1];
+        o[0] += f * a.x; o[1] += f * a.y; o[2] += f * a.z; o[3] += f * a.w;
+        o[4] += f * d.x; o[5] += f * d.y; o[6] += f * d.z; o[7] += f * d.w;
+    }
+    float inv = L > 0.f ? 1.0f / L : 0.f;
+    unsigned short h[8];
+    for (int j = 0; j < 8; ++j) h[j] = f2bf(o[j] * inv);
+    int m = b * T + r / G;
+    int kidx = (kvh * G + r % G) * DH + c8 * 8;
+    int ks = kidx >> 4, half = (kidx >> 3) & 1;
+    int64_t dst = ((int64_t)ks * mb_pad + (m >> 5)) * 64 + (m & 31) + 32 * half;
+    xp[dst] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
+int attn_chunk_pages() { return ATT_CP; }
+
+spec_status launch_attention_bf16(const bf16_t* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
+                                  const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
+                                  int mb_pad, bf16_t* xp_out, hipStream_t s)
+{
+    int R = T * G;
+    int RB = (int)cdiv(R, 16);
+    float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+    dim3 grid((unsigned)max_chunks, (unsigned)Hkv, (unsigned)B);
+    const unsigned short* qq = (const unsigned short*)q;
+    switch (RB) {
+        case 1: attn_partial_kernel<1><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, part_o, part_ml); break;
+        case 2: attn_partial_kernel<2><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, part_o, part_ml); break;
+        default: set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 32", R); return SPEC_EUNSUPPORTED;
+    }
+    SPEC_LAUNCH_CHECK("attn_partial_kernel");
+    int64_t total = (int64_t)B * Hkv * R * (DH / 8);
+    attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, RB * 16, max_chunks, seq_ids, kv,
+                                                                  mb_pad, (uint4*)xp_out);
+    SPEC_LAUNCH_CHECK("attn_reduce_kernel");
+    return SPEC_OK;
+}
+
+}  // namespace specv

@@ -1,0 +1,136 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "spec_verify.h"
+
+namespace specv {
+
+void set_error(const char* fmt, ...);
+int tune(const char* name);
+
+#define SPEC_HIP_TRY(expr)                                                                  \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess) {                                                             \
+            specv::set_error("%s failed: %s", #expr, hipGetErrorString(e_));                \
+            return SPEC_EHIP;                                                               \
+        }                                                                                   \
+    } while (0)
+
+#define SPEC_LAUNCH_CHECK(name)                                                             \
+    do {                                                                                    \
+        hipError_t e_ = hipGetLastError();                                                  \
+        if (e_ != hipSuccess) {                                                             \
+            specv::set_error("launch of %s failed: %s", name, hipGetErrorString(e_));       \
+            return SPEC_EHIP;                                                               \
+        }                                                                                   \
+    } while (0)
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits in host-side signatures
+
+// ---- device-resident KV bookkeeping, shared by all kernels that touch the cache ----
+struct KvView {
+    void* pool;                // base of the pool
+    const int32_t* ctx_len;    // [max_seqs]
+    const int32_t* n_held;     // [max_seqs] pages held
+    const int32_t* page_table; // [max_seqs, max_pages]
+    int32_t max_pages;         // per sequence
+    int64_t n_pages;           // pool pages
+    int32_t n_kv_heads, head_dim;
+    int32_t alias_mod;
+    int32_t elem_bytes;
+};
+
+// ---- packed bf16 matrix for the MFMA GEMM (see gemm_bf16.hip for the tiling) ----
+struct PackedW {
+    const bf16_t* data = nullptr;  // [n_blocks][k_steps][64 lanes][8]
+    int32_t N = 0, K = 0;          // logical sizes
+    int32_t n_blocks = 0;          // ceil(N / 32)
+    int32_t k_steps = 0;           // K / 16
+};
+
+}  // namespace specv
+
+struct spec_model {
+    spec_model_desc desc;
+    int device = 0;
+    std::vector<const void*> w;            // canonical pointers, borrowed
+    // bf16 path: packed matrices in one arena
+    void* arena = nullptr;
+    size_t arena_bytes = 0;
+    std::vector<specv::PackedW> wqkv, wo, wgu, wd;
+    specv::PackedW head;
+    const void* embed() const { return w[0]; }
+    const void* layer_w(int l, int i) const { return w[1 + 9 * l + i]; }   // i: 0 attn_norm .. 8 wd
+    const void* final_norm() const { return w[1 + 9 * desc.n_layers]; }
+    const void* head_w() const { return desc.tied_head ? w[0] : w[2 + 9 * desc.n_layers]; }
+};
+
+struct spec_kv {
+    const spec_model* model = nullptr;
+    int device = 0;
+    int32_t max_seqs = 0, max_pages = 0, alias_mod = 0;
+    int64_t n_pages = 0;
+    void* pool = nullptr;
+    // device state (one allocation)
+    int32_t* d_state = nullptr;
+    int32_t *d_ctx_len = nullptr, *d_n_held = nullptr, *d_page_table = nullptr, *d_free_stack = nullptr,
+            *d_free_count = nullptr, *d_error = nullptr;
+    size_t state_ints = 0;
+    // host mirror, valid when !device_ahead
+    std::vector<int32_t> h_ctx_len, h_n_held, h_page_table, h_free_stack;
+    int64_t h_free_count = 0;
+    bool device_ahead = false;
+    // conservative bounds kept while the device is ahead of the mirror
+    struct Bounds {
+        int64_t max_ctx = 0;       // upper bound of the longest context
+        int64_t base_pages = 0;    // pages in use at the last exact count
+        int64_t added_ctx = 0;     // positions committed since (upper bound)
+        int64_t touched = 0;       // batch entries stepped since (each may round up one more page)
+        int64_t pages() const { return base_pages + (added_ctx + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE + touched; }
+    } ub;
+    std::map<const void*, Bounds> snapshots;   // bounds saved with spec_kv_snapshot, by buffer
+    void recount();                // exact bounds from the host mirror
+    specv::KvView view() const;
+};
+
+namespace specv {
+
+// ---- kv bookkeeping kernels (kvbook.hip) ----
+spec_status launch_kv_reserve(spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, hipStream_t s);
+spec_status launch_kv_commit(spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, const int32_t* dev_accept_len,
+                             int32_t* dev_new_ctx_len, int32_t* dev_commit_slots, hipStream_t s);
+
+// ---- fp32 generic path (forward_f32.hip) ----
+size_t f32_workspace_bytes(const spec_model_desc& d, int B, int k);
+spec_status f32_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids,
+                        const int32_t* dev_tokens, float* dev_logits, void* ws, hipStream_t s);
+
+// ---- bf16 MFMA path (forward_bf16.hip, gemm_bf16.hip, attn_bf16.hip) ----
+size_t bf16_packed_elems(int N, int K);
+spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_rows, int n_parts, int K,
+                             bf16_t* dev_out, PackedW* out, hipStream_t s);
+size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k);
+spec_status bf16_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids,
+                         const int32_t* dev_tokens, float* dev_logits, void* ws, size_t ws_bytes, hipStream_t s);
+
+// in-block layouts of the cache, by storage type (host + device)
+__host__ __device__ inline int64_t kv_block_offset(int dtype, int is_v, int t, int c, int head_dim)
+{
+    if (dtype == SPEC_F32) return (int64_t)t * head_dim + c;            // natural [t][c]
+    if (!is_v)                                                           // K: [c/8][t][8]
+        return ((int64_t)(c >> 3) * SPEC_PAGE_SIZE + t) * 8 + (c & 7);
+    // V: [c/32][t/4][c%16][(c/16)%2][t%4]
+    int cb = c >> 4, c1 = c & 15, g = t >> 2, j = t & 3;
+    return ((((int64_t)(cb >> 1) * 4 + g) * 16 + c1) * 8) + (cb & 1) * 4 + j;
+}
+
+}  // namespace specv

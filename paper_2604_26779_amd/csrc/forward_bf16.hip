@@ -1,0 +1,311 @@
+// bf16 verify forward: orchestration and the small kernels between the GEMMs and the attention.
+//
+// Per layer (residual stream x in fp32, every GEMM input in bf16 operand order "xp"):
+//   xp_h  = RMSNorm(x) * g                         (fused into the kernel that last touched x)
+//   part  = xp_h W_qkv^T                           gemm, split-K slices
+//   q, K, V = rotary(sum part)                     qkv_rope_kernel: q -> bf16 rows, K/V -> paged cache
+//   xp_a  = attention(q, cache)                    attn_bf16.hip
+//   part  = xp_a W_o^T ; x += sum part ; xp_h = RMSNorm(x) * g2        residual_rmsnorm_kernel
+//   part  = xp_h [W_g; W_u]^T ; xp_f = silu(gate) * up                  swiglu_pack_kernel
+//   part  = xp_f W_d^T ; x += sum part ; xp_h = RMSNorm(x) * g_next     residual_rmsnorm_kernel
+// logits = xp_h W_head^T (fp32, written in place by the GEMM).
+#include <algorithm>
+
+#include "common.h"
+
+namespace specv {
+
+// from gemm_bf16.hip / attn_bf16.hip
+int gemm_mb_pad(int M);
+int gemm_pick_splits(const PackedW& W, int M, int forced);
+spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, hipStream_t s);
+int attn_chunk_pages();
+spec_status launch_attention_bf16(const bf16_t* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
+                                  const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
+                                  int mb_pad, bf16_t* xp_out, hipStream_t s);
+
+__device__ inline unsigned short to_bf16(float f)
+{
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (unsigned short)((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+__device__ inline float from_bf16(unsigned short h) { return __uint_as_float((unsigned int)h << 16); }
+
+__device__ inline uint4 pack8(const float* v)
+{
+    unsigned short h[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) h[j] = to_bf16(v[j]);
+    return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
+// index (in 16-byte words) of elements k .. k+7 (k % 8 == 0) of row m in operand order
+__device__ inline int64_t xp_index(int m, int k, int mb_pad)
+{
+    return ((int64_t)(k >> 4) * mb_pad + (m >> 5)) * 64 + (m & 31) + 32 * ((k >> 3) & 1);
+}
+
+__device__ inline float block_sum_256(float v, float* lds4)
+{
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return lds4[0] + lds4[1] + lds4[2] + lds4[3];
+}
+
+// x[m] = (FIRST ? embed[token] : x[m] + sum_s part[s][m]);  xp = RMSNorm(x[m]) * gain
+// one workgroup of 256 threads per row; d % 8 == 0
+template <bool FIRST>
+__global__ __launch_bounds__(256) void residual_rmsnorm_kernel(
+    float* __restrict__ x, const float* __restrict__ part, int splits, int64_t split_stride, const int32_t* __restrict__ tokens,
+    const unsigned short* __restrict__ embed, int vocab, const unsigned short* __restrict__ gain, int d, float eps, int mb_pad,
+    uint4* __restrict__ xp)
+{
+    __shared__ float lds4[4];
+    const int m = blockIdx.x;
+    float* xr = x + (int64_t)m * d;
+    float ss = 0.f;
+    int tok = 0;
+    if (FIRST) { tok = tokens[m]; tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok); }
+    for (int c = threadIdx.x * 8; c < d; c += 2048) {
+        float v[8];
+        if (FIRST) {
+            uint4 e = *(const uint4*)(embed + (int64_t)tok * d + c);
+            unsigned int w[4] = {e.x, e.y, e.z, e.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { v[2 * j] = from_bf16(w[j] & 0xffff); v[2 * j + 1] = from_bf16(w[j] >> 16); }
+        } else {
+            float4 a = *(const float4*)(xr + c), b = *(const float4*)(xr + c + 4);
+            for (int s = 0; s < splits; ++s) {
+                const float* ps = part + s * split_stride + (int64_t)m * d + c;
+                float4 p0 = *(const float4*)ps, p1 = *(const float4*)(ps + 4);
+                a.x += p0.x; a.y += p0.y; a.z += p0.z; a.w += p0.w;
+                b.x += p1.x; b.y += p1.y; b.z += p1.z; b.w += p1.w;
+            }
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        }
+        *(float4*)(xr + c) = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)(xr + c + 4) = make_float4(v[4], v[5], v[6], v[7]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
+    }
+    float tot = block_sum_256(ss, lds4);
+    float r = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int c = threadIdx.x * 8; c < d; c += 2048) {
+        float4 a = *(const float4*)(xr + c), b = *(const float4*)(xr + c + 4);      // this thread's own writes
+        uint4 g = *(const uint4*)(gain + c);
+        float v[8] = {a.x * r * from_bf16(g.x & 0xffff), a.y * r * from_bf16(g.x >> 16), a.z * r * from_bf16(g.y & 0xffff),
+                      a.w * r * from_bf16(g.y >> 16),    b.x * r * from_bf16(g.z & 0xffff), b.y * r * from_bf16(g.z >> 16),
+                      b.z * r * from_bf16(g.w & 0xffff), b.w * r * from_bf16(g.w >> 16)};
+        xp[xp_index(m, c, mb_pad)] = pack8(v);
+    }
+}
+
+// cos/sin of pos * theta^(-2j/dh) per input row, in fp64 (the angle reaches thousands of radians)
+__global__ void rope_table_kernel(int M, int T, const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ ctx_len,
+                                  int half, double theta, float2* __restrict__ table)
+{
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= M * half) return;
+    int m = idx / half, j = idx % half;
+    int pos = ctx_len[seq_ids[m / T]] + m % T;
+    double ang = (double)pos * pow(theta, -2.0 * (double)j / (double)(2 * half));
+    table[idx] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// sums the split-K slices of the QKV projection, rotates q and k, writes q as bf16 rows and the
+// new k, v into their cache slots (speculatively: positions ctx .. ctx+k).  One workgroup per row.
+__global__ __launch_bounds__(256) void qkv_rope_kernel(
+    const float* __restrict__ part, int splits, int64_t split_stride, int T, int Hq, int Hkv,
+    const float2* __restrict__ rope, const int32_t* __restrict__ seq_ids, KvView kv, int layer_pool,
+    unsigned short* __restrict__ q_out)
+{
+    constexpr int DHc = 128, HALF = 64;
+    const int m = blockIdx.x;
+    const int b = m / T, i = m % T;
+    const int seq = seq_ids[b];
+    const int pos = kv.ctx_len[seq] + i;
+    const int lp = pos / SPEC_PAGE_SIZE, t = pos % SPEC_PAGE_SIZE;
+    const bool writable = lp < kv.n_held[seq];
+    const int64_t page = writable ? kv.page_table[(int64_t)seq * kv.max_pages + lp] : 0;
+    const int nqkv = (Hq + 2 * Hkv) * DHc;
+    const float* row = part + (int64_t)m * nqkv;
+    unsigned short* pool = (unsigned short*)kv.pool;
+    const int64_t block = (int64_t)SPEC_PAGE_SIZE * DHc;
+    auto sum4 = [&](int n) {
+        float4 v = *(const float4*)(row + n);
+        for (int s = 1; s < splits; ++s) {
+            float4 p = *(const float4*)(row + s * split_stride + n);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        return v;
+    };
+    // rotary part: heads 0 .. Hq+Hkv-1, 16 quads of the lower half each
+    for (int e = threadIdx.x; e < (Hq + Hkv) * (HALF / 4); e += 256) {
+        int h = e / (HALF / 4), j = (e % (HALF / 4)) * 4;
+        float4 lo = sum4(h * DHc + j), hi = sum4(h * DHc + j + HALF);
+        const float2* cs = rope + (int64_t)m * HALF + j;
+        float l[4] = {lo.x, lo.y, lo.z, lo.w}, u[4] = {hi.x, hi.y, hi.z, hi.w}, rl[4], ru[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            float2 c = cs[a];
+            rl[a] = l[a] * c.x - u[a] * c.y;
+            ru[a] = u[a] * c.x + l[a] * c.y;
+        }
+        uint2 plo = make_uint2(to_bf16(rl[0]) | (to_bf16(rl[1]) << 16), to_bf16(rl[2]) | (to_bf16(rl[3]) << 16));
+        uint2 phi = make_uint2(to_bf16(ru[0]) | (to_bf16(ru[1]) << 16), to_bf16(ru[2]) | (to_bf16(ru[3]) << 16));
+        if (h < Hq) {
+            unsigned short* dst = q_out + ((int64_t)m * Hq + h) * DHc;
+            *(uint2*)(dst + j) = plo;
+            *(uint2*)(dst + j + HALF) = phi;
+        } else if (writable) {
+            int kh = h - Hq;
+            unsigned short* dst = pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 0) * Hkv + kh) * block;
+            *(uint2*)(dst + kv_block_offset(SPEC_BF16, 0, t, j, DHc)) = plo;
+            *(uint2*)(dst + kv_block_offset(SPEC_BF16, 0, t, j + HALF, DHc)) = phi;
+        }
+    }
+    // values: no rotation
+    if (writable)
+        for (int e = threadIdx.x; e < Hkv * (DHc / 4); e += 256) {
+            int kh = e / (DHc / 4), c = (e % (DHc / 4)) * 4;
+            float4 v = sum4((Hq + Hkv + kh) * DHc + c);
+            unsigned short* dst = pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 1) * Hkv + kh) * block;
+            dst[kv_block_offset(SPEC_BF16, 1, t, c + 0, DHc)] = to_bf16(v.x);
+            dst[kv_block_offset(SPEC_BF16, 1, t, c + 1, DHc)] = to_bf16(v.y);
+            dst[kv_block_offset(SPEC_BF16, 1, t, c + 2, DHc)] = to_bf16(v.z);
+            dst[kv_block_offset(SPEC_BF16, 1, t, c + 3, DHc)] = to_bf16(v.w);
+        }
+}
+
+// act = silu(sum gate) * (sum up) from the gate/up projection [M][2F] -> bf16 operand order (K = F)
+__global__ void swiglu_pack_kernel(const float* __restrict__ part, int splits, int64_t split_stride, int M, int F, int mb_pad,
+                                   uint4* __restrict__ xp)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int f8 = F / 8;
+    if (idx >= (int64_t)M * f8) return;
+    int m = (int)(idx / f8), f = (int)(idx % f8) * 8;
+    const float* row = part + (int64_t)m * 2 * F;
+    float g[8], u[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        float4 a = *(const float4*)(row + f + 4 * h), c = *(const float4*)(row + F + f + 4 * h);
+        for (int s = 1; s < splits; ++s) {
+            float4 a2 = *(const float4*)(row + s * split_stride + f + 4 * h), c2 = *(const float4*)(row + s * split_stride + F + f + 4 * h);
+            a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+            c.x += c2.x; c.y += c2.y; c.z += c2.z; c.w += c2.w;
+        }
+        g[4 * h] = a.x; g[4 * h + 1] = a.y; g[4 * h + 2] = a.z; g[4 * h + 3] = a.w;
+        u[4 * h] = c.x; u[4 * h + 1] = c.y; u[4 * h + 2] = c.z; u[4 * h + 3] = c.w;
+    }
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = g[j] / (1.0f + expf(-g[j])) * u[j];
+    xp[xp_index(m, f, mb_pad)] = pack8(v);
+}
+
+// ------------------------------------------------------------------ host side
+struct Bf16Plan {
+    int M, mb_pad, max_chunks, RBrows;
+    int s_qkv, s_o, s_gu, s_down, s_head;
+    size_t off_x, off_xp_h, off_xp_a, off_xp_f, off_part, off_q, off_rope, off_att_o, off_att_ml, total;
+};
+
+static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plus)
+{
+    const spec_model_desc& d = m->desc;
+    Bf16Plan p;
+    int T = k + 1;
+    p.M = B * T;
+    p.mb_pad = gemm_mb_pad(p.M);
+    int G = d.n_q_heads / d.n_kv_heads;
+    p.RBrows = (int)cdiv(T * G, 16) * 16;
+    p.max_chunks = (int)cdiv(cdiv(max_ctx_plus, SPEC_PAGE_SIZE), attn_chunk_pages());
+    if (p.max_chunks < 1) p.max_chunks = 1;
+    p.s_qkv = gemm_pick_splits(m->wqkv[0], p.M, tune("splits_qkv"));
+    p.s_o = gemm_pick_splits(m->wo[0], p.M, tune("splits_o"));
+    p.s_gu = gemm_pick_splits(m->wgu[0], p.M, tune("splits_gu"));
+    p.s_down = gemm_pick_splits(m->wd[0], p.M, tune("splits_down"));
+    p.s_head = 1;
+    int D = d.d_model, F = d.ffn_dim, nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
+    size_t rows = (size_t)p.mb_pad * 32;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    p.off_x = take((size_t)p.M * D * 4);
+    p.off_xp_h = take(rows * D * 2);
+    p.off_xp_a = take(rows * nq * 2);
+    p.off_xp_f = take(rows * F * 2);
+    size_t part = std::max(std::max((size_t)p.s_qkv * nqkv, (size_t)p.s_o * D), std::max((size_t)p.s_gu * 2 * F, (size_t)p.s_down * D));
+    p.off_part = take(part * p.M * 4);
+    p.off_q = take((size_t)p.M * nq * 2);
+    p.off_rope = take((size_t)p.M * (d.head_dim / 2) * 8);
+    size_t items = (size_t)B * d.n_kv_heads * p.max_chunks;
+    p.off_att_o = take(items * p.RBrows * d.head_dim * 4);
+    p.off_att_ml = take(items * p.RBrows * 2 * 4);
+    p.total = off;
+    return p;
+}
+
+size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k)
+{
+    return make_plan(m, B, k, (int64_t)kv->max_pages * SPEC_PAGE_SIZE).total;
+}
+
+spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, const int32_t* dev_tokens,
+                         float* dev_logits, void* ws, size_t ws_bytes, hipStream_t s)
+{
+    const spec_model_desc& d = mdl->desc;
+    const int T = k + 1, G = d.n_q_heads / d.n_kv_heads;
+    if (T * G > 32) { set_error("bf16 path: (k+1) * (query heads per kv head) = %d exceeds 32", T * G); return SPEC_EUNSUPPORTED; }
+    // the workspace is laid out for the longest context the cache allows; the launch only spans
+    // the chunks the current bound on the longest sequence needs
+    Bf16Plan p = make_plan(mdl, B, k, (int64_t)kv->max_pages * SPEC_PAGE_SIZE);
+    if (p.total > ws_bytes) { set_error("spec_verify_forward: workspace too small for the current split settings (%zu < %zu)", ws_bytes, p.total); return SPEC_EINVAL; }
+    int live_chunks = (int)cdiv(cdiv(kv->ub.max_ctx + T, SPEC_PAGE_SIZE), attn_chunk_pages());
+    if (live_chunks > p.max_chunks) live_chunks = p.max_chunks;
+    if (live_chunks < 1) live_chunks = 1;
+
+    char* base = (char*)ws;
+    float* x = (float*)(base + p.off_x);
+    bf16_t* xp_h = (bf16_t*)(base + p.off_xp_h);
+    bf16_t* xp_a = (bf16_t*)(base + p.off_xp_a);
+    bf16_t* xp_f = (bf16_t*)(base + p.off_xp_f);
+    float* part = (float*)(base + p.off_part);
+    bf16_t* qbuf = (bf16_t*)(base + p.off_q);
+    float2* rope = (float2*)(base + p.off_rope);
+    float* att_o = (float*)(base + p.off_att_o);
+    float* att_ml = (float*)(base + p.off_att_ml);
+
+    const int M = p.M, D = d.d_model, F = d.ffn_dim, Hq = d.n_q_heads, Hkv = d.n_kv_heads;
+    const int nqkv = (Hq + 2 * Hkv) * d.head_dim;
+    KvView view = kv->view();
+    spec_status st;
+
+    rope_table_kernel<<<(unsigned)cdiv((int64_t)M * 64, 256), 256, 0, s>>>(M, T, dev_seq_ids, kv->d_ctx_len, 64, (double)d.rope_theta, rope);
+    residual_rmsnorm_kernel<true><<<M, 256, 0, s>>>(x, nullptr, 0, 0, dev_tokens, (const unsigned short*)mdl->embed(), d.vocab,
+                                                    (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+    for (int l = 0; l < d.n_layers; ++l) {
+        int lp = kv->alias_mod > 0 ? l % kv->alias_mod : l;
+        if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, s)) != SPEC_OK) return st;
+        qkv_rope_kernel<<<M, 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, (unsigned short*)qbuf);
+        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_chunks, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
+        if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, s)) != SPEC_OK) return st;
+        residual_rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
+                                                         (const unsigned short*)mdl->layer_w(l, 5), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+        if ((st = launch_gemm_bf16(mdl->wgu[l], xp_h, M, part, 2 * F, p.s_gu, s)) != SPEC_OK) return st;
+        swiglu_pack_kernel<<<(unsigned)cdiv((int64_t)M * (F / 8), 256), 256, 0, s>>>(part, p.s_gu, (int64_t)M * 2 * F, M, F, p.mb_pad, (uint4*)xp_f);
+        if ((st = launch_gemm_bf16(mdl->wd[l], xp_f, M, part, D, p.s_down, s)) != SPEC_OK) return st;
+        const void* next_gain = l + 1 < d.n_layers ? mdl->layer_w(l + 1, 0) : mdl->final_norm();
+        residual_rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
+                                                         (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+    }
+    if ((st = launch_gemm_bf16(mdl->head, xp_h, M, dev_logits, d.vocab, 1, s)) != SPEC_OK) return st;
+    SPEC_LAUNCH_CHECK("bf16 forward");
+    return SPEC_OK;
+}
+
+}  // namespace specv

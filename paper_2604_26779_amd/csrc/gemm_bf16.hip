@@ -1,0 +1,207 @@
+// bf16 MFMA GEMM for the verify step's projections:  out[m][n] = sum_k x[m][k] * W[n][k],
+// fp32 accumulation, M = B*(k+1) rows (a few dozen to a few hundred), N and K in the thousands.
+// At these shapes the weights are streamed once from HBM and everything else is noise, so the
+// kernel is organised around the weight stream:
+//
+//   * W is re-tiled once (at model creation) into MFMA operand order: for every block of 32
+//     output columns and every 16-wide k-step, the 64 lanes' 16-byte operands are contiguous
+//     (1 KiB).  A wavefront owns one 32-column block and reads its stream with perfectly
+//     coalesced 16-byte loads straight into registers; no LDS round trip for the weights.
+//   * the activations are written by the producing kernel in the same operand order
+//     ([k-step][32-row block][lane][8]), staged through LDS in slabs of KS k-steps (double
+//     buffered, one barrier per slab) and shared by the 4 wavefronts of the workgroup.
+//   * v_mfma_f32_32x32x16_bf16: A = activation fragment (rows m), B = weight fragment
+//     (columns n), so a lane ends up with one output column and 16 rows: stores are
+//     128-byte row segments.
+//   * K is split across workgroups (grid.y) when N alone gives too few workgroups to keep
+//     256 CUs streaming; partial sums go to separate fp32 slices that the consumer adds up
+//     in a fixed order (deterministic).
+#include "common.h"
+
+namespace specv {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int GEMM_KS = 8;          // k-steps (of 16) per LDS slab
+constexpr int GEMM_THREADS = 256;
+
+size_t bf16_packed_elems(int N, int K) { return (size_t)cdiv(N, 32) * 32 * (size_t)K; }
+
+// ------------------------------------------------------------------ weight re-tiling
+struct PackParts { const bf16_t* ptr[4]; int row_end[4]; int n; };
+
+__global__ void pack_w_kernel(PackParts parts, int N, int K, int k_steps, int64_t total, uint4* __restrict__ out)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte operand per thread
+    if (idx >= total) return;
+    int lane = (int)(idx & 63);
+    int64_t frag = idx >> 6;
+    int ks = (int)(frag % k_steps);
+    int nb = (int)(frag / k_steps);
+    int n = nb * 32 + (lane & 31);
+    int k0 = ks * 16 + (lane >> 5) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (n < N) {
+        int start = 0;
+        for (int p = 0; p < parts.n; ++p) {
+            if (n < parts.row_end[p]) {
+                v = *(const uint4*)(parts.ptr[p] + (int64_t)(n - start) * K + k0);
+                break;
+            }
+            start = parts.row_end[p];
+        }
+    }
+    out[idx] = v;
+}
+
+spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_rows, int n_parts, int K, bf16_t* dev_out,
+                             PackedW* out, hipStream_t s)
+{
+    if (n_parts < 1 || n_parts > 4 || K % 128) { set_error("bf16_pack_matrix: bad shape"); return SPEC_EINVAL; }
+    PackParts pp;
+    pp.n = n_parts;
+    int N = 0;
+    for (int i = 0; i < n_parts; ++i) {
+        if (((uintptr_t)dev_parts[i] & 15) != 0) { set_error("bf16 weights must be 16-byte aligned"); return SPEC_EINVAL; }
+        N += part_rows[i];
+        pp.ptr[i] = dev_parts[i];
+        pp.row_end[i] = N;
+    }
+    out->data = dev_out;
+    out->N = N;
+    out->K = K;
+    out->n_blocks = (int)cdiv(N, 32);
+    out->k_steps = K / 16;
+    int64_t total = (int64_t)out->n_blocks * out->k_steps * 64;
+    pack_w_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(pp, N, K, out->k_steps, total, (uint4*)dev_out);
+    SPEC_LAUNCH_CHECK("pack_w_kernel");
+    return SPEC_OK;
+}
+
+// ------------------------------------------------------------------ the GEMM
+// Wp : [n_blocks][k_steps][64] u32x4_t          Xp : [k_steps][mb_pad][64] u32x4_t
+// out: [splits][M][ldo] fp32 (slice stride = split_stride floats)
+template <int MB>
+__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
+    const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
+    int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride)
+{
+    constexpr int KS = GEMM_KS;
+    constexpr int SLAB = KS * MB * 64;                  // u32x4_t per slab
+    constexpr int XPT = SLAB / GEMM_THREADS;            // u32x4_t per thread per slab
+    __shared__ u32x4_t lds[2 * SLAB];
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nb = blockIdx.x * 4 + wave;
+    const bool active = nb < n_blocks;
+    const int ks0 = blockIdx.y * ksteps_per_split;
+    int ks1 = ks0 + ksteps_per_split;
+    if (ks1 > k_steps) ks1 = k_steps;
+    const int n_slabs = (ks1 - ks0) / KS;
+    const int mt = blockIdx.z;
+
+    const u32x4_t* wptr = Wp + ((int64_t)(active ? nb : 0) * k_steps + ks0) * 64 + lane;
+    const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mt * MB) * 64;
+
+    f32x16_t acc[MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+    u32x4_t w[KS], xr[XPT];
+
+    auto load_x = [&](int slab) {
+#pragma unroll
+        for (int j = 0; j < XPT; ++j) {
+            int idx = threadIdx.x + GEMM_THREADS * j;
+            int kl = idx / (MB * 64), rem = idx % (MB * 64);
+            xr[j] = xbase[((int64_t)(slab * KS + kl) * mb_pad) * 64 + rem];
+        }
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < XPT; ++j) lds[buf * SLAB + threadIdx.x + GEMM_THREADS * j] = xr[j];
+    };
+
+    if (n_slabs > 0) {
+#pragma unroll
+        for (int i = 0; i < KS; ++i) w[i] = __builtin_nontemporal_load(wptr + i * 64);
+        load_x(0);
+        store_x(0);
+        __syncthreads();
+        int buf = 0;
+        for (int s = 0; s < n_slabs; ++s) {
+            const bool more = s + 1 < n_slabs;
+            // the weight registers are refilled one k-step at a time, right after their last use:
+            // the stream stays KS fragments (8 KiB per wavefront) ahead of the MFMAs
+            const u32x4_t* wnext = wptr + (int64_t)(more ? s + 1 : s) * KS * 64;
+            if (more) load_x(s + 1);
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) {
+                bf16x8_t bw = __builtin_bit_cast(bf16x8_t, w[kk]);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    bf16x8_t a = __builtin_bit_cast(bf16x8_t, lds[buf * SLAB + (kk * MB + mb) * 64 + lane]);
+                    acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bw, acc[mb], 0, 0, 0);
+                }
+                if (more) w[kk] = __builtin_nontemporal_load(wnext + kk * 64);
+            }
+            if (more) store_x(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    if (!active) return;
+    float* o = out + (int64_t)blockIdx.y * split_stride;
+    const int n = nb * 32 + (lane & 31);
+    if (n >= N) return;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            int m = (mt * MB + mb) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (m < M) o[(int64_t)m * ldo + n] = acc[mb][r];
+        }
+}
+
+// rows of the activation buffer are padded to whole tiles of MB 32-row blocks
+int gemm_mb(int M) { int mb = (int)cdiv(M, 32); return mb > 4 ? 4 : mb; }
+int gemm_mb_pad(int M) { int mb = gemm_mb(M); return (int)cdiv(cdiv(M, 32), mb) * mb; }
+
+int gemm_pick_splits(const PackedW& W, int M, int forced)
+{
+    int n_tiles = (int)cdiv(W.n_blocks, 4);
+    int m_tiles = gemm_mb_pad(M) / gemm_mb(M);
+    int max_splits = W.k_steps / (tune("gemm_min_ksteps") > GEMM_KS ? tune("gemm_min_ksteps") : GEMM_KS);
+    if (max_splits < 1) max_splits = 1;
+    int splits = forced > 0 ? forced : (int)((tune("gemm_wg_target") + n_tiles * m_tiles / 2) / (n_tiles * m_tiles));
+    if (splits < 1) splits = 1;
+    if (splits > max_splits) splits = max_splits;
+    int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KS) * GEMM_KS;
+    return (int)cdiv(W.k_steps, kps);
+}
+
+// out must hold splits * M * ldo floats
+spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, hipStream_t s)
+{
+    int mb = gemm_mb(M), mb_pad = gemm_mb_pad(M);
+    int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KS) * GEMM_KS;
+    dim3 grid((unsigned)cdiv(W.n_blocks, 4), (unsigned)cdiv(W.k_steps, kps), (unsigned)(mb_pad / mb));
+    int64_t stride = (int64_t)M * ldo;
+    const u32x4_t* wp = (const u32x4_t*)W.data;
+    const u32x4_t* xp = (const u32x4_t*)Xp;
+    switch (mb) {
+        case 1: gemm_bf16_kernel<1><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride); break;
+        case 2: gemm_bf16_kernel<2><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride); break;
+        case 3: gemm_bf16_kernel<3><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride); break;
+        default: gemm_bf16_kernel<4><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride); break;
+    }
+    SPEC_LAUNCH_CHECK("gemm_bf16_kernel");
+    return SPEC_OK;
+}
+
+}  // namespace specv

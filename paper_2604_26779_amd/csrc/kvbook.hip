@@ -1,0 +1,148 @@
+// Device-side KV bookkeeping: page reservation before the forward pass and the commit after
+// sampling.  Both run as one workgroup so that the order in which pages leave and re-enter the
+// free stack is a pure function of the batch order (a block-wide exclusive scan gives every
+// batch entry its place on the stack).
+#include "common.h"
+
+namespace specv {
+
+constexpr int KVB_THREADS = 256;
+
+__device__ inline int block_exclusive_scan(int v, int* lds, int* total)
+{
+    int t = threadIdx.x;
+    lds[t] = v;
+    __syncthreads();
+    for (int off = 1; off < KVB_THREADS; off <<= 1) {
+        int add = (t >= off) ? lds[t - off] : 0;
+        __syncthreads();
+        lds[t] += add;
+        __syncthreads();
+    }
+    int incl = lds[t];
+    *total = lds[KVB_THREADS - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+// error bits
+constexpr int KV_ERR_NOMEM = 1, KV_ERR_SEQ = 2, KV_ERR_LEN = 4;
+
+__global__ __launch_bounds__(KVB_THREADS) void kv_reserve_kernel(
+    int B, int k, const int32_t* __restrict__ seq_ids, int max_seqs, int max_pages,
+    const int32_t* __restrict__ ctx_len, int32_t* __restrict__ n_held, int32_t* __restrict__ page_table,
+    const int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count, int32_t* __restrict__ error)
+{
+    __shared__ int lds[KVB_THREADS];
+    __shared__ int s_free;
+    if (threadIdx.x == 0) s_free = *free_count;
+    __syncthreads();
+    for (int base = 0; base < B; base += KVB_THREADS) {
+        int b = base + threadIdx.x;
+        int seq = -1, held = 0, want = 0;
+        if (b < B) {
+            seq = seq_ids[b];
+            if (seq < 0 || seq >= max_seqs) { atomicOr(error, KV_ERR_SEQ); seq = -1; }
+        }
+        if (seq >= 0) {
+            held = n_held[seq];
+            int need = (ctx_len[seq] + k + 1 + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
+            if (need > max_pages) { atomicOr(error, KV_ERR_LEN); need = held; }
+            want = need > held ? need - held : 0;
+        }
+        int total;
+        int off = block_exclusive_scan(want, lds, &total);
+        int avail = s_free;
+        __syncthreads();
+        if (total > avail) {
+            // not enough pages for this group of entries: nobody grows, the step is flagged
+            if (threadIdx.x == 0) atomicOr(error, KV_ERR_NOMEM);
+        } else {
+            for (int j = 0; j < want; ++j)
+                page_table[(int64_t)seq * max_pages + held + j] = free_stack[avail - 1 - off - j];
+            if (want > 0) n_held[seq] = held + want;
+            if (threadIdx.x == 0) s_free = avail - total;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *free_count = s_free;
+}
+
+__global__ __launch_bounds__(KVB_THREADS) void kv_commit_kernel(
+    int B, int k, const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ accept_len, int max_seqs,
+    int max_pages, int32_t* __restrict__ ctx_len, int32_t* __restrict__ n_held,
+    int32_t* __restrict__ page_table, int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count,
+    int32_t* __restrict__ error, int32_t* __restrict__ new_ctx_len, int32_t* __restrict__ commit_slots)
+{
+    __shared__ int lds[KVB_THREADS];
+    __shared__ int s_free;
+    if (threadIdx.x == 0) s_free = *free_count;
+    __syncthreads();
+    for (int base = 0; base < B; base += KVB_THREADS) {
+        int b = base + threadIdx.x;
+        int seq = -1, held = 0, keep = 0, release = 0;
+        if (b < B) {
+            seq = seq_ids[b];
+            if (seq < 0 || seq >= max_seqs) { atomicOr(error, KV_ERR_SEQ); seq = -1; }
+        }
+        if (seq >= 0) {
+            held = n_held[seq];
+            int ctx = ctx_len[seq];
+            int n = accept_len[b];
+            n = n < 0 ? 0 : (n > k ? k : n);
+            int fresh = ctx + n + 1;
+            int cap = held * SPEC_PAGE_SIZE;           // a step that could not reserve keeps what fits
+            if (fresh > cap) fresh = cap > ctx ? cap : ctx;
+            for (int i = 0; i <= k; ++i) {
+                int pos = ctx + i;
+                int slot = -1;
+                if (pos < fresh)
+                    slot = page_table[(int64_t)seq * max_pages + pos / SPEC_PAGE_SIZE] * SPEC_PAGE_SIZE +
+                           pos % SPEC_PAGE_SIZE;
+                if (commit_slots) commit_slots[(int64_t)b * (k + 1) + i] = slot;
+            }
+            keep = (fresh + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
+            release = held > keep ? held - keep : 0;
+            ctx_len[seq] = fresh;
+            if (new_ctx_len) new_ctx_len[b] = fresh;
+        } else if (b < B) {
+            if (new_ctx_len) new_ctx_len[b] = -1;
+            if (commit_slots)
+                for (int i = 0; i <= k; ++i) commit_slots[(int64_t)b * (k + 1) + i] = -1;
+        }
+        int total;
+        int off = block_exclusive_scan(release, lds, &total);
+        int top = s_free;
+        __syncthreads();
+        for (int j = 0; j < release; ++j) {             // last logical page first
+            int64_t at = (int64_t)seq * max_pages + held - 1 - j;
+            free_stack[top + off + j] = page_table[at];
+            page_table[at] = -1;
+        }
+        if (release > 0) n_held[seq] = keep;
+        if (threadIdx.x == 0) s_free = top + total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *free_count = s_free;
+}
+
+spec_status launch_kv_reserve(spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, hipStream_t s)
+{
+    kv_reserve_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, dev_seq_ids, kv->max_seqs, kv->max_pages, kv->d_ctx_len,
+                                                kv->d_n_held, kv->d_page_table, kv->d_free_stack,
+                                                kv->d_free_count, kv->d_error);
+    SPEC_LAUNCH_CHECK("kv_reserve_kernel");
+    return SPEC_OK;
+}
+
+spec_status launch_kv_commit(spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, const int32_t* dev_accept_len,
+                             int32_t* dev_new_ctx_len, int32_t* dev_commit_slots, hipStream_t s)
+{
+    kv_commit_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, dev_seq_ids, dev_accept_len, kv->max_seqs, kv->max_pages,
+                                               kv->d_ctx_len, kv->d_n_held, kv->d_page_table, kv->d_free_stack,
+                                               kv->d_free_count, kv->d_error, dev_new_ctx_len, dev_commit_slots);
+    SPEC_LAUNCH_CHECK("kv_commit_kernel");
+    return SPEC_OK;
+}
+
+}  // namespace specv

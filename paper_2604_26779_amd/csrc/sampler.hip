@@ -1,0 +1,200 @@
+// Fused vocabulary-wide softmax + lossless rejection sampling (the rejection procedure the
+// paper's Section 2.1 relies on; acceptance length as defined in its Section 2.2).
+//
+// Two launches per step:
+//   1. row_stats_kernel: one workgroup per logits row -> (max, sum of exp) of logits / T.
+//   2. reject_sample_kernel: one workgroup per sequence -> accept tests in order, then one
+//      exponential-race draw over the single row that decides the emitted token
+//      (residual row at the first rejection, bonus row after k acceptances).
+// Only the rows' statistics, the k probed q entries and one q row are read: (k+1+2) V floats
+// per sequence at most.
+#include "common.h"
+
+namespace specv {
+
+constexpr int SAMP_THREADS = 1024;
+
+struct Philox4 { uint32_t x, y, z, w; };
+
+__device__ inline Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return Philox4{c0, c1, c2, c3};
+}
+
+__device__ inline void online_merge(float& m, float& s, float m2, float s2)
+{
+    float mm = fmaxf(m, m2);
+    if (mm == -INFINITY) { m = mm; s = 0.f; return; }
+    s = s * expf(m - mm) + s2 * expf(m2 - mm);
+    m = mm;
+}
+
+__global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __restrict__ logits, int V, float inv_t,
+                                                                  float2* __restrict__ stats)
+{
+    const float* row = logits + (int64_t)blockIdx.x * V;
+    float m = -INFINITY, s = 0.f;
+    for (int v = threadIdx.x; v < V; v += SAMP_THREADS) {
+        float z = row[v] * inv_t;
+        if (z > m) { s = s * expf(m - z) + 1.f; m = z; }
+        else if (z > -INFINITY) s += expf(z - m);
+    }
+    // wavefront reduction, then across the 16 wavefronts through LDS
+    for (int off = 32; off > 0; off >>= 1) {
+        float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
+        online_merge(m, s, m2, s2);
+    }
+    __shared__ float lm[SAMP_THREADS / 64], ls[SAMP_THREADS / 64];
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) { lm[wave] = m; ls[wave] = s; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float M = lm[0], S = ls[0];
+        for (int w = 1; w < SAMP_THREADS / 64; ++w) online_merge(M, S, lm[w], ls[w]);
+        stats[blockIdx.x] = make_float2(M, S);
+    }
+}
+
+// mode 0: w = max(0, e/S - q); mode 1: w = e  (e = exp(z - m))
+template <int MODE>
+__device__ inline void race_scan(const float* __restrict__ lrow, const float* __restrict__ qrow, int V, float inv_t,
+                                 float m, float inv_s, uint32_t k0, uint32_t k1, uint32_t c1, uint32_t c2, uint32_t c3,
+                                 float& best, int& best_v)
+{
+    int groups = (V + 3) >> 2;
+    for (int g = threadIdx.x; g < groups; g += SAMP_THREADS) {
+        Philox4 r = philox4x32_10((uint32_t)g, c1, c2, c3, k0, k1);
+        uint32_t words[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int v = g * 4 + j;
+            if (v >= V) break;
+            float e = expf(lrow[v] * inv_t - m);
+            float w = (MODE == 0) ? fmaxf(0.f, e * inv_s - qrow[v]) : e;
+            if (!(w > 0.f)) continue;
+            float u = ((float)(words[j] >> 9) + 0.5f) * (1.0f / 8388608.0f);
+            float key = w / (-logf(u));
+            if (key > best) { best = key; best_v = v; }     // v ascends inside a thread: ties keep the lowest
+        }
+    }
+}
+
+__device__ inline void argmax_merge(float& key, int& v, float key2, int v2)
+{
+    if (key2 > key || (key2 == key && v2 >= 0 && (v < 0 || v2 < v))) { key = key2; v = v2; }
+}
+
+__device__ inline void block_argmax(float& key, int& v, float* lk, int* lv)
+{
+    for (int off = 32; off > 0; off >>= 1) {
+        float k2 = __shfl_xor(key, off);
+        int v2 = __shfl_xor(v, off);
+        argmax_merge(key, v, k2, v2);
+    }
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __syncthreads();
+    if (lane == 0) { lk[wave] = key; lv[wave] = v; }
+    __syncthreads();
+    key = lk[0]; v = lv[0];
+    for (int w = 1; w < SAMP_THREADS / 64; ++w) argmax_merge(key, v, lk[w], lv[w]);
+}
+
+__global__ __launch_bounds__(SAMP_THREADS) void reject_sample_kernel(
+    int k, int V, const float* __restrict__ logits, const float* __restrict__ q, const int32_t* __restrict__ draft,
+    float inv_t, uint32_t seed_lo, uint32_t seed_hi, uint32_t step4, const float2* __restrict__ stats,
+    int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens, float* __restrict__ dbg)
+{
+    const int b = blockIdx.x;
+    const float* L = logits + (int64_t)b * (k + 1) * V;
+    const float* Qb = q ? q + (int64_t)b * k * V : nullptr;
+    __shared__ int s_n;
+    __shared__ float lk[SAMP_THREADS / 64];
+    __shared__ int lv[SAMP_THREADS / 64];
+
+    if (threadIdx.x == 0) {
+        int n = 0;
+        for (int i = 0; i < k; ++i) {
+            if (dbg) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = d[1] = d[2] = NAN; }
+        }
+        for (int i = 0; i < k; ++i) {
+            int x = draft[(int64_t)b * k + i];
+            if (x < 0 || x >= V) break;
+            float2 st = stats[(int64_t)b * (k + 1) + i];
+            float P = expf(L[(int64_t)i * V + x] * inv_t - st.x) / st.y;
+            float Q = Qb[(int64_t)i * V + x];
+            Philox4 r = philox4x32_10(0u, (uint32_t)i, (uint32_t)b, step4 + 0u, seed_lo, seed_hi);
+            float u = (float)(r.x >> 8) * (1.0f / 16777216.0f);
+            if (dbg) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = P; d[1] = Q; d[2] = u; }
+            if ((double)u * (double)Q < (double)P) n += 1; else break;
+        }
+        s_n = n;
+    }
+    __syncthreads();
+    const int n = s_n;
+
+    const float* lrow = L + (int64_t)n * V;
+    float2 st = stats[(int64_t)b * (k + 1) + n];
+    float best = -1.f;
+    int best_v = -1;
+    const uint32_t c1 = (uint32_t)n, c2 = (uint32_t)b, c3 = step4 + 1u;
+    if (n < k) {
+        race_scan<0>(lrow, Qb + (int64_t)n * V, V, inv_t, st.x, 1.0f / st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v);
+        block_argmax(best, best_v, lk, lv);
+    }
+    if (best_v < 0) {                                // bonus row, or a residual that is identically zero
+        best = -1.f;
+        race_scan<1>(lrow, nullptr, V, inv_t, st.x, 1.0f, seed_lo, seed_hi, c1, c2, c3, best, best_v);
+        block_argmax(best, best_v, lk, lv);
+    }
+    if (threadIdx.x == 0) {
+        accept_len[b] = n;
+        int32_t* o = out_tokens + (int64_t)b * (k + 1);
+        for (int i = 0; i < n; ++i) o[i] = draft[(int64_t)b * k + i];
+        o[n] = best_v;
+        for (int i = n + 1; i <= k; ++i) o[i] = -1;
+    }
+}
+
+}  // namespace specv
+
+extern "C" size_t spec_sample_workspace_bytes(int32_t B, int32_t k)
+{
+    if (B < 1 || k < 0) return 0;
+    return specv::align_up((size_t)B * (size_t)(k + 1) * sizeof(float2), 256);
+}
+
+extern "C" spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
+                                          const int32_t* dev_draft_tokens, float temperature, uint64_t seed,
+                                          uint64_t step, int32_t* dev_accept_len, int32_t* dev_out_tokens,
+                                          float* dev_dbg, void* dev_workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace specv;
+    if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT || V < 1) { set_error("spec_reject_sample: B, k or V out of range"); return SPEC_EINVAL; }
+    if (!(temperature > 0.f)) { set_error("spec_reject_sample: temperature must be > 0"); return SPEC_EINVAL; }
+    if (step >= (1ull << 30)) { set_error("spec_reject_sample: step must be < 2^30"); return SPEC_EINVAL; }
+    if (!dev_logits || !dev_accept_len || !dev_out_tokens || !dev_workspace || (k > 0 && (!dev_q || !dev_draft_tokens))) {
+        set_error("spec_reject_sample: null pointer"); return SPEC_EINVAL;
+    }
+    if (workspace_bytes < spec_sample_workspace_bytes(B, k)) { set_error("spec_reject_sample: workspace too small"); return SPEC_EINVAL; }
+    hipStream_t s = (hipStream_t)stream;
+    float inv_t = 1.0f / temperature;
+    float2* stats = (float2*)dev_workspace;
+    row_stats_kernel<<<B * (k + 1), SAMP_THREADS, 0, s>>>(dev_logits, V, inv_t, stats);
+    SPEC_LAUNCH_CHECK("row_stats_kernel");
+    reject_sample_kernel<<<B, SAMP_THREADS, 0, s>>>(k, V, dev_logits, dev_q, dev_draft_tokens, inv_t, (uint32_t)seed,
+                                                    (uint32_t)(seed >> 32), (uint32_t)(step * 4u), stats,
+                                                    dev_accept_len, dev_out_tokens, dev_dbg);
+    SPEC_LAUNCH_CHECK("reject_sample_kernel");
+    return SPEC_OK;
+}

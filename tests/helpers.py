@@ -1,0 +1,70 @@
+"""Shared test helpers: oracle-side input preparation and the comparison rules of the parity tests."""
+import numpy as np
+
+import synth_inputs as si
+from oracle import forward as of
+
+
+def oracle_drafts(cfg, w_or, kv_or, tokens0, ctx_len, k, noise_std, temperature, seed):
+    """Draft tokens and draft distributions the way the workloads define them:
+    q_i = softmax((target logits of the prefix + N(0, noise_std)) / T), x_i ~ q_i, with the target
+    logits taken from the ORACLE run autoregressively (inputs may come from the oracle, never from
+    the HIP path).  Returns tokens [B, k+1] (row 0 = tokens0) and q [B, k, V] fp32."""
+    rng = np.random.Generator(np.random.Philox(int(seed) + 4))
+    B, V = len(tokens0), cfg["vocab"]
+    toks = np.asarray(tokens0, dtype=np.int32).reshape(B, 1)
+    q = np.zeros((B, k, V), dtype=np.float32)
+    for i in range(k):
+        logits, _ = of.verify_forward(cfg, w_or, kv_or, toks, ctx_len)
+        qi = si.noisy_draft_distribution(logits[:, -1, :], rng.standard_normal((B, V)) * noise_std, temperature)
+        q[:, i, :] = qi
+        toks = np.concatenate([toks, si.draw_from(qi, rng).reshape(B, 1)], axis=1)
+    return toks.astype(np.int32), q
+
+
+def sampler_exemptions(pqu, keys, ratio_tol=1e-3, tie_tol=1e-4):
+    """Which trials may legitimately differ between fp32 kernels and the fp64 oracle.
+
+    near_threshold[b]: some evaluated accept test had |u - P/Q| < ratio_tol (the exemption the
+    build's target states); near_tie[b]: the two best race keys differ by less than tie_tol relative."""
+    B, k, _ = pqu.shape
+    near_threshold = np.zeros(B, dtype=bool)
+    for b in range(B):
+        for i in range(k):
+            P, Q, u = pqu[b, i]
+            if np.isnan(u):
+                continue
+            if Q > 0 and abs(u - P / Q) < ratio_tol:
+                near_threshold[b] = True
+    near_tie = (keys[:, 1] > 0) & ((keys[:, 0] - keys[:, 1]) <= tie_tol * keys[:, 0])
+    return near_threshold, near_tie
+
+
+def assert_sampler_parity(n_gpu, out_gpu, n_or, out_or, pqu, keys, max_exempt_frac=0.05):
+    """Bit-exact accept lengths and tokens except counted near-threshold / near-tie trials."""
+    near_threshold, near_tie = sampler_exemptions(pqu, keys)
+    B = len(n_or)
+    used = 0
+    for b in range(B):
+        same = n_gpu[b] == n_or[b] and np.array_equal(out_gpu[b], out_or[b])
+        if same:
+            continue
+        if near_threshold[b]:
+            used += 1
+            continue
+        if near_tie[b] and n_gpu[b] == n_or[b] and np.array_equal(out_gpu[b][:n_or[b]], out_or[b][:n_or[b]]):
+            used += 1
+            continue
+        raise AssertionError("sampler mismatch at b=%d: gpu n=%d %s, oracle n=%d %s, P/Q/u=%s keys=%s" %
+                             (b, n_gpu[b], out_gpu[b], n_or[b], out_or[b], pqu[b], keys[b]))
+    assert used <= max(2, max_exempt_frac * B), "too many exempted trials: %d of %d" % (used, B)
+    return dict(trials=B, near_threshold=int(near_threshold.sum()), near_tie=int(near_tie.sum()), exempt_used=used)
+
+
+def logits_close(got, want, abs_tol, rel_tol):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    err = np.abs(got - want)
+    bound = abs_tol + rel_tol * np.abs(want)
+    worst = float((err - bound).max())
+    return worst <= 0.0, float(err.max()), worst

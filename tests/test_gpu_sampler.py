@@ -1,0 +1,118 @@
+"""GPU parity of spec_reject_sample against the C oracle on the same seeded inputs.
+
+Accept lengths and emitted tokens must be bit-exact, except trials the oracle itself flags as
+decided by less than the kernel's fp32 precision: an accept test with |u - P/Q| < 1e-3, or a
+race whose two best keys differ by less than 1e-4 relative.  Those are counted and printed.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import sampler as oracle_sampler
+from tests.helpers import assert_sampler_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_gpu(logits, q, draft, temperature, seed, step):
+    from paper_2604_26779_amd import binding as sv
+    B, T, V = logits.shape
+    k = T - 1
+    dev = "cuda"
+    d_logits = torch.from_numpy(logits).to(dev)
+    d_q = torch.from_numpy(q).to(dev) if k > 0 else None
+    d_draft = torch.from_numpy(draft).to(dev) if k > 0 else None
+    n = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    out = torch.full((B, T), -7, dtype=torch.int32, device=dev)
+    dbg = torch.zeros((B, max(k, 1), 3), dtype=torch.float32, device=dev)
+    ws = torch.empty(sv.spec_sample_workspace_bytes(B, k), dtype=torch.uint8, device=dev)
+    sv.spec_reject_sample(B, k, V, d_logits, d_q, d_draft, temperature, seed, step, n, out, dbg, ws)
+    torch.cuda.synchronize()
+    return n.cpu().numpy(), out.cpu().numpy(), dbg.cpu().numpy()
+
+
+@pytest.mark.parametrize("B,k,V,temperature,noise", [
+    (7, 3, 1000, 1.0, 1.0),          # several wavefronts, ragged tail (V % 4 == 0 but V % 1024 != 0)
+    (5, 7, 4001, 0.7, 0.5),          # V % 4 != 0, k = 7, temperature != 1
+    (3, 0, 50, 1.0, 1.0),            # k = 0: plain sampling from the target
+    (64, 1, 257, 1.3, 2.0),
+    (32, 3, 128256, 1.0, 1.0),       # the full-size vocabulary and batch of the 8B workload
+    (256, 5, 32000, 1.0, 0.3),
+])
+def test_parity_on_synthetic_logits(B, k, V, temperature, noise):
+    logits, q, draft = si.make_sampler_case(B, k, V, seed=B * 1000 + k, noise_std=noise, temperature=temperature)
+    seed, step = 0x1234ABCD5678EF01, 11
+    n_or, out_or, pqu, keys = oracle_sampler.reject_sample(logits, q, draft, temperature, seed, step, debug=True)
+    n_gpu, out_gpu, dbg = _run_gpu(logits, q, draft, temperature, seed, step)
+    stats = assert_sampler_parity(n_gpu, out_gpu, n_or, out_or, pqu, keys)
+    print("sampler parity", dict(B=B, k=k, V=V), stats, "mean accepted+1 = %.3f" % (n_or.mean() + 1))
+    # the debug triples agree with the oracle's where both evaluated the test
+    for b in range(B):
+        for i in range(min(k, n_or[b] + 1)):
+            if n_gpu[b] == n_or[b]:
+                assert dbg[b, i, 2] == np.float32(pqu[b, i, 2])                 # identical uniform
+                assert abs(dbg[b, i, 0] - pqu[b, i, 0]) <= 1e-5 * pqu[b, i, 0] + 1e-12
+                assert dbg[b, i, 1] == np.float32(pqu[b, i, 1])
+
+
+def test_draft_equal_target_and_zero_probability_draft():
+    B, k, V = 40, 3, 3000
+    rng = np.random.default_rng(5)
+    logits = (rng.standard_normal((B, k + 1, V)) * 2).astype(np.float32)
+    z = logits[:, :k].astype(np.float64)
+    z -= z.max(-1, keepdims=True)
+    q = np.exp(z)
+    q = (q / q.sum(-1, keepdims=True)).astype(np.float32)
+    draft = rng.integers(0, V, size=(B, k)).astype(np.int32)
+    n_gpu, out_gpu, _ = _run_gpu(logits, q, draft, 1.0, 99, 0)
+    n_or, out_or = oracle_sampler.reject_sample(logits, q, draft, 1.0, 99, 0)
+    # P/Q is 1 up to rounding: the oracle accepts everything; the kernel may reject only where its
+    # fp32 P rounds below Q and u lands within that rounding of 1
+    assert np.all(n_or == k)
+    assert (n_gpu == k).mean() > 0.9
+    agree = n_gpu == k
+    assert np.array_equal(out_gpu[agree], out_or[agree])
+
+    # a one-hot draft distribution on a token the target gives zero probability
+    logits2 = logits.copy()
+    logits2[:, :, 17] = -np.inf
+    q2 = np.zeros_like(q)
+    q2[:, :, 17] = 1.0
+    draft2 = np.full((B, k), 17, dtype=np.int32)
+    n_gpu, out_gpu, _ = _run_gpu(logits2, q2, draft2, 1.0, 7, 3)
+    n_or, out_or, pqu, keys = oracle_sampler.reject_sample(logits2, q2, draft2, 1.0, 7, 3, debug=True)
+    assert np.all(n_gpu == 0) and np.all(n_or == 0)
+    assert_sampler_parity(n_gpu, out_gpu, n_or, out_or, pqu, keys)
+    assert np.all(out_gpu[:, 0] != 17) and np.all(out_gpu[:, 1:] == -1)
+
+
+def test_out_of_range_draft_is_rejected_and_results_are_deterministic():
+    B, k, V = 6, 3, 500
+    logits, q, draft = si.make_sampler_case(B, k, V, seed=3)
+    draft[2, 1] = V + 5
+    draft[4, 0] = -1
+    a = _run_gpu(logits, q, draft, 1.0, 5, 5)
+    b = _run_gpu(logits, q, draft, 1.0, 5, 5)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    assert a[0][2] <= 1 and a[0][4] == 0
+    c = _run_gpu(logits, q, draft, 1.0, 5, 6)
+    assert not np.array_equal(a[1], c[1])
+
+
+def test_argument_errors():
+    from paper_2604_26779_amd import binding as sv
+    t = torch.zeros(16, dtype=torch.float32, device="cuda")
+    i = torch.zeros(16, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    for args in [
+        (0, 1, 4, t, t, i, 1.0, 0, 0, i, i, None, ws),            # B < 1
+        (1, 16, 4, t, t, i, 1.0, 0, 0, i, i, None, ws),           # k > SPEC_MAX_DRAFT
+        (1, 1, 4, t, t, i, 0.0, 0, 0, i, i, None, ws),            # temperature 0
+        (1, 1, 4, t, None, i, 1.0, 0, 0, i, i, None, ws),         # q missing with k > 0
+        (1, 1, 4, t, t, i, 1.0, 0, 1 << 30, i, i, None, ws),      # step too large
+        (1, 1, 4, t, t, i, 1.0, 0, 0, i, i, None, ws[:4]),        # workspace too small
+    ]:
+        with pytest.raises(sv.SpecError) as e:
+            sv.spec_reject_sample(*args)
+        assert e.value.status == sv.SPEC_EINVAL

@@ -1,0 +1,247 @@
+"""GPU parity of the whole verify step (forward -> rejection sampling -> KV commit) through the
+C ABI against the CPU oracle, on workloads the oracle finishes in seconds:
+
+  * tiny_fp32_b4_ctx128_k3 : the fp32 configuration, true prefill computed by the oracle;
+    logits within 1e-4, end-to-end sampling and commit compared with the oracle's own chain.
+  * small_bf16_b5_k3       : the MFMA path at a size that spans several GEMM tiles, ragged N and
+    vocabulary tails, ragged contexts (several attention chunks, partial pages), GQA;
+    logits within 2e-2 abs + 1e-2 rel of the fp64 oracle on bf16-rounded weights and cache.
+Drafts and draft distributions come from the oracle run autoregressively (never from the HIP path).
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import commit as oracle_commit
+from oracle import forward as of
+from oracle import sampler as oracle_sampler
+from tests.helpers import assert_sampler_parity, logits_close, oracle_drafts
+
+pytestmark = pytest.mark.gpu
+
+SEED = si.DEFAULT_SEED
+TOL = {"f32": (1e-4, 1e-4), "bf16": (2e-2, 1e-2)}
+KV_TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _setup(workload_name, k=None, prefill="oracle", shuffle=True, seed=SEED, B=None):
+    from paper_2604_26779_amd.session import VerifySession
+    wl = dict(si.WORKLOADS[workload_name])
+    if k is not None:
+        wl["k"] = k
+    if B is not None:
+        wl["B"] = B
+    cfg = si.MODELS[wl["model"]]
+    weights = si.make_weights(cfg, seed=seed)
+    w_or = si.weights_for_oracle(cfg, weights)
+    batch = si.make_batch(wl, seed=seed, shuffle_pages=shuffle)
+    ctx_len = batch["ctx_len"]
+    if prefill == "oracle":
+        toks = np.stack(batch["ctx_tokens"]) if len(set(ctx_len)) == 1 else None
+        if toks is not None:
+            kv_or = of.prefill(cfg, w_or, toks)
+        else:
+            per = [of.prefill(cfg, w_or, t[None, :]) for t in batch["ctx_tokens"]]
+            kv_or = [[per[b][l][0] for b in range(len(per))] for l in range(cfg["n_layers"])]
+        # the cache holds storage-type values: round what the oracle computed, then both sides use that
+        kv_or = [[(si.round_to_storage(K, cfg["dtype"]), si.round_to_storage(V, cfg["dtype"])) for (K, V) in per_l]
+                 for per_l in kv_or]
+    else:
+        kv_or = si.kv_for_oracle(si.make_logical_kv(cfg, ctx_len, seed=seed))
+    max_ctx = int(ctx_len.max()) + 64
+    sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=wl["B"] + 2, max_ctx_len=max_ctx,
+                         n_pages=batch["n_pages"] + 4 * wl["B"] + 64)
+    sess.pool.normal_()                                   # stale data everywhere a step must not read
+    seq_ids = np.arange(wl["B"], dtype=np.int32) + 1      # sequence ids differ from batch positions
+    for b in range(wl["B"]):
+        sess.assign(int(seq_ids[b]), int(ctx_len[b]), batch["page_lists"][b])
+        for l in range(cfg["n_layers"]):
+            K, V = kv_or[l][b]
+            sess.write_logical_kv(l, batch["page_lists"][b], torch.from_numpy(K), torch.from_numpy(V))
+    return wl, cfg, w_or, kv_or, batch, sess, seq_ids
+
+
+def _book(batch, sess, seq_ids, ctx_len):
+    book = oracle_commit.KVBook(sess.n_pages, si.PAGE_SIZE)
+    for b, s in enumerate(seq_ids):
+        book.assign(int(s), int(ctx_len[b]), batch["page_lists"][b])
+    return book
+
+
+def _check_state(sess, book, seq_ids):
+    st = sess.state()
+    for s in seq_ids:
+        s = int(s)
+        assert st["ctx_len"][s] == book.ctx_len[s]
+        assert st["n_pages"][s] == len(book.pages[s])
+        assert list(st["page_table"][s][:len(book.pages[s])]) == book.pages[s]
+    assert list(st["free_stack"]) == book.free
+
+
+@pytest.mark.parametrize("workload", ["tiny_fp32_b4_ctx128_k3", "small_bf16_b5_k3"])
+def test_full_step_parity(workload):
+    wl, cfg, w_or, kv_or, batch, sess, seq_ids = _setup(workload)
+    B, k, T_ = wl["B"], wl["k"], wl["temperature"]
+    ctx_len = batch["ctx_len"]
+    tokens, q = oracle_drafts(cfg, w_or, kv_or, batch["tokens0"], ctx_len, k, wl["noise_std"], T_, SEED)
+    want_logits, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens, ctx_len)
+
+    d_seq = torch.from_numpy(seq_ids).cuda()
+    d_tok = torch.from_numpy(tokens).cuda()
+    logits = sess.forward(d_seq, d_tok)
+    torch.cuda.synchronize()
+    got = logits.cpu().numpy()
+    ok, max_err, worst = logits_close(got, want_logits, *TOL[cfg["dtype"]])
+    print(workload, "logits max abs err %.3e (|logit| max %.2f)" % (max_err, np.abs(want_logits).max()))
+    assert ok, (max_err, worst)
+
+    # the k+1 new cache entries of every layer sit in the reserved slots
+    book = _book(batch, sess, seq_ids, ctx_len)
+    book.reserve([int(s) for s in seq_ids], k)
+    st = sess.state()
+    for b, s in enumerate(seq_ids):
+        pages = book.pages[int(s)]
+        assert list(st["page_table"][int(s)][:len(pages)]) == pages
+        for l in range(cfg["n_layers"]):
+            K, V = sess.read_logical_kv(l, pages, int(ctx_len[b]) + k + 1)
+            K, V = K.float().cpu().numpy(), V.float().cpu().numpy()
+            c = int(ctx_len[b])
+            assert np.array_equal(K[:c], kv_or[l][b][0]) and np.array_equal(V[:c], kv_or[l][b][1])   # context untouched
+            assert np.max(np.abs(K[c:] - new_kv[l][0][b])) < KV_TOL[cfg["dtype"]] * max(1.0, np.abs(new_kv[l][0][b]).max())
+            assert np.max(np.abs(V[c:] - new_kv[l][1][b])) < KV_TOL[cfg["dtype"]] * max(1.0, np.abs(new_kv[l][1][b]).max())
+
+    # sampling: (1) kernel vs oracle sampler on identical logits (the oracle's), bit-exact modulo flagged trials
+    seed, step = 424242, 3
+    d_q, d_draft = torch.from_numpy(q).cuda(), torch.from_numpy(tokens[:, 1:].copy()).cuda()
+    d_or_logits = torch.from_numpy(want_logits.astype(np.float32)).cuda()
+    n_dev, out_dev = sess.sample(d_or_logits, d_q, d_draft, T_, seed, step)
+    torch.cuda.synchronize()
+    n_or, out_or, pqu, keys = oracle_sampler.reject_sample(want_logits.astype(np.float32), q, tokens[:, 1:], T_, seed, step,
+                                                           debug=True)
+    print(workload, "sampler on oracle logits", assert_sampler_parity(n_dev.cpu().numpy(), out_dev.cpu().numpy(), n_or, out_or, pqu, keys))
+
+    # (2) the chained step: HIP logits -> HIP sampler -> HIP commit, no host sync in between
+    n_dev, out_dev = sess.sample(logits, d_q, d_draft, T_, seed, step)
+    new_len, slots = sess.commit(d_seq, n_dev, k)
+    torch.cuda.synchronize()
+    n_gpu = n_dev.cpu().numpy()
+    if cfg["dtype"] == "f32":       # logits agree to 1e-4: the chain must reproduce the oracle's chain modulo flagged trials
+        print(workload, "end-to-end", assert_sampler_parity(n_gpu, out_dev.cpu().numpy(), n_or, out_or, pqu, keys, max_exempt_frac=0.5))
+    want_len, want_slots = book.commit([int(s) for s in seq_ids], n_gpu, k)
+    assert list(new_len.cpu().numpy()) == want_len
+    assert slots.cpu().numpy().tolist() == want_slots
+    _check_state(sess, book, seq_ids)
+    print(workload, "accepted lengths", n_gpu.tolist(), "alpha = %.2f" % oracle_commit.mean_acceptance_length(n_gpu))
+    sess.close()
+
+
+@pytest.mark.parametrize("workload,k", [("small_bf16_b5_k3", 1), ("small_bf16_b5_k3", 7), ("tiny_fp32_b4_ctx128_k3", 0),
+                                        ("tiny_fp32_b4_ctx128_k3", 5)])
+def test_logits_parity_other_draft_lengths(workload, k):
+    wl, cfg, w_or, kv_or, batch, sess, seq_ids = _setup(workload, k=k, prefill="synthetic")
+    rng = np.random.default_rng(k)
+    tokens = np.concatenate([batch["tokens0"][:, None], rng.integers(0, cfg["vocab"], size=(wl["B"], k))], axis=1).astype(np.int32)
+    want, _ = of.verify_forward(cfg, w_or, kv_or, tokens, batch["ctx_len"])
+    logits = sess.forward(torch.from_numpy(seq_ids).cuda(), torch.from_numpy(tokens).cuda())
+    torch.cuda.synchronize()
+    ok, max_err, worst = logits_close(logits.cpu().numpy(), want, *TOL[cfg["dtype"]])
+    print(workload, "k=%d" % k, "logits max abs err %.3e" % max_err)
+    assert ok, (max_err, worst)
+    sess.close()
+
+
+def test_multi_step_rollout_matches_oracle_bookkeeping_and_logits():
+    """Three chained steps with forced accept lengths (commit driven from a device tensor): contexts,
+    page lists and the free stack follow the oracle's book, and the third step's logits - which read
+    K/V written by the first two - match the oracle's forward over the grown cache."""
+    wl, cfg, w_or, kv_or, batch, sess, seq_ids = _setup("small_bf16_b5_k3", prefill="synthetic")
+    B, k = wl["B"], wl["k"]
+    rng = np.random.default_rng(77)
+    ctx_len = batch["ctx_len"].copy()
+    book = _book(batch, sess, seq_ids, ctx_len)
+    d_seq = torch.from_numpy(seq_ids).cuda()
+    kv_cur = [[(K.copy(), V.copy()) for (K, V) in per] for per in kv_or]
+    for step in range(3):
+        tokens = rng.integers(0, cfg["vocab"], size=(B, k + 1)).astype(np.int32)
+        want, new_kv = of.verify_forward(cfg, w_or, kv_cur, tokens, ctx_len)
+        logits = sess.forward(d_seq, torch.from_numpy(tokens).cuda())
+        torch.cuda.synchronize()
+        ok, max_err, worst = logits_close(logits.cpu().numpy(), want, *TOL["bf16"])
+        assert ok, (step, max_err, worst)
+        n = rng.integers(0, k + 1, size=B).astype(np.int32)
+        book.reserve([int(s) for s in seq_ids], k)
+        new_len, slots = sess.commit(d_seq, torch.from_numpy(n).cuda(), k)
+        want_len, want_slots = book.commit([int(s) for s in seq_ids], n, k)
+        assert list(new_len.cpu().numpy()) == want_len and slots.cpu().numpy().tolist() == want_slots
+        _check_state(sess, book, seq_ids)
+        # the oracle's cache keeps the accepted prefix, rounded to the storage type like the real cache
+        for l in range(cfg["n_layers"]):
+            for b in range(B):
+                keepK = si.round_to_storage(new_kv[l][0][b][:n[b] + 1], cfg["dtype"])
+                keepV = si.round_to_storage(new_kv[l][1][b][:n[b] + 1], cfg["dtype"])
+                kv_cur[l][b] = (np.concatenate([kv_cur[l][b][0], keepK]), np.concatenate([kv_cur[l][b][1], keepV]))
+        ctx_len = ctx_len + n + 1
+    sess.close()
+
+
+def test_snapshot_restore_and_page_permutation_invariance():
+    wl, cfg, w_or, kv_or, batch, sess, seq_ids = _setup("small_bf16_b5_k3", prefill="synthetic", shuffle=True)
+    from paper_2604_26779_amd import binding as sv
+    B, k = wl["B"], wl["k"]
+    rng = np.random.default_rng(5)
+    tokens = rng.integers(0, cfg["vocab"], size=(B, k + 1)).astype(np.int32)
+    d_seq, d_tok = torch.from_numpy(seq_ids).cuda(), torch.from_numpy(tokens).cuda()
+    snap = torch.empty(sv.spec_kv_state_bytes(sess.kv), dtype=torch.uint8, device="cuda")
+    sv.spec_kv_snapshot(sess.kv, snap)
+    first = sess.forward(d_seq, d_tok).clone()
+    sess.commit(d_seq, torch.full((B,), k, dtype=torch.int32, device="cuda"), k)
+    sv.spec_kv_restore(sess.kv, snap)
+    again = sess.forward(d_seq, d_tok).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(first, again)                       # same state, same launch: bit-identical
+    st = sess.state()
+    assert list(st["ctx_len"][seq_ids]) == list(batch["ctx_len"])
+    with pytest.raises(sv.SpecError):
+        sv.spec_kv_restore(sess.kv, torch.empty_like(snap))
+    sess.close()
+    # contiguous instead of shuffled physical pages: logits must not depend on where pages live
+    wl2, cfg2, _, _, batch2, sess2, seq_ids2 = _setup("small_bf16_b5_k3", prefill="synthetic", shuffle=False)
+    other = sess2.forward(torch.from_numpy(seq_ids2).cuda(), d_tok)
+    torch.cuda.synchronize()
+    assert torch.equal(first, other)
+    sess2.close()
+
+
+def test_forward_argument_errors_and_pool_exhaustion():
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = si.MODELS["tiny_fp32"]
+    weights = {n: t.cuda() for n, t in si.make_weights(cfg).items()}
+    sess = VerifySession(cfg, weights, max_seqs=4, max_ctx_len=64, n_pages=3)
+    sess.assign(0, 16, [2])
+    sess.assign(1, 15, [0])
+    with pytest.raises(sv.SpecError) as e:                 # page already in use
+        sess.assign(2, 5, [0])
+    assert e.value.status == sv.SPEC_EINVAL
+    with pytest.raises(sv.SpecError):                      # wrong number of pages
+        sess.assign(2, 17, [1])
+    d_seq = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    tok = torch.zeros((2, 4), dtype=torch.int32, device="cuda")
+    buf = sess.step_buffers(2, 3)
+    with pytest.raises(sv.SpecError) as e:                 # sequence 0 needs a page, sequence 1 needs a page, one is free
+        sess.forward(d_seq, tok)
+    assert e.value.status == sv.SPEC_ENOMEM
+    with pytest.raises(sv.SpecError) as e:                 # workspace too small
+        sv.spec_verify_forward(sess.model, sess.kv, 2, 3, d_seq, tok, buf["logits"], buf["workspace"][:256])
+    assert e.value.status == sv.SPEC_EINVAL
+    with pytest.raises(sv.SpecError):                      # k out of range
+        sv.spec_verify_forward(sess.model, sess.kv, 2, 16, d_seq, tok, buf["logits"], buf["workspace"])
+    # one sequence alone fits
+    sess.forward(d_seq[:1], tok[:1])
+    torch.cuda.synchronize()
+    assert sess.state()["n_pages"][0] == 2
+    sess.close()
+    with pytest.raises(sv.SpecError) as e:                 # bf16 path needs head_dim 128
+        VerifySession(dict(cfg, dtype="bf16"), {n: t.bfloat16() for n, t in weights.items()}, 2, 64, 8)
+    assert e.value.status == sv.SPEC_EUNSUPPORTED

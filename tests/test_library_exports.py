@@ -1,0 +1,57 @@
+"""CPU checks of the boundary: the shared library loads, exports every function the header
+declares, and rejects bad arguments on the host before any device work (no GPU needed)."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sv():
+    from paper_2604_26779_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "spec_verify.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spec_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported(sv):
+    declared = _declared_functions()
+    assert len(declared) >= 20
+    lib = sv.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(sv.EXPORTS) == declared          # the binding covers the header, name for name
+    for name in declared:
+        assert callable(getattr(sv, name)), name
+
+
+def test_host_side_argument_checks_need_no_gpu(sv):
+    assert sv.spec_tune_get("attn_chunk_pages") == 32
+    with pytest.raises(sv.SpecError) as e:
+        sv.spec_tune_set("no_such_parameter", 1)
+    assert e.value.status == sv.SPEC_EINVAL and "no_such_parameter" in str(e.value)
+    sv.spec_tune_set("splits_o", 4)
+    assert sv.spec_tune_get("splits_o") == 4
+    sv.spec_tune_set("splits_o", 0)
+    cfg = dict(n_layers=3, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, ffn_dim=32, vocab=10,
+               rope_theta=1e4, rms_eps=1e-5, dtype="f32", tied_head=0)
+    assert sv.spec_model_weight_count(cfg) == 1 + 27 + 2
+    assert sv.spec_model_weight_count(dict(cfg, tied_head=1)) == 1 + 27 + 1
+    assert sv.spec_sample_workspace_bytes(4, 3) >= 4 * 4 * 8
+    assert sv.spec_sample_workspace_bytes(0, 3) == 0
+    # validated before any HIP call (the pointers are never dereferenced)
+    assert sv.lib().spec_reject_sample(0, 1, 4, 1, 1, 1, 1.0, 0, 0, 1, 1, None, 1, 64, None) == sv.SPEC_EINVAL
+    assert "out of range" in sv.spec_last_error()
+    assert sv.lib().spec_commit_kv(None, 1, 1, None, None, None, None, None) == sv.SPEC_EINVAL
+    assert sv.lib().spec_verify_forward(None, None, 1, 1, None, None, None, None, 0, None) == sv.SPEC_EINVAL
+    assert sv.lib().spec_verify_workspace_bytes(None, None, 1, 1) == 0
+    assert sv.lib().spec_kv_pool_bytes(None, 1, 0) == -1
