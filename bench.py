@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify step (forward -> rejection sampling -> KV commit) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+One "step" is one pass of the whole hot path over one synthetic batch that is resident in HBM
+before timing starts.  Prints ONE JSON line: accepted tokens/s (whole job = this one GPU),
+ms/step, the roofline object of the dominant kernel (HIP-event timing of every kernel class over
+a second, instrumented run of the same K steps) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+DEFAULT_WORKLOAD = "llama8b_b32_ctx1k-8k_k3"
+
+
+def run_steps(wl, sv, torch, n_steps, accept_out, step0):
+    """n_steps verify steps on the current stream; accept lengths of step i land in accept_out[i]."""
+    sess = wl.sess
+    B, k, V = wl.B, wl.k, wl.cfg["vocab"]
+    buf = sess.step_buffers(B, k)
+    draft = wl.tokens[:, 1:].contiguous()
+    T = wl.wl["temperature"]
+    ws = buf["workspace"]
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + ws.numel() - 256]
+    for i in range(n_steps):
+        wl.restore()                                             # same cache state every step
+        sv.spec_verify_forward(sess.model, sess.kv, B, k, wl.seq_ids, wl.tokens, buf["logits"], ws)
+        sv.spec_reject_sample(B, k, V, buf["logits"], wl.q, draft, T, wl.seed, step0 + i, accept_out[i],
+                              buf["out_tokens"], None, buf["sample_ws"])
+        sv.spec_commit_kv(sess.kv, B, k, wl.seq_ids, accept_out[i], buf["new_ctx_len"], buf["commit_slots"])
+
+
+def cpu_baseline(wl, torch, n_seqs):
+    """The CPU oracle, as it stands, on the first n_seqs sequences of the same batch at full depth."""
+    import numpy as np
+
+    import synth_inputs as si
+    from oracle import commit as oracle_commit
+    from oracle import forward as of
+    from oracle import sampler as oracle_sampler
+    cfg = wl.cfg
+    n_seqs = min(n_seqs, wl.B)
+    # inputs for the oracle: weights and the sampled sequences' cache, copied to the host (not timed)
+    weights = si.make_weights(cfg, seed=wl.seed, device=str(wl.device))
+    w_or = si.weights_for_oracle(cfg, weights)
+    del weights
+    torch.cuda.empty_cache()
+    kv_or = [[tuple(t.float().cpu().numpy() for t in wl.logical_kv(l, b)) for b in range(n_seqs)]
+             for l in range(cfg["n_layers"])]
+    tokens = wl.tokens[:n_seqs].cpu().numpy()
+    q = wl.q[:n_seqs].cpu().numpy()
+    ctx = wl.ctx_len[:n_seqs]
+    book = oracle_commit.KVBook(wl.sess.n_pages, si.PAGE_SIZE)
+    for b in range(n_seqs):
+        book.assign(b, int(ctx[b]), wl.batch["page_lists"][b])
+    t0 = time.perf_counter()
+    logits, _ = of.verify_forward(cfg, w_or, kv_or, tokens, ctx)
+    n, _ = oracle_sampler.reject_sample(logits.astype(np.float32), q, tokens[:, 1:], wl.wl["temperature"], wl.seed, 0)
+    book.reserve(list(range(n_seqs)), wl.k)
+    book.commit(list(range(n_seqs)), n, wl.k)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    produced = float((n + 1).sum())
+    return dict(value=produced / dt, unit="accepted tokens/s", cores=int(cores), kind="oracle",
+                sample="%d of %d sequences of the same batch at full depth (%d layers, full vocabulary): forward + "
+                       "rejection sampling + commit took %.1f s; weights are converted to fp64 per layer inside the timed region; not scaled"
+                       % (n_seqs, wl.B, cfg["n_layers"], dt),
+                seconds=dt), logits
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=2)
+    ap.add_argument("--tune", action="append", default=[], help="name=value launch parameter (repeatable)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU (the verify step shards by sequence with no exchange); "
+                 "run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.workloads import DeviceWorkload, algorithmic_bytes
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    for item in args.tune:
+        name, value = item.split("=")
+        sv.spec_tune_set(name, int(value))
+
+    wl = DeviceWorkload(args.workload)
+    wl.make_drafts()
+    B, k = wl.B, wl.k
+    K, W = args.steps, args.warmup
+    accept = torch.zeros((max(K, W), B), dtype=torch.int32, device="cuda")
+
+    run_steps(wl, sv, torch, W, accept, 0)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    run_steps(wl, sv, torch, K, accept, 1000)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = ev0.elapsed_time(ev1) / K
+    produced = float((accept[:K] + 1).sum().item())          # tokens produced = accepted drafts + 1 per sequence
+    accepted_drafts = float(accept[:K].sum().item())
+    tokens_per_s = produced / (ms_per_step * K / 1e3)
+
+    # instrumented run of the same K steps: HIP events around every kernel class
+    sv.spec_profile_begin(K * 400 + 64)
+    run_steps(wl, sv, torch, K, accept, 1000)
+    prof = sv.spec_profile_end()
+    per_step = {name: ms / K for name, (ms, cnt) in prof.items()}
+    launches = {name: cnt / K for name, (ms, cnt) in prof.items()}
+    alg = algorithmic_bytes(wl.cfg, wl.ctx_len, B, k)
+    gemm_ms = sum(per_step[n] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head"))
+    gemm_launches = sum(launches[n] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head"))
+    classes = {
+        "gemm_bf16_kernel": dict(ms=gemm_ms, launches=gemm_launches, bytes=alg["gemm"]),
+        "attn_partial_kernel": dict(ms=per_step["attn"], launches=launches["attn"], bytes=alg["attn"]),
+    }
+    dom = max(classes, key=lambda n: classes[n]["ms"])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+
+    def roof(c):
+        gbs = c["bytes"] / (c["ms"] / 1e3) / 1e9 if c["ms"] > 0 else 0.0
+        return dict(bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4),
+                    avg_launch_us=round(1e3 * c["ms"] / max(c["launches"], 1), 2),
+                    bytes_per_launch=int(c["bytes"] / max(c["launches"], 1)))
+    roofline = dict(kernel=dom, **roof(classes[dom]), traffic=traffic)
+    total_bytes = alg["gemm"] + alg["attn"] + alg["sampler"] + alg["logits_write"]
+
+    out = {
+        "metric": "accepted tokens/sec/GPU, 8B-shaped verify step k=3; % of HBM/MFMA roofline",
+        "value": round(tokens_per_s, 1), "unit": "accepted tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "B": B, "k": k, "ctx_tokens": int(wl.ctx_len.sum()),
+                   "model": wl.wl["model"], "page_size": 16, "pages": "shuffled"},
+        "verify_steps_per_s": round(1e3 / ms_per_step, 2),
+        "mean_acceptance_length": round(produced / (K * B), 3),
+        "accepted_draft_tokens_per_s": round(accepted_drafts / (ms_per_step * K / 1e3), 1),
+        "step_hbm": {"algorithmic_GB": round(total_bytes / 1e9, 3),
+                     "achieved_GBs": round(total_bytes / (ms_per_step / 1e3) / 1e9, 1),
+                     "frac_of_peak": round(total_bytes / (ms_per_step / 1e3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "roofline": roofline,
+        "kernels": {n: roof(c) for n, c in classes.items()},
+        "ms_per_step_by_class": {n: round(v, 4) for n, v in per_step.items() if v > 0},
+        "wall_s_timed_region": round(wall, 3),
+    }
+    if not args.no_cpu_baseline:
+        base, _ = cpu_baseline(wl, torch, args.cpu_seqs)
+        out["cpu_baseline"] = {kk: (round(v, 3) if isinstance(v, float) else v) for kk, v in base.items()}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -199,6 +199,19 @@ spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const int32_t* dev
 spec_status spec_tune_set(const char* name, int32_t value);
 int32_t spec_tune_get(const char* name);
 
+/*
+ * Per-kernel-class timing with HIP events on the stream the kernels run on (for benchmarks; adds
+ * one event per launch group while on).  spec_profile_begin creates up to max_events events once
+ * and switches recording on; the step calls then bracket each class of launches; spec_profile_end
+ * synchronises the device, switches recording off and fills host_ms[c] / host_counts[c]
+ * (c < spec_profile_class_count(), n = array length) with the summed milliseconds and the number
+ * of timed segments of class c.  Not thread-safe; meant for one stream at a time.
+ */
+int32_t spec_profile_class_count(void);
+const char* spec_profile_class_name(int32_t c);
+spec_status spec_profile_begin(int32_t max_events);
+spec_status spec_profile_end(double* host_ms, int64_t* host_counts, int32_t n);
+
 #ifdef __cplusplus
 }
 #endif

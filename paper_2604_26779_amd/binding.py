@@ -24,7 +24,8 @@ EXPORTS = [
     "spec_kv_alloc", "spec_kv_free", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_sample_workspace_bytes", "spec_reject_sample",
-    "spec_commit_kv", "spec_tune_set", "spec_tune_get",
+    "spec_commit_kv", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
+    "spec_profile_begin", "spec_profile_end",
 ]
 
 
@@ -77,6 +78,10 @@ def lib():
             "spec_commit_kv": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
             "spec_tune_set": (i32, [ctypes.c_char_p, i32]),
             "spec_tune_get": (i32, [ctypes.c_char_p]),
+            "spec_profile_class_count": (i32, []),
+            "spec_profile_class_name": (ctypes.c_char_p, [i32]),
+            "spec_profile_begin": (i32, [i32]),
+            "spec_profile_end": (i32, [vp, vp, i32]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -224,3 +229,25 @@ def spec_tune_set(name, value):
 
 def spec_tune_get(name):
     return lib().spec_tune_get(name.encode())
+
+
+def spec_profile_class_count():
+    return lib().spec_profile_class_count()
+
+
+def spec_profile_class_name(c):
+    name = lib().spec_profile_class_name(c)
+    return name.decode() if name else None
+
+
+def spec_profile_begin(max_events):
+    _check(lib().spec_profile_begin(int(max_events)))
+
+
+def spec_profile_end():
+    """Returns {class name: (milliseconds, timed segments)}."""
+    n = spec_profile_class_count()
+    ms = np.zeros(n, dtype=np.float64)
+    cnt = np.zeros(n, dtype=np.int64)
+    _check(lib().spec_profile_end(ms.ctypes.data, cnt.ctypes.data, n))
+    return {spec_profile_class_name(c): (float(ms[c]), int(cnt[c])) for c in range(n)}

@@ -42,9 +42,58 @@ int tune(const char* name)
     return it == tune_table().end() ? 0 : it->second;
 }
 
+bool g_prof_on = false;
+static std::vector<hipEvent_t> g_prof_events;
+static std::vector<int> g_prof_class;
+static size_t g_prof_used = 0;
+
+void prof_record(int cls, hipStream_t s)
+{
+    if (g_prof_used >= g_prof_events.size()) return;           // out of events: the tail is not timed
+    if (hipEventRecord(g_prof_events[g_prof_used], s) != hipSuccess) return;
+    g_prof_class[g_prof_used++] = cls;
+}
+
+static const char* const PROF_NAMES[PC_COUNT] = {
+    "other", "embed_norm", "gemm_qkv", "qkv_rope", "attn", "attn_reduce", "gemm_o", "resid_norm", "gemm_gu", "swiglu",
+    "gemm_down", "gemm_head", "sample_stats", "sample_draw", "kv_reserve", "kv_commit"};
+
 }  // namespace specv
 
 using namespace specv;
+
+extern "C" int32_t spec_profile_class_count(void) { return PC_COUNT; }
+extern "C" const char* spec_profile_class_name(int32_t c) { return c >= 0 && c < PC_COUNT ? PROF_NAMES[c] : nullptr; }
+
+extern "C" spec_status spec_profile_begin(int32_t max_events)
+{
+    if (max_events < 2 || max_events > (1 << 22)) { set_error("spec_profile_begin: max_events out of range"); return SPEC_EINVAL; }
+    while (g_prof_events.size() < (size_t)max_events) {
+        hipEvent_t e;
+        SPEC_HIP_TRY(hipEventCreate(&e));
+        g_prof_events.push_back(e);
+    }
+    g_prof_class.assign(g_prof_events.size(), 0);
+    g_prof_used = 0;
+    g_prof_on = true;
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_profile_end(double* host_ms, int64_t* host_counts, int32_t n)
+{
+    if (!g_prof_on) { set_error("spec_profile_end: profiling is not on"); return SPEC_ESTATE; }
+    g_prof_on = false;
+    if (!host_ms || !host_counts || n < PC_COUNT) { set_error("spec_profile_end: need %d slots", (int)PC_COUNT); return SPEC_EINVAL; }
+    SPEC_HIP_TRY(hipDeviceSynchronize());
+    for (int i = 0; i < n; ++i) { host_ms[i] = 0.0; host_counts[i] = 0; }
+    for (size_t i = 1; i < g_prof_used; ++i) {
+        float ms = 0.f;
+        SPEC_HIP_TRY(hipEventElapsedTime(&ms, g_prof_events[i - 1], g_prof_events[i]));
+        host_ms[g_prof_class[i]] += ms;
+        host_counts[g_prof_class[i]] += 1;
+    }
+    return SPEC_OK;
+}
 
 extern "C" const char* spec_last_error(void) { return g_error; }
 
@@ -382,8 +431,10 @@ extern "C" spec_status spec_verify_forward(spec_model* m, spec_kv* kv, int32_t B
         if (kv->ub.max_ctx + k + 1 > (int64_t)kv->max_pages * SPEC_PAGE_SIZE) { set_error("spec_verify_forward: a sequence would outgrow max_ctx_len"); return SPEC_EINVAL; }
     }
     hipStream_t s = (hipStream_t)stream;
+    prof_mark(PC_OTHER, s);
     spec_status st = launch_kv_reserve(kv, B, k, dev_seq_ids, s);
     if (st != SPEC_OK) return st;
+    prof_mark(PC_KV_RESERVE, s);
     kv->device_ahead = true;
     st = m->desc.dtype == SPEC_F32 ? f32_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_logits, ws, s)
                                    : bf16_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_logits, ws, ws_bytes, s);
@@ -395,8 +446,10 @@ extern "C" spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const i
 {
     if (!kv || !dev_seq_ids || !dev_accept_len) { set_error("spec_commit_kv: null pointer"); return SPEC_EINVAL; }
     if (B < 1 || B > kv->max_seqs || k < 0 || k > SPEC_MAX_DRAFT) { set_error("spec_commit_kv: B or k out of range"); return SPEC_EINVAL; }
+    prof_mark(PC_OTHER, (hipStream_t)stream);
     spec_status st = launch_kv_commit(kv, B, k, dev_seq_ids, dev_accept_len, dev_new_ctx_len, dev_commit_slots, (hipStream_t)stream);
     if (st != SPEC_OK) return st;
+    prof_mark(PC_KV_COMMIT, (hipStream_t)stream);
     kv->device_ahead = true;
     kv->ub.max_ctx += k + 1;
     kv->ub.added_ctx += (int64_t)B * (k + 1);

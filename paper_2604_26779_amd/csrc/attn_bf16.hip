@@ -281,10 +281,12 @@ spec_status launch_attention_bf16(const bf16_t* q, int B, int T, int G, int Hq, 
         default: set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 32", R); return SPEC_EUNSUPPORTED;
     }
     SPEC_LAUNCH_CHECK("attn_partial_kernel");
+    prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);
     attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, RB * 16, max_chunks, seq_ids, kv,
                                                                   mb_pad, (uint4*)xp_out);
     SPEC_LAUNCH_CHECK("attn_reduce_kernel");
+    prof_mark(PC_ATTN_REDUCE, s);
     return SPEC_OK;
 }
 

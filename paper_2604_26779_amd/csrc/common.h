@@ -13,6 +13,17 @@ namespace specv {
 void set_error(const char* fmt, ...);
 int tune(const char* name);
 
+// per-kernel-class timing with HIP events (spec_profile_begin / spec_profile_end); prof_mark(c, s)
+// is called after the launches of class c and costs one branch when profiling is off
+enum ProfClass {
+    PC_OTHER = 0, PC_EMBED_NORM, PC_GEMM_QKV, PC_QKV_ROPE, PC_ATTN, PC_ATTN_REDUCE, PC_GEMM_O, PC_RESID_NORM,
+    PC_GEMM_GU, PC_SWIGLU, PC_GEMM_DOWN, PC_GEMM_HEAD, PC_SAMPLE_STATS, PC_SAMPLE_DRAW, PC_KV_RESERVE, PC_KV_COMMIT,
+    PC_COUNT
+};
+extern bool g_prof_on;
+void prof_record(int cls, hipStream_t s);
+static inline void prof_mark(int cls, hipStream_t s) { if (g_prof_on) prof_record(cls, s); }
+
 #define SPEC_HIP_TRY(expr)                                                                  \
     do {                                                                                    \
         hipError_t e_ = (expr);                                                             \

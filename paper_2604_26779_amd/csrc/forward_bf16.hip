@@ -288,22 +288,32 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     rope_table_kernel<<<(unsigned)cdiv((int64_t)M * 64, 256), 256, 0, s>>>(M, T, dev_seq_ids, kv->d_ctx_len, 64, (double)d.rope_theta, rope);
     residual_rmsnorm_kernel<true><<<M, 256, 0, s>>>(x, nullptr, 0, 0, dev_tokens, (const unsigned short*)mdl->embed(), d.vocab,
                                                     (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+    prof_mark(PC_EMBED_NORM, s);
     for (int l = 0; l < d.n_layers; ++l) {
         int lp = kv->alias_mod > 0 ? l % kv->alias_mod : l;
         if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, s)) != SPEC_OK) return st;
+        prof_mark(PC_GEMM_QKV, s);
         qkv_rope_kernel<<<M, 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, (unsigned short*)qbuf);
+        prof_mark(PC_QKV_ROPE, s);
         if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_chunks, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
         if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, s)) != SPEC_OK) return st;
+        prof_mark(PC_GEMM_O, s);
         residual_rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)mdl->layer_w(l, 5), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+        prof_mark(PC_RESID_NORM, s);
         if ((st = launch_gemm_bf16(mdl->wgu[l], xp_h, M, part, 2 * F, p.s_gu, s)) != SPEC_OK) return st;
+        prof_mark(PC_GEMM_GU, s);
         swiglu_pack_kernel<<<(unsigned)cdiv((int64_t)M * (F / 8), 256), 256, 0, s>>>(part, p.s_gu, (int64_t)M * 2 * F, M, F, p.mb_pad, (uint4*)xp_f);
+        prof_mark(PC_SWIGLU, s);
         if ((st = launch_gemm_bf16(mdl->wd[l], xp_f, M, part, D, p.s_down, s)) != SPEC_OK) return st;
+        prof_mark(PC_GEMM_DOWN, s);
         const void* next_gain = l + 1 < d.n_layers ? mdl->layer_w(l + 1, 0) : mdl->final_norm();
         residual_rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+        prof_mark(PC_RESID_NORM, s);
     }
     if ((st = launch_gemm_bf16(mdl->head, xp_h, M, dev_logits, d.vocab, 1, s)) != SPEC_OK) return st;
+    prof_mark(PC_GEMM_HEAD, s);
     SPEC_LAUNCH_CHECK("bf16 forward");
     return SPEC_OK;
 }

@@ -190,11 +190,14 @@ extern "C" spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const
     hipStream_t s = (hipStream_t)stream;
     float inv_t = 1.0f / temperature;
     float2* stats = (float2*)dev_workspace;
+    prof_mark(PC_OTHER, s);
     row_stats_kernel<<<B * (k + 1), SAMP_THREADS, 0, s>>>(dev_logits, V, inv_t, stats);
     SPEC_LAUNCH_CHECK("row_stats_kernel");
+    prof_mark(PC_SAMPLE_STATS, s);
     reject_sample_kernel<<<B, SAMP_THREADS, 0, s>>>(k, V, dev_logits, dev_q, dev_draft_tokens, inv_t, (uint32_t)seed,
                                                     (uint32_t)(seed >> 32), (uint32_t)(step * 4u), stats,
                                                     dev_accept_len, dev_out_tokens, dev_dbg);
     SPEC_LAUNCH_CHECK("reject_sample_kernel");
+    prof_mark(PC_SAMPLE_DRAW, s);
     return SPEC_OK;
 }

@@ -1,0 +1,97 @@
+"""Build a full verify-step workload on the GPU from the seeded generators (used by bench.py and
+by the full-size parity tests).  Plumbing only: tensors are drawn, moved and indexed with torch;
+the draft stand-in (q = softmax((logits + noise) / T), x ~ q) is input generation, and the target
+logits it needs come from running the library's own forward pass during set-up.
+"""
+import numpy as np
+import torch
+
+import synth_inputs as si
+
+from . import binding as sv
+from .session import VerifySession
+
+
+class DeviceWorkload:
+    def __init__(self, workload_name, seed=si.DEFAULT_SEED, shuffle_pages=True, device="cuda", extra_pages=None,
+                 drop_canonical=True):
+        self.name = workload_name
+        self.wl = dict(si.WORKLOADS[workload_name])
+        self.cfg = si.MODELS[self.wl["model"]]
+        self.seed = seed
+        self.device = torch.device(device)
+        B, k = self.wl["B"], self.wl["k"]
+        self.B, self.k = B, k
+        self.batch = si.make_batch(self.wl, seed=seed, shuffle_pages=shuffle_pages)
+        self.ctx_len = self.batch["ctx_len"]
+        weights = si.make_weights(self.cfg, seed=seed, device=device)
+        n_pages = self.batch["n_pages"] + (extra_pages if extra_pages is not None else 4 * B + 64)
+        self.sess = VerifySession(self.cfg, weights, max_seqs=B, max_ctx_len=int(self.ctx_len.max()) + 256,
+                                  n_pages=n_pages, device=device)
+        if drop_canonical and self.cfg["dtype"] == "bf16":
+            # the library re-tiled the matrices into its own buffer; keep only what it still reads
+            keep = {"embed"} | {n for n in weights if n.endswith("norm")}
+            self.weights = {n: t for n, t in weights.items() if n in keep}
+            self.sess.weights = list(self.weights.values())
+            del weights
+            torch.cuda.empty_cache()
+        else:
+            self.weights = weights
+        # synthetic cached context: every slot of the pool ~ N(0,1) in the storage type
+        g = torch.Generator(device=device)
+        g.manual_seed(int(seed) + 2)
+        chunk = 1 << 28
+        flat = self.sess.pool
+        for at in range(0, flat.numel(), chunk):
+            flat[at:at + chunk].normal_(generator=g)
+        self.seq_ids = torch.arange(B, dtype=torch.int32, device=device)
+        for b in range(B):
+            self.sess.assign(b, int(self.ctx_len[b]), self.batch["page_lists"][b])
+        self.tokens = torch.zeros((B, k + 1), dtype=torch.int32, device=device)
+        self.tokens[:, 0] = torch.from_numpy(self.batch["tokens0"]).to(device)
+        self.q = torch.zeros((B, k, self.cfg["vocab"]), dtype=torch.float32, device=device)
+        self.snapshot = torch.empty(sv.spec_kv_state_bytes(self.sess.kv), dtype=torch.uint8, device=device)
+        sv.spec_kv_snapshot(self.sess.kv, self.snapshot)
+
+    def make_drafts(self):
+        """Fill tokens[:, 1:] and q: k passes of the target, each fixing the next draft token."""
+        g = torch.Generator(device=self.device)
+        g.manual_seed(int(self.seed) + 5)
+        T, std = self.wl["temperature"], self.wl["noise_std"]
+        for i in range(1, self.k + 1):
+            logits = self.sess.forward(self.seq_ids, self.tokens)
+            row = logits[:, i - 1, :]
+            noise = torch.randn(row.shape, generator=g, device=self.device, dtype=torch.float32) * std
+            qi = torch.softmax((row + noise) / T, dim=-1)
+            self.q[:, i - 1, :] = qi
+            self.tokens[:, i] = torch.multinomial(qi, 1, generator=g)[:, 0].to(torch.int32)
+        torch.cuda.synchronize()
+
+    def logical_kv(self, layer, b):
+        """(K, V) [ctx_len[b], Hkv, dh] of sequence b as the cache holds them (device tensors)."""
+        return self.sess.read_logical_kv(layer, self.batch["page_lists"][b], int(self.ctx_len[b]))
+
+    def restore(self, stream=None):
+        sv.spec_kv_restore(self.sess.kv, self.snapshot, stream)
+
+    def close(self):
+        self.sess.close()
+
+
+def algorithmic_bytes(cfg, ctx_len, B, k):
+    """Bytes one verify step must move, per kernel class (weights once per step, cached K/V once
+    per sequence, logits written once and read by the sampler)."""
+    L, D, F, V = cfg["n_layers"], cfg["d_model"], cfg["ffn_dim"], cfg["vocab"]
+    nq, nkv = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
+    eb = 2 if cfg["dtype"] == "bf16" else 4
+    layer_w = (nq + 2 * nkv) * D + D * nq + 2 * F * D + D * F
+    head_w = V * D
+    tokens = int(np.sum(ctx_len)) + B * (k + 1)
+    return dict(
+        gemm=(L * layer_w + head_w) * eb,
+        gemm_layers=L * layer_w * eb,
+        gemm_head=head_w * eb,
+        attn=tokens * 2 * nkv * eb * L,
+        sampler=B * (k + 1 + 2) * V * 4,
+        logits_write=B * (k + 1) * V * 4,
+    )
