@@ -17,7 +17,12 @@ Conventions of this build (the paper does not state them):
     pos * theta^(-2j/head_dim); no long-context frequency scaling;
   * query head j uses key/value head j // (n_q_heads // n_kv_heads);
   * scores are scaled by 1/sqrt(head_dim); row i sees cache positions 0 .. ctx_len[b]+i;
-  * silu(z) = z / (1 + exp(-z)); all projections are bias-free, weights are [out, in].
+  * silu(z) = z / (1 + exp(-z)); all projections are bias-free, weights are [out, in];
+  * the cache stores keys and values in the model's storage type (cfg["dtype"]: "bf16", "f32", or
+    "f64" for none) and attention reads what the cache stores: the keys and values of the k+1 input
+    positions are rounded to that type (round to nearest even) before any row attends to them, so
+    that a position's key and value are the same numbers in the step that writes them and in every
+    later step - which is what makes the verified distribution the one plain decoding would use.
 """
 import numpy as np
 
@@ -41,6 +46,21 @@ def rope(x, positions, theta):
     return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
 
 
+def round_to_storage(a, dtype_name):
+    """fp64 array rounded to the cache's storage type, returned as fp64."""
+    a = np.asarray(a, dtype=np.float64)
+    if dtype_name == "f64":
+        return a
+    f = a.astype(np.float32)                         # round to nearest even (IEEE conversion)
+    if dtype_name == "f32":
+        return f.astype(np.float64)
+    if dtype_name == "bf16":                         # keep the upper 16 bits, nearest even on the dropped ones
+        u = f.view(np.uint32).astype(np.uint64)
+        u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+        return u.astype(np.uint32).view(np.float32).astype(np.float64)
+    raise ValueError("unknown storage type %r" % (dtype_name,))
+
+
 def silu(z):
     return z / (1.0 + np.exp(-z))
 
@@ -54,7 +74,7 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len):
     """One verify forward.
 
     cfg      dict: n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab,
-                   rope_theta, rms_eps.
+                   rope_theta, rms_eps, dtype (storage type of the cache).
     weights  dict: 'embed' [V,d], 'layers' (list of dicts with attn_norm [d], wq [Hq*dh,d],
                    wk, wv [Hkv*dh,d], wo [d,Hq*dh], ffn_norm [d], wg, wu [F,d], wd [d,F]),
                    'final_norm' [d], 'head' [V,d] or None (tied to 'embed').
@@ -62,7 +82,7 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len):
     tokens   [B, k+1] int, ctx_len [B] int.
 
     Returns (logits [B,k+1,V] fp64, new_kv) with new_kv[layer] = (K [B,k+1,Hkv,dh], V [...]),
-    the keys (after rotation) and values of the k+1 input positions.
+    the keys (after rotation) and values of the k+1 input positions as the cache stores them.
     """
     tokens = np.asarray(tokens)
     B, T = tokens.shape
@@ -83,7 +103,8 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len):
         kx = (h @ np.asarray(w["wk"], dtype=np.float64).T).reshape(B * T, Hkv, dh)
         vx = (h @ np.asarray(w["wv"], dtype=np.float64).T).reshape(B * T, Hkv, dh)
         q = rope(q, pos, theta)
-        kx = rope(kx, pos, theta)
+        kx = round_to_storage(rope(kx, pos, theta), cfg["dtype"])
+        vx = round_to_storage(vx, cfg["dtype"])
         new_kv.append((kx.reshape(B, T, Hkv, dh).copy(), vx.reshape(B, T, Hkv, dh).copy()))
 
         attn = np.zeros((B * T, Hq, dh), dtype=np.float64)

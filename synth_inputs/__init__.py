@@ -47,7 +47,7 @@ WORKLOADS = {
 
 
 def torch_dtype(name):
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f64": torch.float64}[name]
 
 
 def _gen(seed, device):

@@ -21,7 +21,7 @@ import synth_inputs as si
 from oracle import forward as of
 
 CFG = dict(n_layers=2, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, ffn_dim=96, vocab=50,
-           rope_theta=1.0e4, rms_eps=1.0e-5, dtype="f32", tied_head=0)
+           rope_theta=1.0e4, rms_eps=1.0e-5, dtype="f64", tied_head=0)
 
 
 def _weights(cfg, seed=1, std=0.2):
@@ -35,7 +35,7 @@ def _weights(cfg, seed=1, std=0.2):
 
 
 def _random_ctx(cfg, ctx_len, seed=2):
-    return si.kv_for_oracle(si.make_logical_kv(cfg, ctx_len, seed=seed))
+    return si.kv_for_oracle(si.make_logical_kv(dict(cfg, dtype="f32" if cfg["dtype"] == "f64" else cfg["dtype"]), ctx_len, seed=seed))
 
 
 def _torch_reference(cfg, w, kv_ctx, tokens, ctx_len):
@@ -210,3 +210,33 @@ def test_sequences_are_independent():
     all_logits, _ = of.verify_forward(cfg, w, kv, tokens, ctx_len)
     one, _ = of.verify_forward(cfg, w, [[per[1]] for per in kv], tokens[1:2], ctx_len[1:2])
     assert np.max(np.abs(all_logits[1] - one[0])) < 1e-12
+
+
+def test_cache_storage_rounding_matches_library_conversion_and_is_applied_to_new_entries():
+    """The cache stores bf16 (or fp32): the oracle's rounding equals torch's conversion bit for bit, the
+    returned new entries are storage-type values, and a step that re-reads them from the cache (next
+    step's context) sees exactly what the writing step attended to."""
+    rng = np.random.default_rng(9)
+    a = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-6, 6, size=5000),
+                        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38]])
+    want = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(of.round_to_storage(a, "bf16"), want)
+    assert np.array_equal(of.round_to_storage(a, "f32"), a.astype(np.float32).astype(np.float64))
+    assert np.array_equal(of.round_to_storage(a, "f64"), a)
+
+    cfg = dict(CFG, dtype="bf16")
+    w = _weights(cfg, seed=11)
+    kv = _random_ctx(cfg, [6])
+    tokens = np.array([[1, 2, 3, 4]], dtype=np.int32)
+    logits, new_kv = of.verify_forward(cfg, w, kv, tokens, [6])
+    for l in range(cfg["n_layers"]):
+        for t in new_kv[l]:
+            assert np.array_equal(of.round_to_storage(t, "bf16"), t)
+    # decode the last position separately on the cache extended by the first three: same logits
+    cache = [[(np.concatenate([kv[l][0][0], new_kv[l][0][0][:3]]), np.concatenate([kv[l][0][1], new_kv[l][1][0][:3]]))]
+             for l in range(cfg["n_layers"])]
+    last, _ = of.verify_forward(cfg, w, cache, tokens[:, 3:], [9])
+    assert np.max(np.abs(last[0, 0] - logits[0, 3])) < 1e-12
+    # and the rounding matters: the unrounded variant differs
+    plain, _ = of.verify_forward(dict(cfg, dtype="f64"), w, kv, tokens, [6])
+    assert np.max(np.abs(plain - logits)) > 1e-6
