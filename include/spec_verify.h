@@ -72,7 +72,8 @@ int32_t spec_model_weight_count(const spec_model_desc* desc);
  * SPEC_BF16: the matrices are re-tiled once into a library-owned device buffer laid out for the
  * MFMA kernels (one hipMalloc of about the model's size); afterwards only embed and the norm
  * gains are still read from the caller's buffers.  BF16 needs head_dim == 128,
- * d_model % 128 == 0, ffn_dim % 128 == 0 and n_q_heads % n_kv_heads == 0, else SPEC_EUNSUPPORTED.
+ * d_model % 256 == 0, ffn_dim % 256 == 0 and n_q_heads % n_kv_heads == 0, else
+ * SPEC_EUNSUPPORTED.
  * Synchronises the device.  (Paper: the target model of Section 2.1; its shape is the caller's.)
  */
 spec_status spec_model_create(const spec_model_desc* desc, const void* const* dev_weights, int32_t n_weights,
@@ -211,6 +212,16 @@ int32_t spec_profile_class_count(void);
 const char* spec_profile_class_name(int32_t c);
 spec_status spec_profile_begin(int32_t max_events);
 spec_status spec_profile_end(double* host_ms, int64_t* host_counts, int32_t n);
+
+/*
+ * Calibration kernels of known size (for benchmarks: the measured HBM ceiling, and the reference
+ * that hardware traffic counters are scaled by).  spec_calib_read streams `bytes` (multiple of 16,
+ * 16-byte aligned) from dev_src and discards them (dev_sink4: 4 writable bytes);
+ * spec_calib_copy copies dev_src to dev_dst.  `workgroups` of 256 lanes walk the buffer with a grid
+ * stride.  Asynchronous on `stream`.
+ */
+spec_status spec_calib_read(const void* dev_src, size_t bytes, void* dev_sink4, int32_t workgroups, void* stream);
+spec_status spec_calib_copy(void* dev_dst, const void* dev_src, size_t bytes, int32_t workgroups, void* stream);
 
 #ifdef __cplusplus
 }

@@ -25,7 +25,7 @@ EXPORTS = [
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_sample_workspace_bytes", "spec_reject_sample",
     "spec_commit_kv", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
-    "spec_profile_begin", "spec_profile_end",
+    "spec_profile_begin", "spec_profile_end", "spec_calib_read", "spec_calib_copy",
 ]
 
 
@@ -82,6 +82,8 @@ def lib():
             "spec_profile_class_name": (ctypes.c_char_p, [i32]),
             "spec_profile_begin": (i32, [i32]),
             "spec_profile_end": (i32, [vp, vp, i32]),
+            "spec_calib_read": (i32, [vp, sz, vp, i32, vp]),
+            "spec_calib_copy": (i32, [vp, vp, sz, i32, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -251,3 +253,11 @@ def spec_profile_end():
     cnt = np.zeros(n, dtype=np.int64)
     _check(lib().spec_profile_end(ms.ctypes.data, cnt.ctypes.data, n))
     return {spec_profile_class_name(c): (float(ms[c]), int(cnt[c])) for c in range(n)}
+
+
+def spec_calib_read(src, nbytes, sink, workgroups, stream=None):
+    _check(lib().spec_calib_read(_ptr(src), int(nbytes), _ptr(sink), int(workgroups), _stream(stream)))
+
+
+def spec_calib_copy(dst, src, nbytes, workgroups, stream=None):
+    _check(lib().spec_calib_copy(_ptr(dst), _ptr(src), int(nbytes), int(workgroups), _stream(stream)))

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libspecverify.so")
 SOURCES = ["api.hip", "kvbook.hip", "sampler.hip", "forward_f32.hip", "gemm_bf16.hip", "attn_bf16.hip",
-           "forward_bf16.hip"]
+           "forward_bf16.hip", "calib.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

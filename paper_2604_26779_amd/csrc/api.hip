@@ -27,8 +27,8 @@ static std::map<std::string, int>& tune_table()
 {
     // launch parameters with their defaults; see gemm_bf16.hip / attn_bf16.hip for their meaning
     static std::map<std::string, int> t = {
-        {"gemm_wg_target", 512},   // split K until a GEMM launches about this many workgroups
-        {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
+        {"gemm_wg_target", 256},   // split K while a GEMM launches fewer workgroups than this
+        {"gemm_min_ksteps", 64},   // never split below this many 16-wide k-steps per workgroup
         {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
         {"attn_chunk_pages", 32},  // KV pages per attention workgroup
     };
@@ -134,8 +134,8 @@ static spec_status check_desc(const spec_model_desc& d)
     if (d.n_q_heads % d.n_kv_heads) { set_error("spec_model_create: n_q_heads must be a multiple of n_kv_heads"); return SPEC_EUNSUPPORTED; }
     if (d.dtype != SPEC_F32 && d.dtype != SPEC_BF16) { set_error("spec_model_create: unknown dtype"); return SPEC_EINVAL; }
     if (d.dtype == SPEC_BF16) {
-        if (d.head_dim != 128 || d.d_model % 128 || d.ffn_dim % 128) {
-            set_error("spec_model_create: the bf16 path needs head_dim == 128 and d_model, ffn_dim multiples of 128");
+        if (d.head_dim != 128 || d.d_model % 256 || d.ffn_dim % 256) {
+            set_error("spec_model_create: the bf16 path needs head_dim == 128 and d_model, ffn_dim multiples of 256");
             return SPEC_EUNSUPPORTED;
         }
         int rows = d.n_q_heads / d.n_kv_heads;

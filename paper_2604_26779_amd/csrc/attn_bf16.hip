@@ -9,7 +9,7 @@
 //                         reading K and V blocks straight into MFMA operand registers (the cache's
 //                         in-block layout is the operand order, so every load is a contiguous
 //                         1 KiB), two pages in flight per wavefront;
-//                           S^T = K Q^T   v_mfma_f32_16x16x32_bf16 (keys x queries)
+//                           S^T = K Q^T   v_mfma_f32_16x16x32_bf16 (keys x queries; Q as hi + lo bf16)
 //                           O^T += V^T P^T v_mfma_f32_16x16x16_bf16 (P^T comes out of S^T's
 //                                          accumulator layout without any shuffle);
 //                         the wavefronts' results are merged through LDS and written as an
@@ -19,6 +19,7 @@
 // Row r of a (batch entry, kv head) tile is input position r / G, query head kvh*G + r % G.
 // Row i sees cache positions 0 .. ctx+i (causal over the k+1 new positions).
 #include "common.h"
+#include "operand.h"
 
 namespace specv {
 
@@ -31,22 +32,15 @@ typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 constexpr int ATT_CP = 32;                 // pages per workgroup
 constexpr int ATT_WAVES = 4;
 constexpr int ATT_PPW = ATT_CP / ATT_WAVES;  // pages per wavefront
+constexpr int ATT_DEPTH = 3;                 // pages in flight per wavefront
 constexpr int DH = 128;
 constexpr int BLOCK_U4 = SPEC_PAGE_SIZE * DH * 2 / 16;   // 256 16-byte words per K or V block
-
-__device__ inline unsigned short f2bf(float f)
-{
-    unsigned int u = __float_as_uint(f);
-    if ((u & 0x7f800000u) == 0x7f800000u) return (unsigned short)((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
-    u += 0x7fffu + ((u >> 16) & 1u);           // round to nearest even
-    return (unsigned short)(u >> 16);
-}
 
 // part_o : [item][RB*16 rows][128] fp32, part_ml : [item][RB*16][2] (max in log2 domain, sum)
 // item = (b * Hkv + kvh) * max_chunks + chunk
 template <int RB>
 __global__ __launch_bounds__(256) void attn_partial_kernel(
-    const unsigned short* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
+    const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
     int layer_pool, float scale_log2, int max_chunks, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     const int chunk = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -62,21 +56,28 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
     int page_end = page0 + ATT_CP;
     if (page_end > n_pages_seq) page_end = n_pages_seq;
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int lq = lane & 15, lg = lane >> 4;
     const int R = T * G;
 
-    // query operands: lane (row lq, group lg) holds Q[row][s*32 + lg*8 .. +8], s = 0..3
-    bf16x8_t qf[RB][4];
+    // query operands: lane (row lq, group lg) holds Q[row][s*32 + lg*8 .. +8], s = 0..3, split into
+    // hi + lo bf16 (the queries arrive in fp32)
+    bf16x8_t qhi[RB][4], qlo[RB][4];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         int r = rb * 16 + lq;
-        const unsigned short* src = q + ((int64_t)(b * T + r / G) * Hq + kvh * G + r % G) * DH + lg * 8;
+        const float* src = q + ((int64_t)(b * T + r / G) * Hq + kvh * G + r % G) * DH + lg * 8;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (r < R) v = *(const u32x4_t*)(src + s * 32);
-            qf[rb][s] = __builtin_bit_cast(bf16x8_t, v);
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (r < R) {
+                float4 a = *(const float4*)(src + s * 32), c = *(const float4*)(src + s * 32 + 4);
+                v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = c.x; v[5] = c.y; v[6] = c.z; v[7] = c.w;
+            }
+            uint4 h4, l4;
+            split8(v, h4, l4);
+            qhi[rb][s] = __builtin_bit_cast(bf16x8_t, h4);
+            qlo[rb][s] = __builtin_bit_cast(bf16x8_t, l4);
         }
     }
     int row_limit[RB];                       // last visible cache position of this lane's query row
@@ -90,9 +91,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
     const int32_t* pt = kv.page_table + (int64_t)seq * kv.max_pages;
     const u32x4_t* pool = (const u32x4_t*)kv.pool;
     const int64_t layer_base = (int64_t)layer_pool * kv.n_pages;
-    auto block_ptr = [&](int logical_page, int is_v) {
-        int64_t pid = pt[logical_page];
-        return pool + ((((layer_base + pid) * 2 + is_v) * Hkv + kvh) * BLOCK_U4) + lane;
+    auto block_ptr = [&](int physical_page, int is_v) {
+        return pool + ((((layer_base + physical_page) * 2 + is_v) * Hkv + kvh) * BLOCK_U4) + lane;
     };
 
     float mrow[RB], lrow[RB];
@@ -105,10 +105,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
         for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
 
-    u32x4_t kf[2][4], vf[2][4];
-    auto load_page = [&](int slot, int logical_page) {
-        const u32x4_t* kp = block_ptr(logical_page, 0);
-        const u32x4_t* vp = block_ptr(logical_page, 1);
+    u32x4_t kf[ATT_DEPTH][4], vf[ATT_DEPTH][4];
+    auto load_page = [&](int slot, int physical_page) {
+        const u32x4_t* kp = block_ptr(physical_page, 0);
+        const u32x4_t* vp = block_ptr(physical_page, 1);
 #pragma unroll
         for (int s = 0; s < 4; ++s) kf[slot][s] = __builtin_nontemporal_load(kp + s * 64);
 #pragma unroll
@@ -122,8 +122,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
         for (int rb = 0; rb < RB; ++rb) {
             f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[slot][s]), qf[rb][s], sacc, 0, 0, 0);
+            for (int s = 0; s < 4; ++s) {
+                bf16x8_t kk = __builtin_bit_cast(bf16x8_t, kf[slot][s]);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qhi[rb][s], sacc, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qlo[rb][s], sacc, 0, 0, 0);
+            }
             float sv[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -142,9 +145,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
             }
             mrow[rb] = mnew;
             lrow[rb] = lrow[rb] * alpha + (p[0] + p[1] + p[2] + p[3]);
-            s16x4_t pb;
+            s16x4_t pb, pl;                    // probabilities as hi + lo bf16
 #pragma unroll
-            for (int j = 0; j < 4; ++j) pb[j] = (short)f2bf(p[j]);
+            for (int j = 0; j < 4; ++j) {
+                unsigned short h = to_bf16(p[j]);
+                pb[j] = (short)h;
+                pl[j] = (short)to_bf16(p[j] - from_bf16(h));
+            }
             if (alpha != 1.f) {
 #pragma unroll
                 for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] *= alpha;
@@ -161,21 +168,30 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
                 s16x4_t va = __builtin_bit_cast(s16x4_t, u32x2_t{v.x, v.y});
                 s16x4_t vb = __builtin_bit_cast(s16x4_t, u32x2_t{v.z, v.w});
                 oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb, oacc[rb][2 * cp], 0, 0, 0);
+                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pl, oacc[rb][2 * cp], 0, 0, 0);
                 oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pb, oacc[rb][2 * cp + 1], 0, 0, 0);
+                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pl, oacc[rb][2 * cp + 1], 0, 0, 0);
             }
         }
     };
 
-    int pg = page0 + wave;
-    if (pg < page_end) load_page(0, pg);
-    for (int it = 0; it < ATT_PPW; it += 2) {
-        int pg0 = page0 + wave + ATT_WAVES * it, pg1 = pg0 + ATT_WAVES, pg2 = pg1 + ATT_WAVES;
-        if (pg0 >= page_end) break;
-        if (pg1 < page_end) load_page(1, pg1);
-        process(0, pg0);
-        if (pg1 >= page_end) break;
-        if (pg2 < page_end) load_page(0, pg2);
-        process(1, pg1);
+    // All of this wavefront's physical page ids first (one round trip), then a ring of ATT_DEPTH
+    // pages in flight.  The loads are unconditional - past the wavefront's last page they re-read
+    // it (cache hits, result unused) - because the compiler can only count outstanding loads
+    // along branch-free code; a conditional load makes it drain the queue before every use.
+    int pid[ATT_PPW];
+#pragma unroll
+    for (int it = 0; it < ATT_PPW; ++it) {
+        int pg = page0 + wave + ATT_WAVES * it;
+        pid[it] = pt[pg < page_end ? pg : page_end - 1];
+    }
+#pragma unroll
+    for (int it = 0; it < ATT_DEPTH - 1; ++it) load_page(it, pid[it]);
+#pragma unroll
+    for (int it = 0; it < ATT_PPW; ++it) {
+        constexpr int AHEAD = ATT_DEPTH - 1;
+        load_page((it + AHEAD) % ATT_DEPTH, pid[it + AHEAD < ATT_PPW ? it + AHEAD : ATT_PPW - 1]);
+        if (page0 + wave + ATT_WAVES * it < page_end) process(it % ATT_DEPTH, page0 + wave + ATT_WAVES * it);
     }
 
     // per-row sums are spread over the 4 lane groups
@@ -255,18 +271,14 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
         o[4] += f * d.x; o[5] += f * d.y; o[6] += f * d.z; o[7] += f * d.w;
     }
     float inv = L > 0.f ? 1.0f / L : 0.f;
-    unsigned short h[8];
-    for (int j = 0; j < 8; ++j) h[j] = f2bf(o[j] * inv);
-    int m = b * T + r / G;
-    int kidx = (kvh * G + r % G) * DH + c8 * 8;
-    int ks = kidx >> 4, half = (kidx >> 3) & 1;
-    int64_t dst = ((int64_t)ks * mb_pad + (m >> 5)) * 64 + (m & 31) + 32 * half;
-    xp[dst] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    float res[8];
+    for (int j = 0; j < 8; ++j) res[j] = o[j] * inv;
+    xp_store8(xp, b * T + r / G, (kvh * G + r % G) * DH + c8 * 8, mb_pad, res);
 }
 
 int attn_chunk_pages() { return ATT_CP; }
 
-spec_status launch_attention_bf16(const bf16_t* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
+spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
                                   const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s)
 {
@@ -274,7 +286,7 @@ spec_status launch_attention_bf16(const bf16_t* q, int B, int T, int G, int Hq, 
     int RB = (int)cdiv(R, 16);
     float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
     dim3 grid((unsigned)max_chunks, (unsigned)Hkv, (unsigned)B);
-    const unsigned short* qq = (const unsigned short*)q;
+    const float* qq = q;
     switch (RB) {
         case 1: attn_partial_kernel<1><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, part_o, part_ml); break;
         case 2: attn_partial_kernel<2><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, part_o, part_ml); break;

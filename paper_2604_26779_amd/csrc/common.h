@@ -62,7 +62,7 @@ struct KvView {
 
 // ---- packed bf16 matrix for the MFMA GEMM (see gemm_bf16.hip for the tiling) ----
 struct PackedW {
-    const bf16_t* data = nullptr;  // [n_blocks][k_steps][64 lanes][8]
+    const bf16_t* data = nullptr;  // [k_steps / 8][n_blocks][8][64 lanes][8]
     int32_t N = 0, K = 0;          // logical sizes
     int32_t n_blocks = 0;          // ceil(N / 32)
     int32_t k_steps = 0;           // K / 16

@@ -1,6 +1,6 @@
 // bf16 verify forward: orchestration and the small kernels between the GEMMs and the attention.
 //
-// Per layer (residual stream x in fp32, every GEMM input in bf16 operand order "xp"):
+// Per layer (residual stream x in fp32, every GEMM input as hi + lo bf16 pairs in operand order "xp"):
 //   xp_h  = RMSNorm(x) * g                         (fused into the kernel that last touched x)
 //   part  = xp_h W_qkv^T                           gemm, split-K slices
 //   q, K, V = rotary(sum part)                     qkv_rope_kernel: q -> bf16 rows, K/V -> paged cache
@@ -12,6 +12,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "operand.h"
 
 namespace specv {
 
@@ -20,32 +21,9 @@ int gemm_mb_pad(int M);
 int gemm_pick_splits(const PackedW& W, int M, int forced);
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, hipStream_t s);
 int attn_chunk_pages();
-spec_status launch_attention_bf16(const bf16_t* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
+spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
                                   const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s);
-
-__device__ inline unsigned short to_bf16(float f)
-{
-    unsigned int u = __float_as_uint(f);
-    if ((u & 0x7f800000u) == 0x7f800000u) return (unsigned short)((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
-}
-__device__ inline float from_bf16(unsigned short h) { return __uint_as_float((unsigned int)h << 16); }
-
-__device__ inline uint4 pack8(const float* v)
-{
-    unsigned short h[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) h[j] = to_bf16(v[j]);
-    return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-}
-
-// index (in 16-byte words) of elements k .. k+7 (k % 8 == 0) of row m in operand order
-__device__ inline int64_t xp_index(int m, int k, int mb_pad)
-{
-    return ((int64_t)(k >> 4) * mb_pad + (m >> 5)) * 64 + (m & 31) + 32 * ((k >> 3) & 1);
-}
 
 __device__ inline float block_sum_256(float v, float* lds4)
 {
@@ -100,7 +78,7 @@ __global__ __launch_bounds__(256) void residual_rmsnorm_kernel(
         float v[8] = {a.x * r * from_bf16(g.x & 0xffff), a.y * r * from_bf16(g.x >> 16), a.z * r * from_bf16(g.y & 0xffff),
                       a.w * r * from_bf16(g.y >> 16),    b.x * r * from_bf16(g.z & 0xffff), b.y * r * from_bf16(g.z >> 16),
                       b.z * r * from_bf16(g.w & 0xffff), b.w * r * from_bf16(g.w >> 16)};
-        xp[xp_index(m, c, mb_pad)] = pack8(v);
+        xp_store8(xp, m, c, mb_pad, v);
     }
 }
 
@@ -121,7 +99,7 @@ __global__ void rope_table_kernel(int M, int T, const int32_t* __restrict__ seq_
 __global__ __launch_bounds__(256) void qkv_rope_kernel(
     const float* __restrict__ part, int splits, int64_t split_stride, int T, int Hq, int Hkv,
     const float2* __restrict__ rope, const int32_t* __restrict__ seq_ids, KvView kv, int layer_pool,
-    unsigned short* __restrict__ q_out)
+    float* __restrict__ q_out)
 {
     constexpr int DHc = 128, HALF = 64;
     const int m = blockIdx.x;
@@ -158,9 +136,9 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(
         uint2 plo = make_uint2(to_bf16(rl[0]) | (to_bf16(rl[1]) << 16), to_bf16(rl[2]) | (to_bf16(rl[3]) << 16));
         uint2 phi = make_uint2(to_bf16(ru[0]) | (to_bf16(ru[1]) << 16), to_bf16(ru[2]) | (to_bf16(ru[3]) << 16));
         if (h < Hq) {
-            unsigned short* dst = q_out + ((int64_t)m * Hq + h) * DHc;
-            *(uint2*)(dst + j) = plo;
-            *(uint2*)(dst + j + HALF) = phi;
+            float* dst = q_out + ((int64_t)m * Hq + h) * DHc;
+            *(float4*)(dst + j) = make_float4(rl[0], rl[1], rl[2], rl[3]);
+            *(float4*)(dst + j + HALF) = make_float4(ru[0], ru[1], ru[2], ru[3]);
         } else if (writable) {
             int kh = h - Hq;
             unsigned short* dst = pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 0) * Hkv + kh) * block;
@@ -205,7 +183,7 @@ __global__ void swiglu_pack_kernel(const float* __restrict__ part, int splits, i
     float v[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = g[j] / (1.0f + expf(-g[j])) * u[j];
-    xp[xp_index(m, f, mb_pad)] = pack8(v);
+    xp_store8(xp, m, f, mb_pad, v);
 }
 
 // ------------------------------------------------------------------ host side
@@ -236,12 +214,12 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     p.off_x = take((size_t)p.M * D * 4);
-    p.off_xp_h = take(rows * D * 2);
-    p.off_xp_a = take(rows * nq * 2);
-    p.off_xp_f = take(rows * F * 2);
+    p.off_xp_h = take(rows * D * 4);          // hi + lo
+    p.off_xp_a = take(rows * nq * 4);
+    p.off_xp_f = take(rows * F * 4);
     size_t part = std::max(std::max((size_t)p.s_qkv * nqkv, (size_t)p.s_o * D), std::max((size_t)p.s_gu * 2 * F, (size_t)p.s_down * D));
     p.off_part = take(part * p.M * 4);
-    p.off_q = take((size_t)p.M * nq * 2);
+    p.off_q = take((size_t)p.M * nq * 4);
     p.off_rope = take((size_t)p.M * (d.head_dim / 2) * 8);
     size_t items = (size_t)B * d.n_kv_heads * p.max_chunks;
     p.off_att_o = take(items * p.RBrows * d.head_dim * 4);
@@ -275,7 +253,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     bf16_t* xp_a = (bf16_t*)(base + p.off_xp_a);
     bf16_t* xp_f = (bf16_t*)(base + p.off_xp_f);
     float* part = (float*)(base + p.off_part);
-    bf16_t* qbuf = (bf16_t*)(base + p.off_q);
+    float* qbuf = (float*)(base + p.off_q);
     float2* rope = (float2*)(base + p.off_rope);
     float* att_o = (float*)(base + p.off_att_o);
     float* att_ml = (float*)(base + p.off_att_ml);
@@ -293,7 +271,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         int lp = kv->alias_mod > 0 ? l % kv->alias_mod : l;
         if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_QKV, s);
-        qkv_rope_kernel<<<M, 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, (unsigned short*)qbuf);
+        qkv_rope_kernel<<<M, 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, qbuf);
         prof_mark(PC_QKV_ROPE, s);
         if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_chunks, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
         if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, s)) != SPEC_OK) return st;

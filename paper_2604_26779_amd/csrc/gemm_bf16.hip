@@ -7,15 +7,21 @@
 //     output columns and every 16-wide k-step, the 64 lanes' 16-byte operands are contiguous
 //     (1 KiB).  A wavefront owns one 32-column block and reads its stream with perfectly
 //     coalesced 16-byte loads straight into registers; no LDS round trip for the weights.
-//   * the activations are written by the producing kernel in the same operand order
-//     ([k-step][32-row block][lane][8]), staged through LDS in slabs of KS k-steps (double
-//     buffered, one barrier per slab) and shared by the 4 wavefronts of the workgroup.
+//     The fragments are ordered [k-slab][column block][k-step in slab]: all wavefronts of a
+//     launch move through K together, so at any moment the chip reads one contiguous region
+//     (spread evenly over the HBM channels) instead of thousands of streams a power of two apart.
+//   * the activations are written by the producing kernel in the same operand order, as hi + lo
+//     bf16 pairs ([k-step][32-row block][hi|lo][lane][8], see operand.h), staged through LDS in
+//     slabs of KS k-steps (double buffered, one barrier per slab) and shared by the 4 wavefronts
+//     of the workgroup; each weight fragment feeds two MFMAs per row block (hi and lo).
 //   * v_mfma_f32_32x32x16_bf16: A = activation fragment (rows m), B = weight fragment
 //     (columns n), so a lane ends up with one output column and 16 rows: stores are
 //     128-byte row segments.
 //   * K is split across workgroups (grid.y) when N alone gives too few workgroups to keep
 //     256 CUs streaming; partial sums go to separate fp32 slices that the consumer adds up
 //     in a fixed order (deterministic).
+#include <type_traits>
+
 #include "common.h"
 
 namespace specv {
@@ -24,7 +30,9 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int GEMM_KS = 8;          // k-steps (of 16) per LDS slab
+constexpr int GEMM_KS = 4;          // k-steps (of 16) per LDS slab
+constexpr int GEMM_WD = 4;          // slabs of weight fragments each wavefront keeps in flight
+constexpr int GEMM_KUNIT = GEMM_KS * GEMM_WD;   // k-steps per split are a multiple of this
 constexpr int GEMM_THREADS = 256;
 
 size_t bf16_packed_elems(int N, int K) { return (size_t)cdiv(N, 32) * 32 * (size_t)K; }
@@ -38,8 +46,11 @@ __global__ void pack_w_kernel(PackParts parts, int N, int K, int k_steps, int64_
     if (idx >= total) return;
     int lane = (int)(idx & 63);
     int64_t frag = idx >> 6;
-    int ks = (int)(frag % k_steps);
-    int nb = (int)(frag / k_steps);
+    // frag = (slab * n_blocks + nb) * KS + kk
+    int kk = (int)(frag % GEMM_KS);
+    int n_blocks = (N + 31) / 32;
+    int nb = (int)((frag / GEMM_KS) % n_blocks);
+    int ks = (int)(frag / GEMM_KS / n_blocks) * GEMM_KS + kk;
     int n = nb * 32 + (lane & 31);
     int k0 = ks * 16 + (lane >> 5) * 8;
     uint4 v = make_uint4(0, 0, 0, 0);
@@ -59,7 +70,7 @@ __global__ void pack_w_kernel(PackParts parts, int N, int K, int k_steps, int64_
 spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_rows, int n_parts, int K, bf16_t* dev_out,
                              PackedW* out, hipStream_t s)
 {
-    if (n_parts < 1 || n_parts > 4 || K % 128) { set_error("bf16_pack_matrix: bad shape"); return SPEC_EINVAL; }
+    if (n_parts < 1 || n_parts > 4 || K % (16 * GEMM_KUNIT)) { set_error("bf16_pack_matrix: bad shape"); return SPEC_EINVAL; }
     PackParts pp;
     pp.n = n_parts;
     int N = 0;
@@ -81,15 +92,15 @@ spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_row
 }
 
 // ------------------------------------------------------------------ the GEMM
-// Wp : [n_blocks][k_steps][64] u32x4_t          Xp : [k_steps][mb_pad][64] u32x4_t
+// Wp : [k_steps / KS][n_blocks][KS][64] u32x4_t   Xp : [k_steps][mb_pad][hi|lo][64] u32x4_t
 // out: [splits][M][ldo] fp32 (slice stride = split_stride floats)
-template <int MB>
+template <int MB, int WD>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
     const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
     int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride)
 {
     constexpr int KS = GEMM_KS;
-    constexpr int SLAB = KS * MB * 64;                  // u32x4_t per slab
+    constexpr int SLAB = KS * MB * 128;                 // u32x4_t per slab (hi and lo operands)
     constexpr int XPT = SLAB / GEMM_THREADS;            // u32x4_t per thread per slab
     __shared__ u32x4_t lds[2 * SLAB];
 
@@ -102,8 +113,10 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
     const int n_slabs = (ks1 - ks0) / KS;
     const int mt = blockIdx.z;
 
-    const u32x4_t* wptr = Wp + ((int64_t)(active ? nb : 0) * k_steps + ks0) * 64 + lane;
-    const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mt * MB) * 64;
+    // slab s of this wavefront's column block: wptr + s * wslab
+    const u32x4_t* wptr = Wp + (((int64_t)(ks0 / KS) * n_blocks + (active ? nb : 0)) * KS) * 64 + lane;
+    const int64_t wslab = (int64_t)n_blocks * KS * 64;
+    const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mt * MB) * 128;
 
     f32x16_t acc[MB];
 #pragma unroll
@@ -111,47 +124,66 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
-    u32x4_t w[KS], xr[XPT];
+    // the weight stream runs WD slabs (WD * KS fragments of 1 KiB per wavefront) ahead of the MFMAs:
+    // a register ring, each entry refilled right after its last use
+    u32x4_t w[WD][KS], xr[XPT];
 
     auto load_x = [&](int slab) {
 #pragma unroll
         for (int j = 0; j < XPT; ++j) {
             int idx = threadIdx.x + GEMM_THREADS * j;
-            int kl = idx / (MB * 64), rem = idx % (MB * 64);
-            xr[j] = xbase[((int64_t)(slab * KS + kl) * mb_pad) * 64 + rem];
+            int kl = idx / (MB * 128), rem = idx % (MB * 128);
+            xr[j] = xbase[((int64_t)(slab * KS + kl) * mb_pad) * 128 + rem];
         }
     };
     auto store_x = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < XPT; ++j) lds[buf * SLAB + threadIdx.x + GEMM_THREADS * j] = xr[j];
     };
+    int buf = 0;
+    // No branch may sit between the loads and their use: the compiler can only count outstanding
+    // loads (s_waitcnt vmcnt(n)) along straight-line code, and falls back to draining the whole
+    // queue otherwise.  So every slab issues its prefetches unconditionally; past the end they
+    // re-read the last slab (cache hits, results unused).
+    auto slab_body = [&](auto slot_c, int s) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        const int s_w = s + WD < n_slabs ? s + WD : n_slabs - 1;
+        const int s_x = s + 1 < n_slabs ? s + 1 : n_slabs - 1;
+        const u32x4_t* wnext = wptr + (int64_t)s_w * wslab;
+        load_x(s_x);
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            bf16x8_t bw = __builtin_bit_cast(bf16x8_t, w[SLOT][kk]);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                bf16x8_t ahi = __builtin_bit_cast(bf16x8_t, lds[buf * SLAB + (kk * MB + mb) * 128 + lane]);
+                bf16x8_t alo = __builtin_bit_cast(bf16x8_t, lds[buf * SLAB + (kk * MB + mb) * 128 + 64 + lane]);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, bw, acc[mb], 0, 0, 0);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, bw, acc[mb], 0, 0, 0);
+            }
+            w[SLOT][kk] = __builtin_nontemporal_load(wnext + kk * 64);
+        }
+        store_x(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    };
 
+    // n_slabs is a multiple of WD (K % (16 * KS * WD) == 0 and split sizes are rounded to it)
     if (n_slabs > 0) {
 #pragma unroll
-        for (int i = 0; i < KS; ++i) w[i] = __builtin_nontemporal_load(wptr + i * 64);
+        for (int d = 0; d < WD; ++d) {
+            const int sd = d < n_slabs ? d : n_slabs - 1;
+#pragma unroll
+            for (int i = 0; i < KS; ++i) w[d][i] = __builtin_nontemporal_load(wptr + (int64_t)sd * wslab + i * 64);
+        }
         load_x(0);
         store_x(0);
         __syncthreads();
-        int buf = 0;
-        for (int s = 0; s < n_slabs; ++s) {
-            const bool more = s + 1 < n_slabs;
-            // the weight registers are refilled one k-step at a time, right after their last use:
-            // the stream stays KS fragments (8 KiB per wavefront) ahead of the MFMAs
-            const u32x4_t* wnext = wptr + (int64_t)(more ? s + 1 : s) * KS * 64;
-            if (more) load_x(s + 1);
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-                bf16x8_t bw = __builtin_bit_cast(bf16x8_t, w[kk]);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    bf16x8_t a = __builtin_bit_cast(bf16x8_t, lds[buf * SLAB + (kk * MB + mb) * 64 + lane]);
-                    acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bw, acc[mb], 0, 0, 0);
-                }
-                if (more) w[kk] = __builtin_nontemporal_load(wnext + kk * 64);
-            }
-            if (more) store_x(buf ^ 1);
-            __syncthreads();
-            buf ^= 1;
+        for (int s = 0; s < n_slabs; s += WD) {
+            slab_body(std::integral_constant<int, 0>{}, s);
+            if constexpr (WD > 1) slab_body(std::integral_constant<int, 1>{}, s + 1);
+            if constexpr (WD > 2) slab_body(std::integral_constant<int, 2>{}, s + 2);
+            if constexpr (WD > 3) slab_body(std::integral_constant<int, 3>{}, s + 3);
         }
     }
 
@@ -176,12 +208,12 @@ int gemm_pick_splits(const PackedW& W, int M, int forced)
 {
     int n_tiles = (int)cdiv(W.n_blocks, 4);
     int m_tiles = gemm_mb_pad(M) / gemm_mb(M);
-    int max_splits = W.k_steps / (tune("gemm_min_ksteps") > GEMM_KS ? tune("gemm_min_ksteps") : GEMM_KS);
+    int max_splits = W.k_steps / (tune("gemm_min_ksteps") > GEMM_KUNIT ? tune("gemm_min_ksteps") : GEMM_KUNIT);
     if (max_splits < 1) max_splits = 1;
-    int splits = forced > 0 ? forced : (int)((tune("gemm_wg_target") + n_tiles * m_tiles / 2) / (n_tiles * m_tiles));
+    int splits = forced > 0 ? forced : tune("gemm_wg_target") / (n_tiles * m_tiles);
     if (splits < 1) splits = 1;
     if (splits > max_splits) splits = max_splits;
-    int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KS) * GEMM_KS;
+    int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KUNIT) * GEMM_KUNIT;
     return (int)cdiv(W.k_steps, kps);
 }
 
@@ -189,17 +221,19 @@ int gemm_pick_splits(const PackedW& W, int M, int forced)
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, hipStream_t s)
 {
     int mb = gemm_mb(M), mb_pad = gemm_mb_pad(M);
-    int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KS) * GEMM_KS;
+    int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KUNIT) * GEMM_KUNIT;
     dim3 grid((unsigned)cdiv(W.n_blocks, 4), (unsigned)cdiv(W.k_steps, kps), (unsigned)(mb_pad / mb));
     int64_t stride = (int64_t)M * ldo;
     const u32x4_t* wp = (const u32x4_t*)W.data;
     const u32x4_t* xp = (const u32x4_t*)Xp;
+#define SPEC_GEMM_CASE(MBV) gemm_bf16_kernel<MBV, GEMM_WD><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride)
     switch (mb) {
-        case 1: gemm_bf16_kernel<1><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride); break;
-        case 2: gemm_bf16_kernel<2><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride); break;
-        case 3: gemm_bf16_kernel<3><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride); break;
-        default: gemm_bf16_kernel<4><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride); break;
+        case 1: SPEC_GEMM_CASE(1); break;
+        case 2: SPEC_GEMM_CASE(2); break;
+        case 3: SPEC_GEMM_CASE(3); break;
+        default: SPEC_GEMM_CASE(4); break;
     }
+#undef SPEC_GEMM_CASE
     SPEC_LAUNCH_CHECK("gemm_bf16_kernel");
     return SPEC_OK;
 }

@@ -121,18 +121,34 @@ def test_full_step_parity(workload):
                                                            debug=True)
     print(workload, "sampler on oracle logits", assert_sampler_parity(n_dev.cpu().numpy(), out_dev.cpu().numpy(), n_or, out_or, pqu, keys))
 
-    # (2) the chained step: HIP logits -> HIP sampler -> HIP commit, no host sync in between
+    # (2) the chained step: HIP logits -> HIP sampler -> HIP commit, no host sync in between.
+    # Nothing the HIP path produced is handed to the oracle: the chain is checked for what must hold
+    # whatever it sampled, and (fp32 configuration, logits equal to 1e-4) against the oracle's own chain.
+    from paper_2604_26779_amd import binding as sv
+    snap = torch.empty(sv.spec_kv_state_bytes(sess.kv), dtype=torch.uint8, device="cuda")
+    sv.spec_kv_snapshot(sess.kv, snap)
     n_dev, out_dev = sess.sample(logits, d_q, d_draft, T_, seed, step)
     new_len, slots = sess.commit(d_seq, n_dev, k)
     torch.cuda.synchronize()
-    n_gpu = n_dev.cpu().numpy()
-    if cfg["dtype"] == "f32":       # logits agree to 1e-4: the chain must reproduce the oracle's chain modulo flagged trials
-        print(workload, "end-to-end", assert_sampler_parity(n_gpu, out_dev.cpu().numpy(), n_or, out_or, pqu, keys, max_exempt_frac=0.5))
-    want_len, want_slots = book.commit([int(s) for s in seq_ids], n_gpu, k)
+    n_gpu, out_gpu = n_dev.cpu().numpy(), out_dev.cpu().numpy()
+    if cfg["dtype"] == "f32":
+        print(workload, "end-to-end", assert_sampler_parity(n_gpu, out_gpu, n_or, out_or, pqu, keys, max_exempt_frac=0.5))
+    assert np.all((n_gpu >= 0) & (n_gpu <= k))
+    assert list(new_len.cpu().numpy()) == list(ctx_len + n_gpu + 1)
+    slots_h = slots.cpu().numpy()
+    for b in range(B):
+        assert np.array_equal(out_gpu[b, :n_gpu[b]], tokens[b, 1:1 + n_gpu[b]])
+        assert 0 <= out_gpu[b, n_gpu[b]] < cfg["vocab"] and np.all(out_gpu[b, n_gpu[b] + 1:] == -1)
+        assert np.all(slots_h[b, :n_gpu[b] + 1] >= 0) and np.all(slots_h[b, n_gpu[b] + 1:] == -1)
+    print(workload, "accepted lengths", n_gpu.tolist(), "alpha = %.2f" % oracle_commit.mean_acceptance_length(n_gpu))
+
+    # (3) commit parity: same state, accept lengths from the ORACLE's sampler on both sides
+    sv.spec_kv_restore(sess.kv, snap)
+    new_len, slots = sess.commit(d_seq, torch.from_numpy(n_or).cuda(), k)
+    want_len, want_slots = book.commit([int(s) for s in seq_ids], n_or, k)
     assert list(new_len.cpu().numpy()) == want_len
     assert slots.cpu().numpy().tolist() == want_slots
     _check_state(sess, book, seq_ids)
-    print(workload, "accepted lengths", n_gpu.tolist(), "alpha = %.2f" % oracle_commit.mean_acceptance_length(n_gpu))
     sess.close()
 
 
