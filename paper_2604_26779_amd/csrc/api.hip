@@ -27,8 +27,8 @@ static std::map<std::string, int>& tune_table()
 {
     // launch parameters with their defaults; see gemm_bf16.hip / attn_bf16.hip for their meaning
     static std::map<std::string, int> t = {
-        {"gemm_wg_target", 256},   // split K while a GEMM launches fewer workgroups than this
-        {"gemm_min_ksteps", 64},   // never split below this many 16-wide k-steps per workgroup
+        {"gemm_wg_target", 512},   // split K while a GEMM launches fewer workgroups than this
+        {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
         {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
         {"attn_chunk_pages", 32},  // KV pages per attention workgroup
     };

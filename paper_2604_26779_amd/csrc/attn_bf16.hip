@@ -120,13 +120,14 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
         const bool need_mask = (logical_page + 1) * SPEC_PAGE_SIZE > ctx;  // page reaches into the new positions
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+            f32x4_t sacc = {0.f, 0.f, 0.f, 0.f}, sacc2 = {0.f, 0.f, 0.f, 0.f};    // two independent chains
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 bf16x8_t kk = __builtin_bit_cast(bf16x8_t, kf[slot][s]);
                 sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qhi[rb][s], sacc, 0, 0, 0);
-                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qlo[rb][s], sacc, 0, 0, 0);
+                sacc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qlo[rb][s], sacc2, 0, 0, 0);
             }
+            sacc += sacc2;
             float sv[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -136,26 +137,27 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
             float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            float mnew = fmaxf(mrow[rb], mx);
-            float alpha = 1.f, p[4] = {0.f, 0.f, 0.f, 0.f};
-            if (mnew > -INFINITY) {
-                alpha = exp2f(mrow[rb] - mnew);
+            const float mold = mrow[rb];
+            const float mnew = fmaxf(mold, mx);
+            const float msafe = mnew > -INFINITY ? mnew : 0.f;          // a row that has seen no key yet
+            float p[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) p[j] = exp2f(sv[j] - mnew);
-            }
+            for (int j = 0; j < 4; ++j) p[j] = __builtin_amdgcn_exp2f(sv[j] - msafe);
             mrow[rb] = mnew;
-            lrow[rb] = lrow[rb] * alpha + (p[0] + p[1] + p[2] + p[3]);
-            s16x4_t pb, pl;                    // probabilities as hi + lo bf16
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                unsigned short h = to_bf16(p[j]);
-                pb[j] = (short)h;
-                pl[j] = (short)to_bf16(p[j] - from_bf16(h));
-            }
-            if (alpha != 1.f) {
+            // the running maximum rarely moves after the first pages: rescale only when some row's did
+            if (__builtin_amdgcn_ballot_w64(mnew != mold) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f(mold - msafe);
+                lrow[rb] *= alpha;
 #pragma unroll
                 for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] *= alpha;
             }
+            lrow[rb] += (p[0] + p[1]) + (p[2] + p[3]);
+            unsigned int h01, l01, h23, l23;                             // probabilities as hi + lo bf16
+            split2(p[0], p[1], h01, l01);
+            split2(p[2], p[3], h23, l23);
+            const s16x4_t pb = __builtin_bit_cast(s16x4_t, u32x2_t{h01, h23});
+            const s16x4_t pl = __builtin_bit_cast(s16x4_t, u32x2_t{l01, l23});
+            s16x4_t va[4], vb[4];
 #pragma unroll
             for (int cp = 0; cp < 4; ++cp) {
                 u32x4_t v = vf[slot][cp];
@@ -165,12 +167,19 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
                     unsigned int m23 = (key0 + 2 < total ? 0x0000ffffu : 0u) | (key0 + 3 < total ? 0xffff0000u : 0u);
                     v.x &= m01; v.y &= m23; v.z &= m01; v.w &= m23;
                 }
-                s16x4_t va = __builtin_bit_cast(s16x4_t, u32x2_t{v.x, v.y});
-                s16x4_t vb = __builtin_bit_cast(s16x4_t, u32x2_t{v.z, v.w});
-                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb, oacc[rb][2 * cp], 0, 0, 0);
-                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pl, oacc[rb][2 * cp], 0, 0, 0);
-                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pb, oacc[rb][2 * cp + 1], 0, 0, 0);
-                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pl, oacc[rb][2 * cp + 1], 0, 0, 0);
+                va[cp] = __builtin_bit_cast(s16x4_t, u32x2_t{v.x, v.y});
+                vb[cp] = __builtin_bit_cast(s16x4_t, u32x2_t{v.z, v.w});
+            }
+            // hi products of all 8 channel blocks, then the lo products: no two MFMAs on one accumulator adjacent
+#pragma unroll
+            for (int cp = 0; cp < 4; ++cp) {
+                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[cp], pb, oacc[rb][2 * cp], 0, 0, 0);
+                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb[cp], pb, oacc[rb][2 * cp + 1], 0, 0, 0);
+            }
+#pragma unroll
+            for (int cp = 0; cp < 4; ++cp) {
+                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[cp], pl, oacc[rb][2 * cp], 0, 0, 0);
+                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb[cp], pl, oacc[rb][2 * cp + 1], 0, 0, 0);
             }
         }
     };

@@ -151,17 +151,29 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
         const int s_x = s + 1 < n_slabs ? s + 1 : n_slabs - 1;
         const u32x4_t* wnext = wptr + (int64_t)s_w * wslab;
         load_x(s_x);
+        // activation fragments of k-step kk+1 are fetched from LDS while the MFMAs of kk run;
+        // the hi products of all row blocks go first, then the lo products, so that two MFMAs
+        // on the same accumulator are never adjacent
+        u32x4_t a_cur[2 * MB], a_nxt[2 * MB];
+#pragma unroll
+        for (int i = 0; i < 2 * MB; ++i) a_cur[i] = lds[buf * SLAB + i * 64 + lane];
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
+            if (kk + 1 < KS) {
+#pragma unroll
+                for (int i = 0; i < 2 * MB; ++i) a_nxt[i] = lds[buf * SLAB + ((kk + 1) * 2 * MB + i) * 64 + lane];
+            }
             bf16x8_t bw = __builtin_bit_cast(bf16x8_t, w[SLOT][kk]);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                bf16x8_t ahi = __builtin_bit_cast(bf16x8_t, lds[buf * SLAB + (kk * MB + mb) * 128 + lane]);
-                bf16x8_t alo = __builtin_bit_cast(bf16x8_t, lds[buf * SLAB + (kk * MB + mb) * 128 + 64 + lane]);
-                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, bw, acc[mb], 0, 0, 0);
-                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, bw, acc[mb], 0, 0, 0);
-            }
+            for (int part = 0; part < 2; ++part)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a_cur[2 * mb + part]), bw, acc[mb], 0, 0, 0);
             w[SLOT][kk] = __builtin_nontemporal_load(wnext + kk * 64);
+            if (kk + 1 < KS) {
+#pragma unroll
+                for (int i = 0; i < 2 * MB; ++i) a_cur[i] = a_nxt[i];
+            }
         }
         store_x(buf ^ 1);
         __syncthreads();

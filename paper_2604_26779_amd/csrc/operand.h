@@ -17,26 +17,32 @@
 
 namespace specv {
 
-__device__ inline unsigned short to_bf16(float f)
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+
+// two floats -> two bf16 in one 32-bit word (a in the low half); round to nearest even in hardware
+// (v_cvt_pk_bf16_f32 on gfx950)
+__device__ inline unsigned int pack_bf16x2(float a, float b)
 {
-    unsigned int u = __float_as_uint(f);
-    if ((u & 0x7f800000u) == 0x7f800000u) return (unsigned short)((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
-    u += 0x7fffu + ((u >> 16) & 1u);           // round to nearest even
-    return (unsigned short)(u >> 16);
+    return __builtin_bit_cast(unsigned int, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
 }
+__device__ inline unsigned short to_bf16(float f) { return (unsigned short)(pack_bf16x2(f, 0.f) & 0xffffu); }
 __device__ inline float from_bf16(unsigned short h) { return __uint_as_float((unsigned int)h << 16); }
+
+// (a, b) -> hi word and lo word: x = hi + lo with hi = bf16(x), lo = bf16(x - hi)
+__device__ inline void split2(float a, float b, unsigned int& hi, unsigned int& lo)
+{
+    hi = pack_bf16x2(a, b);
+    lo = pack_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+}
 
 // v[0..7] -> 8 x hi and 8 x lo, each packed into 16 bytes
 __device__ inline void split8(const float* v, uint4& hi, uint4& lo)
 {
-    unsigned short h[8], l[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        h[j] = to_bf16(v[j]);
-        l[j] = to_bf16(v[j] - from_bf16(h[j]));
-    }
-    hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+    split2(v[0], v[1], hi.x, lo.x);
+    split2(v[2], v[3], hi.y, lo.y);
+    split2(v[4], v[5], hi.z, lo.z);
+    split2(v[6], v[7], hi.w, lo.w);
 }
 
 // index (in 16-byte words) of the hi operand holding elements k .. k+7 (k % 8 == 0) of row m;
