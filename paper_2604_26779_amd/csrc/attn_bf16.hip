@@ -18,6 +18,8 @@
 //                         in the operand order the O-projection GEMM reads.
 // Row r of a (batch entry, kv head) tile is input position r / G, query head kvh*G + r % G.
 // Row i sees cache positions 0 .. ctx+i (causal over the k+1 new positions).
+#include <type_traits>
+
 #include "common.h"
 #include "operand.h"
 
@@ -39,7 +41,7 @@ constexpr int BLOCK_U4 = SPEC_PAGE_SIZE * DH * 2 / 16;   // 256 16-byte words pe
 // part_o : [item][RB*16 rows][128] fp32, part_ml : [item][RB*16][2] (max in log2 domain, sum)
 // item = (b * Hkv + kvh) * max_chunks + chunk
 template <int RB>
-__global__ __launch_bounds__(256) void attn_partial_kernel(
+__global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
     int layer_pool, float scale_log2, int max_chunks, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
@@ -115,9 +117,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
         for (int s = 0; s < 4; ++s) vf[slot][s] = __builtin_nontemporal_load(vp + s * 64);
     };
 
-    auto process = [&](int slot, int logical_page) {
+    // MASK = true only for pages that reach into the new positions (the last one or two of a
+    // sequence): all other pages run the variant without any per-key compare
+    auto process = [&](auto mask_c, int slot, int logical_page) {
+        constexpr bool need_mask = decltype(mask_c)::value;
         const int key0 = logical_page * SPEC_PAGE_SIZE + lg * 4;          // this lane's 4 keys: key0 .. key0+3
-        const bool need_mask = (logical_page + 1) * SPEC_PAGE_SIZE > ctx;  // page reaches into the new positions
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             f32x4_t sacc = {0.f, 0.f, 0.f, 0.f}, sacc2 = {0.f, 0.f, 0.f, 0.f};    // two independent chains
@@ -200,7 +204,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
     for (int it = 0; it < ATT_PPW; ++it) {
         constexpr int AHEAD = ATT_DEPTH - 1;
         load_page((it + AHEAD) % ATT_DEPTH, pid[it + AHEAD < ATT_PPW ? it + AHEAD : ATT_PPW - 1]);
-        if (page0 + wave + ATT_WAVES * it < page_end) process(it % ATT_DEPTH, page0 + wave + ATT_WAVES * it);
+        const int lpage = page0 + wave + ATT_WAVES * it;
+        if (lpage < page_end) {
+            if ((lpage + 1) * SPEC_PAGE_SIZE > ctx) process(std::true_type{}, it % ATT_DEPTH, lpage);
+            else process(std::false_type{}, it % ATT_DEPTH, lpage);
+        }
     }
 
     // per-row sums are spread over the 4 lane groups
