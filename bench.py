@@ -40,6 +40,28 @@ def run_steps(wl, sv, torch, n_steps, accept_out, step0):
         sv.spec_commit_kv(sess.kv, B, k, wl.seq_ids, accept_out[i], buf["new_ctx_len"], buf["commit_slots"])
 
 
+def hbm_ceiling(sv, torch, nbytes=1 << 30, reps=5):
+    """Measured streaming ceiling: the library's plain read and copy kernels over a buffer of known size."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    src.zero_()
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.uint8, device="cuda")
+    out = {}
+    for name, fn, moved in (("read", lambda: sv.spec_calib_read(src, nbytes, sink, 512), nbytes),
+                            ("copy", lambda: sv.spec_calib_copy(dst, src, nbytes, 1024), 2 * nbytes)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_GBs"] = round(moved * reps / (e0.elapsed_time(e1) / 1e3) / 1e9, 1)
+    out["bytes"] = nbytes
+    return out
+
+
 def cpu_baseline(wl, torch, n_seqs):
     """The CPU oracle, as it stands, on the first n_seqs sequences of the same batch at full depth."""
     import numpy as np
@@ -171,6 +193,7 @@ def main():
         "kernels": {n: roof(c) for n, c in classes.items()},
         "ms_per_step_by_class": {n: round(v, 4) for n, v in per_step.items() if v > 0},
         "wall_s_timed_region": round(wall, 3),
+        "hbm_ceiling_measured": hbm_ceiling(sv, torch),
     }
     if not args.no_cpu_baseline:
         base, _ = cpu_baseline(wl, torch, args.cpu_seqs)
