@@ -279,8 +279,7 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
     float L = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < n_chunks; ++c) {
         float mc = part_ml[((item0 + c) * RBrows + r) * 2];
-        if (!(mc > -INFINITY)) continue;
-        float f = exp2f(mc - M);
+        float f = mc > -INFINITY ? exp2f(mc - M) : 0.f;      // branch-free: the loads of all chunks overlap
         L += f * part_ml[((item0 + c) * RBrows + r) * 2 + 1];
         const float4* src = (const float4*)(part_o + ((item0 + c) * RBrows + r) * DH + c8 * 8);
         float4 a = src[0], d = src[1];

@@ -25,30 +25,34 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
                                   const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s);
 
-__device__ inline float block_sum_256(float v, float* lds4)
+// sum over the workgroup (blockDim.x a multiple of 64, at most 1024)
+__device__ inline float block_sum(float v, float* lds16)
 {
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+    if ((threadIdx.x & 63) == 0) lds16[threadIdx.x >> 6] = v;
     __syncthreads();
-    return lds4[0] + lds4[1] + lds4[2] + lds4[3];
+    float t = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += lds16[w];
+    return t;
 }
 
 // x[m] = (FIRST ? embed[token] : x[m] + sum_s part[s][m]);  xp = RMSNorm(x[m]) * gain
-// one workgroup of 256 threads per row; d % 8 == 0
+// one workgroup per row (256 or 512 threads, 8 elements per thread and pass); d % 8 == 0
 template <bool FIRST>
-__global__ __launch_bounds__(256) void residual_rmsnorm_kernel(
+__global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
     float* __restrict__ x, const float* __restrict__ part, int splits, int64_t split_stride, const int32_t* __restrict__ tokens,
     const unsigned short* __restrict__ embed, int vocab, const unsigned short* __restrict__ gain, int d, float eps, int mb_pad,
     uint4* __restrict__ xp)
 {
-    __shared__ float lds4[4];
+    __shared__ float lds16[16];
     const int m = blockIdx.x;
+    const int stride = blockDim.x * 8;
     float* xr = x + (int64_t)m * d;
     float ss = 0.f;
     int tok = 0;
     if (FIRST) { tok = tokens[m]; tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok); }
-    for (int c = threadIdx.x * 8; c < d; c += 2048) {
+    for (int c = threadIdx.x * 8; c < d; c += stride) {
         float v[8];
         if (FIRST) {
             uint4 e = *(const uint4*)(embed + (int64_t)tok * d + c);
@@ -70,9 +74,9 @@ __global__ __launch_bounds__(256) void residual_rmsnorm_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
     }
-    float tot = block_sum_256(ss, lds4);
+    float tot = block_sum(ss, lds16);
     float r = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int c = threadIdx.x * 8; c < d; c += 2048) {
+    for (int c = threadIdx.x * 8; c < d; c += stride) {
         float4 a = *(const float4*)(xr + c), b = *(const float4*)(xr + c + 4);      // this thread's own writes
         uint4 g = *(const uint4*)(gain + c);
         float v[8] = {a.x * r * from_bf16(g.x & 0xffff), a.y * r * from_bf16(g.x >> 16), a.z * r * from_bf16(g.y & 0xffff),
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(
         return v;
     };
     // rotary part: heads 0 .. Hq+Hkv-1, 16 quads of the lower half each
-    for (int e = threadIdx.x; e < (Hq + Hkv) * (HALF / 4); e += 256) {
+    for (int e = threadIdx.x + 256 * blockIdx.y; e < (Hq + Hkv) * (HALF / 4); e += 256 * gridDim.y) {
         int h = e / (HALF / 4), j = (e % (HALF / 4)) * 4;
         float4 lo = sum4(h * DHc + j), hi = sum4(h * DHc + j + HALF);
         const float2* cs = rope + (int64_t)m * HALF + j;
@@ -148,7 +152,7 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(
     }
     // values: no rotation
     if (writable)
-        for (int e = threadIdx.x; e < Hkv * (DHc / 4); e += 256) {
+        for (int e = threadIdx.x + 256 * blockIdx.y; e < Hkv * (DHc / 4); e += 256 * gridDim.y) {
             int kh = e / (DHc / 4), c = (e % (DHc / 4)) * 4;
             float4 v = sum4((Hq + Hkv + kh) * DHc + c);
             unsigned short* dst = pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 1) * Hkv + kh) * block;
@@ -262,21 +266,22 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     const int nqkv = (Hq + 2 * Hkv) * d.head_dim;
     KvView view = kv->view();
     spec_status st;
+    const int norm_threads = D >= 4096 ? 512 : 256;
 
     rope_table_kernel<<<(unsigned)cdiv((int64_t)M * 64, 256), 256, 0, s>>>(M, T, dev_seq_ids, kv->d_ctx_len, 64, (double)d.rope_theta, rope);
-    residual_rmsnorm_kernel<true><<<M, 256, 0, s>>>(x, nullptr, 0, 0, dev_tokens, (const unsigned short*)mdl->embed(), d.vocab,
+    residual_rmsnorm_kernel<true><<<M, norm_threads, 0, s>>>(x, nullptr, 0, 0, dev_tokens, (const unsigned short*)mdl->embed(), d.vocab,
                                                     (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
     prof_mark(PC_EMBED_NORM, s);
     for (int l = 0; l < d.n_layers; ++l) {
         int lp = kv->alias_mod > 0 ? l % kv->alias_mod : l;
         if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_QKV, s);
-        qkv_rope_kernel<<<M, 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, qbuf);
+        qkv_rope_kernel<<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, qbuf);
         prof_mark(PC_QKV_ROPE, s);
         if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_chunks, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
         if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_O, s);
-        residual_rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
+        residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)mdl->layer_w(l, 5), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
         if ((st = launch_gemm_bf16(mdl->wgu[l], xp_h, M, part, 2 * F, p.s_gu, s)) != SPEC_OK) return st;
@@ -286,7 +291,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         if ((st = launch_gemm_bf16(mdl->wd[l], xp_f, M, part, D, p.s_down, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_DOWN, s);
         const void* next_gain = l + 1 < d.n_layers ? mdl->layer_w(l + 1, 0) : mdl->final_norm();
-        residual_rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
+        residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
     }
