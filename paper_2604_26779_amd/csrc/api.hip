@@ -28,6 +28,7 @@ static std::map<std::string, int>& tune_table()
     // launch parameters with their defaults; see gemm_bf16.hip / attn_bf16.hip for their meaning
     static std::map<std::string, int> t = {
         {"gemm_wg_target", 512},   // split K while a GEMM launches fewer workgroups than this
+        {"fuse_swiglu", 1},        // 1: silu(gate) * up in the gate/up projection's epilogue (unsplit K, even row blocks)
         {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
         {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
         {"attn_chunk_pages", 32},  // KV pages per attention workgroup
@@ -179,20 +180,20 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         }
         bf16_t* at = (bf16_t*)m->arena;
         m->wqkv.resize(L); m->wo.resize(L); m->wgu.resize(L); m->wd.resize(L);
-        auto pack = [&](std::initializer_list<const void*> parts, std::initializer_list<int> rows, int K, PackedW* pw) -> spec_status {
+        auto pack = [&](std::initializer_list<const void*> parts, std::initializer_list<int> rows, int K, PackedW* pw, bool interleave = false) -> spec_status {
             std::vector<const bf16_t*> p;
             for (auto q : parts) p.push_back((const bf16_t*)q);
             std::vector<int> r(rows);
             int N = 0;
             for (int x : r) N += x;
-            spec_status s2 = bf16_pack_matrix(p.data(), r.data(), (int)p.size(), K, at, pw, nullptr);
+            spec_status s2 = bf16_pack_matrix(p.data(), r.data(), (int)p.size(), K, at, pw, interleave, nullptr);
             at += bf16_packed_elems(N, K);
             return s2;
         };
         for (int l = 0; l < L && st == SPEC_OK; ++l) {
             st = pack({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {nq, nkv, nkv}, D, &m->wqkv[l]);
             if (st == SPEC_OK) st = pack({m->layer_w(l, 4)}, {D}, nq, &m->wo[l]);
-            if (st == SPEC_OK) st = pack({m->layer_w(l, 6), m->layer_w(l, 7)}, {F, F}, D, &m->wgu[l]);
+            if (st == SPEC_OK) st = pack({m->layer_w(l, 6), m->layer_w(l, 7)}, {F, F}, D, &m->wgu[l], true);
             if (st == SPEC_OK) st = pack({m->layer_w(l, 8)}, {D}, F, &m->wd[l]);
         }
         if (st == SPEC_OK) st = pack({m->head_w()}, {d.vocab}, D, &m->head);

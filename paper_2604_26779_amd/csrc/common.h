@@ -128,7 +128,7 @@ spec_status f32_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t*
 // ---- bf16 MFMA path (forward_bf16.hip, gemm_bf16.hip, attn_bf16.hip) ----
 size_t bf16_packed_elems(int N, int K);
 spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_rows, int n_parts, int K,
-                             bf16_t* dev_out, PackedW* out, hipStream_t s);
+                             bf16_t* dev_out, PackedW* out, bool interleave, hipStream_t s);
 size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k);
 spec_status bf16_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids,
                          const int32_t* dev_tokens, float* dev_logits, void* ws, size_t ws_bytes, hipStream_t s);

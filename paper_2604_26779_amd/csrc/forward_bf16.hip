@@ -19,7 +19,8 @@ namespace specv {
 // from gemm_bf16.hip / attn_bf16.hip
 int gemm_mb_pad(int M);
 int gemm_pick_splits(const PackedW& W, int M, int forced);
-spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, hipStream_t s);
+spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s);
+bool gemm_can_fuse_swiglu(int M, int splits);
 int attn_chunk_pages();
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
                                   const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
@@ -171,13 +172,15 @@ __global__ void swiglu_pack_kernel(const float* __restrict__ part, int splits, i
     int f8 = F / 8;
     if (idx >= (int64_t)M * f8) return;
     int m = (int)(idx / f8), f = (int)(idx % f8) * 8;
-    const float* row = part + (int64_t)m * 2 * F;
+    // the gate/up weights are tiled with their 32-column blocks interleaved: gate channel f sits in
+    // column (f/32)*64 + f%32 of the projection's output, up channel f 32 columns further
+    const float* row = part + (int64_t)m * 2 * F + (f >> 5) * 64 + (f & 31);
     float g[8], u[8];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        float4 a = *(const float4*)(row + f + 4 * h), c = *(const float4*)(row + F + f + 4 * h);
+        float4 a = *(const float4*)(row + 4 * h), c = *(const float4*)(row + 32 + 4 * h);
         for (int s = 1; s < splits; ++s) {
-            float4 a2 = *(const float4*)(row + s * split_stride + f + 4 * h), c2 = *(const float4*)(row + s * split_stride + F + f + 4 * h);
+            float4 a2 = *(const float4*)(row + s * split_stride + 4 * h), c2 = *(const float4*)(row + s * split_stride + 32 + 4 * h);
             a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
             c.x += c2.x; c.y += c2.y; c.z += c2.z; c.w += c2.w;
         }
@@ -193,6 +196,7 @@ __global__ void swiglu_pack_kernel(const float* __restrict__ part, int splits, i
 // ------------------------------------------------------------------ host side
 struct Bf16Plan {
     int M, mb_pad, max_chunks, RBrows;
+    bool fuse_swiglu;
     int s_qkv, s_o, s_gu, s_down, s_head;
     size_t off_x, off_xp_h, off_xp_a, off_xp_f, off_part, off_q, off_rope, off_att_o, off_att_ml, total;
 };
@@ -210,7 +214,8 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     if (p.max_chunks < 1) p.max_chunks = 1;
     p.s_qkv = gemm_pick_splits(m->wqkv[0], p.M, tune("splits_qkv"));
     p.s_o = gemm_pick_splits(m->wo[0], p.M, tune("splits_o"));
-    p.s_gu = gemm_pick_splits(m->wgu[0], p.M, tune("splits_gu"));
+    p.fuse_swiglu = tune("fuse_swiglu") != 0 && gemm_can_fuse_swiglu(p.M, 1);
+    p.s_gu = p.fuse_swiglu ? 1 : gemm_pick_splits(m->wgu[0], p.M, tune("splits_gu"));
     p.s_down = gemm_pick_splits(m->wd[0], p.M, tune("splits_down"));
     p.s_head = 1;
     int D = d.d_model, F = d.ffn_dim, nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
@@ -274,28 +279,34 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     prof_mark(PC_EMBED_NORM, s);
     for (int l = 0; l < d.n_layers; ++l) {
         int lp = kv->alias_mod > 0 ? l % kv->alias_mod : l;
-        if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, s)) != SPEC_OK) return st;
+        if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_QKV, s);
         qkv_rope_kernel<<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, qbuf);
         prof_mark(PC_QKV_ROPE, s);
         if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_chunks, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
-        if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, s)) != SPEC_OK) return st;
+        if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_O, s);
         residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)mdl->layer_w(l, 5), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
-        if ((st = launch_gemm_bf16(mdl->wgu[l], xp_h, M, part, 2 * F, p.s_gu, s)) != SPEC_OK) return st;
-        prof_mark(PC_GEMM_GU, s);
-        swiglu_pack_kernel<<<(unsigned)cdiv((int64_t)M * (F / 8), 256), 256, 0, s>>>(part, p.s_gu, (int64_t)M * 2 * F, M, F, p.mb_pad, (uint4*)xp_f);
-        prof_mark(PC_SWIGLU, s);
-        if ((st = launch_gemm_bf16(mdl->wd[l], xp_f, M, part, D, p.s_down, s)) != SPEC_OK) return st;
+        if (p.fuse_swiglu) {
+            // gate/up projection with silu(gate) * up in its epilogue: writes the down projection's operand
+            if ((st = launch_gemm_bf16(mdl->wgu[l], xp_h, M, (float*)xp_f, 2 * F, 1, true, s)) != SPEC_OK) return st;
+            prof_mark(PC_GEMM_GU, s);
+        } else {
+            if ((st = launch_gemm_bf16(mdl->wgu[l], xp_h, M, part, 2 * F, p.s_gu, false, s)) != SPEC_OK) return st;
+            prof_mark(PC_GEMM_GU, s);
+            swiglu_pack_kernel<<<(unsigned)cdiv((int64_t)M * (F / 8), 256), 256, 0, s>>>(part, p.s_gu, (int64_t)M * 2 * F, M, F, p.mb_pad, (uint4*)xp_f);
+            prof_mark(PC_SWIGLU, s);
+        }
+        if ((st = launch_gemm_bf16(mdl->wd[l], xp_f, M, part, D, p.s_down, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_DOWN, s);
         const void* next_gain = l + 1 < d.n_layers ? mdl->layer_w(l + 1, 0) : mdl->final_norm();
         residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
     }
-    if ((st = launch_gemm_bf16(mdl->head, xp_h, M, dev_logits, d.vocab, 1, s)) != SPEC_OK) return st;
+    if ((st = launch_gemm_bf16(mdl->head, xp_h, M, dev_logits, d.vocab, 1, false, s)) != SPEC_OK) return st;
     prof_mark(PC_GEMM_HEAD, s);
     SPEC_LAUNCH_CHECK("bf16 forward");
     return SPEC_OK;

@@ -23,6 +23,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "operand.h"
 
 namespace specv {
 
@@ -34,11 +35,12 @@ constexpr int GEMM_KS = 4;          // k-steps (of 16) per LDS slab
 constexpr int GEMM_WD = 4;          // slabs of weight fragments each wavefront keeps in flight
 constexpr int GEMM_KUNIT = GEMM_KS * GEMM_WD;   // k-steps per split are a multiple of this
 constexpr int GEMM_THREADS = 256;
+constexpr int GEMM_EPI_PLAIN = 0, GEMM_EPI_SWIGLU = 1;
 
 size_t bf16_packed_elems(int N, int K) { return (size_t)cdiv(N, 32) * 32 * (size_t)K; }
 
 // ------------------------------------------------------------------ weight re-tiling
-struct PackParts { const bf16_t* ptr[4]; int row_end[4]; int n; };
+struct PackParts { const bf16_t* ptr[4]; int row_end[4]; int n; int interleave; };
 
 __global__ void pack_w_kernel(PackParts parts, int N, int K, int k_steps, int64_t total, uint4* __restrict__ out)
 {
@@ -54,7 +56,11 @@ __global__ void pack_w_kernel(PackParts parts, int N, int K, int k_steps, int64_
     int n = nb * 32 + (lane & 31);
     int k0 = ks * 16 + (lane >> 5) * 8;
     uint4 v = make_uint4(0, 0, 0, 0);
-    if (n < N) {
+    if (parts.interleave) {
+        // two equal parts (gate, up): column block 2j holds rows 32j.. of part 0, block 2j+1 the same rows of part 1
+        int row = (nb >> 1) * 32 + (lane & 31);
+        if (row < parts.row_end[0]) v = *(const uint4*)(parts.ptr[nb & 1] + (int64_t)row * K + k0);
+    } else if (n < N) {
         int start = 0;
         for (int p = 0; p < parts.n; ++p) {
             if (n < parts.row_end[p]) {
@@ -68,11 +74,13 @@ __global__ void pack_w_kernel(PackParts parts, int N, int K, int k_steps, int64_
 }
 
 spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_rows, int n_parts, int K, bf16_t* dev_out,
-                             PackedW* out, hipStream_t s)
+                             PackedW* out, bool interleave, hipStream_t s)
 {
     if (n_parts < 1 || n_parts > 4 || K % (16 * GEMM_KUNIT)) { set_error("bf16_pack_matrix: bad shape"); return SPEC_EINVAL; }
     PackParts pp;
     pp.n = n_parts;
+    pp.interleave = interleave ? 1 : 0;
+    if (interleave && (n_parts != 2 || part_rows[0] != part_rows[1] || part_rows[0] % 32)) { set_error("bf16_pack_matrix: interleaving needs two equal parts of a multiple of 32 rows"); return SPEC_EINVAL; }
     int N = 0;
     for (int i = 0; i < n_parts; ++i) {
         if (((uintptr_t)dev_parts[i] & 15) != 0) { set_error("bf16 weights must be 16-byte aligned"); return SPEC_EINVAL; }
@@ -94,39 +102,50 @@ spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_row
 // ------------------------------------------------------------------ the GEMM
 // Wp : [k_steps / KS][n_blocks][KS][64] u32x4_t   Xp : [k_steps][mb_pad][hi|lo][64] u32x4_t
 // out: [splits][M][ldo] fp32 (slice stride = split_stride floats)
-template <int MB, int WD>
+// MB row blocks (of 32) per workgroup tile; the 4 wavefronts are arranged WM along the rows x 4/WM
+// along the columns.  A wavefront owns MB/WM row blocks and WM column blocks (the tile is always 128
+// columns), so with WM = 2 every activation fragment read from LDS feeds two MFMAs and every weight
+// fragment is read by two wavefronts (the second read hits the CU's L1): half the LDS traffic per MFMA.
+template <int MB, int WM, int WD, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
     const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
     int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride)
 {
     constexpr int KS = GEMM_KS;
+    constexpr int MBW = MB / WM, NBW = WM;
+    static_assert(MB % WM == 0, "row blocks must divide over the wavefronts");
     constexpr int SLAB = KS * MB * 128;                 // u32x4_t per slab (hi and lo operands)
     constexpr int XPT = SLAB / GEMM_THREADS;            // u32x4_t per thread per slab
     __shared__ u32x4_t lds[2 * SLAB];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int nb = blockIdx.x * 4 + wave;
-    const bool active = nb < n_blocks;
+    const int mh = wave % WM, np = wave / WM;
+    const int nb0 = blockIdx.x * 4 + np * NBW;
     const int ks0 = blockIdx.y * ksteps_per_split;
     int ks1 = ks0 + ksteps_per_split;
     if (ks1 > k_steps) ks1 = k_steps;
     const int n_slabs = (ks1 - ks0) / KS;
     const int mt = blockIdx.z;
 
-    // slab s of this wavefront's column block: wptr + s * wslab
-    const u32x4_t* wptr = Wp + (((int64_t)(ks0 / KS) * n_blocks + (active ? nb : 0)) * KS) * 64 + lane;
+    // slab s of column block j of this wavefront: wptr[j] + s * wslab
+    const u32x4_t* wptr[NBW];
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+        wptr[j] = Wp + (((int64_t)(ks0 / KS) * n_blocks + (nb0 + j < n_blocks ? nb0 + j : 0)) * KS) * 64 + lane;
     const int64_t wslab = (int64_t)n_blocks * KS * 64;
     const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mt * MB) * 128;
 
-    f32x16_t acc[MB];
+    f32x16_t acc[MBW][NBW];
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
+    for (int i = 0; i < MBW; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        for (int j = 0; j < NBW; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // the weight stream runs WD slabs (WD * KS fragments of 1 KiB per wavefront) ahead of the MFMAs:
-    // a register ring, each entry refilled right after its last use
-    u32x4_t w[WD][KS], xr[XPT];
+    // the weight stream runs WD slabs ahead of the MFMAs: a register ring, each entry refilled
+    // right after its last use
+    u32x4_t w[WD][KS][NBW], xr[XPT];
 
     auto load_x = [&](int slab) {
 #pragma unroll
@@ -149,44 +168,41 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
         constexpr int SLOT = decltype(slot_c)::value;
         const int s_w = s + WD < n_slabs ? s + WD : n_slabs - 1;
         const int s_x = s + 1 < n_slabs ? s + 1 : n_slabs - 1;
-        const u32x4_t* wnext = wptr + (int64_t)s_w * wslab;
         load_x(s_x);
-        // activation fragments of k-step kk+1 are fetched from LDS while the MFMAs of kk run;
-        // the hi products of all row blocks go first, then the lo products, so that two MFMAs
-        // on the same accumulator are never adjacent
-        u32x4_t a_cur[2 * MB], a_nxt[2 * MB];
-#pragma unroll
-        for (int i = 0; i < 2 * MB; ++i) a_cur[i] = lds[buf * SLAB + i * 64 + lane];
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
-            if (kk + 1 < KS) {
+            u32x4_t a[MBW][2];
 #pragma unroll
-                for (int i = 0; i < 2 * MB; ++i) a_nxt[i] = lds[buf * SLAB + ((kk + 1) * 2 * MB + i) * 64 + lane];
-            }
-            bf16x8_t bw = __builtin_bit_cast(bf16x8_t, w[SLOT][kk]);
+            for (int i = 0; i < MBW; ++i)
+#pragma unroll
+                for (int part = 0; part < 2; ++part)
+                    a[i][part] = lds[buf * SLAB + ((kk * MB + mh * MBW + i) * 2 + part) * 64 + lane];
+            // hi products of all blocks first, then the lo products: two MFMAs on one accumulator are never adjacent
 #pragma unroll
             for (int part = 0; part < 2; ++part)
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a_cur[2 * mb + part]), bw, acc[mb], 0, 0, 0);
-            w[SLOT][kk] = __builtin_nontemporal_load(wnext + kk * 64);
-            if (kk + 1 < KS) {
+                for (int i = 0; i < MBW; ++i)
 #pragma unroll
-                for (int i = 0; i < 2 * MB; ++i) a_cur[i] = a_nxt[i];
-            }
+                    for (int j = 0; j < NBW; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[i][part]),
+                                                                            __builtin_bit_cast(bf16x8_t, w[SLOT][kk][j]), acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) w[SLOT][kk][j] = __builtin_nontemporal_load(wptr[j] + (int64_t)s_w * wslab + kk * 64);
         }
         store_x(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     };
 
-    // n_slabs is a multiple of WD (K % (16 * KS * WD) == 0 and split sizes are rounded to it)
+    // n_slabs is a multiple of WD (K % (16 * GEMM_KUNIT) == 0 and split sizes are rounded to it)
     if (n_slabs > 0) {
 #pragma unroll
         for (int d = 0; d < WD; ++d) {
             const int sd = d < n_slabs ? d : n_slabs - 1;
 #pragma unroll
-            for (int i = 0; i < KS; ++i) w[d][i] = __builtin_nontemporal_load(wptr + (int64_t)sd * wslab + i * 64);
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int j = 0; j < NBW; ++j) w[d][i][j] = __builtin_nontemporal_load(wptr[j] + (int64_t)sd * wslab + i * 64);
         }
         load_x(0);
         store_x(0);
@@ -199,17 +215,48 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
         }
     }
 
-    if (!active) return;
-    float* o = out + (int64_t)blockIdx.y * split_stride;
-    const int n = nb * 32 + (lane & 31);
-    if (n >= N) return;
+    if constexpr (EPI == GEMM_EPI_SWIGLU) {
+        // The weights of the gate/up projection are tiled with gate and up column blocks interleaved,
+        // so this wavefront's two accumulators hold gate and up of the same 32 hidden channels:
+        // silu(gate) * up in registers, transposed through LDS (free after the main loop) into rows,
+        // and written as hi + lo bf16 in the operand order the down projection reads.
+        static_assert(EPI != GEMM_EPI_SWIGLU || NBW == 2, "fused SwiGLU needs two column blocks per wavefront");
+        float* tile = (float*)lds;                              // [MB*32 rows][65]
+        __syncthreads();
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+        for (int i = 0; i < MBW; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int m = (mt * MB + mb) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (m < M) o[(int64_t)m * ldo + n] = acc[mb][r];
+            for (int r = 0; r < 16; ++r) {
+                float g = acc[i][0][r], u = acc[i][NBW - 1][r];
+                int row = (mh * MBW + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                tile[row * 65 + np * 32 + (lane & 31)] = g / (1.0f + __expf(-g)) * u;
+            }
+        __syncthreads();
+        uint4* xo = (uint4*)out;
+        for (int e = threadIdx.x; e < MB * 32 * 8; e += GEMM_THREADS) {
+            int row = e >> 3, g8 = e & 7;
+            int m = mt * MB * 32 + row, f = blockIdx.x * 64 + g8 * 8;
+            if (m >= M || f >= N / 2) continue;
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = tile[row * 65 + g8 * 8 + j];
+            xp_store8(xo, m, f, mb_pad, v);
         }
+        return;
+    }
+    float* o = out + (int64_t)blockIdx.y * split_stride;
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) {
+        const int n = (nb0 + j) * 32 + (lane & 31);
+        if (nb0 + j >= n_blocks || n >= N) continue;
+#pragma unroll
+        for (int i = 0; i < MBW; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int m = (mt * MB + mh * MBW + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (m < M) o[(int64_t)m * ldo + n] = acc[i][j][r];
+            }
+    }
 }
 
 // rows of the activation buffer are padded to whole tiles of MB 32-row blocks
@@ -229,8 +276,12 @@ int gemm_pick_splits(const PackedW& W, int M, int forced)
     return (int)cdiv(W.k_steps, kps);
 }
 
-// out must hold splits * M * ldo floats
-spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, hipStream_t s)
+// out must hold splits * M * ldo floats; with swiglu (gate/up projection, splits == 1, an even number
+// of row blocks) out is instead the hi + lo operand buffer of silu(gate) * up, [N/2] channels wide.
+// Returns SPEC_EUNSUPPORTED (nothing launched) if swiglu is asked for a shape it cannot fuse.
+bool gemm_can_fuse_swiglu(int M, int splits) { return splits == 1 && gemm_mb(M) % 2 == 0; }
+
+spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s)
 {
     int mb = gemm_mb(M), mb_pad = gemm_mb_pad(M);
     int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KUNIT) * GEMM_KUNIT;
@@ -238,14 +289,15 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
     int64_t stride = (int64_t)M * ldo;
     const u32x4_t* wp = (const u32x4_t*)W.data;
     const u32x4_t* xp = (const u32x4_t*)Xp;
-#define SPEC_GEMM_CASE(MBV) gemm_bf16_kernel<MBV, GEMM_WD><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride)
+    if (swiglu && !gemm_can_fuse_swiglu(M, splits)) { set_error("gemm: SwiGLU cannot be fused for this shape"); return SPEC_EUNSUPPORTED; }
+#define SPEC_GEMM_LAUNCH(MBV, WMV, WDV, E) gemm_bf16_kernel<MBV, WMV, WDV, E><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride)
     switch (mb) {
-        case 1: SPEC_GEMM_CASE(1); break;
-        case 2: SPEC_GEMM_CASE(2); break;
-        case 3: SPEC_GEMM_CASE(3); break;
-        default: SPEC_GEMM_CASE(4); break;
+        case 1: SPEC_GEMM_LAUNCH(1, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
+        case 2: if (swiglu) SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_PLAIN); break;
+        case 3: SPEC_GEMM_LAUNCH(3, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
+        default: if (swiglu) SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_PLAIN); break;
     }
-#undef SPEC_GEMM_CASE
+#undef SPEC_GEMM_LAUNCH
     SPEC_LAUNCH_CHECK("gemm_bf16_kernel");
     return SPEC_OK;
 }
