@@ -45,8 +45,10 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
     int layer_pool, float scale_log2, int max_chunks, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
-    const int chunk = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-    const int Hkv = gridDim.y;
+    // chunk is the slowest grid dimension: the first chunks (every sequence has them) are dispatched first,
+    // the chunks only long sequences have - and the empty workgroups of the short ones - last
+    const int kvh = blockIdx.x, b = blockIdx.y, chunk = blockIdx.z;
+    const int Hkv = gridDim.x;
     const int seq = seq_ids[b];
     const int ctx = kv.ctx_len[seq];
     int total = ctx + T;
@@ -301,7 +303,7 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
     int R = T * G;
     int RB = (int)cdiv(R, 16);
     float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-    dim3 grid((unsigned)max_chunks, (unsigned)Hkv, (unsigned)B);
+    dim3 grid((unsigned)Hkv, (unsigned)B, (unsigned)max_chunks);
     const float* qq = q;
     switch (RB) {
         case 1: attn_partial_kernel<1><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, part_o, part_ml); break;
