@@ -261,3 +261,60 @@ def test_forward_argument_errors_and_pool_exhaustion():
     with pytest.raises(sv.SpecError) as e:                 # bf16 path needs head_dim 128
         VerifySession(dict(cfg, dtype="bf16"), {n: t.bfloat16() for n, t in weights.items()}, 2, 64, 8)
     assert e.value.status == sv.SPEC_EUNSUPPORTED
+
+
+def _run_custom_bf16(ctx_list, k, seed=3, vocab=None):
+    """small_bf16 model, synthetic cache, explicit context lengths: returns (max err, worst over tolerance)."""
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = dict(si.MODELS["small_bf16"])
+    if vocab:
+        cfg["vocab"] = vocab
+    B = len(ctx_list)
+    weights = si.make_weights(cfg, seed=seed)
+    w_or = si.weights_for_oracle(cfg, weights)
+    ctx_len = np.array(ctx_list, dtype=np.int64)
+    kv = si.make_logical_kv(cfg, ctx_len, seed=seed)
+    kv_or = si.kv_for_oracle(kv)
+    rng = np.random.default_rng(seed)
+    n_ctx_pages = [-(-int(c) // si.PAGE_SIZE) for c in ctx_len]
+    n_pages = sum(-(-(int(c) + k + 1) // si.PAGE_SIZE) for c in ctx_len) + 16
+    order = rng.permutation(n_pages)
+    sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=B, max_ctx_len=int(ctx_len.max()) + 64,
+                         n_pages=n_pages)
+    sess.pool.fill_(float("nan"))                        # whatever a step reads beyond its data must not matter
+    at = 0
+    for b in range(B):
+        pages = [int(p) for p in order[at:at + n_ctx_pages[b]]]
+        at += n_ctx_pages[b]
+        sess.assign(b, int(ctx_len[b]), pages)
+        for l in range(cfg["n_layers"]):
+            sess.write_logical_kv(l, pages, kv[l][b][0], kv[l][b][1])
+    tokens = rng.integers(0, cfg["vocab"], size=(B, k + 1)).astype(np.int32)
+    want, _ = of.verify_forward(cfg, w_or, kv_or, tokens, ctx_len)
+    got = sess.forward(torch.arange(B, dtype=torch.int32, device="cuda"), torch.from_numpy(tokens).cuda())
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    sess.close()
+    assert np.isfinite(got).all()
+    ok, max_err, worst = logits_close(got, want, *TOL["bf16"])
+    return ok, max_err, worst
+
+
+def test_bf16_edge_contexts_empty_page_and_chunk_boundaries():
+    """Context lengths at the degenerate points: empty cache, one token, page boundaries (15/16/17),
+    attention-chunk boundaries (511/512/513 tokens = 32 pages per chunk), new positions straddling a page
+    and a chunk; the pool is NaN-filled so any read past a sequence's data shows."""
+    ok, max_err, worst = _run_custom_bf16([0, 1, 15, 16, 17, 509, 511, 512, 513, 1023, 1024], k=3)
+    print("edge contexts: logits max abs err %.3e" % max_err)
+    assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("B,k", [(1, 0), (1, 7), (40, 3), (33, 7), (9, 2)])
+def test_bf16_row_block_counts_and_multiple_row_tiles(B, k):
+    """M = B*(k+1) from 1 to 264: every row-block count of the GEMM tile (1..4, fused and unfused
+    SwiGLU), more than one 128-row tile (M = 160, 264: the weights are streamed once per tile), odd k."""
+    rng = np.random.default_rng(B * 10 + k)
+    ctx = [int(c) for c in rng.integers(3, 200, size=B)]
+    ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000)
+    print("B=%d k=%d (M=%d): logits max abs err %.3e" % (B, k, B * (k + 1), max_err))
+    assert ok, (max_err, worst)
