@@ -19,6 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 MFMA peak
 DEFAULT_WORKLOAD = "llama8b_b32_ctx1k-8k_k3"
 
 
@@ -158,9 +159,10 @@ def main():
     alg = algorithmic_bytes(wl.cfg, wl.ctx_len, B, k)
     gemm_ms = sum(per_step[n] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head"))
     gemm_launches = sum(launches[n] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head"))
+    gemm_flops = 2.0 * (alg["gemm"] / 2) * B * (k + 1)          # 2 flop per weight per position (bf16 weights)
     classes = {
-        "gemm_bf16_kernel": dict(ms=gemm_ms, launches=gemm_launches, bytes=alg["gemm"]),
-        "attn_partial_kernel": dict(ms=per_step["attn"], launches=launches["attn"], bytes=alg["attn"]),
+        "gemm_bf16_kernel": dict(ms=gemm_ms, launches=gemm_launches, bytes=alg["gemm"], flops=gemm_flops),
+        "attn_partial_kernel": dict(ms=per_step["attn"], launches=launches["attn"], bytes=alg["attn"], flops=0.0),
     }
     dom = max(classes, key=lambda n: classes[n]["ms"])
     traffic = None
@@ -170,6 +172,11 @@ def main():
 
     def roof(c):
         gbs = c["bytes"] / (c["ms"] / 1e3) / 1e9 if c["ms"] > 0 else 0.0
+        if c["flops"] / c["bytes"] > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:      # above the ridge: a contraction
+            tf = c["flops"] / (c["ms"] / 1e3) / 1e12 if c["ms"] > 0 else 0.0
+            return dict(bound="mfma", achieved=round(tf, 1), peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=round(tf / MFMA_BF16_PEAK_TFLOPS, 4), avg_launch_us=round(1e3 * c["ms"] / max(c["launches"], 1), 2),
+                        flops_per_launch=int(c["flops"] / max(c["launches"], 1)), weight_stream_GBs=round(gbs, 1))
         return dict(bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4),
                     avg_launch_us=round(1e3 * c["ms"] / max(c["launches"], 1), 2),
                     bytes_per_launch=int(c["bytes"] / max(c["launches"], 1)))

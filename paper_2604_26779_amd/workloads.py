@@ -27,7 +27,7 @@ class DeviceWorkload:
         weights = si.make_weights(self.cfg, seed=seed, device=device)
         n_pages = self.batch["n_pages"] + (extra_pages if extra_pages is not None else 4 * B + 64)
         self.sess = VerifySession(self.cfg, weights, max_seqs=B, max_ctx_len=int(self.ctx_len.max()) + 256,
-                                  n_pages=n_pages, device=device)
+                                  n_pages=n_pages, layer_alias_mod=self.wl.get("layer_alias_mod", 0), device=device)
         if drop_canonical and self.cfg["dtype"] == "bf16":
             # the library re-tiled the matrices into its own buffer; keep only what it still reads
             keep = {"embed"} | {n for n in weights if n.endswith("norm")}
@@ -57,7 +57,8 @@ class DeviceWorkload:
         """Fill tokens[:, 1:] and q: k passes of the target, each fixing the next draft token."""
         g = torch.Generator(device=self.device)
         g.manual_seed(int(self.seed) + 5)
-        T, std = self.wl["temperature"], self.wl["noise_std"]
+        T = self.wl["temperature"]
+        std = (self.wl["noise_std"] * torch.from_numpy(self.batch["noise_scale"]).to(self.device, torch.float32))[:, None]
         for i in range(1, self.k + 1):
             logits = self.sess.forward(self.seq_ids, self.tokens)
             row = logits[:, i - 1, :]

@@ -44,6 +44,14 @@ WORKLOADS = {
     "llama8b_b32_ctx1k-8k_k3": dict(model="llama8b_bf16", B=32, k=3, ctx_lo=1024, ctx_hi=8192, noise_std=1.0,
                                     temperature=1.0),
 }
+# Large rollout batch (BASELINE config 2): B=256, contexts uniform in [2048, 16384], k swept.  The
+# cache of 32 distinct layers would not fit one GPU (309 GB on average), so layer l uses layer
+# pool l mod 8 (same bytes streamed per step, an eighth of the footprint); the draft noise of
+# sequence b is scaled by 2*Beta(4,2) so acceptance rates are mixed over the batch.
+for _k in (1, 3, 5, 7):
+    WORKLOADS["llama8b_b256_ctx2k-16k_k%d" % _k] = dict(
+        model="llama8b_bf16", B=256, k=_k, ctx_lo=2048, ctx_hi=16384, noise_std=1.0, temperature=1.0,
+        layer_alias_mod=8, noise_beta=(4.0, 2.0))
 
 
 def torch_dtype(name):
@@ -117,8 +125,11 @@ def make_batch(workload, seed=DEFAULT_SEED, shuffle_pages=True, extra_pages=8):
     for n in ctx_pages:
         page_lists.append([int(p) for p in order[at:at + n]])
         at += n
+    noise_scale = np.ones(B)
+    if workload.get("noise_beta"):
+        noise_scale = 2.0 * rng.beta(workload["noise_beta"][0], workload["noise_beta"][1], size=B)
     return dict(tokens0=tokens0, ctx_len=ctx_len, ctx_tokens=ctx_tokens, page_lists=page_lists,
-                n_pages=int(n_pages))
+                n_pages=int(n_pages), noise_scale=noise_scale)
 
 
 def make_logical_kv(cfg, ctx_len, seed=DEFAULT_SEED, device="cpu"):

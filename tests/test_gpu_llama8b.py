@@ -1,5 +1,7 @@
-"""Full-size parity of the Llama-3-8B-shaped verify step (B=32, contexts 1024..8192, k=3, bf16,
-shuffled 16-token pages), in the launch configuration bench.py times.
+"""Full-size parity of the Llama-3-8B-shaped verify step in the launch configurations bench.py times:
+B=32, contexts 1024..8192, k=3, and the large rollout batch B=256, contexts 2048..16384, k=7 and k=1
+(bf16, shuffled 16-token pages; the large batch on 8 aliased layer pools, which the oracle sees as
+layers l and l+8 reading the same cached context).
 
 The CPU oracle cannot run all 32 sequences in a test's time, and a sequence's logits depend only on
 its own rows and its own cache, so the logits are checked on sampled sequences (the shortest and
@@ -20,51 +22,59 @@ from tests.helpers import logits_close
 
 pytestmark = pytest.mark.gpu
 
-WORKLOAD = "llama8b_b32_ctx1k-8k_k3"
-
-
-def test_llama8b_logits_on_sampled_sequences_and_commit():
+def _check_workload(name, ks):
     from paper_2604_26779_amd.workloads import DeviceWorkload
-    wl = DeviceWorkload(WORKLOAD)
-    cfg, B, k = wl.cfg, wl.B, wl.k
+    wl = DeviceWorkload(name)
+    cfg, B = wl.cfg, wl.B
     rng = np.random.default_rng(123)
-    tokens = np.concatenate([wl.batch["tokens0"][:, None], rng.integers(0, cfg["vocab"], size=(B, k))], axis=1).astype(np.int32)
-    wl.tokens.copy_(torch.from_numpy(tokens))
-    logits = wl.sess.forward(wl.seq_ids, wl.tokens)
-    torch.cuda.synchronize()
-    assert torch.isfinite(logits).all()
-
     picks = sorted({int(np.argmin(wl.ctx_len)), int(np.argmax(wl.ctx_len))})
-    print("oracle on sequences", picks, "contexts", [int(wl.ctx_len[b]) for b in picks], flush=True)
     weights = si.make_weights(cfg, seed=wl.seed, device="cuda")           # the generator's weights again, for the oracle
     w_or = si.weights_for_oracle(cfg, weights)
     del weights
     torch.cuda.empty_cache()
     kv_or = [[tuple(t.float().cpu().numpy() for t in wl.logical_kv(l, b)) for b in picks] for l in range(cfg["n_layers"])]
-    want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks])
-    got = logits[picks].cpu().numpy()
-    ok, max_err, worst = logits_close(got, want, 2e-2, 1e-2)
-    print("llama8b logits max abs err %.3e, |logit| max %.2f" % (max_err, np.abs(want).max()), flush=True)
-    assert ok, (max_err, worst)
+    seq_ids = wl.seq_ids
+    for k in ks:
+        wl.restore()
+        tokens = np.concatenate([wl.batch["tokens0"][:, None], rng.integers(0, cfg["vocab"], size=(B, k))], axis=1).astype(np.int32)
+        logits = wl.sess.forward(seq_ids, torch.from_numpy(tokens).cuda())
+        torch.cuda.synchronize()
+        assert torch.isfinite(logits).all()
+        print(name, "k=%d: oracle on sequences" % k, picks, "contexts", [int(wl.ctx_len[b]) for b in picks], flush=True)
+        want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks])
+        got = logits[picks].cpu().numpy()
+        ok, max_err, worst = logits_close(got, want, 2e-2, 1e-2)
+        print("  logits max abs err %.3e, |logit| max %.2f" % (max_err, np.abs(want).max()), flush=True)
+        assert ok, (max_err, worst)
 
-    # new cache entries of the sampled sequences (last layer) sit where the page table says
-    book = oracle_commit.KVBook(wl.sess.n_pages, si.PAGE_SIZE)
-    for b in range(B):
-        book.assign(b, int(wl.ctx_len[b]), wl.batch["page_lists"][b])
-    book.reserve(list(range(B)), k)
-    last = cfg["n_layers"] - 1
-    for j, b in enumerate(picks):
-        K, V = wl.sess.read_logical_kv(last, book.pages[b], int(wl.ctx_len[b]) + k + 1)
-        c = int(wl.ctx_len[b])
-        assert np.max(np.abs(K[c:].float().cpu().numpy() - new_kv[last][0][j])) < 2e-2 * max(1.0, np.abs(new_kv[last][0][j]).max())
-        assert np.max(np.abs(V[c:].float().cpu().numpy() - new_kv[last][1][j])) < 2e-2 * max(1.0, np.abs(new_kv[last][1][j]).max())
+        # new cache entries of the sampled sequences (last layer) sit where the page table says
+        book = oracle_commit.KVBook(wl.sess.n_pages, si.PAGE_SIZE)
+        for b in range(B):
+            book.assign(b, int(wl.ctx_len[b]), wl.batch["page_lists"][b])
+        book.reserve(list(range(B)), k)
+        last = cfg["n_layers"] - 1
+        for j, b in enumerate(picks):
+            K, V = wl.sess.read_logical_kv(last, book.pages[b], int(wl.ctx_len[b]) + k + 1)
+            c = int(wl.ctx_len[b])
+            assert np.max(np.abs(K[c:].float().cpu().numpy() - new_kv[last][0][j])) < 2e-2 * max(1.0, np.abs(new_kv[last][0][j]).max())
+            assert np.max(np.abs(V[c:].float().cpu().numpy() - new_kv[last][1][j])) < 2e-2 * max(1.0, np.abs(new_kv[last][1][j]).max())
 
-    # commit at full batch size with seeded accept lengths against the oracle's book
-    n = rng.integers(0, k + 1, size=B).astype(np.int32)
-    new_len, slots = wl.sess.commit(wl.seq_ids, torch.from_numpy(n).cuda(), k)
-    want_len, want_slots = book.commit(list(range(B)), n, k)
-    assert list(new_len.cpu().numpy()) == want_len
-    assert slots.cpu().numpy().tolist() == want_slots
-    st = wl.sess.state()
-    assert list(st["ctx_len"][:B]) == want_len and list(st["free_stack"]) == book.free
+        # commit at full batch size with seeded accept lengths against the oracle's book
+        n = rng.integers(0, k + 1, size=B).astype(np.int32)
+        new_len, slots = wl.sess.commit(seq_ids, torch.from_numpy(n).cuda(), k)
+        want_len, want_slots = book.commit(list(range(B)), n, k)
+        assert list(new_len.cpu().numpy()) == want_len
+        assert slots.cpu().numpy().tolist() == want_slots
+        st = wl.sess.state()
+        assert list(st["ctx_len"][:B]) == want_len and list(st["free_stack"]) == book.free
     wl.close()
+    del wl
+    torch.cuda.empty_cache()
+
+
+def test_llama8b_logits_on_sampled_sequences_and_commit():
+    _check_workload("llama8b_b32_ctx1k-8k_k3", [3])
+
+
+def test_llama8b_large_batch_aliased_pool_k7_and_k1():
+    _check_workload("llama8b_b256_ctx2k-16k_k7", [7, 1])
