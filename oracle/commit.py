@@ -62,6 +62,23 @@ class KVBook:
             new_len.append(new)
         return new_len, slots
 
+    def truncate(self, seq_ids, new_len):
+        """Roll sequences back to new_len[b] cached positions (never forwards): the draft model's cache
+        after a verify step keeps only what the verifier kept.  Pages wholly beyond go back to the stack,
+        in batch order, last logical page first.  Returns the lengths now in force."""
+        out = []
+        for b, seq in enumerate(seq_ids):
+            new = int(new_len[b])
+            if new < 0:
+                raise ValueError("negative length")
+            new = min(new, self.ctx_len[seq])
+            keep = -(-new // self.page_size)
+            while len(self.pages[seq]) > keep:
+                self.free.append(self.pages[seq].pop())
+            self.ctx_len[seq] = new
+            out.append(new)
+        return out
+
 
 def mean_acceptance_length(accept_len):
     """Tokens produced per speculation step, the paper's acceptance length (Section 2.2): mean(n + 1)."""

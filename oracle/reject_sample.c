@@ -164,3 +164,44 @@ int oracle_reject_sample(int B, int k, int V, const float* logits, const float* 
     free(p); free(w);
     return 0;
 }
+
+/* Per-vocabulary uniform of the draft model's own draw: stream 2, row = index of the draft position. */
+double oracle_uniform_draft(uint64_t seed, uint64_t step, int b, int row, int v)
+{
+    uint32_t r = draw_word(seed, step, 2, (uint32_t)v >> 2, row, b, v & 3);
+    return ((double)(r >> 9) + 0.5) * (1.0 / 8388608.0);
+}
+
+/*
+ * The draft side of a speculation step (Section 2.1: "a draft model proposes several tokens"):
+ * the proposal distribution of draft position `row` and one token drawn from it.
+ *   logits [B, V] fp32: the draft model's logits for that position.
+ *   q_out  [B, V] fp32: q = softmax(logits / T), the distribution the verifier is later given.
+ *   tokens [B]    int32: x ~ q by the same exponential race as above, on stream 2:
+ *                        x = argmax_v q_v / (-ln u_v), ties to the lowest v.
+ *   dbg_keys [B, 2] may be NULL: winning and runner-up key.
+ * Convention of this build; the paper fixes only that x is a sample of q.
+ */
+int oracle_draft_sample(int B, int V, const float* logits, float temperature, uint64_t seed, uint64_t step, int row,
+                        int32_t* tokens, float* q_out, double* dbg_keys)
+{
+    if (B < 0 || V <= 0 || row < 0 || !(temperature > 0.0f)) return -1;
+    double* p = (double*)malloc(sizeof(double) * (size_t)V);
+    if (!p) return -1;
+    for (int b = 0; b < B; ++b) {
+        softmax_row(logits + (size_t)b * V, V, (double)temperature, p);
+        int x = -1;
+        double best = -1.0, second = -1.0;
+        for (int v = 0; v < V; ++v) {
+            q_out[(size_t)b * V + v] = (float)p[v];
+            if (!(p[v] > 0.0)) continue;
+            double key = p[v] / -log(oracle_uniform_draft(seed, step, b, row, v));
+            if (key > best) { second = best; best = key; x = v; }
+            else if (key > second) second = key;
+        }
+        tokens[b] = x;
+        if (dbg_keys) { dbg_keys[2 * b] = best; dbg_keys[2 * b + 1] = second; }
+    }
+    free(p);
+    return 0;
+}

@@ -39,6 +39,12 @@ def _load():
                                              ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64,
                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_reject_sample.restype = ctypes.c_int
+        lib.oracle_uniform_draft.argtypes = lib.oracle_uniform_vocab.argtypes
+        lib.oracle_uniform_draft.restype = ctypes.c_double
+        lib.oracle_draft_sample.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_float,
+                                            ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int,
+                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_draft_sample.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -86,3 +92,24 @@ def reject_sample(logits, q, draft, temperature, seed, step, debug=False):
     if debug:
         return accept_len, out_tokens, pqu, keys
     return accept_len, out_tokens
+
+
+def uniform_draft(seed, step, b, row, v):
+    return _load().oracle_uniform_draft(seed, step, b, row, v)
+
+
+def draft_sample(logits, temperature, seed, step, row, debug=False):
+    """The draft model's proposal for draft position ``row``: logits [B,V] fp32 ->
+    (tokens [B] int32 drawn from q, q [B,V] fp32 = softmax(logits/T)); with ``debug`` also keys [B,2]."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    B, V = logits.shape
+    tokens = np.zeros(B, dtype=np.int32)
+    q = np.zeros((B, V), dtype=np.float32)
+    keys = np.zeros((B, 2), dtype=np.float64)
+    rc = _load().oracle_draft_sample(B, V, logits.ctypes.data, float(temperature), int(seed), int(step), int(row),
+                                     tokens.ctypes.data, q.ctypes.data, keys.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_draft_sample: invalid arguments")
+    if debug:
+        return tokens, q, keys
+    return tokens, q

@@ -1,0 +1,147 @@
+"""Pins for the draft-side oracles: the proposal draw, the autoregressive draft loop and the cache
+roll-back after verification.
+
+The paper (Section 2.1) needs two things from the draft side: the drafted token is a sample of the
+distribution q that the verifier is given (otherwise the rejection procedure is no longer lossless),
+and the draft proposes k tokens one after the other.  Pinned here without retyping the oracle:
+  * q against scipy's softmax; the drawn tokens against q by chi-square;
+  * draft -> verify chain: with drafts drawn by the draft oracle and verified by the rejection oracle,
+    the first emitted token follows the TARGET distribution (fails if the draw is biased or if its random
+    stream is correlated with the verifier's streams);
+  * the loop against a cache-free recomputation: every iteration's distribution equals the one a single
+    causal pass over the whole token string gives;
+  * roll-back against a set-based model and against "commit with the smaller acceptance" directly.
+"""
+import numpy as np
+from scipy import stats
+from scipy.special import softmax as scipy_softmax
+
+from oracle import draft as od
+from oracle import forward as of
+from oracle import sampler
+from oracle.commit import KVBook
+
+CFG = dict(n_layers=1, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=16, ffn_dim=48, vocab=50,
+           rope_theta=1.0e4, rms_eps=1.0e-5, dtype="f64", tied_head=1)
+
+
+def _weights(cfg, seed=0, std=0.3):
+    rng = np.random.default_rng(seed)
+    d, Hq, Hkv, dh, F, V = cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["ffn_dim"], cfg["vocab"]
+    layers = [dict(attn_norm=1 + 0.1 * rng.standard_normal(d), wq=rng.standard_normal((Hq * dh, d)) * std,
+                   wk=rng.standard_normal((Hkv * dh, d)) * std, wv=rng.standard_normal((Hkv * dh, d)) * std,
+                   wo=rng.standard_normal((d, Hq * dh)) * std, ffn_norm=1 + 0.1 * rng.standard_normal(d),
+                   wg=rng.standard_normal((F, d)) * std, wu=rng.standard_normal((F, d)) * std,
+                   wd=rng.standard_normal((d, F)) * std) for _ in range(cfg["n_layers"])]
+    return dict(embed=rng.standard_normal((V, d)), layers=layers, final_norm=1 + 0.1 * rng.standard_normal(d), head=None)
+
+
+def test_proposal_distribution_is_softmax_and_tokens_follow_it():
+    V, N, T = 16, 400_000, 0.8
+    rng = np.random.default_rng(2)
+    row = (rng.standard_normal(V) * 1.5).astype(np.float32)
+    logits = np.broadcast_to(row, (N, V)).copy()
+    x, q = sampler.draft_sample(logits, T, 11, 4, 2)
+    want = scipy_softmax(row.astype(np.float64) / float(np.float32(T)))      # the temperature is an fp32 argument
+    assert np.max(np.abs(q[0] - want)) < 1e-7 and np.all(q == q[0])
+    obs = np.bincount(x, minlength=V).astype(np.float64)
+    chi2 = float(((obs - want * N) ** 2 / (want * N)).sum())
+    assert stats.chi2.sf(chi2, df=V - 1) > 1e-4
+    # deterministic; a different row, step or seed is a different draw
+    x2, _ = sampler.draft_sample(logits, T, 11, 4, 2)
+    assert np.array_equal(x, x2)
+    for args in ((11, 4, 3), (11, 5, 2), (12, 4, 2)):
+        xo, _ = sampler.draft_sample(logits, T, *args)
+        assert (xo != x).mean() > 0.5
+    # the reported keys: winner above runner-up, and the winner is the reported token's key
+    xs, qs, keys = sampler.draft_sample(logits[:5], T, 11, 4, 2, debug=True)
+    for b in range(5):
+        k_all = [want[v] / -np.log(sampler.uniform_draft(11, 4, b, 2, v)) for v in range(V)]
+        assert int(np.argmax(k_all)) == xs[b] and abs(keys[b, 0] - max(k_all)) < 1e-12 * max(k_all)
+        assert keys[b, 1] < keys[b, 0]
+
+
+def test_draft_then_verify_chain_is_lossless():
+    """Drafts drawn by the draft oracle, verified by the rejection oracle: first emitted token ~ target p_1,
+    and the acceptance length has the closed-form mean for prefix-independent rows."""
+    V, k, N = 12, 3, 500_000
+    rng = np.random.default_rng(8)
+    target = (rng.standard_normal((k + 1, V)) * 1.5).astype(np.float32)
+    draft_logits = (target[:k] + rng.standard_normal((k, V))).astype(np.float32)
+    drafts = np.zeros((N, k), dtype=np.int32)
+    q = np.zeros((N, k, V), dtype=np.float32)
+    for i in range(k):
+        drafts[:, i], q[:, i, :] = sampler.draft_sample(np.broadcast_to(draft_logits[i], (N, V)).copy(), 1.0, 21, 9, i)
+    n, out = sampler.reject_sample(np.broadcast_to(target, (N, k + 1, V)).copy(), q, drafts, 1.0, 21, 9)
+    p = scipy_softmax(target.astype(np.float64), axis=-1)
+    obs = np.bincount(out[:, 0], minlength=V).astype(np.float64)
+    chi2 = float(((obs - p[0] * N) ** 2 / (p[0] * N)).sum())
+    assert stats.chi2.sf(chi2, df=V - 1) > 1e-4
+    kept = n >= 1
+    obs2 = np.bincount(out[kept, 1], minlength=V).astype(np.float64)
+    chi2 = float(((obs2 - p[1] * kept.sum()) ** 2 / (p[1] * kept.sum())).sum())
+    assert stats.chi2.sf(chi2, df=V - 1) > 1e-4
+    beta = np.minimum(p[:k], q[0].astype(np.float64)).sum(axis=-1)
+    alpha = 1 + beta[0] + beta[0] * beta[1] + beta[0] * beta[1] * beta[2]
+    assert abs((n + 1).mean() - alpha) < 0.01
+
+
+def test_draft_loop_equals_cache_free_recomputation():
+    cfg = CFG
+    w = _weights(cfg, seed=5)
+    rng = np.random.default_rng(6)
+    B, C, k, T = 3, 7, 4, 0.9
+    ctx_tokens = rng.integers(0, cfg["vocab"], size=(B, C)).astype(np.int32)
+    pending = rng.integers(0, cfg["vocab"], size=(B, 2)).astype(np.int32)
+    kv = of.prefill(cfg, w, ctx_tokens)
+    drafts, q, kv_out, new_len = od.draft_loop(cfg, w, kv, pending, np.full(B, C), k, T, 77, 3)
+    assert drafts.shape == (B, k) and q.shape == (B, k, cfg["vocab"])
+    assert list(new_len) == [C + 2 + k - 1] * B
+    empty = [[(np.zeros((0, 2, 16)), np.zeros((0, 2, 16))) for _ in range(B)] for _ in range(cfg["n_layers"])]
+    string = np.concatenate([ctx_tokens, pending], axis=1)
+    for i in range(k):
+        logits, _ = of.verify_forward(cfg, w, empty, string, np.zeros(B, dtype=int))
+        x, qi = sampler.draft_sample(logits[:, -1, :].astype(np.float32), T, 77, 3, i)
+        assert np.array_equal(x, drafts[:, i])
+        assert np.max(np.abs(qi - q[:, i, :])) < 1e-6
+        assert np.max(np.abs(q[:, i, :].sum(-1) - 1)) < 1e-5
+        string = np.concatenate([string, x[:, None]], axis=1)
+    # the cache the loop leaves is the cache of the string without the last draft
+    full_kv = of.prefill(cfg, w, string[:, :-1])
+    for b in range(B):
+        assert kv_out[0][b][0].shape[0] == C + 2 + k - 1
+        assert np.max(np.abs(kv_out[0][b][0] - full_kv[0][b][0])) < 1e-10
+        assert np.max(np.abs(kv_out[0][b][1] - full_kv[0][b][1])) < 1e-10
+    # drafts differ across sequences and positions (a constant output would pass the checks above trivially)
+    assert len(set(drafts.reshape(-1).tolist())) > 3
+
+
+def test_truncate_against_set_model_and_against_smaller_commit():
+    P = 16
+    for ctx in (0, 1, 15, 16, 17, 31, 32, 47):
+        for k in (3, 7):
+            for n in range(k + 1):
+                for m in range(n + 1):
+                    a = KVBook(n_pages=12, page_size=P)
+                    a.assign(0, ctx, list(range(5, 5 + -(-ctx // P))))
+                    a.reserve([0], k)
+                    a.commit([0], [n], k)
+                    got = a.truncate([0], [ctx + m + 1])
+                    b = KVBook(n_pages=12, page_size=P)
+                    b.assign(0, ctx, list(range(5, 5 + -(-ctx // P))))
+                    b.reserve([0], k)
+                    b.commit([0], [m], k)
+                    assert got == [ctx + m + 1]
+                    assert a.pages[0] == b.pages[0] and a.free == b.free and a.ctx_len == b.ctx_len
+                    # set model: pages that hold positions 0 .. new-1
+                    assert len(a.pages[0]) == len({p // P for p in range(ctx + m + 1)})
+                    assert sorted(a.free + a.pages[0]) == list(range(12))
+    # never forwards; batch order decides the stack order
+    book = KVBook(n_pages=8, page_size=P)
+    book.assign("a", 40, [1, 2, 3])
+    book.assign("b", 33, [4, 5, 6])
+    assert book.truncate(["a", "b"], [100, 16]) == [40, 16]
+    assert book.pages["a"] == [1, 2, 3] and book.pages["b"] == [4]
+    assert book.free[-2:] == [6, 5]
+    assert book.truncate(["b", "a"], [0, 17]) == [0, 17]
+    assert book.pages["b"] == [] and book.pages["a"] == [1, 2] and book.free[-2:] == [4, 3]
