@@ -23,22 +23,38 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 MFMA peak
 DEFAULT_WORKLOAD = "llama8b_b32_ctx1k-8k_k3"
 
 
-def run_steps(wl, sv, torch, n_steps, accept_out, step0):
-    """n_steps verify steps on the current stream; accept lengths of step i land in accept_out[i]."""
+def run_steps(wl, sv, torch, n_steps, accept_out, step0, marks=None):
+    """n_steps verify steps on the current stream; accept lengths of step i land in accept_out[i].
+    A workload with a draft model runs its draft loop first and rolls the draft's cache back afterwards;
+    marks (a list) then receives (start, after-draft, end) event triples of every step."""
     sess = wl.sess
     B, k, V = wl.B, wl.k, wl.cfg["vocab"]
     buf = sess.step_buffers(B, k)
-    draft = wl.tokens[:, 1:].contiguous()
+    pair = hasattr(wl, "loop")
+    draft = wl.loop.drafts if pair else wl.tokens[:, 1:].contiguous()
     T = wl.wl["temperature"]
     ws = buf["workspace"]
     off = (-ws.data_ptr()) % 256
     ws = ws[off:off + ws.numel() - 256]
     for i in range(n_steps):
         wl.restore()                                             # same cache state every step
+        if pair:
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if marks is not None else None
+            if ev:
+                ev[0].record()
+            wl.loop.run(wl.seq_ids, wl.pending, wl.q, T, wl.seed, step0 + i)
+            wl.tokens[:, 1:] = draft                             # drafted tokens into the verify input rows
+            if ev:
+                ev[1].record()
         sv.spec_verify_forward(sess.model, sess.kv, B, k, wl.seq_ids, wl.tokens, buf["logits"], ws)
         sv.spec_reject_sample(B, k, V, buf["logits"], wl.q, draft, T, wl.seed, step0 + i, accept_out[i],
                               buf["out_tokens"], None, buf["sample_ws"])
         sv.spec_commit_kv(sess.kv, B, k, wl.seq_ids, accept_out[i], buf["new_ctx_len"], buf["commit_slots"])
+        if pair:
+            wl.loop.roll_back(wl.seq_ids, buf["new_ctx_len"])
+            if ev:
+                ev[2].record()
+                marks.append(ev)
 
 
 def hbm_ceiling(sv, torch, nbytes=1 << 30, reps=5):
@@ -123,15 +139,20 @@ def main():
     import torch
 
     from paper_2604_26779_amd import binding as sv
-    from paper_2604_26779_amd.workloads import DeviceWorkload, algorithmic_bytes
+    import synth_inputs as si
+    from paper_2604_26779_amd.workloads import DeviceWorkload, DraftPairWorkload, algorithmic_bytes
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     for item in args.tune:
         name, value = item.split("=")
         sv.spec_tune_set(name, int(value))
 
-    wl = DeviceWorkload(args.workload)
-    wl.make_drafts()
+    pair = "draft_model" in si.WORKLOADS[args.workload]
+    if pair:
+        wl = DraftPairWorkload(args.workload)
+    else:
+        wl = DeviceWorkload(args.workload)
+        wl.make_drafts()
     B, k = wl.B, wl.k
     K, W = args.steps, args.warmup
     accept = torch.zeros((max(K, W), B), dtype=torch.int32, device="cuda")
@@ -151,8 +172,9 @@ def main():
     tokens_per_s = produced / (ms_per_step * K / 1e3)
 
     # instrumented run of the same K steps: HIP events around every kernel class
-    sv.spec_profile_begin(K * 400 + 64)
-    run_steps(wl, sv, torch, K, accept, 1000)
+    marks = [] if pair else None
+    sv.spec_profile_begin(K * (400 + (200 if pair else 0)) + 64)
+    run_steps(wl, sv, torch, K, accept, 1000, marks)
     prof = sv.spec_profile_end()
     per_step = {name: ms / K for name, (ms, cnt) in prof.items()}
     launches = {name: cnt / K for name, (ms, cnt) in prof.items()}
@@ -202,6 +224,12 @@ def main():
         "wall_s_timed_region": round(wall, 3),
         "hbm_ceiling_measured": hbm_ceiling(sv, torch),
     }
+    if pair:
+        out["draft_verify_split_ms"] = {
+            "draft_loop": round(sum(e[0].elapsed_time(e[1]) for e in marks) / K, 4),
+            "verify_sample_commit_rollback": round(sum(e[1].elapsed_time(e[2]) for e in marks) / K, 4),
+            "draft_model": wl.wl["draft_model"], "draft_passes": k}
+        args.no_cpu_baseline = True               # the oracle baseline is reported on the headline workload only
     if not args.no_cpu_baseline:
         base, _ = cpu_baseline(wl, torch, args.cpu_seqs)
         out["cpu_baseline"] = {kk: (round(v, 3) if isinstance(v, float) else v) for kk, v in base.items()}

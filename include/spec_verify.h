@@ -193,6 +193,40 @@ spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const int32_t* dev
                            const int32_t* dev_accept_len, int32_t* dev_new_ctx_len, int32_t* dev_commit_slots,
                            void* stream);
 
+/* ---------------------------------------------------------------- draft side ---------------------------------- */
+
+/*
+ * The draft model's proposal for one draft position (Section 2.1: the draft proposes several tokens, which
+ * the target then verifies; Section 3.1 uses a learned single-layer draft).  A draft model is an ordinary
+ * spec_model with a cache of its own, run with spec_verify_forward one position at a time; this call turns
+ * its logits into q = softmax(logits / temperature) and one token x ~ q:
+ *   dev_logits: row b at dev_logits + b * logits_row_stride (fp32, V entries);
+ *   dev_q:      row b written at dev_q + b * q_row_stride (so that the rows of all k positions can be laid out
+ *               as the [B, k, V] array spec_reject_sample takes);
+ *   x is written to dev_tokens_a[b * stride_a] and dev_tokens_b[b * stride_b] (either pointer may be NULL):
+ *               typically the verify step's token array [B, k+1] and the draft's next input [B].
+ * Draw: exponential race argmax_v q_v / (-ln u_v), ties to the lowest v, Philox4x32-10 with the key and
+ * counter layout of spec_reject_sample on stream 2: counter = (v >> 2, row, b, step*4 + 2), word v & 3,
+ * u_v = ((word >> 9) + 0.5) * 2^-23; `row` is the index of the draft position (0 .. SPEC_MAX_DRAFT).
+ * Errors: SPEC_EINVAL (sizes, strides below V, temperature <= 0, step >= 2^30, null).  Asynchronous on `stream`.
+ */
+spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int64_t logits_row_stride,
+                              float temperature, uint64_t seed, uint64_t step, int32_t row,
+                              int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
+                              float* dev_q, int64_t q_row_stride, void* stream);
+
+/*
+ * Roll a cache back (the draft's cache after verification keeps only what the verifier kept): batch entry b
+ * ends with min(current length, dev_len[b] + delta) cached positions; a negative target is clamped to 0 and
+ * flagged like other bookkeeping errors (reported by the next spec_kv_get_state).  Pages wholly beyond the new
+ * length return to the free stack, a sequence's last page first, batch entries in order.  dev_new_len [B]
+ * (may be NULL) receives the lengths in force.  With dev_len = the target's dev_new_ctx_len and delta = -1
+ * the draft is left one position behind the target, which the next step's first draft pass feeds together
+ * with the newly emitted token.  Asynchronous on `stream`.
+ */
+spec_status spec_kv_truncate(spec_kv* kv, int32_t B, const int32_t* dev_seq_ids, const int32_t* dev_len, int32_t delta,
+                             int32_t* dev_new_len, void* stream);
+
 /* ---------------------------------------------------------------- tuning / introspection -------------------- */
 
 /* Set a launch parameter by name (split factors and the like); unknown names give SPEC_EINVAL.

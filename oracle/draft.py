@@ -22,7 +22,8 @@ from . import sampler as _sampler
 def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, step):
     """pending [B, P] int tokens not yet in the draft's cache, ctx_len [B] its cached length.
 
-    Returns (drafts [B, k] int32, q [B, k, V] fp32, kv_ctx grown by the fed positions, new_len [B]).
+    Returns (drafts [B, k] int32, q [B, k, V] fp32, kv_ctx grown by the fed positions, new_len [B],
+    keys [B, k, 2] = winning and runner-up key of every draw).
     """
     pending = np.asarray(pending)
     B = pending.shape[0]
@@ -30,6 +31,7 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
     kv = [[(np.asarray(K, dtype=np.float64), np.asarray(V, dtype=np.float64)) for (K, V) in per_seq] for per_seq in kv_ctx]
     drafts = np.zeros((B, k), dtype=np.int32)
     q = np.zeros((B, k, cfg["vocab"]), dtype=np.float32)
+    keys = np.zeros((B, k, 2), dtype=np.float64)
     feed = pending
     for i in range(k):
         logits, new_kv = _forward.verify_forward(cfg, weights, kv, feed, ctx_len)
@@ -38,8 +40,8 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
                 K, V = kv[layer][b]
                 kv[layer][b] = (np.concatenate([K, new_kv[layer][0][b]]), np.concatenate([V, new_kv[layer][1][b]]))
         ctx_len += feed.shape[1]
-        x, qi = _sampler.draft_sample(logits[:, -1, :].astype(np.float32), temperature, seed, step, i)
+        x, qi, keys[:, i, :] = _sampler.draft_sample(logits[:, -1, :].astype(np.float32), temperature, seed, step, i, debug=True)
         drafts[:, i] = x
         q[:, i, :] = qi
         feed = x.reshape(B, 1)
-    return drafts, q, kv, ctx_len
+    return drafts, q, kv, ctx_len, keys

@@ -24,7 +24,7 @@ EXPORTS = [
     "spec_kv_alloc", "spec_kv_free", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_sample_workspace_bytes", "spec_reject_sample",
-    "spec_commit_kv", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
+    "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_calib_read", "spec_calib_copy",
 ]
 
@@ -76,6 +76,8 @@ def lib():
             "spec_sample_workspace_bytes": (sz, [i32, i32]),
             "spec_reject_sample": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp, sz, vp]),
             "spec_commit_kv": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
+            "spec_draft_sample": (i32, [i32, i32, vp, i64, f32, u64, u64, i32, vp, i32, vp, i32, vp, i64, vp]),
+            "spec_kv_truncate": (i32, [vp, i32, vp, vp, i32, vp, vp]),
             "spec_tune_set": (i32, [ctypes.c_char_p, i32]),
             "spec_tune_get": (i32, [ctypes.c_char_p]),
             "spec_profile_class_count": (i32, []),
@@ -108,6 +110,13 @@ def _ptr(t):
         assert t.is_contiguous()
         return t.data_ptr()
     return int(t)
+
+
+def _addr(t):
+    """Address of a tensor's first element (views into larger arrays allowed), or a raw address."""
+    if t is None:
+        return None
+    return t.data_ptr() if isinstance(t, torch.Tensor) else int(t)
 
 
 def _stream(stream):
@@ -223,6 +232,18 @@ def spec_reject_sample(B, k, V, logits, q, draft_tokens, temperature, seed, step
 def spec_commit_kv(kv, B, k, seq_ids, accept_len, new_ctx_len, commit_slots, stream=None):
     _check(lib().spec_commit_kv(kv, B, k, _ptr(seq_ids), _ptr(accept_len), _ptr(new_ctx_len), _ptr(commit_slots),
                                 _stream(stream)))
+
+
+def spec_draft_sample(B, V, logits, logits_row_stride, temperature, seed, step, row, tokens_a, stride_a, tokens_b, stride_b,
+                      q, q_row_stride, stream=None):
+    """logits, tokens_a, tokens_b, q: device tensors or raw addresses (ints) of the first row / element."""
+    _check(lib().spec_draft_sample(B, V, _addr(logits), int(logits_row_stride), float(temperature), int(seed), int(step),
+                                   int(row), _addr(tokens_a), int(stride_a), _addr(tokens_b), int(stride_b), _addr(q),
+                                   int(q_row_stride), _stream(stream)))
+
+
+def spec_kv_truncate(kv, B, seq_ids, lengths, delta, new_len, stream=None):
+    _check(lib().spec_kv_truncate(kv, B, _ptr(seq_ids), _ptr(lengths), int(delta), _ptr(new_len), _stream(stream)))
 
 
 def spec_tune_set(name, value):

@@ -57,7 +57,7 @@ void prof_record(int cls, hipStream_t s)
 
 static const char* const PROF_NAMES[PC_COUNT] = {
     "other", "embed_norm", "gemm_qkv", "qkv_rope", "attn", "attn_reduce", "gemm_o", "resid_norm", "gemm_gu", "swiglu",
-    "gemm_down", "gemm_head", "sample_stats", "sample_draw", "kv_reserve", "kv_commit"};
+    "gemm_down", "gemm_head", "sample_stats", "sample_draw", "kv_reserve", "kv_commit", "draft_sample", "kv_truncate"};
 
 }  // namespace specv
 
@@ -455,6 +455,19 @@ extern "C" spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const i
     kv->ub.max_ctx += k + 1;
     kv->ub.added_ctx += (int64_t)B * (k + 1);
     kv->ub.touched = std::min<int64_t>(kv->max_seqs, kv->ub.touched + B);
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_kv_truncate(spec_kv* kv, int32_t B, const int32_t* dev_seq_ids, const int32_t* dev_len, int32_t delta,
+                                        int32_t* dev_new_len, void* stream)
+{
+    if (!kv || !dev_seq_ids || !dev_len) { set_error("spec_kv_truncate: null pointer"); return SPEC_EINVAL; }
+    if (B < 1 || B > kv->max_seqs) { set_error("spec_kv_truncate: B out of range"); return SPEC_EINVAL; }
+    prof_mark(PC_OTHER, (hipStream_t)stream);
+    spec_status st = launch_kv_truncate(kv, B, dev_seq_ids, dev_len, delta, dev_new_len, (hipStream_t)stream);
+    if (st != SPEC_OK) return st;
+    prof_mark(PC_KV_TRUNCATE, (hipStream_t)stream);
+    kv->device_ahead = true;            // lengths only shrink: the conservative bounds stay valid
     return SPEC_OK;
 }
 

@@ -18,7 +18,7 @@ int tune(const char* name);
 enum ProfClass {
     PC_OTHER = 0, PC_EMBED_NORM, PC_GEMM_QKV, PC_QKV_ROPE, PC_ATTN, PC_ATTN_REDUCE, PC_GEMM_O, PC_RESID_NORM,
     PC_GEMM_GU, PC_SWIGLU, PC_GEMM_DOWN, PC_GEMM_HEAD, PC_SAMPLE_STATS, PC_SAMPLE_DRAW, PC_KV_RESERVE, PC_KV_COMMIT,
-    PC_COUNT
+    PC_DRAFT_SAMPLE, PC_KV_TRUNCATE, PC_COUNT
 };
 extern bool g_prof_on;
 void prof_record(int cls, hipStream_t s);
@@ -119,6 +119,9 @@ namespace specv {
 spec_status launch_kv_reserve(spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, hipStream_t s);
 spec_status launch_kv_commit(spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, const int32_t* dev_accept_len,
                              int32_t* dev_new_ctx_len, int32_t* dev_commit_slots, hipStream_t s);
+
+spec_status launch_kv_truncate(spec_kv* kv, int B, const int32_t* dev_seq_ids, const int32_t* dev_len, int delta,
+                               int32_t* dev_new_len, hipStream_t s);
 
 // ---- fp32 generic path (forward_f32.hip) ----
 size_t f32_workspace_bytes(const spec_model_desc& d, int B, int k);

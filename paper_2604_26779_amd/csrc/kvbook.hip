@@ -126,6 +126,64 @@ __global__ __launch_bounds__(KVB_THREADS) void kv_commit_kernel(
     if (threadIdx.x == 0) *free_count = s_free;
 }
 
+// Roll sequences back to min(current, len[b] + delta) cached positions; pages wholly beyond return to
+// the free stack in the same order the commit uses (batch order, a sequence's last page first).
+__global__ __launch_bounds__(KVB_THREADS) void kv_truncate_kernel(
+    int B, const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ len, int delta, int max_seqs, int max_pages,
+    int32_t* __restrict__ ctx_len, int32_t* __restrict__ n_held, int32_t* __restrict__ page_table,
+    int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count, int32_t* __restrict__ error,
+    int32_t* __restrict__ new_len)
+{
+    __shared__ int lds[KVB_THREADS];
+    __shared__ int s_free;
+    if (threadIdx.x == 0) s_free = *free_count;
+    __syncthreads();
+    for (int base = 0; base < B; base += KVB_THREADS) {
+        int b = base + threadIdx.x;
+        int seq = -1, held = 0, keep = 0, release = 0;
+        if (b < B) {
+            seq = seq_ids[b];
+            if (seq < 0 || seq >= max_seqs) { atomicOr(error, KV_ERR_SEQ); seq = -1; }
+        }
+        if (seq >= 0) {
+            held = n_held[seq];
+            int ctx = ctx_len[seq];
+            int want = len[b] + delta;
+            if (want < 0) { atomicOr(error, KV_ERR_LEN); want = 0; }
+            int fresh = want < ctx ? want : ctx;
+            keep = (fresh + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
+            release = held > keep ? held - keep : 0;
+            ctx_len[seq] = fresh;
+            if (new_len) new_len[b] = fresh;
+        } else if (b < B) {
+            if (new_len) new_len[b] = -1;
+        }
+        int total;
+        int off = block_exclusive_scan(release, lds, &total);
+        int top = s_free;
+        __syncthreads();
+        for (int j = 0; j < release; ++j) {
+            int64_t at = (int64_t)seq * max_pages + held - 1 - j;
+            free_stack[top + off + j] = page_table[at];
+            page_table[at] = -1;
+        }
+        if (release > 0) n_held[seq] = keep;
+        if (threadIdx.x == 0) s_free = top + total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *free_count = s_free;
+}
+
+spec_status launch_kv_truncate(spec_kv* kv, int B, const int32_t* dev_seq_ids, const int32_t* dev_len, int delta,
+                               int32_t* dev_new_len, hipStream_t s)
+{
+    kv_truncate_kernel<<<1, KVB_THREADS, 0, s>>>(B, dev_seq_ids, dev_len, delta, kv->max_seqs, kv->max_pages, kv->d_ctx_len,
+                                                 kv->d_n_held, kv->d_page_table, kv->d_free_stack, kv->d_free_count,
+                                                 kv->d_error, dev_new_len);
+    SPEC_LAUNCH_CHECK("kv_truncate_kernel");
+    return SPEC_OK;
+}
+
 spec_status launch_kv_reserve(spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, hipStream_t s)
 {
     kv_reserve_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, dev_seq_ids, kv->max_seqs, kv->max_pages, kv->d_ctx_len,

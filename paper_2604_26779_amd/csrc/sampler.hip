@@ -166,6 +166,62 @@ __global__ __launch_bounds__(SAMP_THREADS) void reject_sample_kernel(
     }
 }
 
+// The draft model's own draw (one workgroup per sequence): q = softmax(logits / T) written out for
+// the verifier, and x = argmax_v e_v / (-ln u_v) on random stream 2 (e = exp(z - max): the argmax
+// does not need the normalisation).  Two passes over the row; the second one hits the cache.
+__global__ __launch_bounds__(SAMP_THREADS) void draft_sample_kernel(
+    int V, const float* __restrict__ logits, int64_t logits_stride, float inv_t, uint32_t seed_lo, uint32_t seed_hi,
+    uint32_t step4, uint32_t row, int32_t* __restrict__ tok_a, int stride_a, int32_t* __restrict__ tok_b, int stride_b,
+    float* __restrict__ q, int64_t q_stride)
+{
+    const int b = blockIdx.x;
+    const float* lrow = logits + (int64_t)b * logits_stride;
+    float* qrow = q + (int64_t)b * q_stride;
+    __shared__ float lm[SAMP_THREADS / 64], ls[SAMP_THREADS / 64];
+    __shared__ float lk[SAMP_THREADS / 64];
+    __shared__ int lv[SAMP_THREADS / 64];
+    float m = -INFINITY, s = 0.f;
+    for (int v = threadIdx.x; v < V; v += SAMP_THREADS) {
+        float z = lrow[v] * inv_t;
+        if (z > m) { s = s * expf(m - z) + 1.f; m = z; }
+        else if (z > -INFINITY) s += expf(z - m);
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
+        online_merge(m, s, m2, s2);
+    }
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) { lm[wave] = m; ls[wave] = s; }
+    __syncthreads();
+    m = lm[0]; s = ls[0];
+    for (int w = 1; w < SAMP_THREADS / 64; ++w) online_merge(m, s, lm[w], ls[w]);
+    const float inv_s = 1.0f / s;
+
+    float best = -1.f;
+    int best_v = -1;
+    const int groups = (V + 3) >> 2;
+    for (int g = threadIdx.x; g < groups; g += SAMP_THREADS) {
+        Philox4 r = philox4x32_10((uint32_t)g, row, (uint32_t)b, step4 + 2u, seed_lo, seed_hi);
+        uint32_t words[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int v = g * 4 + j;
+            if (v >= V) break;
+            float e = expf(lrow[v] * inv_t - m);
+            qrow[v] = e * inv_s;
+            if (!(e > 0.f)) continue;
+            float u = ((float)(words[j] >> 9) + 0.5f) * (1.0f / 8388608.0f);
+            float key = e / (-logf(u));
+            if (key > best) { best = key; best_v = v; }
+        }
+    }
+    block_argmax(best, best_v, lk, lv);
+    if (threadIdx.x == 0) {
+        if (tok_a) tok_a[(int64_t)b * stride_a] = best_v;
+        if (tok_b) tok_b[(int64_t)b * stride_b] = best_v;
+    }
+}
+
 }  // namespace specv
 
 extern "C" size_t spec_sample_workspace_bytes(int32_t B, int32_t k)
@@ -199,5 +255,28 @@ extern "C" spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const
                                                     dev_accept_len, dev_out_tokens, dev_dbg);
     SPEC_LAUNCH_CHECK("reject_sample_kernel");
     prof_mark(PC_SAMPLE_DRAW, s);
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int64_t logits_row_stride,
+                                         float temperature, uint64_t seed, uint64_t step, int32_t row,
+                                         int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
+                                         float* dev_q, int64_t q_row_stride, void* stream)
+{
+    using namespace specv;
+    if (B < 1 || V < 1 || row < 0 || row > SPEC_MAX_DRAFT) { set_error("spec_draft_sample: B, V or row out of range"); return SPEC_EINVAL; }
+    if (!(temperature > 0.f)) { set_error("spec_draft_sample: temperature must be > 0"); return SPEC_EINVAL; }
+    if (step >= (1ull << 30)) { set_error("spec_draft_sample: step must be < 2^30"); return SPEC_EINVAL; }
+    if (!dev_logits || !dev_q || (!dev_tokens_a && !dev_tokens_b)) { set_error("spec_draft_sample: null pointer"); return SPEC_EINVAL; }
+    if (logits_row_stride < V || q_row_stride < V || (dev_tokens_a && stride_a < 1) || (dev_tokens_b && stride_b < 1)) {
+        set_error("spec_draft_sample: a row stride is smaller than the row"); return SPEC_EINVAL;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    prof_mark(PC_OTHER, s);
+    draft_sample_kernel<<<B, SAMP_THREADS, 0, s>>>(V, dev_logits, logits_row_stride, 1.0f / temperature, (uint32_t)seed,
+                                                   (uint32_t)(seed >> 32), (uint32_t)(step * 4u), (uint32_t)row,
+                                                   dev_tokens_a, stride_a, dev_tokens_b, stride_b, dev_q, q_row_stride);
+    SPEC_LAUNCH_CHECK("draft_sample_kernel");
+    prof_mark(PC_DRAFT_SAMPLE, s);
     return SPEC_OK;
 }

@@ -1,0 +1,54 @@
+"""Device-memory plumbing for the draft side of a speculation step: k autoregressive passes of a
+draft model (a VerifySession of its own: its own weights and paged cache), each followed by
+``spec_draft_sample`` and a commit of the fed positions, and the roll-back of the draft's cache
+after verification.  Only pointers, strides and call order are handled here.
+"""
+import torch
+
+from . import binding as sv
+
+
+class DraftLoop:
+    def __init__(self, draft_session, B, k):
+        self.sess, self.B, self.k = draft_session, int(B), int(k)
+        dev = draft_session.device
+        self.feed = torch.zeros(B, dtype=torch.int32, device=dev)          # the single token of passes 2..k
+        self.ones = torch.ones(B, dtype=torch.int32, device=dev)
+        self.zeros = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.drafts = torch.zeros((B, k), dtype=torch.int32, device=dev)
+        self.new_len = torch.zeros(B, dtype=torch.int32, device=dev)
+
+    def run(self, seq_ids, pending, q_out, temperature, seed, step, stream=None):
+        """pending [B, P] int32 (tokens the draft's cache lacks; P = 2 in steady state), q_out [B, k, V] fp32.
+
+        Fills self.drafts [B, k] and q_out; the draft's cache grows by P + k - 1 positions."""
+        sess, B, k = self.sess, self.B, self.k
+        V = sess.cfg["vocab"]
+        P = pending.shape[1]
+        assert q_out.shape == (B, k, V) and q_out.is_contiguous() and pending.is_contiguous()
+        for i in range(k):
+            if i == 0:
+                logits = sess.forward(seq_ids, pending, stream)                          # [B, P, V]
+                last = logits.data_ptr() + (P - 1) * V * 4
+                stride = P * V
+            else:
+                logits = sess.forward(seq_ids, self.feed.view(B, 1), stream)            # [B, 1, V]
+                last, stride = logits.data_ptr(), V
+            sv.spec_draft_sample(B, V, last, stride, temperature, seed, step, i,
+                                 self.drafts.data_ptr() + 4 * i, k, self.feed, 1,
+                                 q_out.data_ptr() + 4 * i * V, k * V, stream)
+            fed = P if i == 0 else 1
+            sv.spec_commit_kv(sess.kv, B, fed - 1, seq_ids, self.ones if fed == 2 else self._full(fed - 1), None, None, stream)
+        return self.drafts
+
+    def _full(self, n):
+        if n == 0:
+            return self.zeros
+        if n == 1:
+            return self.ones
+        return torch.full((self.B,), n, dtype=torch.int32, device=self.sess.device)
+
+    def roll_back(self, seq_ids, target_new_ctx_len, stream=None):
+        """After the target's commit: keep target_new_ctx_len - 1 positions (never more than cached)."""
+        sv.spec_kv_truncate(self.sess.kv, self.B, seq_ids, target_new_ctx_len, -1, self.new_len, stream)
+        return self.new_len

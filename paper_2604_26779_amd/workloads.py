@@ -96,3 +96,49 @@ def algorithmic_bytes(cfg, ctx_len, B, k):
         sampler=B * (k + 1 + 2) * V * 4,
         logits_write=B * (k + 1) * V * 4,
     )
+
+
+class DraftPairWorkload(DeviceWorkload):
+    """A target workload plus a single-layer draft model with a cache of its own that is one position
+    behind the target's (the draft's first pass of a step feeds the previous input and the last emitted
+    token together).  Drafts and q come from the draft loop itself, not from make_drafts."""
+
+    def __init__(self, workload_name, seed=si.DEFAULT_SEED, device="cuda"):
+        super().__init__(workload_name, seed=seed, device=device)
+        from .draft import DraftLoop
+        self.draft_cfg = si.MODELS[self.wl["draft_model"]]
+        B, k = self.B, self.k
+        dweights = si.make_weights(self.draft_cfg, seed=seed + 17, device=device)
+        dctx = self.ctx_len - 1
+        step_pages = [-(-(int(c) + k + 2) // si.PAGE_SIZE) for c in dctx]
+        n_pages = sum(step_pages) + 64
+        self.dsess = VerifySession(self.draft_cfg, dweights, max_seqs=B, max_ctx_len=int(dctx.max()) + 256, n_pages=n_pages,
+                                   device=device)
+        keep = {"embed"} | {n for n in dweights if n.endswith("norm")}
+        if self.draft_cfg["dtype"] == "bf16":
+            self.dsess.weights = [t for n, t in dweights.items() if n in keep]
+        del dweights
+        torch.cuda.empty_cache()
+        g = torch.Generator(device=device)
+        g.manual_seed(int(seed) + 19)
+        self.dsess.pool.normal_(generator=g)
+        rng = np.random.Generator(np.random.Philox(int(seed) + 23))
+        order = rng.permutation(n_pages)
+        at = 0
+        for b in range(B):
+            need = -(-int(dctx[b]) // si.PAGE_SIZE)
+            self.dsess.assign(b, int(dctx[b]), [int(p) for p in order[at:at + need]])
+            at += need
+        prev = torch.from_numpy(rng.integers(0, self.cfg["vocab"], size=B).astype(np.int32)).to(device)
+        self.pending = torch.stack([prev, self.tokens[:, 0]], dim=1).contiguous()
+        self.loop = DraftLoop(self.dsess, B, k)
+        self.dsnapshot = torch.empty(sv.spec_kv_state_bytes(self.dsess.kv), dtype=torch.uint8, device=device)
+        sv.spec_kv_snapshot(self.dsess.kv, self.dsnapshot)
+
+    def restore(self, stream=None):
+        super().restore(stream)
+        sv.spec_kv_restore(self.dsess.kv, self.dsnapshot, stream)
+
+    def close(self):
+        self.dsess.close()
+        super().close()

@@ -33,6 +33,13 @@ MODELS = {
     # Llama-3-8B-shaped (BASELINE config 1).
     "llama8b_bf16": dict(n_layers=32, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
                          vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0),
+    # Single-layer draft models (MTP-style: one decoder layer, output head tied to the embedding).
+    "draft_tiny_fp32": dict(n_layers=1, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn_dim=704,
+                            vocab=1024, rope_theta=1.0e4, rms_eps=1.0e-5, dtype="f32", tied_head=1),
+    "draft_small_bf16": dict(n_layers=1, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1280,
+                             vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1),
+    "draft1l_8b_bf16": dict(n_layers=1, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
+                            vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1),
 }
 
 # name -> batch description of the verify step.
@@ -44,6 +51,14 @@ WORKLOADS = {
     "llama8b_b32_ctx1k-8k_k3": dict(model="llama8b_bf16", B=32, k=3, ctx_lo=1024, ctx_hi=8192, noise_std=1.0,
                                     temperature=1.0),
 }
+# Draft + target pair (BASELINE config 3): a single-layer draft run autoregressively for k = 5, then the
+# 8B-shaped verify, B = 64, contexts of 4096 tokens.
+WORKLOADS["draft_pair_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model="draft1l_8b_bf16", B=64, k=5, ctx_lo=4096,
+                                              ctx_hi=4096, noise_std=0.0, temperature=1.0)
+WORKLOADS["draft_pair_small_b5_k4"] = dict(model="small_bf16", draft_model="draft_small_bf16", B=5, k=4, ctx_lo=20,
+                                           ctx_hi=600, noise_std=0.0, temperature=0.9)
+WORKLOADS["draft_pair_tiny_b4_k3"] = dict(model="tiny_fp32", draft_model="draft_tiny_fp32", B=4, k=3, ctx_lo=100,
+                                          ctx_hi=140, noise_std=0.0, temperature=1.0)
 # Large rollout batch (BASELINE config 2): B=256, contexts uniform in [2048, 16384], k swept.  The
 # cache of 32 distinct layers would not fit one GPU (309 GB on average), so layer l uses layer
 # pool l mod 8 (same bytes streamed per step, an eighth of the footprint); the draft noise of

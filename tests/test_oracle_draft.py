@@ -94,8 +94,8 @@ def test_draft_loop_equals_cache_free_recomputation():
     ctx_tokens = rng.integers(0, cfg["vocab"], size=(B, C)).astype(np.int32)
     pending = rng.integers(0, cfg["vocab"], size=(B, 2)).astype(np.int32)
     kv = of.prefill(cfg, w, ctx_tokens)
-    drafts, q, kv_out, new_len = od.draft_loop(cfg, w, kv, pending, np.full(B, C), k, T, 77, 3)
-    assert drafts.shape == (B, k) and q.shape == (B, k, cfg["vocab"])
+    drafts, q, kv_out, new_len, keys = od.draft_loop(cfg, w, kv, pending, np.full(B, C), k, T, 77, 3)
+    assert drafts.shape == (B, k) and q.shape == (B, k, cfg["vocab"]) and np.all(keys[..., 0] > keys[..., 1])
     assert list(new_len) == [C + 2 + k - 1] * B
     empty = [[(np.zeros((0, 2, 16)), np.zeros((0, 2, 16))) for _ in range(B)] for _ in range(cfg["n_layers"])]
     string = np.concatenate([ctx_tokens, pending], axis=1)
