@@ -38,17 +38,20 @@ constexpr int ATT_DEPTH = 3;                 // pages in flight per wavefront
 constexpr int DH = 128;
 constexpr int BLOCK_U4 = SPEC_PAGE_SIZE * DH * 2 / 16;   // 256 16-byte words per K or V block
 
-// part_o : [item][RB*16 rows][128] fp32, part_ml : [item][RB*16][2] (max in log2 domain, sum)
+// part_o : [item][rows][128] fp32, part_ml : [item][rows][2] (max in log2 domain, sum); rows = RG*RB*16
 // item = (b * Hkv + kvh) * max_chunks + chunk
+// More than 32 query rows per kv head (deep drafts, or many query heads per kv head) are split into RG row
+// groups of RB*16 rows, one workgroup each (blockIdx.x = kvh * RG + row group): the groups of a chunk are
+// dispatched back to back and re-read the same pages through the caches.
 template <int RB>
 __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
-    int layer_pool, float scale_log2, int max_chunks, float* __restrict__ part_o, float* __restrict__ part_ml)
+    int layer_pool, float scale_log2, int max_chunks, int RG, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     // chunk is the slowest grid dimension: the first chunks (every sequence has them) are dispatched first,
     // the chunks only long sequences have - and the empty workgroups of the short ones - last
-    const int kvh = blockIdx.x, b = blockIdx.y, chunk = blockIdx.z;
-    const int Hkv = gridDim.x;
+    const int kvh = blockIdx.x / RG, rb0 = (blockIdx.x % RG) * RB, b = blockIdx.y, chunk = blockIdx.z;
+    const int Hkv = gridDim.x / RG;
     const int seq = seq_ids[b];
     const int ctx = kv.ctx_len[seq];
     int total = ctx + T;
@@ -69,7 +72,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     bf16x8_t qhi[RB][4], qlo[RB][4];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        int r = rb * 16 + lq;
+        int r = (rb0 + rb) * 16 + lq;
         const float* src = q + ((int64_t)(b * T + r / G) * Hq + kvh * G + r % G) * DH + lg * 8;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
@@ -87,7 +90,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     int row_limit[RB];                       // last visible cache position of this lane's query row
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        int r = rb * 16 + lq;
+        int r = (rb0 + rb) * 16 + lq;
         row_limit[rb] = r < R ? ctx + r / G : -1;
     }
 
@@ -233,8 +236,8 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     }
     __syncthreads();
     const int64_t item = ((int64_t)b * Hkv + kvh) * max_chunks + chunk;
-    float* po = part_o + item * (RB * 16) * DH;
-    float* pml = part_ml + item * (RB * 16) * 2;
+    float* po = part_o + item * (RG * RB * 16) * DH;
+    float* pml = part_ml + item * (RG * RB * 16) * 2;
     // element e of the tile: (rb, cb, lane', j) -> row rb*16 + lane'%16, channel cb*16 + (lane'/16)*4 + j
     for (int e = threadIdx.x; e < RB * 8 * 64; e += 256) {
         int l2 = e & 63, cb = (e >> 6) & 7, rb = e >> 9;
@@ -250,7 +253,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) o4[j] += f * s_o[w][rb][cb][l2][j];
         }
-        int r = rb * 16 + row, c = cb * 16 + (l2 >> 4) * 4;
+        int r = (rb0 + rb) * 16 + row, c = cb * 16 + (l2 >> 4) * 4;
         *(float4*)(po + (int64_t)r * DH + c) = make_float4(o4[0], o4[1], o4[2], o4[3]);
         if (cb == 0 && (l2 >> 4) == 0) { pml[r * 2] = M; pml[r * 2 + 1] = L; }
     }
@@ -296,24 +299,30 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
 
 int attn_chunk_pages() { return ATT_CP; }
 
+// rows of a partial tile for R query rows per kv head: whole 16-row blocks, in groups of two beyond 32 rows
+int attn_rows_padded(int R)
+{
+    int blocks = (int)cdiv(R, 16);
+    return blocks <= 2 ? blocks * 16 : (int)cdiv(blocks, 2) * 32;
+}
+
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
                                   const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s)
 {
     int R = T * G;
-    int RB = (int)cdiv(R, 16);
+    const int rows = attn_rows_padded(R);
+    const int RB = rows <= 16 ? 1 : 2, RG = rows / (RB * 16);
+    if (R > 256) { set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 256", R); return SPEC_EUNSUPPORTED; }
     float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-    dim3 grid((unsigned)Hkv, (unsigned)B, (unsigned)max_chunks);
+    dim3 grid((unsigned)(Hkv * RG), (unsigned)B, (unsigned)max_chunks);
     const float* qq = q;
-    switch (RB) {
-        case 1: attn_partial_kernel<1><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, part_o, part_ml); break;
-        case 2: attn_partial_kernel<2><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, part_o, part_ml); break;
-        default: set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 32", R); return SPEC_EUNSUPPORTED;
-    }
+    if (RB == 1) attn_partial_kernel<1><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, part_o, part_ml);
+    else attn_partial_kernel<2><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, part_o, part_ml);
     SPEC_LAUNCH_CHECK("attn_partial_kernel");
     prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);
-    attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, RB * 16, max_chunks, seq_ids, kv,
+    attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, rows, max_chunks, seq_ids, kv,
                                                                   mb_pad, (uint4*)xp_out);
     SPEC_LAUNCH_CHECK("attn_reduce_kernel");
     prof_mark(PC_ATTN_REDUCE, s);

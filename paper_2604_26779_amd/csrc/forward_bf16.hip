@@ -22,6 +22,7 @@ int gemm_pick_splits(const PackedW& W, int M, int forced);
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s);
 bool gemm_can_fuse_swiglu(int M, int splits);
 int attn_chunk_pages();
+int attn_rows_padded(int R);
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
                                   const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s);
@@ -209,7 +210,7 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.M = B * T;
     p.mb_pad = gemm_mb_pad(p.M);
     int G = d.n_q_heads / d.n_kv_heads;
-    p.RBrows = (int)cdiv(T * G, 16) * 16;
+    p.RBrows = attn_rows_padded(T * G);
     p.max_chunks = (int)cdiv(cdiv(max_ctx_plus, SPEC_PAGE_SIZE), attn_chunk_pages());
     if (p.max_chunks < 1) p.max_chunks = 1;
     p.s_qkv = gemm_pick_splits(m->wqkv[0], p.M, tune("splits_qkv"));
@@ -247,7 +248,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
 {
     const spec_model_desc& d = mdl->desc;
     const int T = k + 1, G = d.n_q_heads / d.n_kv_heads;
-    if (T * G > 32) { set_error("bf16 path: (k+1) * (query heads per kv head) = %d exceeds 32", T * G); return SPEC_EUNSUPPORTED; }
+    if (T * G > 256) { set_error("bf16 path: (k+1) * (query heads per kv head) = %d exceeds 256", T * G); return SPEC_EUNSUPPORTED; }
     // the workspace is laid out for the longest context the cache allows; the launch only spans
     // the chunks the current bound on the longest sequence needs
     Bf16Plan p = make_plan(mdl, B, k, (int64_t)kv->max_pages * SPEC_PAGE_SIZE);

@@ -263,10 +263,11 @@ def test_forward_argument_errors_and_pool_exhaustion():
     assert e.value.status == sv.SPEC_EUNSUPPORTED
 
 
-def _run_custom_bf16(ctx_list, k, seed=3, vocab=None):
+def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, **model_changes):
     """small_bf16 model, synthetic cache, explicit context lengths: returns (max err, worst over tolerance)."""
     from paper_2604_26779_amd.session import VerifySession
     cfg = dict(si.MODELS["small_bf16"])
+    cfg.update(model_changes)
     if vocab:
         cfg["vocab"] = vocab
     B = len(ctx_list)
@@ -317,4 +318,14 @@ def test_bf16_row_block_counts_and_multiple_row_tiles(B, k):
     ctx = [int(c) for c in rng.integers(3, 200, size=B)]
     ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000)
     print("B=%d k=%d (M=%d): logits max abs err %.3e" % (B, k, B * (k + 1), max_err))
+    assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("k,heads", [(15, (8, 2)), (3, (16, 1)), (2, (32, 2)), (11, (16, 2))])
+def test_bf16_more_than_32_query_rows_per_kv_head(k, heads):
+    """(k+1) * G = 64, 64, 48 and 96 query rows per kv head: the attention splits them into row groups of 32."""
+    rng = np.random.default_rng(k)
+    ctx = [int(c) for c in rng.integers(1, 700, size=4)] + [511, 0]
+    ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=k, vocab=1000, n_q_heads=heads[0], n_kv_heads=heads[1])
+    print("k=%d Hq/Hkv=%s: logits max abs err %.3e" % (k, heads, max_err))
     assert ok, (max_err, worst)
