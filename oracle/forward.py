@@ -18,6 +18,10 @@ Conventions of this build (the paper does not state them):
   * query head j uses key/value head j // (n_q_heads // n_kv_heads);
   * scores are scaled by 1/sqrt(head_dim); row i sees cache positions 0 .. ctx_len[b]+i;
   * silu(z) = z / (1 + exp(-z)); all projections are bias-free, weights are [out, in];
+  * mixture-of-experts feed-forward (cfg["n_experts"] > 0; the paper's 235B-A22B target, Section 3.1, is of this
+    kind): router logits r = h Wr^T, probabilities softmax(r) over all experts, the top_k most probable experts
+    (ties to the lower index) with their probabilities renormalised to sum to one, output = the weighted sum of
+    those experts' SwiGLU feed-forwards; every expert has its own gate, up and down matrices;
   * the cache stores keys and values in the model's storage type (cfg["dtype"]: "bf16", "f32", or
     "f64" for none) and attention reads what the cache stores: the keys and values of the k+1 input
     positions are rounded to that type (round to nearest even) before any row attends to them, so
@@ -70,7 +74,43 @@ def softmax(s):
     return e / np.sum(e)
 
 
-def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len):
+def moe_route(h, router, top_k):
+    """h [M, d], router [E, d] -> (experts [M, top_k] int, most probable first; weights [M, top_k] summing to one;
+    probabilities [M, E])."""
+    r = np.asarray(h, dtype=np.float64) @ np.asarray(router, dtype=np.float64).T
+    M, E = r.shape
+    prob = np.zeros((M, E))
+    experts = np.zeros((M, top_k), dtype=np.int64)
+    weight = np.zeros((M, top_k))
+    for m in range(M):
+        prob[m] = softmax(r[m])
+        left = prob[m].copy()
+        for j in range(top_k):
+            e = int(np.argmax(left))                # first maximum: ties go to the lower index
+            experts[m, j] = e
+            weight[m, j] = prob[m, e]
+            left[e] = -1.0
+        weight[m] /= np.sum(weight[m])
+    return experts, weight, prob
+
+
+def moe_ffn(h, w, top_k, route_log=None):
+    """Mixture-of-experts SwiGLU feed-forward of rows h [M, d]; w: router [E,d], wg/wu [E,F,d], wd [E,d,F]."""
+    h = np.asarray(h, dtype=np.float64)
+    experts, weight, prob = moe_route(h, w["router"], top_k)
+    if route_log is not None:
+        route_log.append((experts, weight, prob))
+    out = np.zeros_like(h)
+    for m in range(h.shape[0]):
+        for j in range(top_k):
+            e = experts[m, j]
+            gate = np.asarray(w["wg"][e], dtype=np.float64) @ h[m]
+            up = np.asarray(w["wu"][e], dtype=np.float64) @ h[m]
+            out[m] += weight[m, j] * (np.asarray(w["wd"][e], dtype=np.float64) @ (silu(gate) * up))
+    return out
+
+
+def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None):
     """One verify forward.
 
     cfg      dict: n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab,
@@ -80,6 +120,8 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len):
                    'final_norm' [d], 'head' [V,d] or None (tied to 'embed').
     kv_ctx   kv_ctx[layer][b] = (K [ctx_len[b], Hkv, dh], V [ctx_len[b], Hkv, dh]) cached context.
     tokens   [B, k+1] int, ctx_len [B] int.
+    Mixture-of-experts models (cfg n_experts, top_k > 0): every layer dict has 'router' [E,d] and stacked
+    wg, wu [E,F,d], wd [E,d,F]; route_log (a list) receives per layer (experts, weights, probabilities).
 
     Returns (logits [B,k+1,V] fp64, new_kv) with new_kv[layer] = (K [B,k+1,Hkv,dh], V [...]),
     the keys (after rotation) and values of the k+1 input positions as the cache stores them.
@@ -121,9 +163,12 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len):
         x = x + attn.reshape(B * T, Hq * dh) @ np.asarray(w["wo"], dtype=np.float64).T
 
         h = rmsnorm(x, w["ffn_norm"], eps)
-        gate = h @ np.asarray(w["wg"], dtype=np.float64).T
-        up = h @ np.asarray(w["wu"], dtype=np.float64).T
-        x = x + (silu(gate) * up) @ np.asarray(w["wd"], dtype=np.float64).T
+        if cfg.get("n_experts", 0) > 0:
+            x = x + moe_ffn(h, w, cfg["top_k"], route_log)
+        else:
+            gate = h @ np.asarray(w["wg"], dtype=np.float64).T
+            up = h @ np.asarray(w["wu"], dtype=np.float64).T
+            x = x + (silu(gate) * up) @ np.asarray(w["wd"], dtype=np.float64).T
 
     head = weights.get("head")
     head = embed if head is None else np.asarray(head, dtype=np.float64)

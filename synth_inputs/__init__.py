@@ -33,6 +33,14 @@ MODELS = {
     # Llama-3-8B-shaped (BASELINE config 1).
     "llama8b_bf16": dict(n_layers=32, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
                          vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0),
+    # Mixture-of-experts models: a small one for parity tests, and a 4-layer slice at the widths of a
+    # 235B-A22B-class target (BASELINE config 4): 64 query / 4 kv heads, 128 experts, top-8, expert width 1536.
+    "small_moe_bf16": dict(n_layers=2, d_model=512, n_q_heads=16, n_kv_heads=1, head_dim=128, ffn_dim=256, vocab=4000,
+                           rope_theta=1.0e6, rms_eps=1.0e-6, dtype="bf16", tied_head=0, n_experts=12, top_k=3,
+                           expert_ffn_dim=256),
+    "moe235b_slice_bf16": dict(n_layers=4, d_model=4096, n_q_heads=64, n_kv_heads=4, head_dim=128, ffn_dim=1536,
+                               vocab=151936, rope_theta=1.0e6, rms_eps=1.0e-6, dtype="bf16", tied_head=0, n_experts=128,
+                               top_k=8, expert_ffn_dim=1536),
     # Single-layer draft models (MTP-style: one decoder layer, output head tied to the embedding).
     "draft_tiny_fp32": dict(n_layers=1, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn_dim=704,
                             vocab=1024, rope_theta=1.0e4, rms_eps=1.0e-5, dtype="f32", tied_head=1),
@@ -59,6 +67,10 @@ WORKLOADS["draft_pair_small_b5_k4"] = dict(model="small_bf16", draft_model="draf
                                            ctx_hi=600, noise_std=0.0, temperature=0.9)
 WORKLOADS["draft_pair_tiny_b4_k3"] = dict(model="tiny_fp32", draft_model="draft_tiny_fp32", B=4, k=3, ctx_lo=100,
                                           ctx_hi=140, noise_std=0.0, temperature=1.0)
+# Mixture-of-experts verify slice (BASELINE config 4): B = 128, contexts uniform in [4096, 32768], k = 3.
+WORKLOADS["moe235b_slice_b128_ctx4k-32k_k3"] = dict(model="moe235b_slice_bf16", B=128, k=3, ctx_lo=4096, ctx_hi=32768,
+                                                    noise_std=1.0, temperature=1.0)
+WORKLOADS["small_moe_b6_k3"] = dict(model="small_moe_bf16", B=6, k=3, ctx_lo=5, ctx_hi=600, noise_std=1.0, temperature=1.0)
 # Large rollout batch (BASELINE config 2): B=256, contexts uniform in [2048, 16384], k swept.  The
 # cache of 32 distinct layers would not fit one GPU (309 GB on average), so layer l uses layer
 # pool l mod 8 (same bytes streamed per step, an eighth of the footprint); the draft noise of
@@ -84,10 +96,15 @@ def weight_shapes(cfg):
     d, Hq, Hkv, dh, F, V = (cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
                             cfg["ffn_dim"], cfg["vocab"])
     out = [("embed", (V, d))]
+    E = cfg.get("n_experts", 0)
     for l in range(cfg["n_layers"]):
         out += [(f"l{l}.attn_norm", (d,)), (f"l{l}.wq", (Hq * dh, d)), (f"l{l}.wk", (Hkv * dh, d)),
-                (f"l{l}.wv", (Hkv * dh, d)), (f"l{l}.wo", (d, Hq * dh)), (f"l{l}.ffn_norm", (d,)),
-                (f"l{l}.wg", (F, d)), (f"l{l}.wu", (F, d)), (f"l{l}.wd", (d, F))]
+                (f"l{l}.wv", (Hkv * dh, d)), (f"l{l}.wo", (d, Hq * dh)), (f"l{l}.ffn_norm", (d,))]
+        if E > 0:        # mixture of experts: stacked expert matrices, then the router
+            Fe = cfg["expert_ffn_dim"]
+            out += [(f"l{l}.wg", (E, Fe, d)), (f"l{l}.wu", (E, Fe, d)), (f"l{l}.wd", (E, d, Fe)), (f"l{l}.router", (E, d))]
+        else:
+            out += [(f"l{l}.wg", (F, d)), (f"l{l}.wu", (F, d)), (f"l{l}.wd", (d, F))]
     out.append(("final_norm", (d,)))
     if not cfg.get("tied_head", 0):
         out.append(("head", (V, d)))
@@ -102,6 +119,8 @@ def make_weights(cfg, seed=DEFAULT_SEED, device="cpu", std=0.02):
     for name, shape in weight_shapes(cfg):
         if name.endswith("norm"):
             weights[name] = torch.ones(shape, dtype=dt, device=device)
+        elif name.endswith("router"):          # router logits of a unit-RMS input ~ N(0, 1)
+            weights[name] = (torch.randn(shape, generator=g, device=device, dtype=torch.float32) / math.sqrt(shape[-1])).to(dt)
         else:
             weights[name] = (torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std).to(dt)
     return weights
@@ -112,9 +131,9 @@ def weights_for_oracle(cfg, weights):
     def f(name):
         return weights[name].detach().to("cpu", torch.float32).numpy()
     layers = []
+    names = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd") + (("router",) if cfg.get("n_experts", 0) > 0 else ())
     for l in range(cfg["n_layers"]):
-        layers.append({k: f(f"l{l}.{k}") for k in
-                       ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd")})
+        layers.append({k: f(f"l{l}.{k}") for k in names})
     return {"embed": f("embed"), "layers": layers, "final_norm": f("final_norm"),
             "head": None if cfg.get("tied_head", 0) else f("head")}
 
