@@ -47,19 +47,24 @@ const char* spec_last_error(void);
 
 /* ---------------------------------------------------------------- model ------------------------------------ */
 
-/* Plain data, copied by spec_model_create.  Dense pre-norm decoder: RMSNorm, grouped-query attention
- * with rotary embedding (pair j with j + head_dim/2, angle pos * rope_theta^(-2j/head_dim)), SwiGLU. */
+/* Plain data, copied by spec_model_create.  Pre-norm decoder: RMSNorm, grouped-query attention
+ * with rotary embedding (pair j with j + head_dim/2, angle pos * rope_theta^(-2j/head_dim)), SwiGLU
+ * feed-forward, dense or a routed mixture of experts (the 235B-A22B-class target of Section 3.1):
+ * router probabilities softmax(h Wr^T) over all experts, the top_k most probable experts (ties to the
+ * lower index), their probabilities renormalised to sum to one, output = weighted sum of those
+ * experts' SwiGLU feed-forwards of width expert_ffn_dim. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
     float rope_theta, rms_eps;
     int32_t dtype;             /* SPEC_F32 or SPEC_BF16: storage type of weights and of the KV cache */
     int32_t tied_head;         /* 1: output head = embedding matrix */
+    int32_t n_experts, top_k, expert_ffn_dim;   /* 0, 0, 0: dense feed-forward of width ffn_dim */
 } spec_model_desc;
 
 typedef struct spec_model spec_model;
 typedef struct spec_kv spec_kv;
 
-/* Number of weight pointers spec_model_create expects: 1 + 9*n_layers + 1 + (tied_head ? 0 : 1). */
+/* Number of weight pointers spec_model_create expects: 1 + (9 + (n_experts ? 1 : 0))*n_layers + 1 + (tied_head ? 0 : 1). */
 int32_t spec_model_weight_count(const spec_model_desc* desc);
 
 /*
@@ -67,13 +72,16 @@ int32_t spec_model_weight_count(const spec_model_desc* desc);
  *   embed [vocab, d_model];
  *   per layer: attn_norm [d], wq [Hq*dh, d], wk [Hkv*dh, d], wv [Hkv*dh, d], wo [d, Hq*dh],
  *              ffn_norm [d], wg [ffn, d], wu [ffn, d], wd [d, ffn];
+ *              with n_experts > 0 instead: wg [E, Fe, d], wu [E, Fe, d], wd [E, d, Fe] (the experts stacked,
+ *              Fe = expert_ffn_dim), then router [E, d];
  *   final_norm [d]; head [vocab, d] unless tied_head.
  * SPEC_F32: the pointers are borrowed for the model's lifetime (kernels read them in place).
  * SPEC_BF16: the matrices are re-tiled once into a library-owned device buffer laid out for the
  * MFMA kernels (one hipMalloc of about the model's size); afterwards only embed and the norm
  * gains are still read from the caller's buffers.  BF16 needs head_dim == 128,
- * d_model % 256 == 0, ffn_dim % 256 == 0 and n_q_heads % n_kv_heads == 0, else
- * SPEC_EUNSUPPORTED.
+ * d_model % 256 == 0, ffn_dim % 256 == 0 (expert_ffn_dim % 256 == 0, n_experts <= 256,
+ * 1 <= top_k <= min(n_experts, 16) for a mixture) and n_q_heads % n_kv_heads == 0, else
+ * SPEC_EUNSUPPORTED; the fp32 path is dense only.
  * Synchronises the device.  (Paper: the target model of Section 2.1; its shape is the caller's.)
  */
 spec_status spec_model_create(const spec_model_desc* desc, const void* const* dev_weights, int32_t n_weights,

@@ -39,7 +39,8 @@ class spec_model_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim",
                                               "ffn_dim", "vocab")] + \
                [("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("dtype", ctypes.c_int32),
-                ("tied_head", ctypes.c_int32)]
+                ("tied_head", ctypes.c_int32), ("n_experts", ctypes.c_int32), ("top_k", ctypes.c_int32),
+                ("expert_ffn_dim", ctypes.c_int32)]
 
 
 _lib = None
@@ -132,6 +133,7 @@ def make_desc(cfg):
     d.rope_theta, d.rms_eps = float(cfg["rope_theta"]), float(cfg["rms_eps"])
     d.dtype = {"f32": SPEC_F32, "bf16": SPEC_BF16}[cfg["dtype"]]
     d.tied_head = int(cfg.get("tied_head", 0))
+    d.n_experts, d.top_k, d.expert_ffn_dim = (int(cfg.get(n, 0)) for n in ("n_experts", "top_k", "expert_ffn_dim"))
     return d
 
 

@@ -57,7 +57,7 @@ void prof_record(int cls, hipStream_t s)
 
 static const char* const PROF_NAMES[PC_COUNT] = {
     "other", "embed_norm", "gemm_qkv", "qkv_rope", "attn", "attn_reduce", "gemm_o", "resid_norm", "gemm_gu", "swiglu",
-    "gemm_down", "gemm_head", "sample_stats", "sample_draw", "kv_reserve", "kv_commit", "draft_sample", "kv_truncate"};
+    "gemm_down", "gemm_head", "sample_stats", "sample_draw", "kv_reserve", "kv_commit", "draft_sample", "kv_truncate", "moe_route", "moe_gather"};
 
 }  // namespace specv
 
@@ -122,7 +122,7 @@ extern "C" int32_t spec_tune_get(const char* name)
 extern "C" int32_t spec_model_weight_count(const spec_model_desc* d)
 {
     if (!d || d->n_layers < 0) return -1;
-    return 1 + 9 * d->n_layers + 1 + (d->tied_head ? 0 : 1);
+    return 1 + (9 + (d->n_experts > 0 ? 1 : 0)) * d->n_layers + 1 + (d->tied_head ? 0 : 1);
 }
 
 static spec_status check_desc(const spec_model_desc& d)
@@ -134,6 +134,14 @@ static spec_status check_desc(const spec_model_desc& d)
     }
     if (d.n_q_heads % d.n_kv_heads) { set_error("spec_model_create: n_q_heads must be a multiple of n_kv_heads"); return SPEC_EUNSUPPORTED; }
     if (d.dtype != SPEC_F32 && d.dtype != SPEC_BF16) { set_error("spec_model_create: unknown dtype"); return SPEC_EINVAL; }
+    if (d.n_experts < 0 || d.top_k < 0 || d.expert_ffn_dim < 0) { set_error("spec_model_create: negative mixture-of-experts size"); return SPEC_EINVAL; }
+    if (d.n_experts > 0) {
+        if (d.dtype != SPEC_BF16) { set_error("spec_model_create: the fp32 path is dense only"); return SPEC_EUNSUPPORTED; }
+        if (d.n_experts > 256 || d.top_k < 1 || d.top_k > 16 || d.top_k > d.n_experts || d.expert_ffn_dim < 1 || d.expert_ffn_dim % 256) {
+            set_error("spec_model_create: mixture of experts needs n_experts <= 256, 1 <= top_k <= min(n_experts, 16), expert_ffn_dim %% 256 == 0");
+            return SPEC_EUNSUPPORTED;
+        }
+    }
     if (d.dtype == SPEC_BF16) {
         if (d.head_dim != 128 || d.d_model % 256 || d.ffn_dim % 256) {
             set_error("spec_model_create: the bf16 path needs head_dim == 128 and d_model, ffn_dim multiples of 256");
@@ -167,9 +175,11 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         const spec_model_desc& d = *desc;
         int L = d.n_layers, D = d.d_model, F = d.ffn_dim;
         int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim;
+        const int E = d.n_experts, Fe = d.expert_ffn_dim;
         size_t elems = 0;
-        elems += (size_t)L * (bf16_packed_elems(nq + 2 * nkv, D) + bf16_packed_elems(D, nq) + bf16_packed_elems(2 * F, D) +
-                              bf16_packed_elems(D, F));
+        elems += (size_t)L * (bf16_packed_elems(nq + 2 * nkv, D) + bf16_packed_elems(D, nq));
+        if (E > 0) elems += (size_t)L * ((size_t)E * (bf16_packed_elems(2 * Fe, D) + bf16_packed_elems(D, Fe)) + bf16_packed_elems(E, D));
+        else elems += (size_t)L * (bf16_packed_elems(2 * F, D) + bf16_packed_elems(D, F));
         elems += bf16_packed_elems(d.vocab, D);
         m->arena_bytes = elems * sizeof(bf16_t);
         hipError_t e = hipMalloc(&m->arena, m->arena_bytes);
@@ -179,7 +189,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
             return SPEC_ENOMEM;
         }
         bf16_t* at = (bf16_t*)m->arena;
-        m->wqkv.resize(L); m->wo.resize(L); m->wgu.resize(L); m->wd.resize(L);
+        m->wqkv.resize(L); m->wo.resize(L); m->wgu.resize(L); m->wd.resize(L); m->router.resize(L);
         auto pack = [&](std::initializer_list<const void*> parts, std::initializer_list<int> rows, int K, PackedW* pw, bool interleave = false) -> spec_status {
             std::vector<const bf16_t*> p;
             for (auto q : parts) p.push_back((const bf16_t*)q);
@@ -193,8 +203,21 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         for (int l = 0; l < L && st == SPEC_OK; ++l) {
             st = pack({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {nq, nkv, nkv}, D, &m->wqkv[l]);
             if (st == SPEC_OK) st = pack({m->layer_w(l, 4)}, {D}, nq, &m->wo[l]);
-            if (st == SPEC_OK) st = pack({m->layer_w(l, 6), m->layer_w(l, 7)}, {F, F}, D, &m->wgu[l], true);
-            if (st == SPEC_OK) st = pack({m->layer_w(l, 8)}, {D}, F, &m->wd[l]);
+            if (E > 0) {
+                // every expert re-tiled on its own, all experts of a matrix back to back (equal sizes)
+                const bf16_t *wg = (const bf16_t*)m->layer_w(l, 6), *wu = (const bf16_t*)m->layer_w(l, 7), *wdn = (const bf16_t*)m->layer_w(l, 8);
+                m->moe_gu_stride = (int64_t)bf16_packed_elems(2 * Fe, D);
+                m->moe_d_stride = (int64_t)bf16_packed_elems(D, Fe);
+                PackedW tmp;
+                for (int e = 0; e < E && st == SPEC_OK; ++e)
+                    st = pack({wg + (size_t)e * Fe * D, wu + (size_t)e * Fe * D}, {Fe, Fe}, D, e == 0 ? &m->wgu[l] : &tmp, true);
+                for (int e = 0; e < E && st == SPEC_OK; ++e)
+                    st = pack({wdn + (size_t)e * D * Fe}, {D}, Fe, e == 0 ? &m->wd[l] : &tmp);
+                if (st == SPEC_OK) st = pack({m->layer_w(l, 9)}, {E}, D, &m->router[l]);
+            } else {
+                if (st == SPEC_OK) st = pack({m->layer_w(l, 6), m->layer_w(l, 7)}, {F, F}, D, &m->wgu[l], true);
+                if (st == SPEC_OK) st = pack({m->layer_w(l, 8)}, {D}, F, &m->wd[l]);
+            }
         }
         if (st == SPEC_OK) st = pack({m->head_w()}, {d.vocab}, D, &m->head);
         if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }

@@ -18,7 +18,7 @@ int tune(const char* name);
 enum ProfClass {
     PC_OTHER = 0, PC_EMBED_NORM, PC_GEMM_QKV, PC_QKV_ROPE, PC_ATTN, PC_ATTN_REDUCE, PC_GEMM_O, PC_RESID_NORM,
     PC_GEMM_GU, PC_SWIGLU, PC_GEMM_DOWN, PC_GEMM_HEAD, PC_SAMPLE_STATS, PC_SAMPLE_DRAW, PC_KV_RESERVE, PC_KV_COMMIT,
-    PC_DRAFT_SAMPLE, PC_KV_TRUNCATE, PC_COUNT
+    PC_DRAFT_SAMPLE, PC_KV_TRUNCATE, PC_MOE_ROUTE, PC_MOE_GATHER, PC_COUNT
 };
 extern bool g_prof_on;
 void prof_record(int cls, hipStream_t s);
@@ -77,12 +77,16 @@ struct spec_model {
     // bf16 path: packed matrices in one arena
     void* arena = nullptr;
     size_t arena_bytes = 0;
-    std::vector<specv::PackedW> wqkv, wo, wgu, wd;
+    std::vector<specv::PackedW> wqkv, wo, wgu, wd;   // mixture of experts: wgu / wd describe expert 0, the
+    std::vector<specv::PackedW> router;              // others follow at moe_gu_stride / moe_d_stride elements
+    int64_t moe_gu_stride = 0, moe_d_stride = 0;
     specv::PackedW head;
+    bool moe() const { return desc.n_experts > 0; }
+    int per_layer() const { return moe() ? 10 : 9; }
     const void* embed() const { return w[0]; }
-    const void* layer_w(int l, int i) const { return w[1 + 9 * l + i]; }   // i: 0 attn_norm .. 8 wd
-    const void* final_norm() const { return w[1 + 9 * desc.n_layers]; }
-    const void* head_w() const { return desc.tied_head ? w[0] : w[2 + 9 * desc.n_layers]; }
+    const void* layer_w(int l, int i) const { return w[1 + per_layer() * l + i]; }   // i: 0 attn_norm .. 8 wd, 9 router
+    const void* final_norm() const { return w[1 + per_layer() * desc.n_layers]; }
+    const void* head_w() const { return desc.tied_head ? w[0] : w[2 + per_layer() * desc.n_layers]; }
 };
 
 struct spec_kv {

@@ -23,6 +23,15 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
 bool gemm_can_fuse_swiglu(int M, int splits);
 int attn_chunk_pages();
 int attn_rows_padded(int R);
+int moe_rows_bound(int M, int top_k, int E);
+spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, const bf16_t* Xp, int rows_pad, int max_tiles,
+                                     const int32_t* tiles, float* out, int ldo, bool swiglu, hipStream_t s);
+spec_status launch_moe_route(const float* part, int splits, int64_t split_stride, int M, int E, int top_k, int32_t* ids, float* wts,
+                             int32_t* row0, int32_t* tiles, int32_t* src_row, int32_t* pair_row, hipStream_t s);
+spec_status launch_moe_gather(const bf16_t* xp_src, int mb_pad_src, const int32_t* src_row, const int32_t* row0, int E, int d,
+                              int rows_bound, bf16_t* xp_dst, hipStream_t s);
+spec_status launch_moe_combine_norm(float* x, const float* y, const int32_t* pair_row, const float* wts, int M, int top_k,
+                                    const void* gain, int d, float eps, int mb_pad, bf16_t* xp, hipStream_t s);
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
                                   const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s);
@@ -200,6 +209,9 @@ struct Bf16Plan {
     bool fuse_swiglu;
     int s_qkv, s_o, s_gu, s_down, s_head;
     size_t off_x, off_xp_h, off_xp_a, off_xp_f, off_part, off_q, off_rope, off_att_o, off_att_ml, total;
+    // mixture of experts: padded-row bound, router splits, routing tables, permuted activations, expert outputs
+    int moe_rows, s_router;
+    size_t off_ids, off_wts, off_row0, off_tiles, off_src_row, off_pair_row, off_xp_e, off_y_e;
 };
 
 static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plus)
@@ -215,20 +227,35 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     if (p.max_chunks < 1) p.max_chunks = 1;
     p.s_qkv = gemm_pick_splits(m->wqkv[0], p.M, tune("splits_qkv"));
     p.s_o = gemm_pick_splits(m->wo[0], p.M, tune("splits_o"));
-    p.fuse_swiglu = tune("fuse_swiglu") != 0 && gemm_can_fuse_swiglu(p.M, 1);
-    p.s_gu = p.fuse_swiglu ? 1 : gemm_pick_splits(m->wgu[0], p.M, tune("splits_gu"));
-    p.s_down = gemm_pick_splits(m->wd[0], p.M, tune("splits_down"));
+    const bool moe = m->moe();
+    p.fuse_swiglu = !moe && tune("fuse_swiglu") != 0 && gemm_can_fuse_swiglu(p.M, 1);
+    p.s_gu = (p.fuse_swiglu || moe) ? 1 : gemm_pick_splits(m->wgu[0], p.M, tune("splits_gu"));
+    p.s_down = moe ? 1 : gemm_pick_splits(m->wd[0], p.M, tune("splits_down"));
     p.s_head = 1;
-    int D = d.d_model, F = d.ffn_dim, nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
+    p.s_router = moe ? gemm_pick_splits(m->router[0], p.M, 0) : 0;
+    p.moe_rows = moe ? moe_rows_bound(p.M, d.top_k, d.n_experts) : 0;
+    int D = d.d_model, F = moe ? d.expert_ffn_dim : d.ffn_dim, nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
     size_t rows = (size_t)p.mb_pad * 32;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     p.off_x = take((size_t)p.M * D * 4);
     p.off_xp_h = take(rows * D * 4);          // hi + lo
     p.off_xp_a = take(rows * nq * 4);
-    p.off_xp_f = take(rows * F * 4);
+    p.off_xp_f = take((moe ? (size_t)p.moe_rows : rows) * F * 4);     // mixture: the permuted rows' silu(gate)*up
     size_t part = std::max(std::max((size_t)p.s_qkv * nqkv, (size_t)p.s_o * D), std::max((size_t)p.s_gu * 2 * F, (size_t)p.s_down * D));
+    if (moe) part = std::max(std::max((size_t)p.s_qkv * nqkv, (size_t)p.s_o * D), (size_t)p.s_router * d.n_experts);
     p.off_part = take(part * p.M * 4);
+    if (moe) {
+        size_t pairs = (size_t)p.M * d.top_k;
+        p.off_ids = take(pairs * 4);
+        p.off_wts = take(pairs * 4);
+        p.off_pair_row = take(pairs * 4);
+        p.off_row0 = take((size_t)(d.n_experts + 1) * 4);
+        p.off_tiles = take((size_t)(1 + 2 * (p.moe_rows / 64)) * 4);
+        p.off_src_row = take((size_t)p.moe_rows * 4);
+        p.off_xp_e = take((size_t)p.moe_rows * D * 4);
+        p.off_y_e = take((size_t)p.moe_rows * D * 4);
+    }
     p.off_q = take((size_t)p.M * nq * 4);
     p.off_rope = take((size_t)p.M * (d.head_dim / 2) * 8);
     size_t items = (size_t)B * d.n_kv_heads * p.max_chunks;
@@ -290,6 +317,32 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)mdl->layer_w(l, 5), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
+        const void* next_gain = l + 1 < d.n_layers ? mdl->layer_w(l + 1, 0) : mdl->final_norm();
+        if (mdl->moe()) {
+            // router -> top-k -> rows permuted into per-expert tiles -> grouped gate/up (SwiGLU fused) and down
+            // projections over the tile list -> weighted combine + residual + next RMSNorm
+            const int E = d.n_experts, Fe = d.expert_ffn_dim, max_tiles = p.moe_rows / 64;
+            int32_t* ids = (int32_t*)(base + p.off_ids);
+            float* wts = (float*)(base + p.off_wts);
+            int32_t* pair_row = (int32_t*)(base + p.off_pair_row);
+            int32_t* row0 = (int32_t*)(base + p.off_row0);
+            int32_t* tiles = (int32_t*)(base + p.off_tiles);
+            int32_t* src_row = (int32_t*)(base + p.off_src_row);
+            bf16_t* xp_e = (bf16_t*)(base + p.off_xp_e);
+            float* y_e = (float*)(base + p.off_y_e);
+            if ((st = launch_gemm_bf16(mdl->router[l], xp_h, M, part, E, p.s_router, false, s)) != SPEC_OK) return st;
+            if ((st = launch_moe_route(part, p.s_router, (int64_t)M * E, M, E, d.top_k, ids, wts, row0, tiles, src_row, pair_row, s)) != SPEC_OK) return st;
+            prof_mark(PC_MOE_ROUTE, s);
+            if ((st = launch_moe_gather(xp_h, p.mb_pad, src_row, row0, E, D, p.moe_rows, xp_e, s)) != SPEC_OK) return st;
+            prof_mark(PC_MOE_GATHER, s);
+            if ((st = launch_gemm_bf16_grouped(mdl->wgu[l], mdl->moe_gu_stride, xp_e, p.moe_rows, max_tiles, tiles, (float*)xp_f, 2 * Fe, true, s)) != SPEC_OK) return st;
+            prof_mark(PC_GEMM_GU, s);
+            if ((st = launch_gemm_bf16_grouped(mdl->wd[l], mdl->moe_d_stride, xp_f, p.moe_rows, max_tiles, tiles, y_e, D, false, s)) != SPEC_OK) return st;
+            prof_mark(PC_GEMM_DOWN, s);
+            if ((st = launch_moe_combine_norm(x, y_e, pair_row, wts, M, d.top_k, next_gain, D, d.rms_eps, p.mb_pad, xp_h, s)) != SPEC_OK) return st;
+            prof_mark(PC_RESID_NORM, s);
+            continue;
+        }
         if (p.fuse_swiglu) {
             // gate/up projection with silu(gate) * up in its epilogue: writes the down projection's operand
             if ((st = launch_gemm_bf16(mdl->wgu[l], xp_h, M, (float*)xp_f, 2 * F, 1, true, s)) != SPEC_OK) return st;
@@ -302,7 +355,6 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         }
         if ((st = launch_gemm_bf16(mdl->wd[l], xp_f, M, part, D, p.s_down, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_DOWN, s);
-        const void* next_gain = l + 1 < d.n_layers ? mdl->layer_w(l + 1, 0) : mdl->final_norm();
         residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);

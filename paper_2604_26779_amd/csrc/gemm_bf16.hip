@@ -106,10 +106,14 @@ spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_row
 // along the columns.  A wavefront owns MB/WM row blocks and WM column blocks (the tile is always 128
 // columns), so with WM = 2 every activation fragment read from LDS feeds two MFMAs and every weight
 // fragment is read by two wavefronts (the second read hits the CU's L1): half the LDS traffic per MFMA.
-template <int MB, int WM, int WD, int EPI>
+// GROUPED (mixture of experts): blockIdx.z walks a device-side list of row tiles, tiles[0] = number of
+// tiles, then (group, first row block) pairs; group g multiplies by the matrix at Wp + g * w_group_stride
+// (all groups have the same shape).  Tiles past the list's end exit at once.
+template <int MB, int WM, int WD, int EPI, bool GROUPED = false>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
     const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
-    int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride)
+    int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride,
+    const int32_t* __restrict__ tiles = nullptr, int64_t w_group_stride = 0)
 {
     constexpr int KS = GEMM_KS;
     constexpr int MBW = MB / WM, NBW = WM;
@@ -125,7 +129,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
     int ks1 = ks0 + ksteps_per_split;
     if (ks1 > k_steps) ks1 = k_steps;
     const int n_slabs = (ks1 - ks0) / KS;
-    const int mt = blockIdx.z;
+    int mblk0 = blockIdx.z * MB;                        // first 32-row block of this tile
+    if constexpr (GROUPED) {
+        if ((int)blockIdx.z >= tiles[0]) return;
+        Wp += (int64_t)tiles[1 + 2 * blockIdx.z] * w_group_stride;
+        mblk0 = tiles[2 + 2 * blockIdx.z];
+    }
 
     // slab s of column block j of this wavefront: wptr[j] + s * wslab
     const u32x4_t* wptr[NBW];
@@ -133,7 +142,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
     for (int j = 0; j < NBW; ++j)
         wptr[j] = Wp + (((int64_t)(ks0 / KS) * n_blocks + (nb0 + j < n_blocks ? nb0 + j : 0)) * KS) * 64 + lane;
     const int64_t wslab = (int64_t)n_blocks * KS * 64;
-    const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mt * MB) * 128;
+    const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mblk0) * 128;
 
     f32x16_t acc[MBW][NBW];
 #pragma unroll
@@ -235,7 +244,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
         uint4* xo = (uint4*)out;
         for (int e = threadIdx.x; e < MB * 32 * 8; e += GEMM_THREADS) {
             int row = e >> 3, g8 = e & 7;
-            int m = mt * MB * 32 + row, f = blockIdx.x * 64 + g8 * 8;
+            int m = mblk0 * 32 + row, f = blockIdx.x * 64 + g8 * 8;
             if (m >= M || f >= N / 2) continue;
             float v[8];
 #pragma unroll
@@ -253,7 +262,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
         for (int i = 0; i < MBW; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                int m = (mt * MB + mh * MBW + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                int m = (mblk0 + mh * MBW + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (m < M) o[(int64_t)m * ldo + n] = acc[i][j][r];
             }
     }
@@ -299,6 +308,27 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
     }
 #undef SPEC_GEMM_LAUNCH
     SPEC_LAUNCH_CHECK("gemm_bf16_kernel");
+    return SPEC_OK;
+}
+
+// Grouped GEMM over a device-side tile list (see the kernel): 64-row tiles, group g uses the matrix g *
+// group_stride elements after W0; Xp and the output cover rows_pad rows (a multiple of 64).  With swiglu
+// the output is the hi + lo operand buffer of silu(gate) * up (rows_pad / 32 row blocks per k-step).
+spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, const bf16_t* Xp, int rows_pad, int max_tiles,
+                                     const int32_t* tiles, float* out, int ldo, bool swiglu, hipStream_t s)
+{
+    if (rows_pad % 64 || max_tiles < 1 || W0.k_steps % GEMM_KUNIT) { set_error("grouped gemm: bad shape"); return SPEC_EINVAL; }
+    dim3 grid((unsigned)cdiv(W0.n_blocks, 4), 1, (unsigned)max_tiles);
+    const u32x4_t* wp = (const u32x4_t*)W0.data;
+    const u32x4_t* xp = (const u32x4_t*)Xp;
+    const int64_t stride16 = group_stride / 8;             // in 16-byte words
+    if (swiglu)
+        gemm_bf16_kernel<2, 2, 2, GEMM_EPI_SWIGLU, true><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W0.n_blocks, W0.k_steps, W0.k_steps,
+                                                                                       rows_pad / 32, rows_pad, W0.N, ldo, 0, tiles, stride16);
+    else
+        gemm_bf16_kernel<2, 2, 2, GEMM_EPI_PLAIN, true><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W0.n_blocks, W0.k_steps, W0.k_steps,
+                                                                                      rows_pad / 32, rows_pad, W0.N, ldo, 0, tiles, stride16);
+    SPEC_LAUNCH_CHECK("gemm_bf16_kernel (grouped)");
     return SPEC_OK;
 }
 
