@@ -181,7 +181,7 @@ def main():
     alg = algorithmic_bytes(wl.cfg, wl.ctx_len, B, k)
     gemm_ms = sum(per_step[n] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head"))
     gemm_launches = sum(launches[n] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head"))
-    gemm_flops = 2.0 * (alg["gemm"] / 2) * B * (k + 1)          # 2 flop per weight per position (bf16 weights)
+    gemm_flops = alg["gemm_flops"]                              # 2 flop per weight an input row meets, per position
     classes = {
         "gemm_bf16_kernel": dict(ms=gemm_ms, launches=gemm_launches, bytes=alg["gemm"], flops=gemm_flops),
         "attn_partial_kernel": dict(ms=per_step["attn"], launches=launches["attn"], bytes=alg["attn"], flops=0.0),

@@ -86,9 +86,16 @@ def algorithmic_bytes(cfg, ctx_len, B, k):
     nq, nkv = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
     eb = 2 if cfg["dtype"] == "bf16" else 4
     layer_w = (nq + 2 * nkv) * D + D * nq + 2 * F * D + D * F
+    if cfg.get("n_experts", 0) > 0:          # every expert's matrices are touched once the batch is a few dozen rows
+        E, Fe = cfg["n_experts"], cfg["expert_ffn_dim"]
+        layer_w = (nq + 2 * nkv) * D + D * nq + E * 3 * Fe * D + E * D
     head_w = V * D
+    active_w = layer_w                         # matrix entries one input row multiplies with, per layer
+    if cfg.get("n_experts", 0) > 0:
+        active_w = (nq + 2 * nkv) * D + D * nq + cfg["top_k"] * 3 * cfg["expert_ffn_dim"] * D + cfg["n_experts"] * D
     tokens = int(np.sum(ctx_len)) + B * (k + 1)
     return dict(
+        gemm_flops=2.0 * (L * active_w + head_w) * B * (k + 1),
         gemm=(L * layer_w + head_w) * eb,
         gemm_layers=L * layer_w * eb,
         gemm_head=head_w * eb,

@@ -22,12 +22,12 @@ from tests.helpers import logits_close
 
 pytestmark = pytest.mark.gpu
 
-def _check_workload(name, ks):
+def _check_workload(name, ks, moe_margin=None):
     from paper_2604_26779_amd.workloads import DeviceWorkload
     wl = DeviceWorkload(name)
     cfg, B = wl.cfg, wl.B
     rng = np.random.default_rng(123)
-    picks = sorted({int(np.argmin(wl.ctx_len)), int(np.argmax(wl.ctx_len))})
+    picks = sorted({int(np.argmin(wl.ctx_len)), int(np.argmax(wl.ctx_len))} | ({3, 17, 40, 99} if moe_margin is not None else set()))
     weights = si.make_weights(cfg, seed=wl.seed, device="cuda")           # the generator's weights again, for the oracle
     w_or = si.weights_for_oracle(cfg, weights)
     del weights
@@ -41,8 +41,20 @@ def _check_workload(name, ks):
         torch.cuda.synchronize()
         assert torch.isfinite(logits).all()
         print(name, "k=%d: oracle on sequences" % k, picks, "contexts", [int(wl.ctx_len[b]) for b in picks], flush=True)
-        want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks])
+        log = []
+        want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks], route_log=log)
         got = logits[picks].cpu().numpy()
+        if moe_margin is not None:
+            # rows whose expert choice the oracle decides by less than the margin (and the rows after them in the
+            # sequence) may legitimately differ: counted, reported, left out of the comparison
+            fragile = np.zeros((len(picks), k + 1), dtype=bool)
+            for experts, weight, prob in log:
+                srt = np.sort(np.log(prob), axis=-1)[:, ::-1]
+                fragile |= ((srt[:, cfg["top_k"] - 1] - srt[:, cfg["top_k"]]) < moe_margin).reshape(len(picks), k + 1)
+            keep = ~np.logical_or.accumulate(fragile, axis=1)
+            print("  rows exempted for routing margins: %d of %d" % ((~keep).sum(), keep.size), flush=True)
+            assert keep.sum() >= keep.size // 2
+            got, want = got[keep], want[keep]
         ok, max_err, worst = logits_close(got, want, 2e-2, 1e-2)
         print("  logits max abs err %.3e, |logit| max %.2f" % (max_err, np.abs(want).max()), flush=True)
         assert ok, (max_err, worst)
@@ -78,3 +90,8 @@ def test_llama8b_logits_on_sampled_sequences_and_commit():
 
 def test_llama8b_large_batch_aliased_pool_k7_and_k1():
     _check_workload("llama8b_b256_ctx2k-16k_k7", [7, 1])
+
+
+def test_moe_slice_full_size():
+    """4 mixture-of-experts layers at 235B-A22B widths (128 experts, top-8), B = 128, contexts 4096..32768, k = 3."""
+    _check_workload("moe235b_slice_b128_ctx4k-32k_k3", [3], moe_margin=1e-3)
