@@ -178,14 +178,24 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
         const int s_w = s + WD < n_slabs ? s + WD : n_slabs - 1;
         const int s_x = s + 1 < n_slabs ? s + 1 : n_slabs - 1;
         load_x(s_x);
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) {
-            u32x4_t a[MBW][2];
+        // keep these loads HERE: left alone, the scheduler sinks them to the end of the slab, next to the LDS
+        // stores that consume them, and the whole round trip to L2 is then paid once per slab
+        __builtin_amdgcn_sched_barrier(0);
+        // LDS reads run one k-step ahead of the MFMAs that use them (two register sets): with one or two
+        // wavefronts per SIMD nothing else would hide the LDS latency.  The scheduling barriers keep that order.
+        u32x4_t a[2][MBW][2];
+        auto read_a = [&](int set, int kk) {
 #pragma unroll
             for (int i = 0; i < MBW; ++i)
 #pragma unroll
                 for (int part = 0; part < 2; ++part)
-                    a[i][part] = lds[buf * SLAB + ((kk * MB + mh * MBW + i) * 2 + part) * 64 + lane];
+                    a[set][i][part] = lds[buf * SLAB + ((kk * MB + mh * MBW + i) * 2 + part) * 64 + lane];
+        };
+        read_a(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            if (kk + 1 < KS) read_a((kk + 1) & 1, kk + 1);
+            __builtin_amdgcn_sched_barrier(0);
             // hi products of all blocks first, then the lo products: two MFMAs on one accumulator are never adjacent
 #pragma unroll
             for (int part = 0; part < 2; ++part)
@@ -193,11 +203,15 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
                 for (int i = 0; i < MBW; ++i)
 #pragma unroll
                     for (int j = 0; j < NBW; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[i][part]),
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[kk & 1][i][part]),
                                                                             __builtin_bit_cast(bf16x8_t, w[SLOT][kk][j]), acc[i][j], 0, 0, 0);
 #pragma unroll
             for (int j = 0; j < NBW; ++j) w[SLOT][kk][j] = __builtin_nontemporal_load(wptr[j] + (int64_t)s_w * wslab + kk * 64);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // ... and the weight loads of this slab stay above the LDS stores, so that waiting for the (older)
+        // activation loads does not drain the weight stream
+        __builtin_amdgcn_sched_barrier(0);
         store_x(buf ^ 1);
         __syncthreads();
         buf ^= 1;
