@@ -283,7 +283,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
 }
 
 // rows of the activation buffer are padded to whole tiles of MB 32-row blocks
-int gemm_mb(int M) { int mb = (int)cdiv(M, 32); return mb > 4 ? 4 : mb; }
+int gemm_mb(int M) { int mb = (int)cdiv(M, 32), cap = tune("gemm_max_mb"); cap = cap < 1 ? 1 : (cap > 4 ? 4 : cap); return mb > cap ? cap : mb; }
 int gemm_mb_pad(int M) { int mb = gemm_mb(M); return (int)cdiv(cdiv(M, 32), mb) * mb; }
 
 int gemm_pick_splits(const PackedW& W, int M, int forced)
