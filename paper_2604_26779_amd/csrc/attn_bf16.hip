@@ -41,17 +41,22 @@ constexpr int BLOCK_U4 = SPEC_PAGE_SIZE * DH * 2 / 16;   // 256 16-byte words pe
 // part_o : [item][rows][128] fp32, part_ml : [item][rows][2] (max in log2 domain, sum); rows = RG*RB*16
 // item = (b * Hkv + kvh) * max_chunks + chunk
 // More than 32 query rows per kv head (deep drafts, or many query heads per kv head) are split into RG row
-// groups of RB*16 rows, one workgroup each (blockIdx.x = kvh * RG + row group): the groups of a chunk are
-// dispatched back to back and re-read the same pages through the caches.
+// groups of RB*16 rows, one workgroup each.  The row groups of a (batch entry, kv head, chunk) re-read the same
+// pages, so they are placed on the same XCD (workgroups go to XCDs round-robin by linear id: blockIdx.x spans
+// a multiple of 8 values - kv head and the low bits of the batch index - and the row group sits in
+// blockIdx.y, 8 ids apart) and next to each other in dispatch order: the second read hits that XCD's L2.
 template <int RB>
 __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
-    int layer_pool, float scale_log2, int max_chunks, int RG, float* __restrict__ part_o, float* __restrict__ part_ml)
+    int layer_pool, float scale_log2, int max_chunks, int RG, int Hkv, int BP, int B, float* __restrict__ part_o,
+    float* __restrict__ part_ml)
 {
     // chunk is the slowest grid dimension: the first chunks (every sequence has them) are dispatched first,
     // the chunks only long sequences have - and the empty workgroups of the short ones - last
-    const int kvh = blockIdx.x / RG, rb0 = (blockIdx.x % RG) * RB, b = blockIdx.y, chunk = blockIdx.z;
-    const int Hkv = gridDim.x / RG;
+    // blockIdx.x = kvh + Hkv * (b % BP), blockIdx.y = row group + RG * (b / BP)
+    const int kvh = blockIdx.x % Hkv, rb0 = (blockIdx.y % RG) * RB, chunk = blockIdx.z;
+    const int b = (blockIdx.y / RG) * BP + blockIdx.x / Hkv;
+    if (b >= B) return;
     const int seq = seq_ids[b];
     const int ctx = kv.ctx_len[seq];
     int total = ctx + T;
@@ -315,10 +320,12 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
     const int RB = rows <= 16 ? 1 : 2, RG = rows / (RB * 16);
     if (R > 256) { set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 256", R); return SPEC_EUNSUPPORTED; }
     float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-    dim3 grid((unsigned)(Hkv * RG), (unsigned)B, (unsigned)max_chunks);
+    int BP = 1;                                   // batch entries folded into blockIdx.x so that it spans a multiple of 8
+    while ((Hkv * BP) % 8 != 0) BP *= 2;
+    dim3 grid((unsigned)(Hkv * BP), (unsigned)(RG * cdiv(B, BP)), (unsigned)max_chunks);
     const float* qq = q;
-    if (RB == 1) attn_partial_kernel<1><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, part_o, part_ml);
-    else attn_partial_kernel<2><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, part_o, part_ml);
+    if (RB == 1) attn_partial_kernel<1><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, Hkv, BP, B, part_o, part_ml);
+    else attn_partial_kernel<2><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, Hkv, BP, B, part_o, part_ml);
     SPEC_LAUNCH_CHECK("attn_partial_kernel");
     prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);
