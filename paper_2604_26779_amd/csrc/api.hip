@@ -27,7 +27,7 @@ static std::map<std::string, int>& tune_table()
 {
     // launch parameters with their defaults; see gemm_bf16.hip / attn_bf16.hip for their meaning
     static std::map<std::string, int> t = {
-        {"gemm_wg_target", 512},   // split K while a GEMM launches fewer workgroups than this
+        {"gemm_wg_target", 256},   // split K while a GEMM launches fewer workgroups than this
         {"fuse_swiglu", 1},        // 1: silu(gate) * up in the gate/up projection's epilogue (unsplit K, even row blocks)
         {"gemm_max_mb", 4},        // 32-row blocks per GEMM tile (1..4): smaller tiles = more workgroups, weights read once per tile
         {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
