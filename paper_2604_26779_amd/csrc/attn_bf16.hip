@@ -317,7 +317,11 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
 {
     int R = T * G;
     const int rows = attn_rows_padded(R);
-    const int RB = rows <= 16 ? 1 : 2, RG = rows / (RB * 16);
+    // 17..32 rows: one workgroup with two 16-row blocks per wavefront (one workgroup per CU); more rows: groups of
+    // 16 rows at two workgroups per CU, which measured 1.6x faster at 64 rows than groups of 32
+    const int forced = tune("attn_row_blocks");
+    const int RB = forced == 1 || forced == 2 ? (rows <= 16 ? 1 : forced) : (rows > 16 && rows <= 32 ? 2 : 1);
+    const int RG = rows / (RB * 16);
     if (R > 256) { set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 256", R); return SPEC_EUNSUPPORTED; }
     float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
     int BP = 1;                                   // batch entries folded into blockIdx.x so that it spans a multiple of 8
