@@ -45,3 +45,45 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
         q[:, i, :] = qi
         feed = x.reshape(B, 1)
     return drafts, q, kv, ctx_len, keys
+
+
+def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperature, seed, n_steps):
+    """Several speculation steps in a row (the decode phase of a rollout, Section 2.1-2.2): every step drafts k
+    tokens with the draft model, verifies them with the target, keeps the accepted prefix and emits one more
+    token, which is the first input of the next step.
+
+    kv_t / kv_d: cached context of target (ctx_len[b] positions) and draft (ctx_len[b] - 1 positions: it lacks
+    `prev`, the last input the target has cached); t0 [B]: the last emitted token (cached by neither).
+    Random numbers: step s uses counter word `step = s`.
+
+    Returns (history, kv_t, kv_d, ctx_len) with history[s] = dict(drafts [B,k], accept_len [B], out_tokens [B,k+1]);
+    the caches hold what each model keeps after the last step (target: ctx_len positions, draft: ctx_len - 1).
+    """
+    from . import sampler as _s
+    B = len(t0)
+    ctx_len = np.asarray(ctx_len, dtype=np.int64).copy()
+    prev = np.asarray(prev, dtype=np.int32).copy()
+    t0 = np.asarray(t0, dtype=np.int32).copy()
+    kv_t = [[(np.asarray(K, dtype=np.float64), np.asarray(V, dtype=np.float64)) for (K, V) in per] for per in kv_t]
+    kv_d = [[(np.asarray(K, dtype=np.float64), np.asarray(V, dtype=np.float64)) for (K, V) in per] for per in kv_d]
+    history = []
+    for s in range(n_steps):
+        pending = np.stack([prev, t0], axis=1)
+        drafts, q, kv_d_grown, _, _ = draft_loop(cfg_d, w_d, kv_d, pending, ctx_len - 1, k, temperature, seed, s)
+        tokens = np.concatenate([t0[:, None], drafts], axis=1).astype(np.int32)
+        logits, new_kv = _forward.verify_forward(cfg_t, w_t, kv_t, tokens, ctx_len)
+        n, out = _s.reject_sample(logits.astype(np.float32), q, drafts, temperature, seed, s)
+        history.append(dict(drafts=drafts, accept_len=n.copy(), out_tokens=out.copy(), tokens=tokens))
+        for b in range(B):
+            keep = int(n[b]) + 1                                   # inputs 0..n stay in the target's cache
+            for layer in range(cfg_t["n_layers"]):
+                K, V = kv_t[layer][b]
+                kv_t[layer][b] = (np.concatenate([K, new_kv[layer][0][b][:keep]]), np.concatenate([V, new_kv[layer][1][b][:keep]]))
+            new_len = int(ctx_len[b]) + keep
+            for layer in range(cfg_d["n_layers"]):                 # the draft keeps one position less than the target
+                K, V = kv_d_grown[layer][b]
+                kv_d[layer][b] = (K[:new_len - 1], V[:new_len - 1])
+            prev[b] = tokens[b, n[b]]
+            t0[b] = out[b, n[b]]
+            ctx_len[b] = new_len
+    return history, kv_t, kv_d, ctx_len

@@ -145,3 +145,45 @@ def test_truncate_against_set_model_and_against_smaller_commit():
     assert book.free[-2:] == [6, 5]
     assert book.truncate(["b", "a"], [0, 17]) == [0, 17]
     assert book.pages["b"] == [] and book.pages["a"] == [1, 2] and book.free[-2:] == [4, 3]
+
+
+def test_rollout_over_several_steps_keeps_consistent_caches():
+    """Three speculation steps in a row: lengths add up, the kept tokens re-fed as one causal pass reproduce both
+    caches (a wrongly kept or dropped position, or a stale draft cache after roll-back, fails this), a draft that
+    is the target itself gets everything accepted, and the run is deterministic."""
+    cfg_t = dict(CFG, n_layers=2, tied_head=1)
+    cfg_d = CFG
+    w_t, w_d = _weights(cfg_t, seed=11), _weights(cfg_d, seed=12)
+    rng = np.random.default_rng(13)
+    B, C, k, T, S = 3, 6, 3, 1.0, 3
+    string = rng.integers(0, cfg_t["vocab"], size=(B, C + 1)).astype(np.int32)      # C cached tokens, then t0
+    kv_t = of.prefill(cfg_t, w_t, string[:, :C])
+    kv_d = of.prefill(cfg_d, w_d, string[:, :C - 1])
+    hist, kv_t2, kv_d2, ctx = od.rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, string[:, C - 1], string[:, C], np.full(B, C), k, T, 5, S)
+    assert len(hist) == S
+    total = np.zeros(B, dtype=int)
+    kept = [list(string[b]) for b in range(B)]                                       # ..., t0
+    for h in hist:
+        n, out = h["accept_len"], h["out_tokens"]
+        assert np.all((0 <= n) & (n <= k))
+        for b in range(B):
+            assert list(out[b, :n[b]]) == list(h["drafts"][b, :n[b]]) and np.all(out[b, n[b] + 1:] == -1) and out[b, n[b]] >= 0
+            assert h["tokens"][b, 0] == kept[b][-1]                                  # this step's first input = last emitted token
+            kept[b] += list(out[b, :n[b] + 1])
+        total += n + 1
+    assert list(ctx) == list(C + total)
+    assert len({tuple(h["accept_len"]) for h in hist}) > 1 or k == 0                 # acceptance really varies here
+    for b in range(B):
+        s = np.array(kept[b], dtype=np.int32)[None, :]
+        want_t = of.prefill(cfg_t, w_t, s[:, :ctx[b]])
+        want_d = of.prefill(cfg_d, w_d, s[:, :ctx[b] - 1])
+        assert kv_t2[0][b][0].shape[0] == ctx[b] and kv_d2[0][b][0].shape[0] == ctx[b] - 1
+        for l in range(cfg_t["n_layers"]):
+            assert np.max(np.abs(kv_t2[l][b][0] - want_t[l][0][0])) < 1e-9 and np.max(np.abs(kv_t2[l][b][1] - want_t[l][0][1])) < 1e-9
+        assert np.max(np.abs(kv_d2[0][b][0] - want_d[0][0][0])) < 1e-9 and np.max(np.abs(kv_d2[0][b][1] - want_d[0][0][1])) < 1e-9
+    hist2, _, _, ctx2 = od.rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, string[:, C - 1], string[:, C], np.full(B, C), k, T, 5, S)
+    assert all(np.array_equal(a["out_tokens"], b["out_tokens"]) for a, b in zip(hist, hist2)) and list(ctx) == list(ctx2)
+    # the target as its own draft: p == q, every draft is kept
+    kv_same = of.prefill(cfg_d, w_d, string[:, :C])
+    hist3, _, _, ctx3 = od.rollout(cfg_d, w_d, cfg_d, w_d, kv_same, kv_d, string[:, C - 1], string[:, C], np.full(B, C), k, T, 5, 2)
+    assert all(np.all(h["accept_len"] == k) for h in hist3) and list(ctx3) == [C + 2 * (k + 1)] * B
