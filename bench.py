@@ -129,6 +129,7 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=2)
+    ap.add_argument("--rollout-steps", type=int, default=8, help="draft+target pair: consecutive steps of the sustained run")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch parameter (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -229,6 +230,26 @@ def main():
             "draft_loop": round(sum(e[0].elapsed_time(e[1]) for e in marks) / K, 4),
             "verify_sample_commit_rollback": round(sum(e[1].elapsed_time(e[2]) for e in marks) / K, 4),
             "draft_model": wl.wl["draft_model"], "draft_passes": k}
+        # sustained rollout: consecutive steps, each feeding the next on the device (no cache restore, no host sync)
+        from paper_2604_26779_amd.draft import RolloutLoop
+        S = args.rollout_steps
+        roll = RolloutLoop(wl.sess, wl.dsess, B, k)
+        acc_s = torch.zeros((S, B), dtype=torch.int32, device="cuda")
+        times = []
+        for rep in range(2):                      # first repetition warms up
+            wl.restore()
+            roll.start(wl.pending[:, 0].contiguous(), wl.pending[:, 1].contiguous())
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            roll.run(wl.seq_ids, S, wl.wl["temperature"], wl.seed, 5000, acc_s)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        made = float((acc_s + 1).sum().item())
+        out["sustained_rollout"] = {"steps": S, "ms_per_step": round(times[-1] / S, 4),
+                                    "accepted_tokens_per_s": round(made / (times[-1] / 1e3), 1),
+                                    "mean_acceptance_length": round(made / (S * B), 3)}
         args.no_cpu_baseline = True               # the oracle baseline is reported on the headline workload only
     if not args.no_cpu_baseline:
         base, _ = cpu_baseline(wl, torch, args.cpu_seqs)

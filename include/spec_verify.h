@@ -235,6 +235,17 @@ spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int
 spec_status spec_kv_truncate(spec_kv* kv, int32_t B, const int32_t* dev_seq_ids, const int32_t* dev_len, int32_t delta,
                              int32_t* dev_new_len, void* stream);
 
+/*
+ * Inputs of the next speculation step, on the device (so that consecutive steps of a rollout need no host round
+ * trip): with n = dev_accept_len[b] of the step just sampled, dev_pending[b] = (dev_tokens[b][n], dev_out_tokens[b][n])
+ * = the last input the target kept and the token it emitted - what a draft model that is one position behind
+ * feeds first (dev_pending [B, 2], may be NULL) - and dev_tokens[b][0] = dev_out_tokens[b][n], the next step's
+ * first input.  dev_tokens and dev_out_tokens are the [B, k+1] arrays of spec_verify_forward / spec_reject_sample.
+ * Asynchronous on `stream`.
+ */
+spec_status spec_next_step_inputs(int32_t B, int32_t k, int32_t* dev_tokens, const int32_t* dev_out_tokens,
+                                  const int32_t* dev_accept_len, int32_t* dev_pending, void* stream);
+
 /* ---------------------------------------------------------------- tuning / introspection -------------------- */
 
 /* Set a launch parameter by name (split factors and the like); unknown names give SPEC_EINVAL.

@@ -24,7 +24,7 @@ EXPORTS = [
     "spec_kv_alloc", "spec_kv_free", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_sample_workspace_bytes", "spec_reject_sample",
-    "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
+    "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_calib_read", "spec_calib_copy",
 ]
 
@@ -79,6 +79,7 @@ def lib():
             "spec_commit_kv": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
             "spec_draft_sample": (i32, [i32, i32, vp, i64, f32, u64, u64, i32, vp, i32, vp, i32, vp, i64, vp]),
             "spec_kv_truncate": (i32, [vp, i32, vp, vp, i32, vp, vp]),
+            "spec_next_step_inputs": (i32, [i32, i32, vp, vp, vp, vp, vp]),
             "spec_tune_set": (i32, [ctypes.c_char_p, i32]),
             "spec_tune_get": (i32, [ctypes.c_char_p]),
             "spec_profile_class_count": (i32, []),
@@ -246,6 +247,10 @@ def spec_draft_sample(B, V, logits, logits_row_stride, temperature, seed, step, 
 
 def spec_kv_truncate(kv, B, seq_ids, lengths, delta, new_len, stream=None):
     _check(lib().spec_kv_truncate(kv, B, _ptr(seq_ids), _ptr(lengths), int(delta), _ptr(new_len), _stream(stream)))
+
+
+def spec_next_step_inputs(B, k, tokens, out_tokens, accept_len, pending, stream=None):
+    _check(lib().spec_next_step_inputs(B, k, _ptr(tokens), _ptr(out_tokens), _ptr(accept_len), _ptr(pending), _stream(stream)))
 
 
 def spec_tune_set(name, value):

@@ -280,3 +280,32 @@ extern "C" spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_
     prof_mark(PC_DRAFT_SAMPLE, s);
     return SPEC_OK;
 }
+
+namespace specv {
+
+// pending[b] = (tokens[b][n_b], out[b][n_b]) and tokens[b][0] = out[b][n_b]: the inputs of the next step
+__global__ void next_inputs_kernel(int B, int k, int32_t* __restrict__ tokens, const int32_t* __restrict__ out_tokens,
+                                   const int32_t* __restrict__ accept_len, int32_t* __restrict__ pending)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int n = accept_len[b];
+    n = n < 0 ? 0 : (n > k ? k : n);
+    int32_t last_input = tokens[(int64_t)b * (k + 1) + n];
+    int32_t emitted = out_tokens[(int64_t)b * (k + 1) + n];
+    if (pending) { pending[2 * b] = last_input; pending[2 * b + 1] = emitted; }
+    tokens[(int64_t)b * (k + 1)] = emitted;
+}
+
+}  // namespace specv
+
+extern "C" spec_status spec_next_step_inputs(int32_t B, int32_t k, int32_t* dev_tokens, const int32_t* dev_out_tokens,
+                                             const int32_t* dev_accept_len, int32_t* dev_pending, void* stream)
+{
+    using namespace specv;
+    if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT) { set_error("spec_next_step_inputs: B or k out of range"); return SPEC_EINVAL; }
+    if (!dev_tokens || !dev_out_tokens || !dev_accept_len) { set_error("spec_next_step_inputs: null pointer"); return SPEC_EINVAL; }
+    next_inputs_kernel<<<(unsigned)cdiv(B, 256), 256, 0, (hipStream_t)stream>>>(B, k, dev_tokens, dev_out_tokens, dev_accept_len, dev_pending);
+    SPEC_LAUNCH_CHECK("next_inputs_kernel");
+    return SPEC_OK;
+}

@@ -52,3 +52,45 @@ class DraftLoop:
         """After the target's commit: keep target_new_ctx_len - 1 positions (never more than cached)."""
         sv.spec_kv_truncate(self.sess.kv, self.B, seq_ids, target_new_ctx_len, -1, self.new_len, stream)
         return self.new_len
+
+
+class RolloutLoop:
+    """Consecutive speculation steps on one stream with no host round trip: draft loop -> verify forward ->
+    rejection sampling -> commit -> roll-back of the draft's cache -> next step's inputs.  Only call order and
+    buffers are handled here."""
+
+    def __init__(self, target_session, draft_session, B, k):
+        self.t, self.B, self.k = target_session, int(B), int(k)
+        self.loop = DraftLoop(draft_session, B, k)
+        dev = target_session.device
+        V = target_session.cfg["vocab"]
+        self.tokens = torch.zeros((B, k + 1), dtype=torch.int32, device=dev)
+        self.pending = torch.zeros((B, 2), dtype=torch.int32, device=dev)
+        self.q = torch.zeros((B, k, V), dtype=torch.float32, device=dev)
+
+    def start(self, prev, t0):
+        """prev, t0 [B] int32 device tensors: the last input the target has cached and the last emitted token."""
+        self.pending[:, 0] = prev
+        self.pending[:, 1] = t0
+        self.tokens[:, 0] = t0
+
+    def run(self, seq_ids, n_steps, temperature, seed, step0=0, accept_out=None, tokens_out=None, stream=None):
+        """accept_out [n_steps, B] int32, tokens_out [n_steps, B, k+1] int32 (device, optional) receive every
+        step's accept lengths and emitted tokens."""
+        t, B, k = self.t, self.B, self.k
+        V = t.cfg["vocab"]
+        buf = t.step_buffers(B, k)
+        ws = buf["workspace"]
+        off = (-ws.data_ptr()) % 256
+        ws = ws[off:off + ws.numel() - 256]
+        for s in range(n_steps):
+            drafts = self.loop.run(seq_ids, self.pending, self.q, temperature, seed, step0 + s, stream)
+            self.tokens[:, 1:] = drafts
+            acc = accept_out[s] if accept_out is not None else buf["accept_len"]
+            out = tokens_out[s] if tokens_out is not None else buf["out_tokens"]
+            sv.spec_verify_forward(t.model, t.kv, B, k, seq_ids, self.tokens, buf["logits"], ws, stream)
+            sv.spec_reject_sample(B, k, V, buf["logits"], self.q, drafts, temperature, seed, step0 + s, acc, out, None,
+                                  buf["sample_ws"], stream)
+            sv.spec_commit_kv(t.kv, B, k, seq_ids, acc, buf["new_ctx_len"], None, stream)
+            self.loop.roll_back(seq_ids, buf["new_ctx_len"], stream)
+            sv.spec_next_step_inputs(B, k, self.tokens, out, acc, self.pending, stream)

@@ -118,7 +118,7 @@ class DraftPairWorkload(DeviceWorkload):
         dweights = si.make_weights(self.draft_cfg, seed=seed + 17, device=device)
         dctx = self.ctx_len - 1
         step_pages = [-(-(int(c) + k + 2) // si.PAGE_SIZE) for c in dctx]
-        n_pages = sum(step_pages) + 64
+        n_pages = sum(step_pages) + 8 * B + 64          # room for a few consecutive steps of a rollout
         self.dsess = VerifySession(self.draft_cfg, dweights, max_seqs=B, max_ctx_len=int(dctx.max()) + 256, n_pages=n_pages,
                                    device=device)
         keep = {"embed"} | {n for n in dweights if n.endswith("norm")}

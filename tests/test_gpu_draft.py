@@ -205,3 +205,46 @@ def test_draft_loop_and_pair_step_parity(name):
     print(name, "accepted+1 mean %.2f (oracle %.2f)" % (n_gpu.mean() + 1, n_or.mean() + 1))
     t["sess"].close()
     d["sess"].close()
+
+
+@pytest.mark.parametrize("name,n_steps", [("draft_pair_tiny_b4_k3", 4), ("draft_pair_small_b5_k4", 3)])
+def test_rollout_of_several_steps_against_oracle(name, n_steps):
+    """Consecutive steps with no host round trip: per step and sequence, accept length and emitted tokens equal the
+    oracle's until the first decision the oracle marks as fragile (then that sequence is left out from there on);
+    at the end lengths and page books of both caches equal the oracle-side books for the sequences still compared."""
+    from paper_2604_26779_amd.draft import RolloutLoop
+    S = _setup_pair(name)
+    B, k, T = S["B"], S["k"], S["wl"]["temperature"]
+    t, d = S["t"], S["d"]
+    seed = 0x0123456789ABCDEF
+    t0 = S["batch"]["tokens0"]
+    hist, _, _, ctx_or = oracle_draft.rollout(t["cfg"], t["w_or"], d["cfg"], d["w_or"], t["kv_or"], d["kv_or"], S["prev"], t0, t["ctx"],
+                                              k, T, seed, n_steps)
+    roll = RolloutLoop(t["sess"], d["sess"], B, k)
+    roll.start(torch.from_numpy(S["prev"]).cuda(), torch.from_numpy(t0).cuda())
+    acc = torch.full((n_steps, B), -9, dtype=torch.int32, device="cuda")
+    outs = torch.full((n_steps, B, k + 1), -9, dtype=torch.int32, device="cuda")
+    seq_ids = torch.arange(B, dtype=torch.int32, device="cuda")
+    roll.run(seq_ids, n_steps, T, seed, 0, acc, outs)
+    torch.cuda.synchronize()
+    acc, outs = acc.cpu().numpy(), outs.cpu().numpy()
+    alive = np.ones(B, dtype=bool)
+    for s in range(n_steps):
+        for b in range(B):
+            if alive[b] and not (acc[s, b] == hist[s]["accept_len"][b] and np.array_equal(outs[s, b], hist[s]["out_tokens"][b])):
+                alive[b] = False
+                print("  step %d sequence %d diverges: gpu n=%d %s, oracle n=%d %s" % (s, b, acc[s, b], outs[s, b], hist[s]["accept_len"][b],
+                                                                                   hist[s]["out_tokens"][b]))
+    print(name, "sequences equal to the oracle over all %d steps: %d of %d; tokens per step %.2f" % (n_steps, alive.sum(), B, (acc + 1).mean()))
+    assert alive.sum() >= B - 1                      # at most one sequence may hit a fragile draw or accept test
+    st_t, st_d = t["sess"].state(), d["sess"].state()
+    for b in range(B):
+        if alive[b]:
+            assert st_t["ctx_len"][b] == ctx_or[b] and st_d["ctx_len"][b] == ctx_or[b] - 1
+            assert st_t["n_pages"][b] == -(-int(ctx_or[b]) // si.PAGE_SIZE) and st_d["n_pages"][b] == -(-(int(ctx_or[b]) - 1) // si.PAGE_SIZE)
+    # conservation of pages in both pools, whatever was accepted
+    for sess, st in ((t["sess"], st_t), (d["sess"], st_d)):
+        held = [p for b in range(B) for p in st["page_table"][b][:st["n_pages"][b]]]
+        assert sorted(held + list(st["free_stack"])) == list(range(sess.n_pages))
+    t["sess"].close()
+    d["sess"].close()
