@@ -55,3 +55,25 @@ def test_host_side_argument_checks_need_no_gpu(sv):
     assert sv.lib().spec_verify_forward(None, None, 1, 1, None, None, None, None, 0, None) == sv.SPEC_EINVAL
     assert sv.lib().spec_verify_workspace_bytes(None, None, 1, 1) == 0
     assert sv.lib().spec_kv_pool_bytes(None, 1, 0) == -1
+
+
+def test_argument_checks_of_the_draft_side_calls(sv):
+    L = sv.lib()
+    ok = dict(B=2, V=10, logits=1, lstride=10, T=1.0, seed=0, step=0, row=0, ta=1, sa=1, tb=None, sb=0, q=1, qstride=10)
+
+    def draft(**kw):
+        a = dict(ok, **kw)
+        return L.spec_draft_sample(a["B"], a["V"], a["logits"], a["lstride"], a["T"], a["seed"], a["step"], a["row"], a["ta"], a["sa"],
+                                   a["tb"], a["sb"], a["q"], a["qstride"], None)
+    for bad in (dict(B=0), dict(V=0), dict(row=-1), dict(row=16), dict(T=0.0), dict(step=1 << 30), dict(logits=None), dict(q=None),
+                dict(ta=None), dict(lstride=9), dict(qstride=9), dict(sa=0)):
+        assert draft(**bad) == sv.SPEC_EINVAL, bad
+        assert "spec_draft_sample" in sv.spec_last_error()
+    assert L.spec_kv_truncate(None, 1, None, None, -1, None, None) == sv.SPEC_EINVAL
+    assert L.spec_next_step_inputs(0, 3, 1, 1, 1, None, None) == sv.SPEC_EINVAL
+    assert L.spec_next_step_inputs(2, 16, 1, 1, 1, None, None) == sv.SPEC_EINVAL
+    assert L.spec_next_step_inputs(2, 3, None, 1, 1, None, None) == sv.SPEC_EINVAL
+    # mixture-of-experts descriptions are counted with their router; the fp32 path refuses them at creation
+    moe = dict(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=256, vocab=10, rope_theta=1e4, rms_eps=1e-5,
+               dtype="bf16", tied_head=0, n_experts=4, top_k=2, expert_ffn_dim=256)
+    assert sv.spec_model_weight_count(moe) == 1 + 2 * 10 + 2
