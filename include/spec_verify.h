@@ -180,6 +180,9 @@ spec_status spec_verify_forward(spec_model* model, spec_kv* kv, int32_t B, int32
  * then -1.  dev_dbg [B, k, 3] fp32, may be NULL: P, Q, u of every accept test evaluated (NaN elsewhere).
  * Needs B >= 1, 0 <= k <= SPEC_MAX_DRAFT, V >= 1, temperature > 0, step < 2^30; draft tokens
  * outside [0, V) are treated as rejected.  dev_q and dev_draft_tokens may be NULL when k == 0.
+ * dev_q == NULL with k > 0 means one-hot draft distributions (a deterministic drafter such as an n-gram
+ * table, Section 3.1): q_i(x_i) = 1, so x_i is kept with probability p_i(x_i) and the residual is p_i with
+ * entry x_i removed; no [B, k, V] array is read.
  * dev_workspace: at least spec_sample_workspace_bytes(B, k) bytes.  Asynchronous on `stream`.
  */
 size_t spec_sample_workspace_bytes(int32_t B, int32_t k);

@@ -66,11 +66,11 @@ __global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __
     }
 }
 
-// mode 0: w = max(0, e/S - q); mode 1: w = e  (e = exp(z - m))
+// mode 0: w = max(0, e/S - q); mode 1: w = e; mode 2: w = e except 0 at the drafted token  (e = exp(z - m))
 template <int MODE>
 __device__ inline void race_scan(const float* __restrict__ lrow, const float* __restrict__ qrow, int V, float inv_t,
                                  float m, float inv_s, uint32_t k0, uint32_t k1, uint32_t c1, uint32_t c2, uint32_t c3,
-                                 float& best, int& best_v)
+                                 float& best, int& best_v, int hot = -1)
 {
     int groups = (V + 3) >> 2;
     for (int g = threadIdx.x; g < groups; g += SAMP_THREADS) {
@@ -81,7 +81,8 @@ __device__ inline void race_scan(const float* __restrict__ lrow, const float* __
             int v = g * 4 + j;
             if (v >= V) break;
             float e = expf(lrow[v] * inv_t - m);
-            float w = (MODE == 0) ? fmaxf(0.f, e * inv_s - qrow[v]) : e;
+            // MODE 2: one-hot draft distribution on token `hot`: the residual is p with that entry removed
+            float w = (MODE == 0) ? fmaxf(0.f, e * inv_s - qrow[v]) : ((MODE == 2 && v == hot) ? 0.f : e);
             if (!(w > 0.f)) continue;
             float u = ((float)(words[j] >> 9) + 0.5f) * (1.0f / 8388608.0f);
             float key = w / (-logf(u));
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(SAMP_THREADS) void reject_sample_kernel(
             if (x < 0 || x >= V) break;
             float2 st = stats[(int64_t)b * (k + 1) + i];
             float P = expf(L[(int64_t)i * V + x] * inv_t - st.x) / st.y;
-            float Q = Qb[(int64_t)i * V + x];
+            float Q = Qb ? Qb[(int64_t)i * V + x] : 1.0f;          // no q array: one-hot drafts (a deterministic drafter)
             Philox4 r = philox4x32_10(0u, (uint32_t)i, (uint32_t)b, step4 + 0u, seed_lo, seed_hi);
             float u = (float)(r.x >> 8) * (1.0f / 16777216.0f);
             if (dbg) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = P; d[1] = Q; d[2] = u; }
@@ -149,7 +150,8 @@ __global__ __launch_bounds__(SAMP_THREADS) void reject_sample_kernel(
     int best_v = -1;
     const uint32_t c1 = (uint32_t)n, c2 = (uint32_t)b, c3 = step4 + 1u;
     if (n < k) {
-        race_scan<0>(lrow, Qb + (int64_t)n * V, V, inv_t, st.x, 1.0f / st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v);
+        if (Qb) race_scan<0>(lrow, Qb + (int64_t)n * V, V, inv_t, st.x, 1.0f / st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v);
+        else race_scan<2>(lrow, nullptr, V, inv_t, st.x, 1.0f, seed_lo, seed_hi, c1, c2, c3, best, best_v, draft[(int64_t)b * k + n]);
         block_argmax(best, best_v, lk, lv);
     }
     if (best_v < 0) {                                // bonus row, or a residual that is identically zero
@@ -239,7 +241,7 @@ extern "C" spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const
     if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT || V < 1) { set_error("spec_reject_sample: B, k or V out of range"); return SPEC_EINVAL; }
     if (!(temperature > 0.f)) { set_error("spec_reject_sample: temperature must be > 0"); return SPEC_EINVAL; }
     if (step >= (1ull << 30)) { set_error("spec_reject_sample: step must be < 2^30"); return SPEC_EINVAL; }
-    if (!dev_logits || !dev_accept_len || !dev_out_tokens || !dev_workspace || (k > 0 && (!dev_q || !dev_draft_tokens))) {
+    if (!dev_logits || !dev_accept_len || !dev_out_tokens || !dev_workspace || (k > 0 && !dev_draft_tokens)) {
         set_error("spec_reject_sample: null pointer"); return SPEC_EINVAL;
     }
     if (workspace_bytes < spec_sample_workspace_bytes(B, k)) { set_error("spec_reject_sample: workspace too small"); return SPEC_EINVAL; }

@@ -109,10 +109,38 @@ def test_argument_errors():
         (0, 1, 4, t, t, i, 1.0, 0, 0, i, i, None, ws),            # B < 1
         (1, 16, 4, t, t, i, 1.0, 0, 0, i, i, None, ws),           # k > SPEC_MAX_DRAFT
         (1, 1, 4, t, t, i, 0.0, 0, 0, i, i, None, ws),            # temperature 0
-        (1, 1, 4, t, None, i, 1.0, 0, 0, i, i, None, ws),         # q missing with k > 0
+        (1, 1, 4, t, t, None, 1.0, 0, 0, i, i, None, ws),         # drafts missing with k > 0
         (1, 1, 4, t, t, i, 1.0, 0, 1 << 30, i, i, None, ws),      # step too large
         (1, 1, 4, t, t, i, 1.0, 0, 0, i, i, None, ws[:4]),        # workspace too small
     ]:
         with pytest.raises(sv.SpecError) as e:
             sv.spec_reject_sample(*args)
         assert e.value.status == sv.SPEC_EINVAL
+
+
+@pytest.mark.parametrize("B,k,V", [(48, 3, 5000), (16, 5, 128256)])
+def test_one_hot_drafts_without_a_q_array(B, k, V):
+    """A deterministic drafter (n-gram table): q is one-hot on the drafted token, so the library is given no q at
+    all.  Must equal the oracle run on the explicit one-hot array: accept with probability p(x), residual = p
+    without x."""
+    from paper_2604_26779_amd import binding as sv
+    rng = np.random.Generator(np.random.Philox(B + k))
+    logits = (rng.standard_normal((B, k + 1, V)) * 3.0).astype(np.float32)
+    # drafts: random tokens; for two thirds of them the target is made to favour that token (p(x) around 0.5 .. 0.9)
+    draft = rng.integers(0, V, size=(B, k)).astype(np.int32)
+    boost = np.where(rng.random((B, k)) < 0.67, np.log(V) + rng.uniform(4.0, 6.5, size=(B, k)), 0.0).astype(np.float32)
+    np.put_along_axis(logits[:, :k], draft[:, :, None].astype(np.int64), boost[:, :, None], axis=2)
+    q = np.zeros((B, k, V), dtype=np.float32)
+    np.put_along_axis(q, draft[:, :, None].astype(np.int64), 1.0, axis=2)
+    seed, step = 77, 3
+    n_or, out_or, pqu, keys = oracle_sampler.reject_sample(logits, q, draft, 1.0, seed, step, debug=True)
+    n = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    out = torch.full((B, k + 1), -7, dtype=torch.int32, device="cuda")
+    ws = torch.empty(sv.spec_sample_workspace_bytes(B, k), dtype=torch.uint8, device="cuda")
+    sv.spec_reject_sample(B, k, V, torch.from_numpy(logits).cuda(), None, torch.from_numpy(draft).cuda(), 1.0, seed, step, n, out, None, ws)
+    torch.cuda.synchronize()
+    stats = assert_sampler_parity(n.cpu().numpy(), out.cpu().numpy(), n_or, out_or, pqu, keys)
+    print("one-hot drafts", dict(B=B, k=k, V=V), stats, "mean accepted+1 = %.3f" % (n_or.mean() + 1))
+    assert 0 < n_or.mean() < k                      # both outcomes occur
+    rejected = n_or < k
+    assert np.all(out_or[rejected, n_or[rejected]] != draft[rejected, n_or[rejected]])      # the rejected token is never re-drawn
