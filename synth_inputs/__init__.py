@@ -24,17 +24,17 @@ DEFAULT_SEED = 20260427
 
 # name -> model description.  dtype is the storage type of weights and of the KV cache.
 MODELS = {
-    # Tiny fp32 decoder (BASELINE config 0): 2 layers, MHA, vocab 1024.
+    # Tiny fp32 decoder: 2 layers, MHA, vocab 1024.
     "tiny_fp32": dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn_dim=704,
                       vocab=1024, rope_theta=1.0e4, rms_eps=1.0e-5, dtype="f32", tied_head=0),
     # Small bf16 model for parity tests of the MFMA path: several tiles plus ragged tails in N and V.
     "small_bf16": dict(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1280,
                        vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0),
-    # Llama-3-8B-shaped (BASELINE config 1).
+    # Llama-3-8B-shaped.
     "llama8b_bf16": dict(n_layers=32, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
                          vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0),
     # Mixture-of-experts models: a small one for parity tests, and a 4-layer slice at the widths of a
-    # 235B-A22B-class target (BASELINE config 4): 64 query / 4 kv heads, 128 experts, top-8, expert width 1536.
+    # 235B-A22B-class target: 64 query / 4 kv heads, 128 experts, top-8, expert width 1536.
     "small_moe_bf16": dict(n_layers=2, d_model=512, n_q_heads=16, n_kv_heads=1, head_dim=128, ffn_dim=256, vocab=4000,
                            rope_theta=1.0e6, rms_eps=1.0e-6, dtype="bf16", tied_head=0, n_experts=12, top_k=3,
                            expert_ffn_dim=256),
@@ -59,7 +59,7 @@ WORKLOADS = {
     "llama8b_b32_ctx1k-8k_k3": dict(model="llama8b_bf16", B=32, k=3, ctx_lo=1024, ctx_hi=8192, noise_std=1.0,
                                     temperature=1.0),
 }
-# Draft + target pair (BASELINE config 3): a single-layer draft run autoregressively for k = 5, then the
+# Draft + target pair: a single-layer draft run autoregressively for k = 5, then the
 # 8B-shaped verify, B = 64, contexts of 4096 tokens.
 WORKLOADS["draft_pair_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model="draft1l_8b_bf16", B=64, k=5, ctx_lo=4096,
                                               ctx_hi=4096, noise_std=0.0, temperature=1.0)
@@ -67,11 +67,11 @@ WORKLOADS["draft_pair_small_b5_k4"] = dict(model="small_bf16", draft_model="draf
                                            ctx_hi=600, noise_std=0.0, temperature=0.9)
 WORKLOADS["draft_pair_tiny_b4_k3"] = dict(model="tiny_fp32", draft_model="draft_tiny_fp32", B=4, k=3, ctx_lo=100,
                                           ctx_hi=140, noise_std=0.0, temperature=1.0)
-# Mixture-of-experts verify slice (BASELINE config 4): B = 128, contexts uniform in [4096, 32768], k = 3.
+# Mixture-of-experts verify slice: B = 128, contexts uniform in [4096, 32768], k = 3.
 WORKLOADS["moe235b_slice_b128_ctx4k-32k_k3"] = dict(model="moe235b_slice_bf16", B=128, k=3, ctx_lo=4096, ctx_hi=32768,
                                                     noise_std=1.0, temperature=1.0)
 WORKLOADS["small_moe_b6_k3"] = dict(model="small_moe_bf16", B=6, k=3, ctx_lo=5, ctx_hi=600, noise_std=1.0, temperature=1.0)
-# Large rollout batch (BASELINE config 2): B=256, contexts uniform in [2048, 16384], k swept.  The
+# Large rollout batch: B=256, contexts uniform in [2048, 16384], k swept.  The
 # cache of 32 distinct layers would not fit one GPU (309 GB on average), so layer l uses layer
 # pool l mod 8 (same bytes streamed per step, an eighth of the footprint); the draft noise of
 # sequence b is scaled by 2*Beta(4,2) so acceptance rates are mixed over the batch.
