@@ -39,6 +39,8 @@ def _run_gpu(logits, q, draft, temperature, seed, step):
     (64, 1, 257, 1.3, 2.0),
     (32, 3, 128256, 1.0, 1.0),       # the full-size vocabulary and batch of the 8B workload
     (256, 5, 32000, 1.0, 0.3),
+    (256, 7, 128256, 1.0, 1.0),      # the large rollout batch at its deepest draft
+    (128, 3, 151936, 1.0, 1.0),      # the mixture-of-experts slice's vocabulary and batch
 ])
 def test_parity_on_synthetic_logits(B, k, V, temperature, noise):
     logits, q, draft = si.make_sampler_case(B, k, V, seed=B * 1000 + k, noise_std=noise, temperature=temperature)
