@@ -130,6 +130,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=2)
     ap.add_argument("--rollout-steps", type=int, default=8, help="draft+target pair: consecutive steps of the sustained run")
+    ap.add_argument("--graph", action="store_true", help="record the K steps into a HIP graph and time its replay (default: one host launch per kernel)")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch parameter (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -161,11 +162,29 @@ def main():
     run_steps(wl, sv, torch, W, accept, 0)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    run_steps(wl, sv, torch, K, accept, 1000)
-    ev1.record()
-    torch.cuda.synchronize()
+    if not args.graph:
+        t0 = time.perf_counter()
+        ev0.record()
+        run_steps(wl, sv, torch, K, accept, 1000)
+        ev1.record()
+        torch.cuda.synchronize()
+    else:
+        # the K steps (each with its own random-counter value) are recorded once into a HIP graph on a side stream and
+        # replayed: the ~350 launches of a step then cost the GPU's own node-to-node time, not a host launch each
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            sv.spec_graph_capture_begin(side)
+            run_steps(wl, sv, torch, K, accept, 1000)
+            graph = sv.spec_graph_capture_end(side)
+            sv.spec_graph_launch(graph, side)                   # untimed first replay
+            side.synchronize()
+            t0 = time.perf_counter()
+            ev0.record(side)
+            sv.spec_graph_launch(graph, side)
+            ev1.record(side)
+            side.synchronize()
+        torch.cuda.synchronize()
+        sv.spec_graph_destroy(graph)
     wall = time.perf_counter() - t0
     ms_per_step = ev0.elapsed_time(ev1) / K
     produced = float((accept[:K] + 1).sum().item())          # tokens produced = accepted drafts + 1 per sequence
@@ -223,6 +242,7 @@ def main():
         "kernels": {n: roof(c) for n, c in classes.items()},
         "ms_per_step_by_class": {n: round(v, 4) for n, v in per_step.items() if v > 0},
         "wall_s_timed_region": round(wall, 3),
+        "launch": "HIP graph: the K steps recorded once, replayed" if args.graph else "one host launch per kernel",
         "hbm_ceiling_measured": hbm_ceiling(sv, torch),
     }
     if pair:

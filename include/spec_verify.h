@@ -63,6 +63,7 @@ typedef struct {
 
 typedef struct spec_model spec_model;
 typedef struct spec_kv spec_kv;
+typedef struct spec_graph spec_graph;
 
 /* Number of weight pointers spec_model_create expects: 1 + (9 + (n_experts ? 1 : 0))*n_layers + 1 + (tied_head ? 0 : 1). */
 int32_t spec_model_weight_count(const spec_model_desc* desc);
@@ -268,6 +269,23 @@ int32_t spec_profile_class_count(void);
 const char* spec_profile_class_name(int32_t c);
 spec_status spec_profile_begin(int32_t max_events);
 spec_status spec_profile_end(double* host_ms, int64_t* host_counts, int32_t n);
+
+/*
+ * Replay of a recorded sequence of step calls (for callers whose steps are short enough that launching ~350 small
+ * kernels per step costs more than running them).  Between spec_graph_capture_begin and spec_graph_capture_end every
+ * call of this library on `stream` (which must not be the default stream) is recorded instead of executed; the
+ * result replays with spec_graph_launch.  The step calls allocate nothing and use no memset, so they record cleanly;
+ * what is baked in: all pointer and scalar arguments (the random-counter `step` included - record several steps with
+ * their own `step` values into one graph), the split factors in force, and the number of attention chunks launched,
+ * which follows the longest context the cache's host-side bound knew at recording time: replay only from a cache
+ * state whose contexts are no longer than that (e.g. after spec_kv_restore of the state it was recorded from; the
+ * restore itself may be part of the recording).  Event profiling must be off while recording.  The host-side
+ * bounds of the caches are advanced while recording as if the calls had run once.
+ */
+spec_status spec_graph_capture_begin(void* stream);
+spec_status spec_graph_capture_end(void* stream, spec_graph** out);
+spec_status spec_graph_launch(spec_graph* graph, void* stream);
+spec_status spec_graph_destroy(spec_graph* graph);
 
 /*
  * Calibration kernels of known size (for benchmarks: the measured HBM ceiling, and the reference

@@ -25,7 +25,8 @@ EXPORTS = [
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_sample_workspace_bytes", "spec_reject_sample",
     "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
-    "spec_profile_begin", "spec_profile_end", "spec_calib_read", "spec_calib_copy",
+    "spec_profile_begin", "spec_profile_end", "spec_graph_capture_begin", "spec_graph_capture_end", "spec_graph_launch",
+    "spec_graph_destroy", "spec_calib_read", "spec_calib_copy",
 ]
 
 
@@ -86,6 +87,10 @@ def lib():
             "spec_profile_class_name": (ctypes.c_char_p, [i32]),
             "spec_profile_begin": (i32, [i32]),
             "spec_profile_end": (i32, [vp, vp, i32]),
+            "spec_graph_capture_begin": (i32, [vp]),
+            "spec_graph_capture_end": (i32, [vp, vp]),
+            "spec_graph_launch": (i32, [vp, vp]),
+            "spec_graph_destroy": (i32, [vp]),
             "spec_calib_read": (i32, [vp, sz, vp, i32, vp]),
             "spec_calib_copy": (i32, [vp, vp, sz, i32, vp]),
         }
@@ -281,6 +286,24 @@ def spec_profile_end():
     cnt = np.zeros(n, dtype=np.int64)
     _check(lib().spec_profile_end(ms.ctypes.data, cnt.ctypes.data, n))
     return {spec_profile_class_name(c): (float(ms[c]), int(cnt[c])) for c in range(n)}
+
+
+def spec_graph_capture_begin(stream=None):
+    _check(lib().spec_graph_capture_begin(_stream(stream)))
+
+
+def spec_graph_capture_end(stream=None):
+    out = ctypes.c_void_p()
+    _check(lib().spec_graph_capture_end(_stream(stream), ctypes.byref(out)))
+    return out
+
+
+def spec_graph_launch(graph, stream=None):
+    _check(lib().spec_graph_launch(graph, _stream(stream)))
+
+
+def spec_graph_destroy(graph):
+    _check(lib().spec_graph_destroy(graph))
 
 
 def spec_calib_read(src, nbytes, sink, workgroups, stream=None):

@@ -516,3 +516,53 @@ extern "C" spec_status spec_kv_restore(spec_kv* kv, const void* dev_buf, void* s
     kv->device_ahead = true;
     return SPEC_OK;
 }
+
+// ------------------------------------------------------------------------------------------ graphs
+
+struct spec_graph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
+extern "C" spec_status spec_graph_capture_begin(void* stream)
+{
+    if (!stream) { set_error("spec_graph_capture_begin: capture needs a stream of its own, not the default stream"); return SPEC_EINVAL; }
+    if (g_prof_on) { set_error("spec_graph_capture_begin: switch event profiling off first"); return SPEC_ESTATE; }
+    SPEC_HIP_TRY(hipStreamBeginCapture((hipStream_t)stream, hipStreamCaptureModeThreadLocal));
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_graph_capture_end(void* stream, spec_graph** out)
+{
+    if (!stream || !out) { set_error("spec_graph_capture_end: null pointer"); return SPEC_EINVAL; }
+    hipGraph_t g = nullptr;
+    SPEC_HIP_TRY(hipStreamEndCapture((hipStream_t)stream, &g));
+    spec_graph* sg = new (std::nothrow) spec_graph();
+    if (!sg) { (void)hipGraphDestroy(g); set_error("spec_graph_capture_end: out of host memory"); return SPEC_ENOMEM; }
+    sg->graph = g;
+    hipError_t e = hipGraphInstantiate(&sg->exec, g, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        set_error("spec_graph_capture_end: hipGraphInstantiate failed: %s", hipGetErrorString(e));
+        (void)hipGraphDestroy(g);
+        delete sg;
+        return SPEC_EHIP;
+    }
+    *out = sg;
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_graph_launch(spec_graph* graph, void* stream)
+{
+    if (!graph || !graph->exec) { set_error("spec_graph_launch: null graph"); return SPEC_EINVAL; }
+    SPEC_HIP_TRY(hipGraphLaunch(graph->exec, (hipStream_t)stream));
+    return SPEC_OK;
+}
+
+extern "C" spec_status spec_graph_destroy(spec_graph* graph)
+{
+    if (!graph) return SPEC_OK;
+    if (graph->exec) (void)hipGraphExecDestroy(graph->exec);
+    if (graph->graph) (void)hipGraphDestroy(graph->graph);
+    delete graph;
+    return SPEC_OK;
+}
