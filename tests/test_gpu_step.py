@@ -263,7 +263,7 @@ def test_forward_argument_errors_and_pool_exhaustion():
     assert e.value.status == sv.SPEC_EUNSUPPORTED
 
 
-def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, **model_changes):
+def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, **model_changes):
     """small_bf16 model, synthetic cache, explicit context lengths: returns (max err, worst over tolerance)."""
     from paper_2604_26779_amd.session import VerifySession
     cfg = dict(si.MODELS["small_bf16"])
@@ -275,6 +275,8 @@ def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, **model_changes):
     w_or = si.weights_for_oracle(cfg, weights)
     ctx_len = np.array(ctx_list, dtype=np.int64)
     kv = si.make_logical_kv(cfg, ctx_len, seed=seed)
+    if key_scale != 1.0:        # larger cached keys -> larger scores -> a peaked softmax (a few keys carry the weight)
+        kv = [[((K.float() * key_scale).to(K.dtype), V) for (K, V) in per_seq] for per_seq in kv]
     kv_or = si.kv_for_oracle(kv)
     rng = np.random.default_rng(seed)
     n_ctx_pages = [-(-int(c) // si.PAGE_SIZE) for c in ctx_len]
@@ -328,4 +330,16 @@ def test_bf16_more_than_32_query_rows_per_kv_head(k, heads):
     ctx = [int(c) for c in rng.integers(1, 700, size=4)] + [511, 0]
     ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=k, vocab=1000, n_q_heads=heads[0], n_kv_heads=heads[1])
     print("k=%d Hq/Hkv=%s: logits max abs err %.3e" % (k, heads, max_err))
+    assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("key_scale", [6.0, 20.0])
+def test_bf16_peaked_attention(key_scale):
+    """The synthetic cache gives nearly flat attention; trained models do not.  With the cached keys scaled up the
+    scores spread over tens of units and a handful of keys carry the softmax: the online softmax's rescaling, the
+    hi+lo split of the probabilities and the merge of chunks with very different maxima are then what is tested."""
+    rng = np.random.default_rng(int(key_scale))
+    ctx = [int(c) for c in rng.integers(30, 1500, size=5)] + [513, 16]
+    ok, max_err, worst = _run_custom_bf16(ctx, k=3, seed=21, vocab=1000, key_scale=key_scale)
+    print("key scale %.0f: logits max abs err %.3e" % (key_scale, max_err))
     assert ok, (max_err, worst)
