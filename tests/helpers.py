@@ -68,3 +68,14 @@ def logits_close(got, want, abs_tol, rel_tol):
     bound = abs_tol + rel_tol * np.abs(want)
     worst = float((err - bound).max())
     return worst <= 0.0, float(err.max()), worst
+
+
+def random_norm_gains(weights, seed):
+    """RMSNorm gains 1 + 0.3 N(0,1) in the weights' own type (the generator's are all 1, which would hide a gain
+    applied at the wrong place or taken from the wrong layer)."""
+    import torch
+    g = torch.Generator().manual_seed(int(seed) + 4242)
+    for name, t in weights.items():
+        if name.endswith("norm"):
+            weights[name] = (1.0 + 0.3 * torch.randn(t.shape, generator=g)).to(t.dtype).to(t.device)
+    return weights

@@ -12,6 +12,7 @@ import torch
 
 import synth_inputs as si
 from oracle import forward as of
+from tests.helpers import random_norm_gains
 
 pytestmark = pytest.mark.gpu
 
@@ -21,7 +22,7 @@ MARGIN = 2e-3
 def _run(cfg, ctx_list, k, seed):
     from paper_2604_26779_amd.session import VerifySession
     B = len(ctx_list)
-    weights = si.make_weights(cfg, seed=seed)
+    weights = random_norm_gains(si.make_weights(cfg, seed=seed), seed)
     w_or = si.weights_for_oracle(cfg, weights)
     ctx_len = np.array(ctx_list, dtype=np.int64)
     kv = si.make_logical_kv(cfg, ctx_len, seed=seed)

@@ -16,7 +16,7 @@ import synth_inputs as si
 from oracle import commit as oracle_commit
 from oracle import forward as of
 from oracle import sampler as oracle_sampler
-from tests.helpers import assert_sampler_parity, logits_close, oracle_drafts
+from tests.helpers import random_norm_gains, assert_sampler_parity, logits_close, oracle_drafts
 
 pytestmark = pytest.mark.gpu
 
@@ -33,7 +33,7 @@ def _setup(workload_name, k=None, prefill="oracle", shuffle=True, seed=SEED, B=N
     if B is not None:
         wl["B"] = B
     cfg = si.MODELS[wl["model"]]
-    weights = si.make_weights(cfg, seed=seed)
+    weights = random_norm_gains(si.make_weights(cfg, seed=seed), seed)
     w_or = si.weights_for_oracle(cfg, weights)
     batch = si.make_batch(wl, seed=seed, shuffle_pages=shuffle)
     ctx_len = batch["ctx_len"]
@@ -271,7 +271,7 @@ def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, **model_cha
     if vocab:
         cfg["vocab"] = vocab
     B = len(ctx_list)
-    weights = si.make_weights(cfg, seed=seed)
+    weights = random_norm_gains(si.make_weights(cfg, seed=seed), seed)
     w_or = si.weights_for_oracle(cfg, weights)
     ctx_len = np.array(ctx_list, dtype=np.int64)
     kv = si.make_logical_kv(cfg, ctx_len, seed=seed)
