@@ -15,7 +15,7 @@ from oracle import commit as oracle_commit
 from oracle import draft as oracle_draft
 from oracle import forward as of
 from oracle import sampler as oracle_sampler
-from tests.helpers import sampler_exemptions
+from tests.helpers import random_norm_gains, sampler_exemptions
 
 pytestmark = pytest.mark.gpu
 
@@ -96,7 +96,7 @@ def _setup_pair(name, seed=7):
     rng = np.random.default_rng(seed)
     out["prev"] = rng.integers(0, cfg_t["vocab"], size=B).astype(np.int32)
     for tag, cfg, clen, s in (("t", cfg_t, ctx, seed), ("d", cfg_d, ctx - 1, seed + 17)):
-        weights = si.make_weights(cfg, seed=s)
+        weights = random_norm_gains(si.make_weights(cfg, seed=s), s)
         kv = si.make_logical_kv(cfg, clen, seed=s)
         n_pages = sum(-(-(int(c) + k + 2) // si.PAGE_SIZE) for c in clen) + 8
         sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=B, max_ctx_len=int(clen.max()) + 64,
