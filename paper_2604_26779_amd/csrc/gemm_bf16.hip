@@ -286,16 +286,21 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
 int gemm_mb(int M) { int mb = (int)cdiv(M, 32), cap = tune("gemm_max_mb"); cap = cap < 1 ? 1 : (cap > 4 ? 4 : cap); return mb > cap ? cap : mb; }
 int gemm_mb_pad(int M) { int mb = gemm_mb(M); return (int)cdiv(cdiv(M, 32), mb) * mb; }
 
+// k-steps per split come in units of one pass of the weight ring: 2 slabs for the 2x2 arrangement (even row-block
+// counts), 4 for the others
+static int gemm_kunit(int M) { return gemm_mb(M) % 2 == 0 ? GEMM_KS * 2 : GEMM_KUNIT; }
+
 int gemm_pick_splits(const PackedW& W, int M, int forced)
 {
+    const int unit = gemm_kunit(M);
     int n_tiles = (int)cdiv(W.n_blocks, 4);
     int m_tiles = gemm_mb_pad(M) / gemm_mb(M);
-    int max_splits = W.k_steps / (tune("gemm_min_ksteps") > GEMM_KUNIT ? tune("gemm_min_ksteps") : GEMM_KUNIT);
+    int max_splits = W.k_steps / (tune("gemm_min_ksteps") > unit ? tune("gemm_min_ksteps") : unit);
     if (max_splits < 1) max_splits = 1;
     int splits = forced > 0 ? forced : tune("gemm_wg_target") / (n_tiles * m_tiles);
     if (splits < 1) splits = 1;
     if (splits > max_splits) splits = max_splits;
-    int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KUNIT) * GEMM_KUNIT;
+    int kps = (int)cdiv(cdiv(W.k_steps, splits), unit) * unit;
     return (int)cdiv(W.k_steps, kps);
 }
 
@@ -307,7 +312,7 @@ bool gemm_can_fuse_swiglu(int M, int splits) { return splits == 1 && gemm_mb(M) 
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s)
 {
     int mb = gemm_mb(M), mb_pad = gemm_mb_pad(M);
-    int kps = (int)cdiv(cdiv(W.k_steps, splits), GEMM_KUNIT) * GEMM_KUNIT;
+    int kps = (int)cdiv(cdiv(W.k_steps, splits), gemm_kunit(M)) * gemm_kunit(M);
     dim3 grid((unsigned)cdiv(W.n_blocks, 4), (unsigned)cdiv(W.k_steps, kps), (unsigned)(mb_pad / mb));
     int64_t stride = (int64_t)M * ldo;
     const u32x4_t* wp = (const u32x4_t*)W.data;
