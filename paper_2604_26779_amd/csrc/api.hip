@@ -33,7 +33,7 @@ static std::map<std::string, int>& tune_table()
         {"gemm_max_mb", 4},        // 32-row blocks per GEMM tile (1..4): smaller tiles = more workgroups, weights read once per tile
         {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
         {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
-        {"attn_chunk_pages", 32},  // KV pages per attention workgroup
+        {"attn_chunk_pages", 0},   // KV pages per attention workgroup (32 or 64; 0 = by the number of query rows)
     };
     return t;
 }

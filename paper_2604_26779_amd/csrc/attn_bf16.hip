@@ -31,9 +31,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int ATT_CP = 32;                 // pages per workgroup
+constexpr int ATT_CP_DEFAULT = 64;         // pages per workgroup (template parameter CP: 32 or 64)
 constexpr int ATT_WAVES = 4;
-constexpr int ATT_PPW = ATT_CP / ATT_WAVES;  // pages per wavefront
 constexpr int ATT_DEPTH = 3;                 // pages in flight per wavefront
 constexpr int DH = 128;
 constexpr int BLOCK_U4 = SPEC_PAGE_SIZE * DH * 2 / 16;   // 256 16-byte words per K or V block
@@ -45,7 +44,7 @@ constexpr int BLOCK_U4 = SPEC_PAGE_SIZE * DH * 2 / 16;   // 256 16-byte words pe
 // pages, so they are placed on the same XCD (workgroups go to XCDs round-robin by linear id: blockIdx.x spans
 // a multiple of 8 values - kv head and the low bits of the batch index - and the row group sits in
 // blockIdx.y, 8 ids apart) and next to each other in dispatch order: the second read hits that XCD's L2.
-template <int RB>
+template <int RB, int ATT_CP>
 __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
     int layer_pool, float scale_log2, int max_chunks, int RG, int Hkv, int BP, int B, float* __restrict__ part_o,
@@ -63,6 +62,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     const int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
     if (total > cap) total = cap;
     const int n_pages_seq = (total + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
+    constexpr int ATT_PPW = ATT_CP / ATT_WAVES;      // pages per wavefront
     const int page0 = chunk * ATT_CP;
     if (page0 >= n_pages_seq) return;
     int page_end = page0 + ATT_CP;
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
 // one thread per (batch entry, kv head, row, 8 channels): merge chunks, normalise, write the bf16
 // operand of the O projection: xp[k-step][m-block][lane][8] with k = head*128 + channel
 __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int B, int T,
-                                   int G, int Hkv, int RBrows, int max_chunks, const int32_t* __restrict__ seq_ids,
+                                   int G, int Hkv, int RBrows, int max_chunks, int chunk_pages, const int32_t* __restrict__ seq_ids,
                                    KvView kv, int mb_pad, uint4* __restrict__ xp)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -282,7 +282,7 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
     int totalk = kv.ctx_len[seq] + T;
     int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
     if (totalk > cap) totalk = cap;
-    int n_chunks = ((totalk + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE + ATT_CP - 1) / ATT_CP;
+    int n_chunks = ((totalk + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE + chunk_pages - 1) / chunk_pages;
     int64_t item0 = ((int64_t)b * Hkv + kvh) * max_chunks;
     float M = -INFINITY;
     for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part_ml[((item0 + c) * RBrows + r) * 2]);
@@ -302,7 +302,14 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
     xp_store8(xp, b * T + r / G, (kvh * G + r % G) * DH + c8 * 8, mb_pad, res);
 }
 
-int attn_chunk_pages() { return ATT_CP; }
+// pages per workgroup for R query rows per kv head: 64 (fewer prologues and merges per byte) unless the rows are split
+// into several 16-row groups, where the shorter chunks measured faster; the tuning parameter overrides (32 or 64)
+int attn_chunk_pages(int R)
+{
+    const int forced = tune("attn_chunk_pages");
+    if (forced == 32 || forced == 64) return forced;
+    return R > 32 ? 32 : ATT_CP_DEFAULT;
+}
 
 // rows of a partial tile for R query rows per kv head: whole 16-row blocks, in groups of two beyond 32 rows
 int attn_rows_padded(int R)
@@ -328,12 +335,15 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
     while ((Hkv * BP) % 8 != 0) BP *= 2;
     dim3 grid((unsigned)(Hkv * BP), (unsigned)(RG * cdiv(B, BP)), (unsigned)max_chunks);
     const float* qq = q;
-    if (RB == 1) attn_partial_kernel<1><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, Hkv, BP, B, part_o, part_ml);
-    else attn_partial_kernel<2><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, Hkv, BP, B, part_o, part_ml);
+    const int cp = attn_chunk_pages(R);
+#define SPEC_ATTN_LAUNCH(RBV, CPV) attn_partial_kernel<RBV, CPV><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, Hkv, BP, B, part_o, part_ml)
+    if (RB == 1) { if (cp == 32) SPEC_ATTN_LAUNCH(1, 32); else SPEC_ATTN_LAUNCH(1, 64); }
+    else { if (cp == 32) SPEC_ATTN_LAUNCH(2, 32); else SPEC_ATTN_LAUNCH(2, 64); }
+#undef SPEC_ATTN_LAUNCH
     SPEC_LAUNCH_CHECK("attn_partial_kernel");
     prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);
-    attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, rows, max_chunks, seq_ids, kv,
+    attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, rows, max_chunks, cp, seq_ids, kv,
                                                                   mb_pad, (uint4*)xp_out);
     SPEC_LAUNCH_CHECK("attn_reduce_kernel");
     prof_mark(PC_ATTN_REDUCE, s);

@@ -21,7 +21,7 @@ int gemm_mb_pad(int M);
 int gemm_pick_splits(const PackedW& W, int M, int forced);
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s);
 bool gemm_can_fuse_swiglu(int M, int splits);
-int attn_chunk_pages();
+int attn_chunk_pages(int R);
 int attn_rows_padded(int R);
 int moe_rows_bound(int M, int top_k, int E);
 spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, const bf16_t* Xp, int rows_pad, int max_tiles,
@@ -223,7 +223,7 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.mb_pad = gemm_mb_pad(p.M);
     int G = d.n_q_heads / d.n_kv_heads;
     p.RBrows = attn_rows_padded(T * G);
-    p.max_chunks = (int)cdiv(cdiv(max_ctx_plus, SPEC_PAGE_SIZE), attn_chunk_pages());
+    p.max_chunks = (int)cdiv(cdiv(max_ctx_plus, SPEC_PAGE_SIZE), attn_chunk_pages(T * G));
     if (p.max_chunks < 1) p.max_chunks = 1;
     p.s_qkv = gemm_pick_splits(m->wqkv[0], p.M, tune("splits_qkv"));
     p.s_o = gemm_pick_splits(m->wo[0], p.M, tune("splits_o"));
@@ -280,7 +280,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     // the chunks the current bound on the longest sequence needs
     Bf16Plan p = make_plan(mdl, B, k, (int64_t)kv->max_pages * SPEC_PAGE_SIZE);
     if (p.total > ws_bytes) { set_error("spec_verify_forward: workspace too small for the current split settings (%zu < %zu)", ws_bytes, p.total); return SPEC_EINVAL; }
-    int live_chunks = (int)cdiv(cdiv(kv->ub.max_ctx + T, SPEC_PAGE_SIZE), attn_chunk_pages());
+    int live_chunks = (int)cdiv(cdiv(kv->ub.max_ctx + T, SPEC_PAGE_SIZE), attn_chunk_pages(T * G));
     if (live_chunks > p.max_chunks) live_chunks = p.max_chunks;
     if (live_chunks < 1) live_chunks = 1;
 

@@ -35,7 +35,7 @@ def test_every_declared_function_is_exported(sv):
 
 
 def test_host_side_argument_checks_need_no_gpu(sv):
-    assert sv.spec_tune_get("attn_chunk_pages") == 32
+    assert sv.spec_tune_get("attn_chunk_pages") == 0
     with pytest.raises(sv.SpecError) as e:
         sv.spec_tune_set("no_such_parameter", 1)
     assert e.value.status == sv.SPEC_EINVAL and "no_such_parameter" in str(e.value)
