@@ -37,6 +37,29 @@ constexpr int ATT_DEPTH = 3;                 // pages in flight per wavefront
 constexpr int DH = 128;
 constexpr int BLOCK_U4 = SPEC_PAGE_SIZE * DH * 2 / 16;   // 256 16-byte words per K or V block
 
+// max / sum over the 4 lanes {l, l^16, l^32, l^48} with the two lane-swap instructions of gfx950 (rows of 16
+// lanes, then halves of 32): plain vector ALU work, where a shuffle would take a round trip through the LDS
+// crossbar on the softmax's critical path.  After a swap of x with itself the two results hold, lane by lane,
+// the two values to combine.
+__device__ inline float quad_max(float x)
+{
+    unsigned u = __float_as_uint(x);
+    auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    u = __float_as_uint(x);
+    auto b = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ inline float quad_sum(float x)
+{
+    unsigned u = __float_as_uint(x);
+    auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    u = __float_as_uint(x);
+    auto b = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 // part_o : [item][rows][128] fp32, part_ml : [item][rows][2] (max in log2 domain, sum); rows = RG*RB*16
 // item = (b * Hkv + kvh) * max_chunks + chunk
 // More than 32 query rows per kv head (deep drafts, or many query heads per kv head) are split into RG row
@@ -149,8 +172,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
                 if (need_mask && key0 + j > row_limit[rb]) sv[j] = -INFINITY;
             }
             float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            mx = quad_max(mx);
             const float mold = mrow[rb];
             const float mnew = fmaxf(mold, mx);
             const float msafe = mnew > -INFINITY ? mnew : 0.f;          // a row that has seen no key yet
@@ -224,8 +246,7 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     // per-row sums are spread over the 4 lane groups
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        lrow[rb] += __shfl_xor(lrow[rb], 16);
-        lrow[rb] += __shfl_xor(lrow[rb], 32);
+        lrow[rb] = quad_sum(lrow[rb]);
     }
 
     // merge the 4 wavefronts through LDS
