@@ -70,7 +70,7 @@ __device__ inline float quad_sum(float x)
 template <int RB, int ATT_CP>
 __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
-    int layer_pool, float scale_log2, int max_chunks, int RG, int Hkv, int BP, int B, float* __restrict__ part_o,
+    int layer_pool, float scale_log2, int max_chunks, int RG, int rows, int Hkv, int BP, int B, float* __restrict__ part_o,
     float* __restrict__ part_ml)
 {
     // chunk is the slowest grid dimension: the first chunks (every sequence has them) are dispatched first,
@@ -262,8 +262,8 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
     }
     __syncthreads();
     const int64_t item = ((int64_t)b * Hkv + kvh) * max_chunks + chunk;
-    float* po = part_o + item * (RG * RB * 16) * DH;
-    float* pml = part_ml + item * (RG * RB * 16) * 2;
+    float* po = part_o + item * rows * DH;
+    float* pml = part_ml + item * rows * 2;
     // element e of the tile: (rb, cb, lane', j) -> row rb*16 + lane'%16, channel cb*16 + (lane'/16)*4 + j
     for (int e = threadIdx.x; e < RB * 8 * 64; e += 256) {
         int l2 = e & 63, cb = (e >> 6) & 7, rb = e >> 9;
@@ -282,6 +282,264 @@ __global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
         int r = (rb0 + rb) * 16 + row, c = cb * 16 + (l2 >> 4) * 4;
         *(float4*)(po + (int64_t)r * DH + c) = make_float4(o4[0], o4[1], o4[2], o4[3]);
         if (cb == 0 && (l2 >> 4) == 0) { pml[r * 2] = M; pml[r * 2 + 1] = L; }
+    }
+}
+
+// The same pass for 3 or 4 row blocks (33..64 query rows per kv head; more rows: RG such workgroups): every K/V block
+// is read once and used for all NRB row blocks.  What no longer fits in registers moves: the queries (hi + lo) sit in
+// LDS in operand order and are re-read per page, the accumulators of all row blocks stay in registers.  The page loop
+// is a run-time loop over groups of ATT_DEPTH pages (the register ring needs compile-time slots, nothing else does),
+// so the code stays a few KiB whatever the chunk length; a wavefront's physical page ids sit in one register, lane j
+// holding its j-th page, and are broadcast with v_readlane.  Pages that need masks (those reaching into the new
+// positions, or past the end of the sequence: the last one or two) are left out of the pipelined loop and done last.
+template <int NRB>
+__global__ __launch_bounds__(256, 1) void attn_wide_kernel(
+    const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
+    int layer_pool, float scale_log2, int max_chunks, int chunk_pages, int RG, int rows, int Hkv, int BP, int B,
+    float* __restrict__ part_o, float* __restrict__ part_ml)
+{
+    const int kvh = blockIdx.x % Hkv, rb0 = (blockIdx.y % RG) * NRB, chunk = blockIdx.z;
+    const int b = (blockIdx.y / RG) * BP + blockIdx.x / Hkv;
+    if (b >= B) return;
+    const int seq = seq_ids[b];
+    const int ctx = kv.ctx_len[seq];
+    int total = ctx + T;
+    const int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
+    if (total > cap) total = cap;
+    const int n_pages_seq = (total + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
+    const int page0 = chunk * chunk_pages;
+    if (page0 >= n_pages_seq) return;
+    int page_end = page0 + chunk_pages;
+    if (page_end > n_pages_seq) page_end = n_pages_seq;
+    int plain_end = ctx / SPEC_PAGE_SIZE;          // pages before this one are visible to every row, every slot valid
+    if (plain_end > page_end) plain_end = page_end;
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int lq = lane & 15, lg = lane >> 4;
+    const int R = T * G;
+
+    __shared__ u32x4_t s_q[NRB][4][2][64];                      // [row block][32 channels][hi | lo][lane]
+    __shared__ float s_o[ATT_WAVES][8][64][4];
+    __shared__ float s_m[ATT_WAVES][16], s_l[ATT_WAVES][16];
+    for (int f = wave; f < NRB * 4; f += ATT_WAVES) {
+        const int rb = f >> 2, sgm = f & 3;
+        const int r = (rb0 + rb) * 16 + lq;
+        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (r < R) {
+            const float* src = q + ((int64_t)(b * T + r / G) * Hq + kvh * G + r % G) * DH + lg * 8 + sgm * 32;
+            float4 a = *(const float4*)src, c = *(const float4*)(src + 4);
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = c.x; v[5] = c.y; v[6] = c.z; v[7] = c.w;
+        }
+        uint4 h4, l4;
+        split8(v, h4, l4);
+        s_q[rb][sgm][0][lane] = u32x4_t{h4.x, h4.y, h4.z, h4.w};
+        s_q[rb][sgm][1][lane] = u32x4_t{l4.x, l4.y, l4.z, l4.w};
+    }
+    int row_limit[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        int r = (rb0 + rb) * 16 + lq;
+        row_limit[rb] = r < R ? ctx + r / G : -1;
+    }
+
+    const int32_t* pt = kv.page_table + (int64_t)seq * kv.max_pages;
+    const u32x4_t* pool = (const u32x4_t*)kv.pool;
+    const int64_t layer_base = (int64_t)layer_pool * kv.n_pages;
+    auto block_ptr = [&](int physical_page, int is_v) {
+        return pool + ((((layer_base + physical_page) * 2 + is_v) * Hkv + kvh) * BLOCK_U4) + lane;
+    };
+    // lane j: physical id of this wavefront's j-th page (chunk_pages <= 256: at most 64 per wavefront), clamped to the chunk
+    int my_pid;
+    {
+        int pg = page0 + wave + ATT_WAVES * lane;
+        my_pid = pt[pg < page_end ? pg : page_end - 1];
+    }
+    auto pid_at = [&](int it) { return __builtin_amdgcn_readlane(my_pid, it < 63 ? it : 63); };
+
+    float mrow[NRB], lrow[NRB];
+    f32x4_t oacc[NRB][8];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        mrow[rb] = -INFINITY;
+        lrow[rb] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+    u32x4_t kf[ATT_DEPTH][4], vf[ATT_DEPTH][4];
+    auto load_page = [&](int slot, int physical_page) {
+        const u32x4_t* kp = block_ptr(physical_page, 0);
+        const u32x4_t* vp = block_ptr(physical_page, 1);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) kf[slot][s] = __builtin_nontemporal_load(kp + s * 64);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) vf[slot][s] = __builtin_nontemporal_load(vp + s * 64);
+    };
+    __syncthreads();                                  // the queries are in LDS
+
+    // query fragments of one row block, double buffered: those of the next row block (of the next page after the
+    // last) are read from LDS while the softmax of the current one runs
+    bf16x8_t qh[2][4], ql[2][4];
+    auto load_q = [&](int buf, int rb) {
+#pragma unroll
+        for (int sg = 0; sg < 4; ++sg) {
+            qh[buf][sg] = __builtin_bit_cast(bf16x8_t, s_q[rb][sg][0][lane]);
+            ql[buf][sg] = __builtin_bit_cast(bf16x8_t, s_q[rb][sg][1][lane]);
+        }
+    };
+    load_q(0, 0);
+
+    auto process = [&](auto mask_c, int slot, int logical_page) {
+        constexpr bool need_mask = decltype(mask_c)::value;
+        const int key0 = logical_page * SPEC_PAGE_SIZE + lg * 4;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            // the three phases of a row block are pinned in this order (left alone, the scheduler hoists the query
+            // reads of all row blocks to the top of the page and runs out of registers)
+            __builtin_amdgcn_sched_barrier(0);
+            f32x4_t sacc = {0.f, 0.f, 0.f, 0.f}, sacc2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sg = 0; sg < 4; ++sg) {
+                const bf16x8_t kk = __builtin_bit_cast(bf16x8_t, kf[slot][sg]);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[rb & 1][sg], sacc, 0, 0, 0);
+                sacc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[rb & 1][sg], sacc2, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                constexpr int dummy = 0; (void)dummy;
+                const int nrb = rb + 1 < NRB ? rb + 1 : 0;
+                load_q(nrb & 1, nrb);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            sacc += sacc2;
+            float sv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                sv[j] = sacc[j] * scale_log2;
+                if (need_mask && key0 + j > row_limit[rb]) sv[j] = -INFINITY;
+            }
+            const float mx = quad_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])));
+            // The reference point of the exponentials only has to keep them in range, so it moves only when the
+            // maximum has grown by more than 2^8 (after the first pages: hardly ever), and the accumulators are
+            // rescaled in place then.
+#ifndef ATT_NO_RESCALE
+            if (__builtin_amdgcn_ballot_w64(mx > mrow[rb] + 8.0f) != 0) {
+                // the accumulators were last written by MFMAs of the previous page: far more than the 18 wait
+                // states an accumulator read needs after one, but the assembler block is opaque to the compiler's
+                // hazard pass, so spell them out
+                asm volatile("s_nop 15\n\ts_nop 15");
+                const float mnew = fmaxf(mrow[rb], mx);
+                const float alpha = mnew > -INFINITY ? __builtin_amdgcn_exp2f(mrow[rb] - mnew) : 1.0f;
+                mrow[rb] = mnew;
+                lrow[rb] *= alpha;
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        // in place, in the accumulation registers (with a plain multiply the compiler moves the
+                        // whole accumulator to the vector registers and back on both sides of this branch)
+                        float t;
+                        asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %2, %1\n\tv_accvgpr_write_b32 %0, %1"
+                                     : "+a"(oacc[rb][cb][j]), "=&v"(t) : "v"(alpha));
+                    }
+            }
+#endif
+            const float msafe = mrow[rb] > -INFINITY ? mrow[rb] : 0.f;
+            float p[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) p[j] = __builtin_amdgcn_exp2f(sv[j] - msafe);
+            lrow[rb] += (p[0] + p[1]) + (p[2] + p[3]);
+            unsigned int h01, l01, h23, l23;
+            split2(p[0], p[1], h01, l01);
+            split2(p[2], p[3], h23, l23);
+            const s16x4_t pb = __builtin_bit_cast(s16x4_t, u32x2_t{h01, h23});
+            const s16x4_t pl = __builtin_bit_cast(s16x4_t, u32x2_t{l01, l23});
+            s16x4_t va[4], vb[4];
+#pragma unroll
+            for (int cp = 0; cp < 4; ++cp) {
+                u32x4_t v = vf[slot][cp];
+                if (need_mask) {
+                    unsigned int m01 = (key0 + 0 < total ? 0x0000ffffu : 0u) | (key0 + 1 < total ? 0xffff0000u : 0u);
+                    unsigned int m23 = (key0 + 2 < total ? 0x0000ffffu : 0u) | (key0 + 3 < total ? 0xffff0000u : 0u);
+                    v.x &= m01; v.y &= m23; v.z &= m01; v.w &= m23;
+                }
+                va[cp] = __builtin_bit_cast(s16x4_t, u32x2_t{v.x, v.y});
+                vb[cp] = __builtin_bit_cast(s16x4_t, u32x2_t{v.z, v.w});
+            }
+#pragma unroll
+            for (int cp = 0; cp < 4; ++cp) {
+                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[cp], pb, oacc[rb][2 * cp], 0, 0, 0);
+                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb[cp], pb, oacc[rb][2 * cp + 1], 0, 0, 0);
+            }
+#pragma unroll
+            for (int cp = 0; cp < 4; ++cp) {
+                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[cp], pl, oacc[rb][2 * cp], 0, 0, 0);
+                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb[cp], pl, oacc[rb][2 * cp + 1], 0, 0, 0);
+            }
+        }
+    };
+
+    // mask-free pages of this wavefront: page0 + wave + 4 * it, it < n_plain.  Ring of ATT_DEPTH pages; the main
+    // loop takes whole groups of ATT_DEPTH pages and has no branch in its body, so that the compiler can count the
+    // loads in flight exactly; the last one or two pages follow it.  Loads past the wavefront's last page re-read
+    // its clamped id (cache hits, results unused).
+    static_assert(ATT_DEPTH == 3, "the loop body below is written for a ring of 3");
+    const int n_plain = plain_end > page0 + wave ? (plain_end - page0 - wave + ATT_WAVES - 1) / ATT_WAVES : 0;
+    load_page(0, pid_at(0));
+    load_page(1, pid_at(1));
+    int it = 0;
+    for (; it + 3 <= n_plain; it += 3) {
+        load_page(2, pid_at(it + 2));
+        process(std::false_type{}, 0, page0 + wave + ATT_WAVES * it);
+        load_page(0, pid_at(it + 3));
+        process(std::false_type{}, 1, page0 + wave + ATT_WAVES * (it + 1));
+        load_page(1, pid_at(it + 4));
+        process(std::false_type{}, 2, page0 + wave + ATT_WAVES * (it + 2));
+    }
+    if (it < n_plain) process(std::false_type{}, 0, page0 + wave + ATT_WAVES * it);
+    if (it + 1 < n_plain) process(std::false_type{}, 1, page0 + wave + ATT_WAVES * (it + 1));
+    // masked pages of the chunk (at most two in all: T <= 16), each by the wavefront whose turn it is
+    {
+        const int t0 = plain_end > page0 ? plain_end : page0;
+        for (int lp = t0 + ((wave - (t0 - page0)) & (ATT_WAVES - 1)); lp < page_end; lp += ATT_WAVES) {
+            load_page(2, pt[lp]);
+            process(std::true_type{}, 2, lp);
+        }
+    }
+
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) lrow[rb] = quad_sum(lrow[rb]);
+
+    // merge the 4 wavefronts through LDS, one row block at a time
+    const int64_t item = ((int64_t)b * Hkv + kvh) * max_chunks + chunk;
+    float* po = part_o + item * rows * DH;
+    float* pml = part_ml + item * rows * 2;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s_o[wave][cb][lane][j] = oacc[rb][cb][j];
+        if (lg == 0) { s_m[wave][lq] = mrow[rb]; s_l[wave][lq] = lrow[rb]; }
+        __syncthreads();
+        for (int e = threadIdx.x; e < 8 * 64; e += 256) {
+            int l2 = e & 63, cb = e >> 6;
+            int row = l2 & 15;
+            float mw[ATT_WAVES], M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < ATT_WAVES; ++w) { mw[w] = s_m[w][row]; M = fmaxf(M, mw[w]); }
+            float o4[4] = {0.f, 0.f, 0.f, 0.f}, L = 0.f;
+#pragma unroll
+            for (int w = 0; w < ATT_WAVES; ++w) {
+                float f = mw[w] > -INFINITY ? exp2f(mw[w] - M) : 0.f;
+                L += f * s_l[w][row];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o4[j] += f * s_o[w][cb][l2][j];
+            }
+            int r = (rb0 + rb) * 16 + row, c = cb * 16 + (l2 >> 4) * 4;
+            *(float4*)(po + (int64_t)r * DH + c) = make_float4(o4[0], o4[1], o4[2], o4[3]);
+            if (cb == 0 && (l2 >> 4) == 0) { pml[r * 2] = M; pml[r * 2 + 1] = L; }
+        }
+        __syncthreads();
     }
 }
 
@@ -323,20 +581,46 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
     xp_store8(xp, b * T + r / G, (kvh * G + r % G) * DH + c8 * 8, mb_pad, res);
 }
 
-// pages per workgroup for R query rows per kv head: 64 (fewer prologues and merges per byte) unless the rows are split
-// into several 16-row groups, where the shorter chunks measured faster; the tuning parameter overrides (32 or 64)
-int attn_chunk_pages(int R)
+// How R query rows per kv head are laid over workgroups.
+//   up to 32 rows : the unrolled kernel, 1 or 2 row blocks in registers (queries too), 64-page chunks
+//   more          : RG workgroups of 3 or 4 row blocks each (attn_wide_kernel), 64-page chunks
+// tuning parameter attn_row_blocks = 1 or 2 forces the unrolled kernel with that many blocks per workgroup and row
+// groups beyond (groups of 16 rows then take 32-page chunks, which measured faster there); attn_chunk_pages
+// overrides the chunk length (32 or 64).
+struct AttnPlan { bool wide; int RB, RG, chunk_pages; };
+static AttnPlan attn_plan(int R)
 {
-    const int forced = tune("attn_chunk_pages");
-    if (forced == 32 || forced == 64) return forced;
-    return R > 32 ? 32 : ATT_CP_DEFAULT;
+    const int blocks = (int)cdiv(R, 16);
+    const int forced = tune("attn_row_blocks");
+    AttnPlan p;
+    if (forced == 1 || forced == 2 || blocks <= 2) {
+        p.wide = false;
+        p.RB = blocks <= 1 ? 1 : (forced == 1 || forced == 2 ? forced : blocks);
+        p.RG = (int)cdiv(blocks, p.RB);
+        p.chunk_pages = p.RG > 1 ? 32 : ATT_CP_DEFAULT;
+    } else {
+        p.wide = true;
+        p.RG = (int)cdiv(blocks, 4);
+        p.RB = (int)cdiv(blocks, p.RG);
+        p.chunk_pages = ATT_CP_DEFAULT;
+    }
+    const int cp = tune("attn_chunk_pages");
+    if (cp == 32 || cp == 64) p.chunk_pages = cp;
+    return p;
 }
 
-// rows of a partial tile for R query rows per kv head: whole 16-row blocks, in groups of two beyond 32 rows
+int attn_chunk_pages(int R) { return attn_plan(R).chunk_pages; }
+
+// rows of a partial tile for R query rows per kv head: enough for every layout above (the workspace is sized before
+// the tuning parameters are final)
 int attn_rows_padded(int R)
 {
-    int blocks = (int)cdiv(R, 16);
-    return blocks <= 2 ? blocks * 16 : (int)cdiv(blocks, 2) * 32;
+    const int blocks = (int)cdiv(R, 16);
+    if (blocks <= 2) return blocks * 16;
+    const int rg = (int)cdiv(blocks, 4);
+    const int wide = rg * (int)cdiv(blocks, rg);
+    const int pairs = (int)cdiv(blocks, 2) * 2;
+    return (wide > pairs ? wide : pairs) * 16;
 }
 
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
@@ -344,23 +628,25 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
                                   int mb_pad, bf16_t* xp_out, hipStream_t s)
 {
     int R = T * G;
-    const int rows = attn_rows_padded(R);
-    // 17..32 rows: one workgroup with two 16-row blocks per wavefront (one workgroup per CU); more rows: groups of
-    // 16 rows at two workgroups per CU, which measured 1.6x faster at 64 rows than groups of 32
-    const int forced = tune("attn_row_blocks");
-    const int RB = forced == 1 || forced == 2 ? (rows <= 16 ? 1 : forced) : (rows > 16 && rows <= 32 ? 2 : 1);
-    const int RG = rows / (RB * 16);
     if (R > 256) { set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 256", R); return SPEC_EUNSUPPORTED; }
+    const int rows = attn_rows_padded(R);
+    const AttnPlan pl = attn_plan(R);
+    const int RG = pl.RG, cp = pl.chunk_pages;
     float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
     int BP = 1;                                   // batch entries folded into blockIdx.x so that it spans a multiple of 8
     while ((Hkv * BP) % 8 != 0) BP *= 2;
     dim3 grid((unsigned)(Hkv * BP), (unsigned)(RG * cdiv(B, BP)), (unsigned)max_chunks);
     const float* qq = q;
-    const int cp = attn_chunk_pages(R);
-#define SPEC_ATTN_LAUNCH(RBV, CPV) attn_partial_kernel<RBV, CPV><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, Hkv, BP, B, part_o, part_ml)
-    if (RB == 1) { if (cp == 32) SPEC_ATTN_LAUNCH(1, 32); else SPEC_ATTN_LAUNCH(1, 64); }
-    else { if (cp == 32) SPEC_ATTN_LAUNCH(2, 32); else SPEC_ATTN_LAUNCH(2, 64); }
+    if (pl.wide) {
+#define SPEC_ATTN_WIDE(NRBV) attn_wide_kernel<NRBV><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, cp, RG, rows, Hkv, BP, B, part_o, part_ml)
+        if (pl.RB == 3) SPEC_ATTN_WIDE(3); else SPEC_ATTN_WIDE(4);
+#undef SPEC_ATTN_WIDE
+    } else {
+#define SPEC_ATTN_LAUNCH(RBV, CPV) attn_partial_kernel<RBV, CPV><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, rows, Hkv, BP, B, part_o, part_ml)
+        if (pl.RB == 1) { if (cp == 32) SPEC_ATTN_LAUNCH(1, 32); else SPEC_ATTN_LAUNCH(1, 64); }
+        else { if (cp == 32) SPEC_ATTN_LAUNCH(2, 32); else SPEC_ATTN_LAUNCH(2, 64); }
 #undef SPEC_ATTN_LAUNCH
+    }
     SPEC_LAUNCH_CHECK("attn_partial_kernel");
     prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);
