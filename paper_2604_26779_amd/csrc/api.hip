@@ -29,11 +29,11 @@ static std::map<std::string, int>& tune_table()
     static std::map<std::string, int> t = {
         {"gemm_wg_target", 256},   // split K while a GEMM launches fewer workgroups than this
         {"fuse_swiglu", 1},        // 1: silu(gate) * up in the gate/up projection's epilogue (unsplit K, even row blocks)
-        {"attn_row_blocks", 0},    // 16-row blocks per attention workgroup beyond 16 query rows per kv head (1, 2; 0 = by row count)
+        {"attn_row_blocks", 0},    // most 16-row blocks per attention workgroup (1..4; 0 = up to 4, groups as equal as possible)
         {"gemm_max_mb", 4},        // 32-row blocks per GEMM tile (1..4): smaller tiles = more workgroups, weights read once per tile
         {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
         {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
-        {"attn_chunk_pages", 0},   // KV pages per attention workgroup (32 or 64; 0 = by the number of query rows)
+        {"attn_chunk_pages", 0},   // KV pages per attention workgroup (a multiple of 4 up to 256; 0 = by batch size and context bound)
     };
     return t;
 }

@@ -4,20 +4,22 @@
 // ride on ONE pass over that head's cached keys and values: that sharing is what makes verifying
 // k drafts cost about one decode step.  The pass is split along the context so that short and
 // long sequences fill the machine evenly:
-//   attn_partial_kernel : workgroup = (chunk of ATT_CP pages, kv head, batch entry); each of its 4
-//                         wavefronts walks every 4th page of the chunk with its own online softmax,
+//   attn_partial_kernel : workgroup = (chunk of pages, kv head, batch entry[, group of row blocks]); each of
+//                         its 4 wavefronts walks every 4th page of the chunk with its own online softmax,
 //                         reading K and V blocks straight into MFMA operand registers (the cache's
 //                         in-block layout is the operand order, so every load is a contiguous
-//                         1 KiB), two pages in flight per wavefront;
+//                         1 KiB), two pages in flight per wavefront; every block is used for all the
+//                         workgroup's 1..4 blocks of 16 query rows;
 //                           S^T = K Q^T   v_mfma_f32_16x16x32_bf16 (keys x queries; Q as hi + lo bf16)
 //                           O^T += V^T P^T v_mfma_f32_16x16x16_bf16 (P^T comes out of S^T's
 //                                          accumulator layout without any shuffle);
 //                         the wavefronts' results are merged through LDS and written as an
-//                         un-normalised partial (O, max, sum).
+//                         un-normalised partial (O, reference point, sum).
 //   attn_reduce_kernel  : merges the chunks of a (batch entry, kv head) and writes the bf16 result
 //                         in the operand order the O-projection GEMM reads.
 // Row r of a (batch entry, kv head) tile is input position r / G, query head kvh*G + r % G.
 // Row i sees cache positions 0 .. ctx+i (causal over the k+1 new positions).
+#include <algorithm>
 #include <type_traits>
 
 #include "common.h"
@@ -31,7 +33,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int ATT_CP_DEFAULT = 64;         // pages per workgroup (template parameter CP: 32 or 64)
+constexpr int ATT_CP_MIN = 32;               // shortest chunk (pages per workgroup) the launch policy picks; longest: 256
 constexpr int ATT_WAVES = 4;
 constexpr int ATT_DEPTH = 3;                 // pages in flight per wavefront
 constexpr int DH = 128;
@@ -60,240 +62,23 @@ __device__ inline float quad_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// part_o : [item][rows][128] fp32, part_ml : [item][rows][2] (max in log2 domain, sum); rows = RG*RB*16
-// item = (b * Hkv + kvh) * max_chunks + chunk
-// More than 32 query rows per kv head (deep drafts, or many query heads per kv head) are split into RG row
-// groups of RB*16 rows, one workgroup each.  The row groups of a (batch entry, kv head, chunk) re-read the same
-// pages, so they are placed on the same XCD (workgroups go to XCDs round-robin by linear id: blockIdx.x spans
-// a multiple of 8 values - kv head and the low bits of the batch index - and the row group sits in
-// blockIdx.y, 8 ids apart) and next to each other in dispatch order: the second read hits that XCD's L2.
-template <int RB, int ATT_CP>
-__global__ __launch_bounds__(256, RB == 1 ? 2 : 1) void attn_partial_kernel(
-    const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
-    int layer_pool, float scale_log2, int max_chunks, int RG, int rows, int Hkv, int BP, int B, float* __restrict__ part_o,
-    float* __restrict__ part_ml)
-{
-    // chunk is the slowest grid dimension: the first chunks (every sequence has them) are dispatched first,
-    // the chunks only long sequences have - and the empty workgroups of the short ones - last
-    // blockIdx.x = kvh + Hkv * (b % BP), blockIdx.y = row group + RG * (b / BP)
-    const int kvh = blockIdx.x % Hkv, rb0 = (blockIdx.y % RG) * RB, chunk = blockIdx.z;
-    const int b = (blockIdx.y / RG) * BP + blockIdx.x / Hkv;
-    if (b >= B) return;
-    const int seq = seq_ids[b];
-    const int ctx = kv.ctx_len[seq];
-    int total = ctx + T;
-    const int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
-    if (total > cap) total = cap;
-    const int n_pages_seq = (total + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
-    constexpr int ATT_PPW = ATT_CP / ATT_WAVES;      // pages per wavefront
-    const int page0 = chunk * ATT_CP;
-    if (page0 >= n_pages_seq) return;
-    int page_end = page0 + ATT_CP;
-    if (page_end > n_pages_seq) page_end = n_pages_seq;
-
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int lq = lane & 15, lg = lane >> 4;
-    const int R = T * G;
-
-    // query operands: lane (row lq, group lg) holds Q[row][s*32 + lg*8 .. +8], s = 0..3, split into
-    // hi + lo bf16 (the queries arrive in fp32)
-    bf16x8_t qhi[RB][4], qlo[RB][4];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        int r = (rb0 + rb) * 16 + lq;
-        const float* src = q + ((int64_t)(b * T + r / G) * Hq + kvh * G + r % G) * DH + lg * 8;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            if (r < R) {
-                float4 a = *(const float4*)(src + s * 32), c = *(const float4*)(src + s * 32 + 4);
-                v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = c.x; v[5] = c.y; v[6] = c.z; v[7] = c.w;
-            }
-            uint4 h4, l4;
-            split8(v, h4, l4);
-            qhi[rb][s] = __builtin_bit_cast(bf16x8_t, h4);
-            qlo[rb][s] = __builtin_bit_cast(bf16x8_t, l4);
-        }
-    }
-    int row_limit[RB];                       // last visible cache position of this lane's query row
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        int r = (rb0 + rb) * 16 + lq;
-        row_limit[rb] = r < R ? ctx + r / G : -1;
-    }
-
-    // this wavefront's pages: page0 + wave, + 4, ...
-    const int32_t* pt = kv.page_table + (int64_t)seq * kv.max_pages;
-    const u32x4_t* pool = (const u32x4_t*)kv.pool;
-    const int64_t layer_base = (int64_t)layer_pool * kv.n_pages;
-    auto block_ptr = [&](int physical_page, int is_v) {
-        return pool + ((((layer_base + physical_page) * 2 + is_v) * Hkv + kvh) * BLOCK_U4) + lane;
-    };
-
-    float mrow[RB], lrow[RB];
-    f32x4_t oacc[RB][8];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        mrow[rb] = -INFINITY;
-        lrow[rb] = 0.f;
-#pragma unroll
-        for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    }
-
-    u32x4_t kf[ATT_DEPTH][4], vf[ATT_DEPTH][4];
-    auto load_page = [&](int slot, int physical_page) {
-        const u32x4_t* kp = block_ptr(physical_page, 0);
-        const u32x4_t* vp = block_ptr(physical_page, 1);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) kf[slot][s] = __builtin_nontemporal_load(kp + s * 64);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) vf[slot][s] = __builtin_nontemporal_load(vp + s * 64);
-    };
-
-    // MASK = true only for pages that reach into the new positions (the last one or two of a
-    // sequence): all other pages run the variant without any per-key compare
-    auto process = [&](auto mask_c, int slot, int logical_page) {
-        constexpr bool need_mask = decltype(mask_c)::value;
-        const int key0 = logical_page * SPEC_PAGE_SIZE + lg * 4;          // this lane's 4 keys: key0 .. key0+3
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            f32x4_t sacc = {0.f, 0.f, 0.f, 0.f}, sacc2 = {0.f, 0.f, 0.f, 0.f};    // two independent chains
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                bf16x8_t kk = __builtin_bit_cast(bf16x8_t, kf[slot][s]);
-                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qhi[rb][s], sacc, 0, 0, 0);
-                sacc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qlo[rb][s], sacc2, 0, 0, 0);
-            }
-            sacc += sacc2;
-            float sv[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                sv[j] = sacc[j] * scale_log2;
-                if (need_mask && key0 + j > row_limit[rb]) sv[j] = -INFINITY;
-            }
-            float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-            mx = quad_max(mx);
-            const float mold = mrow[rb];
-            const float mnew = fmaxf(mold, mx);
-            const float msafe = mnew > -INFINITY ? mnew : 0.f;          // a row that has seen no key yet
-            float p[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) p[j] = __builtin_amdgcn_exp2f(sv[j] - msafe);
-            mrow[rb] = mnew;
-            // the running maximum rarely moves after the first pages: rescale only when some row's did
-            if (__builtin_amdgcn_ballot_w64(mnew != mold) != 0) {
-                const float alpha = __builtin_amdgcn_exp2f(mold - msafe);
-                lrow[rb] *= alpha;
-#pragma unroll
-                for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] *= alpha;
-            }
-            lrow[rb] += (p[0] + p[1]) + (p[2] + p[3]);
-            unsigned int h01, l01, h23, l23;                             // probabilities as hi + lo bf16
-            split2(p[0], p[1], h01, l01);
-            split2(p[2], p[3], h23, l23);
-            const s16x4_t pb = __builtin_bit_cast(s16x4_t, u32x2_t{h01, h23});
-            const s16x4_t pl = __builtin_bit_cast(s16x4_t, u32x2_t{l01, l23});
-            s16x4_t va[4], vb[4];
-#pragma unroll
-            for (int cp = 0; cp < 4; ++cp) {
-                u32x4_t v = vf[slot][cp];
-                if (need_mask) {
-                    // slots past the end of the sequence hold whatever the pool held: 0 * NaN would poison O
-                    unsigned int m01 = (key0 + 0 < total ? 0x0000ffffu : 0u) | (key0 + 1 < total ? 0xffff0000u : 0u);
-                    unsigned int m23 = (key0 + 2 < total ? 0x0000ffffu : 0u) | (key0 + 3 < total ? 0xffff0000u : 0u);
-                    v.x &= m01; v.y &= m23; v.z &= m01; v.w &= m23;
-                }
-                va[cp] = __builtin_bit_cast(s16x4_t, u32x2_t{v.x, v.y});
-                vb[cp] = __builtin_bit_cast(s16x4_t, u32x2_t{v.z, v.w});
-            }
-            // hi products of all 8 channel blocks, then the lo products: no two MFMAs on one accumulator adjacent
-#pragma unroll
-            for (int cp = 0; cp < 4; ++cp) {
-                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[cp], pb, oacc[rb][2 * cp], 0, 0, 0);
-                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb[cp], pb, oacc[rb][2 * cp + 1], 0, 0, 0);
-            }
-#pragma unroll
-            for (int cp = 0; cp < 4; ++cp) {
-                oacc[rb][2 * cp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[cp], pl, oacc[rb][2 * cp], 0, 0, 0);
-                oacc[rb][2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb[cp], pl, oacc[rb][2 * cp + 1], 0, 0, 0);
-            }
-        }
-    };
-
-    // All of this wavefront's physical page ids first (one round trip), then a ring of ATT_DEPTH
-    // pages in flight.  The loads are unconditional - past the wavefront's last page they re-read
-    // it (cache hits, result unused) - because the compiler can only count outstanding loads
-    // along branch-free code; a conditional load makes it drain the queue before every use.
-    int pid[ATT_PPW];
-#pragma unroll
-    for (int it = 0; it < ATT_PPW; ++it) {
-        int pg = page0 + wave + ATT_WAVES * it;
-        pid[it] = pt[pg < page_end ? pg : page_end - 1];
-    }
-#pragma unroll
-    for (int it = 0; it < ATT_DEPTH - 1; ++it) load_page(it, pid[it]);
-#pragma unroll
-    for (int it = 0; it < ATT_PPW; ++it) {
-        constexpr int AHEAD = ATT_DEPTH - 1;
-        load_page((it + AHEAD) % ATT_DEPTH, pid[it + AHEAD < ATT_PPW ? it + AHEAD : ATT_PPW - 1]);
-        const int lpage = page0 + wave + ATT_WAVES * it;
-        if (lpage < page_end) {
-            if ((lpage + 1) * SPEC_PAGE_SIZE > ctx) process(std::true_type{}, it % ATT_DEPTH, lpage);
-            else process(std::false_type{}, it % ATT_DEPTH, lpage);
-        }
-    }
-
-    // per-row sums are spread over the 4 lane groups
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        lrow[rb] = quad_sum(lrow[rb]);
-    }
-
-    // merge the 4 wavefronts through LDS
-    __shared__ float s_o[ATT_WAVES][RB][8][64][4];
-    __shared__ float s_m[ATT_WAVES][RB][16], s_l[ATT_WAVES][RB][16];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-        for (int cb = 0; cb < 8; ++cb)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) s_o[wave][rb][cb][lane][j] = oacc[rb][cb][j];
-        if (lg == 0) { s_m[wave][rb][lq] = mrow[rb]; s_l[wave][rb][lq] = lrow[rb]; }
-    }
-    __syncthreads();
-    const int64_t item = ((int64_t)b * Hkv + kvh) * max_chunks + chunk;
-    float* po = part_o + item * rows * DH;
-    float* pml = part_ml + item * rows * 2;
-    // element e of the tile: (rb, cb, lane', j) -> row rb*16 + lane'%16, channel cb*16 + (lane'/16)*4 + j
-    for (int e = threadIdx.x; e < RB * 8 * 64; e += 256) {
-        int l2 = e & 63, cb = (e >> 6) & 7, rb = e >> 9;
-        int row = l2 & 15;
-        float mw[ATT_WAVES], M = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < ATT_WAVES; ++w) { mw[w] = s_m[w][rb][row]; M = fmaxf(M, mw[w]); }
-        float o4[4] = {0.f, 0.f, 0.f, 0.f}, L = 0.f;
-#pragma unroll
-        for (int w = 0; w < ATT_WAVES; ++w) {
-            float f = mw[w] > -INFINITY ? exp2f(mw[w] - M) : 0.f;
-            L += f * s_l[w][rb][row];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) o4[j] += f * s_o[w][rb][cb][l2][j];
-        }
-        int r = (rb0 + rb) * 16 + row, c = cb * 16 + (l2 >> 4) * 4;
-        *(float4*)(po + (int64_t)r * DH + c) = make_float4(o4[0], o4[1], o4[2], o4[3]);
-        if (cb == 0 && (l2 >> 4) == 0) { pml[r * 2] = M; pml[r * 2 + 1] = L; }
-    }
-}
-
-// The same pass for 3 or 4 row blocks (33..64 query rows per kv head; more rows: RG such workgroups): every K/V block
-// is read once and used for all NRB row blocks.  What no longer fits in registers moves: the queries (hi + lo) sit in
-// LDS in operand order and are re-read per page, the accumulators of all row blocks stay in registers.  The page loop
-// is a run-time loop over groups of ATT_DEPTH pages (the register ring needs compile-time slots, nothing else does),
-// so the code stays a few KiB whatever the chunk length; a wavefront's physical page ids sit in one register, lane j
-// holding its j-th page, and are broadcast with v_readlane.  Pages that need masks (those reaching into the new
-// positions, or past the end of the sequence: the last one or two) are left out of the pipelined loop and done last.
+// part_o : [item][rows][128] fp32, part_ml : [item][rows][2] (reference point in log2 domain, sum relative to it)
+// item = (b * Hkv + kvh) * max_chunks + chunk;  rows = attn_rows_padded(R)
+// A workgroup takes NRB (1..4) blocks of 16 query rows.  What does not fit in registers for 4 of them moves: the
+// queries (hi + lo) sit in LDS in operand order and are re-read per page (double buffered, one row block ahead),
+// the accumulators of all row blocks stay in registers.  More than 64 query rows per kv head (deep drafts with many
+// query heads per kv head) are split into RG groups of NRB row blocks, one workgroup each; the groups of a (batch
+// entry, kv head, chunk) re-read the same pages, so they are placed on the same XCD (workgroups go to XCDs
+// round-robin by linear id: blockIdx.x spans a multiple of 8 values - kv head and the low bits of the batch index -
+// and the row group sits in blockIdx.y, 8 ids apart) and next to each other in dispatch order: the repeated reads
+// hit that XCD's L2.
+// The page loop is a run-time loop over groups of ATT_DEPTH pages (the register ring needs compile-time slots,
+// nothing else does), so the code stays a few KiB whatever the chunk length; a wavefront's physical page ids sit
+// in one register, lane j holding its j-th page, and are broadcast with v_readlane.  Pages that need masks (those
+// reaching into the new positions, or past the end of the sequence: the last one or two) are left out of the
+// pipelined loop and done last.
 template <int NRB>
-__global__ __launch_bounds__(256, 1) void attn_wide_kernel(
+__global__ __launch_bounds__(256, NRB == 1 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
     int layer_pool, float scale_log2, int max_chunks, int chunk_pages, int RG, int rows, int Hkv, int BP, int B,
     float* __restrict__ part_o, float* __restrict__ part_ml)
@@ -388,8 +173,22 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(
     };
     load_q(0, 0);
 
-    auto process = [&](auto mask_c, int slot, int logical_page) {
+    // One page for all row blocks.  The exponentials are taken against a reference point per row, which only has to
+    // keep them in range; three ways of handling it (MODE):
+    //   REF_INIT  : first page of the wavefront - the reference becomes this page's row maximum;
+    //   REF_FIXED : the reference stays where it is, whatever the scores (fp32 has 2^127 of headroom; the largest
+    //               exponent seen is tracked in mrel and checked after the loop).  No branch, no rescaling: the
+    //               accumulators are touched by MFMAs only, which is what lets them stay in the accumulation
+    //               registers without copies;
+    //   REF_ADAPT : the reference follows the running maximum in steps of 2^8 and the accumulators are rescaled in
+    //               place when it moves (masked pages, and the recomputation after an exponent check failed).
+    constexpr int REF_INIT = 0, REF_FIXED = 1, REF_ADAPT = 2;
+    float mrel[NRB];                                  // largest (score - reference) this lane has seen, log2 units
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) mrel[rb] = -INFINITY;
+    auto process = [&](auto mask_c, auto mode_c, int slot, int logical_page) {
         constexpr bool need_mask = decltype(mask_c)::value;
+        constexpr int MODE = decltype(mode_c)::value;
         const int key0 = logical_page * SPEC_PAGE_SIZE + lg * 4;
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
@@ -404,11 +203,7 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(
                 sacc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[rb & 1][sg], sacc2, 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            {
-                constexpr int dummy = 0; (void)dummy;
-                const int nrb = rb + 1 < NRB ? rb + 1 : 0;
-                load_q(nrb & 1, nrb);
-            }
+            load_q((rb + 1 < NRB ? rb + 1 : 0) & 1, rb + 1 < NRB ? rb + 1 : 0);
             __builtin_amdgcn_sched_barrier(0);
             sacc += sacc2;
             float sv[4];
@@ -417,36 +212,38 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(
                 sv[j] = sacc[j] * scale_log2;
                 if (need_mask && key0 + j > row_limit[rb]) sv[j] = -INFINITY;
             }
-            const float mx = quad_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])));
-            // The reference point of the exponentials only has to keep them in range, so it moves only when the
-            // maximum has grown by more than 2^8 (after the first pages: hardly ever), and the accumulators are
-            // rescaled in place then.
-#ifndef ATT_NO_RESCALE
-            if (__builtin_amdgcn_ballot_w64(mx > mrow[rb] + 8.0f) != 0) {
-                // the accumulators were last written by MFMAs of the previous page: far more than the 18 wait
-                // states an accumulator read needs after one, but the assembler block is opaque to the compiler's
-                // hazard pass, so spell them out
-                asm volatile("s_nop 15\n\ts_nop 15");
-                const float mnew = fmaxf(mrow[rb], mx);
-                const float alpha = mnew > -INFINITY ? __builtin_amdgcn_exp2f(mrow[rb] - mnew) : 1.0f;
-                mrow[rb] = mnew;
-                lrow[rb] *= alpha;
+            if (MODE != REF_FIXED) {
+                const float mx = quad_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])));
+                if (MODE == REF_INIT) {
+                    mrow[rb] = mx;
+                } else if (__builtin_amdgcn_ballot_w64(mx > mrow[rb] + 8.0f) != 0) {
+                    // the accumulators were last written by MFMAs of the previous page: far more than the 18 wait
+                    // states an accumulator read needs after one, but the assembler block is opaque to the
+                    // compiler's hazard pass, so spell them out
+                    asm volatile("s_nop 15\n\ts_nop 15");
+                    const float mnew = fmaxf(mrow[rb], mx);
+                    const float alpha = mnew > -INFINITY ? __builtin_amdgcn_exp2f(mrow[rb] - mnew) : 1.0f;
+                    mrow[rb] = mnew;
+                    lrow[rb] *= alpha;
 #pragma unroll
-                for (int cb = 0; cb < 8; ++cb)
+                    for (int cb = 0; cb < 8; ++cb)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        // in place, in the accumulation registers (with a plain multiply the compiler moves the
-                        // whole accumulator to the vector registers and back on both sides of this branch)
-                        float t;
-                        asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %2, %1\n\tv_accvgpr_write_b32 %0, %1"
-                                     : "+a"(oacc[rb][cb][j]), "=&v"(t) : "v"(alpha));
-                    }
+                        for (int j = 0; j < 4; ++j) {
+                            // in place, in the accumulation registers
+                            float t;
+                            asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %2, %1\n\tv_accvgpr_write_b32 %0, %1"
+                                         : "+a"(oacc[rb][cb][j]), "=&v"(t) : "v"(alpha));
+                        }
+                }
             }
-#endif
             const float msafe = mrow[rb] > -INFINITY ? mrow[rb] : 0.f;
             float p[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) p[j] = __builtin_amdgcn_exp2f(sv[j] - msafe);
+            for (int j = 0; j < 4; ++j) {
+                const float e = sv[j] - msafe;
+                if (MODE == REF_FIXED) mrel[rb] = fmaxf(mrel[rb], e);
+                p[j] = __builtin_amdgcn_exp2f(e);
+            }
             lrow[rb] += (p[0] + p[1]) + (p[2] + p[3]);
             unsigned int h01, l01, h23, l23;
             split2(p[0], p[1], h01, l01);
@@ -477,32 +274,59 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(
             }
         }
     };
+    using plain_t = std::false_type;
+    using masked_t = std::true_type;
+    using init_t = std::integral_constant<int, REF_INIT>;
+    using fixed_t = std::integral_constant<int, REF_FIXED>;
+    using adapt_t = std::integral_constant<int, REF_ADAPT>;
 
-    // mask-free pages of this wavefront: page0 + wave + 4 * it, it < n_plain.  Ring of ATT_DEPTH pages; the main
-    // loop takes whole groups of ATT_DEPTH pages and has no branch in its body, so that the compiler can count the
-    // loads in flight exactly; the last one or two pages follow it.  Loads past the wavefront's last page re-read
-    // its clamped id (cache hits, results unused).
+    // mask-free pages of this wavefront: page0 + wave + 4 * it, it < n_plain.  Ring of ATT_DEPTH pages (page `it` in
+    // slot it % 3); the first page sets the reference points, the main loop then takes whole groups of three pages
+    // and has no branch in its body, so that the compiler can count the loads in flight exactly; the last one or two
+    // pages follow it.  Loads past the wavefront's last page re-read its clamped id (cache hits, results unused).
     static_assert(ATT_DEPTH == 3, "the loop body below is written for a ring of 3");
     const int n_plain = plain_end > page0 + wave ? (plain_end - page0 - wave + ATT_WAVES - 1) / ATT_WAVES : 0;
-    load_page(0, pid_at(0));
-    load_page(1, pid_at(1));
-    int it = 0;
-    for (; it + 3 <= n_plain; it += 3) {
-        load_page(2, pid_at(it + 2));
-        process(std::false_type{}, 0, page0 + wave + ATT_WAVES * it);
-        load_page(0, pid_at(it + 3));
-        process(std::false_type{}, 1, page0 + wave + ATT_WAVES * (it + 1));
-        load_page(1, pid_at(it + 4));
-        process(std::false_type{}, 2, page0 + wave + ATT_WAVES * (it + 2));
+    auto lpage_of = [&](int it) { return page0 + wave + ATT_WAVES * it; };
+    if (n_plain > 0) {
+        load_page(0, pid_at(0));
+        load_page(1, pid_at(1));
+        load_page(2, pid_at(2));
+        process(plain_t{}, init_t{}, 0, lpage_of(0));
+        int it = 1;
+        for (; it + 3 <= n_plain; it += 3) {
+            load_page(0, pid_at(it + 2));
+            process(plain_t{}, fixed_t{}, 1, lpage_of(it));
+            load_page(1, pid_at(it + 3));
+            process(plain_t{}, fixed_t{}, 2, lpage_of(it + 1));
+            load_page(2, pid_at(it + 4));
+            process(plain_t{}, fixed_t{}, 0, lpage_of(it + 2));
+        }
+        if (it < n_plain) process(plain_t{}, fixed_t{}, 1, lpage_of(it));
+        if (it + 1 < n_plain) process(plain_t{}, fixed_t{}, 2, lpage_of(it + 1));
+        // exponent check: 2^100 per term leaves room for the sums; beyond it, start over with the moving reference
+        bool redo = false;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) redo = redo || mrel[rb] > 100.0f;
+        if (__builtin_amdgcn_ballot_w64(redo) != 0) {
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) {
+                mrow[rb] = -INFINITY;
+                lrow[rb] = 0.f;
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            }
+            for (int it2 = 0; it2 < n_plain; ++it2) {
+                load_page(0, pid_at(it2));
+                process(plain_t{}, adapt_t{}, 0, lpage_of(it2));
+            }
+        }
     }
-    if (it < n_plain) process(std::false_type{}, 0, page0 + wave + ATT_WAVES * it);
-    if (it + 1 < n_plain) process(std::false_type{}, 1, page0 + wave + ATT_WAVES * (it + 1));
     // masked pages of the chunk (at most two in all: T <= 16), each by the wavefront whose turn it is
     {
         const int t0 = plain_end > page0 ? plain_end : page0;
         for (int lp = t0 + ((wave - (t0 - page0)) & (ATT_WAVES - 1)); lp < page_end; lp += ATT_WAVES) {
-            load_page(2, pt[lp]);
-            process(std::true_type{}, 2, lp);
+            load_page(0, pt[lp]);
+            process(masked_t{}, adapt_t{}, 0, lp);
         }
     }
 
@@ -581,72 +405,74 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
     xp_store8(xp, b * T + r / G, (kvh * G + r % G) * DH + c8 * 8, mb_pad, res);
 }
 
-// How R query rows per kv head are laid over workgroups.
-//   up to 32 rows : the unrolled kernel, 1 or 2 row blocks in registers (queries too), 64-page chunks
-//   more          : RG workgroups of 3 or 4 row blocks each (attn_wide_kernel), 64-page chunks
-// tuning parameter attn_row_blocks = 1 or 2 forces the unrolled kernel with that many blocks per workgroup and row
-// groups beyond (groups of 16 rows then take 32-page chunks, which measured faster there); attn_chunk_pages
-// overrides the chunk length (32 or 64).
-struct AttnPlan { bool wide; int RB, RG, chunk_pages; };
-static AttnPlan attn_plan(int R)
+// How R query rows per kv head are laid over workgroups: RG groups of NRB row blocks, NRB <= 4 and as equal as
+// possible (tuning parameter attn_row_blocks = 1..4 caps NRB instead), and the chunk length: the longest of 32, 64,
+// 128, 256 pages that still leaves about two rounds of workgroups for the chip - longer chunks mean fewer
+// prologues, merges and partial results per byte.  The contexts are only known on the device; the host's bound on
+// the longest one stands in for all of them.  attn_chunk_pages overrides (a multiple of 4, at most 256).
+struct AttnPlan { int RB, RG, chunk_pages; };
+static AttnPlan attn_plan(int R, int B, int Hkv, int pages_bound)
 {
     const int blocks = (int)cdiv(R, 16);
     const int forced = tune("attn_row_blocks");
     AttnPlan p;
-    if (forced == 1 || forced == 2 || blocks <= 2) {
-        p.wide = false;
-        p.RB = blocks <= 1 ? 1 : (forced == 1 || forced == 2 ? forced : blocks);
+    if (forced >= 1 && forced <= 4) {
+        p.RB = forced < blocks ? forced : blocks;
         p.RG = (int)cdiv(blocks, p.RB);
-        p.chunk_pages = p.RG > 1 ? 32 : ATT_CP_DEFAULT;
     } else {
-        p.wide = true;
         p.RG = (int)cdiv(blocks, 4);
         p.RB = (int)cdiv(blocks, p.RG);
-        p.chunk_pages = ATT_CP_DEFAULT;
     }
+    const int64_t slots = 256 * (p.RB == 1 ? 2 : 1);         // workgroups resident at once
+    p.chunk_pages = ATT_CP_MIN;
+    for (int c = 2 * ATT_CP_MIN; c <= 256; c *= 2)
+        if ((int64_t)B * Hkv * p.RG * cdiv(pages_bound, c) >= 2 * slots) p.chunk_pages = c;
     const int cp = tune("attn_chunk_pages");
-    if (cp == 32 || cp == 64) p.chunk_pages = cp;
+    if (cp >= 4 && cp <= 256 && cp % ATT_WAVES == 0) p.chunk_pages = cp;
     return p;
 }
 
-int attn_chunk_pages(int R) { return attn_plan(R).chunk_pages; }
+// the shortest chunk any launch of R query rows per kv head may use: sizes the partial-result buffers
+int attn_min_chunk_pages(int R)
+{
+    const int cp = tune("attn_chunk_pages");
+    if (cp >= 4 && cp <= 256 && cp % ATT_WAVES == 0 && cp < ATT_CP_MIN) return cp;
+    return ATT_CP_MIN;
+}
 
 // rows of a partial tile for R query rows per kv head: enough for every layout above (the workspace is sized before
 // the tuning parameters are final)
 int attn_rows_padded(int R)
 {
     const int blocks = (int)cdiv(R, 16);
-    if (blocks <= 2) return blocks * 16;
-    const int rg = (int)cdiv(blocks, 4);
-    const int wide = rg * (int)cdiv(blocks, rg);
-    const int pairs = (int)cdiv(blocks, 2) * 2;
-    return (wide > pairs ? wide : pairs) * 16;
+    int most = blocks;
+    for (int n = 1; n <= 4 && n <= blocks; ++n) most = std::max(most, (int)cdiv(blocks, n) * n);
+    return most * 16;
 }
 
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
-                                  const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
+                                  const KvView& kv, int layer_pool, int pages_bound, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s)
 {
     int R = T * G;
     if (R > 256) { set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 256", R); return SPEC_EUNSUPPORTED; }
     const int rows = attn_rows_padded(R);
-    const AttnPlan pl = attn_plan(R);
+    const AttnPlan pl = attn_plan(R, B, Hkv, pages_bound);
     const int RG = pl.RG, cp = pl.chunk_pages;
+    const int max_chunks = (int)cdiv(pages_bound, cp);
     float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
     int BP = 1;                                   // batch entries folded into blockIdx.x so that it spans a multiple of 8
     while ((Hkv * BP) % 8 != 0) BP *= 2;
     dim3 grid((unsigned)(Hkv * BP), (unsigned)(RG * cdiv(B, BP)), (unsigned)max_chunks);
     const float* qq = q;
-    if (pl.wide) {
-#define SPEC_ATTN_WIDE(NRBV) attn_wide_kernel<NRBV><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, cp, RG, rows, Hkv, BP, B, part_o, part_ml)
-        if (pl.RB == 3) SPEC_ATTN_WIDE(3); else SPEC_ATTN_WIDE(4);
-#undef SPEC_ATTN_WIDE
-    } else {
-#define SPEC_ATTN_LAUNCH(RBV, CPV) attn_partial_kernel<RBV, CPV><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, RG, rows, Hkv, BP, B, part_o, part_ml)
-        if (pl.RB == 1) { if (cp == 32) SPEC_ATTN_LAUNCH(1, 32); else SPEC_ATTN_LAUNCH(1, 64); }
-        else { if (cp == 32) SPEC_ATTN_LAUNCH(2, 32); else SPEC_ATTN_LAUNCH(2, 64); }
-#undef SPEC_ATTN_LAUNCH
+#define SPEC_ATTN_LAUNCH(NRBV) attn_partial_kernel<NRBV><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, cp, RG, rows, Hkv, BP, B, part_o, part_ml)
+    switch (pl.RB) {
+    case 1: SPEC_ATTN_LAUNCH(1); break;
+    case 2: SPEC_ATTN_LAUNCH(2); break;
+    case 3: SPEC_ATTN_LAUNCH(3); break;
+    default: SPEC_ATTN_LAUNCH(4); break;
     }
+#undef SPEC_ATTN_LAUNCH
     SPEC_LAUNCH_CHECK("attn_partial_kernel");
     prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);

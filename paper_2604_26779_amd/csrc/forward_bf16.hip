@@ -21,7 +21,7 @@ int gemm_mb_pad(int M);
 int gemm_pick_splits(const PackedW& W, int M, int forced);
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s);
 bool gemm_can_fuse_swiglu(int M, int splits);
-int attn_chunk_pages(int R);
+int attn_min_chunk_pages(int R);
 int attn_rows_padded(int R);
 int moe_rows_bound(int M, int top_k, int E);
 spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, const bf16_t* Xp, int rows_pad, int max_tiles,
@@ -33,7 +33,7 @@ spec_status launch_moe_gather(const bf16_t* xp_src, int mb_pad_src, const int32_
 spec_status launch_moe_combine_norm(float* x, const float* y, const int32_t* pair_row, const float* wts, int M, int top_k,
                                     const void* gain, int d, float eps, int mb_pad, bf16_t* xp, hipStream_t s);
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
-                                  const KvView& kv, int layer_pool, int max_chunks, float* part_o, float* part_ml,
+                                  const KvView& kv, int layer_pool, int pages_bound, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s);
 
 // sum over the workgroup (blockDim.x a multiple of 64, at most 1024)
@@ -223,7 +223,7 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.mb_pad = gemm_mb_pad(p.M);
     int G = d.n_q_heads / d.n_kv_heads;
     p.RBrows = attn_rows_padded(T * G);
-    p.max_chunks = (int)cdiv(cdiv(max_ctx_plus, SPEC_PAGE_SIZE), attn_chunk_pages(T * G));
+    p.max_chunks = (int)cdiv(cdiv(max_ctx_plus, SPEC_PAGE_SIZE), attn_min_chunk_pages(T * G));   // the most any launch may use
     if (p.max_chunks < 1) p.max_chunks = 1;
     p.s_qkv = gemm_pick_splits(m->wqkv[0], p.M, tune("splits_qkv"));
     p.s_o = gemm_pick_splits(m->wo[0], p.M, tune("splits_o"));
@@ -280,9 +280,10 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     // the chunks the current bound on the longest sequence needs
     Bf16Plan p = make_plan(mdl, B, k, (int64_t)kv->max_pages * SPEC_PAGE_SIZE);
     if (p.total > ws_bytes) { set_error("spec_verify_forward: workspace too small for the current split settings (%zu < %zu)", ws_bytes, p.total); return SPEC_EINVAL; }
-    int live_chunks = (int)cdiv(cdiv(kv->ub.max_ctx + T, SPEC_PAGE_SIZE), attn_chunk_pages(T * G));
-    if (live_chunks > p.max_chunks) live_chunks = p.max_chunks;
-    if (live_chunks < 1) live_chunks = 1;
+    // pages of the longest live context (the host's bound), capped by what the buffers were sized for
+    int live_pages = (int)cdiv(kv->ub.max_ctx + T, SPEC_PAGE_SIZE);
+    if (live_pages > p.max_chunks * attn_min_chunk_pages(T * G)) live_pages = p.max_chunks * attn_min_chunk_pages(T * G);
+    if (live_pages < 1) live_pages = 1;
 
     char* base = (char*)ws;
     float* x = (float*)(base + p.off_x);
@@ -311,7 +312,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         prof_mark(PC_GEMM_QKV, s);
         qkv_rope_kernel<<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, qbuf);
         prof_mark(PC_QKV_ROPE, s);
-        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_chunks, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
+        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_pages, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
         if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_O, s);
         residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,

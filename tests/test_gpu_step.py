@@ -263,7 +263,7 @@ def test_forward_argument_errors_and_pool_exhaustion():
     assert e.value.status == sv.SPEC_EUNSUPPORTED
 
 
-def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, **model_changes):
+def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, key_scale_fn=None, **model_changes):
     """small_bf16 model, synthetic cache, explicit context lengths: returns (max err, worst over tolerance)."""
     from paper_2604_26779_amd.session import VerifySession
     cfg = dict(si.MODELS["small_bf16"])
@@ -277,6 +277,9 @@ def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, **model_cha
     kv = si.make_logical_kv(cfg, ctx_len, seed=seed)
     if key_scale != 1.0:        # larger cached keys -> larger scores -> a peaked softmax (a few keys carry the weight)
         kv = [[((K.float() * key_scale).to(K.dtype), V) for (K, V) in per_seq] for per_seq in kv]
+    if key_scale_fn is not None:    # a scale per cached position: key_scale_fn(ctx) -> [ctx] factors
+        kv = [[((K.float() * torch.as_tensor(key_scale_fn(K.shape[0]), dtype=torch.float32).view(-1, 1, 1)).to(K.dtype), V)
+               for (K, V) in per_seq] for per_seq in kv]
     kv_or = si.kv_for_oracle(kv)
     rng = np.random.default_rng(seed)
     n_ctx_pages = [-(-int(c) // si.PAGE_SIZE) for c in ctx_len]
@@ -343,3 +346,40 @@ def test_bf16_peaked_attention(key_scale):
     ok, max_err, worst = _run_custom_bf16(ctx, k=3, seed=21, vocab=1000, key_scale=key_scale)
     print("key scale %.0f: logits max abs err %.3e" % (key_scale, max_err))
     assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("row_blocks,chunk_pages", [(1, 4), (2, 12), (3, 32), (4, 256), (0, 8)])
+def test_bf16_attention_layouts(row_blocks, chunk_pages):
+    """96 query rows per kv head (6 row blocks) under every way of laying them over workgroups (1..4 row blocks per
+    workgroup, 6 / 3 / 2 / 2 groups) and chunk lengths from 4 pages (many chunks, wavefronts with one page or none)
+    to 256 (one chunk, up to 11 pages per wavefront: whole groups of three, remainders of one and two)."""
+    from paper_2604_26779_amd import binding as sv
+    sv.spec_tune_set("attn_row_blocks", row_blocks)
+    sv.spec_tune_set("attn_chunk_pages", chunk_pages)
+    try:
+        ctx = [0, 5, 16, 63, 64, 65, 130, 255, 300, 517, 700]
+        ok, max_err, worst = _run_custom_bf16(ctx, k=5, seed=31 + row_blocks, vocab=1000, n_q_heads=16, n_kv_heads=1)
+    finally:
+        sv.spec_tune_set("attn_row_blocks", 0)
+        sv.spec_tune_set("attn_chunk_pages", 0)
+    print("row blocks %d, chunk %d pages: logits max abs err %.3e" % (row_blocks, chunk_pages, max_err))
+    assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("case", ["late_keys_huge", "last_page_large"])
+def test_bf16_attention_reference_point_moves(case):
+    """The attention keeps the exponentials' reference point of a wavefront where its first page put it and checks
+    the exponent range afterwards.  late_keys_huge: keys from position 64 on are 150 times larger, so the scores
+    outgrow the first pages' by hundreds of units: the range check fails and the chunk is recomputed with the moving
+    reference.  last_page_large: only the keys of the last, partial page are 12 times larger: the masked pages'
+    moving reference steps up and rescales the accumulators."""
+    if case == "late_keys_huge":
+        fn = lambda n: np.where(np.arange(n) >= 64, 150.0, 1.0)
+    else:
+        fn = lambda n: np.where(np.arange(n) >= 16 * (n // 16), 12.0, 1.0)
+    ctx = [70, 200, 333, 519, 1000, 1531]
+    for heads in [(8, 2), (16, 1)]:
+        ok, max_err, worst = _run_custom_bf16(ctx, k=3, seed=41, vocab=1000, key_scale_fn=fn, n_q_heads=heads[0],
+                                              n_kv_heads=heads[1])
+        print("%s, Hq/Hkv=%s: logits max abs err %.3e" % (case, heads, max_err))
+        assert ok, (max_err, worst)
