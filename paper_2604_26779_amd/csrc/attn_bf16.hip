@@ -78,7 +78,7 @@ __device__ inline float quad_sum(float x)
 // reaching into the new positions, or past the end of the sequence: the last one or two) are left out of the
 // pipelined loop and done last.
 template <int NRB>
-__global__ __launch_bounds__(256, NRB == 1 ? 2 : 1) void attn_partial_kernel(
+__global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
     int layer_pool, float scale_log2, int max_chunks, int chunk_pages, int RG, int rows, int Hkv, int BP, int B,
     float* __restrict__ part_o, float* __restrict__ part_ml)
@@ -423,7 +423,7 @@ static AttnPlan attn_plan(int R, int B, int Hkv, int pages_bound)
         p.RG = (int)cdiv(blocks, 4);
         p.RB = (int)cdiv(blocks, p.RG);
     }
-    const int64_t slots = 256 * (p.RB == 1 ? 2 : 1);         // workgroups resident at once
+    const int64_t slots = 256 * (p.RB <= 2 ? 2 : 1);         // workgroups resident at once
     p.chunk_pages = ATT_CP_MIN;
     for (int c = 2 * ATT_CP_MIN; c <= 256; c *= 2)
         if ((int64_t)B * Hkv * p.RG * cdiv(pages_bound, c) >= 2 * slots) p.chunk_pages = c;
