@@ -271,6 +271,41 @@ def main():
                                     "accepted_tokens_per_s": round(made / (times[-1] / 1e3), 1),
                                     "mean_acceptance_length": round(made / (S * B), 3)}
         args.no_cpu_baseline = True               # the oracle baseline is reported on the headline workload only
+    else:
+        # model-free n-gram drafter on the same batch: histories of the contexts' lengths over a small alphabet (so
+        # that endings recur), a few consecutive steps of draft -> verify with point-mass drafts -> commit -> history
+        # update.  With random weights nothing is accepted; what is reported is what the drafter and its step cost.
+        from paper_2604_26779_amd.draft import NgramRollout
+        S = args.rollout_steps
+        g = torch.Generator(device="cuda")
+        g.manual_seed(int(wl.seed) + 9)
+        cap = int(wl.ctx_len.max()) + 1 + S * (k + 1)
+        hist = torch.randint(0, 12, (B, cap), generator=g, device="cuda", dtype=torch.int32)
+        hist_len0 = torch.from_numpy((wl.ctx_len + 1).astype("int32")).cuda()
+        roll = NgramRollout(wl.sess, B, k, n_max=3, n_min=1)
+        acc_s = torch.zeros((S, B), dtype=torch.int32, device="cuda")
+        times = []
+        for rep in range(2):                      # first repetition warms up
+            wl.restore()
+            hist_len = hist_len0.clone()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            roll.run(wl.seq_ids, hist, hist_len, S, wl.wl["temperature"], wl.seed, 7000, acc_s)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            sv.spec_ngram_draft(B, k, 3, 1, hist, hist_len0, wl.seq_ids, roll.tokens, roll.n_drafted)
+        e1.record()
+        torch.cuda.synchronize()
+        wl.restore()
+        out["ngram_drafter"] = {"n": "1..3", "steps": S, "ms_per_step": round(times[-1] / S, 4),
+                                "draft_kernel_us": round(1e3 * e0.elapsed_time(e1) / 20, 2),
+                                "rows_with_an_occurrence": int((roll.n_drafted > 0).sum().item()),
+                                "mean_acceptance_length": round(float((acc_s + 1).sum().item()) / (S * B), 3)}
     if not args.no_cpu_baseline:
         base, _ = cpu_baseline(wl, torch, args.cpu_seqs)
         out["cpu_baseline"] = {kk: (round(v, 3) if isinstance(v, float) else v) for kk, v in base.items()}

@@ -271,6 +271,36 @@ spec_status spec_profile_begin(int32_t max_events);
 spec_status spec_profile_end(double* host_ms, int64_t* host_counts, int32_t n);
 
 /*
+ * Model-free n-gram drafting (the paper's n-gram baseline: Section 3.1 set-up, Section 3.2 and Table 2; the paper
+ * gives no algorithm - this is prompt-lookup drafting): the drafts of a step are copied from the sequence's own
+ * token history, from behind the most recent earlier occurrence of its current ending.
+ *
+ * dev_hist [n_rows, hist_stride] int32 (device) holds one history per row, dev_hist_len [n_rows] its length L; the
+ * last token h[L-1] is the one the verifier emitted last.  Batch entry b uses row dev_seq_ids[b] (row b if
+ * dev_seq_ids is NULL).  For n = n_max down to n_min (1 <= n_min <= n_max <= 16) the ending h[L-n..L-1] is searched
+ * at start positions j with j + n <= L - 1 (a token follows the occurrence; it may overlap the ending); the longest
+ * n with an occurrence wins, among its occurrences the largest j.  Output, for the [B, k+1] token array of
+ * spec_verify_forward: dev_tokens[b][0] = h[L-1]; dev_tokens[b][1..c] = h[j+n .. j+n+c-1] with
+ * c = min(k, L - (j+n)); the slots c+1..k repeat the last drafted token; dev_n_drafted[b] = c (may be NULL).
+ * Without an occurrence c = 0 and every slot holds h[L-1].  A row index outside [0, n_rows) or an empty history
+ * gives c = -1 and zeros.  Such drafts are point masses: verify them with spec_reject_sample(dev_q = NULL).
+ * Integer work, bit-exact.  Asynchronous on `stream`; nothing is allocated.
+ */
+spec_status spec_ngram_draft(int32_t B, int32_t k, int32_t n_max, int32_t n_min, const int32_t* dev_hist,
+                             int64_t hist_stride, int32_t n_rows, const int32_t* dev_hist_len, const int32_t* dev_seq_ids,
+                             int32_t* dev_tokens, int32_t* dev_n_drafted, void* stream);
+
+/*
+ * After a verify step the accepted drafts and the emitted token join the history: row r of batch entry b gets
+ * dev_out_tokens[b][0..n], n = dev_accept_len[b] clamped to [0, k], appended at dev_hist_len[r], which advances.
+ * A history that reaches hist_stride tokens keeps what fits (its length saturates).  Rows outside [0, n_rows) are
+ * skipped.  Two batch entries must not name the same row.  Asynchronous on `stream`.
+ */
+spec_status spec_ngram_append(int32_t B, int32_t k, int32_t* dev_hist, int64_t hist_stride, int32_t n_rows,
+                              int32_t* dev_hist_len, const int32_t* dev_seq_ids, const int32_t* dev_out_tokens,
+                              const int32_t* dev_accept_len, void* stream);
+
+/*
  * Replay of a recorded sequence of step calls (for callers whose steps are short enough that launching ~350 small
  * kernels per step costs more than running them).  Between spec_graph_capture_begin and spec_graph_capture_end every
  * call of this library on `stream` (which must not be the default stream) is recorded instead of executed; the

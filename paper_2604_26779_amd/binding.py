@@ -24,7 +24,7 @@ EXPORTS = [
     "spec_kv_alloc", "spec_kv_free", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_sample_workspace_bytes", "spec_reject_sample",
-    "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
+    "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_graph_capture_begin", "spec_graph_capture_end", "spec_graph_launch",
     "spec_graph_destroy", "spec_calib_read", "spec_calib_copy",
 ]
@@ -81,6 +81,8 @@ def lib():
             "spec_draft_sample": (i32, [i32, i32, vp, i64, f32, u64, u64, i32, vp, i32, vp, i32, vp, i64, vp]),
             "spec_kv_truncate": (i32, [vp, i32, vp, vp, i32, vp, vp]),
             "spec_next_step_inputs": (i32, [i32, i32, vp, vp, vp, vp, vp]),
+            "spec_ngram_draft": (i32, [i32, i32, i32, i32, vp, i64, i32, vp, vp, vp, vp, vp]),
+            "spec_ngram_append": (i32, [i32, i32, vp, i64, i32, vp, vp, vp, vp, vp]),
             "spec_tune_set": (i32, [ctypes.c_char_p, i32]),
             "spec_tune_get": (i32, [ctypes.c_char_p]),
             "spec_profile_class_count": (i32, []),
@@ -256,6 +258,17 @@ def spec_kv_truncate(kv, B, seq_ids, lengths, delta, new_len, stream=None):
 
 def spec_next_step_inputs(B, k, tokens, out_tokens, accept_len, pending, stream=None):
     _check(lib().spec_next_step_inputs(B, k, _ptr(tokens), _ptr(out_tokens), _ptr(accept_len), _ptr(pending), _stream(stream)))
+
+
+def spec_ngram_draft(B, k, n_max, n_min, hist, hist_len, seq_ids, tokens, n_drafted, stream=None):
+    """hist [n_rows, cap] int32, hist_len [n_rows], tokens [B, k+1] (out), n_drafted [B] or None."""
+    _check(lib().spec_ngram_draft(B, k, int(n_max), int(n_min), _ptr(hist), int(hist.shape[1]), int(hist.shape[0]), _ptr(hist_len),
+                                  _ptr(seq_ids), _ptr(tokens), _ptr(n_drafted), _stream(stream)))
+
+
+def spec_ngram_append(B, k, hist, hist_len, seq_ids, out_tokens, accept_len, stream=None):
+    _check(lib().spec_ngram_append(B, k, _ptr(hist), int(hist.shape[1]), int(hist.shape[0]), _ptr(hist_len), _ptr(seq_ids),
+                                   _ptr(out_tokens), _ptr(accept_len), _stream(stream)))
 
 
 def spec_tune_set(name, value):

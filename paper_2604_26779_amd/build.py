@@ -13,7 +13,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libspecverify.so")
-SOURCES = ["api.hip", "kvbook.hip", "sampler.hip", "forward_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "moe.hip",
+SOURCES = ["api.hip", "kvbook.hip", "sampler.hip", "forward_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "moe.hip", "ngram.hip",
            "forward_bf16.hip", "calib.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -59,7 +59,7 @@ void prof_record(int cls, hipStream_t s)
 
 static const char* const PROF_NAMES[PC_COUNT] = {
     "other", "embed_norm", "gemm_qkv", "qkv_rope", "attn", "attn_reduce", "gemm_o", "resid_norm", "gemm_gu", "swiglu",
-    "gemm_down", "gemm_head", "sample_stats", "sample_draw", "kv_reserve", "kv_commit", "draft_sample", "kv_truncate", "moe_route", "moe_gather"};
+    "gemm_down", "gemm_head", "sample_stats", "sample_draw", "kv_reserve", "kv_commit", "draft_sample", "kv_truncate", "moe_route", "moe_gather", "ngram"};
 
 }  // namespace specv
 

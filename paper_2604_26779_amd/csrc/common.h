@@ -18,7 +18,7 @@ int tune(const char* name);
 enum ProfClass {
     PC_OTHER = 0, PC_EMBED_NORM, PC_GEMM_QKV, PC_QKV_ROPE, PC_ATTN, PC_ATTN_REDUCE, PC_GEMM_O, PC_RESID_NORM,
     PC_GEMM_GU, PC_SWIGLU, PC_GEMM_DOWN, PC_GEMM_HEAD, PC_SAMPLE_STATS, PC_SAMPLE_DRAW, PC_KV_RESERVE, PC_KV_COMMIT,
-    PC_DRAFT_SAMPLE, PC_KV_TRUNCATE, PC_MOE_ROUTE, PC_MOE_GATHER, PC_COUNT
+    PC_DRAFT_SAMPLE, PC_KV_TRUNCATE, PC_MOE_ROUTE, PC_MOE_GATHER, PC_NGRAM, PC_COUNT
 };
 extern bool g_prof_on;
 void prof_record(int cls, hipStream_t s);

@@ -94,3 +94,35 @@ class RolloutLoop:
             sv.spec_commit_kv(t.kv, B, k, seq_ids, acc, buf["new_ctx_len"], None, stream)
             self.loop.roll_back(seq_ids, buf["new_ctx_len"], stream)
             sv.spec_next_step_inputs(B, k, self.tokens, out, acc, self.pending, stream)
+
+
+class NgramRollout:
+    """Consecutive speculation steps with the model-free n-gram drafter, on one stream with no host round trip:
+    drafts from the histories -> verify forward -> rejection sampling with point-mass drafts -> commit -> history
+    update.  Only call order and buffers are handled here; histories are rows of a caller-owned [n_rows, cap]
+    int32 device array, batch entry b using row seq_ids[b]."""
+
+    def __init__(self, target_session, B, k, n_max=3, n_min=1):
+        self.t, self.B, self.k, self.n_max, self.n_min = target_session, int(B), int(k), int(n_max), int(n_min)
+        dev = target_session.device
+        self.tokens = torch.zeros((B, k + 1), dtype=torch.int32, device=dev)
+        self.drafts = torch.zeros((B, k), dtype=torch.int32, device=dev)
+        self.n_drafted = torch.zeros(B, dtype=torch.int32, device=dev)
+
+    def run(self, seq_ids, hist, hist_len, n_steps, temperature, seed, step0=0, accept_out=None, tokens_out=None, stream=None):
+        t, B, k = self.t, self.B, self.k
+        V = t.cfg["vocab"]
+        buf = t.step_buffers(B, k)
+        ws = buf["workspace"]
+        off = (-ws.data_ptr()) % 256
+        ws = ws[off:off + ws.numel() - 256]
+        for s in range(n_steps):
+            sv.spec_ngram_draft(B, k, self.n_max, self.n_min, hist, hist_len, seq_ids, self.tokens, self.n_drafted, stream)
+            self.drafts.copy_(self.tokens[:, 1:])
+            acc = accept_out[s] if accept_out is not None else buf["accept_len"]
+            out = tokens_out[s] if tokens_out is not None else buf["out_tokens"]
+            sv.spec_verify_forward(t.model, t.kv, B, k, seq_ids, self.tokens, buf["logits"], ws, stream)
+            sv.spec_reject_sample(B, k, V, buf["logits"], None, self.drafts, temperature, seed, step0 + s, acc, out, None,
+                                  buf["sample_ws"], stream)
+            sv.spec_commit_kv(t.kv, B, k, seq_ids, acc, buf["new_ctx_len"], None, stream)
+            sv.spec_ngram_append(B, k, hist, hist_len, seq_ids, out, acc, stream)
