@@ -1,0 +1,76 @@
+"""Pins of the slot bookkeeping oracle: a hand-worked drain, and invariants over random rollouts that a wrong
+order (slots not served in batch order), a double admission, counting behind the end of a response or a missed
+release would break."""
+import numpy as np
+
+from oracle import commit as oracle_commit
+from oracle import rollout as oro
+
+
+def test_hand_worked_drain():
+    k = 3
+    slot_seq = np.array([0, 1, 2], dtype=np.int32)
+    active = np.array([1, 1, 1], dtype=np.int32)
+    gen = np.zeros(6, dtype=np.int32)
+    target = np.array([2, 5, 9, 3, 4, 1], dtype=np.int32)
+    queue = [3, 4]
+    first = np.array([10, 11, 12, 13, 14, 15], dtype=np.int32)
+    tokens = np.zeros((3, k + 1), dtype=np.int32)
+    # step 1: accept 1, 3, 0 -> seq 0 made min(2, 2) = 2 and retires (slot 0 <- seq 3), seq 1 made 4, seq 2 made 1
+    rel, keep, head, made = oro.retire_and_backfill(slot_seq, active, [1, 3, 0], k, gen, target, queue, 0, first, tokens)
+    assert list(slot_seq) == [3, 1, 2] and list(active) == [1, 1, 1] and head == 1 and made == 7
+    assert list(rel) == [0, 1, 2] and list(keep) == [0, oro.KEEP_ALL, oro.KEEP_ALL] and tokens[0, 0] == 13
+    assert list(gen[:3]) == [2, 4, 1]
+    # step 2: accept 3, 3, 3 -> seq 3 made min(4, 3) = 3 retires (slot 0 <- seq 4); seq 1 made min(4, 1) = 1 retires:
+    # the queue is empty by then, slot 1 idles; seq 2 made 4
+    rel, keep, head, made = oro.retire_and_backfill(slot_seq, active, [3, 3, 3], k, gen, target, queue, head, first, tokens)
+    assert list(slot_seq) == [4, 1, 2] and list(active) == [1, 0, 1] and head == 2 and made == 8
+    assert list(rel) == [3, 1, 2] and list(keep) == [0, 0, oro.KEEP_ALL] and tokens[0, 0] == 14
+    # step 3: the idle slot is released again and counts nothing, whatever its accept length says
+    rel, keep, head, made = oro.retire_and_backfill(slot_seq, active, [0, 3, 0], k, gen, target, queue, head, first, tokens)
+    assert list(rel) == [4, 1, 2] and list(keep) == [oro.KEEP_ALL, 0, oro.KEEP_ALL] and made == 2 and list(active) == [1, 0, 1]
+
+
+def test_random_rollouts_invariants():
+    rng = np.random.default_rng(3)
+    for trial in range(40):
+        B, k = int(rng.integers(1, 9)), int(rng.integers(0, 6))
+        n_seqs = B + int(rng.integers(0, 12))
+        target = rng.integers(1, 30, size=n_seqs).astype(np.int32)
+        first = rng.integers(100, 200, size=n_seqs).astype(np.int32)
+        ctx0 = rng.integers(0, 50, size=n_seqs)
+        book = oracle_commit.KVBook(n_pages=400, page_size=16)
+        for s in range(n_seqs):
+            need = -(-int(ctx0[s]) // 16)
+            book.assign(s, int(ctx0[s]), list(reversed(book.free[len(book.free) - need:])))
+        n_free0 = len(book.free) + sum(len(p) for p in book.pages.values())
+        slot_seq = np.arange(B, dtype=np.int32)
+        active = np.ones(B, dtype=np.int32)
+        queue = list(range(B, n_seqs))
+        gen = np.zeros(n_seqs, dtype=np.int32)
+        tokens = np.zeros((B, k + 1), dtype=np.int32)
+        head, total, admitted = 0, 0, []
+        for step in range(200):
+            if not active.any():
+                break
+            seqs = [int(s) for s in slot_seq]
+            book.reserve(seqs, k)
+            n = rng.integers(0, k + 1, size=B)
+            book.commit(seqs, n, k)
+            before = slot_seq.copy()
+            rel, keep, head2, made = oro.retire_and_backfill(slot_seq, active, n, k, gen, target, queue, head, first, tokens)
+            admitted += queue[head:head2]
+            # slots served in batch order: the admitted sequences land in increasing slot index
+            changed = [b for b in range(B) if slot_seq[b] != before[b]]
+            assert [int(slot_seq[b]) for b in changed] == queue[head:head2]
+            assert all(tokens[b, 0] == first[slot_seq[b]] for b in changed)
+            head = head2
+            total += made
+            book.truncate([int(s) for s in rel], [int(x) for x in keep])
+            for b in range(B):                               # retired and idle sequences hold nothing
+                if keep[b] == 0:
+                    assert book.ctx_len[int(rel[b])] == 0 and book.pages[int(rel[b])] == []
+        assert not active.any() and head == len(queue) and admitted == queue
+        assert np.array_equal(gen, target) and total == int(target.sum())
+        assert len(book.free) + sum(len(p) for p in book.pages.values()) == n_free0       # no page lost or doubled
+        assert all(book.pages[s] == [] for s in range(n_seqs))
