@@ -121,6 +121,76 @@ def cpu_baseline(wl, torch, n_seqs):
                 seconds=dt), logits
 
 
+def run_continuous(args, wl, sv, torch):
+    """Continuous rollout workload: `slots` batch slots over B sequences (the rest wait, prompts cached), long-tailed
+    response lengths, n-gram drafter; timed from the first step until every sequence has finished."""
+    import numpy as np
+
+    import synth_inputs as si
+    from paper_2604_26779_amd.draft import ContinuousRollout
+    from paper_2604_26779_amd.workloads import algorithmic_bytes
+    n_seqs, slots, k = wl.B, wl.wl["slots"], wl.k
+    target = si.response_lengths(wl.wl, wl.seed)
+    max_steps = int(target.sum())                               # one token per live slot and step at the very least
+    g = torch.Generator(device="cuda")
+    g.manual_seed(int(wl.seed) + 9)
+    cap = int(wl.ctx_len.max()) + 1 + int(target.max()) + k + 1
+    hist0 = torch.randint(0, 12, (n_seqs, cap), generator=g, device="cuda", dtype=torch.int32)
+    hist_len0 = torch.from_numpy((wl.ctx_len + 1).astype("int32")).cuda()
+    first = hist0[torch.arange(n_seqs, device="cuda"), (hist_len0 - 1).long()].contiguous()
+    chunk = 16
+    result = None
+    for rep in range(2):                                        # first repetition warms up
+        wl.restore()
+        hist, hist_len = hist0.clone(), hist_len0.clone()
+        roll = ContinuousRollout(wl.sess, slots, k, torch.arange(slots, dtype=torch.int32), torch.from_numpy(target),
+                                 torch.arange(slots, n_seqs, dtype=torch.int32), first)
+        roll.tokens[:, 0] = first[:slots]
+        live = torch.zeros(max_steps + chunk, dtype=torch.int32, device="cuda")
+        if rep == 1:
+            sv.spec_profile_begin((max_steps + chunk) * 420 + 64)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        steps = 0
+        while steps < max_steps:                                # the host looks at the live count every `chunk` steps
+            roll.run(hist, hist_len, chunk, wl.wl["temperature"], wl.seed, 9000 + steps, live[steps:steps + chunk])
+            steps += chunk
+            if int(live[steps - 1].item()) == 0:
+                break
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        live_h = live[:steps].cpu().numpy()
+        used = int(np.argmax(live_h == 0)) + 1 if (live_h == 0).any() else steps
+        result = dict(dt=dt, steps=steps, used=used, live=live_h, produced=int(roll.produced.item()))
+    prof = sv.spec_profile_end()
+    r = result
+    ms_per_step = 1e3 * r["dt"] / r["steps"]
+    gemm_ms = sum(prof[n][0] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head")) / r["steps"]
+    gemm_launches = sum(prof[n][1] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head")) / r["steps"]
+    alg = algorithmic_bytes(wl.cfg, wl.ctx_len[:slots], slots, k)
+    gbs = alg["gemm"] / (gemm_ms / 1e3) / 1e9
+    occupancy = float(r["live"][:r["used"]].mean()) / slots
+    out = {
+        "metric": "accepted tokens/sec/GPU, 8B-shaped verify step k=3; % of HBM/MFMA roofline",
+        "value": round(r["produced"] / r["dt"], 1), "unit": "accepted tokens/s", "n_gpus": 1, "steps": r["steps"], "warmup": 0,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "slots": slots, "sequences": n_seqs, "k": k, "ctx_tokens": int(wl.ctx_len.sum()),
+                   "model": wl.wl["model"], "page_size": 16, "pages": "shuffled", "drafter": "n-gram 1..3"},
+        "continuous_rollout": {
+            "response_tokens": r["produced"], "response_len_min_median_max": [int(target.min()), int(np.median(target)), int(target.max())],
+            "steps_until_drained": r["used"], "mean_live_slot_fraction": round(occupancy, 3),
+            "steps_with_at_most_a_quarter_live": int((r["live"][:r["used"]] <= slots // 4).sum()),
+            "tokens_per_s_if_all_slots_stayed_live": round(slots * 1e3 / ms_per_step, 1),
+            "host_syncs": "one every %d steps (live-slot count)" % chunk},
+        "roofline": dict(kernel="gemm_bf16_kernel", bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                         frac=round(gbs / HBM_PEAK_GBS, 4), avg_launch_us=round(1e3 * gemm_ms / max(gemm_launches, 1), 2),
+                         bytes_per_launch=int(alg["gemm"] / max(gemm_launches, 1)), traffic=None),
+        "ms_per_step_by_class": {n: round(ms / r["steps"], 4) for n, (ms, cnt) in prof.items() if ms > 0},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -149,6 +219,9 @@ def main():
         name, value = item.split("=")
         sv.spec_tune_set(name, int(value))
 
+    if "slots" in si.WORKLOADS[args.workload]:
+        run_continuous(args, DeviceWorkload(args.workload), sv, torch)
+        return
     pair = "draft_model" in si.WORKLOADS[args.workload]
     if pair:
         wl = DraftPairWorkload(args.workload)

@@ -301,6 +301,32 @@ spec_status spec_ngram_append(int32_t B, int32_t k, int32_t* dev_hist, int64_t h
                               const int32_t* dev_accept_len, void* stream);
 
 /*
+ * Slot bookkeeping of a continuous rollout, on the device (the paper's rollouts have long-tailed response lengths,
+ * Section 2.2 / Section 4: batch slots drain unevenly while the decode phase keeps running; the paper describes no
+ * mechanism - this is continuous batching over already prefilled sequences).  Call after spec_commit_kv and
+ * spec_next_step_inputs of a step.  For batch slot b, in batch order:
+ *   live slot (dev_active[b] != 0), sequence s = dev_slot_seq[b], n = dev_accept_len[b] clamped to [0, k]:
+ *     made = min(n + 1, dev_target_len[s] - dev_gen_len[s]) response tokens count (those behind the end of the
+ *     response are dropped); dev_gen_len[s] += made.  If the response is complete the sequence is retired
+ *     (dev_keep_len[b] = 0): the next waiting sequence dev_queue[*dev_queue_head] takes the slot
+ *     (dev_slot_seq[b], *dev_queue_head advance; dev_tokens[b][0] = dev_first_token[new sequence]), or, with the
+ *     queue (queue_len entries) exhausted, the slot goes idle (dev_active[b] = 0, the sequence id stays).
+ *     Otherwise dev_keep_len[b] = 2^30 (keep everything).
+ *   idle slot: counts nothing; dev_keep_len[b] = 0 (whatever later steps cached for it is dropped again).
+ * dev_release_seq[b] receives the sequence the slot held on entry: hand (dev_release_seq, dev_keep_len, delta 0) to
+ * spec_kv_truncate of every cache involved to release the retired sequences' pages.  *dev_produced (int64, device)
+ * is increased by the tokens counted.  Waiting sequences must already hold their prompt's cache
+ * (spec_kv_seq_assign) - prefill is outside this library.  Sequence ids index dev_gen_len, dev_target_len and
+ * dev_first_token (n_seqs entries each); a slot whose sequence id is out of range is treated as idle.
+ * dev_tokens is the [B, k+1] input array of the next spec_verify_forward.  Asynchronous on `stream`.
+ */
+spec_status spec_rollout_retire(int32_t B, int32_t k, int32_t n_seqs, int32_t* dev_slot_seq, int32_t* dev_active,
+                                const int32_t* dev_accept_len, int32_t* dev_gen_len, const int32_t* dev_target_len,
+                                const int32_t* dev_queue, int32_t queue_len, int32_t* dev_queue_head,
+                                const int32_t* dev_first_token, int32_t* dev_tokens, int32_t* dev_release_seq,
+                                int32_t* dev_keep_len, int64_t* dev_produced, void* stream);
+
+/*
  * Replay of a recorded sequence of step calls (for callers whose steps are short enough that launching ~350 small
  * kernels per step costs more than running them).  Between spec_graph_capture_begin and spec_graph_capture_end every
  * call of this library on `stream` (which must not be the default stream) is recorded instead of executed; the

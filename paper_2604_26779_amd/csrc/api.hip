@@ -496,6 +496,26 @@ extern "C" spec_status spec_kv_truncate(spec_kv* kv, int32_t B, const int32_t* d
     return SPEC_OK;
 }
 
+extern "C" spec_status spec_rollout_retire(int32_t B, int32_t k, int32_t n_seqs, int32_t* dev_slot_seq, int32_t* dev_active,
+                                           const int32_t* dev_accept_len, int32_t* dev_gen_len, const int32_t* dev_target_len,
+                                           const int32_t* dev_queue, int32_t queue_len, int32_t* dev_queue_head,
+                                           const int32_t* dev_first_token, int32_t* dev_tokens, int32_t* dev_release_seq,
+                                           int32_t* dev_keep_len, int64_t* dev_produced, void* stream)
+{
+    if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT || n_seqs < 1 || queue_len < 0) { set_error("spec_rollout_retire: size out of range"); return SPEC_EINVAL; }
+    if (!dev_slot_seq || !dev_active || !dev_accept_len || !dev_gen_len || !dev_target_len || !dev_queue_head || !dev_first_token ||
+        !dev_tokens || !dev_release_seq || !dev_keep_len || !dev_produced || (queue_len > 0 && !dev_queue)) {
+        set_error("spec_rollout_retire: null pointer");
+        return SPEC_EINVAL;
+    }
+    spec_status st = launch_rollout_retire(B, k, n_seqs, dev_slot_seq, dev_active, dev_accept_len, dev_gen_len, dev_target_len, dev_queue,
+                                           queue_len, dev_queue_head, dev_first_token, dev_tokens, dev_release_seq, dev_keep_len,
+                                           dev_produced, (hipStream_t)stream);
+    if (st != SPEC_OK) return st;
+    prof_mark(PC_OTHER, (hipStream_t)stream);
+    return SPEC_OK;
+}
+
 extern "C" size_t spec_kv_state_bytes(const spec_kv* kv) { return kv ? kv->state_ints * sizeof(int32_t) : 0; }
 
 extern "C" spec_status spec_kv_snapshot(spec_kv* kv, void* dev_buf, void* stream)

@@ -124,6 +124,10 @@ spec_status launch_kv_reserve(spec_kv* kv, int B, int k, const int32_t* dev_seq_
 spec_status launch_kv_commit(spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, const int32_t* dev_accept_len,
                              int32_t* dev_new_ctx_len, int32_t* dev_commit_slots, hipStream_t s);
 
+spec_status launch_rollout_retire(int B, int k, int n_seqs, int32_t* slot_seq, int32_t* active, const int32_t* accept_len,
+                                  int32_t* gen_len, const int32_t* target_len, const int32_t* queue, int queue_len,
+                                  int32_t* queue_head, const int32_t* first_token, int32_t* tokens, int32_t* release_seq,
+                                  int32_t* keep_len, int64_t* produced, hipStream_t s);
 spec_status launch_kv_truncate(spec_kv* kv, int B, const int32_t* dev_seq_ids, const int32_t* dev_len, int delta,
                                int32_t* dev_new_len, hipStream_t s);
 

@@ -174,6 +174,75 @@ __global__ __launch_bounds__(KVB_THREADS) void kv_truncate_kernel(
     if (threadIdx.x == 0) *free_count = s_free;
 }
 
+// Slot bookkeeping of a continuous rollout: finished sequences leave their slot, waiting ones take it over in
+// batch order (a block scan over "this slot needs a successor" hands out the queue entries), the rest idle.
+__global__ __launch_bounds__(KVB_THREADS) void rollout_retire_kernel(
+    int B, int k, int n_seqs, int32_t* __restrict__ slot_seq, int32_t* __restrict__ active,
+    const int32_t* __restrict__ accept_len, int32_t* __restrict__ gen_len, const int32_t* __restrict__ target_len,
+    const int32_t* __restrict__ queue, int queue_len, int32_t* __restrict__ queue_head,
+    const int32_t* __restrict__ first_token, int32_t* __restrict__ tokens, int32_t* __restrict__ release_seq,
+    int32_t* __restrict__ keep_len, long long* __restrict__ produced)
+{
+    __shared__ int lds[KVB_THREADS];
+    __shared__ int s_head;
+    if (threadIdx.x == 0) s_head = *queue_head;
+    __syncthreads();
+    long long made_sum = 0;
+    for (int base = 0; base < B; base += KVB_THREADS) {
+        const int b = base + threadIdx.x;
+        int wants = 0, made = 0;
+        if (b < B) {
+            const int s = slot_seq[b];
+            release_seq[b] = s;
+            const bool live = active[b] != 0 && s >= 0 && s < n_seqs;
+            if (!live) {
+                keep_len[b] = 0;
+            } else {
+                int n = accept_len[b];
+                n = n < 0 ? 0 : (n > k ? k : n);
+                const int left = target_len[s] - gen_len[s];
+                made = n + 1 < left ? n + 1 : left;
+                if (made < 0) made = 0;
+                gen_len[s] += made;
+                if (made >= left) { wants = 1; keep_len[b] = 0; }
+                else keep_len[b] = 1 << 30;
+            }
+        }
+        int total;
+        const int rank = block_exclusive_scan(wants, lds, &total);
+        const int head = s_head;
+        __syncthreads();
+        if (wants) {
+            if (head + rank < queue_len) {
+                const int nxt = queue[head + rank];
+                slot_seq[b] = nxt;
+                tokens[(int64_t)b * (k + 1)] = nxt >= 0 && nxt < n_seqs ? first_token[nxt] : 0;
+            } else {
+                active[b] = 0;
+            }
+        }
+        if (threadIdx.x == 0) s_head = head + total < queue_len ? head + total : queue_len;
+        made_sum += made;
+        __syncthreads();
+    }
+    // tokens counted this step, summed over the block
+    int total;
+    block_exclusive_scan((int)made_sum, lds, &total);
+    if (threadIdx.x == 0) { *queue_head = s_head; *produced += total; }
+}
+
+spec_status launch_rollout_retire(int B, int k, int n_seqs, int32_t* slot_seq, int32_t* active, const int32_t* accept_len,
+                                  int32_t* gen_len, const int32_t* target_len, const int32_t* queue, int queue_len,
+                                  int32_t* queue_head, const int32_t* first_token, int32_t* tokens, int32_t* release_seq,
+                                  int32_t* keep_len, int64_t* produced, hipStream_t s)
+{
+    rollout_retire_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, n_seqs, slot_seq, active, accept_len, gen_len, target_len, queue,
+                                                    queue_len, queue_head, first_token, tokens, release_seq, keep_len,
+                                                    (long long*)produced);
+    SPEC_LAUNCH_CHECK("rollout_retire_kernel");
+    return SPEC_OK;
+}
+
 spec_status launch_kv_truncate(spec_kv* kv, int B, const int32_t* dev_seq_ids, const int32_t* dev_len, int delta,
                                int32_t* dev_new_len, hipStream_t s)
 {

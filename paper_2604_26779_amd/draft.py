@@ -126,3 +126,52 @@ class NgramRollout:
                                   buf["sample_ws"], stream)
             sv.spec_commit_kv(t.kv, B, k, seq_ids, acc, buf["new_ctx_len"], None, stream)
             sv.spec_ngram_append(B, k, hist, hist_len, seq_ids, out, acc, stream)
+
+
+class ContinuousRollout:
+    """A rollout over B batch slots that outlives its sequences: n-gram drafts -> verify forward -> rejection
+    sampling -> commit -> history update -> next inputs -> slot bookkeeping (finished sequences retire, waiting ones
+    take their slot, the rest idle) -> release of the retired caches; one stream, no host round trip.  Sequence ids
+    index every per-sequence array (histories, lengths, targets, first tokens); waiting sequences are already
+    prefilled.  Only call order and buffers are handled here."""
+
+    def __init__(self, target_session, B, k, slot_seq, target_len, queue, first_token, n_max=3, n_min=1):
+        self.t, self.B, self.k, self.n_max, self.n_min = target_session, int(B), int(k), int(n_max), int(n_min)
+        dev = target_session.device
+        n_seqs = int(target_len.shape[0])
+        self.slot_seq = slot_seq.to(dev, torch.int32).clone()
+        self.target_len = target_len.to(dev, torch.int32)
+        self.first_token = first_token.to(dev, torch.int32)
+        self.queue = queue.to(dev, torch.int32) if queue is not None and len(queue) else None
+        self.active = torch.ones(B, dtype=torch.int32, device=dev)
+        self.gen_len = torch.zeros(n_seqs, dtype=torch.int32, device=dev)
+        self.queue_head = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.produced = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.tokens = torch.zeros((B, k + 1), dtype=torch.int32, device=dev)
+        self.drafts = torch.zeros((B, k), dtype=torch.int32, device=dev)
+        self.release_seq = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.keep_len = torch.zeros(B, dtype=torch.int32, device=dev)
+
+    def run(self, hist, hist_len, n_steps, temperature, seed, step0=0, live_out=None, stream=None):
+        """live_out [n_steps] int32 (device, optional) receives the number of live slots after every step."""
+        t, B, k = self.t, self.B, self.k
+        V = t.cfg["vocab"]
+        buf = t.step_buffers(B, k)
+        ws = buf["workspace"]
+        off = (-ws.data_ptr()) % 256
+        ws = ws[off:off + ws.numel() - 256]
+        acc, out = buf["accept_len"], buf["out_tokens"]
+        for s in range(n_steps):
+            sv.spec_ngram_draft(B, k, self.n_max, self.n_min, hist, hist_len, self.slot_seq, self.tokens, None, stream)
+            self.drafts.copy_(self.tokens[:, 1:])
+            sv.spec_verify_forward(t.model, t.kv, B, k, self.slot_seq, self.tokens, buf["logits"], ws, stream)
+            sv.spec_reject_sample(B, k, V, buf["logits"], None, self.drafts, temperature, seed, step0 + s, acc, out, None,
+                                  buf["sample_ws"], stream)
+            sv.spec_commit_kv(t.kv, B, k, self.slot_seq, acc, buf["new_ctx_len"], None, stream)
+            sv.spec_ngram_append(B, k, hist, hist_len, self.slot_seq, out, acc, stream)
+            sv.spec_rollout_retire(B, k, self.slot_seq, self.active, acc, self.gen_len, self.target_len, self.queue,
+                                   self.queue_head, self.first_token, self.tokens, self.release_seq, self.keep_len,
+                                   self.produced, stream)
+            sv.spec_kv_truncate(t.kv, B, self.release_seq, self.keep_len, 0, None, stream)
+            if live_out is not None:
+                live_out[s] = self.active.sum()

@@ -59,6 +59,11 @@ WORKLOADS = {
     "llama8b_b32_ctx1k-8k_k3": dict(model="llama8b_bf16", B=32, k=3, ctx_lo=1024, ctx_hi=8192, noise_std=1.0,
                                     temperature=1.0),
 }
+# Continuous rollout: 32 batch slots, 64 sequences (32 waiting, prompts cached), response lengths long-tailed
+# (log-normal, median 24 tokens, clipped to 4..160): the slots drain unevenly, the tail runs with few live slots.
+WORKLOADS["rollout_b32_q32_ctx1k-8k_k3"] = dict(model="llama8b_bf16", B=64, slots=32, k=3, ctx_lo=1024, ctx_hi=8192,
+                                                noise_std=1.0, temperature=1.0, resp_median=24, resp_sigma=0.8,
+                                                resp_lo=4, resp_hi=160)
 # Draft + target pair: a single-layer draft run autoregressively for k = 5, then the
 # 8B-shaped verify, B = 64, contexts of 4096 tokens.
 WORKLOADS["draft_pair_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model="draft1l_8b_bf16", B=64, k=5, ctx_lo=4096,
@@ -234,3 +239,12 @@ def ceil_div(a, b):
 __all__ = ["PAGE_SIZE", "DEFAULT_SEED", "MODELS", "WORKLOADS", "torch_dtype", "weight_shapes", "make_weights",
            "weights_for_oracle", "make_batch", "make_logical_kv", "kv_for_oracle", "round_to_storage",
            "make_sampler_case", "draw_from", "noisy_draft_distribution", "ceil_div", "math"]
+
+
+def response_lengths(workload, seed=DEFAULT_SEED):
+    """Long-tailed synthetic response lengths [B] (int32) of a continuous-rollout workload: log-normal with the
+    workload's median and sigma, clipped to [resp_lo, resp_hi]."""
+    rng = np.random.default_rng(int(seed) + 23)
+    n = workload["B"]
+    x = np.exp(rng.normal(np.log(workload["resp_median"]), workload["resp_sigma"], size=n))
+    return np.clip(np.rint(x), workload["resp_lo"], workload["resp_hi"]).astype(np.int32)

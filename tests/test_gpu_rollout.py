@@ -1,0 +1,110 @@
+"""GPU parity of the continuous rollout's slot bookkeeping (spec_rollout_retire + spec_kv_truncate) against the CPU
+oracle: slots, queue head, response counters, next-step inputs, page lists and the free stack are integers and must
+match bit for bit at every step; the logits of every slot - including slots that were taken over by a waiting
+sequence and idle ones - follow the oracle's forward over the caches as the oracle's book keeps them."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import commit as oracle_commit
+from oracle import forward as of
+from oracle import rollout as oro
+from tests.helpers import logits_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("seed,B,n_seqs,k", [(1, 4, 9, 3), (2, 6, 6, 2), (3, 3, 12, 5)])
+def test_retire_backfill_chain(seed, B, n_seqs, k):
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = si.MODELS["tiny_fp32"]
+    rng = np.random.default_rng(seed)
+    weights = si.make_weights(cfg, seed=seed)
+    w_or = si.weights_for_oracle(cfg, weights)
+    ctx0 = rng.integers(0, 40, size=n_seqs).astype(np.int64)
+    kv0 = si.make_logical_kv(cfg, ctx0, seed=seed)                       # the waiting sequences' prompts are cached already
+    kv_or = si.kv_for_oracle(kv0)
+    n_pages = 64
+    sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=n_seqs, max_ctx_len=512, n_pages=n_pages)
+    book = oracle_commit.KVBook(n_pages=n_pages, page_size=si.PAGE_SIZE)
+    order = [int(p) for p in rng.permutation(n_pages)]
+    at = 0
+    for s in range(n_seqs):
+        need = -(-int(ctx0[s]) // si.PAGE_SIZE)
+        pages = order[at:at + need]
+        at += need
+        sess.assign(s, int(ctx0[s]), pages)
+        book.assign(s, int(ctx0[s]), pages)
+        for l in range(cfg["n_layers"]):
+            sess.write_logical_kv(l, pages, kv0[l][s][0], kv0[l][s][1])
+    target = rng.integers(1, 14, size=n_seqs).astype(np.int32)
+    first = rng.integers(0, cfg["vocab"], size=n_seqs).astype(np.int32)
+    queue = np.arange(B, n_seqs, dtype=np.int32)
+    # oracle state
+    slot_seq = np.arange(B, dtype=np.int32)
+    active = np.ones(B, dtype=np.int32)
+    gen = np.zeros(n_seqs, dtype=np.int32)
+    tokens = rng.integers(0, cfg["vocab"], size=(B, k + 1)).astype(np.int32)
+    tokens[:, 0] = first[:B]
+    head, produced = 0, 0
+    kv_cur = [[(kv_or[l][s][0].copy(), kv_or[l][s][1].copy()) for s in range(n_seqs)] for l in range(cfg["n_layers"])]
+    ctx = ctx0.copy()
+    # device state
+    dev = lambda a, dt=torch.int32: torch.from_numpy(np.asarray(a)).to("cuda", dt)
+    d_slot, d_active, d_gen = dev(slot_seq), dev(active), dev(gen)
+    d_target, d_first, d_queue = dev(target), dev(first), (dev(queue) if len(queue) else None)
+    d_head = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_prod = torch.zeros(1, dtype=torch.int64, device="cuda")
+    d_tok = dev(tokens)
+    d_rel, d_keep = torch.zeros(B, dtype=torch.int32, device="cuda"), torch.zeros(B, dtype=torch.int32, device="cuda")
+    steps = 0
+    while active.any() and steps < 60:
+        steps += 1
+        seqs = [int(s) for s in slot_seq]
+        kv_slots = [[kv_cur[l][s] for s in seqs] for l in range(cfg["n_layers"])]
+        want, new_kv = of.verify_forward(cfg, w_or, kv_slots, tokens, ctx[seqs])
+        logits = sess.forward(d_slot, d_tok)
+        torch.cuda.synchronize()
+        ok, max_err, worst = logits_close(logits.cpu().numpy(), want, 1e-4, 1e-4)
+        assert ok, (steps, max_err, worst)
+        n = rng.integers(0, k + 1, size=B).astype(np.int32)
+        book.reserve(seqs, k)
+        book.commit(seqs, n, k)
+        d_n = dev(n)
+        sess.commit(d_slot, d_n, k)
+        for bi, s in enumerate(seqs):                                    # the kept positions join the oracle's caches
+            for l in range(cfg["n_layers"]):
+                K, V = kv_cur[l][s]
+                kv_cur[l][s] = (np.concatenate([K, new_kv[l][0][bi][:n[bi] + 1]]), np.concatenate([V, new_kv[l][1][bi][:n[bi] + 1]]))
+            ctx[s] += n[bi] + 1
+        # next inputs: what the sampler would have emitted (forced here), fresh drafts; then the slot bookkeeping
+        nxt = rng.integers(0, cfg["vocab"], size=(B, k + 1)).astype(np.int32)
+        tokens = nxt.copy()
+        d_tok.copy_(dev(nxt))
+        rel, keep, head, made = oro.retire_and_backfill(slot_seq, active, n, k, gen, target, list(queue), head, first, tokens)
+        produced += made
+        sv.spec_rollout_retire(B, k, d_slot, d_active, d_n, d_gen, d_target, d_queue, d_head, d_first, d_tok, d_rel, d_keep, d_prod)
+        sv.spec_kv_truncate(sess.kv, B, d_rel, d_keep, 0, None)
+        book.truncate([int(s) for s in rel], [int(x) for x in keep])
+        for b in range(B):
+            if keep[b] == 0:
+                s = int(rel[b])
+                ctx[s] = 0
+                for l in range(cfg["n_layers"]):
+                    kv_cur[l][s] = (kv_cur[l][s][0][:0], kv_cur[l][s][1][:0])
+        torch.cuda.synchronize()
+        assert np.array_equal(d_slot.cpu().numpy(), slot_seq) and np.array_equal(d_active.cpu().numpy(), active), steps
+        assert np.array_equal(d_gen.cpu().numpy(), gen) and int(d_head.item()) == head and int(d_prod.item()) == produced
+        assert np.array_equal(d_tok.cpu().numpy(), tokens) and np.array_equal(d_rel.cpu().numpy(), rel)
+        assert np.array_equal(d_keep.cpu().numpy(), keep)
+        st = sess.state()
+        for s in range(n_seqs):
+            assert st["ctx_len"][s] == book.ctx_len[s], (steps, s)
+            assert st["n_pages"][s] == len(book.pages[s]), (steps, s)
+            assert list(st["page_table"][s][:len(book.pages[s])]) == book.pages[s], (steps, s)
+        assert list(st["free_stack"]) == book.free, steps
+    assert not active.any() and head == len(queue) and np.array_equal(gen, target) and produced == int(target.sum())
+    print("B=%d, %d sequences, k=%d: drained in %d steps, %d tokens" % (B, n_seqs, k, steps, produced))
+    sess.close()
