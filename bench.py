@@ -202,6 +202,7 @@ def main():
     ap.add_argument("--rollout-steps", type=int, default=8, help="draft+target pair: consecutive steps of the sustained run")
     ap.add_argument("--graph", action="store_true", help="record the K steps into a HIP graph and time its replay (default: one host launch per kernel)")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch parameter (repeatable)")
+    ap.add_argument("--k", type=int, default=None, help="draft length instead of the workload's own (the draft-length sweep of Table 4)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU (the verify step shards by sequence with no exchange); "
@@ -219,6 +220,8 @@ def main():
         name, value = item.split("=")
         sv.spec_tune_set(name, int(value))
 
+    if args.k is not None:
+        si.WORKLOADS[args.workload] = dict(si.WORKLOADS[args.workload], k=args.k)
     if "slots" in si.WORKLOADS[args.workload]:
         run_continuous(args, DeviceWorkload(args.workload), sv, torch)
         return
