@@ -20,7 +20,7 @@ namespace specv {
 int gemm_mb_pad(int M);
 int gemm_pick_splits(const PackedW& W, int M, int forced);
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s);
-bool gemm_can_fuse_swiglu(int M, int splits);
+bool gemm_can_fuse_swiglu(const PackedW& W, int M, int splits);
 int attn_min_chunk_pages(int R);
 int attn_rows_padded(int R);
 int moe_rows_bound(int M, int top_k, int E);
@@ -228,7 +228,7 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.s_qkv = gemm_pick_splits(m->wqkv[0], p.M, tune("splits_qkv"));
     p.s_o = gemm_pick_splits(m->wo[0], p.M, tune("splits_o"));
     const bool moe = m->moe();
-    p.fuse_swiglu = !moe && tune("fuse_swiglu") != 0 && gemm_can_fuse_swiglu(p.M, 1);
+    p.fuse_swiglu = !moe && tune("fuse_swiglu") != 0 && gemm_can_fuse_swiglu(m->wgu[0], p.M, 1);
     p.s_gu = (p.fuse_swiglu || moe) ? 1 : gemm_pick_splits(m->wgu[0], p.M, tune("splits_gu"));
     p.s_down = moe ? 1 : gemm_pick_splits(m->wd[0], p.M, tune("splits_down"));
     p.s_head = 1;

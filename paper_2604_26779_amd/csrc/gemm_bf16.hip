@@ -109,22 +109,31 @@ spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_row
 // GROUPED (mixture of experts): blockIdx.z walks a device-side list of row tiles, tiles[0] = number of
 // tiles, then (group, first row block) pairs; group g multiplies by the matrix at Wp + g * w_group_stride
 // (all groups have the same shape).  Tiles past the list's end exit at once.
-template <int MB, int WM, int WD, int EPI, bool GROUPED = false>
-__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
+// Large row counts (MB = 6 or 8: 192 or 256 rows per tile) take NBW_T = 4 column blocks per wavefront, i.e. a 256-column
+// tile: a wavefront then owns 3-4 x 4 accumulator blocks (192-256 accumulation registers, one workgroup per CU) and
+// every fragment it fetches feeds 4 (weights: 6-8) MFMAs, which halves the LDS and vector-memory traffic per MFMA
+// that bounds the 128 x 128 tile.  Its two LDS slabs (96-128 KiB) are dynamic shared memory.
+template <int MB, int WM, int WD, int EPI, bool GROUPED = false, int NBW_T = WM>
+__global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kernel(
     const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
     int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride,
     const int32_t* __restrict__ tiles = nullptr, int64_t w_group_stride = 0)
 {
     constexpr int KS = GEMM_KS;
-    constexpr int MBW = MB / WM, NBW = WM;
+    constexpr int MBW = MB / WM, NBW = NBW_T;
+    constexpr int TILE_NB = (4 / WM) * NBW;             // 32-column blocks per workgroup tile
+    constexpr bool BIG = MB >= 6;
     static_assert(MB % WM == 0, "row blocks must divide over the wavefronts");
     constexpr int SLAB = KS * MB * 128;                 // u32x4_t per slab (hi and lo operands)
     constexpr int XPT = SLAB / GEMM_THREADS;            // u32x4_t per thread per slab
-    __shared__ u32x4_t lds[2 * SLAB];
+    static_assert(SLAB % GEMM_THREADS == 0, "a slab must divide over the threads");
+    extern __shared__ u32x4_t lds_dyn[];
+    __shared__ u32x4_t lds_static[BIG ? 1 : 2 * SLAB];
+    u32x4_t* const lds = BIG ? lds_dyn : lds_static;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int mh = wave % WM, np = wave / WM;
-    const int nb0 = blockIdx.x * 4 + np * NBW;
+    const int nb0 = blockIdx.x * TILE_NB + np * NBW;
     const int ks0 = blockIdx.y * ksteps_per_split;
     int ks1 = ks0 + ksteps_per_split;
     if (ks1 > k_steps) ks1 = k_steps;
@@ -195,6 +204,15 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
             if (kk + 1 < KS) read_a((kk + 1) & 1, kk + 1);
+            if constexpr (BIG) {
+                // a slab of the 256-row tile lasts longer than the trip to L2: the next slab's activations go to LDS
+                // under the MFMAs of the last two k-steps instead of after them
+                if (kk >= KS - 2) {
+#pragma unroll
+                    for (int j = (kk - (KS - 2)) * (XPT / 2); j < (kk - (KS - 2) + 1) * (XPT / 2); ++j)
+                        lds[(buf ^ 1) * SLAB + threadIdx.x + GEMM_THREADS * j] = xr[j];
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
             // hi products of all blocks first, then the lo products: two MFMAs on one accumulator are never adjacent
 #pragma unroll
@@ -212,7 +230,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
         // ... and the weight loads of this slab stay above the LDS stores, so that waiting for the (older)
         // activation loads does not drain the weight stream
         __builtin_amdgcn_sched_barrier(0);
-        store_x(buf ^ 1);
+        if constexpr (!BIG) store_x(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     };
@@ -238,7 +256,40 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
         }
     }
 
-    if constexpr (EPI == GEMM_EPI_SWIGLU) {
+    if constexpr (EPI == GEMM_EPI_SWIGLU && BIG) {
+        // 256-column tile: a wavefront's four accumulator columns are (gate, up) of two groups of 32 hidden channels.
+        // Same transpose through LDS as below, one half of the rows (the wavefronts with the same mh) at a time.
+        static_assert(!BIG || NBW == 4, "the 256-column tile has four column blocks per wavefront");
+        float* tile = (float*)lds;                              // [MBW*32 rows][129]
+        uint4* xo = (uint4*)out;
+#pragma unroll
+        for (int half = 0; half < WM; ++half) {
+            __syncthreads();
+            if (mh == half) {
+#pragma unroll
+                for (int i = 0; i < MBW; ++i)
+#pragma unroll
+                    for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            float g = acc[i][2 * cg][r], u = acc[i][2 * cg + 1][r];
+                            int row = i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                            tile[row * 129 + (np * 2 + cg) * 32 + (lane & 31)] = g / (1.0f + __expf(-g)) * u;
+                        }
+            }
+            __syncthreads();
+            for (int e = threadIdx.x; e < MBW * 32 * 16; e += GEMM_THREADS) {
+                int row = e >> 4, g8 = e & 15;
+                int m = (mblk0 + half * MBW) * 32 + row, f = blockIdx.x * 128 + g8 * 8;
+                if (m >= M || f >= N / 2) continue;
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = tile[row * 129 + g8 * 8 + j];
+                xp_store8(xo, m, f, mb_pad, v);
+            }
+        }
+        return;
+    } else if constexpr (EPI == GEMM_EPI_SWIGLU) {
         // The weights of the gate/up projection are tiled with gate and up column blocks interleaved,
         // so this wavefront's two accumulators hold gate and up of the same 32 hidden channels:
         // silu(gate) * up in registers, transposed through LDS (free after the main loop) into rows,
@@ -282,22 +333,60 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(
     }
 }
 
-// rows of the activation buffer are padded to whole tiles of MB 32-row blocks
+// Tile shapes.  Up to 4 row blocks (128 rows) a launch has one kind of tile: MB = min(row blocks, gemm_max_mb) x 128
+// columns.  From gemm_big_min_blocks row blocks on (0 = never) the 256-column tile with 8 or 6 row blocks is available
+// too, and each GEMM takes it when it still fills the chip: at least 200 tiles, or - K split, two or more tiles of
+// rows - at least 192 workgroups of 32 or more k-steps each (a 256 x 256 tile with a short K spends its time in prologue
+// and epilogue; with one tile of rows the extra split-K slices cost the consumers more than the GEMM gains; and a fused
+// SwiGLU epilogue cannot split K at all).  Both kinds read the same activation buffer, so its rows are padded
+// to a multiple of both tile heights: 8 blocks, or 12 where that pads less (then the big tile has 6 row blocks).
+static int gemm_big_mb(int M)
+{
+    const int nb = (int)cdiv(M, 32), from = tune("gemm_big_min_blocks");
+    if (from <= 0 || nb < from || nb < 6) return 0;
+    return cdiv(nb, 12) * 12 < cdiv(nb, 8) * 8 ? 6 : 8;
+}
 int gemm_mb(int M) { int mb = (int)cdiv(M, 32), cap = tune("gemm_max_mb"); cap = cap < 1 ? 1 : (cap > 4 ? 4 : cap); return mb > cap ? cap : mb; }
-int gemm_mb_pad(int M) { int mb = gemm_mb(M); return (int)cdiv(cdiv(M, 32), mb) * mb; }
+int gemm_mb_pad(int M)
+{
+    const int nb = (int)cdiv(M, 32), big = gemm_big_mb(M);
+    if (big) return (int)cdiv(nb, big == 6 ? 12 : 8) * (big == 6 ? 12 : 8);
+    const int mb = gemm_mb(M);
+    return (int)cdiv(nb, mb) * mb;
+}
 
-// k-steps per split come in units of one pass of the weight ring: 2 slabs for the 2x2 arrangement (even row-block
-// counts), 4 for the others
-static int gemm_kunit(int M) { return gemm_mb(M) % 2 == 0 ? GEMM_KS * 2 : GEMM_KUNIT; }
+struct GemmShape { int mb, tile_nb, kunit, m_tiles, n_tiles; };
+static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
+{
+    GemmShape g;
+    const int pad = gemm_mb_pad(M), big = gemm_big_mb(M);
+    if (big) {
+        const int64_t tiles = (int64_t)cdiv(W.n_blocks, 8) * (pad / big);
+        int64_t splits = tune("gemm_wg_target") / tiles;
+        if (splits > W.k_steps / 32) splits = W.k_steps / 32;
+        if (splits < 1) splits = 1;
+        if (tiles >= 200 || (!fused_swiglu && pad / big >= 2 && tiles * splits >= 192)) {
+            g.mb = big; g.tile_nb = 8; g.kunit = GEMM_KS * 2;
+            g.m_tiles = pad / big; g.n_tiles = (int)cdiv(W.n_blocks, 8);
+            return g;
+        }
+    }
+    g.mb = big ? 4 : gemm_mb(M);
+    g.tile_nb = 4;
+    // k-steps per split come in units of one pass of the weight ring: 2 slabs for the 2x2 arrangement (even row-block
+    // counts), 4 for the others
+    g.kunit = g.mb % 2 == 0 ? GEMM_KS * 2 : GEMM_KUNIT;
+    g.m_tiles = pad / g.mb; g.n_tiles = (int)cdiv(W.n_blocks, 4);
+    return g;
+}
 
 int gemm_pick_splits(const PackedW& W, int M, int forced)
 {
-    const int unit = gemm_kunit(M);
-    int n_tiles = (int)cdiv(W.n_blocks, 4);
-    int m_tiles = gemm_mb_pad(M) / gemm_mb(M);
+    const GemmShape g = gemm_shape(W, M, false);
+    const int unit = g.kunit;
     int max_splits = W.k_steps / (tune("gemm_min_ksteps") > unit ? tune("gemm_min_ksteps") : unit);
     if (max_splits < 1) max_splits = 1;
-    int splits = forced > 0 ? forced : tune("gemm_wg_target") / (n_tiles * m_tiles);
+    int splits = forced > 0 ? forced : tune("gemm_wg_target") / (g.n_tiles * g.m_tiles);
     if (splits < 1) splits = 1;
     if (splits > max_splits) splits = max_splits;
     int kps = (int)cdiv(cdiv(W.k_steps, splits), unit) * unit;
@@ -307,24 +396,40 @@ int gemm_pick_splits(const PackedW& W, int M, int forced)
 // out must hold splits * M * ldo floats; with swiglu (gate/up projection, splits == 1, an even number
 // of row blocks) out is instead the hi + lo operand buffer of silu(gate) * up, [N/2] channels wide.
 // Returns SPEC_EUNSUPPORTED (nothing launched) if swiglu is asked for a shape it cannot fuse.
-bool gemm_can_fuse_swiglu(int M, int splits) { return splits == 1 && gemm_mb(M) % 2 == 0; }
+bool gemm_can_fuse_swiglu(const PackedW& W, int M, int splits) { return splits == 1 && gemm_shape(W, M, true).mb % 2 == 0; }
 
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s)
 {
-    int mb = gemm_mb(M), mb_pad = gemm_mb_pad(M);
-    int kps = (int)cdiv(cdiv(W.k_steps, splits), gemm_kunit(M)) * gemm_kunit(M);
-    dim3 grid((unsigned)cdiv(W.n_blocks, 4), (unsigned)cdiv(W.k_steps, kps), (unsigned)(mb_pad / mb));
+    const GemmShape g = gemm_shape(W, M, swiglu);
+    const int mb = g.mb, mb_pad = gemm_mb_pad(M);
+    int kps = (int)cdiv(cdiv(W.k_steps, splits), g.kunit) * g.kunit;
+    dim3 grid((unsigned)g.n_tiles, (unsigned)cdiv(W.k_steps, kps), (unsigned)g.m_tiles);
     int64_t stride = (int64_t)M * ldo;
     const u32x4_t* wp = (const u32x4_t*)W.data;
     const u32x4_t* xp = (const u32x4_t*)Xp;
-    if (swiglu && !gemm_can_fuse_swiglu(M, splits)) { set_error("gemm: SwiGLU cannot be fused for this shape"); return SPEC_EUNSUPPORTED; }
+    if (swiglu && !gemm_can_fuse_swiglu(W, M, splits)) { set_error("gemm: SwiGLU cannot be fused for this shape"); return SPEC_EUNSUPPORTED; }
 #define SPEC_GEMM_LAUNCH(MBV, WMV, WDV, E) gemm_bf16_kernel<MBV, WMV, WDV, E><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride)
+    // the 256-column tile: two LDS slabs of MB * 8 KiB as dynamic shared memory (beyond the 64 KiB a kernel gets by default)
+#define SPEC_GEMM_LAUNCH_BIG(MBV, E) do { \
+        auto kern = gemm_bf16_kernel<MBV, 2, 1, E, false, 4>; \
+        constexpr int lds_bytes = 2 * GEMM_KS * MBV * 128 * 16; \
+        static bool raised = false; \
+        if (!raised) { \
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes); \
+            if (e != hipSuccess) { set_error("gemm: cannot reserve %d bytes of LDS: %s", lds_bytes, hipGetErrorString(e)); return SPEC_EHIP; } \
+            raised = true; \
+        } \
+        kern<<<grid, GEMM_THREADS, lds_bytes, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0); \
+    } while (0)
     switch (mb) {
         case 1: SPEC_GEMM_LAUNCH(1, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
         case 2: if (swiglu) SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_PLAIN); break;
         case 3: SPEC_GEMM_LAUNCH(3, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
+        case 6: if (swiglu) SPEC_GEMM_LAUNCH_BIG(6, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH_BIG(6, GEMM_EPI_PLAIN); break;
+        case 8: if (swiglu) SPEC_GEMM_LAUNCH_BIG(8, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH_BIG(8, GEMM_EPI_PLAIN); break;
         default: if (swiglu) SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_PLAIN); break;
     }
+#undef SPEC_GEMM_LAUNCH_BIG
 #undef SPEC_GEMM_LAUNCH
     SPEC_LAUNCH_CHECK("gemm_bf16_kernel");
     return SPEC_OK;

@@ -383,3 +383,20 @@ def test_bf16_attention_reference_point_moves(case):
                                               n_kv_heads=heads[1])
         print("%s, Hq/Hkv=%s: logits max abs err %.3e" % (case, heads, max_err))
         assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("B,k,big_from", [(64, 3, 8), (33, 7, 8), (12, 15, 6), (50, 3, 6), (96, 3, 8), (40, 5, 8)])
+def test_bf16_large_row_tiles(B, k, big_from):
+    """The 192- and 256-row x 256-column GEMM tiles (tuning parameter gemm_big_min_blocks): M = 256 (one 8-block tile),
+    264 (9 blocks -> two 6-block tiles, the second half empty), 192 (one 6-block tile), 200 (7 blocks -> one 8-block tile),
+    384 (two 6-block tiles) and 240; column counts that are not multiples of 256, fused SwiGLU epilogue, split K."""
+    from paper_2604_26779_amd import binding as sv
+    sv.spec_tune_set("gemm_big_min_blocks", big_from)
+    try:
+        rng = np.random.default_rng(B * 10 + k)
+        ctx = [int(c) for c in rng.integers(3, 120, size=B)]
+        ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000)
+    finally:
+        sv.spec_tune_set("gemm_big_min_blocks", 0)
+    print("B=%d k=%d (M=%d), big tiles from %d row blocks: logits max abs err %.3e" % (B, k, B * (k + 1), big_from, max_err))
+    assert ok, (max_err, worst)
