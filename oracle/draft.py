@@ -19,8 +19,13 @@ from . import forward as _forward
 from . import sampler as _sampler
 
 
-def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, step):
+def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, step, pending_hidden=None):
     """pending [B, P] int tokens not yet in the draft's cache, ctx_len [B] its cached length.
+
+    A draft that takes hidden states (cfg fuse_hidden) gets pending_hidden [B, P, d]: for each pending token the
+    verifier's hidden state of the position before it.  Iterations after the first pair the drafted token with the
+    draft's own hidden state of the position before it (the last row of the previous iteration), as EAGLE- and
+    MTP-style drafters chain their predictions.
 
     Returns (drafts [B, k] int32, q [B, k, V] fp32, kv_ctx grown by the fed positions, new_len [B],
     keys [B, k, 2] = winning and runner-up key of every draw).
@@ -33,8 +38,14 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
     q = np.zeros((B, k, cfg["vocab"]), dtype=np.float32)
     keys = np.zeros((B, k, 2), dtype=np.float64)
     feed = pending
+    fused = bool(cfg.get("fuse_hidden", 0))
+    feed_hidden = np.asarray(pending_hidden, dtype=np.float64) if fused else None
     for i in range(k):
-        logits, new_kv = _forward.verify_forward(cfg, weights, kv, feed, ctx_len)
+        if fused:
+            logits, new_kv, hid = _forward.verify_forward(cfg, weights, kv, feed, ctx_len, hidden_in=feed_hidden, return_hidden=True)
+            feed_hidden = hid[:, -1:, :]
+        else:
+            logits, new_kv = _forward.verify_forward(cfg, weights, kv, feed, ctx_len)
         for layer in range(cfg["n_layers"]):
             for b in range(B):
                 K, V = kv[layer][b]
@@ -47,7 +58,21 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
     return drafts, q, kv, ctx_len, keys
 
 
-def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperature, seed, n_steps):
+def next_pending_hidden(pending_hidden, target_hidden, accept_len):
+    """Hidden states for the next step's two pending tokens (the last input the verifier kept, and the token it
+    emitted): the verifier's hidden states of the positions before them.  With n accepted, the kept input is row n
+    of the verify pass: the state before it is row n-1 - or, for n = 0, the state that was paired with the old
+    emitted token (pending_hidden[b][1]) - and the state before the new emitted token is row n."""
+    B = len(accept_len)
+    out = np.zeros_like(np.asarray(pending_hidden, dtype=np.float64))
+    for b in range(B):
+        n = int(accept_len[b])
+        out[b, 0] = target_hidden[b, n - 1] if n >= 1 else pending_hidden[b][1]
+        out[b, 1] = target_hidden[b, n]
+    return out
+
+
+def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperature, seed, n_steps, pending_hidden=None):
     """Several speculation steps in a row (the decode phase of a rollout, Section 2.1-2.2): every step drafts k
     tokens with the draft model, verifies them with the target, keeps the accepted prefix and emits one more
     token, which is the first input of the next step.
@@ -69,10 +94,17 @@ def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperatur
     history = []
     for s in range(n_steps):
         pending = np.stack([prev, t0], axis=1)
-        drafts, q, kv_d_grown, _, _ = draft_loop(cfg_d, w_d, kv_d, pending, ctx_len - 1, k, temperature, seed, s)
+        fused = bool(cfg_d.get("fuse_hidden", 0))
+        drafts, q, kv_d_grown, _, _ = draft_loop(cfg_d, w_d, kv_d, pending, ctx_len - 1, k, temperature, seed, s,
+                                                 pending_hidden if fused else None)
         tokens = np.concatenate([t0[:, None], drafts], axis=1).astype(np.int32)
-        logits, new_kv = _forward.verify_forward(cfg_t, w_t, kv_t, tokens, ctx_len)
+        if fused:
+            logits, new_kv, hid_t = _forward.verify_forward(cfg_t, w_t, kv_t, tokens, ctx_len, return_hidden=True)
+        else:
+            logits, new_kv = _forward.verify_forward(cfg_t, w_t, kv_t, tokens, ctx_len)
         n, out = _s.reject_sample(logits.astype(np.float32), q, drafts, temperature, seed, s)
+        if fused:
+            pending_hidden = next_pending_hidden(pending_hidden, hid_t, n)
         history.append(dict(drafts=drafts, accept_len=n.copy(), out_tokens=out.copy(), tokens=tokens))
         for b in range(B):
             keep = int(n[b]) + 1                                   # inputs 0..n stay in the target's cache

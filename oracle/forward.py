@@ -110,7 +110,7 @@ def moe_ffn(h, w, top_k, route_log=None):
     return out
 
 
-def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None):
+def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden_in=None, return_hidden=False):
     """One verify forward.
 
     cfg      dict: n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab,
@@ -123,8 +123,15 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None):
     Mixture-of-experts models (cfg n_experts, top_k > 0): every layer dict has 'router' [E,d] and stacked
     wg, wu [E,F,d], wd [E,d,F]; route_log (a list) receives per layer (experts, weights, probabilities).
 
+    Draft models that take the verifier's hidden states (cfg fuse_hidden; the paper's EAGLE-3 and MTP drafting
+    paths, Section 2.3, consume target hidden states; the combination used here is the MTP one): weights['fuse'] =
+    dict(w_fuse [d, 2d], norm_e [d], norm_h [d]) and hidden_in [B, k+1, d]; the input of the first layer is
+    w_fuse . [RMSNorm(embedding) * norm_e ; RMSNorm(hidden_in) * norm_h], hidden_in[b][i] being the hidden state
+    of the position before input i.
+
     Returns (logits [B,k+1,V] fp64, new_kv) with new_kv[layer] = (K [B,k+1,Hkv,dh], V [...]),
-    the keys (after rotation) and values of the k+1 input positions as the cache stores them.
+    the keys (after rotation) and values of the k+1 input positions as the cache stores them; with return_hidden
+    also the residual stream after the last layer, before the final norm, [B,k+1,d].
     """
     tokens = np.asarray(tokens)
     B, T = tokens.shape
@@ -135,6 +142,11 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None):
 
     embed = np.asarray(weights["embed"], dtype=np.float64)
     x = embed[tokens.reshape(-1)]                                   # [B*T, d]
+    if cfg.get("fuse_hidden", 0):
+        f = weights["fuse"]
+        h_in = np.asarray(hidden_in, dtype=np.float64).reshape(B * T, -1)
+        both = np.concatenate([rmsnorm(x, f["norm_e"], eps), rmsnorm(h_in, f["norm_h"], eps)], axis=1)
+        x = both @ np.asarray(f["w_fuse"], dtype=np.float64).T
     pos = (np.asarray(ctx_len)[:, None] + np.arange(T)[None, :]).reshape(-1)
 
     new_kv = []
@@ -173,6 +185,8 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None):
     head = weights.get("head")
     head = embed if head is None else np.asarray(head, dtype=np.float64)
     logits = rmsnorm(x, weights["final_norm"], eps) @ head.T
+    if return_hidden:
+        return logits.reshape(B, T, -1), new_kv, x.reshape(B, T, -1).copy()
     return logits.reshape(B, T, -1), new_kv
 
 

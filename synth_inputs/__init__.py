@@ -46,6 +46,11 @@ MODELS = {
                             vocab=1024, rope_theta=1.0e4, rms_eps=1.0e-5, dtype="f32", tied_head=1),
     "draft_small_bf16": dict(n_layers=1, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1280,
                              vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1),
+    # The same, taking the verifier's hidden states as a second input (EAGLE-3 / MTP style input fusion).
+    "draft_fused_small_bf16": dict(n_layers=1, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1280,
+                                   vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1, fuse_hidden=1),
+    "draft1l_fused_8b_bf16": dict(n_layers=1, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
+                                  vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1, fuse_hidden=1),
     "draft1l_8b_bf16": dict(n_layers=1, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
                             vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1),
 }
@@ -68,6 +73,10 @@ WORKLOADS["rollout_b32_q32_ctx1k-8k_k3"] = dict(model="llama8b_bf16", B=64, slot
 # 8B-shaped verify, B = 64, contexts of 4096 tokens.
 WORKLOADS["draft_pair_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model="draft1l_8b_bf16", B=64, k=5, ctx_lo=4096,
                                               ctx_hi=4096, noise_std=0.0, temperature=1.0)
+WORKLOADS["draft_pair_fused_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model="draft1l_fused_8b_bf16", B=64, k=5,
+                                                    ctx_lo=4096, ctx_hi=4096, noise_std=0.0, temperature=1.0)
+WORKLOADS["draft_pair_fused_small_b5_k4"] = dict(model="small_bf16", draft_model="draft_fused_small_bf16", B=5, k=4, ctx_lo=20,
+                                                 ctx_hi=600, noise_std=0.0, temperature=0.9)
 WORKLOADS["draft_pair_small_b5_k4"] = dict(model="small_bf16", draft_model="draft_small_bf16", B=5, k=4, ctx_lo=20,
                                            ctx_hi=600, noise_std=0.0, temperature=0.9)
 WORKLOADS["draft_pair_tiny_b4_k3"] = dict(model="tiny_fp32", draft_model="draft_tiny_fp32", B=4, k=3, ctx_lo=100,
@@ -113,6 +122,8 @@ def weight_shapes(cfg):
     out.append(("final_norm", (d,)))
     if not cfg.get("tied_head", 0):
         out.append(("head", (V, d)))
+    if cfg.get("fuse_hidden", 0):      # a draft model that also takes the verifier's hidden states
+        out += [("w_fuse", (d, 2 * d)), ("fuse_e_norm", (d,)), ("fuse_h_norm", (d,))]
     return out
 
 
@@ -139,8 +150,11 @@ def weights_for_oracle(cfg, weights):
     names = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd") + (("router",) if cfg.get("n_experts", 0) > 0 else ())
     for l in range(cfg["n_layers"]):
         layers.append({k: f(f"l{l}.{k}") for k in names})
-    return {"embed": f("embed"), "layers": layers, "final_norm": f("final_norm"),
-            "head": None if cfg.get("tied_head", 0) else f("head")}
+    out = {"embed": f("embed"), "layers": layers, "final_norm": f("final_norm"),
+           "head": None if cfg.get("tied_head", 0) else f("head")}
+    if cfg.get("fuse_hidden", 0):
+        out["fuse"] = {"w_fuse": f("w_fuse"), "norm_e": f("fuse_e_norm"), "norm_h": f("fuse_h_norm")}
+    return out
 
 
 def make_batch(workload, seed=DEFAULT_SEED, shuffle_pages=True, extra_pages=8):

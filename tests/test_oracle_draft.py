@@ -33,7 +33,11 @@ def _weights(cfg, seed=0, std=0.3):
                    wo=rng.standard_normal((d, Hq * dh)) * std, ffn_norm=1 + 0.1 * rng.standard_normal(d),
                    wg=rng.standard_normal((F, d)) * std, wu=rng.standard_normal((F, d)) * std,
                    wd=rng.standard_normal((d, F)) * std) for _ in range(cfg["n_layers"])]
-    return dict(embed=rng.standard_normal((V, d)), layers=layers, final_norm=1 + 0.1 * rng.standard_normal(d), head=None)
+    out = dict(embed=rng.standard_normal((V, d)), layers=layers, final_norm=1 + 0.1 * rng.standard_normal(d), head=None)
+    if cfg.get("fuse_hidden", 0):
+        out["fuse"] = dict(w_fuse=rng.standard_normal((d, 2 * d)) * std, norm_e=1 + 0.1 * rng.standard_normal(d),
+                           norm_h=1 + 0.1 * rng.standard_normal(d))
+    return out
 
 
 def test_proposal_distribution_is_softmax_and_tokens_follow_it():
@@ -187,3 +191,42 @@ def test_rollout_over_several_steps_keeps_consistent_caches():
     kv_same = of.prefill(cfg_d, w_d, string[:, :C])
     hist3, _, _, ctx3 = od.rollout(cfg_d, w_d, cfg_d, w_d, kv_same, kv_d, string[:, C - 1], string[:, C], np.full(B, C), k, T, 5, 2)
     assert all(np.all(h["accept_len"] == k) for h in hist3) and list(ctx3) == [C + 2 * (k + 1)] * B
+
+
+def test_fused_draft_loop_chains_its_own_hidden_states():
+    """The draft with hidden-state input: iteration 1 pairs the pending tokens with the hidden states it is given,
+    iteration i > 1 pairs x_{i-1} with the draft's own hidden state of the position before.  Checked against a
+    cache-free recomputation written position by position, and next_pending_hidden against its three cases."""
+    cfg = dict(CFG, fuse_hidden=1)
+    w = _weights(cfg, seed=8)
+    d = cfg["d_model"]
+    rng = np.random.default_rng(9)
+    B, C, k, T = 2, 5, 3, 0.8
+    ctx_tokens = rng.integers(0, cfg["vocab"], size=(B, C)).astype(np.int32)
+    ctx_hidden = rng.standard_normal((B, C, d))
+    pending = rng.integers(0, cfg["vocab"], size=(B, 2)).astype(np.int32)
+    pend_hidden = rng.standard_normal((B, 2, d))
+    empty = [[(np.zeros((0, 2, 16)), np.zeros((0, 2, 16))) for _ in range(B)] for _ in range(cfg["n_layers"])]
+    _, kv0 = of.verify_forward(cfg, w, empty, ctx_tokens, np.zeros(B, dtype=int), hidden_in=ctx_hidden)
+    kv = [[(kv0[l][0][b], kv0[l][1][b]) for b in range(B)] for l in range(cfg["n_layers"])]
+    drafts, q, kv_out, new_len, _ = od.draft_loop(cfg, w, kv, pending, np.full(B, C), k, T, 31, 2, pend_hidden)
+    # recomputation: one causal pass over the whole string with the hidden inputs assembled by hand
+    string = np.concatenate([ctx_tokens, pending], axis=1)
+    hidden = np.concatenate([ctx_hidden, pend_hidden], axis=1)
+    for i in range(k):
+        logits, _, h_out = of.verify_forward(cfg, w, empty, string, np.zeros(B, dtype=int), hidden_in=hidden, return_hidden=True)
+        x, qi = sampler.draft_sample(logits[:, -1, :].astype(np.float32), T, 31, 2, i)
+        assert np.array_equal(x, drafts[:, i]) and np.max(np.abs(qi - q[:, i, :])) < 1e-6
+        string = np.concatenate([string, x[:, None]], axis=1)
+        hidden = np.concatenate([hidden, h_out[:, -1:, :]], axis=1)          # the draft's own state before x
+    assert list(new_len) == [C + 2 + k - 1] * B
+    # a different pending hidden state changes the proposals' distribution
+    _, q2, _, _, _ = od.draft_loop(cfg, w, kv, pending, np.full(B, C), k, T, 31, 2, pend_hidden[:, ::-1, :] * 1.0 + 0.5)
+    assert np.max(np.abs(q2 - q)) > 1e-4
+    # next step's pending hidden states
+    H = rng.standard_normal((3, 4, d))
+    old = rng.standard_normal((3, 2, d))
+    new = od.next_pending_hidden(old, H, np.array([0, 2, 3]))
+    assert np.array_equal(new[0, 0], old[0, 1]) and np.array_equal(new[0, 1], H[0, 0])
+    assert np.array_equal(new[1, 0], H[1, 1]) and np.array_equal(new[1, 1], H[1, 2])
+    assert np.array_equal(new[2, 0], H[2, 2]) and np.array_equal(new[2, 1], H[2, 3])

@@ -240,3 +240,46 @@ def test_cache_storage_rounding_matches_library_conversion_and_is_applied_to_new
     # and the rounding matters: the unrounded variant differs
     plain, _ = of.verify_forward(dict(cfg, dtype="f64"), w, kv, tokens, [6])
     assert np.max(np.abs(plain - logits)) > 1e-6
+
+
+def test_hidden_state_input_against_torch_composition_and_special_cases():
+    """A draft that also takes hidden states: the first layer's input against torch library calls (rms_norm, cat,
+    linear), the returned hidden state against the logits it must reproduce, and three reductions: w_fuse = [A | 0]
+    ignores the hidden states; w_fuse = [0 | I] with unit gains starts the layers from RMSNorm(hidden); a hidden
+    input scaled by a constant changes nothing (it is normalised)."""
+    cfg = dict(CFG, n_layers=1, tied_head=1, fuse_hidden=1)
+    d = cfg["d_model"]
+    w = _weights(cfg, seed=4)
+    assert w["fuse"]["w_fuse"].shape == (d, 2 * d)
+    rng = np.random.default_rng(1)
+    ctx_len = np.array([3, 0])
+    kv = _random_ctx(cfg, ctx_len)
+    tokens = rng.integers(0, cfg["vocab"], size=(2, 3)).astype(np.int32)
+    hid = rng.standard_normal((2, 3, d)) * 2.5
+    logits, new_kv, h_out = of.verify_forward(cfg, w, kv, tokens, ctx_len, hidden_in=hid, return_hidden=True)
+    # (1) the layers run on x0 = linear(cat(rms_norm(embed), rms_norm(hidden))): feed x0 to a plain model through a
+    # one-hot "embedding" table holding x0 itself
+    T64 = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    e = F.rms_norm(F.embedding(torch.from_numpy(tokens.reshape(-1).astype(np.int64)), T64(w["embed"])), (d,), T64(w["fuse"]["norm_e"]), cfg["rms_eps"])
+    h = F.rms_norm(T64(hid.reshape(-1, d)), (d,), T64(w["fuse"]["norm_h"]), cfg["rms_eps"])
+    x0 = F.linear(torch.cat([e, h], dim=1), T64(w["fuse"]["w_fuse"])).numpy()
+    plain_cfg = dict(cfg, fuse_hidden=0, vocab=6, tied_head=0)
+    plain_w = dict(w, embed=x0, head=w["embed"])
+    ids = np.arange(6, dtype=np.int32).reshape(2, 3)
+    want = _torch_reference(plain_cfg, plain_w, kv, ids, ctx_len)
+    assert np.max(np.abs(logits - want)) < 1e-10 and np.max(np.abs(want)) > 0.05
+    # (2) the hidden state returned is what the head sees
+    again = of.rmsnorm(h_out.reshape(-1, d), w["final_norm"], cfg["rms_eps"]) @ np.asarray(w["embed"], dtype=np.float64).T
+    assert np.max(np.abs(again.reshape(logits.shape) - logits)) < 1e-10
+    # (3) reductions
+    wa = dict(w, fuse=dict(w["fuse"], w_fuse=np.concatenate([w["fuse"]["w_fuse"][:, :d], np.zeros((d, d))], axis=1)))
+    a1, _ = of.verify_forward(cfg, wa, kv, tokens, ctx_len, hidden_in=hid)
+    a2, _ = of.verify_forward(cfg, wa, kv, tokens, ctx_len, hidden_in=rng.standard_normal((2, 3, d)))
+    assert np.max(np.abs(a1 - a2)) < 1e-12 and np.max(np.abs(a1 - logits)) > 1e-3
+    wb = dict(w, fuse=dict(w_fuse=np.concatenate([np.zeros((d, d)), np.eye(d)], axis=1), norm_e=np.ones(d), norm_h=np.ones(d)))
+    b1, _ = of.verify_forward(cfg, wb, kv, tokens, ctx_len, hidden_in=hid)
+    table = of.rmsnorm(hid.reshape(-1, d), np.ones(d), cfg["rms_eps"])
+    b2 = _torch_reference(plain_cfg, dict(w, embed=table, head=w["embed"]), kv, ids, ctx_len)
+    assert np.max(np.abs(b1 - b2)) < 1e-10
+    c1, _ = of.verify_forward(cfg, w, kv, tokens, ctx_len, hidden_in=hid * 7.0)
+    assert np.max(np.abs(c1 - logits)) < 1e-4            # up to the epsilon inside the norm
