@@ -42,11 +42,14 @@ def run_steps(wl, sv, torch, n_steps, accept_out, step0, marks=None):
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if marks is not None else None
             if ev:
                 ev[0].record()
-            wl.loop.run(wl.seq_ids, wl.pending, wl.q, T, wl.seed, step0 + i)
+            wl.loop.run(wl.seq_ids, wl.pending, wl.q, T, wl.seed, step0 + i, pending_hidden=wl.pending_hidden)
             wl.tokens[:, 1:] = draft                             # drafted tokens into the verify input rows
             if ev:
                 ev[1].record()
-        sv.spec_verify_forward(sess.model, sess.kv, B, k, wl.seq_ids, wl.tokens, buf["logits"], ws)
+        if pair and wl.pending_hidden is not None:            # the draft consumes the target's hidden states: export them
+            sv.spec_verify_forward_hidden(sess.model, sess.kv, B, k, wl.seq_ids, wl.tokens, None, buf["logits"], wl.target_hidden, ws)
+        else:
+            sv.spec_verify_forward(sess.model, sess.kv, B, k, wl.seq_ids, wl.tokens, buf["logits"], ws)
         sv.spec_reject_sample(B, k, V, buf["logits"], wl.q, draft, T, wl.seed, step0 + i, accept_out[i],
                               buf["out_tokens"], None, buf["sample_ws"])
         sv.spec_commit_kv(sess.kv, B, k, wl.seq_ids, accept_out[i], buf["new_ctx_len"], buf["commit_slots"])
@@ -334,7 +337,7 @@ def main():
         times = []
         for rep in range(2):                      # first repetition warms up
             wl.restore()
-            roll.start(wl.pending[:, 0].contiguous(), wl.pending[:, 1].contiguous())
+            roll.start(wl.pending[:, 0].contiguous(), wl.pending[:, 1].contiguous(), wl.pending_hidden)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()

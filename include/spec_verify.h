@@ -52,20 +52,27 @@ const char* spec_last_error(void);
  * feed-forward, dense or a routed mixture of experts (the 235B-A22B-class target of Section 3.1):
  * router probabilities softmax(h Wr^T) over all experts, the top_k most probable experts (ties to the
  * lower index), their probabilities renormalised to sum to one, output = weighted sum of those
- * experts' SwiGLU feed-forwards of width expert_ffn_dim. */
+ * experts' SwiGLU feed-forwards of width expert_ffn_dim.
+ * fuse_hidden = 1 describes a draft model that takes the verifier's hidden states as a second input (the paper's
+ * drafting paths, Section 2.3: EAGLE-3 and native multi-token-prediction heads both consume target hidden states;
+ * the combination is the multi-token-prediction one): the first layer's input is
+ *     w_fuse . [ RMSNorm(embedding of the token) * fuse_e_norm ; RMSNorm(hidden state) * fuse_h_norm ],
+ * the hidden state being that of the position before the token (spec_verify_forward_hidden). */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
     float rope_theta, rms_eps;
     int32_t dtype;             /* SPEC_F32 or SPEC_BF16: storage type of weights and of the KV cache */
     int32_t tied_head;         /* 1: output head = embedding matrix */
     int32_t n_experts, top_k, expert_ffn_dim;   /* 0, 0, 0: dense feed-forward of width ffn_dim */
+    int32_t fuse_hidden;       /* 1: a draft model whose input also takes hidden states (bf16, dense, ffn_dim >= 2 d_model) */
 } spec_model_desc;
 
 typedef struct spec_model spec_model;
 typedef struct spec_kv spec_kv;
 typedef struct spec_graph spec_graph;
 
-/* Number of weight pointers spec_model_create expects: 1 + (9 + (n_experts ? 1 : 0))*n_layers + 1 + (tied_head ? 0 : 1). */
+/* Number of weight pointers spec_model_create expects:
+ * 1 + (9 + (n_experts ? 1 : 0))*n_layers + 1 + (tied_head ? 0 : 1) + (fuse_hidden ? 3 : 0). */
 int32_t spec_model_weight_count(const spec_model_desc* desc);
 
 /*
@@ -75,7 +82,8 @@ int32_t spec_model_weight_count(const spec_model_desc* desc);
  *              ffn_norm [d], wg [ffn, d], wu [ffn, d], wd [d, ffn];
  *              with n_experts > 0 instead: wg [E, Fe, d], wu [E, Fe, d], wd [E, d, Fe] (the experts stacked,
  *              Fe = expert_ffn_dim), then router [E, d];
- *   final_norm [d]; head [vocab, d] unless tied_head.
+ *   final_norm [d]; head [vocab, d] unless tied_head;
+ *   with fuse_hidden: w_fuse [d, 2d] (columns 0..d-1 meet the embedding half), fuse_e_norm [d], fuse_h_norm [d].
  * SPEC_F32: the pointers are borrowed for the model's lifetime (kernels read them in place).
  * SPEC_BF16: the matrices are re-tiled once into a library-owned device buffer laid out for the
  * MFMA kernels (one hipMalloc of about the model's size); afterwards only embed and the norm
@@ -160,11 +168,19 @@ spec_status spec_kv_restore(spec_kv* kv, const void* dev_buf, void* stream);
  * Errors: SPEC_EINVAL (null, B < 1, k < 0, k > SPEC_MAX_DRAFT, workspace too small, kv of another
  * model), SPEC_ENOMEM (the pool cannot hold k+1 more positions for every batch entry),
  * SPEC_EHIP.  Asynchronous on `stream`.
+ *
+ * spec_verify_forward_hidden is the same pass with the hidden states exposed (bf16 models): dev_hidden_out
+ * [B, k+1, d_model] fp32 (may be NULL) receives the residual stream after the last layer, before the final norm -
+ * what a hidden-state-consuming draft model is fed; dev_hidden_in [B, k+1, d_model] fp32 is required for a model
+ * created with fuse_hidden (row i: the hidden state of the position before input row i) and must be NULL otherwise.
  */
 size_t spec_verify_workspace_bytes(const spec_model* model, const spec_kv* kv, int32_t B, int32_t k);
 spec_status spec_verify_forward(spec_model* model, spec_kv* kv, int32_t B, int32_t k,
                                 const int32_t* dev_seq_ids, const int32_t* dev_tokens, float* dev_logits,
                                 void* dev_workspace, size_t workspace_bytes, void* stream);
+spec_status spec_verify_forward_hidden(spec_model* model, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                       const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits,
+                                       float* dev_hidden_out, void* dev_workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Lossless rejection sampling (the rejection procedure of Section 2.1; acceptance length as in
@@ -269,6 +285,18 @@ int32_t spec_profile_class_count(void);
 const char* spec_profile_class_name(int32_t c);
 spec_status spec_profile_begin(int32_t max_events);
 spec_status spec_profile_end(double* host_ms, int64_t* host_counts, int32_t n);
+
+/*
+ * Hidden states for the next step's two pending tokens of a hidden-state-consuming draft model (see
+ * spec_next_step_inputs: the last input the verifier kept, and the token it emitted): the verifier's hidden states
+ * of the positions before them.  With n = dev_accept_len[b] clamped to [0, k] and H = dev_target_hidden
+ * [B, k+1, d] (spec_verify_forward_hidden of the step just sampled), dev_pending_hidden [B, 2, d] becomes
+ *   row 0 = H[b][n-1] if n >= 1, else its own old row 1 (the state that was paired with the old emitted token),
+ *   row 1 = H[b][n].
+ * fp32, plain copies.  Asynchronous on `stream`.
+ */
+spec_status spec_next_step_hidden(int32_t B, int32_t k, int32_t d, const float* dev_target_hidden,
+                                  const int32_t* dev_accept_len, float* dev_pending_hidden, void* stream);
 
 /*
  * Model-free n-gram drafting (the paper's n-gram baseline: Section 3.1 set-up, Section 3.2 and Table 2; the paper

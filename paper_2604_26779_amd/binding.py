@@ -23,7 +23,7 @@ EXPORTS = [
     "spec_last_error", "spec_model_weight_count", "spec_model_create", "spec_model_destroy", "spec_kv_pool_bytes",
     "spec_kv_alloc", "spec_kv_free", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
-    "spec_verify_workspace_bytes", "spec_verify_forward", "spec_sample_workspace_bytes", "spec_reject_sample",
+    "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample",
     "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_graph_capture_begin", "spec_graph_capture_end", "spec_graph_launch",
     "spec_graph_destroy", "spec_calib_read", "spec_calib_copy",
@@ -41,7 +41,7 @@ class spec_model_desc(ctypes.Structure):
                                               "ffn_dim", "vocab")] + \
                [("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("dtype", ctypes.c_int32),
                 ("tied_head", ctypes.c_int32), ("n_experts", ctypes.c_int32), ("top_k", ctypes.c_int32),
-                ("expert_ffn_dim", ctypes.c_int32)]
+                ("expert_ffn_dim", ctypes.c_int32), ("fuse_hidden", ctypes.c_int32)]
 
 
 _lib = None
@@ -75,6 +75,8 @@ def lib():
             "spec_kv_restore": (i32, [vp, vp, vp]),
             "spec_verify_workspace_bytes": (sz, [vp, vp, i32, i32]),
             "spec_verify_forward": (i32, [vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]),
+            "spec_verify_forward_hidden": (i32, [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]),
+            "spec_next_step_hidden": (i32, [i32, i32, i32, vp, vp, vp, vp]),
             "spec_sample_workspace_bytes": (sz, [i32, i32]),
             "spec_reject_sample": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp, sz, vp]),
             "spec_commit_kv": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
@@ -143,6 +145,7 @@ def make_desc(cfg):
     d.dtype = {"f32": SPEC_F32, "bf16": SPEC_BF16}[cfg["dtype"]]
     d.tied_head = int(cfg.get("tied_head", 0))
     d.n_experts, d.top_k, d.expert_ffn_dim = (int(cfg.get(n, 0)) for n in ("n_experts", "top_k", "expert_ffn_dim"))
+    d.fuse_hidden = int(cfg.get("fuse_hidden", 0))
     return d
 
 
@@ -227,6 +230,17 @@ def spec_verify_workspace_bytes(model, kv, B, k):
 def spec_verify_forward(model, kv, B, k, seq_ids, tokens, logits, workspace, stream=None):
     _check(lib().spec_verify_forward(model, kv, B, k, _ptr(seq_ids), _ptr(tokens), _ptr(logits), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def spec_verify_forward_hidden(model, kv, B, k, seq_ids, tokens, hidden_in, logits, hidden_out, workspace, stream=None):
+    """hidden_in / hidden_out: [B, k+1, d] fp32 device tensors or None."""
+    _check(lib().spec_verify_forward_hidden(model, kv, B, k, _ptr(seq_ids), _ptr(tokens), _ptr(hidden_in), _ptr(logits),
+                                            _ptr(hidden_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream(stream)))
+
+
+def spec_next_step_hidden(B, k, d, target_hidden, accept_len, pending_hidden, stream=None):
+    _check(lib().spec_next_step_hidden(B, k, int(d), _ptr(target_hidden), _ptr(accept_len), _ptr(pending_hidden), _stream(stream)))
 
 
 def spec_sample_workspace_bytes(B, k):

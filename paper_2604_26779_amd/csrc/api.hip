@@ -125,7 +125,7 @@ extern "C" int32_t spec_tune_get(const char* name)
 extern "C" int32_t spec_model_weight_count(const spec_model_desc* d)
 {
     if (!d || d->n_layers < 0) return -1;
-    return 1 + (9 + (d->n_experts > 0 ? 1 : 0)) * d->n_layers + 1 + (d->tied_head ? 0 : 1);
+    return 1 + (9 + (d->n_experts > 0 ? 1 : 0)) * d->n_layers + 1 + (d->tied_head ? 0 : 1) + (d->fuse_hidden ? 3 : 0);
 }
 
 static spec_status check_desc(const spec_model_desc& d)
@@ -142,6 +142,12 @@ static spec_status check_desc(const spec_model_desc& d)
         if (d.dtype != SPEC_BF16) { set_error("spec_model_create: the fp32 path is dense only"); return SPEC_EUNSUPPORTED; }
         if (d.n_experts > 256 || d.top_k < 1 || d.top_k > 16 || d.top_k > d.n_experts || d.expert_ffn_dim < 1 || d.expert_ffn_dim % 256) {
             set_error("spec_model_create: mixture of experts needs n_experts <= 256, 1 <= top_k <= min(n_experts, 16), expert_ffn_dim %% 256 == 0");
+            return SPEC_EUNSUPPORTED;
+        }
+    }
+    if (d.fuse_hidden) {
+        if (d.dtype != SPEC_BF16 || d.n_experts > 0 || d.ffn_dim < 2 * d.d_model) {
+            set_error("spec_model_create: a model with hidden-state input must be bf16, dense, with ffn_dim >= 2 * d_model");
             return SPEC_EUNSUPPORTED;
         }
     }
@@ -184,6 +190,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         if (E > 0) elems += (size_t)L * ((size_t)E * (bf16_packed_elems(2 * Fe, D) + bf16_packed_elems(D, Fe)) + bf16_packed_elems(E, D));
         else elems += (size_t)L * (bf16_packed_elems(2 * F, D) + bf16_packed_elems(D, F));
         elems += bf16_packed_elems(d.vocab, D);
+        if (d.fuse_hidden) elems += bf16_packed_elems(D, 2 * D);
         m->arena_bytes = elems * sizeof(bf16_t);
         hipError_t e = hipMalloc(&m->arena, m->arena_bytes);
         if (e != hipSuccess) {
@@ -223,6 +230,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
             }
         }
         if (st == SPEC_OK) st = pack({m->head_w()}, {d.vocab}, D, &m->head);
+        if (st == SPEC_OK && d.fuse_hidden) st = pack({m->fuse_w(0)}, {D}, 2 * D, &m->wfuse);
         if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }
         if (st != SPEC_OK) { (void)hipFree(m->arena); delete m; return st; }
     }
@@ -433,11 +441,17 @@ extern "C" size_t spec_verify_workspace_bytes(const spec_model* m, const spec_kv
     return m->desc.dtype == SPEC_F32 ? f32_workspace_bytes(m->desc, B, k) : bf16_workspace_bytes(m, kv, B, k);
 }
 
-extern "C" spec_status spec_verify_forward(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
-                                           const int32_t* dev_tokens, float* dev_logits, void* ws, size_t ws_bytes, void* stream)
+extern "C" spec_status spec_verify_forward_hidden(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                                  const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits,
+                                                  float* dev_hidden_out, void* ws, size_t ws_bytes, void* stream)
 {
     if (!m || !kv || !dev_seq_ids || !dev_tokens || !dev_logits || !ws) { set_error("spec_verify_forward: null pointer"); return SPEC_EINVAL; }
     if (kv->model != m) { set_error("spec_verify_forward: the cache belongs to another model"); return SPEC_EINVAL; }
+    if ((m->desc.fuse_hidden != 0) != (dev_hidden_in != nullptr)) {
+        set_error("spec_verify_forward: hidden-state input %s", m->desc.fuse_hidden ? "is required by this model (spec_verify_forward_hidden)" : "given to a model that takes none");
+        return SPEC_EINVAL;
+    }
+    if (dev_hidden_out && m->desc.dtype != SPEC_BF16) { set_error("spec_verify_forward_hidden: hidden-state output needs a bf16 model"); return SPEC_EUNSUPPORTED; }
     if (B < 1 || B > kv->max_seqs || k < 0 || k > SPEC_MAX_DRAFT) { set_error("spec_verify_forward: B or k out of range"); return SPEC_EINVAL; }
     if (ws_bytes < spec_verify_workspace_bytes(m, kv, B, k)) { set_error("spec_verify_forward: workspace too small (%zu < %zu)", ws_bytes, spec_verify_workspace_bytes(m, kv, B, k)); return SPEC_EINVAL; }
     if (((uintptr_t)ws & 255) != 0) { set_error("spec_verify_forward: workspace must be 256-byte aligned"); return SPEC_EINVAL; }
@@ -464,8 +478,14 @@ extern "C" spec_status spec_verify_forward(spec_model* m, spec_kv* kv, int32_t B
     prof_mark(PC_KV_RESERVE, s);
     kv->device_ahead = true;
     st = m->desc.dtype == SPEC_F32 ? f32_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_logits, ws, s)
-                                   : bf16_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_logits, ws, ws_bytes, s);
+                                   : bf16_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_hidden_in, dev_logits, dev_hidden_out, ws, ws_bytes, s);
     return st;
+}
+
+extern "C" spec_status spec_verify_forward(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                           const int32_t* dev_tokens, float* dev_logits, void* ws, size_t ws_bytes, void* stream)
+{
+    return spec_verify_forward_hidden(m, kv, B, k, dev_seq_ids, dev_tokens, nullptr, dev_logits, nullptr, ws, ws_bytes, stream);
 }
 
 extern "C" spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids, const int32_t* dev_accept_len,

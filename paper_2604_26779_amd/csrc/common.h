@@ -80,13 +80,15 @@ struct spec_model {
     std::vector<specv::PackedW> wqkv, wo, wgu, wd;   // mixture of experts: wgu / wd describe expert 0, the
     std::vector<specv::PackedW> router;              // others follow at moe_gu_stride / moe_d_stride elements
     int64_t moe_gu_stride = 0, moe_d_stride = 0;
-    specv::PackedW head;
+    specv::PackedW head, wfuse;
     bool moe() const { return desc.n_experts > 0; }
     int per_layer() const { return moe() ? 10 : 9; }
     const void* embed() const { return w[0]; }
     const void* layer_w(int l, int i) const { return w[1 + per_layer() * l + i]; }   // i: 0 attn_norm .. 8 wd, 9 router
     const void* final_norm() const { return w[1 + per_layer() * desc.n_layers]; }
     const void* head_w() const { return desc.tied_head ? w[0] : w[2 + per_layer() * desc.n_layers]; }
+    // fuse_hidden: w_fuse, fuse_e_norm, fuse_h_norm follow the head
+    const void* fuse_w(int i) const { return w[2 + per_layer() * desc.n_layers + (desc.tied_head ? 0 : 1) + i]; }
 };
 
 struct spec_kv {
@@ -142,7 +144,8 @@ spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_row
                              bf16_t* dev_out, PackedW* out, bool interleave, hipStream_t s);
 size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k);
 spec_status bf16_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids,
-                         const int32_t* dev_tokens, float* dev_logits, void* ws, size_t ws_bytes, hipStream_t s);
+                         const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits, float* dev_hidden_out,
+                         void* ws, size_t ws_bytes, hipStream_t s);
 
 // in-block layouts of the cache, by storage type (host + device)
 __host__ __device__ inline int64_t kv_block_offset(int dtype, int is_v, int t, int c, int head_dim)

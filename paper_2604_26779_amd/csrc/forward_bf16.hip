@@ -48,9 +48,10 @@ __device__ inline float block_sum(float v, float* lds16)
     return t;
 }
 
-// x[m] = (FIRST ? embed[token] : x[m] + sum_s part[s][m]);  xp = RMSNorm(x[m]) * gain
+// x[m] = embed[token] (RES_EMBED), x[m] + sum_s part[s][m] (RES_ADD) or sum_s part[s][m] (RES_SET);  xp = RMSNorm(x[m]) * gain
 // one workgroup per row (256 or 512 threads, 8 elements per thread and pass); d % 8 == 0
-template <bool FIRST>
+constexpr int RES_ADD = 0, RES_EMBED = 1, RES_SET = 2;
+template <int MODE>
 __global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
     float* __restrict__ x, const float* __restrict__ part, int splits, int64_t split_stride, const int32_t* __restrict__ tokens,
     const unsigned short* __restrict__ embed, int vocab, const unsigned short* __restrict__ gain, int d, float eps, int mb_pad,
@@ -62,6 +63,7 @@ __global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
     float* xr = x + (int64_t)m * d;
     float ss = 0.f;
     int tok = 0;
+    constexpr bool FIRST = MODE == RES_EMBED;
     if (FIRST) { tok = tokens[m]; tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok); }
     for (int c = threadIdx.x * 8; c < d; c += stride) {
         float v[8];
@@ -71,7 +73,8 @@ __global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) { v[2 * j] = from_bf16(w[j] & 0xffff); v[2 * j + 1] = from_bf16(w[j] >> 16); }
         } else {
-            float4 a = *(const float4*)(xr + c), b = *(const float4*)(xr + c + 4);
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            if (MODE == RES_ADD) { a = *(const float4*)(xr + c); b = *(const float4*)(xr + c + 4); }
             for (int s = 0; s < splits; ++s) {
                 const float* ps = part + s * split_stride + (int64_t)m * d + c;
                 float4 p0 = *(const float4*)ps, p1 = *(const float4*)(ps + 4);
@@ -94,6 +97,49 @@ __global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
                       a.w * r * from_bf16(g.y >> 16),    b.x * r * from_bf16(g.z & 0xffff), b.y * r * from_bf16(g.z >> 16),
                       b.z * r * from_bf16(g.w & 0xffff), b.w * r * from_bf16(g.w >> 16)};
         xp_store8(xp, m, c, mb_pad, v);
+    }
+}
+
+// Input of a draft model that also takes hidden states: the operand of the fusion projection,
+// [RMSNorm(embed[token]) * g_e ; RMSNorm(hidden_in[m]) * g_h] (2d channels), as hi + lo bf16.  One workgroup per row.
+__global__ __launch_bounds__(512) void fuse_input_kernel(
+    const int32_t* __restrict__ tokens, const unsigned short* __restrict__ embed, int vocab, const float* __restrict__ hidden_in,
+    const unsigned short* __restrict__ gain_e, const unsigned short* __restrict__ gain_h, int d, float eps, int mb_pad,
+    uint4* __restrict__ xp)
+{
+    __shared__ float lds16[16];
+    const int m = blockIdx.x;
+    const int stride = blockDim.x * 8;
+    int tok = tokens[m];
+    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+    const unsigned short* er = embed + (int64_t)tok * d;
+    const float* hr = hidden_in + (int64_t)m * d;
+    float ss_e = 0.f, ss_h = 0.f;
+    for (int c = threadIdx.x * 8; c < d; c += stride) {
+        uint4 e = *(const uint4*)(er + c);
+        unsigned int w[4] = {e.x, e.y, e.z, e.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { float lo = from_bf16(w[j] & 0xffff), hi = from_bf16(w[j] >> 16); ss_e += lo * lo + hi * hi; }
+        float4 a = *(const float4*)(hr + c), b = *(const float4*)(hr + c + 4);
+        ss_h += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+    }
+    const float re = 1.0f / sqrtf(block_sum(ss_e, lds16) / (float)d + eps);
+    const float rh = 1.0f / sqrtf(block_sum(ss_h, lds16) / (float)d + eps);
+    for (int c = threadIdx.x * 8; c < d; c += stride) {
+        uint4 e = *(const uint4*)(er + c), ge = *(const uint4*)(gain_e + c), gh = *(const uint4*)(gain_h + c);
+        unsigned int w[4] = {e.x, e.y, e.z, e.w}, g1[4] = {ge.x, ge.y, ge.z, ge.w}, g2[4] = {gh.x, gh.y, gh.z, gh.w};
+        float4 a = *(const float4*)(hr + c), b = *(const float4*)(hr + c + 4);
+        float hv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        float ve[8], vh[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            ve[2 * j] = from_bf16(w[j] & 0xffff) * re * from_bf16(g1[j] & 0xffff);
+            ve[2 * j + 1] = from_bf16(w[j] >> 16) * re * from_bf16(g1[j] >> 16);
+            vh[2 * j] = hv[2 * j] * rh * from_bf16(g2[j] & 0xffff);
+            vh[2 * j + 1] = hv[2 * j + 1] * rh * from_bf16(g2[j] >> 16);
+        }
+        xp_store8(xp, m, c, mb_pad, ve);
+        xp_store8(xp, m, d + c, mb_pad, vh);
     }
 }
 
@@ -207,7 +253,7 @@ __global__ void swiglu_pack_kernel(const float* __restrict__ part, int splits, i
 struct Bf16Plan {
     int M, mb_pad, max_chunks, RBrows;
     bool fuse_swiglu;
-    int s_qkv, s_o, s_gu, s_down, s_head;
+    int s_qkv, s_o, s_gu, s_down, s_head, s_fuse;
     size_t off_x, off_xp_h, off_xp_a, off_xp_f, off_part, off_q, off_rope, off_att_o, off_att_ml, total;
     // mixture of experts: padded-row bound, router splits, routing tables, permuted activations, expert outputs
     int moe_rows, s_router;
@@ -232,6 +278,7 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.s_gu = (p.fuse_swiglu || moe) ? 1 : gemm_pick_splits(m->wgu[0], p.M, tune("splits_gu"));
     p.s_down = moe ? 1 : gemm_pick_splits(m->wd[0], p.M, tune("splits_down"));
     p.s_head = 1;
+    p.s_fuse = d.fuse_hidden ? gemm_pick_splits(m->wfuse, p.M, 0) : 0;
     p.s_router = moe ? gemm_pick_splits(m->router[0], p.M, 0) : 0;
     p.moe_rows = moe ? moe_rows_bound(p.M, d.top_k, d.n_experts) : 0;
     int D = d.d_model, F = moe ? d.expert_ffn_dim : d.ffn_dim, nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
@@ -244,6 +291,7 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.off_xp_f = take((moe ? (size_t)p.moe_rows : rows) * F * 4);     // mixture: the permuted rows' silu(gate)*up
     size_t part = std::max(std::max((size_t)p.s_qkv * nqkv, (size_t)p.s_o * D), std::max((size_t)p.s_gu * 2 * F, (size_t)p.s_down * D));
     if (moe) part = std::max(std::max((size_t)p.s_qkv * nqkv, (size_t)p.s_o * D), (size_t)p.s_router * d.n_experts);
+    part = std::max(part, (size_t)p.s_fuse * D);
     p.off_part = take(part * p.M * 4);
     if (moe) {
         size_t pairs = (size_t)p.M * d.top_k;
@@ -271,7 +319,7 @@ size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k
 }
 
 spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, const int32_t* dev_tokens,
-                         float* dev_logits, void* ws, size_t ws_bytes, hipStream_t s)
+                         const float* dev_hidden_in, float* dev_logits, float* dev_hidden_out, void* ws, size_t ws_bytes, hipStream_t s)
 {
     const spec_model_desc& d = mdl->desc;
     const int T = k + 1, G = d.n_q_heads / d.n_kv_heads;
@@ -303,8 +351,18 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     const int norm_threads = D >= 4096 ? 512 : 256;
 
     rope_table_kernel<<<(unsigned)cdiv((int64_t)M * 64, 256), 256, 0, s>>>(M, T, dev_seq_ids, kv->d_ctx_len, 64, (double)d.rope_theta, rope);
-    residual_rmsnorm_kernel<true><<<M, norm_threads, 0, s>>>(x, nullptr, 0, 0, dev_tokens, (const unsigned short*)mdl->embed(), d.vocab,
-                                                    (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+    if (d.fuse_hidden) {
+        // hidden-state input: x = w_fuse . [RMSNorm(embed) ; RMSNorm(hidden_in)] (the feed-forward operand buffer is free here)
+        fuse_input_kernel<<<M, norm_threads, 0, s>>>(dev_tokens, (const unsigned short*)mdl->embed(), d.vocab, dev_hidden_in,
+                                                     (const unsigned short*)mdl->fuse_w(1), (const unsigned short*)mdl->fuse_w(2), D, d.rms_eps,
+                                                     p.mb_pad, (uint4*)xp_f);
+        if ((st = launch_gemm_bf16(mdl->wfuse, xp_f, M, part, D, p.s_fuse, false, s)) != SPEC_OK) return st;
+        residual_rmsnorm_kernel<RES_SET><<<M, norm_threads, 0, s>>>(x, part, p.s_fuse, (int64_t)M * D, nullptr, nullptr, 0,
+                                                                   (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+    } else {
+        residual_rmsnorm_kernel<RES_EMBED><<<M, norm_threads, 0, s>>>(x, nullptr, 0, 0, dev_tokens, (const unsigned short*)mdl->embed(), d.vocab,
+                                                        (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+    }
     prof_mark(PC_EMBED_NORM, s);
     for (int l = 0; l < d.n_layers; ++l) {
         int lp = kv->alias_mod > 0 ? l % kv->alias_mod : l;
@@ -315,7 +373,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_pages, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
         if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_O, s);
-        residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
+        residual_rmsnorm_kernel<RES_ADD><<<M, norm_threads, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)mdl->layer_w(l, 5), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
         const void* next_gain = l + 1 < d.n_layers ? mdl->layer_w(l + 1, 0) : mdl->final_norm();
@@ -356,9 +414,16 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         }
         if ((st = launch_gemm_bf16(mdl->wd[l], xp_f, M, part, D, p.s_down, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_DOWN, s);
-        residual_rmsnorm_kernel<false><<<M, norm_threads, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
+        residual_rmsnorm_kernel<RES_ADD><<<M, norm_threads, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
+    }
+    if (dev_hidden_out) {
+        // the residual stream after the last layer: what a hidden-state-consuming draft model is fed
+        if (hipMemcpyAsync(dev_hidden_out, x, (size_t)M * D * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess) {
+            set_error("spec_verify_forward_hidden: copy of the hidden states failed");
+            return SPEC_EHIP;
+        }
     }
     if ((st = launch_gemm_bf16(mdl->head, xp_h, M, dev_logits, d.vocab, 1, false, s)) != SPEC_OK) return st;
     prof_mark(PC_GEMM_HEAD, s);

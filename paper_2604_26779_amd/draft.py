@@ -17,22 +17,41 @@ class DraftLoop:
         self.zeros = torch.zeros(B, dtype=torch.int32, device=dev)
         self.drafts = torch.zeros((B, k), dtype=torch.int32, device=dev)
         self.new_len = torch.zeros(B, dtype=torch.int32, device=dev)
+        # a draft that takes hidden states chains its own: the last row of a pass feeds the next pass
+        self.fused = bool(draft_session.cfg.get("fuse_hidden", 0))
+        d = draft_session.cfg["d_model"]
+        self.hid_first = None                                               # [B, P, d], allocated on first use
+        self.hid = [torch.zeros((B, 1, d), dtype=torch.float32, device=dev) for _ in range(2)] if self.fused else None
 
-    def run(self, seq_ids, pending, q_out, temperature, seed, step, stream=None):
-        """pending [B, P] int32 (tokens the draft's cache lacks; P = 2 in steady state), q_out [B, k, V] fp32.
+    def run(self, seq_ids, pending, q_out, temperature, seed, step, stream=None, pending_hidden=None):
+        """pending [B, P] int32 (tokens the draft's cache lacks; P = 2 in steady state), q_out [B, k, V] fp32;
+        pending_hidden [B, P, d] fp32 for a draft with hidden-state input (the verifier's hidden state of the position
+        before each pending token).
 
         Fills self.drafts [B, k] and q_out; the draft's cache grows by P + k - 1 positions."""
         sess, B, k = self.sess, self.B, self.k
         V = sess.cfg["vocab"]
         P = pending.shape[1]
         assert q_out.shape == (B, k, V) and q_out.is_contiguous() and pending.is_contiguous()
+        if self.fused:
+            assert pending_hidden is not None and pending_hidden.is_contiguous()
+            if self.hid_first is None or self.hid_first.shape[1] != P:
+                self.hid_first = torch.zeros((B, P, sess.cfg["d_model"]), dtype=torch.float32, device=sess.device)
         for i in range(k):
             if i == 0:
-                logits = sess.forward(seq_ids, pending, stream)                          # [B, P, V]
+                if self.fused:
+                    logits = sess.forward(seq_ids, pending, stream, hidden_in=pending_hidden, hidden_out=self.hid_first)
+                    self.hid[0].copy_(self.hid_first[:, P - 1:P, :])
+                else:
+                    logits = sess.forward(seq_ids, pending, stream)                      # [B, P, V]
                 last = logits.data_ptr() + (P - 1) * V * 4
                 stride = P * V
             else:
-                logits = sess.forward(seq_ids, self.feed.view(B, 1), stream)            # [B, 1, V]
+                if self.fused:
+                    logits = sess.forward(seq_ids, self.feed.view(B, 1), stream, hidden_in=self.hid[(i - 1) & 1],
+                                          hidden_out=self.hid[i & 1])
+                else:
+                    logits = sess.forward(seq_ids, self.feed.view(B, 1), stream)        # [B, 1, V]
                 last, stride = logits.data_ptr(), V
             sv.spec_draft_sample(B, V, last, stride, temperature, seed, step, i,
                                  self.drafts.data_ptr() + 4 * i, k, self.feed, 1,
@@ -67,12 +86,20 @@ class RolloutLoop:
         self.tokens = torch.zeros((B, k + 1), dtype=torch.int32, device=dev)
         self.pending = torch.zeros((B, 2), dtype=torch.int32, device=dev)
         self.q = torch.zeros((B, k, V), dtype=torch.float32, device=dev)
+        self.fused = self.loop.fused
+        if self.fused:
+            d = target_session.cfg["d_model"]
+            self.pending_hidden = torch.zeros((B, 2, d), dtype=torch.float32, device=dev)
+            self.target_hidden = torch.zeros((B, k + 1, d), dtype=torch.float32, device=dev)
 
-    def start(self, prev, t0):
-        """prev, t0 [B] int32 device tensors: the last input the target has cached and the last emitted token."""
+    def start(self, prev, t0, pending_hidden=None):
+        """prev, t0 [B] int32 device tensors: the last input the target has cached and the last emitted token;
+        pending_hidden [B, 2, d] for a draft with hidden-state input: the target's hidden states before each of them."""
         self.pending[:, 0] = prev
         self.pending[:, 1] = t0
         self.tokens[:, 0] = t0
+        if self.fused:
+            self.pending_hidden.copy_(pending_hidden)
 
     def run(self, seq_ids, n_steps, temperature, seed, step0=0, accept_out=None, tokens_out=None, stream=None):
         """accept_out [n_steps, B] int32, tokens_out [n_steps, B, k+1] int32 (device, optional) receive every
@@ -84,16 +111,23 @@ class RolloutLoop:
         off = (-ws.data_ptr()) % 256
         ws = ws[off:off + ws.numel() - 256]
         for s in range(n_steps):
-            drafts = self.loop.run(seq_ids, self.pending, self.q, temperature, seed, step0 + s, stream)
+            drafts = self.loop.run(seq_ids, self.pending, self.q, temperature, seed, step0 + s, stream,
+                                   self.pending_hidden if self.fused else None)
             self.tokens[:, 1:] = drafts
             acc = accept_out[s] if accept_out is not None else buf["accept_len"]
             out = tokens_out[s] if tokens_out is not None else buf["out_tokens"]
-            sv.spec_verify_forward(t.model, t.kv, B, k, seq_ids, self.tokens, buf["logits"], ws, stream)
+            if self.fused:
+                sv.spec_verify_forward_hidden(t.model, t.kv, B, k, seq_ids, self.tokens, None, buf["logits"], self.target_hidden,
+                                              ws, stream)
+            else:
+                sv.spec_verify_forward(t.model, t.kv, B, k, seq_ids, self.tokens, buf["logits"], ws, stream)
             sv.spec_reject_sample(B, k, V, buf["logits"], self.q, drafts, temperature, seed, step0 + s, acc, out, None,
                                   buf["sample_ws"], stream)
             sv.spec_commit_kv(t.kv, B, k, seq_ids, acc, buf["new_ctx_len"], None, stream)
             self.loop.roll_back(seq_ids, buf["new_ctx_len"], stream)
             sv.spec_next_step_inputs(B, k, self.tokens, out, acc, self.pending, stream)
+            if self.fused:
+                sv.spec_next_step_hidden(B, k, t.cfg["d_model"], self.target_hidden, acc, self.pending_hidden, stream)
 
 
 class NgramRollout:

@@ -99,14 +99,19 @@ class VerifySession:
             )
         return self._bufs[key]
 
-    def forward(self, seq_ids, tokens, stream=None):
-        """seq_ids [B] int32, tokens [B, k+1] int32 device tensors -> logits [B, k+1, V] (device, fp32)."""
+    def forward(self, seq_ids, tokens, stream=None, hidden_in=None, hidden_out=None):
+        """seq_ids [B] int32, tokens [B, k+1] int32 device tensors -> logits [B, k+1, V] (device, fp32).
+        hidden_in / hidden_out [B, k+1, d] fp32: hidden-state input of a fuse_hidden model / hidden states out."""
         B, T = tokens.shape
         buf = self.step_buffers(B, T - 1)
         ws = buf["workspace"]
         off = (-ws.data_ptr()) % 256
-        sv.spec_verify_forward(self.model, self.kv, B, T - 1, seq_ids, tokens, buf["logits"], ws[off:off + ws.numel() - 256],
-                               stream)
+        if hidden_in is None and hidden_out is None:
+            sv.spec_verify_forward(self.model, self.kv, B, T - 1, seq_ids, tokens, buf["logits"], ws[off:off + ws.numel() - 256],
+                                   stream)
+        else:
+            sv.spec_verify_forward_hidden(self.model, self.kv, B, T - 1, seq_ids, tokens, hidden_in, buf["logits"], hidden_out,
+                                          ws[off:off + ws.numel() - 256], stream)
         return buf["logits"]
 
     def sample(self, logits, q, draft, temperature, seed, step, stream=None, debug=True):

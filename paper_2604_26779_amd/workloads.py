@@ -139,6 +139,11 @@ class DraftPairWorkload(DeviceWorkload):
         prev = torch.from_numpy(rng.integers(0, self.cfg["vocab"], size=B).astype(np.int32)).to(device)
         self.pending = torch.stack([prev, self.tokens[:, 0]], dim=1).contiguous()
         self.loop = DraftLoop(self.dsess, B, k)
+        # a draft with hidden-state input: the target's hidden states before the two pending tokens (synthetic)
+        self.pending_hidden = None
+        if self.draft_cfg.get("fuse_hidden", 0):
+            self.pending_hidden = torch.randn((B, 2, self.cfg["d_model"]), generator=g, device=device, dtype=torch.float32)
+            self.target_hidden = torch.zeros((B, k + 1, self.cfg["d_model"]), dtype=torch.float32, device=device)
         self.dsnapshot = torch.empty(sv.spec_kv_state_bytes(self.dsess.kv), dtype=torch.uint8, device=device)
         sv.spec_kv_snapshot(self.dsess.kv, self.dsnapshot)
 

@@ -15,7 +15,7 @@ from oracle import commit as oracle_commit
 from oracle import draft as oracle_draft
 from oracle import forward as of
 from oracle import sampler as oracle_sampler
-from tests.helpers import random_norm_gains, sampler_exemptions
+from tests.helpers import logits_close, random_norm_gains, sampler_exemptions
 
 pytestmark = pytest.mark.gpu
 
@@ -95,6 +95,8 @@ def _setup_pair(name, seed=7):
     out = dict(wl=wl, B=B, k=k, ctx=ctx, batch=batch)
     rng = np.random.default_rng(seed)
     out["prev"] = rng.integers(0, cfg_t["vocab"], size=B).astype(np.int32)
+    # a draft with hidden-state input also gets the target's hidden states before its two pending tokens (inputs here)
+    out["pend_hidden"] = (rng.standard_normal((B, 2, cfg_t["d_model"])) * 1.5).astype(np.float32) if cfg_d.get("fuse_hidden", 0) else None
     for tag, cfg, clen, s in (("t", cfg_t, ctx, seed), ("d", cfg_d, ctx - 1, seed + 17)):
         weights = random_norm_gains(si.make_weights(cfg, seed=s), s)
         kv = si.make_logical_kv(cfg, clen, seed=s)
@@ -138,7 +140,7 @@ def _compare_drafts(x_gpu, q_gpu, x_or, q_or, keys, tol):
     return valid, exempt
 
 
-@pytest.mark.parametrize("name", ["draft_pair_tiny_b4_k3", "draft_pair_small_b5_k4"])
+@pytest.mark.parametrize("name", ["draft_pair_tiny_b4_k3", "draft_pair_small_b5_k4", "draft_pair_fused_small_b5_k4"])
 def test_draft_loop_and_pair_step_parity(name):
     from paper_2604_26779_amd.draft import DraftLoop
     S = _setup_pair(name)
@@ -152,7 +154,8 @@ def test_draft_loop_and_pair_step_parity(name):
     pending = np.stack([S["prev"], t0], axis=1).astype(np.int32)
 
     # ---- oracle: draft loop, verify forward on its drafts, rejection sampling, commit, roll-back
-    x_or, q_or, _, dlen_or, keys = oracle_draft.draft_loop(d["cfg"], d["w_or"], d["kv_or"], pending, d["ctx"], k, T, seed, step)
+    x_or, q_or, _, dlen_or, keys = oracle_draft.draft_loop(d["cfg"], d["w_or"], d["kv_or"], pending, d["ctx"], k, T, seed, step,
+                                                           S["pend_hidden"])
     tokens_or = np.concatenate([t0[:, None], x_or], axis=1).astype(np.int32)
     logits_or, _ = of.verify_forward(t["cfg"], t["w_or"], t["kv_or"], tokens_or, t["ctx"])
     n_or, out_or, pqu, rkeys = oracle_sampler.reject_sample(logits_or.astype(np.float32), q_or, x_or, T, seed, step, debug=True)
@@ -170,7 +173,8 @@ def test_draft_loop_and_pair_step_parity(name):
     # ---- HIP path
     loop = DraftLoop(d["sess"], B, k)
     q = torch.zeros((B, k, V), dtype=torch.float32, device="cuda")
-    drafts = loop.run(seq_ids, torch.from_numpy(pending).cuda(), q, T, seed, step)
+    drafts = loop.run(seq_ids, torch.from_numpy(pending).cuda(), q, T, seed, step,
+                      pending_hidden=None if S["pend_hidden"] is None else torch.from_numpy(S["pend_hidden"]).cuda())
     tokens = torch.cat([torch.from_numpy(t0).cuda().view(B, 1), drafts], dim=1).contiguous()
     logits, n, out = t["sess"].step(seq_ids, tokens, q, drafts, T, seed, step)
     new_len = t["sess"].step_buffers(B, k)["new_ctx_len"]
@@ -207,7 +211,7 @@ def test_draft_loop_and_pair_step_parity(name):
     d["sess"].close()
 
 
-@pytest.mark.parametrize("name,n_steps", [("draft_pair_tiny_b4_k3", 4), ("draft_pair_small_b5_k4", 3)])
+@pytest.mark.parametrize("name,n_steps", [("draft_pair_tiny_b4_k3", 4), ("draft_pair_small_b5_k4", 3), ("draft_pair_fused_small_b5_k4", 3)])
 def test_rollout_of_several_steps_against_oracle(name, n_steps):
     """Consecutive steps with no host round trip: per step and sequence, accept length and emitted tokens equal the
     oracle's until the first decision the oracle marks as fragile (then that sequence is left out from there on);
@@ -219,9 +223,10 @@ def test_rollout_of_several_steps_against_oracle(name, n_steps):
     seed = 0x0123456789ABCDEF
     t0 = S["batch"]["tokens0"]
     hist, _, _, ctx_or = oracle_draft.rollout(t["cfg"], t["w_or"], d["cfg"], d["w_or"], t["kv_or"], d["kv_or"], S["prev"], t0, t["ctx"],
-                                              k, T, seed, n_steps)
+                                              k, T, seed, n_steps, pending_hidden=S["pend_hidden"])
     roll = RolloutLoop(t["sess"], d["sess"], B, k)
-    roll.start(torch.from_numpy(S["prev"]).cuda(), torch.from_numpy(t0).cuda())
+    roll.start(torch.from_numpy(S["prev"]).cuda(), torch.from_numpy(t0).cuda(),
+               None if S["pend_hidden"] is None else torch.from_numpy(S["pend_hidden"]).cuda())
     acc = torch.full((n_steps, B), -9, dtype=torch.int32, device="cuda")
     outs = torch.full((n_steps, B, k + 1), -9, dtype=torch.int32, device="cuda")
     seq_ids = torch.arange(B, dtype=torch.int32, device="cuda")
@@ -248,3 +253,53 @@ def test_rollout_of_several_steps_against_oracle(name, n_steps):
         assert sorted(held + list(st["free_stack"])) == list(range(sess.n_pages))
     t["sess"].close()
     d["sess"].close()
+
+
+def test_hidden_state_output_input_and_next_step_copy():
+    """spec_verify_forward_hidden on its own: the target's hidden states (residual stream after the last layer) and a
+    fused draft model's logits and hidden states against the oracle, and spec_next_step_hidden bit for bit."""
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    rng = np.random.default_rng(3)
+    for name, fused in (("small_bf16", False), ("draft_fused_small_bf16", True)):
+        cfg = dict(si.MODELS[name], vocab=1000)
+        B, k = 7, 3
+        ctx = rng.integers(0, 150, size=B).astype(np.int64)
+        weights = random_norm_gains(si.make_weights(cfg, seed=5), 5)
+        w_or = si.weights_for_oracle(cfg, weights)
+        kv = si.make_logical_kv(cfg, ctx, seed=5)
+        n_pages = sum(-(-(int(c) + k + 1) // si.PAGE_SIZE) for c in ctx) + 8
+        sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=B, max_ctx_len=int(ctx.max()) + 64, n_pages=n_pages)
+        at = 0
+        for b in range(B):
+            need = -(-int(ctx[b]) // si.PAGE_SIZE)
+            pages = list(range(at, at + need))
+            at += need
+            sess.assign(b, int(ctx[b]), pages)
+            for l in range(cfg["n_layers"]):
+                sess.write_logical_kv(l, pages, kv[l][b][0], kv[l][b][1])
+        tokens = rng.integers(0, cfg["vocab"], size=(B, k + 1)).astype(np.int32)
+        hid_in = (rng.standard_normal((B, k + 1, cfg["d_model"])) * 3.0).astype(np.float32) if fused else None
+        want, _, want_h = of.verify_forward(cfg, w_or, si.kv_for_oracle(kv), tokens, ctx, hidden_in=hid_in, return_hidden=True)
+        hid_out = torch.full((B, k + 1, cfg["d_model"]), float("nan"), dtype=torch.float32, device="cuda")
+        seq = torch.arange(B, dtype=torch.int32, device="cuda")
+        got = sess.forward(seq, torch.from_numpy(tokens).cuda(), hidden_in=None if hid_in is None else torch.from_numpy(hid_in).cuda(),
+                           hidden_out=hid_out)
+        torch.cuda.synchronize()
+        ok, max_err, worst = logits_close(got.cpu().numpy(), want, *TOL["bf16"])
+        assert ok, (name, max_err, worst)
+        okh, max_err_h, worst_h = logits_close(hid_out.cpu().numpy(), want_h, *TOL["bf16"])
+        assert okh, (name, max_err_h, worst_h)
+        print(name, "logits max abs err %.3e, hidden states max abs err %.3e (|h| up to %.2f)" % (max_err, max_err_h, np.abs(want_h).max()))
+        with pytest.raises(sv.SpecError):                  # a hidden-state input where none is taken, or none where one is needed
+            sess.forward(seq, torch.from_numpy(tokens).cuda(), hidden_in=None if fused else hid_out, hidden_out=hid_out if fused else None)
+        sess.close()
+    B, k, d = 6, 4, 256
+    H = rng.standard_normal((B, k + 1, d)).astype(np.float32)
+    old = rng.standard_normal((B, 2, d)).astype(np.float32)
+    n = np.array([0, 1, 4, 2, 0, 3], dtype=np.int32)
+    want = oracle_draft.next_pending_hidden(old, H, n).astype(np.float32)
+    pend = torch.from_numpy(old).cuda()
+    sv.spec_next_step_hidden(B, k, d, torch.from_numpy(H).cuda(), torch.from_numpy(n).cuda(), pend)
+    torch.cuda.synchronize()
+    assert np.array_equal(pend.cpu().numpy(), want)
