@@ -77,3 +77,34 @@ def test_argument_checks_of_the_draft_side_calls(sv):
     moe = dict(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=256, vocab=10, rope_theta=1e4, rms_eps=1e-5,
                dtype="bf16", tied_head=0, n_experts=4, top_k=2, expert_ffn_dim=256)
     assert sv.spec_model_weight_count(moe) == 1 + 2 * 10 + 2
+
+
+def test_argument_checks_of_the_rollout_side_calls(sv):
+    """n-gram drafter, slot bookkeeping and hidden-state calls reject bad sizes and null pointers before any HIP call."""
+    L = sv.lib()
+    # spec_ngram_draft(B, k, n_max, n_min, hist, stride, n_rows, hist_len, seq_ids, tokens, n_drafted, stream)
+    assert L.spec_ngram_draft(0, 3, 3, 1, 1, 8, 2, 1, None, 1, None, None) == sv.SPEC_EINVAL
+    assert L.spec_ngram_draft(2, 16, 3, 1, 1, 8, 2, 1, None, 1, None, None) == sv.SPEC_EINVAL
+    assert L.spec_ngram_draft(2, 3, 17, 1, 1, 8, 2, 1, None, 1, None, None) == sv.SPEC_EINVAL      # n_max > 16
+    assert L.spec_ngram_draft(2, 3, 2, 3, 1, 8, 2, 1, None, 1, None, None) == sv.SPEC_EINVAL       # n_min > n_max
+    assert L.spec_ngram_draft(2, 3, 3, 0, 1, 8, 2, 1, None, 1, None, None) == sv.SPEC_EINVAL
+    assert L.spec_ngram_draft(2, 3, 3, 1, None, 8, 2, 1, None, 1, None, None) == sv.SPEC_EINVAL
+    assert L.spec_ngram_draft(2, 3, 3, 1, 1, 0, 2, 1, None, 1, None, None) == sv.SPEC_EINVAL
+    assert "spec_ngram_draft" in sv.spec_last_error()
+    assert L.spec_ngram_append(2, 3, 1, 8, 2, 1, None, None, 1, None) == sv.SPEC_EINVAL
+    assert L.spec_ngram_append(2, 3, 1, 8, 0, 1, None, 1, 1, None) == sv.SPEC_EINVAL
+    # spec_rollout_retire(B, k, n_seqs, slot_seq, active, accept, gen, target, queue, queue_len, head, first, tokens, rel, keep, produced, stream)
+    good = [2, 3, 4, 1, 1, 1, 1, 1, 1, 2, 1, 1, 1, 1, 1, 1, None]
+    for pos, bad in ((0, 0), (1, 16), (2, 0), (9, -1), (3, None), (8, None), (15, None)):
+        a = list(good)
+        a[pos] = bad
+        assert L.spec_rollout_retire(*a) == sv.SPEC_EINVAL, (pos, bad)
+        assert "spec_rollout_retire" in sv.spec_last_error()
+    assert L.spec_next_step_hidden(0, 3, 8, 1, 1, 1, None) == sv.SPEC_EINVAL
+    assert L.spec_next_step_hidden(2, 3, 0, 1, 1, 1, None) == sv.SPEC_EINVAL
+    assert L.spec_next_step_hidden(2, 3, 8, None, 1, 1, None) == sv.SPEC_EINVAL
+    assert L.spec_verify_forward_hidden(None, None, 1, 1, None, None, None, None, None, None, 0, None) == sv.SPEC_EINVAL
+    # a model with hidden-state input: three more weights; bf16, dense and wide enough only
+    fused = dict(n_layers=1, d_model=256, n_q_heads=2, n_kv_heads=2, head_dim=128, ffn_dim=512, vocab=10, rope_theta=1e4, rms_eps=1e-5,
+                 dtype="bf16", tied_head=1, fuse_hidden=1)
+    assert sv.spec_model_weight_count(fused) == 1 + 9 + 1 + 3
