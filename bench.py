@@ -201,7 +201,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=2)
+    ap.add_argument("--cpu-seqs", type=int, default=6)
     ap.add_argument("--rollout-steps", type=int, default=8, help="draft+target pair: consecutive steps of the sustained run")
     ap.add_argument("--graph", action="store_true", help="record the K steps into a HIP graph and time its replay (default: one host launch per kernel)")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch parameter (repeatable)")
