@@ -57,3 +57,14 @@ def retire_and_backfill(slot_seq, active, accept_len, k, gen_len, target_len, qu
         else:
             keep_len[b] = KEEP_ALL
     return release_seq, keep_len, head, produced
+
+
+def compact_slots(slot_seq, active, tokens):
+    """Live slots move to the front, in their order; idle ones follow, in theirs (a stable partition), so that a
+    step over the first `n_live` slots covers every live sequence.  Returns (slot_seq, active, tokens, n_live) as
+    new arrays."""
+    slot_seq, active, tokens = np.asarray(slot_seq), np.asarray(active), np.asarray(tokens)
+    live = [b for b in range(len(active)) if active[b]]
+    idle = [b for b in range(len(active)) if not active[b]]
+    order = live + idle
+    return slot_seq[order].copy(), active[order].copy(), tokens[order].copy(), len(live)

@@ -74,3 +74,25 @@ def test_random_rollouts_invariants():
         assert np.array_equal(gen, target) and total == int(target.sum())
         assert len(book.free) + sum(len(p) for p in book.pages.values()) == n_free0       # no page lost or doubled
         assert all(book.pages[s] == [] for s in range(n_seqs))
+
+
+def test_compact_slots():
+    slot_seq = np.array([7, 3, 9, 1, 4], dtype=np.int32)
+    active = np.array([0, 1, 0, 1, 1], dtype=np.int32)
+    tokens = np.arange(10, dtype=np.int32).reshape(5, 2)
+    s2, a2, t2, n = oro.compact_slots(slot_seq, active, tokens)
+    assert n == 3 and list(s2) == [3, 1, 4, 7, 9] and list(a2) == [1, 1, 1, 0, 0]
+    assert t2.tolist() == [[2, 3], [6, 7], [8, 9], [0, 1], [4, 5]]
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        B = int(rng.integers(1, 40))
+        seq = rng.permutation(100)[:B].astype(np.int32)
+        act = (rng.random(B) < 0.5).astype(np.int32)
+        tok = rng.integers(0, 1000, size=(B, 4)).astype(np.int32)
+        s2, a2, t2, n = oro.compact_slots(seq, act, tok)
+        assert n == act.sum() and np.all(a2[:n] == 1) and np.all(a2[n:] == 0)
+        assert sorted(s2.tolist()) == sorted(seq.tolist())                    # a permutation ...
+        assert list(s2[:n]) == [int(s) for s, a in zip(seq, act) if a]        # ... that keeps the live ones in order
+        for b in range(B):                                                    # rows travel with their slot
+            src = int(np.where(seq == s2[b])[0][0])
+            assert np.array_equal(t2[b], tok[src])
