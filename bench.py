@@ -142,34 +142,38 @@ def run_continuous(args, wl, sv, torch):
     hist_len0 = torch.from_numpy((wl.ctx_len + 1).astype("int32")).cuda()
     first = hist0[torch.arange(n_seqs, device="cuda"), (hist_len0 - 1).long()].contiguous()
     chunk = 16
-    result = None
-    for rep in range(2):                                        # first repetition warms up
+    results = {}
+    # three passes over the same rollout: a warm-up, a timed one with all slots riding along to the end, and a timed one
+    # that moves the live slots to the front and shrinks the batch (in steps of 8 slots) whenever the host looks
+    for rep, mode in enumerate(("warm-up", "compacted", "fixed batch")):
         wl.restore()
         hist, hist_len = hist0.clone(), hist_len0.clone()
         roll = ContinuousRollout(wl.sess, slots, k, torch.arange(slots, dtype=torch.int32), torch.from_numpy(target),
                                  torch.arange(slots, n_seqs, dtype=torch.int32), first)
         roll.tokens[:, 0] = first[:slots]
         live = torch.zeros(max_steps + chunk, dtype=torch.int32, device="cuda")
-        if rep == 1:
+        if mode == "fixed batch":                               # the instrumented pass (events around every kernel class)
             sv.spec_profile_begin((max_steps + chunk) * 420 + 64)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        steps = 0
+        steps, sizes = 0, []
         while steps < max_steps:                                # the host looks at the live count every `chunk` steps
+            sizes.append(roll.B_cur)
             roll.run(hist, hist_len, chunk, wl.wl["temperature"], wl.seed, 9000 + steps, live[steps:steps + chunk])
             steps += chunk
-            if int(live[steps - 1].item()) == 0:
+            n_live = roll.compact(granule=8) if mode == "compacted" else int(live[steps - 1].item())
+            if n_live == 0:
                 break
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         live_h = live[:steps].cpu().numpy()
         used = int(np.argmax(live_h == 0)) + 1 if (live_h == 0).any() else steps
-        result = dict(dt=dt, steps=steps, used=used, live=live_h, produced=int(roll.produced.item()))
+        results[mode] = dict(dt=dt, steps=steps, used=used, live=live_h, produced=int(roll.produced.item()), sizes=sizes)
     prof = sv.spec_profile_end()
-    r = result
+    r, fixed = results["compacted"], results["fixed batch"]
     ms_per_step = 1e3 * r["dt"] / r["steps"]
-    gemm_ms = sum(prof[n][0] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head")) / r["steps"]
-    gemm_launches = sum(prof[n][1] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head")) / r["steps"]
+    gemm_ms = sum(prof[n][0] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head")) / fixed["steps"]
+    gemm_launches = sum(prof[n][1] for n in ("gemm_qkv", "gemm_o", "gemm_gu", "gemm_down", "gemm_head")) / fixed["steps"]
     alg = algorithmic_bytes(wl.cfg, wl.ctx_len[:slots], slots, k)
     gbs = alg["gemm"] / (gemm_ms / 1e3) / 1e9
     occupancy = float(r["live"][:r["used"]].mean()) / slots
@@ -184,12 +188,15 @@ def run_continuous(args, wl, sv, torch):
             "response_tokens": r["produced"], "response_len_min_median_max": [int(target.min()), int(np.median(target)), int(target.max())],
             "steps_until_drained": r["used"], "mean_live_slot_fraction": round(occupancy, 3),
             "steps_with_at_most_a_quarter_live": int((r["live"][:r["used"]] <= slots // 4).sum()),
-            "tokens_per_s_if_all_slots_stayed_live": round(slots * 1e3 / ms_per_step, 1),
-            "host_syncs": "one every %d steps (live-slot count)" % chunk},
+            "batch_sizes_per_%d_steps" % chunk: r["sizes"],
+            "fixed_batch_under_event_profiling": {"tokens_per_s": round(fixed["produced"] / fixed["dt"], 1),
+                                                  "ms_per_step": round(1e3 * fixed["dt"] / fixed["steps"], 4)},
+            "tokens_per_s_if_all_slots_stayed_live": round(slots * 1e3 / (1e3 * fixed["dt"] / fixed["steps"]), 1),
+            "host_syncs": "one every %d steps (live-slot count, batch resize)" % chunk},
         "roofline": dict(kernel="gemm_bf16_kernel", bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                          frac=round(gbs / HBM_PEAK_GBS, 4), avg_launch_us=round(1e3 * gemm_ms / max(gemm_launches, 1), 2),
                          bytes_per_launch=int(alg["gemm"] / max(gemm_launches, 1)), traffic=None),
-        "ms_per_step_by_class": {n: round(ms / r["steps"], 4) for n, (ms, cnt) in prof.items() if ms > 0},
+        "ms_per_step_by_class": {n: round(ms / fixed["steps"], 4) for n, (ms, cnt) in prof.items() if ms > 0},
     }
     print(json.dumps(out))
 

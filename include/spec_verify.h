@@ -355,6 +355,18 @@ spec_status spec_rollout_retire(int32_t B, int32_t k, int32_t n_seqs, int32_t* d
                                 int32_t* dev_keep_len, int64_t* dev_produced, void* stream);
 
 /*
+ * Compaction of the batch slots of a continuous rollout: the live slots (dev_active[b] != 0) move to the front in
+ * their order, the idle ones follow in theirs; dev_slot_seq [B], dev_active [B] and the rows of dev_tokens
+ * [B, k+1] travel together.  *dev_n_live (device) receives the number of live slots: a step over the first
+ * n_live slots then covers every live sequence, and costs what a batch of that size costs - the answer to the
+ * under-used tail of a long-tailed rollout (Section 4 of the paper discusses it; the mechanism is this library's).
+ * The caller reads n_live back when it chooses to resize the batch.  dev_scratch: B * (k + 3) int32 of device
+ * memory, contents irrelevant.  Asynchronous on `stream`.
+ */
+spec_status spec_rollout_compact(int32_t B, int32_t k, int32_t* dev_slot_seq, int32_t* dev_active, int32_t* dev_tokens,
+                                 int32_t* dev_n_live, int32_t* dev_scratch, void* stream);
+
+/*
  * Replay of a recorded sequence of step calls (for callers whose steps are short enough that launching ~350 small
  * kernels per step costs more than running them).  Between spec_graph_capture_begin and spec_graph_capture_end every
  * call of this library on `stream` (which must not be the default stream) is recorded instead of executed; the

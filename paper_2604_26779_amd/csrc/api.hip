@@ -537,6 +537,17 @@ extern "C" spec_status spec_rollout_retire(int32_t B, int32_t k, int32_t n_seqs,
     return SPEC_OK;
 }
 
+extern "C" spec_status spec_rollout_compact(int32_t B, int32_t k, int32_t* dev_slot_seq, int32_t* dev_active, int32_t* dev_tokens,
+                                            int32_t* dev_n_live, int32_t* dev_scratch, void* stream)
+{
+    if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT) { set_error("spec_rollout_compact: B or k out of range"); return SPEC_EINVAL; }
+    if (!dev_slot_seq || !dev_active || !dev_tokens || !dev_n_live || !dev_scratch) { set_error("spec_rollout_compact: null pointer"); return SPEC_EINVAL; }
+    spec_status st = launch_rollout_compact(B, k, dev_slot_seq, dev_active, dev_tokens, dev_n_live, dev_scratch, (hipStream_t)stream);
+    if (st != SPEC_OK) return st;
+    prof_mark(PC_OTHER, (hipStream_t)stream);
+    return SPEC_OK;
+}
+
 extern "C" size_t spec_kv_state_bytes(const spec_kv* kv) { return kv ? kv->state_ints * sizeof(int32_t) : 0; }
 
 extern "C" spec_status spec_kv_snapshot(spec_kv* kv, void* dev_buf, void* stream)

@@ -243,6 +243,60 @@ spec_status launch_rollout_retire(int B, int k, int n_seqs, int32_t* slot_seq, i
     return SPEC_OK;
 }
 
+// Stable partition of the slots by liveness.  One workgroup; pass 1 copies everything to scratch and scans the
+// flags, pass 2 writes the rows back at their new places.
+__global__ __launch_bounds__(KVB_THREADS) void rollout_compact_kernel(int B, int k, int32_t* __restrict__ slot_seq,
+                                                                      int32_t* __restrict__ active, int32_t* __restrict__ tokens,
+                                                                      int32_t* __restrict__ n_live, int32_t* __restrict__ scratch)
+{
+    __shared__ int lds[KVB_THREADS];
+    __shared__ int s_live_total;
+    const int T = k + 1;
+    int32_t* sc_seq = scratch;                 // [B]
+    int32_t* sc_dst = scratch + B;             // [B] new index of old slot b
+    int32_t* sc_tok = scratch + 2 * B;         // [B, T]
+    // number of live slots first (the idle ones start behind them)
+    int count = 0;
+    for (int b = threadIdx.x; b < B; b += KVB_THREADS) count += active[b] != 0;
+    int total;
+    block_exclusive_scan(count, lds, &total);
+    if (threadIdx.x == 0) s_live_total = total;
+    __syncthreads();
+    const int live_total = s_live_total;
+    int live_before = 0;                       // live slots in the groups already handled
+    for (int base = 0; base < B; base += KVB_THREADS) {
+        const int b = base + threadIdx.x;
+        const int is_live = b < B && active[b] != 0;
+        int group_live;
+        const int rank = block_exclusive_scan(is_live, lds, &group_live);
+        if (b < B) {
+            // live slot: its rank among the live ones; idle slot: behind all live ones, in order
+            const int dst = is_live ? live_before + rank : live_total + (b - (live_before + rank));
+            sc_dst[b] = dst;
+            sc_seq[b] = slot_seq[b];
+            for (int i = 0; i < T; ++i) sc_tok[(int64_t)b * T + i] = tokens[(int64_t)b * T + i];
+        }
+        live_before += group_live;
+        __syncthreads();
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += KVB_THREADS) {
+        const int dst = sc_dst[b];
+        slot_seq[dst] = sc_seq[b];
+        active[dst] = dst < live_total ? 1 : 0;
+        for (int i = 0; i < T; ++i) tokens[(int64_t)dst * T + i] = sc_tok[(int64_t)b * T + i];
+    }
+    if (threadIdx.x == 0) *n_live = live_total;
+}
+
+spec_status launch_rollout_compact(int B, int k, int32_t* slot_seq, int32_t* active, int32_t* tokens, int32_t* n_live,
+                                   int32_t* scratch, hipStream_t s)
+{
+    rollout_compact_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, slot_seq, active, tokens, n_live, scratch);
+    SPEC_LAUNCH_CHECK("rollout_compact_kernel");
+    return SPEC_OK;
+}
+
 spec_status launch_kv_truncate(spec_kv* kv, int B, const int32_t* dev_seq_ids, const int32_t* dev_len, int delta,
                                int32_t* dev_new_len, hipStream_t s)
 {

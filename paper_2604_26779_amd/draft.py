@@ -185,21 +185,33 @@ class ContinuousRollout:
         self.drafts = torch.zeros((B, k), dtype=torch.int32, device=dev)
         self.release_seq = torch.zeros(B, dtype=torch.int32, device=dev)
         self.keep_len = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.n_live = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.scratch = torch.zeros(B * (k + 3), dtype=torch.int32, device=dev)
+        self.B_cur = int(B)                    # slots a step covers: all of them until compact() shrinks the batch
+
+    def compact(self, granule=8, stream=None):
+        """Move the live slots to the front and shrink the batch to them (rounded up to `granule` slots; the idle
+        slots behind keep riding along).  Reads the live count back: a host synchronisation.  Returns the count."""
+        sv.spec_rollout_compact(self.B_cur, self.k, self.slot_seq, self.active, self.tokens, self.n_live, self.scratch, stream)
+        n = int(self.n_live.item())
+        self.B_cur = max(granule, min(self.B_cur, -(-n // granule) * granule)) if n > 0 else min(self.B_cur, granule)
+        return n
 
     def run(self, hist, hist_len, n_steps, temperature, seed, step0=0, live_out=None, stream=None):
         """live_out [n_steps] int32 (device, optional) receives the number of live slots after every step."""
-        t, B, k = self.t, self.B, self.k
+        t, B, k = self.t, self.B_cur, self.k
         V = t.cfg["vocab"]
         buf = t.step_buffers(B, k)
         ws = buf["workspace"]
         off = (-ws.data_ptr()) % 256
         ws = ws[off:off + ws.numel() - 256]
         acc, out = buf["accept_len"], buf["out_tokens"]
+        drafts = self.drafts[:B]               # the first B rows of contiguous [slots, ...] arrays are contiguous
         for s in range(n_steps):
             sv.spec_ngram_draft(B, k, self.n_max, self.n_min, hist, hist_len, self.slot_seq, self.tokens, None, stream)
-            self.drafts.copy_(self.tokens[:, 1:])
+            drafts.copy_(self.tokens[:B, 1:])
             sv.spec_verify_forward(t.model, t.kv, B, k, self.slot_seq, self.tokens, buf["logits"], ws, stream)
-            sv.spec_reject_sample(B, k, V, buf["logits"], None, self.drafts, temperature, seed, step0 + s, acc, out, None,
+            sv.spec_reject_sample(B, k, V, buf["logits"], None, drafts, temperature, seed, step0 + s, acc, out, None,
                                   buf["sample_ws"], stream)
             sv.spec_commit_kv(t.kv, B, k, self.slot_seq, acc, buf["new_ctx_len"], None, stream)
             sv.spec_ngram_append(B, k, hist, hist_len, self.slot_seq, out, acc, stream)
@@ -208,4 +220,4 @@ class ContinuousRollout:
                                    self.produced, stream)
             sv.spec_kv_truncate(t.kv, B, self.release_seq, self.keep_len, 0, None, stream)
             if live_out is not None:
-                live_out[s] = self.active.sum()
+                live_out[s] = self.active[:B].sum()

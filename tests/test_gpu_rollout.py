@@ -108,3 +108,60 @@ def test_retire_backfill_chain(seed, B, n_seqs, k):
     assert not active.any() and head == len(queue) and np.array_equal(gen, target) and produced == int(target.sum())
     print("B=%d, %d sequences, k=%d: drained in %d steps, %d tokens" % (B, n_seqs, k, steps, produced))
     sess.close()
+
+
+def test_compaction_and_shrinking_batch():
+    """spec_rollout_compact bit for bit against the oracle (more slots than one pass of the workgroup, none / all
+    live), and a whole rollout with the n-gram drafter that compacts and shrinks its batch as slots go idle: every
+    sequence still produces exactly its response length and ends with an empty cache."""
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.draft import ContinuousRollout
+    from paper_2604_26779_amd.session import VerifySession
+    rng = np.random.default_rng(11)
+    for B, k, p_live in ((1, 0, 1.0), (5, 3, 0.5), (300, 2, 0.3), (64, 15, 0.0), (257, 1, 1.0), (600, 4, 0.7)):
+        seq = rng.permutation(5000)[:B].astype(np.int32)
+        act = (rng.random(B) < p_live).astype(np.int32)
+        tok = rng.integers(0, 1 << 20, size=(B, k + 1)).astype(np.int32)
+        s2, a2, t2, n = oro.compact_slots(seq, act, tok)
+        d_seq, d_act, d_tok = (torch.from_numpy(x).cuda() for x in (seq, act, tok))
+        d_n = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        sv.spec_rollout_compact(B, k, d_seq, d_act, d_tok, d_n, torch.empty(B * (k + 3), dtype=torch.int32, device="cuda"))
+        torch.cuda.synchronize()
+        assert int(d_n.item()) == n and np.array_equal(d_seq.cpu().numpy(), s2) and np.array_equal(d_act.cpu().numpy(), a2)
+        assert np.array_equal(d_tok.cpu().numpy(), t2)
+    # a rollout that shrinks: 12 slots, 20 sequences, tiny model
+    cfg = si.MODELS["tiny_fp32"]
+    slots, n_seqs, k = 12, 20, 2
+    weights = si.make_weights(cfg, seed=4)
+    ctx0 = rng.integers(1, 30, size=n_seqs).astype(np.int64)
+    n_pages = 160
+    sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=n_seqs, max_ctx_len=256, n_pages=n_pages)
+    sess.pool.normal_()
+    at = 0
+    for s in range(n_seqs):
+        need = -(-int(ctx0[s]) // si.PAGE_SIZE)
+        sess.assign(s, int(ctx0[s]), list(range(at, at + need)))
+        at += need
+    target = rng.integers(1, 25, size=n_seqs).astype(np.int32)
+    cap = 128
+    hist = torch.from_numpy(rng.integers(0, 5, size=(n_seqs, cap)).astype(np.int32)).cuda()
+    hist_len = torch.from_numpy((ctx0 + 1).astype(np.int32)).cuda()
+    first = hist[torch.arange(n_seqs, device="cuda"), (hist_len - 1).long()].contiguous()
+    roll = ContinuousRollout(sess, slots, k, torch.arange(slots, dtype=torch.int32), torch.from_numpy(target),
+                             torch.arange(slots, n_seqs, dtype=torch.int32), first)
+    roll.tokens[:, 0] = first[:slots]
+    sizes = []
+    for chunk in range(40):
+        roll.run(hist, hist_len, 4, 1.0, 99, chunk * 4)
+        n_live = roll.compact(granule=4)
+        sizes.append(roll.B_cur)
+        if n_live == 0:
+            break
+    torch.cuda.synchronize()
+    assert n_live == 0 and int(roll.produced.item()) == int(target.sum())
+    assert np.array_equal(roll.gen_len.cpu().numpy(), target) and int(roll.queue_head.item()) == n_seqs - slots
+    assert sizes[0] == slots and sizes[-1] == 4 and sorted(sizes, reverse=True) == sizes and len(set(sizes)) >= 3
+    st = sess.state()
+    assert np.all(st["ctx_len"][:n_seqs] == 0) and np.all(st["n_pages"][:n_seqs] == 0) and len(st["free_stack"]) == n_pages
+    print("shrinking rollout: batch sizes", sizes, "tokens", int(roll.produced.item()))
+    sess.close()

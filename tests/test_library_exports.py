@@ -100,6 +100,9 @@ def test_argument_checks_of_the_rollout_side_calls(sv):
         a[pos] = bad
         assert L.spec_rollout_retire(*a) == sv.SPEC_EINVAL, (pos, bad)
         assert "spec_rollout_retire" in sv.spec_last_error()
+    assert L.spec_rollout_compact(0, 3, 1, 1, 1, 1, 1, None) == sv.SPEC_EINVAL
+    assert L.spec_rollout_compact(2, 3, 1, 1, 1, None, 1, None) == sv.SPEC_EINVAL
+    assert "spec_rollout_compact" in sv.spec_last_error()
     assert L.spec_next_step_hidden(0, 3, 8, 1, 1, 1, None) == sv.SPEC_EINVAL
     assert L.spec_next_step_hidden(2, 3, 0, 1, 1, 1, None) == sv.SPEC_EINVAL
     assert L.spec_next_step_hidden(2, 3, 8, None, 1, 1, None) == sv.SPEC_EINVAL
