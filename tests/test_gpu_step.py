@@ -400,3 +400,19 @@ def test_bf16_large_row_tiles(B, k, big_from):
         sv.spec_tune_set("gemm_big_min_blocks", 0)
     print("B=%d k=%d (M=%d), big tiles from %d row blocks: logits max abs err %.3e" % (B, k, B * (k + 1), big_from, max_err))
     assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("chunk_pages", [64, 128])
+def test_bf16_attention_long_chunks_at_their_boundaries(chunk_pages):
+    """The chunk lengths the launch policy picks for large batches (64 and 128 pages = 1024 and 2048 tokens): contexts
+    one token short of, at and one past a chunk boundary, and new positions that straddle it (k = 3)."""
+    from paper_2604_26779_amd import binding as sv
+    sv.spec_tune_set("attn_chunk_pages", chunk_pages)
+    try:
+        edge = chunk_pages * 16
+        ctx = [edge - 4, edge - 3, edge - 1, edge, edge + 1, 2 * edge - 2, 2 * edge + 5, 17]
+        ok, max_err, worst = _run_custom_bf16(ctx, k=3, seed=50 + chunk_pages, vocab=1000)
+    finally:
+        sv.spec_tune_set("attn_chunk_pages", 0)
+    print("chunk %d pages: logits max abs err %.3e" % (chunk_pages, max_err))
+    assert ok, (max_err, worst)
