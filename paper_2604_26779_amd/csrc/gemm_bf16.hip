@@ -100,6 +100,9 @@ spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_row
 }
 
 // ------------------------------------------------------------------ the GEMM
+// s_waitcnt operand: at most n vector-memory operations outstanding, the other counters not waited for
+constexpr int vmcnt_imm(int n) { return (n & 15) | 0x70 | 0xF00 | ((n >> 4) << 14); }
+
 // Wp : [k_steps / KS][n_blocks][KS][64] u32x4_t   Xp : [k_steps][mb_pad][hi|lo][64] u32x4_t
 // out: [splits][M][ldo] fp32 (slice stride = split_stride floats)
 // MB row blocks (of 32) per workgroup tile; the 4 wavefronts are arranged WM along the rows x 4/WM
@@ -177,6 +180,21 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 #pragma unroll
         for (int j = 0; j < XPT; ++j) lds[buf * SLAB + threadIdx.x + GEMM_THREADS * j] = xr[j];
     };
+    // The 128-column tiles skip the registers: their activation slabs go from global memory straight into LDS
+    // (global_load ... lds: no staging registers, no LDS store instructions).  Each instruction moves 64 x 16 bytes:
+    // per-lane global addresses, LDS address = the wavefront-uniform base given here + 16 * lane.  (The 256-column
+    // tile measured slightly faster with its stores spread under the MFMAs, and keeps them.)
+    auto stage_x = [&](int slab, int tobuf) {
+#pragma unroll
+        for (int j = 0; j < XPT; ++j) {
+            int idx = threadIdx.x + GEMM_THREADS * j;
+            int kl = idx / (MB * 128), rem = idx % (MB * 128);
+            const u32x4_t* src = xbase + ((int64_t)(slab * KS + kl) * mb_pad) * 128 + rem;
+            u32x4_t* dst = lds + tobuf * SLAB + (idx - lane);
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+        }
+    };
     int buf = 0;
     // No branch may sit between the loads and their use: the compiler can only count outstanding
     // loads (s_waitcnt vmcnt(n)) along straight-line code, and falls back to draining the whole
@@ -186,7 +204,8 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
         constexpr int SLOT = decltype(slot_c)::value;
         const int s_w = s + WD < n_slabs ? s + WD : n_slabs - 1;
         const int s_x = s + 1 < n_slabs ? s + 1 : n_slabs - 1;
-        load_x(s_x);
+        // the next slab's activations are the oldest loads of this slab: what is waited for at its end
+        if constexpr (BIG) load_x(s_x); else stage_x(s_x, buf ^ 1);
         // keep these loads HERE: left alone, the scheduler sinks them to the end of the slab, next to the LDS
         // stores that consume them, and the whole round trip to L2 is then paid once per slab
         __builtin_amdgcn_sched_barrier(0);
@@ -230,8 +249,15 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
         // ... and the weight loads of this slab stay above the LDS stores, so that waiting for the (older)
         // activation loads does not drain the weight stream
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (!BIG) store_x(buf ^ 1);
-        __syncthreads();
+        if constexpr (BIG) {
+            __syncthreads();
+        } else {
+            // Wait for the transfers into LDS only: the slab's own weight reloads (KS * NBW of them) were issued later
+            // and stay in flight (__syncthreads would drain the whole queue).  No wavefront reads the other buffer
+            // before this barrier, and all have finished reading this one when they pass the next.
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(KS * NBW));
+            __builtin_amdgcn_s_barrier();
+        }
         buf ^= 1;
     };
 
@@ -245,9 +271,15 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 #pragma unroll
                 for (int j = 0; j < NBW; ++j) w[d][i][j] = __builtin_nontemporal_load(wptr[j] + (int64_t)sd * wslab + i * 64);
         }
-        load_x(0);
-        store_x(0);
-        __syncthreads();
+        if constexpr (BIG) {
+            load_x(0);
+            store_x(0);
+            __syncthreads();
+        } else {
+            stage_x(0, 0);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_s_barrier();
+        }
         for (int s = 0; s < n_slabs; s += WD) {
             slab_body(std::integral_constant<int, 0>{}, s);
             if constexpr (WD > 1) slab_body(std::integral_constant<int, 1>{}, s + 1);
