@@ -33,7 +33,8 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int GEMM_KS = 4;          // k-steps (of 16) per LDS slab
 constexpr int GEMM_WD = 4;          // slabs of weight fragments each wavefront keeps in flight
-constexpr int GEMM_KUNIT = GEMM_KS * GEMM_WD;   // k-steps per split are a multiple of this
+constexpr int GEMM_KUNIT = GEMM_KS * GEMM_WD;
+constexpr int GEMM_XCDS = 8;        // accelerator dies, each with its own L2; workgroup i of a launch runs on die i % 8   // k-steps per split are a multiple of this
 constexpr int GEMM_THREADS = 256;
 constexpr int GEMM_EPI_PLAIN = 0, GEMM_EPI_SWIGLU = 1;
 
@@ -136,16 +137,32 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int mh = wave % WM, np = wave / WM;
-    const int nb0 = blockIdx.x * TILE_NB + np * NBW;
-    const int ks0 = blockIdx.y * ksteps_per_split;
+    // Which tile this workgroup computes.  Workgroups go to the 8 XCDs (each with an L2 of its own) round robin in
+    // launch order, so the launch index is re-mapped: XCD j takes a contiguous stretch of the tiles in the order
+    // (row tile fastest, then column tile, then k-split).  The workgroups that share a weight tile then share an L2,
+    // and an XCD reads the activations of one or two k-splits instead of all of them.
+    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+#ifndef SPEC_GEMM_NO_XCD_MAP
+    if constexpr (!GROUPED) {
+        const int nx = gridDim.x, ny = gridDim.y, nz = gridDim.z;
+        const int total = nx * ny * nz, lin = bx + nx * (by + ny * bz);
+        const int xcd = lin % GEMM_XCDS, slot = lin / GEMM_XCDS;
+        const int v = xcd * (total / GEMM_XCDS) + (xcd < total % GEMM_XCDS ? xcd : total % GEMM_XCDS) + slot;
+        bz = v % nz;
+        bx = (v / nz) % nx;
+        by = v / (nz * nx);
+    }
+#endif
+    const int nb0 = bx * TILE_NB + np * NBW;
+    const int ks0 = by * ksteps_per_split;
     int ks1 = ks0 + ksteps_per_split;
     if (ks1 > k_steps) ks1 = k_steps;
     const int n_slabs = (ks1 - ks0) / KS;
-    int mblk0 = blockIdx.z * MB;                        // first 32-row block of this tile
+    int mblk0 = bz * MB;                        // first 32-row block of this tile
     if constexpr (GROUPED) {
-        if ((int)blockIdx.z >= tiles[0]) return;
-        Wp += (int64_t)tiles[1 + 2 * blockIdx.z] * w_group_stride;
-        mblk0 = tiles[2 + 2 * blockIdx.z];
+        if (bz >= tiles[0]) return;
+        Wp += (int64_t)tiles[1 + 2 * bz] * w_group_stride;
+        mblk0 = tiles[2 + 2 * bz];
     }
 
     // slab s of column block j of this wavefront: wptr[j] + s * wslab
@@ -312,7 +329,7 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
             __syncthreads();
             for (int e = threadIdx.x; e < MBW * 32 * 16; e += GEMM_THREADS) {
                 int row = e >> 4, g8 = e & 15;
-                int m = (mblk0 + half * MBW) * 32 + row, f = blockIdx.x * 128 + g8 * 8;
+                int m = (mblk0 + half * MBW) * 32 + row, f = bx * 128 + g8 * 8;
                 if (m >= M || f >= N / 2) continue;
                 float v[8];
 #pragma unroll
@@ -341,7 +358,7 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
         uint4* xo = (uint4*)out;
         for (int e = threadIdx.x; e < MB * 32 * 8; e += GEMM_THREADS) {
             int row = e >> 3, g8 = e & 7;
-            int m = mblk0 * 32 + row, f = blockIdx.x * 64 + g8 * 8;
+            int m = mblk0 * 32 + row, f = bx * 64 + g8 * 8;
             if (m >= M || f >= N / 2) continue;
             float v[8];
 #pragma unroll
@@ -350,7 +367,7 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
         }
         return;
     }
-    float* o = out + (int64_t)blockIdx.y * split_stride;
+    float* o = out + (int64_t)by * split_stride;
 #pragma unroll
     for (int j = 0; j < NBW; ++j) {
         const int n = (nb0 + j) * 32 + (lane & 31);
