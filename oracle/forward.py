@@ -26,9 +26,13 @@ Conventions of this build (the paper does not state them):
     "f64" for none) and attention reads what the cache stores: the keys and values of the k+1 input
     positions are rounded to that type (round to nearest even) before any row attends to them, so
     that a position's key and value are the same numbers in the step that writes them and in every
-    later step - which is what makes the verified distribution the one plain decoding would use.
+    later step - which is what makes the verified distribution the one plain decoding would use;
+  * an 8-bit cache (cfg["kv_dtype"] == "fp8_e4m3", see ``oracle/fp8.py``) stores encode(x / scale) with one scale
+    per (layer, kv head) for keys and one for values, and attention reads decode(code) * scale.
 """
 import numpy as np
+
+from . import fp8
 
 
 def rmsnorm(x, gain, eps):
@@ -110,7 +114,8 @@ def moe_ffn(h, w, top_k, route_log=None):
     return out
 
 
-def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden_in=None, return_hidden=False):
+def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden_in=None, return_hidden=False,
+                   kv_scales=None):
     """One verify forward.
 
     cfg      dict: n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab,
@@ -128,6 +133,9 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden
     dict(w_fuse [d, 2d], norm_e [d], norm_h [d]) and hidden_in [B, k+1, d]; the input of the first layer is
     w_fuse . [RMSNorm(embedding) * norm_e ; RMSNorm(hidden_in) * norm_h], hidden_in[b][i] being the hidden state
     of the position before input i.
+
+    8-bit cache (cfg kv_dtype "fp8_e4m3"): kv_scales = (k_scale [L, Hkv], v_scale [L, Hkv]); kv_ctx then holds the
+    values the cache returns (decode(code) * scale), and so does new_kv.
 
     Returns (logits [B,k+1,V] fp64, new_kv) with new_kv[layer] = (K [B,k+1,Hkv,dh], V [...]),
     the keys (after rotation) and values of the k+1 input positions as the cache stores them; with return_hidden
@@ -157,8 +165,12 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden
         kx = (h @ np.asarray(w["wk"], dtype=np.float64).T).reshape(B * T, Hkv, dh)
         vx = (h @ np.asarray(w["wv"], dtype=np.float64).T).reshape(B * T, Hkv, dh)
         q = rope(q, pos, theta)
-        kx = round_to_storage(rope(kx, pos, theta), cfg["dtype"])
-        vx = round_to_storage(vx, cfg["dtype"])
+        if cfg.get("kv_dtype") == "fp8_e4m3":
+            kx = fp8.store(rope(kx, pos, theta), np.asarray(kv_scales[0], dtype=np.float64)[layer][None, :, None])
+            vx = fp8.store(vx, np.asarray(kv_scales[1], dtype=np.float64)[layer][None, :, None])
+        else:
+            kx = round_to_storage(rope(kx, pos, theta), cfg["dtype"])
+            vx = round_to_storage(vx, cfg["dtype"])
         new_kv.append((kx.reshape(B, T, Hkv, dh).copy(), vx.reshape(B, T, Hkv, dh).copy()))
 
         attn = np.zeros((B * T, Hq, dh), dtype=np.float64)
@@ -190,7 +202,7 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden
     return logits.reshape(B, T, -1), new_kv
 
 
-def prefill(cfg, weights, tokens):
+def prefill(cfg, weights, tokens, kv_scales=None):
     """Cache contents for context tokens [B, C]: a verify forward from an empty cache.
 
     Returns kv_ctx in the form ``verify_forward`` takes.
@@ -200,5 +212,5 @@ def prefill(cfg, weights, tokens):
     Hkv, dh = cfg["n_kv_heads"], cfg["head_dim"]
     empty = [[(np.zeros((0, Hkv, dh)), np.zeros((0, Hkv, dh))) for _ in range(B)]
              for _ in range(cfg["n_layers"])]
-    _, new_kv = verify_forward(cfg, weights, empty, tokens, np.zeros(B, dtype=np.int64))
+    _, new_kv = verify_forward(cfg, weights, empty, tokens, np.zeros(B, dtype=np.int64), kv_scales=kv_scales)
     return [[(new_kv[layer][0][b], new_kv[layer][1][b]) for b in range(B)] for layer in range(cfg["n_layers"])]
