@@ -39,7 +39,7 @@ typedef enum {
     SPEC_EUNSUPPORTED = -5   /* shape or type outside what the kernels cover */
 } spec_status;
 
-enum { SPEC_F32 = 0, SPEC_BF16 = 1 };
+enum { SPEC_F32 = 0, SPEC_BF16 = 1, SPEC_FP8_E4M3 = 2 /* KV cache only */ };
 enum { SPEC_MAX_DRAFT = 15 };          /* largest k */
 enum { SPEC_PAGE_SIZE = 16 };          /* tokens per KV page */
 
@@ -57,7 +57,13 @@ const char* spec_last_error(void);
  * drafting paths, Section 2.3: EAGLE-3 and native multi-token-prediction heads both consume target hidden states;
  * the combination is the multi-token-prediction one): the first layer's input is
  *     w_fuse . [ RMSNorm(embedding of the token) * fuse_e_norm ; RMSNorm(hidden state) * fuse_h_norm ],
- * the hidden state being that of the position before the token (spec_verify_forward_hidden). */
+ * the hidden state being that of the position before the token (spec_verify_forward_hidden).
+ * kv_dtype = SPEC_FP8_E4M3 (bf16 models only; 0 = the cache stores `dtype`): an 8-bit cache, the FP8 serving the
+ * paper's projections assume (Section 4, simulator set-up).  Keys (after rotation) and values are stored as OCP
+ * E4M3 codes (1-4-3 bits, bias 7, no infinities, largest magnitude 448) of x / scale, rounded to nearest even and
+ * saturated, with one fp32 scale per (layer, kv head) for keys and one for values (spec_kv_set_scales); attention
+ * reads code * scale.  As with the other storage types the k+1 new positions are encoded before any row attends
+ * to them. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
     float rope_theta, rms_eps;
@@ -65,6 +71,7 @@ typedef struct {
     int32_t tied_head;         /* 1: output head = embedding matrix */
     int32_t n_experts, top_k, expert_ffn_dim;   /* 0, 0, 0: dense feed-forward of width ffn_dim */
     int32_t fuse_hidden;       /* 1: a draft model whose input also takes hidden states (bf16, dense, ffn_dim >= 2 d_model) */
+    int32_t kv_dtype;          /* 0: the cache stores `dtype`; SPEC_FP8_E4M3: 8-bit cache with scales (bf16 models) */
 } spec_model_desc;
 
 typedef struct spec_model spec_model;
@@ -102,7 +109,8 @@ spec_status spec_model_destroy(spec_model* model);
 /*
  * Paged KV cache (the cache the decode-phase verification of Section 2.2 runs against; paging and
  * layout are this library's).  The pool is caller-owned device memory of spec_kv_pool_bytes():
- *   pool[layer_pool][page][K=0|V=1][kv_head] -> one block of SPEC_PAGE_SIZE * head_dim elements,
+ *   pool[layer_pool][page][K=0|V=1][kv_head] -> one block of SPEC_PAGE_SIZE * head_dim elements (of the cache's
+ *   storage type: `dtype`, or one byte each with kv_dtype = SPEC_FP8_E4M3),
  * layer_pool = layer if layer_alias_mod == 0, else layer % layer_alias_mod (several layers share a
  * pool region: a way to run a cache larger than memory through the real access pattern; each
  * layer writes its new entries before it reads, cached context then is per region, not per layer).
@@ -116,6 +124,13 @@ int64_t spec_kv_pool_bytes(const spec_model* model, int64_t n_pages, int32_t lay
 spec_status spec_kv_alloc(const spec_model* model, int32_t max_seqs, int32_t max_ctx_len, int64_t n_pages,
                           void* dev_pool, int32_t layer_alias_mod, spec_kv** out);
 spec_status spec_kv_free(spec_kv* kv);
+
+/*
+ * 8-bit cache only: the scales, dev_k_scale and dev_v_scale [n_layers * n_kv_heads] fp32 in device memory (> 0),
+ * borrowed until spec_kv_free.  Must be called before the first forward pass on this cache (SPEC_ESTATE otherwise);
+ * SPEC_EINVAL for a cache that is not 8-bit.  The caller's page contents are codes under these scales.
+ */
+spec_status spec_kv_set_scales(spec_kv* kv, const float* dev_k_scale, const float* dev_v_scale);
 
 /* Element offset (in elements) of (t, c) inside a K (is_v = 0) or V (is_v = 1) block; -1 on bad input. */
 int64_t spec_kv_block_offset(const spec_kv* kv, int32_t is_v, int32_t t, int32_t c);

@@ -15,13 +15,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspecverify.so")
 
 SPEC_OK, SPEC_EINVAL, SPEC_ENOMEM, SPEC_EHIP, SPEC_ESTATE, SPEC_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
-SPEC_F32, SPEC_BF16 = 0, 1
+SPEC_F32, SPEC_BF16, SPEC_FP8_E4M3 = 0, 1, 2
 SPEC_MAX_DRAFT = 15
 SPEC_PAGE_SIZE = 16
 
 EXPORTS = [
     "spec_last_error", "spec_model_weight_count", "spec_model_create", "spec_model_destroy", "spec_kv_pool_bytes",
-    "spec_kv_alloc", "spec_kv_free", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
+    "spec_kv_alloc", "spec_kv_free", "spec_kv_set_scales", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample",
     "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
@@ -41,7 +41,7 @@ class spec_model_desc(ctypes.Structure):
                                               "ffn_dim", "vocab")] + \
                [("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("dtype", ctypes.c_int32),
                 ("tied_head", ctypes.c_int32), ("n_experts", ctypes.c_int32), ("top_k", ctypes.c_int32),
-                ("expert_ffn_dim", ctypes.c_int32), ("fuse_hidden", ctypes.c_int32)]
+                ("expert_ffn_dim", ctypes.c_int32), ("fuse_hidden", ctypes.c_int32), ("kv_dtype", ctypes.c_int32)]
 
 
 _lib = None
@@ -65,6 +65,7 @@ def lib():
             "spec_kv_pool_bytes": (i64, [vp, i64, i32]),
             "spec_kv_alloc": (i32, [vp, i32, i32, i64, vp, i32, vp]),
             "spec_kv_free": (i32, [vp]),
+            "spec_kv_set_scales": (i32, [vp, vp, vp]),
             "spec_kv_block_offset": (i64, [vp, i32, i32, i32]),
             "spec_kv_block_base": (i64, [vp, i32, i64, i32, i32]),
             "spec_kv_seq_assign": (i32, [vp, i32, i32, vp, i32]),
@@ -147,6 +148,7 @@ def make_desc(cfg):
     d.tied_head = int(cfg.get("tied_head", 0))
     d.n_experts, d.top_k, d.expert_ffn_dim = (int(cfg.get(n, 0)) for n in ("n_experts", "top_k", "expert_ffn_dim"))
     d.fuse_hidden = int(cfg.get("fuse_hidden", 0))
+    d.kv_dtype = {None: 0, "fp8_e4m3": SPEC_FP8_E4M3}[cfg.get("kv_dtype")]
     return d
 
 
@@ -176,6 +178,11 @@ def spec_kv_alloc(model, max_seqs, max_ctx_len, n_pages, pool, layer_alias_mod=0
     out = ctypes.c_void_p()
     _check(lib().spec_kv_alloc(model, max_seqs, max_ctx_len, n_pages, _ptr(pool), layer_alias_mod, ctypes.byref(out)))
     return out
+
+
+def spec_kv_set_scales(kv, k_scale, v_scale):
+    """k_scale, v_scale: fp32 device tensors [n_layers * n_kv_heads]; the caller keeps them alive."""
+    _check(lib().spec_kv_set_scales(kv, _ptr(k_scale), _ptr(v_scale)))
 
 
 def spec_kv_free(kv):

@@ -145,6 +145,10 @@ static spec_status check_desc(const spec_model_desc& d)
             return SPEC_EUNSUPPORTED;
         }
     }
+    if (d.kv_dtype != 0 && !(d.kv_dtype == SPEC_FP8_E4M3 && d.dtype == SPEC_BF16)) {
+        set_error("spec_model_create: kv_dtype must be 0 or SPEC_FP8_E4M3 (bf16 models only)");
+        return SPEC_EUNSUPPORTED;
+    }
     if (d.fuse_hidden) {
         if (d.dtype != SPEC_BF16 || d.n_experts > 0 || d.ffn_dim < 2 * d.d_model) {
             set_error("spec_model_create: a model with hidden-state input must be bf16, dense, with ffn_dim >= 2 * d_model");
@@ -248,7 +252,9 @@ extern "C" spec_status spec_model_destroy(spec_model* m)
 
 // ------------------------------------------------------------------------------------------ cache
 
-static int elem_bytes(int dtype) { return dtype == SPEC_F32 ? 4 : 2; }
+static int elem_bytes(int dtype) { return dtype == SPEC_F32 ? 4 : dtype == SPEC_FP8_E4M3 ? 1 : 2; }
+// storage type of the cache's blocks
+static int kv_storage(const spec_model_desc& d) { return d.kv_dtype == SPEC_FP8_E4M3 ? SPEC_FP8_E4M3 : d.dtype; }
 
 void spec_kv::recount()
 {
@@ -271,7 +277,10 @@ specv::KvView spec_kv::view() const
     v.n_kv_heads = model->desc.n_kv_heads;
     v.head_dim = model->desc.head_dim;
     v.alias_mod = alias_mod;
-    v.elem_bytes = elem_bytes(model->desc.dtype);
+    v.elem_bytes = elem_bytes(kv_storage(model->desc));
+    v.fp8 = model->desc.kv_dtype == SPEC_FP8_E4M3;
+    v.k_scale = k_scale;
+    v.v_scale = v_scale;
     return v;
 }
 
@@ -279,7 +288,7 @@ extern "C" int64_t spec_kv_pool_bytes(const spec_model* m, int64_t n_pages, int3
 {
     if (!m || n_pages < 1 || alias < 0) return -1;
     int pools = alias > 0 ? (alias < m->desc.n_layers ? alias : m->desc.n_layers) : m->desc.n_layers;
-    return (int64_t)pools * n_pages * 2 * m->desc.n_kv_heads * SPEC_PAGE_SIZE * m->desc.head_dim * elem_bytes(m->desc.dtype);
+    return (int64_t)pools * n_pages * 2 * m->desc.n_kv_heads * SPEC_PAGE_SIZE * m->desc.head_dim * elem_bytes(kv_storage(m->desc));
 }
 
 extern "C" spec_status spec_kv_alloc(const spec_model* m, int32_t max_seqs, int32_t max_ctx_len, int64_t n_pages,
@@ -335,12 +344,21 @@ extern "C" spec_status spec_kv_free(spec_kv* kv)
     return SPEC_OK;
 }
 
+extern "C" spec_status spec_kv_set_scales(spec_kv* kv, const float* dev_k_scale, const float* dev_v_scale)
+{
+    if (!kv || !dev_k_scale || !dev_v_scale) { set_error("spec_kv_set_scales: null pointer"); return SPEC_EINVAL; }
+    if (kv->model->desc.kv_dtype != SPEC_FP8_E4M3) { set_error("spec_kv_set_scales: not an 8-bit cache"); return SPEC_EINVAL; }
+    kv->k_scale = dev_k_scale;
+    kv->v_scale = dev_v_scale;
+    return SPEC_OK;
+}
+
 extern "C" int32_t spec_kv_max_pages_per_seq(const spec_kv* kv) { return kv ? kv->max_pages : -1; }
 
 extern "C" int64_t spec_kv_block_offset(const spec_kv* kv, int32_t is_v, int32_t t, int32_t c)
 {
     if (!kv || t < 0 || t >= SPEC_PAGE_SIZE || c < 0 || c >= kv->model->desc.head_dim || (is_v != 0 && is_v != 1)) return -1;
-    return kv_block_offset(kv->model->desc.dtype, is_v, t, c, kv->model->desc.head_dim);
+    return kv_block_offset(kv_storage(kv->model->desc), is_v, t, c, kv->model->desc.head_dim);
 }
 
 extern "C" int64_t spec_kv_block_base(const spec_kv* kv, int32_t layer, int64_t page, int32_t is_v, int32_t h)
@@ -453,6 +471,7 @@ extern "C" spec_status spec_verify_forward_hidden(spec_model* m, spec_kv* kv, in
     }
     if (dev_hidden_out && m->desc.dtype != SPEC_BF16) { set_error("spec_verify_forward_hidden: hidden-state output needs a bf16 model"); return SPEC_EUNSUPPORTED; }
     if (B < 1 || B > kv->max_seqs || k < 0 || k > SPEC_MAX_DRAFT) { set_error("spec_verify_forward: B or k out of range"); return SPEC_EINVAL; }
+    if (m->desc.kv_dtype == SPEC_FP8_E4M3 && !(kv->k_scale && kv->v_scale)) { set_error("spec_verify_forward: the 8-bit cache has no scales yet (spec_kv_set_scales)"); return SPEC_ESTATE; }
     if (ws_bytes < spec_verify_workspace_bytes(m, kv, B, k)) { set_error("spec_verify_forward: workspace too small (%zu < %zu)", ws_bytes, spec_verify_workspace_bytes(m, kv, B, k)); return SPEC_EINVAL; }
     if (((uintptr_t)ws & 255) != 0) { set_error("spec_verify_forward: workspace must be 256-byte aligned"); return SPEC_EINVAL; }
     // page budget: every batch entry may need ceil((k+1)/P)+1 more pages than it holds at most

@@ -77,10 +77,13 @@ __device__ inline float quad_sum(float x)
 // in one register, lane j holding its j-th page, and are broadcast with v_readlane.  Pages that need masks (those
 // reaching into the new positions, or past the end of the sequence: the last one or two) are left out of the
 // pipelined loop and done last.
-template <int NRB>
+// KV8: the blocks hold E4M3 codes (half the bytes, two MFMA fragments per 16-byte word); a page's codes are widened to
+// bf16 in registers once (exact: 3 mantissa bits) and feed the same MFMAs.  The key scale of the (layer, kv head) is
+// folded into the score scale here, the value scale into the final normalisation (attn_reduce_kernel).
+template <int NRB, bool KV8>
 __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
     const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
-    int layer_pool, float scale_log2, int max_chunks, int chunk_pages, int RG, int rows, int Hkv, int BP, int B,
+    int layer_pool, int layer, float scale_log2_in, int max_chunks, int chunk_pages, int RG, int rows, int Hkv, int BP, int B,
     float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     const int kvh = blockIdx.x % Hkv, rb0 = (blockIdx.y % RG) * NRB, chunk = blockIdx.z;
@@ -102,6 +105,7 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int lq = lane & 15, lg = lane >> 4;
     const int R = T * G;
+    const float scale_log2 = KV8 ? scale_log2_in * kv.k_scale[layer * Hkv + kvh] : scale_log2_in;
 
     __shared__ u32x4_t s_q[NRB][4][2][64];                      // [row block][32 channels][hi | lo][lane]
     __shared__ float s_o[ATT_WAVES][8][64][4];
@@ -131,7 +135,7 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
     const u32x4_t* pool = (const u32x4_t*)kv.pool;
     const int64_t layer_base = (int64_t)layer_pool * kv.n_pages;
     auto block_ptr = [&](int physical_page, int is_v) {
-        return pool + ((((layer_base + physical_page) * 2 + is_v) * Hkv + kvh) * BLOCK_U4) + lane;
+        return pool + ((((layer_base + physical_page) * 2 + is_v) * Hkv + kvh) * (KV8 ? BLOCK_U4 / 2 : BLOCK_U4)) + lane;
     };
     // lane j: physical id of this wavefront's j-th page (chunk_pages <= 256: at most 64 per wavefront), clamped to the chunk
     int my_pid;
@@ -150,14 +154,27 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) oacc[rb][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
-    u32x4_t kf[ATT_DEPTH][4], vf[ATT_DEPTH][4];
+    constexpr int NF = KV8 ? 2 : 4;                   // 16-byte words per lane and block
+    u32x4_t kf[ATT_DEPTH][NF], vf[ATT_DEPTH][NF];
     auto load_page = [&](int slot, int physical_page) {
         const u32x4_t* kp = block_ptr(physical_page, 0);
         const u32x4_t* vp = block_ptr(physical_page, 1);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kf[slot][s] = __builtin_nontemporal_load(kp + s * 64);
+        for (int s = 0; s < NF; ++s) kf[slot][s] = __builtin_nontemporal_load(kp + s * 64);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) vf[slot][s] = __builtin_nontemporal_load(vp + s * 64);
+        for (int s = 0; s < NF; ++s) vf[slot][s] = __builtin_nontemporal_load(vp + s * 64);
+    };
+    // fragment i (8 bf16) of a block held as codes: the i-th group of 8 bytes
+    auto widen = [&](const u32x4_t (&f)[NF], int i) {
+        if constexpr (KV8) {
+            const unsigned int wa = f[i >> 1][(i & 1) * 2], wb = f[i >> 1][(i & 1) * 2 + 1];
+            return u32x4_t{__builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wa, 1.0f, false)),
+                           __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wa, 1.0f, true)),
+                           __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wb, 1.0f, false)),
+                           __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wb, 1.0f, true))};
+        } else {
+            return f[i];
+        }
     };
     __syncthreads();                                  // the queries are in LDS
 
@@ -190,6 +207,9 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
         constexpr bool need_mask = decltype(mask_c)::value;
         constexpr int MODE = decltype(mode_c)::value;
         const int key0 = logical_page * SPEC_PAGE_SIZE + lg * 4;
+        u32x4_t kcur[4], vcur[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { kcur[i] = widen(kf[slot], i); vcur[i] = widen(vf[slot], i); }
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
             // the three phases of a row block are pinned in this order (left alone, the scheduler hoists the query
@@ -198,7 +218,7 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
             f32x4_t sacc = {0.f, 0.f, 0.f, 0.f}, sacc2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int sg = 0; sg < 4; ++sg) {
-                const bf16x8_t kk = __builtin_bit_cast(bf16x8_t, kf[slot][sg]);
+                const bf16x8_t kk = __builtin_bit_cast(bf16x8_t, kcur[sg]);
                 sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[rb & 1][sg], sacc, 0, 0, 0);
                 sacc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[rb & 1][sg], sacc2, 0, 0, 0);
             }
@@ -253,7 +273,7 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
             s16x4_t va[4], vb[4];
 #pragma unroll
             for (int cp = 0; cp < 4; ++cp) {
-                u32x4_t v = vf[slot][cp];
+                u32x4_t v = vcur[cp];
                 if (need_mask) {
                     unsigned int m01 = (key0 + 0 < total ? 0x0000ffffu : 0u) | (key0 + 1 < total ? 0xffff0000u : 0u);
                     unsigned int m23 = (key0 + 2 < total ? 0x0000ffffu : 0u) | (key0 + 3 < total ? 0xffff0000u : 0u);
@@ -371,7 +391,7 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
 // operand of the O projection: xp[k-step][m-block][lane][8] with k = head*128 + channel
 __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int B, int T,
                                    int G, int Hkv, int RBrows, int max_chunks, int chunk_pages, const int32_t* __restrict__ seq_ids,
-                                   KvView kv, int mb_pad, uint4* __restrict__ xp)
+                                   KvView kv, int layer, int mb_pad, uint4* __restrict__ xp)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int R = T * G;
@@ -400,6 +420,7 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
         o[4] += f * d.x; o[5] += f * d.y; o[6] += f * d.z; o[7] += f * d.w;
     }
     float inv = L > 0.f ? 1.0f / L : 0.f;
+    if (kv.fp8) inv *= kv.v_scale[layer * Hkv + kvh];     // 8-bit cache: the values were accumulated as codes
     float res[8];
     for (int j = 0; j < 8; ++j) res[j] = o[j] * inv;
     xp_store8(xp, b * T + r / G, (kvh * G + r % G) * DH + c8 * 8, mb_pad, res);
@@ -451,7 +472,7 @@ int attn_rows_padded(int R)
 }
 
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
-                                  const KvView& kv, int layer_pool, int pages_bound, float* part_o, float* part_ml,
+                                  const KvView& kv, int layer_pool, int layer, int pages_bound, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s)
 {
     int R = T * G;
@@ -465,7 +486,10 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
     while ((Hkv * BP) % 8 != 0) BP *= 2;
     dim3 grid((unsigned)(Hkv * BP), (unsigned)(RG * cdiv(B, BP)), (unsigned)max_chunks);
     const float* qq = q;
-#define SPEC_ATTN_LAUNCH(NRBV) attn_partial_kernel<NRBV><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, scale_log2, max_chunks, cp, RG, rows, Hkv, BP, B, part_o, part_ml)
+#define SPEC_ATTN_LAUNCH(NRBV) do { \
+        if (kv.fp8) attn_partial_kernel<NRBV, true><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, layer, scale_log2, max_chunks, cp, RG, rows, Hkv, BP, B, part_o, part_ml); \
+        else attn_partial_kernel<NRBV, false><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, layer, scale_log2, max_chunks, cp, RG, rows, Hkv, BP, B, part_o, part_ml); \
+    } while (0)
     switch (pl.RB) {
     case 1: SPEC_ATTN_LAUNCH(1); break;
     case 2: SPEC_ATTN_LAUNCH(2); break;
@@ -477,7 +501,7 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
     prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);
     attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, rows, max_chunks, cp, seq_ids, kv,
-                                                                  mb_pad, (uint4*)xp_out);
+                                                                  layer, mb_pad, (uint4*)xp_out);
     SPEC_LAUNCH_CHECK("attn_reduce_kernel");
     prof_mark(PC_ATTN_REDUCE, s);
     return SPEC_OK;

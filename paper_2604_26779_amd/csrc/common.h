@@ -58,6 +58,9 @@ struct KvView {
     int32_t n_kv_heads, head_dim;
     int32_t alias_mod;
     int32_t elem_bytes;
+    int32_t fp8;               // 1: blocks hold E4M3 codes of x / scale
+    const float* k_scale;      // [n_layers * n_kv_heads], fp8 only
+    const float* v_scale;
 };
 
 // ---- packed bf16 matrix for the MFMA GEMM (see gemm_bf16.hip for the tiling) ----
@@ -97,6 +100,7 @@ struct spec_kv {
     int32_t max_seqs = 0, max_pages = 0, alias_mod = 0;
     int64_t n_pages = 0;
     void* pool = nullptr;
+    const float *k_scale = nullptr, *v_scale = nullptr;   // 8-bit cache: borrowed device arrays [n_layers * n_kv_heads]
     // device state (one allocation)
     int32_t* d_state = nullptr;
     int32_t *d_ctx_len = nullptr, *d_n_held = nullptr, *d_page_table = nullptr, *d_free_stack = nullptr,
@@ -153,6 +157,12 @@ spec_status bf16_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t
 __host__ __device__ inline int64_t kv_block_offset(int dtype, int is_v, int t, int c, int head_dim)
 {
     if (dtype == SPEC_F32) return (int64_t)t * head_dim + c;            // natural [t][c]
+    if (dtype == SPEC_FP8_E4M3) {
+        // one-byte elements, same MFMA operand order as bf16 with two fragments per 16-byte word:
+        // K: [c/64][(c/8)%4][t][(c/32)%2][c%8]      V: [c/64][t/4][c%16][(c/32)%2][(c/16)%2][t%4]
+        if (!is_v) return ((((int64_t)(c >> 6) * 4 + ((c >> 3) & 3)) * SPEC_PAGE_SIZE + t) * 2 + ((c >> 5) & 1)) * 8 + (c & 7);
+        return (((((int64_t)(c >> 6) * 4 + (t >> 2)) * 16 + (c & 15)) * 2 + ((c >> 5) & 1)) * 2 + ((c >> 4) & 1)) * 4 + (t & 3);
+    }
     if (!is_v)                                                           // K: [c/8][t][8]
         return ((int64_t)(c >> 3) * SPEC_PAGE_SIZE + t) * 8 + (c & 7);
     // V: [c/32][t/4][c%16][(c/16)%2][t%4]

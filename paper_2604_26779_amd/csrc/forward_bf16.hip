@@ -33,7 +33,7 @@ spec_status launch_moe_gather(const bf16_t* xp_src, int mb_pad_src, const int32_
 spec_status launch_moe_combine_norm(float* x, const float* y, const int32_t* pair_row, const float* wts, int M, int top_k,
                                     const void* gain, int d, float eps, int mb_pad, bf16_t* xp, hipStream_t s);
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
-                                  const KvView& kv, int layer_pool, int pages_bound, float* part_o, float* part_ml,
+                                  const KvView& kv, int layer_pool, int layer, int pages_bound, float* part_o, float* part_ml,
                                   int mb_pad, bf16_t* xp_out, hipStream_t s);
 
 // sum over the workgroup (blockDim.x a multiple of 64, at most 1024)
@@ -157,9 +157,11 @@ __global__ void rope_table_kernel(int M, int T, const int32_t* __restrict__ seq_
 
 // sums the split-K slices of the QKV projection, rotates q and k, writes q as bf16 rows and the
 // new k, v into their cache slots (speculatively: positions ctx .. ctx+k).  One workgroup per row.
+// KV8: the cache holds E4M3 codes of x / scale, one scale per (layer, kv head) for keys and one for values.
+template <bool KV8>
 __global__ __launch_bounds__(256) void qkv_rope_kernel(
     const float* __restrict__ part, int splits, int64_t split_stride, int T, int Hq, int Hkv,
-    const float2* __restrict__ rope, const int32_t* __restrict__ seq_ids, KvView kv, int layer_pool,
+    const float2* __restrict__ rope, const int32_t* __restrict__ seq_ids, KvView kv, int layer_pool, int layer,
     float* __restrict__ q_out)
 {
     constexpr int DHc = 128, HALF = 64;
@@ -202,9 +204,18 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(
             *(float4*)(dst + j + HALF) = make_float4(ru[0], ru[1], ru[2], ru[3]);
         } else if (writable) {
             int kh = h - Hq;
-            unsigned short* dst = pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 0) * Hkv + kh) * block;
-            *(uint2*)(dst + kv_block_offset(SPEC_BF16, 0, t, j, DHc)) = plo;
-            *(uint2*)(dst + kv_block_offset(SPEC_BF16, 0, t, j + HALF, DHc)) = phi;
+            if constexpr (KV8) {
+                const float ks = kv.k_scale[layer * Hkv + kh];
+                unsigned char* dst = (unsigned char*)kv.pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 0) * Hkv + kh) * block;
+                *(unsigned int*)(dst + kv_block_offset(SPEC_FP8_E4M3, 0, t, j, DHc)) =
+                    to_e4m3(rl[0] / ks) | (to_e4m3(rl[1] / ks) << 8) | (to_e4m3(rl[2] / ks) << 16) | (to_e4m3(rl[3] / ks) << 24);
+                *(unsigned int*)(dst + kv_block_offset(SPEC_FP8_E4M3, 0, t, j + HALF, DHc)) =
+                    to_e4m3(ru[0] / ks) | (to_e4m3(ru[1] / ks) << 8) | (to_e4m3(ru[2] / ks) << 16) | (to_e4m3(ru[3] / ks) << 24);
+            } else {
+                unsigned short* dst = pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 0) * Hkv + kh) * block;
+                *(uint2*)(dst + kv_block_offset(SPEC_BF16, 0, t, j, DHc)) = plo;
+                *(uint2*)(dst + kv_block_offset(SPEC_BF16, 0, t, j + HALF, DHc)) = phi;
+            }
         }
     }
     // values: no rotation
@@ -212,6 +223,15 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(
         for (int e = threadIdx.x + 256 * blockIdx.y; e < Hkv * (DHc / 4); e += 256 * gridDim.y) {
             int kh = e / (DHc / 4), c = (e % (DHc / 4)) * 4;
             float4 v = sum4((Hq + Hkv + kh) * DHc + c);
+            if constexpr (KV8) {
+                const float vs = kv.v_scale[layer * Hkv + kh];
+                unsigned char* dst8 = (unsigned char*)kv.pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 1) * Hkv + kh) * block;
+                dst8[kv_block_offset(SPEC_FP8_E4M3, 1, t, c + 0, DHc)] = (unsigned char)to_e4m3(v.x / vs);
+                dst8[kv_block_offset(SPEC_FP8_E4M3, 1, t, c + 1, DHc)] = (unsigned char)to_e4m3(v.y / vs);
+                dst8[kv_block_offset(SPEC_FP8_E4M3, 1, t, c + 2, DHc)] = (unsigned char)to_e4m3(v.z / vs);
+                dst8[kv_block_offset(SPEC_FP8_E4M3, 1, t, c + 3, DHc)] = (unsigned char)to_e4m3(v.w / vs);
+                continue;
+            }
             unsigned short* dst = pool + ((((int64_t)layer_pool * kv.n_pages + page) * 2 + 1) * Hkv + kh) * block;
             dst[kv_block_offset(SPEC_BF16, 1, t, c + 0, DHc)] = to_bf16(v.x);
             dst[kv_block_offset(SPEC_BF16, 1, t, c + 1, DHc)] = to_bf16(v.y);
@@ -368,9 +388,12 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         int lp = kv->alias_mod > 0 ? l % kv->alias_mod : l;
         if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_QKV, s);
-        qkv_rope_kernel<<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, qbuf);
+        if (view.fp8)
+            qkv_rope_kernel<true><<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, l, qbuf);
+        else
+            qkv_rope_kernel<false><<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, l, qbuf);
         prof_mark(PC_QKV_ROPE, s);
-        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, live_pages, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
+        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, l, live_pages, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
         if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_O, s);
         residual_rmsnorm_kernel<RES_ADD><<<M, norm_threads, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,

@@ -26,6 +26,18 @@ __device__ inline unsigned int pack_bf16x2(float a, float b)
 {
     return __builtin_bit_cast(unsigned int, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
 }
+// fp32 -> OCP E4M3 code (1-4-3 bits, bias 7, no infinities, largest magnitude 448 = 0x7e): round to nearest even,
+// saturating; NaN is not handled (it saturates).
+__device__ inline unsigned int to_e4m3(float x)
+{
+    const unsigned int u = __float_as_uint(x), sign = (u >> 24) & 0x80u, au = u & 0x7fffffffu;
+    const float a = __uint_as_float(au);
+    if (!(a < 448.0f)) return sign | 0x7eu;
+    if (a < 0.015625f) return sign | (unsigned int)__float2int_rn(a * 512.0f);      // zero, subnormals (steps of 2^-9), up to 2^-6 itself
+    const unsigned int r = (au + 0x7ffffu + ((au >> 20) & 1u)) >> 20;                // keep 3 mantissa bits, ties to even
+    return sign | (r - ((127u - 7u) << 3));
+}
+
 __device__ inline unsigned short to_bf16(float f) { return (unsigned short)(pack_bf16x2(f, 0.f) & 0xffffu); }
 __device__ inline float from_bf16(unsigned short h) { return __uint_as_float((unsigned int)h << 16); }
 

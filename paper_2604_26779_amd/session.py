@@ -18,14 +18,24 @@ class VerifySession:
         self.model = sv.spec_model_create(self.cfg, self.weights)
         self.max_seqs, self.n_pages, self.alias = int(max_seqs), int(n_pages), int(layer_alias_mod)
         self.dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[cfg["dtype"]]
+        self.kv8 = cfg.get("kv_dtype") == "fp8_e4m3"
+        if self.kv8:                       # 8-bit cache: the pool holds E4M3 codes, moved around as bytes
+            self.dtype = torch.uint8
         nbytes = sv.spec_kv_pool_bytes(self.model, self.n_pages, self.alias)
         self.pool = torch.empty(nbytes // self.dtype.itemsize, dtype=self.dtype, device=self.device)
         self.kv = sv.spec_kv_alloc(self.model, self.max_seqs, int(max_ctx_len), self.n_pages, self.pool, self.alias)
+        self.k_scale = self.v_scale = None
         P, dh = sv.SPEC_PAGE_SIZE, cfg["head_dim"]
         # in-block element order, asked from the library
         self.perm = [torch.tensor([sv.spec_kv_block_offset(self.kv, is_v, t, c) for t in range(P) for c in range(dh)],
                                   dtype=torch.long, device=self.device) for is_v in (0, 1)]
         self._bufs = {}
+
+    def set_scales(self, k_scale, v_scale):
+        """8-bit cache: fp32 scales [n_layers, n_kv_heads] for keys and values (kept alive here)."""
+        self.k_scale = torch.as_tensor(k_scale, dtype=torch.float32).to(self.device).contiguous()
+        self.v_scale = torch.as_tensor(v_scale, dtype=torch.float32).to(self.device).contiguous()
+        sv.spec_kv_set_scales(self.kv, self.k_scale, self.v_scale)
 
     def close(self):
         if self.kv is not None:
@@ -42,7 +52,8 @@ class VerifySession:
         return self.pool.view(pools, self.n_pages, 2, self.cfg["n_kv_heads"], sv.SPEC_PAGE_SIZE * self.cfg["head_dim"])
 
     def write_logical_kv(self, layer, page_ids, K, V):
-        """K, V [n_tokens, Hkv, dh] -> the sequence's pages of `layer` (tokens beyond n_tokens zero-filled)."""
+        """K, V [n_tokens, Hkv, dh] -> the sequence's pages of `layer` (tokens beyond n_tokens zero-filled).
+        8-bit cache: K, V are the codes (uint8, or float8_e4m3fn tensors whose bytes are taken)."""
         P, dh, Hkv = sv.SPEC_PAGE_SIZE, self.cfg["head_dim"], self.cfg["n_kv_heads"]
         n_tok = K.shape[0]
         npg = -(-n_tok // P)
@@ -53,7 +64,7 @@ class VerifySession:
         view = self.pool_view()
         for is_v, src in ((0, K), (1, V)):
             pad = torch.zeros((npg * P, Hkv, dh), dtype=self.dtype, device=self.device)
-            pad[:n_tok] = src.to(self.device, self.dtype)
+            pad[:n_tok] = src.view(torch.uint8).to(self.device) if self.kv8 else src.to(self.device, self.dtype)
             blocks = pad.view(npg, P, Hkv, dh).permute(0, 2, 1, 3).reshape(npg, Hkv, P * dh)
             phys = torch.empty_like(blocks)
             phys[:, :, self.perm[is_v]] = blocks

@@ -42,8 +42,17 @@ class DeviceWorkload:
         g.manual_seed(int(seed) + 2)
         chunk = 1 << 28
         flat = self.sess.pool
-        for at in range(0, flat.numel(), chunk):
-            flat[at:at + chunk].normal_(generator=g)
+        if self.sess.kv8:
+            # codes of N(0, KV8_NOMINAL) entries (the library's cast), under the synthetic scales
+            for at in range(0, flat.numel(), chunk):
+                n = min(chunk, flat.numel() - at)
+                draw = torch.empty(n, dtype=torch.bfloat16, device=device).normal_(0.0, si.KV8_NOMINAL, generator=g)
+                flat[at:at + n] = draw.to(torch.float8_e4m3fn).view(torch.uint8)
+            self.kv_scales = si.kv_scales(self.cfg, seed=seed)
+            self.sess.set_scales(*self.kv_scales)
+        else:
+            for at in range(0, flat.numel(), chunk):
+                flat[at:at + chunk].normal_(generator=g)
         self.seq_ids = torch.arange(B, dtype=torch.int32, device=device)
         for b in range(B):
             self.sess.assign(b, int(self.ctx_len[b]), self.batch["page_lists"][b])
@@ -70,7 +79,10 @@ class DeviceWorkload:
 
     def logical_kv(self, layer, b):
         """(K, V) [ctx_len[b], Hkv, dh] of sequence b as the cache holds them (device tensors)."""
-        return self.sess.read_logical_kv(layer, self.batch["page_lists"][b], int(self.ctx_len[b]))
+        K, V = self.sess.read_logical_kv(layer, self.batch["page_lists"][b], int(self.ctx_len[b]))
+        if self.sess.kv8:                                 # bytes -> the library's 8-bit float type (codes)
+            K, V = K.view(torch.float8_e4m3fn), V.view(torch.float8_e4m3fn)
+        return K, V
 
     def restore(self, stream=None):
         sv.spec_kv_restore(self.sess.kv, self.snapshot, stream)
@@ -85,6 +97,7 @@ def algorithmic_bytes(cfg, ctx_len, B, k):
     L, D, F, V = cfg["n_layers"], cfg["d_model"], cfg["ffn_dim"], cfg["vocab"]
     nq, nkv = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
     eb = 2 if cfg["dtype"] == "bf16" else 4
+    kvb = 1 if cfg.get("kv_dtype") == "fp8_e4m3" else eb
     layer_w = (nq + 2 * nkv) * D + D * nq + 2 * F * D + D * F
     if cfg.get("n_experts", 0) > 0:          # every expert's matrices are touched once the batch is a few dozen rows
         E, Fe = cfg["n_experts"], cfg["expert_ffn_dim"]
@@ -99,7 +112,7 @@ def algorithmic_bytes(cfg, ctx_len, B, k):
         gemm=(L * layer_w + head_w) * eb,
         gemm_layers=L * layer_w * eb,
         gemm_head=head_w * eb,
-        attn=tokens * 2 * nkv * eb * L,
+        attn=tokens * 2 * nkv * kvb * L,
         sampler=B * (k + 1 + 2) * V * 4,
         logits_write=B * (k + 1) * V * 4,
     )

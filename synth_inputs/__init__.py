@@ -95,6 +95,16 @@ for _k in (1, 3, 5, 7):
         layer_alias_mod=8, noise_beta=(4.0, 2.0))
 
 
+# 8-bit (E4M3) KV cache variants: the same models and workloads with the cache stored as codes under one scale per
+# (layer, kv head).  With one byte per element the B=256 cache of 32 distinct layers (155 GB) fits one GPU un-aliased.
+for _name in ("small_bf16", "llama8b_bf16"):
+    MODELS[_name + "_kv8"] = dict(MODELS[_name], kv_dtype="fp8_e4m3")
+WORKLOADS["small_bf16_kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_kv8")
+WORKLOADS["llama8b_kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_kv8")
+WORKLOADS["llama8b_kv8_b256_ctx2k-16k_k3"] = dict(WORKLOADS["llama8b_b256_ctx2k-16k_k3"], model="llama8b_bf16_kv8",
+                                                  layer_alias_mod=0)
+
+
 def torch_dtype(name):
     return {"f32": torch.float32, "bf16": torch.bfloat16, "f64": torch.float64}[name]
 
@@ -188,23 +198,41 @@ def make_batch(workload, seed=DEFAULT_SEED, shuffle_pages=True, extra_pages=8):
 def make_logical_kv(cfg, ctx_len, seed=DEFAULT_SEED, device="cpu"):
     """Synthetic cached context: kv[layer][b] = (K, V), each [ctx_len[b], Hkv, dh] ~ N(0,1) in storage type."""
     g = _gen(int(seed) + 2, device)
-    dt = torch_dtype(cfg["dtype"])
+    kv8 = cfg.get("kv_dtype") == "fp8_e4m3"          # the tensors then hold codes: N(0, KV8_NOMINAL) cast by the library
+    dt = torch.float8_e4m3fn if kv8 else torch_dtype(cfg["dtype"])
+    std = KV8_NOMINAL if kv8 else 1.0
     Hkv, dh = cfg["n_kv_heads"], cfg["head_dim"]
     kv = []
     for _ in range(cfg["n_layers"]):
         per_seq = []
         for c in ctx_len:
-            K = torch.randn((int(c), Hkv, dh), generator=g, device=device, dtype=torch.float32).to(dt)
-            V = torch.randn((int(c), Hkv, dh), generator=g, device=device, dtype=torch.float32).to(dt)
+            K = (torch.randn((int(c), Hkv, dh), generator=g, device=device, dtype=torch.float32) * std).to(dt)
+            V = (torch.randn((int(c), Hkv, dh), generator=g, device=device, dtype=torch.float32) * std).to(dt)
             per_seq.append((K, V))
         kv.append(per_seq)
     return kv
 
 
-def kv_for_oracle(kv):
-    """kv[layer][b] = (K, V) tensors -> the same nesting with fp32 numpy arrays."""
-    return [[(K.detach().to("cpu", torch.float32).numpy(), V.detach().to("cpu", torch.float32).numpy())
-             for (K, V) in per_seq] for per_seq in kv]
+def kv_for_oracle(kv, scales=None):
+    """kv[layer][b] = (K, V) tensors -> the same nesting with fp32 numpy arrays.  With scales (k_scale, v_scale
+    [L, Hkv], an 8-bit cache whose tensors hold codes): what the cache returns, code * scale, in fp64."""
+    if scales is None:
+        return [[(K.detach().to("cpu", torch.float32).numpy(), V.detach().to("cpu", torch.float32).numpy())
+                 for (K, V) in per_seq] for per_seq in kv]
+    ks, vs = (np.asarray(a, dtype=np.float64) for a in scales)
+    return [[(K.detach().to("cpu", torch.float64).numpy() * ks[l][None, :, None], V.detach().to("cpu", torch.float64).numpy() * vs[l][None, :, None])
+             for (K, V) in per_seq] for l, per_seq in enumerate(kv)]
+
+
+KV8_NOMINAL = 48.0      # standard deviation of the synthetic cached context in code units (|x| stays below 448)
+
+
+def kv_scales(cfg, seed=DEFAULT_SEED):
+    """Synthetic calibration of an 8-bit cache: (k_scale, v_scale), each [L, Hkv] fp32, between 1/64 and 1/43 (not
+    powers of two), so that N(0,1)-sized entries use the upper binades of the format without saturating."""
+    rng = np.random.Generator(np.random.Philox(int(seed) + 31))
+    shape = (cfg["n_layers"], cfg["n_kv_heads"])
+    return ((1.0 + 0.5 * rng.random(shape)) / 64.0).astype(np.float32), ((1.0 + 0.5 * rng.random(shape)) / 64.0).astype(np.float32)
 
 
 def round_to_storage(array, dtype_name):

@@ -263,10 +263,11 @@ def test_forward_argument_errors_and_pool_exhaustion():
     assert e.value.status == sv.SPEC_EUNSUPPORTED
 
 
-def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, key_scale_fn=None, **model_changes):
-    """small_bf16 model, synthetic cache, explicit context lengths: returns (max err, worst over tolerance)."""
+def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, key_scale_fn=None, kv8=False, **model_changes):
+    """small_bf16 model, synthetic cache, explicit context lengths: returns (max err, worst over tolerance).
+    kv8: the 8-bit cache (codes under the synthetic scales; key_scale then multiplies the key scales instead)."""
     from paper_2604_26779_amd.session import VerifySession
-    cfg = dict(si.MODELS["small_bf16"])
+    cfg = dict(si.MODELS["small_bf16_kv8" if kv8 else "small_bf16"])
     cfg.update(model_changes)
     if vocab:
         cfg["vocab"] = vocab
@@ -275,19 +276,27 @@ def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, key_scale_f
     w_or = si.weights_for_oracle(cfg, weights)
     ctx_len = np.array(ctx_list, dtype=np.int64)
     kv = si.make_logical_kv(cfg, ctx_len, seed=seed)
+    scales = None
+    if kv8:
+        assert key_scale_fn is None
+        scales = si.kv_scales(cfg, seed=seed)
+        scales = (scales[0] * np.float32(key_scale), scales[1])
+        key_scale = 1.0
     if key_scale != 1.0:        # larger cached keys -> larger scores -> a peaked softmax (a few keys carry the weight)
         kv = [[((K.float() * key_scale).to(K.dtype), V) for (K, V) in per_seq] for per_seq in kv]
     if key_scale_fn is not None:    # a scale per cached position: key_scale_fn(ctx) -> [ctx] factors
         kv = [[((K.float() * torch.as_tensor(key_scale_fn(K.shape[0]), dtype=torch.float32).view(-1, 1, 1)).to(K.dtype), V)
                for (K, V) in per_seq] for per_seq in kv]
-    kv_or = si.kv_for_oracle(kv)
+    kv_or = si.kv_for_oracle(kv, scales)
     rng = np.random.default_rng(seed)
     n_ctx_pages = [-(-int(c) // si.PAGE_SIZE) for c in ctx_len]
     n_pages = sum(-(-(int(c) + k + 1) // si.PAGE_SIZE) for c in ctx_len) + 16
     order = rng.permutation(n_pages)
     sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=B, max_ctx_len=int(ctx_len.max()) + 64,
                          n_pages=n_pages)
-    sess.pool.fill_(float("nan"))                        # whatever a step reads beyond its data must not matter
+    sess.pool.fill_(0x7F if kv8 else float("nan"))       # (NaN in either storage type) whatever a step reads beyond its data must not matter
+    if kv8:
+        sess.set_scales(*scales)
     at = 0
     for b in range(B):
         pages = [int(p) for p in order[at:at + n_ctx_pages[b]]]
@@ -296,7 +305,7 @@ def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, key_scale_f
         for l in range(cfg["n_layers"]):
             sess.write_logical_kv(l, pages, kv[l][b][0], kv[l][b][1])
     tokens = rng.integers(0, cfg["vocab"], size=(B, k + 1)).astype(np.int32)
-    want, _ = of.verify_forward(cfg, w_or, kv_or, tokens, ctx_len)
+    want, _ = of.verify_forward(cfg, w_or, kv_or, tokens, ctx_len, kv_scales=scales)
     got = sess.forward(torch.arange(B, dtype=torch.int32, device="cuda"), torch.from_numpy(tokens).cuda())
     torch.cuda.synchronize()
     got = got.cpu().numpy()
@@ -391,13 +400,14 @@ def test_bf16_large_row_tiles(B, k, big_from):
     264 (9 blocks -> two 6-block tiles, the second half empty), 192 (one 6-block tile), 200 (7 blocks -> one 8-block tile),
     384 (two 6-block tiles) and 240; column counts that are not multiples of 256, fused SwiGLU epilogue, split K."""
     from paper_2604_26779_amd import binding as sv
+    before = sv.spec_tune_get("gemm_big_min_blocks")
     sv.spec_tune_set("gemm_big_min_blocks", big_from)
     try:
         rng = np.random.default_rng(B * 10 + k)
         ctx = [int(c) for c in rng.integers(3, 120, size=B)]
         ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000)
     finally:
-        sv.spec_tune_set("gemm_big_min_blocks", 0)
+        sv.spec_tune_set("gemm_big_min_blocks", before)
     print("B=%d k=%d (M=%d), big tiles from %d row blocks: logits max abs err %.3e" % (B, k, B * (k + 1), big_from, max_err))
     assert ok, (max_err, worst)
 
