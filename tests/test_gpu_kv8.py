@@ -5,8 +5,9 @@ What is compared, and how:
     attending to them: the bf16 tolerance (2e-2 abs + 1e-2 rel).  The cached codes are inputs (identical on
     both sides); the new positions' codes are decided by floating point (fp32 kernels, fp64 oracle), so
   * the new positions' codes in the cache are compared one by one: equal, except that a code may be the
-    neighbouring one (one step of the 3-bit mantissa) where the value sat at a rounding boundary; such elements
-    are counted, printed and bounded (1 %); the cached context's bytes must be untouched;
+    neighbouring one (one step of the 3-bit mantissa) where the value sat at a rounding boundary (near zero, where
+    the grid is finer than the kernels' own error, within 1e-3 in value); such elements are counted, printed and
+    bounded (1 %); the cached context's bytes must be untouched;
   * every attention layout (1..4 row blocks per workgroup, row groups, chunk lengths, masked last pages, empty
     caches, chunk boundaries) with the pool's unused bytes set to the format's NaN code.
 """
@@ -77,8 +78,10 @@ def test_kv8_small_workload_logits_and_cache_codes():
                 assert np.array_equal(dev[:c], kv[l][b][which].view(torch.uint8).numpy())           # context untouched
                 want_code = fp8.encode(new_kv[l][which][b] / np.asarray(scales[which], dtype=np.float64)[l][None, :, None])
                 diff = np.abs(_sign_magnitude_rank(dev[c:]) - _sign_magnitude_rank(want_code))
-                assert diff.max() <= 1, "a stored code is more than one step from the oracle's"
-                flips += int((diff == 1).sum())
+                # near zero the grid (2^-9 * scale) is finer than the kernels' own error: compare values there
+                far = np.abs(fp8.decode(dev[c:]) - fp8.decode(want_code)) * np.float64(scales[which][l])[None, :, None] > 1e-3
+                assert not np.any((diff > 1) & far), "a stored code is neither the oracle's neighbour nor within 1e-3 of it"
+                flips += int((diff >= 1).sum())
                 total += diff.size
     print("new positions' codes: %d of %d one step from the oracle's" % (flips, total))
     assert flips <= 0.01 * total

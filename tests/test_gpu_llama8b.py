@@ -32,7 +32,10 @@ def _check_workload(name, ks, moe_margin=None):
     w_or = si.weights_for_oracle(cfg, weights)
     del weights
     torch.cuda.empty_cache()
-    kv_or = [[tuple(t.float().cpu().numpy() for t in wl.logical_kv(l, b)) for b in picks] for l in range(cfg["n_layers"])]
+    kv8 = cfg.get("kv_dtype") == "fp8_e4m3"
+    scales = wl.kv_scales if kv8 else None                               # 8-bit cache: the oracle reads code * scale
+    kv_or = [[tuple(t.float().cpu().numpy().astype(np.float64) * (np.float64(scales[i][l])[None, :, None] if kv8 else 1.0)
+                    for i, t in enumerate(wl.logical_kv(l, b))) for b in picks] for l in range(cfg["n_layers"])]
     seq_ids = wl.seq_ids
     for k in ks:
         wl.restore()
@@ -42,7 +45,7 @@ def _check_workload(name, ks, moe_margin=None):
         assert torch.isfinite(logits).all()
         print(name, "k=%d: oracle on sequences" % k, picks, "contexts", [int(wl.ctx_len[b]) for b in picks], flush=True)
         log = []
-        want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks], route_log=log)
+        want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks], route_log=log, kv_scales=scales)
         got = logits[picks].cpu().numpy()
         if moe_margin is not None:
             # rows whose expert choice the oracle decides by less than the margin (and the rows after them in the
@@ -68,6 +71,20 @@ def _check_workload(name, ks, moe_margin=None):
         for j, b in enumerate(picks):
             K, V = wl.sess.read_logical_kv(last, book.pages[b], int(wl.ctx_len[b]) + k + 1)
             c = int(wl.ctx_len[b])
+            if kv8:
+                # codes: equal to the oracle's, or the neighbouring code where the value sat at a rounding boundary; near zero
+                # the grid (steps of 2^-9 * scale = 4e-5) is finer than the kernels' own error after 32 layers, so there
+                # the values are compared instead (2e-3, the bf16 path's bound on a key or value entry)
+                from oracle import fp8
+                rank = lambda code: np.where(code.astype(np.int64) & 0x80, -(code.astype(np.int64) & 0x7F), code.astype(np.int64) & 0x7F)
+                for which, dev in ((0, K), (1, V)):
+                    want_code = fp8.encode(new_kv[last][which][j] / np.float64(scales[which][last])[None, :, None])
+                    got_code = dev[c:].cpu().numpy()
+                    diff = np.abs(rank(got_code) - rank(want_code))
+                    far = np.abs(fp8.decode(got_code) - fp8.decode(want_code)) * np.float64(scales[which][last])[None, :, None] > 2e-3
+                    assert not np.any((diff > 1) & far), "a stored code is neither the oracle's neighbour nor within 2e-3 of it"
+                    assert (diff >= 1).sum() <= 0.02 * diff.size, (diff.max(), (diff >= 1).sum())
+                continue
             assert np.max(np.abs(K[c:].float().cpu().numpy() - new_kv[last][0][j])) < 2e-2 * max(1.0, np.abs(new_kv[last][0][j]).max())
             assert np.max(np.abs(V[c:].float().cpu().numpy() - new_kv[last][1][j])) < 2e-2 * max(1.0, np.abs(new_kv[last][1][j]).max())
 
@@ -90,6 +107,17 @@ def test_llama8b_logits_on_sampled_sequences_and_commit():
 
 def test_llama8b_large_batch_aliased_pool_k7_and_k1():
     _check_workload("llama8b_b256_ctx2k-16k_k7", [7, 1])
+
+
+def test_llama8b_8bit_cache_full_size():
+    """The same step with the E4M3 cache (codes N(0, 48) under per-(layer, kv head) scales)."""
+    _check_workload("llama8b_kv8_b32_ctx1k-8k_k3", [3])
+
+
+def test_llama8b_8bit_cache_large_batch_all_layers_distinct():
+    """B = 256, contexts 2048..16384: with one byte per entry the cache of 32 distinct layers (155 GB) fits one GPU,
+    so no layer pools are shared here."""
+    _check_workload("llama8b_kv8_b256_ctx2k-16k_k3", [3])
 
 
 def test_moe_slice_full_size():
