@@ -95,6 +95,11 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
     const int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
     if (total > cap) total = cap;
     const int n_pages_seq = (total + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
+    // the sequence's pages go over its ceil(pages / chunk_pages) chunks in equal shares (a multiple of the wavefront
+    // count each), so that no workgroup is left with a short tail chunk that is mostly prologue and merge
+    const int n_chunks_seq = (n_pages_seq + chunk_pages - 1) / chunk_pages;
+    if (chunk >= n_chunks_seq) return;
+    chunk_pages = ((n_pages_seq + n_chunks_seq - 1) / n_chunks_seq + ATT_WAVES - 1) / ATT_WAVES * ATT_WAVES;
     const int page0 = chunk * chunk_pages;
     if (page0 >= n_pages_seq) return;
     int page_end = page0 + chunk_pages;
