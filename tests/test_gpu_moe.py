@@ -26,13 +26,17 @@ def _run(cfg, ctx_list, k, seed):
     w_or = si.weights_for_oracle(cfg, weights)
     ctx_len = np.array(ctx_list, dtype=np.int64)
     kv = si.make_logical_kv(cfg, ctx_len, seed=seed)
-    kv_or = si.kv_for_oracle(kv)
+    kv8 = cfg.get("kv_dtype") == "fp8_e4m3"               # 8-bit cache: codes under the synthetic scales
+    scales = si.kv_scales(cfg, seed=seed) if kv8 else None
+    kv_or = si.kv_for_oracle(kv, scales)
     rng = np.random.default_rng(seed)
     n_pages = sum(-(-(int(c) + k + 1) // si.PAGE_SIZE) for c in ctx_len) + 16
     order = rng.permutation(n_pages)
     sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=B, max_ctx_len=int(ctx_len.max()) + 64,
                          n_pages=n_pages)
-    sess.pool.fill_(float("nan"))
+    sess.pool.fill_(0x7F if kv8 else float("nan"))
+    if kv8:
+        sess.set_scales(*scales)
     at = 0
     for b in range(B):
         need = -(-int(ctx_len[b]) // si.PAGE_SIZE)
@@ -43,7 +47,7 @@ def _run(cfg, ctx_list, k, seed):
             sess.write_logical_kv(l, pages, kv[l][b][0], kv[l][b][1])
     tokens = rng.integers(0, cfg["vocab"], size=(B, k + 1)).astype(np.int32)
     log = []
-    want, _ = of.verify_forward(cfg, w_or, kv_or, tokens, ctx_len, route_log=log)
+    want, _ = of.verify_forward(cfg, w_or, kv_or, tokens, ctx_len, route_log=log, kv_scales=scales)
     got = sess.forward(torch.arange(B, dtype=torch.int32, device="cuda"), torch.from_numpy(tokens).cuda())
     torch.cuda.synchronize()
     got = got.cpu().numpy()
@@ -95,3 +99,13 @@ def test_moe_shapes(B, k, changes):
     print("moe B=%d k=%d %s: max abs err %.3e on %d rows, %d exempted; max rows/expert %d, idle experts %d" %
           (B, k, changes, max_err, n_rows - n_exempt, n_exempt, loads[0].max(), (loads[0] == 0).sum()))
     assert n_exempt <= max(2, n_rows // 4)
+
+
+def test_small_moe_with_the_8bit_cache():
+    """The mixture-of-experts forward over the E4M3 cache (64 query rows per kv head: the 4-row-block attention)."""
+    wl = si.WORKLOADS["small_moe_b6_k3"]
+    cfg = dict(si.MODELS[wl["model"]], kv_dtype="fp8_e4m3")
+    ctx = [int(c) for c in si.make_batch(wl)["ctx_len"]]
+    max_err, n_exempt, n_rows, loads = _run(cfg, ctx, wl["k"], seed=12)
+    print("small moe, 8-bit cache: max abs err %.3e on %d rows, %d exempted" % (max_err, n_rows - n_exempt, n_exempt))
+    assert n_exempt <= n_rows // 4
