@@ -63,7 +63,11 @@ const char* spec_last_error(void);
  * E4M3 codes (1-4-3 bits, bias 7, no infinities, largest magnitude 448) of x / scale, rounded to nearest even and
  * saturated, with one fp32 scale per (layer, kv head) for keys and one for values (spec_kv_set_scales); attention
  * reads code * scale.  As with the other storage types the k+1 new positions are encoded before any row attends
- * to them. */
+ * to them.
+ * w_dtype = SPEC_FP8_E4M3 (bf16, dense, untied head, no hidden-state input): the matrices wq .. wd and head are
+ * E4M3 codes [out_features, in_features], one byte each, with one fp32 scale per output row (W[n][k] = code * scale[n]);
+ * embed and the norm gains stay `dtype`.  The kernels widen the codes to bf16 in registers (exact) and apply the
+ * scale to the accumulated output, so the arithmetic is that of the bf16 path on the dequantised matrix. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
     float rope_theta, rms_eps;
@@ -72,6 +76,7 @@ typedef struct {
     int32_t n_experts, top_k, expert_ffn_dim;   /* 0, 0, 0: dense feed-forward of width ffn_dim */
     int32_t fuse_hidden;       /* 1: a draft model whose input also takes hidden states (bf16, dense, ffn_dim >= 2 d_model) */
     int32_t kv_dtype;          /* 0: the cache stores `dtype`; SPEC_FP8_E4M3: 8-bit cache with scales (bf16 models) */
+    int32_t w_dtype;           /* 0: the matrices are `dtype`; SPEC_FP8_E4M3: 8-bit matrices with one scale per output row */
 } spec_model_desc;
 
 typedef struct spec_model spec_model;
@@ -79,7 +84,8 @@ typedef struct spec_kv spec_kv;
 typedef struct spec_graph spec_graph;
 
 /* Number of weight pointers spec_model_create expects:
- * 1 + (9 + (n_experts ? 1 : 0))*n_layers + 1 + (tied_head ? 0 : 1) + (fuse_hidden ? 3 : 0). */
+ * 1 + (9 + (n_experts ? 1 : 0))*n_layers + 1 + (tied_head ? 0 : 1) + (fuse_hidden ? 3 : 0)
+ * + (w_dtype == SPEC_FP8_E4M3 ? 7*n_layers + 1 : 0). */
 int32_t spec_model_weight_count(const spec_model_desc* desc);
 
 /*
@@ -90,7 +96,9 @@ int32_t spec_model_weight_count(const spec_model_desc* desc);
  *              with n_experts > 0 instead: wg [E, Fe, d], wu [E, Fe, d], wd [E, d, Fe] (the experts stacked,
  *              Fe = expert_ffn_dim), then router [E, d];
  *   final_norm [d]; head [vocab, d] unless tied_head;
- *   with fuse_hidden: w_fuse [d, 2d] (columns 0..d-1 meet the embedding half), fuse_e_norm [d], fuse_h_norm [d].
+ *   with fuse_hidden: w_fuse [d, 2d] (columns 0..d-1 meet the embedding half), fuse_e_norm [d], fuse_h_norm [d];
+ *   with w_dtype = SPEC_FP8_E4M3, after all of the above: the fp32 scales [out_features] of wq, wk, wv, wo, wg, wu, wd
+ *   of layer 0, then of layer 1, ..., then of head (the matrices themselves then hold codes, 8-byte aligned).
  * SPEC_F32: the pointers are borrowed for the model's lifetime (kernels read them in place).
  * SPEC_BF16: the matrices are re-tiled once into a library-owned device buffer laid out for the
  * MFMA kernels (one hipMalloc of about the model's size); afterwards only embed and the norm

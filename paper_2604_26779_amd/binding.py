@@ -41,7 +41,7 @@ class spec_model_desc(ctypes.Structure):
                                               "ffn_dim", "vocab")] + \
                [("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("dtype", ctypes.c_int32),
                 ("tied_head", ctypes.c_int32), ("n_experts", ctypes.c_int32), ("top_k", ctypes.c_int32),
-                ("expert_ffn_dim", ctypes.c_int32), ("fuse_hidden", ctypes.c_int32), ("kv_dtype", ctypes.c_int32)]
+                ("expert_ffn_dim", ctypes.c_int32), ("fuse_hidden", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("w_dtype", ctypes.c_int32)]
 
 
 _lib = None
@@ -149,6 +149,7 @@ def make_desc(cfg):
     d.n_experts, d.top_k, d.expert_ffn_dim = (int(cfg.get(n, 0)) for n in ("n_experts", "top_k", "expert_ffn_dim"))
     d.fuse_hidden = int(cfg.get("fuse_hidden", 0))
     d.kv_dtype = {None: 0, "fp8_e4m3": SPEC_FP8_E4M3}[cfg.get("kv_dtype")]
+    d.w_dtype = {None: 0, "fp8_e4m3": SPEC_FP8_E4M3}[cfg.get("w_dtype")]
     return d
 
 

@@ -125,7 +125,8 @@ extern "C" int32_t spec_tune_get(const char* name)
 extern "C" int32_t spec_model_weight_count(const spec_model_desc* d)
 {
     if (!d || d->n_layers < 0) return -1;
-    return 1 + (9 + (d->n_experts > 0 ? 1 : 0)) * d->n_layers + 1 + (d->tied_head ? 0 : 1) + (d->fuse_hidden ? 3 : 0);
+    return 1 + (9 + (d->n_experts > 0 ? 1 : 0)) * d->n_layers + 1 + (d->tied_head ? 0 : 1) + (d->fuse_hidden ? 3 : 0) +
+           (d->w_dtype == SPEC_FP8_E4M3 ? 7 * d->n_layers + 1 : 0);
 }
 
 static spec_status check_desc(const spec_model_desc& d)
@@ -147,6 +148,10 @@ static spec_status check_desc(const spec_model_desc& d)
     }
     if (d.kv_dtype != 0 && !(d.kv_dtype == SPEC_FP8_E4M3 && d.dtype == SPEC_BF16)) {
         set_error("spec_model_create: kv_dtype must be 0 or SPEC_FP8_E4M3 (bf16 models only)");
+        return SPEC_EUNSUPPORTED;
+    }
+    if (d.w_dtype != 0 && !(d.w_dtype == SPEC_FP8_E4M3 && d.dtype == SPEC_BF16 && d.n_experts == 0 && !d.fuse_hidden && !d.tied_head)) {
+        set_error("spec_model_create: w_dtype must be 0 or SPEC_FP8_E4M3 (bf16, dense, untied head, no hidden-state input)");
         return SPEC_EUNSUPPORTED;
     }
     if (d.fuse_hidden) {
@@ -184,7 +189,43 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
     m->w.assign(dev_weights, dev_weights + n_weights);
     SPEC_HIP_TRY(hipGetDevice(&m->device));
 
-    if (desc->dtype == SPEC_BF16) {
+    if (desc->dtype == SPEC_BF16 && desc->w_dtype == SPEC_FP8_E4M3) {
+        // 8-bit weights: codes and scales re-tiled into one arena, matrix by matrix
+        const spec_model_desc& d = *desc;
+        const int L = d.n_layers, D = d.d_model, F = d.ffn_dim;
+        const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim;
+        m->arena_bytes = (size_t)L * (w8_packed_bytes(nq + 2 * nkv, D) + w8_packed_bytes(D, nq) + w8_packed_bytes(2 * F, D) + w8_packed_bytes(D, F)) +
+                         w8_packed_bytes(d.vocab, D);
+        hipError_t e = hipMalloc(&m->arena, m->arena_bytes);
+        if (e != hipSuccess) {
+            set_error("spec_model_create: hipMalloc of %zu bytes for the tiled weights failed: %s", m->arena_bytes, hipGetErrorString(e));
+            delete m;
+            return SPEC_ENOMEM;
+        }
+        char* at = (char*)m->arena;
+        m->wqkv.resize(L); m->wo.resize(L); m->wgu.resize(L); m->wd.resize(L); m->router.resize(L);
+        auto pack8 = [&](std::initializer_list<const void*> parts, std::initializer_list<const float*> scales, std::initializer_list<int> rows,
+                         int K, PackedW* pw, bool interleave = false) -> spec_status {
+            std::vector<const unsigned char*> p;
+            for (auto q : parts) p.push_back((const unsigned char*)q);
+            std::vector<const float*> sc(scales);
+            std::vector<int> r(rows);
+            int N = 0;
+            for (int x : r) N += x;
+            spec_status s2 = w8_pack_matrix(p.data(), sc.data(), r.data(), (int)p.size(), K, at, pw, interleave, nullptr);
+            at += w8_packed_bytes(N, K);
+            return s2;
+        };
+        for (int l = 0; l < L && st == SPEC_OK; ++l) {
+            st = pack8({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {m->w_scale(l, 0), m->w_scale(l, 1), m->w_scale(l, 2)}, {nq, nkv, nkv}, D, &m->wqkv[l]);
+            if (st == SPEC_OK) st = pack8({m->layer_w(l, 4)}, {m->w_scale(l, 3)}, {D}, nq, &m->wo[l]);
+            if (st == SPEC_OK) st = pack8({m->layer_w(l, 6), m->layer_w(l, 7)}, {m->w_scale(l, 4), m->w_scale(l, 5)}, {F, F}, D, &m->wgu[l], true);
+            if (st == SPEC_OK) st = pack8({m->layer_w(l, 8)}, {m->w_scale(l, 6)}, {D}, F, &m->wd[l]);
+        }
+        if (st == SPEC_OK) st = pack8({m->head_w()}, {m->head_scale()}, {d.vocab}, D, &m->head);
+        if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }
+        if (st != SPEC_OK) { (void)hipFree(m->arena); delete m; return st; }
+    } else if (desc->dtype == SPEC_BF16) {
         const spec_model_desc& d = *desc;
         int L = d.n_layers, D = d.d_model, F = d.ffn_dim;
         int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim;

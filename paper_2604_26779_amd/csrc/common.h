@@ -69,6 +69,8 @@ struct PackedW {
     int32_t N = 0, K = 0;          // logical sizes
     int32_t n_blocks = 0;          // ceil(N / 32)
     int32_t k_steps = 0;           // K / 16
+    int32_t w8 = 0;                // 1: E4M3 codes, two k-steps per 16-byte word; scale = per-column factors, tiled order
+    const float* scale = nullptr;
 };
 
 }  // namespace specv
@@ -92,6 +94,10 @@ struct spec_model {
     const void* head_w() const { return desc.tied_head ? w[0] : w[2 + per_layer() * desc.n_layers]; }
     // fuse_hidden: w_fuse, fuse_e_norm, fuse_h_norm follow the head
     const void* fuse_w(int i) const { return w[2 + per_layer() * desc.n_layers + (desc.tied_head ? 0 : 1) + i]; }
+    // 8-bit weights (dense, untied head): the scales follow everything else, 7 per layer in matrix order
+    // (wq wk wv wo wg wu wd), then the head's
+    const float* w_scale(int l, int i) const { return (const float*)w[3 + per_layer() * desc.n_layers + 7 * l + i]; }
+    const float* head_scale() const { return (const float*)w[3 + per_layer() * desc.n_layers + 7 * desc.n_layers]; }
 };
 
 struct spec_kv {
@@ -148,6 +154,9 @@ spec_status f32_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t*
 size_t bf16_packed_elems(int N, int K);
 spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_rows, int n_parts, int K,
                              bf16_t* dev_out, PackedW* out, bool interleave, hipStream_t s);
+size_t w8_packed_bytes(int N, int K);
+spec_status w8_pack_matrix(const unsigned char* const* dev_parts, const float* const* dev_scales, const int* part_rows, int n_parts,
+                           int K, void* dev_out, PackedW* out, bool interleave, hipStream_t s);
 size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k);
 spec_status bf16_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids,
                          const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits, float* dev_hidden_out,

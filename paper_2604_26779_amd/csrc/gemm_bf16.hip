@@ -100,6 +100,84 @@ spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_row
     return SPEC_OK;
 }
 
+// 8-bit weights (E4M3 codes, one fp32 scale per output row): the same tiling with two k-steps per 16-byte word,
+// [k_steps / KS][n_blocks][KS / 2][64 lanes][2 fragments of 8 codes], and the scales in tiled column order.
+struct PackParts8 { const unsigned char* ptr[4]; const float* scale[4]; int row_end[4]; int n; int interleave; };
+
+__device__ inline bool pack8_source(const PackParts8& parts, int nb, int col, int N, int* part, int* row)
+{
+    if (parts.interleave) {
+        *part = nb & 1;
+        *row = (nb >> 1) * 32 + col;
+        return *row < parts.row_end[0];
+    }
+    const int n = nb * 32 + col;
+    if (n >= N) return false;
+    int start = 0;
+    for (int p = 0; p < parts.n; ++p) {
+        if (n < parts.row_end[p]) { *part = p; *row = n - start; return true; }
+        start = parts.row_end[p];
+    }
+    return false;
+}
+
+__global__ void pack_w8_kernel(PackParts8 parts, int N, int K, int64_t total, uint4* __restrict__ out, float* __restrict__ scale_out)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte word (two fragments) per thread
+    const int n_blocks = (N + 31) / 32;
+    if (idx < (int64_t)n_blocks * 32) {                                // the scales, tiled column order; padding columns 0
+        int part, row;
+        scale_out[idx] = pack8_source(parts, (int)(idx >> 5), (int)(idx & 31), N, &part, &row) ? parts.scale[part][row] : 0.f;
+    }
+    if (idx >= total) return;
+    const int lane = (int)(idx & 63);
+    const int64_t frag2 = idx >> 6;                                    // (slab * n_blocks + nb) * (KS / 2) + pair
+    const int pair = (int)(frag2 % (GEMM_KS / 2));
+    const int nb = (int)((frag2 / (GEMM_KS / 2)) % n_blocks);
+    const int ks = (int)(frag2 / (GEMM_KS / 2) / n_blocks) * GEMM_KS + 2 * pair;
+    const int k0 = ks * 16 + (lane >> 5) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    int part, row;
+    if (pack8_source(parts, nb, lane & 31, N, &part, &row)) {
+        const unsigned char* src = parts.ptr[part] + (int64_t)row * K + k0;
+        const uint2 a = *(const uint2*)src, b = *(const uint2*)(src + 16);
+        v = make_uint4(a.x, a.y, b.x, b.y);
+    }
+    out[idx] = v;
+}
+
+size_t w8_packed_bytes(int N, int K) { return align_up((size_t)cdiv(N, 32) * 32 * ((size_t)K + sizeof(float)), 256); }
+
+// dev_out: w8_packed_bytes(N, K) bytes: the tiled codes, then the tiled scales
+spec_status w8_pack_matrix(const unsigned char* const* dev_parts, const float* const* dev_scales, const int* part_rows, int n_parts,
+                           int K, void* dev_out, PackedW* out, bool interleave, hipStream_t s)
+{
+    if (n_parts < 1 || n_parts > 4 || K % (16 * GEMM_KUNIT)) { set_error("w8_pack_matrix: bad shape"); return SPEC_EINVAL; }
+    PackParts8 pp;
+    pp.n = n_parts;
+    pp.interleave = interleave ? 1 : 0;
+    if (interleave && (n_parts != 2 || part_rows[0] != part_rows[1] || part_rows[0] % 32)) { set_error("w8_pack_matrix: interleaving needs two equal parts of a multiple of 32 rows"); return SPEC_EINVAL; }
+    int N = 0;
+    for (int i = 0; i < n_parts; ++i) {
+        if (((uintptr_t)dev_parts[i] & 7) != 0 || ((uintptr_t)dev_scales[i] & 3) != 0) { set_error("8-bit weights must be 8-byte aligned"); return SPEC_EINVAL; }
+        N += part_rows[i];
+        pp.ptr[i] = dev_parts[i];
+        pp.scale[i] = dev_scales[i];
+        pp.row_end[i] = N;
+    }
+    out->data = (const bf16_t*)dev_out;
+    out->N = N;
+    out->K = K;
+    out->n_blocks = (int)cdiv(N, 32);
+    out->k_steps = K / 16;
+    out->w8 = 1;
+    out->scale = (const float*)((const char*)dev_out + (size_t)out->n_blocks * 32 * K);
+    int64_t total = (int64_t)out->n_blocks * (out->k_steps / 2) * 64;
+    pack_w8_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(pp, N, K, total, (uint4*)dev_out, (float*)out->scale);
+    SPEC_LAUNCH_CHECK("pack_w8_kernel");
+    return SPEC_OK;
+}
+
 // ------------------------------------------------------------------ the GEMM
 // s_waitcnt operand: at most n vector-memory operations outstanding, the other counters not waited for
 constexpr int vmcnt_imm(int n) { return (n & 15) | 0x70 | 0xF00 | ((n >> 4) << 14); }
@@ -117,13 +195,18 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | 0x70 | 0xF00 | ((n >> 4) << 1
 // tile: a wavefront then owns 3-4 x 4 accumulator blocks (192-256 accumulation registers, one workgroup per CU) and
 // every fragment it fetches feeds 4 (weights: 6-8) MFMAs, which halves the LDS and vector-memory traffic per MFMA
 // that bounds the 128 x 128 tile.  Its two LDS slabs (96-128 KiB) are dynamic shared memory.
-template <int MB, int WM, int WD, int EPI, bool GROUPED = false, int NBW_T = WM>
+// W8: the weights are E4M3 codes, two k-steps per 16-byte word (half the weight bytes and load instructions); a
+// fragment is widened to bf16 in registers right before its MFMAs (exact) and the output column's scale is applied to
+// the accumulators in the epilogue.
+template <int MB, int WM, int WD, int EPI, bool GROUPED = false, int NBW_T = WM, bool W8 = false>
 __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kernel(
     const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
     int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride,
-    const int32_t* __restrict__ tiles = nullptr, int64_t w_group_stride = 0)
+    const int32_t* __restrict__ tiles = nullptr, int64_t w_group_stride = 0, const float* __restrict__ wscale = nullptr)
 {
     constexpr int KS = GEMM_KS;
+    constexpr int KSW = W8 ? KS / 2 : KS;               // 16-byte words of one column block per lane and slab
+    static_assert(!(W8 && GROUPED), "the grouped GEMM has no 8-bit variant");
     constexpr int MBW = MB / WM, NBW = NBW_T;
     constexpr int TILE_NB = (4 / WM) * NBW;             // 32-column blocks per workgroup tile
     constexpr bool BIG = MB >= 6;
@@ -169,8 +252,8 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
     const u32x4_t* wptr[NBW];
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
-        wptr[j] = Wp + (((int64_t)(ks0 / KS) * n_blocks + (nb0 + j < n_blocks ? nb0 + j : 0)) * KS) * 64 + lane;
-    const int64_t wslab = (int64_t)n_blocks * KS * 64;
+        wptr[j] = Wp + (((int64_t)(ks0 / KS) * n_blocks + (nb0 + j < n_blocks ? nb0 + j : 0)) * KSW) * 64 + lane;
+    const int64_t wslab = (int64_t)n_blocks * KSW * 64;
     const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mblk0) * 128;
 
     f32x16_t acc[MBW][NBW];
@@ -183,7 +266,7 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 
     // the weight stream runs WD slabs ahead of the MFMAs: a register ring, each entry refilled
     // right after its last use
-    u32x4_t w[WD][KS][NBW], xr[XPT];
+    u32x4_t w[WD][KSW][NBW], xr[XPT];
 
     auto load_x = [&](int slab) {
 #pragma unroll
@@ -250,6 +333,19 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
+            u32x4_t wk[NBW];                             // this k-step's weight fragments as bf16
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) {
+                if constexpr (W8) {
+                    const unsigned int wa = w[SLOT][kk >> 1][j][(kk & 1) * 2], wb = w[SLOT][kk >> 1][j][(kk & 1) * 2 + 1];
+                    wk[j] = u32x4_t{__builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wa, 1.0f, false)),
+                                    __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wa, 1.0f, true)),
+                                    __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wb, 1.0f, false)),
+                                    __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wb, 1.0f, true))};
+                } else {
+                    wk[j] = w[SLOT][kk][j];
+                }
+            }
             // hi products of all blocks first, then the lo products: two MFMAs on one accumulator are never adjacent
 #pragma unroll
             for (int part = 0; part < 2; ++part)
@@ -258,9 +354,12 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 #pragma unroll
                     for (int j = 0; j < NBW; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[kk & 1][i][part]),
-                                                                            __builtin_bit_cast(bf16x8_t, w[SLOT][kk][j]), acc[i][j], 0, 0, 0);
+                                                                            __builtin_bit_cast(bf16x8_t, wk[j]), acc[i][j], 0, 0, 0);
+            if (!W8 || (kk & 1)) {                       // (8-bit: a word serves two k-steps and is refilled after the second)
 #pragma unroll
-            for (int j = 0; j < NBW; ++j) w[SLOT][kk][j] = __builtin_nontemporal_load(wptr[j] + (int64_t)s_w * wslab + kk * 64);
+                for (int j = 0; j < NBW; ++j)
+                    w[SLOT][W8 ? kk >> 1 : kk][j] = __builtin_nontemporal_load(wptr[j] + (int64_t)s_w * wslab + (W8 ? kk >> 1 : kk) * 64);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         // ... and the weight loads of this slab stay above the LDS stores, so that waiting for the (older)
@@ -269,10 +368,10 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
         if constexpr (BIG) {
             __syncthreads();
         } else {
-            // Wait for the transfers into LDS only: the slab's own weight reloads (KS * NBW of them) were issued later
+            // Wait for the transfers into LDS only: the slab's own weight reloads (KSW * NBW of them) were issued later
             // and stay in flight (__syncthreads would drain the whole queue).  No wavefront reads the other buffer
             // before this barrier, and all have finished reading this one when they pass the next.
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(KS * NBW));
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(KSW * NBW));
             __builtin_amdgcn_s_barrier();
         }
         buf ^= 1;
@@ -284,7 +383,7 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
         for (int d = 0; d < WD; ++d) {
             const int sd = d < n_slabs ? d : n_slabs - 1;
 #pragma unroll
-            for (int i = 0; i < KS; ++i)
+            for (int i = 0; i < KSW; ++i)
 #pragma unroll
                 for (int j = 0; j < NBW; ++j) w[d][i][j] = __builtin_nontemporal_load(wptr[j] + (int64_t)sd * wslab + i * 64);
         }
@@ -322,6 +421,10 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             float g = acc[i][2 * cg][r], u = acc[i][2 * cg + 1][r];
+                            if constexpr (W8) {
+                                g *= wscale[(nb0 + 2 * cg) * 32 + (lane & 31)];
+                                u *= wscale[(nb0 + 2 * cg + 1) * 32 + (lane & 31)];
+                            }
                             int row = i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                             tile[row * 129 + (np * 2 + cg) * 32 + (lane & 31)] = g / (1.0f + __expf(-g)) * u;
                         }
@@ -351,6 +454,10 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 float g = acc[i][0][r], u = acc[i][NBW - 1][r];
+                if constexpr (W8) {
+                    g *= wscale[nb0 * 32 + (lane & 31)];
+                    u *= wscale[(nb0 + NBW - 1) * 32 + (lane & 31)];
+                }
                 int row = (mh * MBW + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 tile[row * 65 + np * 32 + (lane & 31)] = g / (1.0f + __expf(-g)) * u;
             }
@@ -372,12 +479,13 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
     for (int j = 0; j < NBW; ++j) {
         const int n = (nb0 + j) * 32 + (lane & 31);
         if (nb0 + j >= n_blocks || n >= N) continue;
+        const float sc = W8 ? wscale[n] : 1.0f;
 #pragma unroll
         for (int i = 0; i < MBW; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int m = (mblk0 + mh * MBW + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (m < M) o[(int64_t)m * ldo + n] = acc[i][j][r];
+                if (m < M) o[(int64_t)m * ldo + n] = W8 ? acc[i][j][r] * sc : acc[i][j][r];
             }
     }
 }
@@ -457,10 +565,11 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
     const u32x4_t* wp = (const u32x4_t*)W.data;
     const u32x4_t* xp = (const u32x4_t*)Xp;
     if (swiglu && !gemm_can_fuse_swiglu(W, M, splits)) { set_error("gemm: SwiGLU cannot be fused for this shape"); return SPEC_EUNSUPPORTED; }
-#define SPEC_GEMM_LAUNCH(MBV, WMV, WDV, E) gemm_bf16_kernel<MBV, WMV, WDV, E><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride)
+#define SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, W8V) gemm_bf16_kernel<MBV, WMV, WDV, E, false, WMV, W8V><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
+#define SPEC_GEMM_LAUNCH(MBV, WMV, WDV, E) do { if (W.w8) SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, true); else SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, false); } while (0)
     // the 256-column tile: two LDS slabs of MB * 8 KiB as dynamic shared memory (beyond the 64 KiB a kernel gets by default)
-#define SPEC_GEMM_LAUNCH_BIG(MBV, E) do { \
-        auto kern = gemm_bf16_kernel<MBV, 2, 1, E, false, 4>; \
+#define SPEC_GEMM_LAUNCH_BIG_W(MBV, E, W8V) do { \
+        auto kern = gemm_bf16_kernel<MBV, 2, 1, E, false, 4, W8V>; \
         constexpr int lds_bytes = 2 * GEMM_KS * MBV * 128 * 16; \
         static bool raised = false; \
         if (!raised) { \
@@ -468,8 +577,9 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
             if (e != hipSuccess) { set_error("gemm: cannot reserve %d bytes of LDS: %s", lds_bytes, hipGetErrorString(e)); return SPEC_EHIP; } \
             raised = true; \
         } \
-        kern<<<grid, GEMM_THREADS, lds_bytes, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0); \
+        kern<<<grid, GEMM_THREADS, lds_bytes, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale); \
     } while (0)
+#define SPEC_GEMM_LAUNCH_BIG(MBV, E) do { if (W.w8) SPEC_GEMM_LAUNCH_BIG_W(MBV, E, true); else SPEC_GEMM_LAUNCH_BIG_W(MBV, E, false); } while (0)
     switch (mb) {
         case 1: SPEC_GEMM_LAUNCH(1, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
         case 2: if (swiglu) SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_PLAIN); break;
@@ -479,7 +589,9 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
         default: if (swiglu) SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_PLAIN); break;
     }
 #undef SPEC_GEMM_LAUNCH_BIG
+#undef SPEC_GEMM_LAUNCH_BIG_W
 #undef SPEC_GEMM_LAUNCH
+#undef SPEC_GEMM_LAUNCH_W
     SPEC_LAUNCH_CHECK("gemm_bf16_kernel");
     return SPEC_OK;
 }

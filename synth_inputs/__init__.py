@@ -99,8 +99,13 @@ for _k in (1, 3, 5, 7):
 # (layer, kv head).  With one byte per element the B=256 cache of 32 distinct layers (155 GB) fits one GPU un-aliased.
 for _name in ("small_bf16", "llama8b_bf16"):
     MODELS[_name + "_kv8"] = dict(MODELS[_name], kv_dtype="fp8_e4m3")
+    MODELS[_name + "_w8kv8"] = dict(MODELS[_name], kv_dtype="fp8_e4m3", w_dtype="fp8_e4m3")     # 8-bit matrices as well
+    MODELS[_name + "_w8"] = dict(MODELS[_name], w_dtype="fp8_e4m3")
 WORKLOADS["small_bf16_kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_kv8")
 WORKLOADS["llama8b_kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_kv8")
+WORKLOADS["small_bf16_w8kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_w8kv8")
+WORKLOADS["llama8b_w8kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8kv8")
+WORKLOADS["llama8b_w8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8")
 WORKLOADS["llama8b_kv8_b256_ctx2k-16k_k3"] = dict(WORKLOADS["llama8b_b256_ctx2k-16k_k3"], model="llama8b_bf16_kv8",
                                                   layer_alias_mod=0)
 
@@ -149,13 +154,30 @@ def make_weights(cfg, seed=DEFAULT_SEED, device="cpu", std=0.02):
             weights[name] = (torch.randn(shape, generator=g, device=device, dtype=torch.float32) / math.sqrt(shape[-1])).to(dt)
         else:
             weights[name] = (torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std).to(dt)
+    if cfg.get("w_dtype") == "fp8_e4m3":
+        # 8-bit matrices: the bf16 draws above become E4M3 codes under one scale per output row (absmax / 448, the
+        # library's cast); the scales follow all other entries, in matrix order
+        scales = {}
+        for name in [n for n in weights if n.split(".")[-1] in W8_MATRICES]:
+            w = weights[name].to(torch.float32)
+            sc = (w.abs().amax(dim=1) / 448.0).clamp_min(1e-12)
+            weights[name] = (w / sc[:, None]).to(torch.float8_e4m3fn)
+            scales[name + ".scale"] = sc
+            del w
+        weights.update(scales)
     return weights
+
+
+W8_MATRICES = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "head")
 
 
 def weights_for_oracle(cfg, weights):
     """The same values as nested fp32 numpy arrays in the layout the oracle's forward takes."""
     def f(name):
-        return weights[name].detach().to("cpu", torch.float32).numpy()
+        w = weights[name].detach().to("cpu", torch.float32)
+        if name + ".scale" in weights:                # 8-bit matrix: code * scale of its row
+            w = w * weights[name + ".scale"].detach().to("cpu", torch.float32)[:, None]
+        return w.numpy()
     layers = []
     names = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd") + (("router",) if cfg.get("n_experts", 0) > 0 else ())
     for l in range(cfg["n_layers"]):

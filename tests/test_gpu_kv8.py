@@ -175,3 +175,47 @@ def test_kv8_every_code_is_read_exactly():
     print("8-bit cache, all codes: logits max abs err %.3e" % max_err)
     assert ok, (max_err, worst)
     sess.close()
+
+
+# ------------------------------------------------------------------------------------------ 8-bit matrices
+W8 = dict(w_dtype="fp8_e4m3")
+
+
+@pytest.mark.parametrize("B,k,kv8", [(1, 0, False), (1, 7, True), (16, 3, True), (24, 3, False), (40, 3, True), (33, 7, False), (9, 2, True)])
+def test_w8_row_block_counts(B, k, kv8):
+    """E4M3 matrices with one scale per output row (the codes are inputs, the oracle multiplies by the dequantised
+    matrix): M = 1 .. 264 rows, i.e. every row-block count of the 128-column tile (fused and unfused SwiGLU, K split
+    and unsplit), more than one row tile, ragged column counts (vocabulary 1000), with either cache type."""
+    rng = np.random.default_rng(B * 10 + k)
+    ctx = [int(c) for c in rng.integers(3, 200, size=B)]
+    ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000, kv8=kv8, **W8)
+    print("8-bit matrices, B=%d k=%d (M=%d), 8-bit cache %s: logits max abs err %.3e" % (B, k, B * (k + 1), kv8, max_err))
+    assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("B,k,big_from", [(64, 3, 8), (33, 7, 8), (12, 15, 6), (96, 3, 8)])
+def test_w8_large_row_tiles(B, k, big_from):
+    """The 192- and 256-row x 256-column tiles with 8-bit matrices (plain and fused SwiGLU epilogues, split K)."""
+    from paper_2604_26779_amd import binding as sv
+    before = sv.spec_tune_get("gemm_big_min_blocks")
+    sv.spec_tune_set("gemm_big_min_blocks", big_from)
+    try:
+        rng = np.random.default_rng(B * 10 + k)
+        ctx = [int(c) for c in rng.integers(3, 120, size=B)]
+        ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000, kv8=True, **W8)
+    finally:
+        sv.spec_tune_set("gemm_big_min_blocks", before)
+    print("8-bit matrices, B=%d k=%d (M=%d), big tiles from %d row blocks: logits max abs err %.3e" % (B, k, B * (k + 1), big_from, max_err))
+    assert ok, (max_err, worst)
+
+
+def test_w8_description_checks():
+    """8-bit matrices are refused where the kernels have no path for them, with an error and nothing launched."""
+    from paper_2604_26779_amd import binding as sv
+    for changes in (dict(tied_head=1), dict(dtype="f32", head_dim=64)):
+        cfg = dict(si.MODELS["small_bf16_w8"], **changes)
+        desc = sv.make_desc(cfg)
+        n = sv.lib().spec_model_weight_count(__import__("ctypes").byref(desc))
+        dummy = [torch.zeros(64, dtype=torch.uint8, device="cuda")] * n
+        with pytest.raises(sv.SpecError):
+            sv.spec_model_create(cfg, dummy)
