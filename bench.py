@@ -318,7 +318,8 @@ def main():
         "dtype": wl.cfg["dtype"], "data": "synthetic",
         "config": {"workload": args.workload, "B": B, "k": k, "ctx_tokens": int(wl.ctx_len.sum()),
                    "model": wl.wl["model"], "page_size": 16, "pages": "shuffled",
-                   "kv_cache": "fp8_e4m3 codes, one scale per (layer, kv head)" if wl.cfg.get("kv_dtype") else wl.cfg["dtype"]},
+                   "kv_cache": "fp8_e4m3 codes, one scale per (layer, kv head)" if wl.cfg.get("kv_dtype") else wl.cfg["dtype"],
+                   "matrices": "fp8_e4m3 codes, one scale per output row" if wl.cfg.get("w_dtype") else wl.cfg["dtype"]},
         "verify_steps_per_s": round(1e3 / ms_per_step, 2),
         "mean_acceptance_length": round(produced / (K * B), 3),
         "accepted_draft_tokens_per_s": round(accepted_drafts / (ms_per_step * K / 1e3), 1),
@@ -393,7 +394,7 @@ def main():
                                 "draft_kernel_us": round(1e3 * e0.elapsed_time(e1) / 20, 2),
                                 "rows_with_an_occurrence": int((roll.n_drafted > 0).sum().item()),
                                 "mean_acceptance_length": round(float((acc_s + 1).sum().item()) / (S * B), 3)}
-    if wl.cfg.get("kv_dtype"):
+    if wl.cfg.get("kv_dtype") or wl.cfg.get("w_dtype"):
         args.no_cpu_baseline = True                   # the oracle baseline is reported on the headline workload only
     if not args.no_cpu_baseline:
         base, _ = cpu_baseline(wl, torch, args.cpu_seqs)

@@ -254,6 +254,10 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
     for (int j = 0; j < NBW; ++j)
         wptr[j] = Wp + (((int64_t)(ks0 / KS) * n_blocks + (nb0 + j < n_blocks ? nb0 + j : 0)) * KSW) * 64 + lane;
     const int64_t wslab = (int64_t)n_blocks * KSW * 64;
+    // 8-bit weights: this lane's column scales, fetched now so that the epilogue does not wait for them
+    float wsc[NBW];
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) wsc[j] = (W8 && nb0 + j < n_blocks) ? wscale[(nb0 + j) * 32 + (lane & 31)] : 1.0f;
     const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mblk0) * 128;
 
     f32x16_t acc[MBW][NBW];
@@ -396,6 +400,12 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             __builtin_amdgcn_s_barrier();
         }
+        if constexpr (W8) {
+            // keep the scale loads up here, with the first weight loads (left alone, the compiler sinks them to their
+            // use in the epilogue, where nothing hides their latency)
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) asm volatile("" : "+v"(wsc[j]));
+        }
         for (int s = 0; s < n_slabs; s += WD) {
             slab_body(std::integral_constant<int, 0>{}, s);
             if constexpr (WD > 1) slab_body(std::integral_constant<int, 1>{}, s + 1);
@@ -422,8 +432,8 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
                         for (int r = 0; r < 16; ++r) {
                             float g = acc[i][2 * cg][r], u = acc[i][2 * cg + 1][r];
                             if constexpr (W8) {
-                                g *= wscale[(nb0 + 2 * cg) * 32 + (lane & 31)];
-                                u *= wscale[(nb0 + 2 * cg + 1) * 32 + (lane & 31)];
+                                g *= wsc[2 * cg];
+                                u *= wsc[2 * cg + 1];
                             }
                             int row = i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                             tile[row * 129 + (np * 2 + cg) * 32 + (lane & 31)] = g / (1.0f + __expf(-g)) * u;
@@ -455,8 +465,8 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
             for (int r = 0; r < 16; ++r) {
                 float g = acc[i][0][r], u = acc[i][NBW - 1][r];
                 if constexpr (W8) {
-                    g *= wscale[nb0 * 32 + (lane & 31)];
-                    u *= wscale[(nb0 + NBW - 1) * 32 + (lane & 31)];
+                    g *= wsc[0];
+                    u *= wsc[NBW - 1];
                 }
                 int row = (mh * MBW + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 tile[row * 65 + np * 32 + (lane & 31)] = g / (1.0f + __expf(-g)) * u;
@@ -479,7 +489,7 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
     for (int j = 0; j < NBW; ++j) {
         const int n = (nb0 + j) * 32 + (lane & 31);
         if (nb0 + j >= n_blocks || n >= N) continue;
-        const float sc = W8 ? wscale[n] : 1.0f;
+        const float sc = wsc[j];
 #pragma unroll
         for (int i = 0; i < MBW; ++i)
 #pragma unroll

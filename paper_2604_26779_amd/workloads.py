@@ -98,6 +98,7 @@ def algorithmic_bytes(cfg, ctx_len, B, k):
     nq, nkv = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
     eb = 2 if cfg["dtype"] == "bf16" else 4
     kvb = 1 if cfg.get("kv_dtype") == "fp8_e4m3" else eb
+    web = 1 if cfg.get("w_dtype") == "fp8_e4m3" else eb
     layer_w = (nq + 2 * nkv) * D + D * nq + 2 * F * D + D * F
     if cfg.get("n_experts", 0) > 0:          # every expert's matrices are touched once the batch is a few dozen rows
         E, Fe = cfg["n_experts"], cfg["expert_ffn_dim"]
@@ -109,9 +110,9 @@ def algorithmic_bytes(cfg, ctx_len, B, k):
     tokens = int(np.sum(ctx_len)) + B * (k + 1)
     return dict(
         gemm_flops=2.0 * (L * active_w + head_w) * B * (k + 1),
-        gemm=(L * layer_w + head_w) * eb,
-        gemm_layers=L * layer_w * eb,
-        gemm_head=head_w * eb,
+        gemm=(L * layer_w + head_w) * web,
+        gemm_layers=L * layer_w * web,
+        gemm_head=head_w * web,
         attn=tokens * 2 * nkv * kvb * L,
         sampler=B * (k + 1 + 2) * V * 4,
         logits_write=B * (k + 1) * V * 4,

@@ -114,6 +114,12 @@ def test_llama8b_8bit_cache_full_size():
     _check_workload("llama8b_kv8_b32_ctx1k-8k_k3", [3])
 
 
+def test_llama8b_8bit_matrices_and_cache_full_size():
+    """The 8B shape with E4M3 matrices (one scale per output row) and the E4M3 cache: the oracle multiplies by the
+    dequantised matrices (code * scale), the kernels widen the codes in registers."""
+    _check_workload("llama8b_w8kv8_b32_ctx1k-8k_k3", [3])
+
+
 def test_llama8b_8bit_cache_large_batch_all_layers_distinct():
     """B = 256, contexts 2048..16384: with one byte per entry the cache of 32 distinct layers (155 GB) fits one GPU,
     so no layer pools are shared here."""
