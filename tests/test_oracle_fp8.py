@@ -139,3 +139,35 @@ def test_stored_values_differ_from_unrounded_and_power_of_two_scale_is_neutral()
     _, kv4 = of.verify_forward(CFG, w, [[(K, V) for K, V in layer] for layer in kv], tokens, ctx_len, kv_scales=s4)
     normal = np.abs(new_kv[0][0]) >= s4[0][0][None, None, :, None] * 2.0 ** -6
     assert np.array_equal(kv4[0][0][normal], new_kv[0][0][normal])
+
+
+def test_8bit_matrices_reach_the_oracle_as_code_times_scale():
+    """The generator's 8-bit matrices (a library cast of w / scale, scale = row absmax / 448) are handed to the oracle as
+    code * scale: checked against this oracle's own decode of the same bytes, and against the draws they came from
+    (half a mantissa step; the row maximum itself is exact)."""
+    cfg = dict(si.MODELS["small_bf16_w8"])
+    w8 = si.make_weights(cfg, seed=4)
+    w16 = si.make_weights(dict(cfg, w_dtype=None), seed=4)
+    names = [n for n in w16]
+    assert list(w8)[:len(names)] == names and all(n.endswith(".scale") for n in list(w8)[len(names):])
+    w_or = si.weights_for_oracle(cfg, w8)
+    for name, key in (("l0.wq", "wq"), ("l1.wd", "wd"), ("l0.wg", "wg")):
+        codes = w8[name].view(torch.uint8).numpy()
+        scale = w8[name + ".scale"].numpy().astype(np.float64)
+        mine = fp8.decode(codes) * scale[:, None]
+        layer = int(name[1])
+        assert np.allclose(w_or["layers"][layer][key], mine, rtol=1e-6, atol=0)
+        orig = w16[name].to(torch.float64).numpy()
+        big = np.abs(orig) >= scale[:, None] * 2.0 ** -6
+        assert np.max(np.abs(mine - orig)[big] / np.abs(orig)[big]) <= 2.0 ** -4 * (1 + 1e-6)
+        assert np.allclose(np.abs(mine).max(axis=1), np.abs(orig).max(axis=1), rtol=1e-6)
+    assert np.allclose(w_or["head"], fp8.decode(w8["head"].view(torch.uint8).numpy()) * w8["head.scale"].numpy().astype(np.float64)[:, None], rtol=1e-6)
+
+
+def test_weight_count_with_8bit_matrices():
+    from paper_2604_26779_amd import binding as sv
+    import ctypes
+    for name in ("small_bf16", "small_bf16_w8", "small_bf16_w8kv8"):
+        cfg = si.MODELS[name]
+        d = sv.make_desc(cfg)
+        assert sv.lib().spec_model_weight_count(ctypes.byref(d)) == len(si.make_weights(cfg, seed=1))
