@@ -254,10 +254,9 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
     for (int j = 0; j < NBW; ++j)
         wptr[j] = Wp + (((int64_t)(ks0 / KS) * n_blocks + (nb0 + j < n_blocks ? nb0 + j : 0)) * KSW) * 64 + lane;
     const int64_t wslab = (int64_t)n_blocks * KSW * 64;
-    // 8-bit weights: this lane's column scales, fetched now so that the epilogue does not wait for them
-    float wsc[NBW];
+    float wsc[NBW];                                     // 8-bit weights: this lane's column scales
 #pragma unroll
-    for (int j = 0; j < NBW; ++j) wsc[j] = (W8 && nb0 + j < n_blocks) ? wscale[(nb0 + j) * 32 + (lane & 31)] : 1.0f;
+    for (int j = 0; j < NBW; ++j) wsc[j] = 1.0f;
     const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mblk0) * 128;
 
     f32x16_t acc[MBW][NBW];
@@ -383,6 +382,14 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 
     // n_slabs is a multiple of WD (K % (16 * GEMM_KUNIT) == 0 and split sizes are rounded to it)
     if (n_slabs > 0) {
+        if constexpr (W8) {
+            // Fetched with the first weight loads and known to have arrived (the wait below, then the empty asm that
+            // ties the values to this point) on every path into the epilogue: a load the compiler may still count as
+            // outstanding there makes it wait with vmcnt(0) before each of the 64 stores, which serialises them.
+#pragma unroll
+            for (int j = 0; j < NBW; ++j)
+                if (nb0 + j < n_blocks) wsc[j] = wscale[(nb0 + j) * 32 + (lane & 31)];
+        }
 #pragma unroll
         for (int d = 0; d < WD; ++d) {
             const int sd = d < n_slabs ? d : n_slabs - 1;
@@ -401,8 +408,6 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
             __builtin_amdgcn_s_barrier();
         }
         if constexpr (W8) {
-            // keep the scale loads up here, with the first weight loads (left alone, the compiler sinks them to their
-            // use in the epilogue, where nothing hides their latency)
 #pragma unroll
             for (int j = 0; j < NBW; ++j) asm volatile("" : "+v"(wsc[j]));
         }
