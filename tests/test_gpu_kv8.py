@@ -219,3 +219,15 @@ def test_w8_description_checks():
         dummy = [torch.zeros(64, dtype=torch.uint8, device="cuda")] * n
         with pytest.raises(sv.SpecError):
             sv.spec_model_create(cfg, dummy)
+
+
+def test_scales_are_refused_for_a_cache_that_is_not_8bit():
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = dict(si.MODELS["small_bf16"], vocab=1000)
+    weights = si.make_weights(cfg, seed=1)
+    sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=2, max_ctx_len=64, n_pages=16)
+    one = torch.ones(cfg["n_layers"] * cfg["n_kv_heads"], dtype=torch.float32, device="cuda")
+    with pytest.raises(sv.SpecError):
+        sv.spec_kv_set_scales(sess.kv, one, one)
+    sess.close()
