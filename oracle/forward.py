@@ -27,6 +27,8 @@ Conventions of this build (the paper does not state them):
     positions are rounded to that type (round to nearest even) before any row attends to them, so
     that a position's key and value are the same numbers in the step that writes them and in every
     later step - which is what makes the verified distribution the one plain decoding would use;
+  * 8-bit matrices (``matrix`` below): E4M3 codes with one fp32 scale per output row, W[n][k] = decode(code) * scale[n];
+    everything else is computed as with any other matrix;
   * an 8-bit cache (cfg["kv_dtype"] == "fp8_e4m3", see ``oracle/fp8.py``) stores encode(x / scale) with one scale
     per (layer, kv head) for keys and one for values, and attention reads decode(code) * scale.
 """
@@ -114,6 +116,14 @@ def moe_ffn(h, w, top_k, route_log=None):
     return out
 
 
+def matrix(w, key):
+    """A projection matrix of the dict w in fp64.  8-bit matrices (the dict also holds key + "_scale", one factor per
+    output row, and w[key] holds E4M3 codes as uint8): W[n][k] = decode(code[n][k]) * scale[n]."""
+    if key + "_scale" in w:
+        return fp8.decode(np.asarray(w[key], dtype=np.uint8)) * np.asarray(w[key + "_scale"], dtype=np.float64)[:, None]
+    return np.asarray(w[key], dtype=np.float64)
+
+
 def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden_in=None, return_hidden=False,
                    kv_scales=None):
     """One verify forward.
@@ -161,9 +171,9 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden
     for layer in range(cfg["n_layers"]):
         w = weights["layers"][layer]
         h = rmsnorm(x, w["attn_norm"], eps)
-        q = (h @ np.asarray(w["wq"], dtype=np.float64).T).reshape(B * T, Hq, dh)
-        kx = (h @ np.asarray(w["wk"], dtype=np.float64).T).reshape(B * T, Hkv, dh)
-        vx = (h @ np.asarray(w["wv"], dtype=np.float64).T).reshape(B * T, Hkv, dh)
+        q = (h @ matrix(w, "wq").T).reshape(B * T, Hq, dh)
+        kx = (h @ matrix(w, "wk").T).reshape(B * T, Hkv, dh)
+        vx = (h @ matrix(w, "wv").T).reshape(B * T, Hkv, dh)
         q = rope(q, pos, theta)
         if cfg.get("kv_dtype") == "fp8_e4m3":
             kx = fp8.store(rope(kx, pos, theta), np.asarray(kv_scales[0], dtype=np.float64)[layer][None, :, None])
@@ -184,18 +194,18 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden
                     g = j // group
                     s = (K_all[:visible, g, :] @ q[b * T + i, j, :]) * scale
                     attn[b * T + i, j, :] = softmax(s) @ V_all[:visible, g, :]
-        x = x + attn.reshape(B * T, Hq * dh) @ np.asarray(w["wo"], dtype=np.float64).T
+        x = x + attn.reshape(B * T, Hq * dh) @ matrix(w, "wo").T
 
         h = rmsnorm(x, w["ffn_norm"], eps)
         if cfg.get("n_experts", 0) > 0:
             x = x + moe_ffn(h, w, cfg["top_k"], route_log)
         else:
-            gate = h @ np.asarray(w["wg"], dtype=np.float64).T
-            up = h @ np.asarray(w["wu"], dtype=np.float64).T
-            x = x + (silu(gate) * up) @ np.asarray(w["wd"], dtype=np.float64).T
+            gate = h @ matrix(w, "wg").T
+            up = h @ matrix(w, "wu").T
+            x = x + (silu(gate) * up) @ matrix(w, "wd").T
 
     head = weights.get("head")
-    head = embed if head is None else np.asarray(head, dtype=np.float64)
+    head = embed if head is None else matrix(weights, "head")
     logits = rmsnorm(x, weights["final_norm"], eps) @ head.T
     if return_hidden:
         return logits.reshape(B, T, -1), new_kv, x.reshape(B, T, -1).copy()

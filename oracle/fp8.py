@@ -64,3 +64,11 @@ def store(x, scale):
     """What a cache with this scale returns for x: decode(encode(x / scale)) * scale, in fp64."""
     scale = np.asarray(scale, dtype=np.float64)
     return quantise(np.asarray(x, dtype=np.float64) / scale) * scale
+
+
+def cache_values(kv_codes, scales):
+    """kv_codes[layer][b] = (K codes, V codes), uint8 [ctx, Hkv, dh]; scales = (k_scale [L, Hkv], v_scale [L, Hkv]).
+    Returns the same nesting with what the cache returns, decode(code) * scale, in fp64."""
+    ks, vs = (np.asarray(a, dtype=np.float64) for a in scales)
+    return [[(decode(K) * ks[l][None, :, None], decode(V) * vs[l][None, :, None]) for (K, V) in per_seq]
+            for l, per_seq in enumerate(kv_codes)]

@@ -171,19 +171,31 @@ def make_weights(cfg, seed=DEFAULT_SEED, device="cpu", std=0.02):
 W8_MATRICES = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "head")
 
 
-def weights_for_oracle(cfg, weights):
-    """The same values as nested fp32 numpy arrays in the layout the oracle's forward takes."""
+def weights_for_oracle(cfg, weights, library_decode=False):
+    """The same values as nested fp32 numpy arrays in the layout the oracle's forward takes.  8-bit matrices go as
+    bytes plus scales and the oracle decodes them itself; with library_decode (the full-size shapes, where the oracle's
+    elementwise decode of 8e9 codes would take minutes) they go as the library's cast of the codes times the scale, which
+    the oracle's decode is pinned against code by code."""
     def f(name):
-        w = weights[name].detach().to("cpu", torch.float32)
-        if name + ".scale" in weights:                # 8-bit matrix: code * scale of its row
-            w = w * weights[name + ".scale"].detach().to("cpu", torch.float32)[:, None]
-        return w.numpy()
+        if name + ".scale" in weights and library_decode:
+            return (weights[name].detach().to("cpu", torch.float32) * weights[name + ".scale"].detach().to("cpu", torch.float32)[:, None]).numpy()
+        if name + ".scale" in weights:                # 8-bit matrix: the oracle gets the codes (bytes) and the scales
+            return weights[name].detach().to("cpu").view(torch.uint8).numpy()
+        return weights[name].detach().to("cpu", torch.float32).numpy()
+
+    def scales_of(prefix, keys):
+        if library_decode:
+            return {}
+        return {k + "_scale": weights[prefix + k + ".scale"].detach().to("cpu", torch.float32).numpy()
+                for k in keys if prefix + k + ".scale" in weights}
     layers = []
     names = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd") + (("router",) if cfg.get("n_experts", 0) > 0 else ())
     for l in range(cfg["n_layers"]):
         layers.append({k: f(f"l{l}.{k}") for k in names})
+        layers[-1].update(scales_of(f"l{l}.", names))
     out = {"embed": f("embed"), "layers": layers, "final_norm": f("final_norm"),
            "head": None if cfg.get("tied_head", 0) else f("head")}
+    out.update(scales_of("", ("head",)))
     if cfg.get("fuse_hidden", 0):
         out["fuse"] = {"w_fuse": f("w_fuse"), "norm_e": f("fuse_e_norm"), "norm_h": f("fuse_h_norm")}
     return out
@@ -235,15 +247,13 @@ def make_logical_kv(cfg, ctx_len, seed=DEFAULT_SEED, device="cpu"):
     return kv
 
 
-def kv_for_oracle(kv, scales=None):
-    """kv[layer][b] = (K, V) tensors -> the same nesting with fp32 numpy arrays.  With scales (k_scale, v_scale
-    [L, Hkv], an 8-bit cache whose tensors hold codes): what the cache returns, code * scale, in fp64."""
-    if scales is None:
-        return [[(K.detach().to("cpu", torch.float32).numpy(), V.detach().to("cpu", torch.float32).numpy())
-                 for (K, V) in per_seq] for per_seq in kv]
-    ks, vs = (np.asarray(a, dtype=np.float64) for a in scales)
-    return [[(K.detach().to("cpu", torch.float64).numpy() * ks[l][None, :, None], V.detach().to("cpu", torch.float64).numpy() * vs[l][None, :, None])
-             for (K, V) in per_seq] for l, per_seq in enumerate(kv)]
+def kv_for_oracle(kv):
+    """kv[layer][b] = (K, V) tensors -> the same nesting with fp32 numpy arrays (an 8-bit cache, whose tensors hold
+    codes: the bytes as uint8 arrays; the oracle turns them into values itself)."""
+    def conv(t):
+        t = t.detach().to("cpu")
+        return t.view(torch.uint8).numpy() if t.dtype == torch.float8_e4m3fn else t.to(torch.float32).numpy()
+    return [[(conv(K), conv(V)) for (K, V) in per_seq] for per_seq in kv]
 
 
 KV8_NOMINAL = 48.0      # standard deviation of the synthetic cached context in code units (|x| stays below 448)

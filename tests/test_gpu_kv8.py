@@ -43,7 +43,7 @@ def test_kv8_small_workload_logits_and_cache_codes():
     ctx_len, B, k = batch["ctx_len"], wl["B"], wl["k"]
     scales = si.kv_scales(cfg, seed=seed)
     kv = si.make_logical_kv(cfg, ctx_len, seed=seed)                 # codes
-    kv_or = si.kv_for_oracle(kv, scales)
+    kv_or = fp8.cache_values(si.kv_for_oracle(kv), scales)
     rng = np.random.default_rng(11)
     tokens = np.concatenate([batch["tokens0"][:, None], rng.integers(0, cfg["vocab"], size=(B, k))], axis=1).astype(np.int32)
     want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens, ctx_len, kv_scales=scales)

@@ -29,13 +29,17 @@ def _check_workload(name, ks, moe_margin=None):
     rng = np.random.default_rng(123)
     picks = sorted({int(np.argmin(wl.ctx_len)), int(np.argmax(wl.ctx_len))} | ({3, 17, 40, 99} if moe_margin is not None else set()))
     weights = si.make_weights(cfg, seed=wl.seed, device="cuda")           # the generator's weights again, for the oracle
-    w_or = si.weights_for_oracle(cfg, weights)
+    w_or = si.weights_for_oracle(cfg, weights, library_decode=True)
     del weights
     torch.cuda.empty_cache()
     kv8 = cfg.get("kv_dtype") == "fp8_e4m3"
     scales = wl.kv_scales if kv8 else None                               # 8-bit cache: the oracle reads code * scale
-    kv_or = [[tuple(t.float().cpu().numpy().astype(np.float64) * (np.float64(scales[i][l])[None, :, None] if kv8 else 1.0)
-                    for i, t in enumerate(wl.logical_kv(l, b))) for b in picks] for l in range(cfg["n_layers"])]
+    if kv8:
+        from oracle import fp8
+        kv_or = fp8.cache_values([[tuple(t.view(torch.uint8).cpu().numpy() for t in wl.logical_kv(l, b)) for b in picks]
+                                  for l in range(cfg["n_layers"])], scales)
+    else:
+        kv_or = [[tuple(t.float().cpu().numpy() for t in wl.logical_kv(l, b)) for b in picks] for l in range(cfg["n_layers"])]
     seq_ids = wl.seq_ids
     for k in ks:
         wl.restore()

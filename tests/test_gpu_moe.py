@@ -28,7 +28,10 @@ def _run(cfg, ctx_list, k, seed):
     kv = si.make_logical_kv(cfg, ctx_len, seed=seed)
     kv8 = cfg.get("kv_dtype") == "fp8_e4m3"               # 8-bit cache: codes under the synthetic scales
     scales = si.kv_scales(cfg, seed=seed) if kv8 else None
-    kv_or = si.kv_for_oracle(kv, scales)
+    kv_or = si.kv_for_oracle(kv)
+    if kv8:
+        from oracle import fp8
+        kv_or = fp8.cache_values(kv_or, scales)
     rng = np.random.default_rng(seed)
     n_pages = sum(-(-(int(c) + k + 1) // si.PAGE_SIZE) for c in ctx_len) + 16
     order = rng.permutation(n_pages)

@@ -287,7 +287,10 @@ def _run_custom_bf16(ctx_list, k, seed=3, vocab=None, key_scale=1.0, key_scale_f
     if key_scale_fn is not None:    # a scale per cached position: key_scale_fn(ctx) -> [ctx] factors
         kv = [[((K.float() * torch.as_tensor(key_scale_fn(K.shape[0]), dtype=torch.float32).view(-1, 1, 1)).to(K.dtype), V)
                for (K, V) in per_seq] for per_seq in kv]
-    kv_or = si.kv_for_oracle(kv, scales)
+    kv_or = si.kv_for_oracle(kv)
+    if kv8:
+        from oracle import fp8
+        kv_or = fp8.cache_values(kv_or, scales)
     rng = np.random.default_rng(seed)
     n_ctx_pages = [-(-int(c) // si.PAGE_SIZE) for c in ctx_len]
     n_pages = sum(-(-(int(c) + k + 1) // si.PAGE_SIZE) for c in ctx_len) + 16

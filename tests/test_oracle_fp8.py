@@ -141,10 +141,11 @@ def test_stored_values_differ_from_unrounded_and_power_of_two_scale_is_neutral()
     assert np.array_equal(kv4[0][0][normal], new_kv[0][0][normal])
 
 
-def test_8bit_matrices_reach_the_oracle_as_code_times_scale():
-    """The generator's 8-bit matrices (a library cast of w / scale, scale = row absmax / 448) are handed to the oracle as
-    code * scale: checked against this oracle's own decode of the same bytes, and against the draws they came from
-    (half a mantissa step; the row maximum itself is exact)."""
+def test_8bit_matrices_reach_the_oracle_as_codes_and_scales():
+    """The generator's 8-bit matrices (a library cast of w / scale, scale = row absmax / 448) reach the oracle as bytes
+    plus scales; the oracle's own decode * scale is checked against the library's cast back and against the draws the
+    codes came from (half a mantissa step; the row maximum itself is exact), and the forward pass with them against
+    the forward pass on the dequantised matrices given as plain fp64 arrays."""
     cfg = dict(si.MODELS["small_bf16_w8"])
     w8 = si.make_weights(cfg, seed=4)
     w16 = si.make_weights(dict(cfg, w_dtype=None), seed=4)
@@ -152,16 +153,28 @@ def test_8bit_matrices_reach_the_oracle_as_code_times_scale():
     assert list(w8)[:len(names)] == names and all(n.endswith(".scale") for n in list(w8)[len(names):])
     w_or = si.weights_for_oracle(cfg, w8)
     for name, key in (("l0.wq", "wq"), ("l1.wd", "wd"), ("l0.wg", "wg")):
-        codes = w8[name].view(torch.uint8).numpy()
-        scale = w8[name + ".scale"].numpy().astype(np.float64)
-        mine = fp8.decode(codes) * scale[:, None]
         layer = int(name[1])
-        assert np.allclose(w_or["layers"][layer][key], mine, rtol=1e-6, atol=0)
+        mine = of.matrix(w_or["layers"][layer], key)
+        lib = w8[name].to(torch.float64).numpy() * w8[name + ".scale"].to(torch.float64).numpy()[:, None]
+        assert np.array_equal(mine, lib)
         orig = w16[name].to(torch.float64).numpy()
+        scale = w8[name + ".scale"].numpy().astype(np.float64)
         big = np.abs(orig) >= scale[:, None] * 2.0 ** -6
         assert np.max(np.abs(mine - orig)[big] / np.abs(orig)[big]) <= 2.0 ** -4 * (1 + 1e-6)
         assert np.allclose(np.abs(mine).max(axis=1), np.abs(orig).max(axis=1), rtol=1e-6)
-    assert np.allclose(w_or["head"], fp8.decode(w8["head"].view(torch.uint8).numpy()) * w8["head.scale"].numpy().astype(np.float64)[:, None], rtol=1e-6)
+    # the forward pass: codes + scales in, against the same matrices dequantised beforehand
+    plain = {"embed": w_or["embed"], "final_norm": w_or["final_norm"], "head": of.matrix(w_or, "head"),
+             "layers": [{k: (of.matrix(lw, k) if k.startswith("w") else lw[k]) for k in lw if not k.endswith("_scale")}
+                        for lw in w_or["layers"]]}
+    ctx_len = np.array([3, 0])
+    kv = si.kv_for_oracle(si.make_logical_kv(dict(cfg, kv_dtype=None), ctx_len, seed=5))
+    tokens = np.array([[1, 2, 3], [4, 5, 6]])
+    a, _ = of.verify_forward(cfg, w_or, kv, tokens, ctx_len)
+    b, _ = of.verify_forward(dict(cfg, w_dtype=None), plain, kv, tokens, ctx_len)
+    assert np.array_equal(a, b)
+    # ... and given as the library's cast times the scale (what the full-size tests hand over): fp32 products
+    c, _ = of.verify_forward(dict(cfg, w_dtype=None), si.weights_for_oracle(cfg, w8, library_decode=True), kv, tokens, ctx_len)
+    assert np.allclose(a, c, rtol=0, atol=1e-5)
 
 
 def test_weight_count_with_8bit_matrices():
