@@ -106,6 +106,7 @@ WORKLOADS["llama8b_kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_
 WORKLOADS["small_bf16_w8kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_w8kv8")
 WORKLOADS["llama8b_w8kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8kv8")
 WORKLOADS["llama8b_w8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8")
+WORKLOADS["llama8b_w8kv8_b256_ctx2k-16k_k3"] = dict(WORKLOADS["llama8b_b256_ctx2k-16k_k3"], model="llama8b_bf16_w8kv8", layer_alias_mod=0)
 WORKLOADS["llama8b_kv8_b256_ctx2k-16k_k3"] = dict(WORKLOADS["llama8b_b256_ctx2k-16k_k3"], model="llama8b_bf16_kv8",
                                                   layer_alias_mod=0)
 
