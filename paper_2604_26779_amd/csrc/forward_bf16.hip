@@ -75,12 +75,30 @@ __global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
         } else {
             float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
             if (MODE == RES_ADD) { a = *(const float4*)(xr + c); b = *(const float4*)(xr + c + 4); }
-            for (int s = 0; s < splits; ++s) {
-                const float* ps = part + s * split_stride + (int64_t)m * d + c;
-                float4 p0 = *(const float4*)ps, p1 = *(const float4*)(ps + 4);
-                a.x += p0.x; a.y += p0.y; a.z += p0.z; a.w += p0.w;
-                b.x += p1.x; b.y += p1.y; b.z += p1.z; b.w += p1.w;
-            }
+            // the slices are summed in order, but loaded eight (then four) at a time: left as a plain loop the compiler
+            // waits for each slice before it asks for the next, one trip to memory per slice
+            const float* p_row = part + (int64_t)m * d + c;
+            int s = 0;
+            auto add_group = [&](auto n_c) {
+                constexpr int GN = decltype(n_c)::value;
+                float4 p0[GN], p1[GN];
+#pragma unroll
+                for (int u = 0; u < GN; ++u) {
+                    const float* ps = p_row + (s + u) * split_stride;
+                    p0[u] = *(const float4*)ps;
+                    p1[u] = *(const float4*)(ps + 4);
+                }
+#pragma unroll
+                for (int u = 0; u < GN; ++u) {
+                    a.x += p0[u].x; a.y += p0[u].y; a.z += p0[u].z; a.w += p0[u].w;
+                    b.x += p1[u].x; b.y += p1[u].y; b.z += p1[u].z; b.w += p1[u].w;
+                }
+                s += GN;
+            };
+            while (s + 8 <= splits) add_group(std::integral_constant<int, 8>{});
+            if (s + 4 <= splits) add_group(std::integral_constant<int, 4>{});
+            if (s + 2 <= splits) add_group(std::integral_constant<int, 2>{});
+            if (s < splits) add_group(std::integral_constant<int, 1>{});
             v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
         }
         *(float4*)(xr + c) = make_float4(v[0], v[1], v[2], v[3]);
@@ -176,12 +194,24 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(
     const float* row = part + (int64_t)m * nqkv;
     unsigned short* pool = (unsigned short*)kv.pool;
     const int64_t block = (int64_t)SPEC_PAGE_SIZE * DHc;
+    // sum of the slices of 4 adjacent columns, in slice order; the loads go out eight (four, two) at a time - a plain
+    // loop would wait for each slice before asking for the next
     auto sum4 = [&](int n) {
-        float4 v = *(const float4*)(row + n);
-        for (int s = 1; s < splits; ++s) {
-            float4 p = *(const float4*)(row + s * split_stride + n);
-            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-        }
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        int s = 0;
+        auto add_group = [&](auto n_c) {
+            constexpr int GN = decltype(n_c)::value;
+            float4 p[GN];
+#pragma unroll
+            for (int u = 0; u < GN; ++u) p[u] = *(const float4*)(row + (s + u) * split_stride + n);
+#pragma unroll
+            for (int u = 0; u < GN; ++u) { v.x += p[u].x; v.y += p[u].y; v.z += p[u].z; v.w += p[u].w; }
+            s += GN;
+        };
+        while (s + 8 <= splits) add_group(std::integral_constant<int, 8>{});
+        if (s + 4 <= splits) add_group(std::integral_constant<int, 4>{});
+        if (s + 2 <= splits) add_group(std::integral_constant<int, 2>{});
+        if (s < splits) add_group(std::integral_constant<int, 1>{});
         return v;
     };
     // rotary part: heads 0 .. Hq+Hkv-1, 16 quads of the lower half each
