@@ -64,9 +64,10 @@ const char* spec_last_error(void);
  * saturated, with one fp32 scale per (layer, kv head) for keys and one for values (spec_kv_set_scales); attention
  * reads code * scale.  As with the other storage types the k+1 new positions are encoded before any row attends
  * to them.
- * w_dtype = SPEC_FP8_E4M3 (bf16, dense, untied head, no hidden-state input): the matrices wq .. wd and head are
- * E4M3 codes [out_features, in_features], one byte each, with one fp32 scale per output row (W[n][k] = code * scale[n]);
- * embed and the norm gains stay `dtype`.  The kernels widen the codes to bf16 in registers (exact) and apply the
+ * w_dtype = SPEC_FP8_E4M3 (bf16, untied head, no hidden-state input): the matrices wq .. wd and head are
+ * E4M3 codes [out_features, in_features], one byte each, with one fp32 scale per output row (W[n][k] = code * scale[n];
+ * stacked expert matrices: one scale per expert and output row, [E, Fe] for wg and wu, [E, d] for wd);
+ * embed, the norm gains and the router stay `dtype`.  The kernels widen the codes to bf16 in registers (exact) and apply the
  * scale to the accumulated output, so the arithmetic is that of the bf16 path on the dequantised matrix. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;

@@ -110,18 +110,21 @@ def moe_ffn(h, w, top_k, route_log=None):
     for m in range(h.shape[0]):
         for j in range(top_k):
             e = experts[m, j]
-            gate = np.asarray(w["wg"][e], dtype=np.float64) @ h[m]
-            up = np.asarray(w["wu"][e], dtype=np.float64) @ h[m]
-            out[m] += weight[m, j] * (np.asarray(w["wd"][e], dtype=np.float64) @ (silu(gate) * up))
+            gate = matrix(w, "wg", e) @ h[m]
+            up = matrix(w, "wu", e) @ h[m]
+            out[m] += weight[m, j] * (matrix(w, "wd", e) @ (silu(gate) * up))
     return out
 
 
-def matrix(w, key):
-    """A projection matrix of the dict w in fp64.  8-bit matrices (the dict also holds key + "_scale", one factor per
-    output row, and w[key] holds E4M3 codes as uint8): W[n][k] = decode(code[n][k]) * scale[n]."""
+def matrix(w, key, expert=None):
+    """A projection matrix of the dict w in fp64 (expert: one of the stacked expert matrices).  8-bit matrices (the
+    dict also holds key + "_scale", one factor per output row, and w[key] holds E4M3 codes as uint8):
+    W[n][k] = decode(code[n][k]) * scale[n]."""
+    m = w[key] if expert is None else w[key][expert]
     if key + "_scale" in w:
-        return fp8.decode(np.asarray(w[key], dtype=np.uint8)) * np.asarray(w[key + "_scale"], dtype=np.float64)[:, None]
-    return np.asarray(w[key], dtype=np.float64)
+        sc = w[key + "_scale"] if expert is None else w[key + "_scale"][expert]
+        return fp8.decode(np.asarray(m, dtype=np.uint8)) * np.asarray(sc, dtype=np.float64)[:, None]
+    return np.asarray(m, dtype=np.float64)
 
 
 def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden_in=None, return_hidden=False,

@@ -150,8 +150,8 @@ static spec_status check_desc(const spec_model_desc& d)
         set_error("spec_model_create: kv_dtype must be 0 or SPEC_FP8_E4M3 (bf16 models only)");
         return SPEC_EUNSUPPORTED;
     }
-    if (d.w_dtype != 0 && !(d.w_dtype == SPEC_FP8_E4M3 && d.dtype == SPEC_BF16 && d.n_experts == 0 && !d.fuse_hidden && !d.tied_head)) {
-        set_error("spec_model_create: w_dtype must be 0 or SPEC_FP8_E4M3 (bf16, dense, untied head, no hidden-state input)");
+    if (d.w_dtype != 0 && !(d.w_dtype == SPEC_FP8_E4M3 && d.dtype == SPEC_BF16 && !d.fuse_hidden && !d.tied_head)) {
+        set_error("spec_model_create: w_dtype must be 0 or SPEC_FP8_E4M3 (bf16, untied head, no hidden-state input)");
         return SPEC_EUNSUPPORTED;
     }
     if (d.fuse_hidden) {
@@ -194,8 +194,12 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         const spec_model_desc& d = *desc;
         const int L = d.n_layers, D = d.d_model, F = d.ffn_dim;
         const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim;
-        m->arena_bytes = (size_t)L * (w8_packed_bytes(nq + 2 * nkv, D) + w8_packed_bytes(D, nq) + w8_packed_bytes(2 * F, D) + w8_packed_bytes(D, F)) +
-                         w8_packed_bytes(d.vocab, D);
+        const int E = d.n_experts, Fe = d.expert_ffn_dim;
+        m->arena_bytes = (size_t)L * (w8_packed_bytes(nq + 2 * nkv, D) + w8_packed_bytes(D, nq)) + w8_packed_bytes(d.vocab, D);
+        if (E > 0)       // every expert's region (codes, then scales) on its own; the router stays a bf16 matrix
+            m->arena_bytes += (size_t)L * ((size_t)E * (w8_packed_bytes(2 * Fe, D) + w8_packed_bytes(D, Fe)) + align_up(bf16_packed_elems(E, D) * sizeof(bf16_t), 256));
+        else
+            m->arena_bytes += (size_t)L * (w8_packed_bytes(2 * F, D) + w8_packed_bytes(D, F));
         hipError_t e = hipMalloc(&m->arena, m->arena_bytes);
         if (e != hipSuccess) {
             set_error("spec_model_create: hipMalloc of %zu bytes for the tiled weights failed: %s", m->arena_bytes, hipGetErrorString(e));
@@ -219,8 +223,28 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         for (int l = 0; l < L && st == SPEC_OK; ++l) {
             st = pack8({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {m->w_scale(l, 0), m->w_scale(l, 1), m->w_scale(l, 2)}, {nq, nkv, nkv}, D, &m->wqkv[l]);
             if (st == SPEC_OK) st = pack8({m->layer_w(l, 4)}, {m->w_scale(l, 3)}, {D}, nq, &m->wo[l]);
-            if (st == SPEC_OK) st = pack8({m->layer_w(l, 6), m->layer_w(l, 7)}, {m->w_scale(l, 4), m->w_scale(l, 5)}, {F, F}, D, &m->wgu[l], true);
-            if (st == SPEC_OK) st = pack8({m->layer_w(l, 8)}, {m->w_scale(l, 6)}, {D}, F, &m->wd[l]);
+            if (E > 0) {
+                const unsigned char *wg = (const unsigned char*)m->layer_w(l, 6), *wu = (const unsigned char*)m->layer_w(l, 7),
+                                    *wdn = (const unsigned char*)m->layer_w(l, 8);
+                const float *sg = m->w_scale(l, 4), *su = m->w_scale(l, 5), *sd = m->w_scale(l, 6);
+                m->moe_gu_stride = (int64_t)w8_packed_bytes(2 * Fe, D);       // bytes: see launch_gemm_bf16_grouped
+                m->moe_d_stride = (int64_t)w8_packed_bytes(D, Fe);
+                PackedW tmp;
+                for (int e2 = 0; e2 < E && st == SPEC_OK; ++e2)
+                    st = pack8({wg + (size_t)e2 * Fe * D, wu + (size_t)e2 * Fe * D}, {sg + (size_t)e2 * Fe, su + (size_t)e2 * Fe}, {Fe, Fe}, D,
+                               e2 == 0 ? &m->wgu[l] : &tmp, true);
+                for (int e2 = 0; e2 < E && st == SPEC_OK; ++e2)
+                    st = pack8({wdn + (size_t)e2 * D * Fe}, {sd + (size_t)e2 * D}, {D}, Fe, e2 == 0 ? &m->wd[l] : &tmp);
+                if (st == SPEC_OK) {
+                    const bf16_t* rp = (const bf16_t*)m->layer_w(l, 9);
+                    const int rows = E;
+                    st = bf16_pack_matrix(&rp, &rows, 1, D, (bf16_t*)at, &m->router[l], false, nullptr);
+                    at += align_up(bf16_packed_elems(E, D) * sizeof(bf16_t), 256);
+                }
+            } else {
+                if (st == SPEC_OK) st = pack8({m->layer_w(l, 6), m->layer_w(l, 7)}, {m->w_scale(l, 4), m->w_scale(l, 5)}, {F, F}, D, &m->wgu[l], true);
+                if (st == SPEC_OK) st = pack8({m->layer_w(l, 8)}, {m->w_scale(l, 6)}, {D}, F, &m->wd[l]);
+            }
         }
         if (st == SPEC_OK) st = pack8({m->head_w()}, {m->head_scale()}, {d.vocab}, D, &m->head);
         if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }

@@ -206,7 +206,6 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
 {
     constexpr int KS = GEMM_KS;
     constexpr int KSW = W8 ? KS / 2 : KS;               // 16-byte words of one column block per lane and slab
-    static_assert(!(W8 && GROUPED), "the grouped GEMM has no 8-bit variant");
     constexpr int MBW = MB / WM, NBW = NBW_T;
     constexpr int TILE_NB = (4 / WM) * NBW;             // 32-column blocks per workgroup tile
     constexpr bool BIG = MB >= 6;
@@ -245,6 +244,7 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
     if constexpr (GROUPED) {
         if (bz >= tiles[0]) return;
         Wp += (int64_t)tiles[1 + 2 * bz] * w_group_stride;
+        if constexpr (W8) wscale += (int64_t)tiles[1 + 2 * bz] * w_group_stride * 4;   // a group's scales sit in its own region
         mblk0 = tiles[2 + 2 * bz];
     }
 
@@ -621,13 +621,14 @@ spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, co
     dim3 grid((unsigned)cdiv(W0.n_blocks, 4), 1, (unsigned)max_tiles);
     const u32x4_t* wp = (const u32x4_t*)W0.data;
     const u32x4_t* xp = (const u32x4_t*)Xp;
-    const int64_t stride16 = group_stride / 8;             // in 16-byte words
-    if (swiglu)
-        gemm_bf16_kernel<2, 2, 2, GEMM_EPI_SWIGLU, true><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W0.n_blocks, W0.k_steps, W0.k_steps,
-                                                                                       rows_pad / 32, rows_pad, W0.N, ldo, 0, tiles, stride16);
-    else
-        gemm_bf16_kernel<2, 2, 2, GEMM_EPI_PLAIN, true><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W0.n_blocks, W0.k_steps, W0.k_steps,
-                                                                                      rows_pad / 32, rows_pad, W0.N, ldo, 0, tiles, stride16);
+    // distance between the groups' matrices in 16-byte words (group_stride: bf16 elements, or bytes of a whole 8-bit region,
+    // codes and scales, so that the scales of group g sit g * stride behind those of group 0 as well)
+    const int64_t stride16 = W0.w8 ? group_stride / 16 : group_stride / 8;
+#define SPEC_GROUPED_LAUNCH(E, W8V) gemm_bf16_kernel<2, 2, 2, E, true, 2, W8V><<<grid, GEMM_THREADS, 0, s>>>( \
+        wp, xp, out, W0.n_blocks, W0.k_steps, W0.k_steps, rows_pad / 32, rows_pad, W0.N, ldo, 0, tiles, stride16, W0.scale)
+    if (swiglu) { if (W0.w8) SPEC_GROUPED_LAUNCH(GEMM_EPI_SWIGLU, true); else SPEC_GROUPED_LAUNCH(GEMM_EPI_SWIGLU, false); }
+    else { if (W0.w8) SPEC_GROUPED_LAUNCH(GEMM_EPI_PLAIN, true); else SPEC_GROUPED_LAUNCH(GEMM_EPI_PLAIN, false); }
+#undef SPEC_GROUPED_LAUNCH
     SPEC_LAUNCH_CHECK("gemm_bf16_kernel (grouped)");
     return SPEC_OK;
 }

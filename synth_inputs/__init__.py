@@ -101,11 +101,13 @@ for _name in ("small_bf16", "llama8b_bf16"):
     MODELS[_name + "_kv8"] = dict(MODELS[_name], kv_dtype="fp8_e4m3")
     MODELS[_name + "_w8kv8"] = dict(MODELS[_name], kv_dtype="fp8_e4m3", w_dtype="fp8_e4m3")     # 8-bit matrices as well
     MODELS[_name + "_w8"] = dict(MODELS[_name], w_dtype="fp8_e4m3")
+MODELS["moe235b_slice_bf16_w8kv8"] = dict(MODELS["moe235b_slice_bf16"], kv_dtype="fp8_e4m3", w_dtype="fp8_e4m3")
 WORKLOADS["small_bf16_kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_kv8")
 WORKLOADS["llama8b_kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_kv8")
 WORKLOADS["small_bf16_w8kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_w8kv8")
 WORKLOADS["llama8b_w8kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8kv8")
 WORKLOADS["llama8b_w8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8")
+WORKLOADS["moe235b_slice_w8kv8_b128_ctx4k-32k_k3"] = dict(WORKLOADS["moe235b_slice_b128_ctx4k-32k_k3"], model="moe235b_slice_bf16_w8kv8")
 WORKLOADS["llama8b_w8kv8_b256_ctx2k-16k_k3"] = dict(WORKLOADS["llama8b_b256_ctx2k-16k_k3"], model="llama8b_bf16_w8kv8", layer_alias_mod=0)
 WORKLOADS["llama8b_kv8_b256_ctx2k-16k_k3"] = dict(WORKLOADS["llama8b_b256_ctx2k-16k_k3"], model="llama8b_bf16_kv8",
                                                   layer_alias_mod=0)
@@ -161,8 +163,8 @@ def make_weights(cfg, seed=DEFAULT_SEED, device="cpu", std=0.02):
         scales = {}
         for name in [n for n in weights if n.split(".")[-1] in W8_MATRICES]:
             w = weights[name].to(torch.float32)
-            sc = (w.abs().amax(dim=1) / 448.0).clamp_min(1e-12)
-            weights[name] = (w / sc[:, None]).to(torch.float8_e4m3fn)
+            sc = (w.abs().amax(dim=-1) / 448.0).clamp_min(1e-12)       # (stacked expert matrices: one scale per expert and row)
+            weights[name] = (w / sc[..., None]).to(torch.float8_e4m3fn)
             scales[name + ".scale"] = sc
             del w
         weights.update(scales)
@@ -179,7 +181,7 @@ def weights_for_oracle(cfg, weights, library_decode=False):
     the oracle's decode is pinned against code by code."""
     def f(name):
         if name + ".scale" in weights and library_decode:
-            return (weights[name].detach().to("cpu", torch.float32) * weights[name + ".scale"].detach().to("cpu", torch.float32)[:, None]).numpy()
+            return (weights[name].detach().to("cpu", torch.float32) * weights[name + ".scale"].detach().to("cpu", torch.float32)[..., None]).numpy()
         if name + ".scale" in weights:                # 8-bit matrix: the oracle gets the codes (bytes) and the scales
             return weights[name].detach().to("cpu").view(torch.uint8).numpy()
         return weights[name].detach().to("cpu", torch.float32).numpy()

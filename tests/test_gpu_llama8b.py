@@ -135,6 +135,11 @@ def test_moe_slice_full_size():
     _check_workload("moe235b_slice_b128_ctx4k-32k_k3", [3], moe_margin=1e-3)
 
 
+def test_moe_slice_full_size_8bit_matrices_and_cache():
+    """The same slice with every projection (experts included) as E4M3 codes and the E4M3 cache."""
+    _check_workload("moe235b_slice_w8kv8_b128_ctx4k-32k_k3", [3], moe_margin=1e-3)
+
+
 def test_draft_pair_full_size_on_sampled_sequences():
     """Single-layer draft (8B widths, tied 128256-token head) run 5 times + 8B-shaped verify, B = 64, contexts 4096:
     the whole step on the GPU, then for two sampled sequences the oracle's draft loop, verify forward and rejection

@@ -112,3 +112,16 @@ def test_small_moe_with_the_8bit_cache():
     max_err, n_exempt, n_rows, loads = _run(cfg, ctx, wl["k"], seed=12)
     print("small moe, 8-bit cache: max abs err %.3e on %d rows, %d exempted" % (max_err, n_rows - n_exempt, n_exempt))
     assert n_exempt <= n_rows // 4
+
+
+@pytest.mark.parametrize("B,k,changes", [(6, 3, {}), (96, 3, {}), (20, 5, dict(n_experts=4, top_k=4)), (8, 2, dict(n_experts=5, top_k=1, expert_ffn_dim=768))])
+def test_moe_with_8bit_matrices_and_cache(B, k, changes):
+    """Expert, attention and head matrices as E4M3 codes with one scale per (expert and) output row, over the E4M3 cache:
+    the grouped expert GEMMs widen the codes like the dense ones and take each expert's own scales."""
+    cfg = dict(si.MODELS["small_moe_bf16"], vocab=1000, kv_dtype="fp8_e4m3", w_dtype="fp8_e4m3")
+    cfg.update(changes)
+    rng = np.random.default_rng(B + k)
+    ctx = [int(c) for c in rng.integers(0, 150, size=B)]
+    max_err, n_exempt, n_rows, loads = _run(cfg, ctx, k, seed=B * 7 + k)
+    print("moe, 8-bit matrices and cache, B=%d k=%d %s: max abs err %.3e on %d rows, %d exempted" % (B, k, changes, max_err, n_rows - n_exempt, n_exempt))
+    assert n_exempt <= max(2, n_rows // 4)
