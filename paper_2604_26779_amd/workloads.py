@@ -12,6 +12,24 @@ from . import binding as sv
 from .session import VerifySession
 
 
+def fill_pool(sess, cfg, g, seed):
+    """Synthetic cached context: every slot of the pool ~ N(0,1) in the storage type; an 8-bit cache gets the codes of
+    N(0, KV8_NOMINAL) entries (the library's cast) under the synthetic scales, which are installed and returned."""
+    chunk = 1 << 28
+    flat = sess.pool
+    if not sess.kv8:
+        for at in range(0, flat.numel(), chunk):
+            flat[at:at + chunk].normal_(generator=g)
+        return None
+    for at in range(0, flat.numel(), chunk):
+        n = min(chunk, flat.numel() - at)
+        draw = torch.empty(n, dtype=torch.bfloat16, device=flat.device).normal_(0.0, si.KV8_NOMINAL, generator=g)
+        flat[at:at + n] = draw.to(torch.float8_e4m3fn).view(torch.uint8)
+    scales = si.kv_scales(cfg, seed=seed)
+    sess.set_scales(*scales)
+    return scales
+
+
 class DeviceWorkload:
     def __init__(self, workload_name, seed=si.DEFAULT_SEED, shuffle_pages=True, device="cuda", extra_pages=None,
                  drop_canonical=True):
@@ -40,19 +58,7 @@ class DeviceWorkload:
         # synthetic cached context: every slot of the pool ~ N(0,1) in the storage type
         g = torch.Generator(device=device)
         g.manual_seed(int(seed) + 2)
-        chunk = 1 << 28
-        flat = self.sess.pool
-        if self.sess.kv8:
-            # codes of N(0, KV8_NOMINAL) entries (the library's cast), under the synthetic scales
-            for at in range(0, flat.numel(), chunk):
-                n = min(chunk, flat.numel() - at)
-                draw = torch.empty(n, dtype=torch.bfloat16, device=device).normal_(0.0, si.KV8_NOMINAL, generator=g)
-                flat[at:at + n] = draw.to(torch.float8_e4m3fn).view(torch.uint8)
-            self.kv_scales = si.kv_scales(self.cfg, seed=seed)
-            self.sess.set_scales(*self.kv_scales)
-        else:
-            for at in range(0, flat.numel(), chunk):
-                flat[at:at + chunk].normal_(generator=g)
+        self.kv_scales = fill_pool(self.sess, self.cfg, g, seed)
         self.seq_ids = torch.arange(B, dtype=torch.int32, device=device)
         for b in range(B):
             self.sess.assign(b, int(self.ctx_len[b]), self.batch["page_lists"][b])
@@ -142,7 +148,7 @@ class DraftPairWorkload(DeviceWorkload):
         torch.cuda.empty_cache()
         g = torch.Generator(device=device)
         g.manual_seed(int(seed) + 19)
-        self.dsess.pool.normal_(generator=g)
+        self.draft_kv_scales = fill_pool(self.dsess, self.draft_cfg, g, seed + 17)
         rng = np.random.Generator(np.random.Philox(int(seed) + 23))
         order = rng.permutation(n_pages)
         at = 0

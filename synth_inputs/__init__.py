@@ -102,7 +102,7 @@ for _name in ("small_bf16", "llama8b_bf16"):
     MODELS[_name + "_w8kv8"] = dict(MODELS[_name], kv_dtype="fp8_e4m3", w_dtype="fp8_e4m3")     # 8-bit matrices as well
     MODELS[_name + "_w8"] = dict(MODELS[_name], w_dtype="fp8_e4m3")
 # a draft with 8-bit matrices: its output head is then a matrix of its own (the quantised embedding), not tied
-MODELS["draft1l_8b_bf16_w8"] = dict(MODELS["draft1l_8b_bf16"], tied_head=0, w_dtype="fp8_e4m3")
+MODELS["draft1l_8b_bf16_w8"] = dict(MODELS["draft1l_8b_bf16"], tied_head=0, w_dtype="fp8_e4m3", kv_dtype="fp8_e4m3")
 MODELS["moe235b_slice_bf16_w8kv8"] = dict(MODELS["moe235b_slice_bf16"], kv_dtype="fp8_e4m3", w_dtype="fp8_e4m3")
 WORKLOADS["small_bf16_kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_kv8")
 WORKLOADS["llama8b_kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_kv8")
