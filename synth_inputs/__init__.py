@@ -109,6 +109,7 @@ WORKLOADS["llama8b_kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_
 WORKLOADS["small_bf16_w8kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_w8kv8")
 WORKLOADS["llama8b_w8kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8kv8")
 WORKLOADS["llama8b_w8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8")
+WORKLOADS["rollout_w8kv8_b32_q32_ctx1k-8k_k3"] = dict(WORKLOADS["rollout_b32_q32_ctx1k-8k_k3"], model="llama8b_bf16_w8kv8")
 WORKLOADS["draft_pair_w8kv8_b64_ctx4096_k5"] = dict(WORKLOADS["draft_pair_b64_ctx4096_k5"], model="llama8b_bf16_w8kv8",
                                                     draft_model="draft1l_8b_bf16_w8")
 WORKLOADS["moe235b_slice_w8kv8_b128_ctx4k-32k_k3"] = dict(WORKLOADS["moe235b_slice_b128_ctx4k-32k_k3"], model="moe235b_slice_bf16_w8kv8")
