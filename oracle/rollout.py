@@ -68,3 +68,19 @@ def compact_slots(slot_seq, active, tokens):
     idle = [b for b in range(len(active)) if not active[b]]
     order = live + idle
     return slot_seq[order].copy(), active[order].copy(), tokens[order].copy(), len(live)
+
+
+def backfill_pending(pending, slot_seq_before, slot_seq, active, prev_token, first_token):
+    """With a draft model the step also carries, per slot, the pair of tokens the draft has not cached yet: the last
+    input the target has cached and the last emitted token (``oracle/draft.py``).  A slot that a waiting sequence has
+    just taken over starts from that sequence's own pair: the last token of its prompt (cached by the target, not by
+    the draft, whose cache is one position behind) and its first input token.  pending [B, 2] is updated in place;
+    slots that kept their sequence, and idle ones, are left alone.  Returns the slots that changed."""
+    changed = []
+    for b in range(len(slot_seq)):
+        s = int(slot_seq[b])
+        if active[b] and s != int(slot_seq_before[b]):
+            pending[b, 0] = prev_token[s]
+            pending[b, 1] = first_token[s]
+            changed.append(b)
+    return changed

@@ -96,3 +96,32 @@ def test_compact_slots():
         for b in range(B):                                                    # rows travel with their slot
             src = int(np.where(seq == s2[b])[0][0])
             assert np.array_equal(t2[b], tok[src])
+
+
+def test_backfill_pending_touches_only_slots_taken_over():
+    """A slot taken over by a waiting sequence starts from that sequence's own (last prompt token, first input) pair;
+    slots that kept their sequence and idle slots keep what they had.  Checked on a retire step built so that all
+    three kinds of slot occur, against the definition spelled out per slot."""
+    rng = np.random.default_rng(3)
+    B, n_seqs, k = 5, 8, 2
+    slot_seq = np.arange(B, dtype=np.int32)
+    active = np.array([1, 1, 1, 1, 0], dtype=np.int32)                 # slot 4 idle already
+    gen = np.zeros(n_seqs, dtype=np.int32)
+    target = np.array([1, 9, 2, 1, 5, 7, 7, 7], dtype=np.int32)         # slots 0, 2, 3 finish with n = 1
+    queue = [5, 6]                                                      # two successors for three finishing slots
+    first = rng.integers(0, 100, size=n_seqs).astype(np.int32)
+    prev = rng.integers(100, 200, size=n_seqs).astype(np.int32)
+    tokens = rng.integers(0, 100, size=(B, k + 1)).astype(np.int32)
+    pending = rng.integers(200, 300, size=(B, 2)).astype(np.int32)
+    before = slot_seq.copy()
+    old_pending = pending.copy()
+    oro.retire_and_backfill(slot_seq, active, np.ones(B, dtype=np.int32), k, gen, target, queue, 0, first, tokens)
+    assert list(slot_seq) == [5, 1, 6, 3, 4] and list(active) == [1, 1, 1, 0, 0]
+    changed = oro.backfill_pending(pending, before, slot_seq, active, prev, first)
+    assert changed == [0, 2]
+    for b in range(B):
+        if b in (0, 2):
+            assert list(pending[b]) == [prev[slot_seq[b]], first[slot_seq[b]]]
+            assert pending[b, 1] == tokens[b, 0]                        # the same first input the verifier gets
+        else:
+            assert list(pending[b]) == list(old_pending[b])
