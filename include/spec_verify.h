@@ -391,6 +391,20 @@ spec_status spec_rollout_compact(int32_t B, int32_t k, int32_t* dev_slot_seq, in
                                  int32_t* dev_n_live, int32_t* dev_scratch, void* stream);
 
 /*
+ * Continuous rollout with a draft model (the paper's drafting paths, Section 2.3, run inside the rollout loop of
+ * Section 2.2): besides the verifier's inputs every slot carries the pair of tokens its draft model has not cached yet,
+ * dev_pending [B, 2] = (last input the verifier has cached, last emitted token) (spec_next_step_inputs).  For every
+ * live slot whose sequence changed in spec_rollout_retire - dev_slot_seq_before [B] is a copy of dev_slot_seq taken
+ * before that call - the pair becomes the new sequence's own: (dev_prev_token[s], dev_first_token[s]), the last token
+ * of its prompt (cached by the verifier, not by the draft model, whose cache is one position behind) and its first
+ * input token.  Other slots are left alone.  Sequence ids index dev_prev_token and dev_first_token (n_seqs entries
+ * each).  Asynchronous on `stream`.
+ */
+spec_status spec_rollout_pending(int32_t B, int32_t n_seqs, const int32_t* dev_slot_seq_before, const int32_t* dev_slot_seq,
+                                 const int32_t* dev_active, const int32_t* dev_prev_token, const int32_t* dev_first_token,
+                                 int32_t* dev_pending, void* stream);
+
+/*
  * Replay of a recorded sequence of step calls (for callers whose steps are short enough that launching ~350 small
  * kernels per step costs more than running them).  Between spec_graph_capture_begin and spec_graph_capture_end every
  * call of this library on `stream` (which must not be the default stream) is recorded instead of executed; the

@@ -632,6 +632,22 @@ extern "C" spec_status spec_rollout_compact(int32_t B, int32_t k, int32_t* dev_s
     return SPEC_OK;
 }
 
+extern "C" spec_status spec_rollout_pending(int32_t B, int32_t n_seqs, const int32_t* dev_slot_seq_before, const int32_t* dev_slot_seq,
+                                            const int32_t* dev_active, const int32_t* dev_prev_token, const int32_t* dev_first_token,
+                                            int32_t* dev_pending, void* stream)
+{
+    if (B < 1 || n_seqs < 1) { set_error("spec_rollout_pending: B or n_seqs out of range"); return SPEC_EINVAL; }
+    if (!dev_slot_seq_before || !dev_slot_seq || !dev_active || !dev_prev_token || !dev_first_token || !dev_pending) {
+        set_error("spec_rollout_pending: null pointer");
+        return SPEC_EINVAL;
+    }
+    spec_status st = launch_rollout_pending(B, n_seqs, dev_slot_seq_before, dev_slot_seq, dev_active, dev_prev_token, dev_first_token,
+                                            dev_pending, (hipStream_t)stream);
+    if (st != SPEC_OK) return st;
+    prof_mark(PC_OTHER, (hipStream_t)stream);
+    return SPEC_OK;
+}
+
 extern "C" size_t spec_kv_state_bytes(const spec_kv* kv) { return kv ? kv->state_ints * sizeof(int32_t) : 0; }
 
 extern "C" spec_status spec_kv_snapshot(spec_kv* kv, void* dev_buf, void* stream)

@@ -297,6 +297,27 @@ spec_status launch_rollout_compact(int B, int k, int32_t* slot_seq, int32_t* act
     return SPEC_OK;
 }
 
+// pending[b] = (prev_token[s], first_token[s]) for the live slots whose sequence s changed in the retire step
+__global__ void rollout_pending_kernel(int B, int n_seqs, const int32_t* __restrict__ slot_seq_before, const int32_t* __restrict__ slot_seq,
+                                       const int32_t* __restrict__ active, const int32_t* __restrict__ prev_token,
+                                       const int32_t* __restrict__ first_token, int32_t* __restrict__ pending)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int s = slot_seq[b];
+    if (!active[b] || s == slot_seq_before[b] || s < 0 || s >= n_seqs) return;
+    pending[2 * b] = prev_token[s];
+    pending[2 * b + 1] = first_token[s];
+}
+
+spec_status launch_rollout_pending(int B, int n_seqs, const int32_t* slot_seq_before, const int32_t* slot_seq, const int32_t* active,
+                                   const int32_t* prev_token, const int32_t* first_token, int32_t* pending, hipStream_t s)
+{
+    rollout_pending_kernel<<<(unsigned)cdiv(B, 256), 256, 0, s>>>(B, n_seqs, slot_seq_before, slot_seq, active, prev_token, first_token, pending);
+    SPEC_LAUNCH_CHECK("rollout_pending_kernel");
+    return SPEC_OK;
+}
+
 spec_status launch_kv_truncate(spec_kv* kv, int B, const int32_t* dev_seq_ids, const int32_t* dev_len, int delta,
                                int32_t* dev_new_len, hipStream_t s)
 {

@@ -221,3 +221,69 @@ class ContinuousRollout:
             sv.spec_kv_truncate(t.kv, B, self.release_seq, self.keep_len, 0, None, stream)
             if live_out is not None:
                 live_out[s] = self.active[:B].sum()
+
+
+class ContinuousPairRollout:
+    """The continuous rollout with a draft model instead of the n-gram drafter: draft loop -> verify forward -> rejection
+    sampling -> commit -> roll-back of the draft's cache -> next inputs and pending pairs -> slot bookkeeping (finished
+    sequences retire, waiting ones take their slot together with their own pending pair, the rest idle) -> release of the
+    retired sequences' pages in both caches; one stream, no host round trip.  Sequence ids index every per-sequence
+    array; waiting sequences are prefilled in both caches (the draft's one position behind the verifier's).  Only call
+    order and buffers are handled here."""
+
+    def __init__(self, target_session, draft_session, B, k, slot_seq, target_len, queue, prev_token, first_token):
+        self.t, self.d, self.B, self.k = target_session, draft_session, int(B), int(k)
+        dev = target_session.device
+        n_seqs = int(target_len.shape[0])
+        self.loop = DraftLoop(draft_session, B, k)
+        assert not self.loop.fused, "a draft with hidden-state input would also need the waiting sequences' hidden states"
+        self.slot_seq = slot_seq.to(dev, torch.int32).clone()
+        self.slot_seq_before = self.slot_seq.clone()
+        self.target_len = target_len.to(dev, torch.int32)
+        self.prev_token = prev_token.to(dev, torch.int32)
+        self.first_token = first_token.to(dev, torch.int32)
+        self.queue = queue.to(dev, torch.int32) if queue is not None and len(queue) else None
+        self.active = torch.ones(B, dtype=torch.int32, device=dev)
+        self.gen_len = torch.zeros(n_seqs, dtype=torch.int32, device=dev)
+        self.queue_head = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.produced = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.tokens = torch.zeros((B, k + 1), dtype=torch.int32, device=dev)
+        self.pending = torch.zeros((B, 2), dtype=torch.int32, device=dev)
+        self.q = torch.zeros((B, k, target_session.cfg["vocab"]), dtype=torch.float32, device=dev)
+        self.release_seq = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.keep_len = torch.zeros(B, dtype=torch.int32, device=dev)
+        idx = self.slot_seq.long()
+        self.tokens[:, 0] = self.first_token[idx]
+        self.pending[:, 0] = self.prev_token[idx]
+        self.pending[:, 1] = self.first_token[idx]
+
+    def run(self, n_steps, temperature, seed, step0=0, live_out=None, accept_out=None, stream=None):
+        """live_out [n_steps] int32, accept_out [n_steps, B] int32 (device, optional): live slots after and accept
+        lengths of every step."""
+        t, B, k = self.t, self.B, self.k
+        V = t.cfg["vocab"]
+        buf = t.step_buffers(B, k)
+        ws = buf["workspace"]
+        off = (-ws.data_ptr()) % 256
+        ws = ws[off:off + ws.numel() - 256]
+        out = buf["out_tokens"]
+        for s in range(n_steps):
+            acc = accept_out[s] if accept_out is not None else buf["accept_len"]
+            drafts = self.loop.run(self.slot_seq, self.pending, self.q, temperature, seed, step0 + s, stream)
+            self.tokens[:, 1:] = drafts
+            sv.spec_verify_forward(t.model, t.kv, B, k, self.slot_seq, self.tokens, buf["logits"], ws, stream)
+            sv.spec_reject_sample(B, k, V, buf["logits"], self.q, drafts, temperature, seed, step0 + s, acc, out, None,
+                                  buf["sample_ws"], stream)
+            sv.spec_commit_kv(t.kv, B, k, self.slot_seq, acc, buf["new_ctx_len"], None, stream)
+            self.loop.roll_back(self.slot_seq, buf["new_ctx_len"], stream)
+            sv.spec_next_step_inputs(B, k, self.tokens, out, acc, self.pending, stream)
+            self.slot_seq_before.copy_(self.slot_seq)
+            sv.spec_rollout_retire(B, k, self.slot_seq, self.active, acc, self.gen_len, self.target_len, self.queue,
+                                   self.queue_head, self.first_token, self.tokens, self.release_seq, self.keep_len,
+                                   self.produced, stream)
+            sv.spec_rollout_pending(B, self.slot_seq_before, self.slot_seq, self.active, self.prev_token, self.first_token,
+                                    self.pending, stream)
+            sv.spec_kv_truncate(t.kv, B, self.release_seq, self.keep_len, 0, None, stream)
+            sv.spec_kv_truncate(self.d.kv, B, self.release_seq, self.keep_len, 0, None, stream)
+            if live_out is not None:
+                live_out[s] = self.active.sum()

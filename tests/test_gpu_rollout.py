@@ -165,3 +165,79 @@ def test_compaction_and_shrinking_batch():
     assert np.all(st["ctx_len"][:n_seqs] == 0) and np.all(st["n_pages"][:n_seqs] == 0) and len(st["free_stack"]) == n_pages
     print("shrinking rollout: batch sizes", sizes, "tokens", int(roll.produced.item()))
     sess.close()
+
+
+def test_backfilled_slots_get_their_own_pending_pair_and_a_pair_rollout_drains():
+    """spec_rollout_pending bit for bit against the oracle on random slot tables (kept, taken-over and idle slots, more
+    slots than one workgroup), and a whole continuous rollout with a draft model (tiny pair, slots taken over several
+    times): every sequence produces exactly its response length, both caches end empty with every page back on the
+    free stacks, and at every step a live slot's draft cache is one position behind its verifier cache."""
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.draft import ContinuousPairRollout
+    from paper_2604_26779_amd.session import VerifySession
+    rng = np.random.default_rng(21)
+    for B, n_seqs, p_change, p_live in ((1, 3, 1.0, 1.0), (7, 40, 0.5, 0.7), (300, 900, 0.3, 0.5), (513, 600, 0.0, 1.0)):
+        before = rng.permutation(n_seqs)[:B].astype(np.int32)
+        after = before.copy()
+        spare = [s for s in range(n_seqs) if s not in set(before.tolist())]
+        for b in range(B):
+            if spare and rng.random() < p_change:
+                after[b] = spare.pop()
+        active = (rng.random(B) < p_live).astype(np.int32)
+        prev = rng.integers(0, 1 << 20, size=n_seqs).astype(np.int32)
+        first = rng.integers(0, 1 << 20, size=n_seqs).astype(np.int32)
+        pending = rng.integers(0, 1 << 20, size=(B, 2)).astype(np.int32)
+        want = pending.copy()
+        oro.backfill_pending(want, before, after, active, prev, first)
+        d = lambda a: torch.from_numpy(a).cuda()
+        d_pending = d(pending)
+        sv.spec_rollout_pending(B, d(before), d(after), d(active), d(prev), d(first), d_pending)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_pending.cpu().numpy(), want)
+
+    cfg_t, cfg_d = si.MODELS["tiny_fp32"], si.MODELS["draft_tiny_fp32"]
+    slots, n_seqs, k = 5, 13, 3
+    ctx0 = rng.integers(2, 40, size=n_seqs).astype(np.int64)
+    n_pages = 160
+    tsess = VerifySession(cfg_t, {n: t.cuda() for n, t in si.make_weights(cfg_t, seed=5).items()}, max_seqs=n_seqs, max_ctx_len=256,
+                          n_pages=n_pages)
+    dsess = VerifySession(cfg_d, {n: t.cuda() for n, t in si.make_weights(cfg_d, seed=6).items()}, max_seqs=n_seqs, max_ctx_len=256,
+                          n_pages=n_pages)
+    tsess.pool.normal_()
+    dsess.pool.normal_()
+    at = dat = 0
+    for s in range(n_seqs):                               # prompts cached: the draft's cache one position behind
+        need, dneed = -(-int(ctx0[s]) // si.PAGE_SIZE), -(-int(ctx0[s] - 1) // si.PAGE_SIZE)
+        tsess.assign(s, int(ctx0[s]), list(range(at, at + need)))
+        dsess.assign(s, int(ctx0[s]) - 1, list(range(dat, dat + dneed)))
+        at += need
+        dat += dneed
+    target = rng.integers(1, 18, size=n_seqs).astype(np.int32)
+    prev = torch.from_numpy(rng.integers(0, cfg_t["vocab"], size=n_seqs).astype(np.int32))
+    first = torch.from_numpy(rng.integers(0, cfg_t["vocab"], size=n_seqs).astype(np.int32))
+    roll = ContinuousPairRollout(tsess, dsess, slots, k, torch.arange(slots, dtype=torch.int32), torch.from_numpy(target),
+                                 torch.arange(slots, n_seqs, dtype=torch.int32), prev, first)
+    live = torch.zeros(1, dtype=torch.int32, device="cuda")
+    steps = 0
+    while steps < 200:
+        roll.run(1, 1.0, 77, steps, live_out=live)
+        steps += 1
+        torch.cuda.synchronize()
+        ts, ds = tsess.state(), dsess.state()
+        slot_seq, active = roll.slot_seq.cpu().numpy(), roll.active.cpu().numpy()
+        for b in range(slots):
+            s = int(slot_seq[b])
+            if active[b]:
+                assert ds["ctx_len"][s] == ts["ctx_len"][s] - 1, (steps, b, s)
+                assert list(roll.pending[b].cpu().numpy())[1] == int(roll.tokens[b, 0].item())
+            else:
+                assert ts["ctx_len"][s] == 0 and ds["ctx_len"][s] == 0
+        if int(live.item()) == 0:
+            break
+    assert int(live.item()) == 0 and int(roll.produced.item()) == int(target.sum())
+    assert np.array_equal(roll.gen_len.cpu().numpy(), target) and int(roll.queue_head.item()) == n_seqs - slots
+    for st in (tsess.state(), dsess.state()):
+        assert np.all(st["ctx_len"][:n_seqs] == 0) and np.all(st["n_pages"][:n_seqs] == 0) and len(st["free_stack"]) == n_pages
+    print("pair rollout: %d slots, %d sequences, drained in %d steps, %d tokens" % (slots, n_seqs, steps, int(roll.produced.item())))
+    tsess.close()
+    dsess.close()
