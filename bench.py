@@ -201,6 +201,60 @@ def run_continuous(args, wl, sv, torch):
     print(json.dumps(out))
 
 
+def run_continuous_pair(args, wl, sv, torch):
+    """The continuous rollout with the draft model as drafter: `slots` batch slots over B sequences, long-tailed response
+    lengths; timed from the first step until every sequence has finished (fixed batch: idle slots ride along)."""
+    import numpy as np
+
+    import synth_inputs as si
+    from paper_2604_26779_amd.draft import ContinuousPairRollout
+    n_seqs, slots, k = wl.B, wl.wl["slots"], wl.k
+    target = si.response_lengths(wl.wl, wl.seed)
+    max_steps = int(target.sum())
+    g = torch.Generator(device="cuda")
+    g.manual_seed(int(wl.seed) + 9)
+    prev = torch.randint(0, wl.cfg["vocab"], (n_seqs,), generator=g, device="cuda", dtype=torch.int32)
+    first = torch.from_numpy(wl.batch["tokens0"].astype("int32")).cuda()
+    chunk = 16
+    results = {}
+    for mode in ("warm-up", "timed"):
+        wl.restore()
+        roll = ContinuousPairRollout(wl.sess, wl.dsess, slots, k, torch.arange(slots, dtype=torch.int32), torch.from_numpy(target),
+                                     torch.arange(slots, n_seqs, dtype=torch.int32), prev, first)
+        live = torch.zeros(max_steps + chunk, dtype=torch.int32, device="cuda")
+        acc = torch.zeros((max_steps + chunk, slots), dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        steps = 0
+        while steps < max_steps:                                # the host looks at the live count every `chunk` steps
+            roll.run(chunk, wl.wl["temperature"], wl.seed, 9000 + steps, live[steps:steps + chunk], acc[steps:steps + chunk])
+            steps += chunk
+            if int(live[steps - 1].item()) == 0:
+                break
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        live_h = live[:steps].cpu().numpy()
+        used = int(np.argmax(live_h == 0)) + 1 if (live_h == 0).any() else steps
+        results[mode] = dict(dt=dt, steps=steps, used=used, live=live_h, produced=int(roll.produced.item()),
+                             alpha=float((acc[:used] + 1).float().mean().item()))
+    r = results["timed"]
+    out = {
+        "metric": "accepted tokens/sec/GPU, 8B-shaped verify step k=3; % of HBM/MFMA roofline",
+        "value": round(r["produced"] / r["dt"], 1), "unit": "accepted tokens/s", "n_gpus": 1, "steps": r["steps"], "warmup": 0,
+        "ms_per_step": round(1e3 * r["dt"] / r["steps"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "slots": slots, "sequences": n_seqs, "k": k, "ctx_tokens": int(wl.ctx_len.sum()),
+                   "model": wl.wl["model"], "draft_model": wl.wl["draft_model"], "page_size": 16, "pages": "shuffled"},
+        "continuous_rollout": {
+            "response_tokens": r["produced"], "response_len_min_median_max": [int(target.min()), int(np.median(target)), int(target.max())],
+            "steps_until_drained": r["used"], "mean_live_slot_fraction": round(float(r["live"][:r["used"]].mean()) / slots, 3),
+            "mean_acceptance_length_over_all_slots": round(r["alpha"], 3),
+            "host_syncs": "one every %d steps (live-slot count)" % chunk},
+        "roofline": None,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,6 +286,9 @@ def main():
 
     if args.k is not None:
         si.WORKLOADS[args.workload] = dict(si.WORKLOADS[args.workload], k=args.k)
+    if "slots" in si.WORKLOADS[args.workload] and "draft_model" in si.WORKLOADS[args.workload]:
+        run_continuous_pair(args, DraftPairWorkload(args.workload), sv, torch)
+        return
     if "slots" in si.WORKLOADS[args.workload]:
         run_continuous(args, DeviceWorkload(args.workload), sv, torch)
         return

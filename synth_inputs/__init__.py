@@ -109,6 +109,8 @@ WORKLOADS["llama8b_kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_
 WORKLOADS["small_bf16_w8kv8_b5_k3"] = dict(WORKLOADS["small_bf16_b5_k3"], model="small_bf16_w8kv8")
 WORKLOADS["llama8b_w8kv8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8kv8")
 WORKLOADS["llama8b_w8_b32_ctx1k-8k_k3"] = dict(WORKLOADS["llama8b_b32_ctx1k-8k_k3"], model="llama8b_bf16_w8")
+# the same continuous rollout driven by the single-layer draft model instead of the n-gram drafter
+WORKLOADS["rollout_pair_b32_q32_ctx1k-8k_k3"] = dict(WORKLOADS["rollout_b32_q32_ctx1k-8k_k3"], draft_model="draft1l_8b_bf16", noise_std=0.0)
 WORKLOADS["rollout_w8kv8_b32_q32_ctx1k-8k_k3"] = dict(WORKLOADS["rollout_b32_q32_ctx1k-8k_k3"], model="llama8b_bf16_w8kv8")
 WORKLOADS["draft_pair_w8kv8_b64_ctx4096_k5"] = dict(WORKLOADS["draft_pair_b64_ctx4096_k5"], model="llama8b_bf16_w8kv8",
                                                     draft_model="draft1l_8b_bf16_w8")
