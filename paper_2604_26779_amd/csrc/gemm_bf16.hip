@@ -456,6 +456,37 @@ __global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kerne
             }
         }
         return;
+    } else if constexpr (EPI == GEMM_EPI_SWIGLU && WM == 1) {
+        // 256-column tile of the 1 x 4 arrangement (each wavefront: all MB row blocks, gate and up of 32 hidden channels):
+        // the same transpose through LDS, one row block (32 rows x 128 channels) at a time.
+        static_assert(EPI != GEMM_EPI_SWIGLU || WM != 1 || NBW == 2, "fused SwiGLU needs two column blocks per wavefront");
+        float* tile = (float*)lds;                              // [32 rows][129]
+        uint4* xo = (uint4*)out;
+#pragma unroll
+        for (int i = 0; i < MBW; ++i) {
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float g = acc[i][0][r], u = acc[i][NBW - 1][r];
+                if constexpr (W8) {
+                    g *= wsc[0];
+                    u *= wsc[NBW - 1];
+                }
+                const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                tile[row * 129 + np * 32 + (lane & 31)] = g / (1.0f + __expf(-g)) * u;
+            }
+            __syncthreads();
+            for (int e = threadIdx.x; e < 32 * 16; e += GEMM_THREADS) {
+                const int row = e >> 4, g8 = e & 15;
+                const int m = (mblk0 + i) * 32 + row, f = bx * 128 + g8 * 8;
+                if (m >= M || f >= N / 2) continue;
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = tile[row * 129 + g8 * 8 + j];
+                xp_store8(xo, m, f, mb_pad, v);
+            }
+        }
+        return;
     } else if constexpr (EPI == GEMM_EPI_SWIGLU) {
         // The weights of the gate/up projection are tiled with gate and up column blocks interleaved,
         // so this wavefront's two accumulators hold gate and up of the same 32 hidden channels:
@@ -624,10 +655,18 @@ spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, co
     // distance between the groups' matrices in 16-byte words (group_stride: bf16 elements, or bytes of a whole 8-bit region,
     // codes and scales, so that the scales of group g sit g * stride behind those of group 0 as well)
     const int64_t stride16 = W0.w8 ? group_stride / 16 : group_stride / 8;
-#define SPEC_GROUPED_LAUNCH(E, W8V) gemm_bf16_kernel<2, 2, 2, E, true, 2, W8V><<<grid, GEMM_THREADS, 0, s>>>( \
+    // Two tile shapes of 64 rows: 128 columns with the wavefronts 2 x 2, or 256 columns with the wavefronts 1 x 4 (each
+    // its own two column blocks: no weight fragment is fetched twice and the activation slab serves twice the columns,
+    // which is what the expert GEMMs - few rows, all weights touched - are bound by).
+    const bool wide = tune("moe_wide_tiles") != 0 && W0.n_blocks % 8 == 0;
+    if (wide) grid.x = (unsigned)cdiv(W0.n_blocks, 8);
+#define SPEC_GROUPED_LAUNCH(WMV, E, W8V) gemm_bf16_kernel<2, WMV, 2, E, true, 2, W8V><<<grid, GEMM_THREADS, 0, s>>>( \
         wp, xp, out, W0.n_blocks, W0.k_steps, W0.k_steps, rows_pad / 32, rows_pad, W0.N, ldo, 0, tiles, stride16, W0.scale)
-    if (swiglu) { if (W0.w8) SPEC_GROUPED_LAUNCH(GEMM_EPI_SWIGLU, true); else SPEC_GROUPED_LAUNCH(GEMM_EPI_SWIGLU, false); }
-    else { if (W0.w8) SPEC_GROUPED_LAUNCH(GEMM_EPI_PLAIN, true); else SPEC_GROUPED_LAUNCH(GEMM_EPI_PLAIN, false); }
+#define SPEC_GROUPED_LAUNCH_E(E) do { \
+        if (wide) { if (W0.w8) SPEC_GROUPED_LAUNCH(1, E, true); else SPEC_GROUPED_LAUNCH(1, E, false); } \
+        else { if (W0.w8) SPEC_GROUPED_LAUNCH(2, E, true); else SPEC_GROUPED_LAUNCH(2, E, false); } } while (0)
+    if (swiglu) SPEC_GROUPED_LAUNCH_E(GEMM_EPI_SWIGLU); else SPEC_GROUPED_LAUNCH_E(GEMM_EPI_PLAIN);
+#undef SPEC_GROUPED_LAUNCH_E
 #undef SPEC_GROUPED_LAUNCH
     SPEC_LAUNCH_CHECK("gemm_bf16_kernel (grouped)");
     return SPEC_OK;
