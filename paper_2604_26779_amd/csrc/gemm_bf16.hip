@@ -199,7 +199,7 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | 0x70 | 0xF00 | ((n >> 4) << 1
 // fragment is widened to bf16 in registers right before its MFMAs (exact) and the output column's scale is applied to
 // the accumulators in the epilogue.
 template <int MB, int WM, int WD, int EPI, bool GROUPED = false, int NBW_T = WM, bool W8 = false>
-__global__ __launch_bounds__(GEMM_THREADS, MB >= 6 ? 1 : 2) void gemm_bf16_kernel(
+__global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB == 4 && WM == 1)) ? 1 : 2) void gemm_bf16_kernel(
     const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
     int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride,
     const int32_t* __restrict__ tiles = nullptr, int64_t w_group_stride = 0, const float* __restrict__ wscale = nullptr)
@@ -558,7 +558,7 @@ int gemm_mb_pad(int M)
     return (int)cdiv(nb, mb) * mb;
 }
 
-struct GemmShape { int mb, tile_nb, kunit, m_tiles, n_tiles; };
+struct GemmShape { int mb, tile_nb, kunit, m_tiles, n_tiles; bool wide = false; };
 static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
 {
     GemmShape g;
@@ -580,6 +580,12 @@ static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
     // counts), 4 for the others
     g.kunit = g.mb % 2 == 0 ? GEMM_KS * 2 : GEMM_KUNIT;
     g.m_tiles = pad / g.mb; g.n_tiles = (int)cdiv(W.n_blocks, 4);
+    // One tile of 64 or 128 rows, plain epilogue, K unsplit because the columns alone give enough workgroups (the LM head): 256-column
+    // tiles with the wavefronts 1 x 4 - no weight fragment fetched twice, the activation slab serves twice the columns.
+    // (With K split to make up the workgroups the extra slices cost the consumers what the GEMM gains.)
+    if ((g.mb == 4 || g.mb == 2) && g.m_tiles == 1 && !fused_swiglu && tune("gemm_wide4") > 0 && W.n_blocks % 8 == 0 && W.n_blocks / 8 >= tune("gemm_wide4")) {
+        g.wide = true; g.tile_nb = 8; g.n_tiles = W.n_blocks / 8; g.kunit = GEMM_KS * 2;
+    }
     return g;
 }
 
@@ -611,7 +617,7 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
     const u32x4_t* wp = (const u32x4_t*)W.data;
     const u32x4_t* xp = (const u32x4_t*)Xp;
     if (swiglu && !gemm_can_fuse_swiglu(W, M, splits)) { set_error("gemm: SwiGLU cannot be fused for this shape"); return SPEC_EUNSUPPORTED; }
-#define SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, W8V) gemm_bf16_kernel<MBV, WMV, WDV, E, false, WMV, W8V><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
+#define SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, W8V) gemm_bf16_kernel<MBV, WMV, WDV, E, false, (MBV % 2 == 0 && WMV == 1) ? 2 : WMV, W8V><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
 #define SPEC_GEMM_LAUNCH(MBV, WMV, WDV, E) do { if (W.w8) SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, true); else SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, false); } while (0)
     // the 256-column tile: two LDS slabs of MB * 8 KiB as dynamic shared memory (beyond the 64 KiB a kernel gets by default)
 #define SPEC_GEMM_LAUNCH_BIG_W(MBV, E, W8V) do { \
@@ -628,11 +634,19 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
 #define SPEC_GEMM_LAUNCH_BIG(MBV, E) do { if (W.w8) SPEC_GEMM_LAUNCH_BIG_W(MBV, E, true); else SPEC_GEMM_LAUNCH_BIG_W(MBV, E, false); } while (0)
     switch (mb) {
         case 1: SPEC_GEMM_LAUNCH(1, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
-        case 2: if (swiglu) SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_PLAIN); break;
+        case 2:
+            if (g.wide) SPEC_GEMM_LAUNCH(2, 1, 2, GEMM_EPI_PLAIN);
+            else if (swiglu) SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_SWIGLU);
+            else SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_PLAIN);
+            break;
         case 3: SPEC_GEMM_LAUNCH(3, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
         case 6: if (swiglu) SPEC_GEMM_LAUNCH_BIG(6, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH_BIG(6, GEMM_EPI_PLAIN); break;
         case 8: if (swiglu) SPEC_GEMM_LAUNCH_BIG(8, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH_BIG(8, GEMM_EPI_PLAIN); break;
-        default: if (swiglu) SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_PLAIN); break;
+        default:
+            if (g.wide) SPEC_GEMM_LAUNCH(4, 1, 2, GEMM_EPI_PLAIN);
+            else if (swiglu) SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_SWIGLU);
+            else SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_PLAIN);
+            break;
     }
 #undef SPEC_GEMM_LAUNCH_BIG
 #undef SPEC_GEMM_LAUNCH_BIG_W

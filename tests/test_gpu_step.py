@@ -429,3 +429,22 @@ def test_bf16_attention_long_chunks_at_their_boundaries(chunk_pages):
         sv.spec_tune_set("attn_chunk_pages", 0)
     print("chunk %d pages: logits max abs err %.3e" % (chunk_pages, max_err))
     assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("B,k,w8", [(32, 3, False), (25, 3, True), (13, 7, False), (16, 3, False), (9, 4, True)])
+def test_bf16_128x256_tiles_for_single_tile_gemms(B, k, w8):
+    """The 128-row x 256-column tile with the wavefronts 1 x 4 (taken by the LM head of large vocabularies), forced here
+    onto every plain-epilogue GEMM of the small model: M = 128, 100 and 104 rows (and 64 x 256 tiles: M = 64, 45), column counts 1536, 512 and 1024,
+    K split and unsplit, bf16 and 8-bit matrices."""
+    from paper_2604_26779_amd import binding as sv
+    before = sv.spec_tune_get("gemm_wide4")
+    sv.spec_tune_set("gemm_wide4", 1)
+    try:
+        rng = np.random.default_rng(B + k)
+        ctx = [int(c) for c in rng.integers(3, 150, size=B)]
+        extra = dict(w_dtype="fp8_e4m3") if w8 else {}
+        ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1024, **extra)
+    finally:
+        sv.spec_tune_set("gemm_wide4", before)
+    print("128 x 256 tiles, B=%d k=%d (M=%d), 8-bit matrices %s: logits max abs err %.3e" % (B, k, B * (k + 1), w8, max_err))
+    assert ok, (max_err, worst)
