@@ -585,6 +585,14 @@ static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
     // (With K split to make up the workgroups the extra slices cost the consumers what the GEMM gains.)
     if ((g.mb == 4 || g.mb == 2) && g.m_tiles == 1 && !fused_swiglu && tune("gemm_wide4") > 0 && W.n_blocks % 8 == 0 && W.n_blocks / 8 >= tune("gemm_wide4")) {
         g.wide = true; g.tile_nb = 8; g.n_tiles = W.n_blocks / 8; g.kunit = GEMM_KS * 2;
+        return g;
+    }
+    // 97..128 rows: two tiles of 64 rows x 256 columns (wavefronts 1 x 4) instead of one of 128 x 128 (2 x 2): the same
+    // number of workgroups and K splits, the same MFMAs per workgroup and slab, but no weight fragment fetched twice and half
+    // the activation slab per workgroup; the second row tile's weights come from L2 (the two are neighbours on one XCD).
+    if (g.mb == 4 && g.m_tiles == 1 && tune("gemm_split_rows") != 0 && W.n_blocks % 8 == 0) {
+        g.mb = 2; g.m_tiles = 2; g.wide = true; g.tile_nb = 8; g.n_tiles = W.n_blocks / 8; g.kunit = GEMM_KS * 2;
+        return g;
     }
     return g;
 }
@@ -635,7 +643,8 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
     switch (mb) {
         case 1: SPEC_GEMM_LAUNCH(1, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
         case 2:
-            if (g.wide) SPEC_GEMM_LAUNCH(2, 1, 2, GEMM_EPI_PLAIN);
+            if (g.wide && swiglu) SPEC_GEMM_LAUNCH(2, 1, 2, GEMM_EPI_SWIGLU);
+            else if (g.wide) SPEC_GEMM_LAUNCH(2, 1, 2, GEMM_EPI_PLAIN);
             else if (swiglu) SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_SWIGLU);
             else SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_PLAIN);
             break;

@@ -181,7 +181,7 @@ def test_kv8_every_code_is_read_exactly():
 W8 = dict(w_dtype="fp8_e4m3")
 
 
-@pytest.mark.parametrize("B,k,kv8", [(1, 0, False), (1, 7, True), (16, 3, True), (24, 3, False), (40, 3, True), (33, 7, False), (9, 2, True)])
+@pytest.mark.parametrize("B,k,kv8", [(1, 0, False), (1, 7, True), (16, 3, True), (24, 3, False), (32, 3, True), (40, 3, True), (33, 7, False), (9, 2, True)])
 def test_w8_row_block_counts(B, k, kv8):
     """E4M3 matrices with one scale per output row (the codes are inputs, the oracle multiplies by the dequantised
     matrix): M = 1 .. 264 rows, i.e. every row-block count of the 128-column tile (fused and unfused SwiGLU, K split

@@ -431,6 +431,24 @@ def test_bf16_attention_long_chunks_at_their_boundaries(chunk_pages):
     assert ok, (max_err, worst)
 
 
+@pytest.mark.parametrize("split_rows", [0, 1])
+def test_bf16_128_rows_as_one_tile_or_two(split_rows):
+    """GEMMs of 97..128 rows run as two 64-row x 256-column tiles per column stripe (the default) or as one 128 x 128
+    tile: both ways, M = 128 and a ragged 101, fused SwiGLU and K-split projections."""
+    from paper_2604_26779_amd import binding as sv
+    before = sv.spec_tune_get("gemm_split_rows")
+    sv.spec_tune_set("gemm_split_rows", split_rows)
+    try:
+        for B, k in ((32, 3), (101, 0)):
+            rng = np.random.default_rng(B + k)
+            ctx = [int(c) for c in rng.integers(3, 150, size=B)]
+            ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000)
+            print("split rows %d, B=%d k=%d: logits max abs err %.3e" % (split_rows, B, k, max_err))
+            assert ok, (max_err, worst)
+    finally:
+        sv.spec_tune_set("gemm_split_rows", before)
+
+
 @pytest.mark.parametrize("B,k,w8", [(32, 3, False), (25, 3, True), (13, 7, False), (16, 3, False), (9, 4, True)])
 def test_bf16_128x256_tiles_for_single_tile_gemms(B, k, w8):
     """The 128-row x 256-column tile with the wavefronts 1 x 4 (taken by the LM head of large vocabularies), forced here
