@@ -1,10 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the verify step (forward -> rejection sampling -> KV commit) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--no-graph]
 
 One "step" is one pass of the whole hot path over one synthetic batch that is resident in HBM
-before timing starts.  Prints ONE JSON line: accepted tokens/s (whole job = this one GPU),
+before timing starts.  The K timed steps are recorded once into a HIP graph and its replay is timed
+(--no-graph: one host launch per kernel; workloads with a draft model default to that).  Prints ONE JSON line: accepted tokens/s (whole job = this one GPU),
 ms/step, the roofline object of the dominant kernel (HIP-event timing of every kernel class over
 a second, instrumented run of the same K steps) and the CPU oracle timed on a bounded sample.
 """
@@ -264,7 +265,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=6)
     ap.add_argument("--rollout-steps", type=int, default=8, help="draft+target pair: consecutive steps of the sustained run")
-    ap.add_argument("--graph", action="store_true", help="record the K steps into a HIP graph and time its replay (default: one host launch per kernel)")
+    ap.add_argument("--graph", action="store_true", help="record the K timed steps into a HIP graph and time its replay (the default for the single-model workloads)")
+    ap.add_argument("--no-graph", action="store_true", help="one host launch per kernel in the timed region")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch parameter (repeatable)")
     ap.add_argument("--k", type=int, default=None, help="draft length instead of the workload's own (the draft-length sweep of Table 4)")
     args = ap.parse_args()
@@ -305,6 +307,7 @@ def main():
     run_steps(wl, sv, torch, W, accept, 0)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    args.graph = (args.graph or not pair) and not args.no_graph
     if not args.graph:
         t0 = time.perf_counter()
         ev0.record()
