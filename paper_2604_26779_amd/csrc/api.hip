@@ -31,7 +31,7 @@ static std::map<std::string, int>& tune_table()
         {"fuse_swiglu", 1},        // 1: silu(gate) * up in the gate/up projection's epilogue (unsplit K, even row blocks)
         {"attn_row_blocks", 0},    // most 16-row blocks per attention workgroup (1..4; 0 = up to 4, groups as equal as possible)
         {"gemm_max_mb", 4},        // 32-row blocks per GEMM tile (1..4): smaller tiles = more workgroups, weights read once per tile
-        {"gemm_split_rows", 1},     // 1: GEMMs of 97..128 rows run as two 64-row x 256-column tiles per column stripe
+        {"gemm_split_rows", 2},     // GEMMs of up to this many 128-row tiles (97..256 rows at 2) run as 64-row x 256-column tiles instead (0 = never)
         {"gemm_wide4", 400},        // single-tile 128-row GEMMs with a plain epilogue take 128 x 256 tiles from this many such tiles on (0 = never)
         {"moe_wide_tiles", 1},      // grouped expert GEMMs: 64 x 256 tiles, wavefronts 1 x 4 (0: 64 x 128, wavefronts 2 x 2)
         {"gemm_big_min_blocks", 6}, // from this many 32-row blocks on, a GEMM may take 192/256-row x 256-column tiles (0 = never)

@@ -590,8 +590,10 @@ static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
     // 97..128 rows: two tiles of 64 rows x 256 columns (wavefronts 1 x 4) instead of one of 128 x 128 (2 x 2): the same
     // number of workgroups and K splits, the same MFMAs per workgroup and slab, but no weight fragment fetched twice and half
     // the activation slab per workgroup; the second row tile's weights come from L2 (the two are neighbours on one XCD).
-    if (g.mb == 4 && g.m_tiles == 1 && tune("gemm_split_rows") != 0 && W.n_blocks % 8 == 0) {
-        g.mb = 2; g.m_tiles = 2; g.wide = true; g.tile_nb = 8; g.n_tiles = W.n_blocks / 8; g.kunit = GEMM_KS * 2;
+    // The same holds for up to gemm_split_rows 128-row tiles (129..256 rows at 2); a 64-row tile that would hold padding
+    // only is not launched.
+    if (g.mb == 4 && g.m_tiles <= tune("gemm_split_rows") && W.n_blocks % 8 == 0) {
+        g.mb = 2; g.m_tiles = (int)cdiv(cdiv(M, 32), 2); g.wide = true; g.tile_nb = 8; g.n_tiles = W.n_blocks / 8; g.kunit = GEMM_KS * 2;
         return g;
     }
     return g;

@@ -433,8 +433,8 @@ def test_bf16_attention_long_chunks_at_their_boundaries(chunk_pages):
 
 @pytest.mark.parametrize("split_rows", [0, 1])
 def test_bf16_128_rows_as_one_tile_or_two(split_rows):
-    """GEMMs of 97..128 rows run as two 64-row x 256-column tiles per column stripe (the default) or as one 128 x 128
-    tile: both ways, M = 128 and a ragged 101, fused SwiGLU and K-split projections."""
+    """GEMMs of 97..128 rows run as two 64-row x 256-column tiles per column stripe (the default does so up to 256 rows)
+    or as one 128 x 128 tile: both ways, M = 128 and a ragged 101, fused SwiGLU and K-split projections."""
     from paper_2604_26779_amd import binding as sv
     before = sv.spec_tune_get("gemm_split_rows")
     sv.spec_tune_set("gemm_split_rows", split_rows)
@@ -447,6 +447,25 @@ def test_bf16_128_rows_as_one_tile_or_two(split_rows):
             assert ok, (max_err, worst)
     finally:
         sv.spec_tune_set("gemm_split_rows", before)
+
+
+@pytest.mark.parametrize("B,k,w8", [(40, 3, False), (32, 5, False), (64, 3, False), (50, 3, True), (43, 4, False), (33, 3, True)])
+def test_bf16_129_to_256_rows_as_64_row_tiles(B, k, w8):
+    """GEMMs of 129..256 rows as three or four 64-row x 256-column tiles per column stripe (gemm_split_rows = 2, the default;
+    test_bf16_128_rows_as_one_tile_or_two and the 8B-shape sweeps cover the 128 x 128 tiles) instead of two 128 x 128 tiles: M = 160 (the third tile half padding), 192 (no fourth tile), 256, 200, 215 and 132, fused
+    SwiGLU and K-split projections, bf16 and 8-bit matrices."""
+    from paper_2604_26779_amd import binding as sv
+    before = sv.spec_tune_get("gemm_split_rows")
+    sv.spec_tune_set("gemm_split_rows", 2)
+    try:
+        rng = np.random.default_rng(B + k)
+        ctx = [int(c) for c in rng.integers(3, 150, size=B)]
+        extra = dict(w_dtype="fp8_e4m3") if w8 else {}
+        ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000, **extra)
+    finally:
+        sv.spec_tune_set("gemm_split_rows", before)
+    print("64-row tiles, B=%d k=%d (M=%d), 8-bit matrices %s: logits max abs err %.3e" % (B, k, B * (k + 1), w8, max_err))
+    assert ok, (max_err, worst)
 
 
 @pytest.mark.parametrize("B,k,w8", [(32, 3, False), (25, 3, True), (13, 7, False), (16, 3, False), (9, 4, True)])
