@@ -32,6 +32,8 @@ static std::map<std::string, int>& tune_table()
         {"attn_row_blocks", 0},    // most 16-row blocks per attention workgroup (1..4; 0 = up to 4, groups as equal as possible)
         {"gemm_max_mb", 4},        // 32-row blocks per GEMM tile (1..4): smaller tiles = more workgroups, weights read once per tile
         {"gemm_split_rows", 2},     // GEMMs of up to this many 128-row tiles (97..256 rows at 2) run as 64-row x 256-column tiles instead (0 = never)
+        {"gemm_big_min_tiles", 200}, // a GEMM with at least this many 256-column tiles takes them without further conditions
+        {"gemm_tiles_96", 1},       // 129..256 rows, fused gate/up projection: two 96- or 128-row x 256-column tiles per column stripe instead of three or four 64-row ones
         {"gemm_wide4", 400},        // single-tile 128-row GEMMs with a plain epilogue take 128 x 256 tiles from this many such tiles on (0 = never)
         {"moe_wide_tiles", 1},      // grouped expert GEMMs: 64 x 256 tiles, wavefronts 1 x 4 (0: 64 x 128, wavefronts 2 x 2)
         {"gemm_big_min_blocks", 6}, // from this many 32-row blocks on, a GEMM may take 192/256-row x 256-column tiles (0 = never)

@@ -199,7 +199,7 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | 0x70 | 0xF00 | ((n >> 4) << 1
 // fragment is widened to bf16 in registers right before its MFMAs (exact) and the output column's scale is applied to
 // the accumulators in the epilogue.
 template <int MB, int WM, int WD, int EPI, bool GROUPED = false, int NBW_T = WM, bool W8 = false>
-__global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB == 4 && WM == 1)) ? 1 : 2) void gemm_bf16_kernel(
+__global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NBW_T == 2)) ? 1 : 2) void gemm_bf16_kernel(
     const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
     int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride,
     const int32_t* __restrict__ tiles = nullptr, int64_t w_group_stride = 0, const float* __restrict__ wscale = nullptr)
@@ -568,9 +568,10 @@ static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
         int64_t splits = tune("gemm_wg_target") / tiles;
         if (splits > W.k_steps / 32) splits = W.k_steps / 32;
         if (splits < 1) splits = 1;
-        if (tiles >= 200 || (!fused_swiglu && pad / big >= 2 && tiles * splits >= 192)) {
+        if (tiles >= tune("gemm_big_min_tiles") || (!fused_swiglu && pad / big >= 2 && tiles * splits >= 192)) {
             g.mb = big; g.tile_nb = 8; g.kunit = GEMM_KS * 2;
             g.m_tiles = pad / big; g.n_tiles = (int)cdiv(W.n_blocks, 8);
+            if (big == 8 && cdiv(M, 32) <= 6) g.mb = 6;                 // 161..192 rows: the one tile needs 6 row blocks only
             return g;
         }
     }
@@ -592,8 +593,13 @@ static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
     // the activation slab per workgroup; the second row tile's weights come from L2 (the two are neighbours on one XCD).
     // The same holds for up to gemm_split_rows 128-row tiles (129..256 rows at 2); a 64-row tile that would hold padding
     // only is not launched.
+    // 129..256 rows where K is not split (the fused gate/up projection): two tiles of 96 or 128 rows instead of three or four of
+    // 64 - 2 x 112 workgroups fit the chip at once, 3 x 112 and 4 x 112 do not.
     if (g.mb == 4 && g.m_tiles <= tune("gemm_split_rows") && W.n_blocks % 8 == 0) {
-        g.mb = 2; g.m_tiles = (int)cdiv(cdiv(M, 32), 2); g.wide = true; g.tile_nb = 8; g.n_tiles = W.n_blocks / 8; g.kunit = GEMM_KS * 2;
+        const int nb = (int)cdiv(M, 32);
+        if (fused_swiglu && nb >= 5 && tune("gemm_tiles_96") != 0) g.mb = nb <= 6 ? 3 : 4;
+        else g.mb = 2;
+        g.m_tiles = (int)cdiv(nb, g.mb); g.wide = true; g.tile_nb = 8; g.n_tiles = W.n_blocks / 8; g.kunit = GEMM_KS * 2;
         return g;
     }
     return g;
@@ -615,7 +621,7 @@ int gemm_pick_splits(const PackedW& W, int M, int forced)
 // out must hold splits * M * ldo floats; with swiglu (gate/up projection, splits == 1, an even number
 // of row blocks) out is instead the hi + lo operand buffer of silu(gate) * up, [N/2] channels wide.
 // Returns SPEC_EUNSUPPORTED (nothing launched) if swiglu is asked for a shape it cannot fuse.
-bool gemm_can_fuse_swiglu(const PackedW& W, int M, int splits) { return splits == 1 && gemm_shape(W, M, true).mb % 2 == 0; }
+bool gemm_can_fuse_swiglu(const PackedW& W, int M, int splits) { if (splits != 1) return false; const GemmShape g = gemm_shape(W, M, true); return g.mb % 2 == 0 || (g.wide && g.mb == 3); }
 
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s)
 {
@@ -628,6 +634,8 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
     const u32x4_t* xp = (const u32x4_t*)Xp;
     if (swiglu && !gemm_can_fuse_swiglu(W, M, splits)) { set_error("gemm: SwiGLU cannot be fused for this shape"); return SPEC_EUNSUPPORTED; }
 #define SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, W8V) gemm_bf16_kernel<MBV, WMV, WDV, E, false, (MBV % 2 == 0 && WMV == 1) ? 2 : WMV, W8V><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
+#define SPEC_GEMM_LAUNCH_96W(E, W8V) gemm_bf16_kernel<3, 1, 2, E, false, 2, W8V><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
+#define SPEC_GEMM_LAUNCH_96(E) do { if (W.w8) SPEC_GEMM_LAUNCH_96W(E, true); else SPEC_GEMM_LAUNCH_96W(E, false); } while (0)
 #define SPEC_GEMM_LAUNCH(MBV, WMV, WDV, E) do { if (W.w8) SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, true); else SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, false); } while (0)
     // the 256-column tile: two LDS slabs of MB * 8 KiB as dynamic shared memory (beyond the 64 KiB a kernel gets by default)
 #define SPEC_GEMM_LAUNCH_BIG_W(MBV, E, W8V) do { \
@@ -650,16 +658,23 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
             else if (swiglu) SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_SWIGLU);
             else SPEC_GEMM_LAUNCH(2, 2, 2, GEMM_EPI_PLAIN);
             break;
-        case 3: SPEC_GEMM_LAUNCH(3, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
+        case 3:
+            if (g.wide && swiglu) SPEC_GEMM_LAUNCH_96(GEMM_EPI_SWIGLU);
+            else if (g.wide) SPEC_GEMM_LAUNCH_96(GEMM_EPI_PLAIN);
+            else SPEC_GEMM_LAUNCH(3, 1, GEMM_WD, GEMM_EPI_PLAIN);
+            break;
         case 6: if (swiglu) SPEC_GEMM_LAUNCH_BIG(6, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH_BIG(6, GEMM_EPI_PLAIN); break;
         case 8: if (swiglu) SPEC_GEMM_LAUNCH_BIG(8, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH_BIG(8, GEMM_EPI_PLAIN); break;
         default:
-            if (g.wide) SPEC_GEMM_LAUNCH(4, 1, 2, GEMM_EPI_PLAIN);
+            if (g.wide && swiglu) SPEC_GEMM_LAUNCH(4, 1, 2, GEMM_EPI_SWIGLU);
+            else if (g.wide) SPEC_GEMM_LAUNCH(4, 1, 2, GEMM_EPI_PLAIN);
             else if (swiglu) SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_SWIGLU);
             else SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_PLAIN);
             break;
     }
 #undef SPEC_GEMM_LAUNCH_BIG
+#undef SPEC_GEMM_LAUNCH_96
+#undef SPEC_GEMM_LAUNCH_96W
 #undef SPEC_GEMM_LAUNCH_BIG_W
 #undef SPEC_GEMM_LAUNCH
 #undef SPEC_GEMM_LAUNCH_W

@@ -403,14 +403,16 @@ def test_bf16_large_row_tiles(B, k, big_from):
     264 (9 blocks -> two 6-block tiles, the second half empty), 192 (one 6-block tile), 200 (7 blocks -> one 8-block tile),
     384 (two 6-block tiles) and 240; column counts that are not multiples of 256, fused SwiGLU epilogue, split K."""
     from paper_2604_26779_amd import binding as sv
-    before = sv.spec_tune_get("gemm_big_min_blocks")
+    before = sv.spec_tune_get("gemm_big_min_blocks"), sv.spec_tune_get("gemm_big_min_tiles")
     sv.spec_tune_set("gemm_big_min_blocks", big_from)
+    sv.spec_tune_set("gemm_big_min_tiles", 1)                # the small model has far fewer column tiles than the policy asks for
     try:
         rng = np.random.default_rng(B * 10 + k)
         ctx = [int(c) for c in rng.integers(3, 120, size=B)]
         ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000)
     finally:
-        sv.spec_tune_set("gemm_big_min_blocks", before)
+        sv.spec_tune_set("gemm_big_min_blocks", before[0])
+        sv.spec_tune_set("gemm_big_min_tiles", before[1])
     print("B=%d k=%d (M=%d), big tiles from %d row blocks: logits max abs err %.3e" % (B, k, B * (k + 1), big_from, max_err))
     assert ok, (max_err, worst)
 
@@ -452,8 +454,8 @@ def test_bf16_128_rows_as_one_tile_or_two(split_rows):
 @pytest.mark.parametrize("B,k,w8", [(40, 3, False), (32, 5, False), (64, 3, False), (50, 3, True), (43, 4, False), (33, 3, True)])
 def test_bf16_129_to_256_rows_as_64_row_tiles(B, k, w8):
     """GEMMs of 129..256 rows as three or four 64-row x 256-column tiles per column stripe (gemm_split_rows = 2, the default;
-    test_bf16_128_rows_as_one_tile_or_two and the 8B-shape sweeps cover the 128 x 128 tiles) instead of two 128 x 128 tiles: M = 160 (the third tile half padding), 192 (no fourth tile), 256, 200, 215 and 132, fused
-    SwiGLU and K-split projections, bf16 and 8-bit matrices."""
+    test_bf16_128_rows_as_one_tile_or_two and the 8B-shape sweeps cover the 128 x 128 tiles) instead of two 128 x 128 tiles: M = 160 (the third tile half padding), 192 (no fourth tile), 256, 200, 215 and 132, K-split
+    projections; the fused gate/up projection as two 96- or 128-row x 256-column tiles; bf16 and 8-bit matrices."""
     from paper_2604_26779_amd import binding as sv
     before = sv.spec_tune_get("gemm_split_rows")
     sv.spec_tune_set("gemm_split_rows", 2)
