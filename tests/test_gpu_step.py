@@ -452,20 +452,23 @@ def test_bf16_128_rows_as_one_tile_or_two(split_rows):
 
 
 @pytest.mark.parametrize("B,k,w8", [(40, 3, False), (32, 5, False), (64, 3, False), (50, 3, True), (43, 4, False), (33, 3, True)])
-def test_bf16_129_to_256_rows_as_64_row_tiles(B, k, w8):
+@pytest.mark.parametrize("tiles96", [1, 0])
+def test_bf16_129_to_256_rows_as_64_row_tiles(B, k, w8, tiles96):
     """GEMMs of 129..256 rows as three or four 64-row x 256-column tiles per column stripe (gemm_split_rows = 2, the default;
     test_bf16_128_rows_as_one_tile_or_two and the 8B-shape sweeps cover the 128 x 128 tiles) instead of two 128 x 128 tiles: M = 160 (the third tile half padding), 192 (no fourth tile), 256, 200, 215 and 132, K-split
     projections; the fused gate/up projection as two 96- or 128-row x 256-column tiles; bf16 and 8-bit matrices."""
     from paper_2604_26779_amd import binding as sv
-    before = sv.spec_tune_get("gemm_split_rows")
+    before = sv.spec_tune_get("gemm_split_rows"), sv.spec_tune_get("gemm_tiles_96")
     sv.spec_tune_set("gemm_split_rows", 2)
+    sv.spec_tune_set("gemm_tiles_96", tiles96)              # 0: the fused projection in 64-row tiles as well
     try:
         rng = np.random.default_rng(B + k)
         ctx = [int(c) for c in rng.integers(3, 150, size=B)]
         extra = dict(w_dtype="fp8_e4m3") if w8 else {}
         ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k, vocab=1000, **extra)
     finally:
-        sv.spec_tune_set("gemm_split_rows", before)
+        sv.spec_tune_set("gemm_split_rows", before[0])
+        sv.spec_tune_set("gemm_tiles_96", before[1])
     print("64-row tiles, B=%d k=%d (M=%d), 8-bit matrices %s: logits max abs err %.3e" % (B, k, B * (k + 1), w8, max_err))
     assert ok, (max_err, worst)
 
