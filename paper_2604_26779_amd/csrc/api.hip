@@ -36,7 +36,7 @@ static std::map<std::string, int>& tune_table()
         {"gemm_tiles_96", 1},       // 129..256 rows, fused gate/up projection: two 96- or 128-row x 256-column tiles per column stripe instead of three or four 64-row ones
         {"gemm_wide4", 400},        // single-tile 128-row GEMMs with a plain epilogue take 128 x 256 tiles from this many such tiles on (0 = never)
         {"moe_wide_tiles", 1},      // grouped expert GEMMs: 64 x 256 tiles, wavefronts 1 x 4 (0: 64 x 128, wavefronts 2 x 2)
-        {"gemm_big_min_blocks", 6}, // from this many 32-row blocks on, a GEMM may take 192/256-row x 256-column tiles (0 = never)
+        {"gemm_big_min_blocks", 5}, // from this many 32-row blocks on, a GEMM may take 192/256-row x 256-column tiles (0 = never)
         {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
         {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
         {"attn_chunk_pages", 0},   // KV pages per attention workgroup (a multiple of 4 up to 256; 0 = by batch size and context bound)

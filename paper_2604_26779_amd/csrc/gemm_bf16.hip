@@ -538,7 +538,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
 
 // Tile shapes.  Up to 4 row blocks (128 rows) a launch has one kind of tile: MB = min(row blocks, gemm_max_mb) x 128
 // columns.  From gemm_big_min_blocks row blocks on (0 = never) the 256-column tile with 8 or 6 row blocks is available
-// too, and each GEMM takes it when it still fills the chip: at least 200 tiles, or - K split, two or more tiles of
+// too, and each GEMM takes it when it still fills the chip: at least gemm_big_min_tiles (200) tiles, or - K split, two or more tiles of
 // rows - at least 192 workgroups of 32 or more k-steps each (a 256 x 256 tile with a short K spends its time in prologue
 // and epilogue; with one tile of rows the extra split-K slices cost the consumers more than the GEMM gains; and a fused
 // SwiGLU epilogue cannot split K at all).  Both kinds read the same activation buffer, so its rows are padded
@@ -546,7 +546,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
 static int gemm_big_mb(int M)
 {
     const int nb = (int)cdiv(M, 32), from = tune("gemm_big_min_blocks");
-    if (from <= 0 || nb < from || nb < 6) return 0;
+    if (from <= 0 || nb < from || nb < 5) return 0;
     return cdiv(nb, 12) * 12 < cdiv(nb, 8) * 8 ? 6 : 8;
 }
 int gemm_mb(int M) { int mb = (int)cdiv(M, 32), cap = tune("gemm_max_mb"); cap = cap < 1 ? 1 : (cap > 4 ? 4 : cap); return mb > cap ? cap : mb; }
@@ -571,7 +571,7 @@ static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
         if (tiles >= tune("gemm_big_min_tiles") || (!fused_swiglu && pad / big >= 2 && tiles * splits >= 192)) {
             g.mb = big; g.tile_nb = 8; g.kunit = GEMM_KS * 2;
             g.m_tiles = pad / big; g.n_tiles = (int)cdiv(W.n_blocks, 8);
-            if (big == 8 && cdiv(M, 32) <= 6) g.mb = 6;                 // 161..192 rows: the one tile needs 6 row blocks only
+            if (big == 8 && cdiv(M, 32) <= 6) g.mb = 6;                 // 129..192 rows: the one tile needs 6 row blocks only
             return g;
         }
     }

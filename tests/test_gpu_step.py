@@ -397,11 +397,11 @@ def test_bf16_attention_reference_point_moves(case):
         assert ok, (max_err, worst)
 
 
-@pytest.mark.parametrize("B,k,big_from", [(64, 3, 8), (33, 7, 8), (12, 15, 6), (50, 3, 6), (96, 3, 8), (40, 5, 8)])
+@pytest.mark.parametrize("B,k,big_from", [(64, 3, 8), (33, 7, 8), (12, 15, 6), (50, 3, 6), (96, 3, 8), (40, 5, 8), (40, 3, 5), (33, 3, 5)])
 def test_bf16_large_row_tiles(B, k, big_from):
     """The 192- and 256-row x 256-column GEMM tiles (tuning parameter gemm_big_min_blocks): M = 256 (one 8-block tile),
     264 (9 blocks -> two 6-block tiles, the second half empty), 192 (one 6-block tile), 200 (7 blocks -> one 8-block tile),
-    384 (two 6-block tiles) and 240; column counts that are not multiples of 256, fused SwiGLU epilogue, split K."""
+    384 (two 6-block tiles), 240, and 160 and 132 (5 row blocks in one 6-block tile); column counts that are not multiples of 256, fused SwiGLU epilogue, split K."""
     from paper_2604_26779_amd import binding as sv
     before = sv.spec_tune_get("gemm_big_min_blocks"), sv.spec_tune_get("gemm_big_min_tiles")
     sv.spec_tune_set("gemm_big_min_blocks", big_from)
