@@ -233,6 +233,21 @@ spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const float* dev
                                void* dev_workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * spec_reject_sample for callers that cannot allocate device memory or carry a workspace along: code recorded under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic, random
+ * streams and outputs as spec_reject_sample, minus the workspace: the row statistics live in a buffer that is part
+ * of the loaded library (128 KiB of device memory per GPU, held until the process ends).  The call allocates and
+ * frees nothing.  Limit: B * (k + 1) <= 16384 logits rows, SPEC_EINVAL beyond (use spec_reject_sample then).
+ * All calls on one GPU share that buffer: calls whose work may overlap on one GPU (different streams, or graphs
+ * replayed concurrently) race on it; calls on one stream, or otherwise ordered, are safe, and nothing needs
+ * clearing between them (every row's statistics are written before they are read).  The buffer's address is looked
+ * up on the first call on each GPU (that first call should not itself be under capture).  Asynchronous on `stream`.
+ */
+spec_status spec_reject_sample_static(int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
+                                      const int32_t* dev_draft_tokens, float temperature, uint64_t seed, uint64_t step,
+                                      int32_t* dev_accept_len, int32_t* dev_out_tokens, float* dev_dbg, void* stream);
+
+/*
  * KV commit (keeps the accepted prefix; the paper leaves the cache handling to the serving engine).
  * For batch entry b with n = dev_accept_len[b] (values outside 0..k are clamped): positions
  * ctx..ctx+n stay, the new context length is ctx+n+1 (the drawn token is the next step's row 0 and

@@ -23,7 +23,7 @@ EXPORTS = [
     "spec_last_error", "spec_model_weight_count", "spec_model_create", "spec_model_destroy", "spec_kv_pool_bytes",
     "spec_kv_alloc", "spec_kv_free", "spec_kv_set_scales", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
-    "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample",
+    "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample", "spec_reject_sample_static",
     "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_rollout_pending", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_graph_capture_begin", "spec_graph_capture_end", "spec_graph_launch",
     "spec_graph_destroy", "spec_calib_read", "spec_calib_copy",
@@ -80,6 +80,7 @@ def lib():
             "spec_next_step_hidden": (i32, [i32, i32, i32, vp, vp, vp, vp]),
             "spec_sample_workspace_bytes": (sz, [i32, i32]),
             "spec_reject_sample": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp, sz, vp]),
+            "spec_reject_sample_static": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp]),
             "spec_commit_kv": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
             "spec_draft_sample": (i32, [i32, i32, vp, i64, f32, u64, u64, i32, vp, i32, vp, i32, vp, i64, vp]),
             "spec_kv_truncate": (i32, [vp, i32, vp, vp, i32, vp, vp]),
@@ -262,6 +263,11 @@ def spec_reject_sample(B, k, V, logits, q, draft_tokens, temperature, seed, step
     _check(lib().spec_reject_sample(B, k, V, _ptr(logits), _ptr(q), _ptr(draft_tokens), float(temperature),
                                     int(seed), int(step), _ptr(accept_len), _ptr(out_tokens), _ptr(dbg),
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def spec_reject_sample_static(B, k, V, logits, q, draft_tokens, temperature, seed, step, accept_len, out_tokens, dbg, stream=None):
+    _check(lib().spec_reject_sample_static(B, k, V, _ptr(logits), _ptr(q), _ptr(draft_tokens), float(temperature),
+                                           int(seed), int(step), _ptr(accept_len), _ptr(out_tokens), _ptr(dbg), _stream(stream)))
 
 
 def spec_commit_kv(kv, B, k, seq_ids, accept_len, new_ctx_len, commit_slots, stream=None):

@@ -8,6 +8,8 @@
 //      (residual row at the first rejection, bonus row after k acceptances).
 // Only the rows' statistics, the k probed q entries and one q row are read: (k+1+2) V floats
 // per sequence at most.
+#include <mutex>
+
 #include "common.h"
 
 namespace specv {
@@ -232,22 +234,20 @@ extern "C" size_t spec_sample_workspace_bytes(int32_t B, int32_t k)
     return specv::align_up((size_t)B * (size_t)(k + 1) * sizeof(float2), 256);
 }
 
-extern "C" spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
-                                          const int32_t* dev_draft_tokens, float temperature, uint64_t seed,
-                                          uint64_t step, int32_t* dev_accept_len, int32_t* dev_out_tokens,
-                                          float* dev_dbg, void* dev_workspace, size_t workspace_bytes, void* stream)
+namespace specv {
+
+// argument checks and the two launches shared by both entry points; stats: B * (k + 1) float2 of device memory
+static spec_status reject_sample_launch(const char* who, int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
+                                        const int32_t* dev_draft_tokens, float temperature, uint64_t seed, uint64_t step,
+                                        int32_t* dev_accept_len, int32_t* dev_out_tokens, float* dev_dbg, float2* stats, hipStream_t s)
 {
-    using namespace specv;
-    if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT || V < 1) { set_error("spec_reject_sample: B, k or V out of range"); return SPEC_EINVAL; }
-    if (!(temperature > 0.f)) { set_error("spec_reject_sample: temperature must be > 0"); return SPEC_EINVAL; }
-    if (step >= (1ull << 30)) { set_error("spec_reject_sample: step must be < 2^30"); return SPEC_EINVAL; }
-    if (!dev_logits || !dev_accept_len || !dev_out_tokens || !dev_workspace || (k > 0 && !dev_draft_tokens)) {
-        set_error("spec_reject_sample: null pointer"); return SPEC_EINVAL;
+    if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT || V < 1) { set_error("%s: B, k or V out of range", who); return SPEC_EINVAL; }
+    if (!(temperature > 0.f)) { set_error("%s: temperature must be > 0", who); return SPEC_EINVAL; }
+    if (step >= (1ull << 30)) { set_error("%s: step must be < 2^30", who); return SPEC_EINVAL; }
+    if (!dev_logits || !dev_accept_len || !dev_out_tokens || !stats || (k > 0 && !dev_draft_tokens)) {
+        set_error("%s: null pointer", who); return SPEC_EINVAL;
     }
-    if (workspace_bytes < spec_sample_workspace_bytes(B, k)) { set_error("spec_reject_sample: workspace too small"); return SPEC_EINVAL; }
-    hipStream_t s = (hipStream_t)stream;
     float inv_t = 1.0f / temperature;
-    float2* stats = (float2*)dev_workspace;
     prof_mark(PC_OTHER, s);
     row_stats_kernel<<<B * (k + 1), SAMP_THREADS, 0, s>>>(dev_logits, V, inv_t, stats);
     SPEC_LAUNCH_CHECK("row_stats_kernel");
@@ -258,6 +258,62 @@ extern "C" spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const
     SPEC_LAUNCH_CHECK("reject_sample_kernel");
     prof_mark(PC_SAMPLE_DRAW, s);
     return SPEC_OK;
+}
+
+// Row statistics of spec_reject_sample_static: device memory that exists from the moment the library is loaded, so
+// that entry point never allocates.  Every GPU holds its own copy at its own address; the array's name is only a
+// host-side handle, the address kernels are given comes from hipGetSymbolAddress with that GPU current.
+constexpr int SAMP_STATIC_ROWS = 16384;                 // B * (k + 1) at most: 128 KiB per GPU
+static __device__ __align__(256) float2 scratch[SAMP_STATIC_ROWS];
+constexpr int SAMP_MAX_DEVICES = 64;
+static float2* g_scratch_ptr[SAMP_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static spec_status static_scratch(float2** out)
+{
+    int dev = -1;
+    SPEC_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SAMP_MAX_DEVICES) { set_error("spec_reject_sample_static: device index %d is beyond %d", dev, SAMP_MAX_DEVICES - 1); return SPEC_EUNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { set_error("spec_reject_sample_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e)); return SPEC_EHIP; }
+        g_scratch_ptr[dev] = (float2*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SPEC_OK;
+}
+
+}  // namespace specv
+
+extern "C" spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
+                                          const int32_t* dev_draft_tokens, float temperature, uint64_t seed,
+                                          uint64_t step, int32_t* dev_accept_len, int32_t* dev_out_tokens,
+                                          float* dev_dbg, void* dev_workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace specv;
+    if (B >= 1 && k >= 0 && dev_workspace && workspace_bytes < spec_sample_workspace_bytes(B, k)) { set_error("spec_reject_sample: workspace too small"); return SPEC_EINVAL; }
+    return reject_sample_launch("spec_reject_sample", B, k, V, dev_logits, dev_q, dev_draft_tokens, temperature, seed, step, dev_accept_len,
+                                dev_out_tokens, dev_dbg, (float2*)dev_workspace, (hipStream_t)stream);
+}
+
+extern "C" spec_status spec_reject_sample_static(int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
+                                                 const int32_t* dev_draft_tokens, float temperature, uint64_t seed,
+                                                 uint64_t step, int32_t* dev_accept_len, int32_t* dev_out_tokens,
+                                                 float* dev_dbg, void* stream)
+{
+    using namespace specv;
+    if (B >= 1 && k >= 0 && k <= SPEC_MAX_DRAFT && (int64_t)B * (k + 1) > SAMP_STATIC_ROWS) {
+        set_error("spec_reject_sample_static: B * (k + 1) = %lld rows exceed the built-in scratch of %d rows (use spec_reject_sample with a workspace)",
+                  (long long)B * (k + 1), SAMP_STATIC_ROWS);
+        return SPEC_EINVAL;
+    }
+    float2* stats = nullptr;
+    spec_status st = static_scratch(&stats);
+    if (st != SPEC_OK) return st;
+    return reject_sample_launch("spec_reject_sample_static", B, k, V, dev_logits, dev_q, dev_draft_tokens, temperature, seed, step,
+                                dev_accept_len, dev_out_tokens, dev_dbg, stats, (hipStream_t)stream);
 }
 
 extern "C" spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int64_t logits_row_stride,
