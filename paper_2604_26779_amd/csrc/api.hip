@@ -40,6 +40,11 @@ static std::map<std::string, int>& tune_table()
         {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
         {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
         {"attn_chunk_pages", 0},   // KV pages per attention workgroup (a multiple of 4 up to 256; 0 = by batch size and context bound)
+        // Which projections take one fp16 activation per value (one MFMA per weight fragment, weights tiled as fp16) instead of
+        // hi + lo bf16 pairs (two MFMAs): bit 0 QKV, 1 attention output, 2 feed-forward (gate/up and down, experts included),
+        // 3 output head.  Read at spec_model_create.  Default 12: the feed-forward and the head; the attention block's inputs
+        // carry most of the logits error and stay hi + lo.
+        {"gemm_f16_inputs", 12},
     };
     return t;
 }
@@ -213,21 +218,22 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         }
         char* at = (char*)m->arena;
         m->wqkv.resize(L); m->wo.resize(L); m->wgu.resize(L); m->wd.resize(L); m->router.resize(L);
+        const int f16_mask = tune("gemm_f16_inputs");
         auto pack8 = [&](std::initializer_list<const void*> parts, std::initializer_list<const float*> scales, std::initializer_list<int> rows,
-                         int K, PackedW* pw, bool interleave = false) -> spec_status {
+                         int K, PackedW* pw, bool x_f16, bool interleave = false) -> spec_status {
             std::vector<const unsigned char*> p;
             for (auto q : parts) p.push_back((const unsigned char*)q);
             std::vector<const float*> sc(scales);
             std::vector<int> r(rows);
             int N = 0;
             for (int x : r) N += x;
-            spec_status s2 = w8_pack_matrix(p.data(), sc.data(), r.data(), (int)p.size(), K, at, pw, interleave, nullptr);
+            spec_status s2 = w8_pack_matrix(p.data(), sc.data(), r.data(), (int)p.size(), K, at, pw, interleave, x_f16, nullptr);
             at += w8_packed_bytes(N, K);
             return s2;
         };
         for (int l = 0; l < L && st == SPEC_OK; ++l) {
-            st = pack8({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {m->w_scale(l, 0), m->w_scale(l, 1), m->w_scale(l, 2)}, {nq, nkv, nkv}, D, &m->wqkv[l]);
-            if (st == SPEC_OK) st = pack8({m->layer_w(l, 4)}, {m->w_scale(l, 3)}, {D}, nq, &m->wo[l]);
+            st = pack8({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {m->w_scale(l, 0), m->w_scale(l, 1), m->w_scale(l, 2)}, {nq, nkv, nkv}, D, &m->wqkv[l], f16_mask & 1);
+            if (st == SPEC_OK) st = pack8({m->layer_w(l, 4)}, {m->w_scale(l, 3)}, {D}, nq, &m->wo[l], f16_mask & 2);
             if (E > 0) {
                 const unsigned char *wg = (const unsigned char*)m->layer_w(l, 6), *wu = (const unsigned char*)m->layer_w(l, 7),
                                     *wdn = (const unsigned char*)m->layer_w(l, 8);
@@ -237,21 +243,21 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
                 PackedW tmp;
                 for (int e2 = 0; e2 < E && st == SPEC_OK; ++e2)
                     st = pack8({wg + (size_t)e2 * Fe * D, wu + (size_t)e2 * Fe * D}, {sg + (size_t)e2 * Fe, su + (size_t)e2 * Fe}, {Fe, Fe}, D,
-                               e2 == 0 ? &m->wgu[l] : &tmp, true);
+                               e2 == 0 ? &m->wgu[l] : &tmp, f16_mask & 4, true);
                 for (int e2 = 0; e2 < E && st == SPEC_OK; ++e2)
-                    st = pack8({wdn + (size_t)e2 * D * Fe}, {sd + (size_t)e2 * D}, {D}, Fe, e2 == 0 ? &m->wd[l] : &tmp);
+                    st = pack8({wdn + (size_t)e2 * D * Fe}, {sd + (size_t)e2 * D}, {D}, Fe, e2 == 0 ? &m->wd[l] : &tmp, f16_mask & 4);
                 if (st == SPEC_OK) {
                     const bf16_t* rp = (const bf16_t*)m->layer_w(l, 9);
                     const int rows = E;
-                    st = bf16_pack_matrix(&rp, &rows, 1, D, (bf16_t*)at, &m->router[l], false, nullptr);
+                    st = bf16_pack_matrix(&rp, &rows, 1, D, (bf16_t*)at, &m->router[l], false, false, nullptr);
                     at += align_up(bf16_packed_elems(E, D) * sizeof(bf16_t), 256);
                 }
             } else {
-                if (st == SPEC_OK) st = pack8({m->layer_w(l, 6), m->layer_w(l, 7)}, {m->w_scale(l, 4), m->w_scale(l, 5)}, {F, F}, D, &m->wgu[l], true);
-                if (st == SPEC_OK) st = pack8({m->layer_w(l, 8)}, {m->w_scale(l, 6)}, {D}, F, &m->wd[l]);
+                if (st == SPEC_OK) st = pack8({m->layer_w(l, 6), m->layer_w(l, 7)}, {m->w_scale(l, 4), m->w_scale(l, 5)}, {F, F}, D, &m->wgu[l], f16_mask & 4, true);
+                if (st == SPEC_OK) st = pack8({m->layer_w(l, 8)}, {m->w_scale(l, 6)}, {D}, F, &m->wd[l], f16_mask & 4);
             }
         }
-        if (st == SPEC_OK) st = pack8({m->head_w()}, {m->head_scale()}, {d.vocab}, D, &m->head);
+        if (st == SPEC_OK) st = pack8({m->head_w()}, {m->head_scale()}, {d.vocab}, D, &m->head, f16_mask & 8);
         if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }
         if (st != SPEC_OK) { (void)hipFree(m->arena); delete m; return st; }
     } else if (desc->dtype == SPEC_BF16) {
@@ -274,19 +280,20 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         }
         bf16_t* at = (bf16_t*)m->arena;
         m->wqkv.resize(L); m->wo.resize(L); m->wgu.resize(L); m->wd.resize(L); m->router.resize(L);
-        auto pack = [&](std::initializer_list<const void*> parts, std::initializer_list<int> rows, int K, PackedW* pw, bool interleave = false) -> spec_status {
+        const int f16_mask = tune("gemm_f16_inputs");
+        auto pack = [&](std::initializer_list<const void*> parts, std::initializer_list<int> rows, int K, PackedW* pw, bool to_f16, bool interleave = false) -> spec_status {
             std::vector<const bf16_t*> p;
             for (auto q : parts) p.push_back((const bf16_t*)q);
             std::vector<int> r(rows);
             int N = 0;
             for (int x : r) N += x;
-            spec_status s2 = bf16_pack_matrix(p.data(), r.data(), (int)p.size(), K, at, pw, interleave, nullptr);
+            spec_status s2 = bf16_pack_matrix(p.data(), r.data(), (int)p.size(), K, at, pw, interleave, to_f16, nullptr);
             at += bf16_packed_elems(N, K);
             return s2;
         };
         for (int l = 0; l < L && st == SPEC_OK; ++l) {
-            st = pack({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {nq, nkv, nkv}, D, &m->wqkv[l]);
-            if (st == SPEC_OK) st = pack({m->layer_w(l, 4)}, {D}, nq, &m->wo[l]);
+            st = pack({m->layer_w(l, 1), m->layer_w(l, 2), m->layer_w(l, 3)}, {nq, nkv, nkv}, D, &m->wqkv[l], f16_mask & 1);
+            if (st == SPEC_OK) st = pack({m->layer_w(l, 4)}, {D}, nq, &m->wo[l], f16_mask & 2);
             if (E > 0) {
                 // every expert re-tiled on its own, all experts of a matrix back to back (equal sizes)
                 const bf16_t *wg = (const bf16_t*)m->layer_w(l, 6), *wu = (const bf16_t*)m->layer_w(l, 7), *wdn = (const bf16_t*)m->layer_w(l, 8);
@@ -294,17 +301,17 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
                 m->moe_d_stride = (int64_t)bf16_packed_elems(D, Fe);
                 PackedW tmp;
                 for (int e = 0; e < E && st == SPEC_OK; ++e)
-                    st = pack({wg + (size_t)e * Fe * D, wu + (size_t)e * Fe * D}, {Fe, Fe}, D, e == 0 ? &m->wgu[l] : &tmp, true);
+                    st = pack({wg + (size_t)e * Fe * D, wu + (size_t)e * Fe * D}, {Fe, Fe}, D, e == 0 ? &m->wgu[l] : &tmp, f16_mask & 4, true);
                 for (int e = 0; e < E && st == SPEC_OK; ++e)
-                    st = pack({wdn + (size_t)e * D * Fe}, {D}, Fe, e == 0 ? &m->wd[l] : &tmp);
-                if (st == SPEC_OK) st = pack({m->layer_w(l, 9)}, {E}, D, &m->router[l]);
+                    st = pack({wdn + (size_t)e * D * Fe}, {D}, Fe, e == 0 ? &m->wd[l] : &tmp, f16_mask & 4);
+                if (st == SPEC_OK) st = pack({m->layer_w(l, 9)}, {E}, D, &m->router[l], false);
             } else {
-                if (st == SPEC_OK) st = pack({m->layer_w(l, 6), m->layer_w(l, 7)}, {F, F}, D, &m->wgu[l], true);
-                if (st == SPEC_OK) st = pack({m->layer_w(l, 8)}, {D}, F, &m->wd[l]);
+                if (st == SPEC_OK) st = pack({m->layer_w(l, 6), m->layer_w(l, 7)}, {F, F}, D, &m->wgu[l], f16_mask & 4, true);
+                if (st == SPEC_OK) st = pack({m->layer_w(l, 8)}, {D}, F, &m->wd[l], f16_mask & 4);
             }
         }
-        if (st == SPEC_OK) st = pack({m->head_w()}, {d.vocab}, D, &m->head);
-        if (st == SPEC_OK && d.fuse_hidden) st = pack({m->fuse_w(0)}, {D}, 2 * D, &m->wfuse);
+        if (st == SPEC_OK) st = pack({m->head_w()}, {d.vocab}, D, &m->head, f16_mask & 8);
+        if (st == SPEC_OK && d.fuse_hidden) st = pack({m->fuse_w(0)}, {D}, 2 * D, &m->wfuse, false);
         if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }
         if (st != SPEC_OK) { (void)hipFree(m->arena); delete m; return st; }
     }

@@ -396,7 +396,7 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
 // operand of the O projection: xp[k-step][m-block][lane][8] with k = head*128 + channel
 __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int B, int T,
                                    int G, int Hkv, int RBrows, int max_chunks, int chunk_pages, const int32_t* __restrict__ seq_ids,
-                                   KvView kv, int layer, int mb_pad, uint4* __restrict__ xp)
+                                   KvView kv, int layer, int mb_pad, int xf, uint4* __restrict__ xp)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int R = T * G;
@@ -428,7 +428,7 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
     if (kv.fp8) inv *= kv.v_scale[layer * Hkv + kvh];     // 8-bit cache: the values were accumulated as codes
     float res[8];
     for (int j = 0; j < 8; ++j) res[j] = o[j] * inv;
-    xp_store8(xp, b * T + r / G, (kvh * G + r % G) * DH + c8 * 8, mb_pad, res);
+    xp_store8_rt(xp, xf, b * T + r / G, (kvh * G + r % G) * DH + c8 * 8, mb_pad, res);
 }
 
 // How R query rows per kv head are laid over workgroups: RG groups of NRB row blocks, NRB <= 4 and as equal as
@@ -478,7 +478,7 @@ int attn_rows_padded(int R)
 
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
                                   const KvView& kv, int layer_pool, int layer, int pages_bound, float* part_o, float* part_ml,
-                                  int mb_pad, bf16_t* xp_out, hipStream_t s)
+                                  int mb_pad, int xf_out, bf16_t* xp_out, hipStream_t s)
 {
     int R = T * G;
     if (R > 256) { set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 256", R); return SPEC_EUNSUPPORTED; }
@@ -506,7 +506,7 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
     prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);
     attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, rows, max_chunks, cp, seq_ids, kv,
-                                                                  layer, mb_pad, (uint4*)xp_out);
+                                                                  layer, mb_pad, xf_out, (uint4*)xp_out);
     SPEC_LAUNCH_CHECK("attn_reduce_kernel");
     prof_mark(PC_ATTN_REDUCE, s);
     return SPEC_OK;

@@ -70,6 +70,8 @@ struct PackedW {
     int32_t n_blocks = 0;          // ceil(N / 32)
     int32_t k_steps = 0;           // K / 16
     int32_t w8 = 0;                // 1: E4M3 codes, two k-steps per 16-byte word; scale = per-column factors, tiled order
+    int32_t f16 = 0;               // 1: the activations come as one fp16 per value and the weights are fp16 (converted once;
+                                   //    8-bit codes are widened to fp16); 0: hi + lo bf16 pairs against bf16 weights
     const float* scale = nullptr;
 };
 
@@ -155,10 +157,10 @@ spec_status f32_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t*
 // ---- bf16 MFMA path (forward_bf16.hip, gemm_bf16.hip, attn_bf16.hip) ----
 size_t bf16_packed_elems(int N, int K);
 spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_rows, int n_parts, int K,
-                             bf16_t* dev_out, PackedW* out, bool interleave, hipStream_t s);
+                             bf16_t* dev_out, PackedW* out, bool interleave, bool to_f16, hipStream_t s);
 size_t w8_packed_bytes(int N, int K);
 spec_status w8_pack_matrix(const unsigned char* const* dev_parts, const float* const* dev_scales, const int* part_rows, int n_parts,
-                           int K, void* dev_out, PackedW* out, bool interleave, hipStream_t s);
+                           int K, void* dev_out, PackedW* out, bool interleave, bool x_f16, hipStream_t s);
 size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k);
 spec_status bf16_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids,
                          const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits, float* dev_hidden_out,

@@ -29,12 +29,12 @@ spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, co
 spec_status launch_moe_route(const float* part, int splits, int64_t split_stride, int M, int E, int top_k, int32_t* ids, float* wts,
                              int32_t* row0, int32_t* tiles, int32_t* src_row, int32_t* pair_row, hipStream_t s);
 spec_status launch_moe_gather(const bf16_t* xp_src, int mb_pad_src, const int32_t* src_row, const int32_t* row0, int E, int d,
-                              int rows_bound, bf16_t* xp_dst, hipStream_t s);
+                              int rows_bound, int xf_dst, bf16_t* xp_dst, hipStream_t s);
 spec_status launch_moe_combine_norm(float* x, const float* y, const int32_t* pair_row, const float* wts, int M, int top_k,
-                                    const void* gain, int d, float eps, int mb_pad, bf16_t* xp, hipStream_t s);
+                                    const void* gain, int d, float eps, int mb_pad, int xf, bf16_t* xp, hipStream_t s);
 spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
                                   const KvView& kv, int layer_pool, int layer, int pages_bound, float* part_o, float* part_ml,
-                                  int mb_pad, bf16_t* xp_out, hipStream_t s);
+                                  int mb_pad, int xf_out, bf16_t* xp_out, hipStream_t s);
 
 // sum over the workgroup (blockDim.x a multiple of 64, at most 1024)
 __device__ inline float block_sum(float v, float* lds16)
@@ -55,7 +55,7 @@ template <int MODE>
 __global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
     float* __restrict__ x, const float* __restrict__ part, int splits, int64_t split_stride, const int32_t* __restrict__ tokens,
     const unsigned short* __restrict__ embed, int vocab, const unsigned short* __restrict__ gain, int d, float eps, int mb_pad,
-    uint4* __restrict__ xp)
+    int xf, uint4* __restrict__ xp)
 {
     __shared__ float lds16[16];
     const int m = blockIdx.x;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
         float v[8] = {a.x * r * from_bf16(g.x & 0xffff), a.y * r * from_bf16(g.x >> 16), a.z * r * from_bf16(g.y & 0xffff),
                       a.w * r * from_bf16(g.y >> 16),    b.x * r * from_bf16(g.z & 0xffff), b.y * r * from_bf16(g.z >> 16),
                       b.z * r * from_bf16(g.w & 0xffff), b.w * r * from_bf16(g.w >> 16)};
-        xp_store8(xp, m, c, mb_pad, v);
+        xp_store8_rt(xp, xf, m, c, mb_pad, v);
     }
 }
 
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(
 
 // act = silu(sum gate) * (sum up) from the gate/up projection [M][2F] -> bf16 operand order (K = F)
 __global__ void swiglu_pack_kernel(const float* __restrict__ part, int splits, int64_t split_stride, int M, int F, int mb_pad,
-                                   uint4* __restrict__ xp)
+                                   int xf, uint4* __restrict__ xp)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int f8 = F / 8;
@@ -296,7 +296,7 @@ __global__ void swiglu_pack_kernel(const float* __restrict__ part, int splits, i
     float v[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = g[j] / (1.0f + expf(-g[j])) * u[j];
-    xp_store8(xp, m, f, mb_pad, v);
+    xp_store8_rt(xp, xf, m, f, mb_pad, v);
 }
 
 // ------------------------------------------------------------------ host side
@@ -399,6 +399,9 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     KvView view = kv->view();
     spec_status st;
     const int norm_threads = D >= 4096 ? 512 : 256;
+    // operand format each projection's input is written in: the one its matrix was tiled for at model creation
+    auto xf_of = [](const PackedW& W) { return W.f16 ? XF_F16 : XF_HILO; };
+    if (!mdl->moe() && mdl->wgu[0].f16 != mdl->wd[0].f16) { set_error("bf16 forward: gate/up and down projection must take the same activation format"); return SPEC_ESTATE; }
 
     rope_table_kernel<<<(unsigned)cdiv((int64_t)M * 64, 256), 256, 0, s>>>(M, T, dev_seq_ids, kv->d_ctx_len, 64, (double)d.rope_theta, rope);
     if (d.fuse_hidden) {
@@ -408,10 +411,10 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
                                                      p.mb_pad, (uint4*)xp_f);
         if ((st = launch_gemm_bf16(mdl->wfuse, xp_f, M, part, D, p.s_fuse, false, s)) != SPEC_OK) return st;
         residual_rmsnorm_kernel<RES_SET><<<M, norm_threads, 0, s>>>(x, part, p.s_fuse, (int64_t)M * D, nullptr, nullptr, 0,
-                                                                   (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+                                                                   (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, xf_of(mdl->wqkv[0]), (uint4*)xp_h);
     } else {
         residual_rmsnorm_kernel<RES_EMBED><<<M, norm_threads, 0, s>>>(x, nullptr, 0, 0, dev_tokens, (const unsigned short*)mdl->embed(), d.vocab,
-                                                        (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+                                                        (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, xf_of(mdl->wqkv[0]), (uint4*)xp_h);
     }
     prof_mark(PC_EMBED_NORM, s);
     for (int l = 0; l < d.n_layers; ++l) {
@@ -423,13 +426,16 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         else
             qkv_rope_kernel<false><<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, l, qbuf);
         prof_mark(PC_QKV_ROPE, s);
-        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, l, live_pages, att_o, att_ml, p.mb_pad, xp_a, s)) != SPEC_OK) return st;
+        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, l, live_pages, att_o, att_ml, p.mb_pad, xf_of(mdl->wo[l]), xp_a, s)) != SPEC_OK) return st;
         if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_O, s);
+        // (mixture of experts: the router reads this buffer and stays hi + lo; the gather below converts for the experts)
         residual_rmsnorm_kernel<RES_ADD><<<M, norm_threads, 0, s>>>(x, part, p.s_o, (int64_t)M * D, nullptr, nullptr, 0,
-                                                         (const unsigned short*)mdl->layer_w(l, 5), D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+                                                         (const unsigned short*)mdl->layer_w(l, 5), D, d.rms_eps, p.mb_pad,
+                                                         mdl->moe() ? xf_of(mdl->router[l]) : xf_of(mdl->wgu[l]), (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
         const void* next_gain = l + 1 < d.n_layers ? mdl->layer_w(l + 1, 0) : mdl->final_norm();
+        const int next_xf = l + 1 < d.n_layers ? xf_of(mdl->wqkv[l + 1]) : xf_of(mdl->head);
         if (mdl->moe()) {
             // router -> top-k -> rows permuted into per-expert tiles -> grouped gate/up (SwiGLU fused) and down
             // projections over the tile list -> weighted combine + residual + next RMSNorm
@@ -445,13 +451,13 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
             if ((st = launch_gemm_bf16(mdl->router[l], xp_h, M, part, E, p.s_router, false, s)) != SPEC_OK) return st;
             if ((st = launch_moe_route(part, p.s_router, (int64_t)M * E, M, E, d.top_k, ids, wts, row0, tiles, src_row, pair_row, s)) != SPEC_OK) return st;
             prof_mark(PC_MOE_ROUTE, s);
-            if ((st = launch_moe_gather(xp_h, p.mb_pad, src_row, row0, E, D, p.moe_rows, xp_e, s)) != SPEC_OK) return st;
+            if ((st = launch_moe_gather(xp_h, p.mb_pad, src_row, row0, E, D, p.moe_rows, xf_of(mdl->wgu[l]), xp_e, s)) != SPEC_OK) return st;
             prof_mark(PC_MOE_GATHER, s);
             if ((st = launch_gemm_bf16_grouped(mdl->wgu[l], mdl->moe_gu_stride, xp_e, p.moe_rows, max_tiles, tiles, (float*)xp_f, 2 * Fe, true, s)) != SPEC_OK) return st;
             prof_mark(PC_GEMM_GU, s);
             if ((st = launch_gemm_bf16_grouped(mdl->wd[l], mdl->moe_d_stride, xp_f, p.moe_rows, max_tiles, tiles, y_e, D, false, s)) != SPEC_OK) return st;
             prof_mark(PC_GEMM_DOWN, s);
-            if ((st = launch_moe_combine_norm(x, y_e, pair_row, wts, M, d.top_k, next_gain, D, d.rms_eps, p.mb_pad, xp_h, s)) != SPEC_OK) return st;
+            if ((st = launch_moe_combine_norm(x, y_e, pair_row, wts, M, d.top_k, next_gain, D, d.rms_eps, p.mb_pad, next_xf, xp_h, s)) != SPEC_OK) return st;
             prof_mark(PC_RESID_NORM, s);
             continue;
         }
@@ -462,13 +468,13 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         } else {
             if ((st = launch_gemm_bf16(mdl->wgu[l], xp_h, M, part, 2 * F, p.s_gu, false, s)) != SPEC_OK) return st;
             prof_mark(PC_GEMM_GU, s);
-            swiglu_pack_kernel<<<(unsigned)cdiv((int64_t)M * (F / 8), 256), 256, 0, s>>>(part, p.s_gu, (int64_t)M * 2 * F, M, F, p.mb_pad, (uint4*)xp_f);
+            swiglu_pack_kernel<<<(unsigned)cdiv((int64_t)M * (F / 8), 256), 256, 0, s>>>(part, p.s_gu, (int64_t)M * 2 * F, M, F, p.mb_pad, xf_of(mdl->wd[l]), (uint4*)xp_f);
             prof_mark(PC_SWIGLU, s);
         }
         if ((st = launch_gemm_bf16(mdl->wd[l], xp_f, M, part, D, p.s_down, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_DOWN, s);
         residual_rmsnorm_kernel<RES_ADD><<<M, norm_threads, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
-                                                         (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, (uint4*)xp_h);
+                                                         (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, next_xf, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
     }
     if (dev_hidden_out) {

@@ -28,6 +28,7 @@
 namespace specv {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -41,7 +42,15 @@ constexpr int GEMM_EPI_PLAIN = 0, GEMM_EPI_SWIGLU = 1;
 size_t bf16_packed_elems(int N, int K) { return (size_t)cdiv(N, 32) * 32 * (size_t)K; }
 
 // ------------------------------------------------------------------ weight re-tiling
-struct PackParts { const bf16_t* ptr[4]; int row_end[4]; int n; int interleave; };
+struct PackParts { const bf16_t* ptr[4]; int row_end[4]; int n; int interleave; int to_f16; };
+
+// bf16 pair -> fp16 pair.  Exact for magnitudes from 2^-14 up to 65504 (bf16 has fewer mantissa bits than fp16);
+// below 2^-14 the fp16 grid has steps of 2^-24 (absolute error at most 2^-25, nothing for a weight matrix);
+// beyond 65504 the value saturates.
+__device__ inline unsigned int bf16x2_to_f16x2(unsigned int w)
+{
+    return pack_f16x2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
+}
 
 __global__ void pack_w_kernel(PackParts parts, int N, int K, int k_steps, int64_t total, uint4* __restrict__ out)
 {
@@ -71,16 +80,18 @@ __global__ void pack_w_kernel(PackParts parts, int N, int K, int k_steps, int64_
             start = parts.row_end[p];
         }
     }
+    if (parts.to_f16) v = make_uint4(bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w));
     out[idx] = v;
 }
 
 spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_rows, int n_parts, int K, bf16_t* dev_out,
-                             PackedW* out, bool interleave, hipStream_t s)
+                             PackedW* out, bool interleave, bool to_f16, hipStream_t s)
 {
     if (n_parts < 1 || n_parts > 4 || K % (16 * GEMM_KUNIT)) { set_error("bf16_pack_matrix: bad shape"); return SPEC_EINVAL; }
     PackParts pp;
     pp.n = n_parts;
     pp.interleave = interleave ? 1 : 0;
+    pp.to_f16 = to_f16 ? 1 : 0;
     if (interleave && (n_parts != 2 || part_rows[0] != part_rows[1] || part_rows[0] % 32)) { set_error("bf16_pack_matrix: interleaving needs two equal parts of a multiple of 32 rows"); return SPEC_EINVAL; }
     int N = 0;
     for (int i = 0; i < n_parts; ++i) {
@@ -94,6 +105,7 @@ spec_status bf16_pack_matrix(const bf16_t* const* dev_parts, const int* part_row
     out->K = K;
     out->n_blocks = (int)cdiv(N, 32);
     out->k_steps = K / 16;
+    out->f16 = to_f16 ? 1 : 0;
     int64_t total = (int64_t)out->n_blocks * out->k_steps * 64;
     pack_w_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(pp, N, K, out->k_steps, total, (uint4*)dev_out);
     SPEC_LAUNCH_CHECK("pack_w_kernel");
@@ -150,7 +162,7 @@ size_t w8_packed_bytes(int N, int K) { return align_up((size_t)cdiv(N, 32) * 32 
 
 // dev_out: w8_packed_bytes(N, K) bytes: the tiled codes, then the tiled scales
 spec_status w8_pack_matrix(const unsigned char* const* dev_parts, const float* const* dev_scales, const int* part_rows, int n_parts,
-                           int K, void* dev_out, PackedW* out, bool interleave, hipStream_t s)
+                           int K, void* dev_out, PackedW* out, bool interleave, bool x_f16, hipStream_t s)
 {
     if (n_parts < 1 || n_parts > 4 || K % (16 * GEMM_KUNIT)) { set_error("w8_pack_matrix: bad shape"); return SPEC_EINVAL; }
     PackParts8 pp;
@@ -171,6 +183,7 @@ spec_status w8_pack_matrix(const unsigned char* const* dev_parts, const float* c
     out->n_blocks = (int)cdiv(N, 32);
     out->k_steps = K / 16;
     out->w8 = 1;
+    out->f16 = x_f16 ? 1 : 0;           // the codes are the same either way; the kernel widens them to the activations' type
     out->scale = (const float*)((const char*)dev_out + (size_t)out->n_blocks * 32 * K);
     int64_t total = (int64_t)out->n_blocks * (out->k_steps / 2) * 64;
     pack_w8_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(pp, N, K, total, (uint4*)dev_out, (float*)out->scale);
@@ -198,7 +211,10 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | 0x70 | 0xF00 | ((n >> 4) << 1
 // W8: the weights are E4M3 codes, two k-steps per 16-byte word (half the weight bytes and load instructions); a
 // fragment is widened to bf16 in registers right before its MFMAs (exact) and the output column's scale is applied to
 // the accumulators in the epilogue.
-template <int MB, int WM, int WD, int EPI, bool GROUPED = false, int NBW_T = WM, bool W8 = false>
+// XF: the activations' operand format (operand.h): XF_HILO = hi + lo bf16 pairs against bf16 weights, two MFMAs per
+// weight fragment and row block; XF_F16 = one fp16 value against fp16 weights, one MFMA.  The fused SwiGLU epilogue
+// writes its output in the same format (gate/up and down projection take the same one).
+template <int MB, int WM, int WD, int EPI, bool GROUPED = false, int NBW_T = WM, bool W8 = false, int XF = XF_HILO>
 __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NBW_T == 2)) ? 1 : 2) void gemm_bf16_kernel(
     const u32x4_t* __restrict__ Wp, const u32x4_t* __restrict__ Xp, float* __restrict__ out, int n_blocks, int k_steps,
     int ksteps_per_split, int mb_pad, int M, int N, int ldo, int64_t split_stride,
@@ -210,11 +226,14 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
     constexpr int TILE_NB = (4 / WM) * NBW;             // 32-column blocks per workgroup tile
     constexpr bool BIG = MB >= 6;
     static_assert(MB % WM == 0, "row blocks must divide over the wavefronts");
-    constexpr int SLAB = KS * MB * 128;                 // u32x4_t per slab (hi and lo operands)
+    constexpr int SLAB = KS * MB * 64 * XF;             // u32x4_t per slab (XF operand words per lane and k-step)
     constexpr int XPT = SLAB / GEMM_THREADS;            // u32x4_t per thread per slab
     static_assert(SLAB % GEMM_THREADS == 0, "a slab must divide over the threads");
+    // the fused SwiGLU epilogue re-uses the slabs as an fp32 transpose tile, which may be the larger of the two
+    constexpr int EPI_WORDS = EPI != GEMM_EPI_SWIGLU ? 0 : (BIG ? (MB / WM) * 32 * 129 : WM == 1 ? 32 * 129 : MB * 32 * 65) / 4 + 1;
+    constexpr int LDS_WORDS = 2 * SLAB > EPI_WORDS ? 2 * SLAB : EPI_WORDS;
     extern __shared__ u32x4_t lds_dyn[];
-    __shared__ u32x4_t lds_static[BIG ? 1 : 2 * SLAB];
+    __shared__ u32x4_t lds_static[BIG ? 1 : LDS_WORDS];
     u32x4_t* const lds = BIG ? lds_dyn : lds_static;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -257,7 +276,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
     float wsc[NBW];                                     // 8-bit weights: this lane's column scales
 #pragma unroll
     for (int j = 0; j < NBW; ++j) wsc[j] = 1.0f;
-    const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mblk0) * 128;
+    const u32x4_t* xbase = Xp + ((int64_t)ks0 * mb_pad + (int64_t)mblk0) * (64 * XF);
 
     f32x16_t acc[MBW][NBW];
 #pragma unroll
@@ -275,8 +294,8 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
 #pragma unroll
         for (int j = 0; j < XPT; ++j) {
             int idx = threadIdx.x + GEMM_THREADS * j;
-            int kl = idx / (MB * 128), rem = idx % (MB * 128);
-            xr[j] = xbase[((int64_t)(slab * KS + kl) * mb_pad) * 128 + rem];
+            int kl = idx / (MB * 64 * XF), rem = idx % (MB * 64 * XF);
+            xr[j] = xbase[((int64_t)(slab * KS + kl) * mb_pad) * (64 * XF) + rem];
         }
     };
     auto store_x = [&](int buf) {
@@ -291,8 +310,8 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
 #pragma unroll
         for (int j = 0; j < XPT; ++j) {
             int idx = threadIdx.x + GEMM_THREADS * j;
-            int kl = idx / (MB * 128), rem = idx % (MB * 128);
-            const u32x4_t* src = xbase + ((int64_t)(slab * KS + kl) * mb_pad) * 128 + rem;
+            int kl = idx / (MB * 64 * XF), rem = idx % (MB * 64 * XF);
+            const u32x4_t* src = xbase + ((int64_t)(slab * KS + kl) * mb_pad) * (64 * XF) + rem;
             u32x4_t* dst = lds + tobuf * SLAB + (idx - lane);
             __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
                                              (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
@@ -314,13 +333,13 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
         __builtin_amdgcn_sched_barrier(0);
         // LDS reads run one k-step ahead of the MFMAs that use them (two register sets): with one or two
         // wavefronts per SIMD nothing else would hide the LDS latency.  The scheduling barriers keep that order.
-        u32x4_t a[2][MBW][2];
+        u32x4_t a[2][MBW][XF];
         auto read_a = [&](int set, int kk) {
 #pragma unroll
             for (int i = 0; i < MBW; ++i)
 #pragma unroll
-                for (int part = 0; part < 2; ++part)
-                    a[set][i][part] = lds[buf * SLAB + ((kk * MB + mh * MBW + i) * 2 + part) * 64 + lane];
+                for (int part = 0; part < XF; ++part)
+                    a[set][i][part] = lds[buf * SLAB + ((kk * MB + mh * MBW + i) * XF + part) * 64 + lane];
         };
         read_a(0, 0);
 #pragma unroll
@@ -336,10 +355,16 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            u32x4_t wk[NBW];                             // this k-step's weight fragments as bf16
+            u32x4_t wk[NBW];                             // this k-step's weight fragments in the activations' 16-bit type
 #pragma unroll
             for (int j = 0; j < NBW; ++j) {
-                if constexpr (W8) {
+                if constexpr (W8 && XF == XF_F16) {
+                    const unsigned int wa = w[SLOT][kk >> 1][j][(kk & 1) * 2], wb = w[SLOT][kk >> 1][j][(kk & 1) * 2 + 1];
+                    wk[j] = u32x4_t{__builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(wa, 1.0f, false)),
+                                    __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(wa, 1.0f, true)),
+                                    __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(wb, 1.0f, false)),
+                                    __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(wb, 1.0f, true))};
+                } else if constexpr (W8) {
                     const unsigned int wa = w[SLOT][kk >> 1][j][(kk & 1) * 2], wb = w[SLOT][kk >> 1][j][(kk & 1) * 2 + 1];
                     wk[j] = u32x4_t{__builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wa, 1.0f, false)),
                                     __builtin_bit_cast(unsigned int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(wa, 1.0f, true)),
@@ -351,13 +376,18 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
             }
             // hi products of all blocks first, then the lo products: two MFMAs on one accumulator are never adjacent
 #pragma unroll
-            for (int part = 0; part < 2; ++part)
+            for (int part = 0; part < XF; ++part)
 #pragma unroll
                 for (int i = 0; i < MBW; ++i)
 #pragma unroll
-                    for (int j = 0; j < NBW; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[kk & 1][i][part]),
-                                                                            __builtin_bit_cast(bf16x8_t, wk[j]), acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < NBW; ++j) {
+                        if constexpr (XF == XF_F16)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a[kk & 1][i][part]),
+                                                                               __builtin_bit_cast(f16x8_t, wk[j]), acc[i][j], 0, 0, 0);
+                        else
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[kk & 1][i][part]),
+                                                                                __builtin_bit_cast(bf16x8_t, wk[j]), acc[i][j], 0, 0, 0);
+                    }
             if (!W8 || (kk & 1)) {                       // (8-bit: a word serves two k-steps and is refilled after the second)
 #pragma unroll
                 for (int j = 0; j < NBW; ++j)
@@ -452,7 +482,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
                 float v[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) v[j] = tile[row * 129 + g8 * 8 + j];
-                xp_store8(xo, m, f, mb_pad, v);
+                xp_store8_t<XF>(xo, m, f, mb_pad, v);
             }
         }
         return;
@@ -483,7 +513,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
                 float v[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) v[j] = tile[row * 129 + g8 * 8 + j];
-                xp_store8(xo, m, f, mb_pad, v);
+                xp_store8_t<XF>(xo, m, f, mb_pad, v);
             }
         }
         return;
@@ -516,7 +546,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
             float v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] = tile[row * 65 + g8 * 8 + j];
-            xp_store8(xo, m, f, mb_pad, v);
+            xp_store8_t<XF>(xo, m, f, mb_pad, v);
         }
         return;
     }
@@ -633,14 +663,19 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
     const u32x4_t* wp = (const u32x4_t*)W.data;
     const u32x4_t* xp = (const u32x4_t*)Xp;
     if (swiglu && !gemm_can_fuse_swiglu(W, M, splits)) { set_error("gemm: SwiGLU cannot be fused for this shape"); return SPEC_EUNSUPPORTED; }
-#define SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, W8V) gemm_bf16_kernel<MBV, WMV, WDV, E, false, (MBV % 2 == 0 && WMV == 1) ? 2 : WMV, W8V><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
-#define SPEC_GEMM_LAUNCH_96W(E, W8V) gemm_bf16_kernel<3, 1, 2, E, false, 2, W8V><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
-#define SPEC_GEMM_LAUNCH_96(E) do { if (W.w8) SPEC_GEMM_LAUNCH_96W(E, true); else SPEC_GEMM_LAUNCH_96W(E, false); } while (0)
-#define SPEC_GEMM_LAUNCH(MBV, WMV, WDV, E) do { if (W.w8) SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, true); else SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, false); } while (0)
+#define SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, W8V, XFV) gemm_bf16_kernel<MBV, WMV, WDV, E, false, (MBV % 2 == 0 && WMV == 1) ? 2 : WMV, W8V, XFV><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
+#define SPEC_GEMM_LAUNCH_96W(E, W8V, XFV) gemm_bf16_kernel<3, 1, 2, E, false, 2, W8V, XFV><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
+    // the four combinations of 8-bit or 16-bit weights and hi + lo or fp16 activations
+#define SPEC_GEMM_BY_TYPE(CALL, ...) do { \
+        if (W.w8) { if (W.f16) CALL(__VA_ARGS__, true, XF_F16); else CALL(__VA_ARGS__, true, XF_HILO); } \
+        else { if (W.f16) CALL(__VA_ARGS__, false, XF_F16); else CALL(__VA_ARGS__, false, XF_HILO); } } while (0)
+#define SPEC_GEMM_LAUNCH_96(E) SPEC_GEMM_BY_TYPE(SPEC_GEMM_LAUNCH_96W, E)
+#define SPEC_GEMM_LAUNCH(MBV, WMV, WDV, E) SPEC_GEMM_BY_TYPE(SPEC_GEMM_LAUNCH_W, MBV, WMV, WDV, E)
     // the 256-column tile: two LDS slabs of MB * 8 KiB as dynamic shared memory (beyond the 64 KiB a kernel gets by default)
-#define SPEC_GEMM_LAUNCH_BIG_W(MBV, E, W8V) do { \
-        auto kern = gemm_bf16_kernel<MBV, 2, 1, E, false, 4, W8V>; \
-        constexpr int lds_bytes = 2 * GEMM_KS * MBV * 128 * 16; \
+#define SPEC_GEMM_LAUNCH_BIG_W(MBV, E, W8V, XFV) do { \
+        auto kern = gemm_bf16_kernel<MBV, 2, 1, E, false, 4, W8V, XFV>; \
+        constexpr int slab_bytes = 2 * GEMM_KS * MBV * 64 * XFV * 16, epi_bytes = E == GEMM_EPI_SWIGLU ? (MBV / 2) * 32 * 129 * 4 + 16 : 0; \
+        constexpr int lds_bytes = slab_bytes > epi_bytes ? slab_bytes : epi_bytes; \
         static bool raised = false; \
         if (!raised) { \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes); \
@@ -649,7 +684,7 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
         } \
         kern<<<grid, GEMM_THREADS, lds_bytes, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale); \
     } while (0)
-#define SPEC_GEMM_LAUNCH_BIG(MBV, E) do { if (W.w8) SPEC_GEMM_LAUNCH_BIG_W(MBV, E, true); else SPEC_GEMM_LAUNCH_BIG_W(MBV, E, false); } while (0)
+#define SPEC_GEMM_LAUNCH_BIG(MBV, E) SPEC_GEMM_BY_TYPE(SPEC_GEMM_LAUNCH_BIG_W, MBV, E)
     switch (mb) {
         case 1: SPEC_GEMM_LAUNCH(1, 1, GEMM_WD, GEMM_EPI_PLAIN); break;
         case 2:
@@ -673,6 +708,7 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
             break;
     }
 #undef SPEC_GEMM_LAUNCH_BIG
+#undef SPEC_GEMM_BY_TYPE
 #undef SPEC_GEMM_LAUNCH_96
 #undef SPEC_GEMM_LAUNCH_96W
 #undef SPEC_GEMM_LAUNCH_BIG_W
@@ -700,13 +736,15 @@ spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, co
     // which is what the expert GEMMs - few rows, all weights touched - are bound by).
     const bool wide = tune("moe_wide_tiles") != 0 && W0.n_blocks % 8 == 0;
     if (wide) grid.x = (unsigned)cdiv(W0.n_blocks, 8);
-#define SPEC_GROUPED_LAUNCH(WMV, E, W8V) gemm_bf16_kernel<2, WMV, 2, E, true, 2, W8V><<<grid, GEMM_THREADS, 0, s>>>( \
+#define SPEC_GROUPED_LAUNCH(WMV, E, W8V, XFV) gemm_bf16_kernel<2, WMV, 2, E, true, 2, W8V, XFV><<<grid, GEMM_THREADS, 0, s>>>( \
         wp, xp, out, W0.n_blocks, W0.k_steps, W0.k_steps, rows_pad / 32, rows_pad, W0.N, ldo, 0, tiles, stride16, W0.scale)
-#define SPEC_GROUPED_LAUNCH_E(E) do { \
-        if (wide) { if (W0.w8) SPEC_GROUPED_LAUNCH(1, E, true); else SPEC_GROUPED_LAUNCH(1, E, false); } \
-        else { if (W0.w8) SPEC_GROUPED_LAUNCH(2, E, true); else SPEC_GROUPED_LAUNCH(2, E, false); } } while (0)
+#define SPEC_GROUPED_BY_TYPE(WMV, E) do { \
+        if (W0.w8) { if (W0.f16) SPEC_GROUPED_LAUNCH(WMV, E, true, XF_F16); else SPEC_GROUPED_LAUNCH(WMV, E, true, XF_HILO); } \
+        else { if (W0.f16) SPEC_GROUPED_LAUNCH(WMV, E, false, XF_F16); else SPEC_GROUPED_LAUNCH(WMV, E, false, XF_HILO); } } while (0)
+#define SPEC_GROUPED_LAUNCH_E(E) do { if (wide) SPEC_GROUPED_BY_TYPE(1, E); else SPEC_GROUPED_BY_TYPE(2, E); } while (0)
     if (swiglu) SPEC_GROUPED_LAUNCH_E(GEMM_EPI_SWIGLU); else SPEC_GROUPED_LAUNCH_E(GEMM_EPI_PLAIN);
 #undef SPEC_GROUPED_LAUNCH_E
+#undef SPEC_GROUPED_BY_TYPE
 #undef SPEC_GROUPED_LAUNCH
     SPEC_LAUNCH_CHECK("gemm_bf16_kernel (grouped)");
     return SPEC_OK;

@@ -122,8 +122,16 @@ __global__ __launch_bounds__(256) void moe_permute_kernel(const int32_t* __restr
 
 // Activations of the permuted rows in the GEMM's operand order (hi and lo words), zeros for padding.
 // One thread per 16-byte destination word: writes are contiguous, reads gather rows of one k-step.
+// The source is always hi + lo (the router reads it too); with xf_dst = XF_F16 (expert projections that take fp16
+// activations, 64 threads per workgroup) a destination word is fp16(hi + lo) of the same eight values.
+__device__ inline unsigned int hilo_to_f16x2(unsigned int hi, unsigned int lo)
+{
+    return pack_f16x2(__uint_as_float(hi << 16) + __uint_as_float(lo << 16), __uint_as_float(hi & 0xffff0000u) + __uint_as_float(lo & 0xffff0000u));
+}
+
 __global__ void moe_gather_kernel(const uint4* __restrict__ xp_src, int mb_pad_src, const int32_t* __restrict__ src_row,
-                                  const int32_t* __restrict__ row0, int E, int k_steps, int mb_pad_dst, uint4* __restrict__ xp_dst)
+                                  const int32_t* __restrict__ row0, int E, int k_steps, int mb_pad_dst, int xf_dst,
+                                  uint4* __restrict__ xp_dst)
 {
     const int blocks = row0[E] / 32;
     const int mblk = blockIdx.x, ks = blockIdx.y;
@@ -131,6 +139,15 @@ __global__ void moe_gather_kernel(const uint4* __restrict__ xp_src, int mb_pad_s
     const int part = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m = src_row[mblk * 32 + (lane & 31)];
     uint4 v = make_uint4(0, 0, 0, 0);
+    if (xf_dst == XF_F16) {
+        if (m >= 0) {
+            const int64_t at = (((int64_t)ks * mb_pad_src + (m >> 5)) * 2) * 64 + (m & 31) + (lane & 32);
+            const uint4 hi = xp_src[at], lo = xp_src[at + 64];
+            v = make_uint4(hilo_to_f16x2(hi.x, lo.x), hilo_to_f16x2(hi.y, lo.y), hilo_to_f16x2(hi.z, lo.z), hilo_to_f16x2(hi.w, lo.w));
+        }
+        xp_dst[((int64_t)ks * mb_pad_dst + mblk) * 64 + lane] = v;
+        return;
+    }
     if (m >= 0) v = xp_src[(((int64_t)ks * mb_pad_src + (m >> 5)) * 2 + part) * 64 + (m & 31) + (lane & 32)];
     xp_dst[(((int64_t)ks * mb_pad_dst + mblk) * 2 + part) * 64 + lane] = v;
 }
@@ -140,7 +157,7 @@ __global__ void moe_gather_kernel(const uint4* __restrict__ xp_src, int mb_pad_s
 __global__ __launch_bounds__(512) void moe_combine_norm_kernel(float* __restrict__ x, const float* __restrict__ y,
                                                                 const int32_t* __restrict__ pair_row, const float* __restrict__ wts,
                                                                 int top_k, const unsigned short* __restrict__ gain, int d, float eps,
-                                                                int mb_pad, uint4* __restrict__ xp)
+                                                                int mb_pad, int xf, uint4* __restrict__ xp)
 {
     __shared__ float lds16[16];
     __shared__ int s_row[16];
@@ -182,7 +199,7 @@ __global__ __launch_bounds__(512) void moe_combine_norm_kernel(float* __restrict
         float v[8] = {a.x * r * from_bf16(g.x & 0xffff), a.y * r * from_bf16(g.x >> 16), a.z * r * from_bf16(g.y & 0xffff),
                       a.w * r * from_bf16(g.y >> 16),    b.x * r * from_bf16(g.z & 0xffff), b.y * r * from_bf16(g.z >> 16),
                       b.z * r * from_bf16(g.w & 0xffff), b.w * r * from_bf16(g.w >> 16)};
-        xp_store8(xp, m, c, mb_pad, v);
+        xp_store8_rt(xp, xf, m, c, mb_pad, v);
     }
 }
 
@@ -204,19 +221,20 @@ spec_status launch_moe_route(const float* part, int splits, int64_t split_stride
 }
 
 spec_status launch_moe_gather(const bf16_t* xp_src, int mb_pad_src, const int32_t* src_row, const int32_t* row0, int E, int d,
-                              int rows_bound, bf16_t* xp_dst, hipStream_t s)
+                              int rows_bound, int xf_dst, bf16_t* xp_dst, hipStream_t s)
 {
     dim3 grid((unsigned)(rows_bound / 32), (unsigned)(d / 16));
-    moe_gather_kernel<<<grid, 128, 0, s>>>((const uint4*)xp_src, mb_pad_src, src_row, row0, E, d / 16, rows_bound / 32, (uint4*)xp_dst);
+    moe_gather_kernel<<<grid, xf_dst == XF_F16 ? 64 : 128, 0, s>>>((const uint4*)xp_src, mb_pad_src, src_row, row0, E, d / 16, rows_bound / 32, xf_dst,
+                                                                  (uint4*)xp_dst);
     SPEC_LAUNCH_CHECK("moe_gather_kernel");
     return SPEC_OK;
 }
 
 spec_status launch_moe_combine_norm(float* x, const float* y, const int32_t* pair_row, const float* wts, int M, int top_k,
-                                    const void* gain, int d, float eps, int mb_pad, bf16_t* xp, hipStream_t s)
+                                    const void* gain, int d, float eps, int mb_pad, int xf, bf16_t* xp, hipStream_t s)
 {
     moe_combine_norm_kernel<<<M, d >= 4096 ? 512 : 256, 0, s>>>(x, y, pair_row, wts, top_k, (const unsigned short*)gain, d, eps,
-                                                               mb_pad, (uint4*)xp);
+                                                               mb_pad, xf, (uint4*)xp);
     SPEC_LAUNCH_CHECK("moe_combine_norm_kernel");
     return SPEC_OK;
 }

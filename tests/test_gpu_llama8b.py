@@ -3,10 +3,11 @@ B=32, contexts 1024..8192, k=3, and the large rollout batch B=256, contexts 2048
 (bf16, shuffled 16-token pages; the large batch on 8 aliased layer pools, which the oracle sees as
 layers l and l+8 reading the same cached context).
 
-The CPU oracle cannot run all 32 sequences in a test's time, and a sequence's logits depend only on
-its own rows and its own cache, so the logits are checked on sampled sequences (the shortest and
-the longest context: fewest and most attention chunks) computed by the oracle one sequence at a
-time, within 2e-2 abs + 1e-2 rel.  Inputs are the seeded generator's: weights N(0, 0.02) in bf16,
+The CPU oracle cannot run all sequences in a test's time, and a sequence's logits depend only on
+its own rows and its own cache, so the logits are checked on sampled sequences computed by the oracle:
+the shortest and the longest context (fewest and most attention chunks) plus sequences chosen so that
+every 32-row block of the GEMMs' 128-row tiles (B = 32: batch entries 0, 7, 8, 15, 16, 23, 24, 31) and, at
+B = 256, at least one sequence in every 128 rows of the deepest draft is compared; within 2e-2 abs + 1e-2 rel.  Inputs are the seeded generator's: weights N(0, 0.02) in bf16,
 cache N(0, 1) in bf16 (a real prefill of 150k tokens is out of the oracle's reach), tokens uniform.
 The sampler at this vocabulary and batch size is covered on generator-made logits in
 test_gpu_sampler.py; the commit is checked here against the oracle's book with seeded accept lengths.
@@ -22,12 +23,18 @@ from tests.helpers import logits_close
 
 pytestmark = pytest.mark.gpu
 
-def _check_workload(name, ks, moe_margin=None, more_picks=(3, 17, 40, 99)):
+def _one_per_tile(B, rows_per_seq, tile_rows=128):
+    """One batch entry inside every run of tile_rows GEMM rows, at varying places inside the run."""
+    per = max(1, tile_rows // rows_per_seq)
+    return {min(B - 1, t * per + (5 * t + 3) % per) for t in range(-(-B // per))}
+
+
+def _check_workload(name, ks, moe_margin=None, more_picks=(), max_exempt_frac=0.25):
     from paper_2604_26779_amd.workloads import DeviceWorkload
     wl = DeviceWorkload(name)
     cfg, B = wl.cfg, wl.B
     rng = np.random.default_rng(123)
-    picks = sorted({int(np.argmin(wl.ctx_len)), int(np.argmax(wl.ctx_len))} | (set(more_picks) if moe_margin is not None else set()))
+    picks = sorted({int(np.argmin(wl.ctx_len)), int(np.argmax(wl.ctx_len))} | {b for b in more_picks if b < B})
     weights = si.make_weights(cfg, seed=wl.seed, device="cuda")           # the generator's weights again, for the oracle
     w_or = si.weights_for_oracle(cfg, weights, library_decode=True)
     del weights
@@ -60,7 +67,7 @@ def _check_workload(name, ks, moe_margin=None, more_picks=(3, 17, 40, 99)):
                 fragile |= ((srt[:, cfg["top_k"] - 1] - srt[:, cfg["top_k"]]) < moe_margin).reshape(len(picks), k + 1)
             keep = ~np.logical_or.accumulate(fragile, axis=1)
             print("  rows exempted for routing margins: %d of %d" % ((~keep).sum(), keep.size), flush=True)
-            assert keep.sum() >= keep.size // 2
+            assert (~keep).sum() <= max_exempt_frac * keep.size, ((~keep).sum(), keep.size)
             got, want = got[keep], want[keep]
         ok, max_err, worst = logits_close(got, want, 2e-2, 1e-2)
         print("  logits max abs err %.3e, |logit| max %.2f" % (max_err, np.abs(want).max()), flush=True)
@@ -78,16 +85,23 @@ def _check_workload(name, ks, moe_margin=None, more_picks=(3, 17, 40, 99)):
             if kv8:
                 # codes: equal to the oracle's, or the neighbouring code where the value sat at a rounding boundary; near zero
                 # the grid (steps of 2^-9 * scale = 4e-5) is finer than the kernels' own error after 32 layers, so there
-                # the values are compared instead (2e-3, the bf16 path's bound on a key or value entry)
+                # the values are compared instead, with the bound the bf16 cache's entries get below: a key or value entry
+                # is a projection of the same normalised hidden state as a logit, by weights of the same size
                 from oracle import fp8
                 rank = lambda code: np.where(code.astype(np.int64) & 0x80, -(code.astype(np.int64) & 0x7F), code.astype(np.int64) & 0x7F)
                 for which, dev in ((0, K), (1, V)):
                     want_code = fp8.encode(new_kv[last][which][j] / np.float64(scales[which][last])[None, :, None])
                     got_code = dev[c:].cpu().numpy()
                     diff = np.abs(rank(got_code) - rank(want_code))
-                    far = np.abs(fp8.decode(got_code) - fp8.decode(want_code)) * np.float64(scales[which][last])[None, :, None] > 2e-3
-                    assert not np.any((diff > 1) & far), "a stored code is neither the oracle's neighbour nor within 2e-3 of it"
-                    assert (diff >= 1).sum() <= 0.02 * diff.size, (diff.max(), (diff >= 1).sum())
+                    bound = 2e-2 * max(1.0, np.abs(new_kv[last][which][j]).max())
+                    far = np.abs(fp8.decode(got_code) - fp8.decode(want_code)) * np.float64(scales[which][last])[None, :, None] > bound
+                    assert not np.any((diff > 1) & far), "a stored code is neither the oracle's neighbour nor within the bound of it"
+                    # how many codes may differ at all: a code flips where the value's error exceeds its distance to a rounding
+                    # boundary, so the fraction is about E|error| / grid spacing; with value errors up to the logits tolerance
+                    # (rms 3e-3 after 32 layers) on entries of size 1 under a grid of 1/8 .. 1/16 relative steps, finer for
+                    # the many small entries, that is 5-10 %
+                    print("  8-bit %s codes that differ from the oracle's: %d of %d" % ("KV"[which], (diff >= 1).sum(), diff.size), flush=True)
+                    assert (diff >= 1).sum() <= 0.15 * diff.size, (diff.max(), (diff >= 1).sum())
                 continue
             assert np.max(np.abs(K[c:].float().cpu().numpy() - new_kv[last][0][j])) < 2e-2 * max(1.0, np.abs(new_kv[last][0][j]).max())
             assert np.max(np.abs(V[c:].float().cpu().numpy() - new_kv[last][1][j])) < 2e-2 * max(1.0, np.abs(new_kv[last][1][j]).max())
@@ -105,39 +119,46 @@ def _check_workload(name, ks, moe_margin=None, more_picks=(3, 17, 40, 99)):
     torch.cuda.empty_cache()
 
 
+B32_BLOCK_PICKS = (0, 7, 8, 15, 16, 23, 24, 31)        # first and last batch entry of every 32-row block at k = 3
+
+
 def test_llama8b_logits_on_sampled_sequences_and_commit():
-    _check_workload("llama8b_b32_ctx1k-8k_k3", [3])
+    _check_workload("llama8b_b32_ctx1k-8k_k3", [3], more_picks=B32_BLOCK_PICKS)
 
 
-def test_llama8b_large_batch_aliased_pool_k7_and_k1():
-    _check_workload("llama8b_b256_ctx2k-16k_k7", [7, 1])
+def test_llama8b_large_batch_aliased_pool_all_draft_lengths():
+    """k = 7, 5, 3, 1 on the aliased bf16 pools; the sampled sequences cover every 128 rows at k = 7 (and so at every k)."""
+    _check_workload("llama8b_b256_ctx2k-16k_k7", [7, 5, 3, 1], more_picks=_one_per_tile(256, 8))
 
 
 def test_llama8b_8bit_cache_full_size():
     """The same step with the E4M3 cache (codes N(0, 48) under per-(layer, kv head) scales)."""
-    _check_workload("llama8b_kv8_b32_ctx1k-8k_k3", [3])
+    _check_workload("llama8b_kv8_b32_ctx1k-8k_k3", [3], more_picks=B32_BLOCK_PICKS[::2])
 
 
 def test_llama8b_8bit_matrices_and_cache_full_size():
     """The 8B shape with E4M3 matrices (one scale per output row) and the E4M3 cache: the oracle multiplies by the
     dequantised matrices (code * scale), the kernels widen the codes in registers."""
-    _check_workload("llama8b_w8kv8_b32_ctx1k-8k_k3", [3])
+    _check_workload("llama8b_w8kv8_b32_ctx1k-8k_k3", [3], more_picks=B32_BLOCK_PICKS[1::2])
 
 
 def test_llama8b_8bit_cache_large_batch_all_layers_distinct():
     """B = 256, contexts 2048..16384: with one byte per entry the cache of 32 distinct layers (155 GB) fits one GPU,
     so no layer pools are shared here."""
-    _check_workload("llama8b_kv8_b256_ctx2k-16k_k3", [3])
+    _check_workload("llama8b_kv8_b256_ctx2k-16k_k3", [3], more_picks=_one_per_tile(256, 4))
+
+
+MOE_PICKS = (3, 17, 29, 40, 55, 64, 78, 99, 110, 127)
 
 
 def test_moe_slice_full_size():
     """4 mixture-of-experts layers at 235B-A22B widths (128 experts, top-8), B = 128, contexts 4096..32768, k = 3."""
-    _check_workload("moe235b_slice_b128_ctx4k-32k_k3", [3], moe_margin=1e-3)
+    _check_workload("moe235b_slice_b128_ctx4k-32k_k3", [3], moe_margin=1e-3, more_picks=MOE_PICKS)
 
 
 def test_moe_slice_full_size_8bit_matrices_and_cache():
     """The same slice with every projection (experts included) as E4M3 codes and the E4M3 cache."""
-    _check_workload("moe235b_slice_w8kv8_b128_ctx4k-32k_k3", [3], moe_margin=1e-3, more_picks=(17,))
+    _check_workload("moe235b_slice_w8kv8_b128_ctx4k-32k_k3", [3], moe_margin=1e-3, more_picks=MOE_PICKS)
 
 
 def test_draft_pair_full_size_on_sampled_sequences():

@@ -4,7 +4,8 @@ The router's top-k choice is an integer decided by floating point: where the ora
 the last chosen and the first rejected expert (difference of router logits) is below 2e-3 in some layer,
 the kernels' bf16-pair arithmetic may legitimately choose the other expert, and every later row of that
 sequence (which attends to the affected position) changes with it.  Such rows are counted, reported and
-exempted; all other rows must meet the bf16 logits tolerance (2e-2 abs + 1e-2 rel).
+exempted; all other rows must meet the bf16 logits tolerance (2e-2 abs + 1e-2 rel).  The exempted rows depend on the
+oracle and the inputs alone; the seeds below are ones for which they stay at or below a tenth of the rows.
 """
 import numpy as np
 import pytest
@@ -81,27 +82,27 @@ def test_small_moe_workload():
     wl = si.WORKLOADS["small_moe_b6_k3"]
     cfg = si.MODELS[wl["model"]]
     ctx = [int(c) for c in si.make_batch(wl)["ctx_len"]]
-    max_err, n_exempt, n_rows, loads = _run(cfg, ctx, wl["k"], seed=11)
+    max_err, n_exempt, n_rows, loads = _run(cfg, ctx, wl["k"], seed=14)
     print("small moe: max abs err %.3e on %d rows, %d exempted; rows per expert (layer 0): %s" % (max_err, n_rows - n_exempt, n_exempt, loads[0]))
-    assert n_exempt <= n_rows // 4
+    assert n_exempt <= max(2, n_rows // 10), (n_exempt, n_rows)
 
 
-@pytest.mark.parametrize("B,k,changes", [
-    (96, 3, {}),                                             # ~96 rows per expert: two 64-row tiles each, M = 384
-    (3, 0, {}),                                              # fewer rows than experts: most experts idle
-    (20, 5, dict(n_experts=4, top_k=4)),                     # every expert on every row
-    (33, 1, dict(n_experts=200, top_k=8, n_q_heads=8, n_kv_heads=2)),   # more experts than one wavefront's lanes
-    (8, 2, dict(n_experts=5, top_k=1, expert_ffn_dim=768)),  # top-1 routing, wider experts
+@pytest.mark.parametrize("B,k,changes,seed", [
+    (96, 3, {}, 675),                                             # ~96 rows per expert: two 64-row tiles each, M = 384
+    (3, 0, {}, 21),                                               # fewer rows than experts: most experts idle
+    (20, 5, dict(n_experts=4, top_k=4), 145),                     # every expert on every row
+    (33, 1, dict(n_experts=200, top_k=8, n_q_heads=8, n_kv_heads=2), 234),   # more experts than one wavefront's lanes
+    (8, 2, dict(n_experts=5, top_k=1, expert_ffn_dim=768), 58),   # top-1 routing, wider experts
 ])
-def test_moe_shapes(B, k, changes):
+def test_moe_shapes(B, k, changes, seed):
     cfg = dict(si.MODELS["small_moe_bf16"], vocab=1000)
     cfg.update(changes)
     rng = np.random.default_rng(B + k)
     ctx = [int(c) for c in rng.integers(0, 150, size=B)]
-    max_err, n_exempt, n_rows, loads = _run(cfg, ctx, k, seed=B * 7 + k)
+    max_err, n_exempt, n_rows, loads = _run(cfg, ctx, k, seed=seed)
     print("moe B=%d k=%d %s: max abs err %.3e on %d rows, %d exempted; max rows/expert %d, idle experts %d" %
           (B, k, changes, max_err, n_rows - n_exempt, n_exempt, loads[0].max(), (loads[0] == 0).sum()))
-    assert n_exempt <= max(2, n_rows // 4)
+    assert n_exempt <= max(2, n_rows // 10), (n_exempt, n_rows)
 
 
 def test_small_moe_with_the_8bit_cache():
@@ -111,7 +112,7 @@ def test_small_moe_with_the_8bit_cache():
     ctx = [int(c) for c in si.make_batch(wl)["ctx_len"]]
     max_err, n_exempt, n_rows, loads = _run(cfg, ctx, wl["k"], seed=12)
     print("small moe, 8-bit cache: max abs err %.3e on %d rows, %d exempted" % (max_err, n_rows - n_exempt, n_exempt))
-    assert n_exempt <= n_rows // 4
+    assert n_exempt <= max(2, n_rows // 10), (n_exempt, n_rows)
 
 
 @pytest.mark.parametrize("B,k,changes", [(6, 3, {}), (96, 3, {}), (20, 5, dict(n_experts=4, top_k=4)), (8, 2, dict(n_experts=5, top_k=1, expert_ffn_dim=768))])
@@ -124,4 +125,4 @@ def test_moe_with_8bit_matrices_and_cache(B, k, changes):
     ctx = [int(c) for c in rng.integers(0, 150, size=B)]
     max_err, n_exempt, n_rows, loads = _run(cfg, ctx, k, seed=B * 7 + k)
     print("moe, 8-bit matrices and cache, B=%d k=%d %s: max abs err %.3e on %d rows, %d exempted" % (B, k, changes, max_err, n_rows - n_exempt, n_exempt))
-    assert n_exempt <= max(2, n_rows // 4)
+    assert n_exempt <= max(2, n_rows // 10), (n_exempt, n_rows)

@@ -70,11 +70,13 @@ def test_draft_equal_target_and_zero_probability_draft():
     n_gpu, out_gpu, _ = _run_gpu(logits, q, draft, 1.0, 99, 0)
     n_or, out_or = oracle_sampler.reject_sample(logits, q, draft, 1.0, 99, 0)
     # P/Q is 1 up to rounding: the oracle accepts everything; the kernel may reject only where its
-    # fp32 P rounds below Q and u lands within that rounding of 1
+    # fp32 P rounds below Q and u lands within that rounding of 1, i.e. only in a trial with |u - P/Q| < 1e-3
+    # (the stated exemption), of which 40 x 3 uniform draws hold 0.12 on average
     assert np.all(n_or == k)
-    assert (n_gpu == k).mean() > 0.9
-    agree = n_gpu == k
-    assert np.array_equal(out_gpu[agree], out_or[agree])
+    n_or2, out_or2, pqu, keys = oracle_sampler.reject_sample(logits, q, draft, 1.0, 99, 0, debug=True)
+    stats = assert_sampler_parity(n_gpu, out_gpu, n_or2, out_or2, pqu, keys)
+    print("draft == target:", stats)
+    assert stats["exempt_used"] <= stats["near_threshold"] + stats["near_tie"]
 
     # a one-hot draft distribution on a token the target gives zero probability
     logits2 = logits.copy()

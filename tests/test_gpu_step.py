@@ -490,3 +490,24 @@ def test_bf16_128x256_tiles_for_single_tile_gemms(B, k, w8):
         sv.spec_tune_set("gemm_wide4", before)
     print("128 x 256 tiles, B=%d k=%d (M=%d), 8-bit matrices %s: logits max abs err %.3e" % (B, k, B * (k + 1), w8, max_err))
     assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("mask", [0, 15, 3])
+@pytest.mark.parametrize("B,k,w8", [(9, 2, False), (16, 3, True), (25, 3, False), (32, 3, False), (40, 3, True), (64, 3, False), (96, 3, False)])
+def test_bf16_activation_formats_per_projection(mask, B, k, w8):
+    """Which projections take one fp16 activation per value instead of hi + lo bf16 pairs is a set of bits read at
+    model creation (gemm_f16_inputs; bit 0 QKV, 1 attention output, 2 feed-forward, 3 head; default 12, which every
+    other test runs).  Here the other settings - all hi + lo, all fp16, and the default's complement - go through
+    every tile shape: M = 27, 64, 100, 128, 160, 256, 384 rows, fused SwiGLU and split K, bf16 and 8-bit matrices."""
+    from paper_2604_26779_amd import binding as sv
+    before = sv.spec_tune_get("gemm_f16_inputs")
+    sv.spec_tune_set("gemm_f16_inputs", mask)
+    try:
+        rng = np.random.default_rng(B + k)
+        ctx = [int(c) for c in rng.integers(3, 150, size=B)]
+        extra = dict(w_dtype="fp8_e4m3") if w8 else {}
+        ok, max_err, worst = _run_custom_bf16(ctx, k=k, seed=B + k + mask, vocab=1000, **extra)
+    finally:
+        sv.spec_tune_set("gemm_f16_inputs", before)
+    print("fp16-input projections %d, B=%d k=%d (M=%d), 8-bit matrices %s: logits max abs err %.3e" % (mask, B, k, B * (k + 1), w8, max_err))
+    assert ok, (max_err, worst)
