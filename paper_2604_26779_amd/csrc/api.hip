@@ -35,6 +35,7 @@ static std::map<std::string, int>& tune_table()
         {"gemm_big_min_tiles", 200}, // a GEMM with at least this many 256-column tiles takes them without further conditions
         {"gemm_tiles_96", 1},       // 129..256 rows, fused gate/up projection: two 96- or 128-row x 256-column tiles per column stripe instead of three or four 64-row ones
         {"gemm_wide4", 400},        // single-tile 128-row GEMMs with a plain epilogue take 128 x 256 tiles from this many such tiles on (0 = never)
+        {"gemm_one_block", 1},      // 97..128 rows, fp16 activations: one 128 x 128 tile, wavefronts 1 x 4 with one column block each (0: as with hi + lo operands)
         {"moe_wide_tiles", 1},      // grouped expert GEMMs: 64 x 256 tiles, wavefronts 1 x 4 (0: 64 x 128, wavefronts 2 x 2)
         {"gemm_big_min_blocks", 5}, // from this many 32-row blocks on, a GEMM may take 192/256-row x 256-column tiles (0 = never)
         {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup

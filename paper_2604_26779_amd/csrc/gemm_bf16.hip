@@ -486,6 +486,35 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
             }
         }
         return;
+    } else if constexpr (EPI == GEMM_EPI_SWIGLU && WM == 1 && NBW == 1) {
+        // 128-column tile of the 1 x 4 arrangement with one column block per wavefront: wavefronts 0 and 2 hold the gates,
+        // 1 and 3 the ups of 2 x 32 hidden channels.  The raw accumulators go through LDS one row block at a time, and
+        // silu(gate) * up is formed on the way out.
+        float* tile = (float*)lds;                              // [32 rows][129]
+        uint4* xo = (uint4*)out;
+#pragma unroll
+        for (int i = 0; i < MBW; ++i) {
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                tile[row * 129 + np * 32 + (lane & 31)] = W8 ? acc[i][0][r] * wsc[0] : acc[i][0][r];
+            }
+            __syncthreads();
+            {
+                const int e = threadIdx.x;                      // 32 rows x 8 groups of 8 hidden channels
+                const int row = e >> 3, g8 = e & 7;
+                const int m = (mblk0 + i) * 32 + row, f = bx * 64 + g8 * 8;
+                if (m < M && f < N / 2) {
+                    const float* src = tile + row * 129 + (g8 >> 2) * 64 + (g8 & 3) * 8;
+                    float v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) { const float g = src[j], u = src[32 + j]; v[j] = g / (1.0f + __expf(-g)) * u; }
+                    xp_store8_t<XF>(xo, m, f, mb_pad, v);
+                }
+            }
+        }
+        return;
     } else if constexpr (EPI == GEMM_EPI_SWIGLU && WM == 1) {
         // 256-column tile of the 1 x 4 arrangement (each wavefront: all MB row blocks, gate and up of 32 hidden channels):
         // the same transpose through LDS, one row block (32 rows x 128 channels) at a time.
@@ -588,7 +617,7 @@ int gemm_mb_pad(int M)
     return (int)cdiv(nb, mb) * mb;
 }
 
-struct GemmShape { int mb, tile_nb, kunit, m_tiles, n_tiles; bool wide = false; };
+struct GemmShape { int mb, tile_nb, kunit, m_tiles, n_tiles; bool wide = false, one_block = false; };
 static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
 {
     GemmShape g;
@@ -625,6 +654,15 @@ static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
     // only is not launched.
     // 129..256 rows where K is not split (the fused gate/up projection): two tiles of 96 or 128 rows instead of three or four of
     // 64 - 2 x 112 workgroups fit the chip at once, 3 x 112 and 4 x 112 do not.
+    // 97..128 rows with fp16 activations: one tile of 128 rows x 128 columns with the wavefronts 1 x 4, each its own column
+    // block over all four row blocks.  Every weight fragment is then fetched by exactly one wavefront of one workgroup
+    // (the pair of 64-row tiles fetches each twice, which takes up half of a CU's outstanding-request window with
+    // duplicates), at the price of one LDS read per MFMA, which the single fp16 MFMA per fragment leaves room for:
+    // gate/up 56 -> 50 us, down 31 -> 26 us at the 8B shape.  With hi + lo operands the pair stays ahead.
+    if (g.mb == 4 && g.m_tiles == 1 && W.f16 && tune("gemm_one_block") != 0 && W.n_blocks % 4 == 0) {
+        g.one_block = true; g.tile_nb = 4; g.n_tiles = W.n_blocks / 4; g.kunit = GEMM_KS * 2;
+        return g;
+    }
     if (g.mb == 4 && g.m_tiles <= tune("gemm_split_rows") && W.n_blocks % 8 == 0) {
         const int nb = (int)cdiv(M, 32);
         if (fused_swiglu && nb >= 5 && tune("gemm_tiles_96") != 0) g.mb = nb <= 6 ? 3 : 4;
@@ -651,7 +689,7 @@ int gemm_pick_splits(const PackedW& W, int M, int forced)
 // out must hold splits * M * ldo floats; with swiglu (gate/up projection, splits == 1, an even number
 // of row blocks) out is instead the hi + lo operand buffer of silu(gate) * up, [N/2] channels wide.
 // Returns SPEC_EUNSUPPORTED (nothing launched) if swiglu is asked for a shape it cannot fuse.
-bool gemm_can_fuse_swiglu(const PackedW& W, int M, int splits) { if (splits != 1) return false; const GemmShape g = gemm_shape(W, M, true); return g.mb % 2 == 0 || (g.wide && g.mb == 3); }
+bool gemm_can_fuse_swiglu(const PackedW& W, int M, int splits) { if (splits != 1) return false; const GemmShape g = gemm_shape(W, M, true); return g.mb % 2 == 0 || (g.wide && g.mb == 3) || g.one_block; }
 
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s)
 {
@@ -664,6 +702,7 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
     const u32x4_t* xp = (const u32x4_t*)Xp;
     if (swiglu && !gemm_can_fuse_swiglu(W, M, splits)) { set_error("gemm: SwiGLU cannot be fused for this shape"); return SPEC_EUNSUPPORTED; }
 #define SPEC_GEMM_LAUNCH_W(MBV, WMV, WDV, E, W8V, XFV) gemm_bf16_kernel<MBV, WMV, WDV, E, false, (MBV % 2 == 0 && WMV == 1) ? 2 : WMV, W8V, XFV><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
+#define SPEC_GEMM_LAUNCH_1BW(E, W8V, XFV) gemm_bf16_kernel<4, 1, 2, E, false, 1, W8V, XFV><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
 #define SPEC_GEMM_LAUNCH_96W(E, W8V, XFV) gemm_bf16_kernel<3, 1, 2, E, false, 2, W8V, XFV><<<grid, GEMM_THREADS, 0, s>>>(wp, xp, out, W.n_blocks, W.k_steps, kps, mb_pad, M, W.N, ldo, stride, nullptr, 0, W.scale)
     // the four combinations of 8-bit or 16-bit weights and hi + lo or fp16 activations
 #define SPEC_GEMM_BY_TYPE(CALL, ...) do { \
@@ -701,7 +740,11 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
         case 6: if (swiglu) SPEC_GEMM_LAUNCH_BIG(6, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH_BIG(6, GEMM_EPI_PLAIN); break;
         case 8: if (swiglu) SPEC_GEMM_LAUNCH_BIG(8, GEMM_EPI_SWIGLU); else SPEC_GEMM_LAUNCH_BIG(8, GEMM_EPI_PLAIN); break;
         default:
-            if (g.wide && swiglu) SPEC_GEMM_LAUNCH(4, 1, 2, GEMM_EPI_SWIGLU);
+            if (g.one_block) {                               // fp16 activations only
+                if (W.w8) { if (swiglu) SPEC_GEMM_LAUNCH_1BW(GEMM_EPI_SWIGLU, true, XF_F16); else SPEC_GEMM_LAUNCH_1BW(GEMM_EPI_PLAIN, true, XF_F16); }
+                else { if (swiglu) SPEC_GEMM_LAUNCH_1BW(GEMM_EPI_SWIGLU, false, XF_F16); else SPEC_GEMM_LAUNCH_1BW(GEMM_EPI_PLAIN, false, XF_F16); }
+            }
+            else if (g.wide && swiglu) SPEC_GEMM_LAUNCH(4, 1, 2, GEMM_EPI_SWIGLU);
             else if (g.wide) SPEC_GEMM_LAUNCH(4, 1, 2, GEMM_EPI_PLAIN);
             else if (swiglu) SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_SWIGLU);
             else SPEC_GEMM_LAUNCH(4, 2, 2, GEMM_EPI_PLAIN);
@@ -711,6 +754,7 @@ spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* o
 #undef SPEC_GEMM_BY_TYPE
 #undef SPEC_GEMM_LAUNCH_96
 #undef SPEC_GEMM_LAUNCH_96W
+#undef SPEC_GEMM_LAUNCH_1BW
 #undef SPEC_GEMM_LAUNCH_BIG_W
 #undef SPEC_GEMM_LAUNCH
 #undef SPEC_GEMM_LAUNCH_W
