@@ -235,12 +235,13 @@ spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const float* dev
 /*
  * spec_reject_sample for callers that cannot allocate device memory or carry a workspace along: code recorded under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic, random
- * streams and outputs as spec_reject_sample, minus the workspace: the row statistics live in a buffer that is part
- * of the loaded library (128 KiB of device memory per GPU, held until the process ends).  The call allocates and
- * frees nothing.  Limit: B * (k + 1) <= 16384 logits rows, SPEC_EINVAL beyond (use spec_reject_sample then).
+ * streams and outputs as spec_reject_sample, minus the workspace: the row statistics and per-range race results live
+ * in a buffer that is part of the loaded library (384 KiB of device memory per GPU, held until the process ends).
+ * The call allocates and frees nothing.  Limit: B * (k + 1) <= 4096 logits rows, SPEC_EINVAL beyond (use
+ * spec_reject_sample then).
  * All calls on one GPU share that buffer: calls whose work may overlap on one GPU (different streams, or graphs
  * replayed concurrently) race on it; calls on one stream, or otherwise ordered, are safe, and nothing needs
- * clearing between them (every row's statistics are written before they are read).  The buffer's address is looked
+ * clearing between them (every entry is written before it is read).  The buffer's address is looked
  * up on the first call on each GPU (that first call should not itself be under capture).  Asynchronous on `stream`.
  */
 spec_status spec_reject_sample_static(int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,

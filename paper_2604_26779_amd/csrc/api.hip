@@ -40,7 +40,9 @@ static std::map<std::string, int>& tune_table()
         {"gemm_big_min_blocks", 5}, // from this many 32-row blocks on, a GEMM may take 192/256-row x 256-column tiles (0 = never)
         {"gemm_min_ksteps", 32},   // never split below this many 16-wide k-steps per workgroup
         {"splits_qkv", 0}, {"splits_o", 0}, {"splits_gu", 0}, {"splits_down", 0}, {"splits_head", 0},   // 0 = auto
-        {"attn_chunk_pages", 0},   // KV pages per attention workgroup (a multiple of 4 up to 256; 0 = by batch size and context bound)
+        {"attn_chunk_pages", 0},   // KV pages per attention workgroup (a multiple of 4 up to 256; 0 = chosen on the device from the batch's contexts)
+        {"attn_rounds", 1},        // the attention's work list is cut to fill the chip's resident workgroups this many times over (B=32, contexts 1k..8k: 3.41 ms of attention per step at 1, 3.54 at 2, 3.60 at 3)
+        {"attn_min_pages", 16},    // shortest chunk the device-side choice may take (pages)
         // Which projections take one fp16 activation per value (one MFMA per weight fragment, weights tiled as fp16) instead of
         // hi + lo bf16 pairs (two MFMAs): bit 0 QKV, 1 attention output, 2 feed-forward (gate/up and down, experts included),
         // 3 output head.  Read at spec_model_create.  Default 12: the feed-forward and the head; the attention block's inputs
@@ -347,6 +349,8 @@ specv::KvView spec_kv::view() const
 {
     KvView v;
     v.pool = pool;
+    v.entry_seq = d_entry_seq;
+    v.error = d_error;
     v.ctx_len = d_ctx_len;
     v.n_held = d_n_held;
     v.page_table = d_page_table;
@@ -387,7 +391,7 @@ extern "C" spec_status spec_kv_alloc(const spec_model* m, int32_t max_seqs, int3
     kv->n_pages = n_pages;
     kv->pool = dev_pool;
     kv->state_ints = (size_t)max_seqs * 2 + (size_t)max_seqs * kv->max_pages + (size_t)n_pages + 2;
-    hipError_t e = hipMalloc((void**)&kv->d_state, kv->state_ints * sizeof(int32_t));
+    hipError_t e = hipMalloc((void**)&kv->d_state, (kv->state_ints + 3 * (size_t)max_seqs) * sizeof(int32_t));
     if (e != hipSuccess) { set_error("spec_kv_alloc: hipMalloc failed: %s", hipGetErrorString(e)); delete kv; return SPEC_ENOMEM; }
     int32_t* p = kv->d_state;
     kv->d_ctx_len = p; p += max_seqs;
@@ -395,7 +399,10 @@ extern "C" spec_status spec_kv_alloc(const spec_model* m, int32_t max_seqs, int3
     kv->d_page_table = p; p += (size_t)max_seqs * kv->max_pages;
     kv->d_free_stack = p; p += n_pages;
     kv->d_free_count = p; p += 1;
-    kv->d_error = p;
+    kv->d_error = p; p += 1;
+    kv->d_owner = p; p += max_seqs;
+    kv->d_entry_seq = p; p += max_seqs;
+    kv->d_entry_tmp = p;
     kv->h_ctx_len.assign(max_seqs, 0);
     kv->h_n_held.assign(max_seqs, 0);
     kv->h_page_table.assign((size_t)max_seqs * kv->max_pages, -1);
@@ -404,7 +411,9 @@ extern "C" spec_status spec_kv_alloc(const spec_model* m, int32_t max_seqs, int3
     kv->h_free_count = n_pages;
     kv->device_ahead = false;
     // upload
-    std::vector<int32_t> img(kv->state_ints, 0);
+    std::vector<int32_t> img(kv->state_ints + 3 * (size_t)max_seqs, 0);
+    std::fill(img.begin() + kv->state_ints, img.begin() + kv->state_ints + max_seqs, 0x7fffffff);       // d_owner
+    std::fill(img.begin() + kv->state_ints + max_seqs, img.end(), -1);
     std::fill(img.begin() + 2 * max_seqs, img.begin() + 2 * max_seqs + (size_t)max_seqs * kv->max_pages, -1);
     std::copy(kv->h_free_stack.begin(), kv->h_free_stack.end(), img.begin() + 2 * max_seqs + (size_t)max_seqs * kv->max_pages);
     img[kv->state_ints - 2] = (int32_t)n_pages;
@@ -524,7 +533,8 @@ extern "C" spec_status spec_kv_get_state(spec_kv* kv, int32_t* host_ctx_len, int
     if (host_free_stack) std::copy(kv->h_free_stack.begin(), kv->h_free_stack.end(), host_free_stack);
     if (host_n_free) *host_n_free = kv->h_free_count;
     if (err & 1) { set_error("a step ran out of KV pages; its sequences were left without new pages"); return SPEC_ENOMEM; }
-    if (err & 2) { set_error("a step was given a sequence id out of range"); return SPEC_EINVAL; }
+    if (err & 2) { set_error("a step was given a sequence id out of range, or the same id twice: those batch entries were left out"); return SPEC_EINVAL; }
+    if (err & 8) { set_error("a step met contexts longer than the bound its launch was sized for (a graph replayed from a longer cache state?): its logits are not valid"); return SPEC_ESTATE; }
     if (err & 4) { set_error("a sequence outgrew max_ctx_len"); return SPEC_EINVAL; }
     return SPEC_OK;
 }

@@ -4,7 +4,13 @@
 // ride on ONE pass over that head's cached keys and values: that sharing is what makes verifying
 // k drafts cost about one decode step.  The pass is split along the context so that short and
 // long sequences fill the machine evenly:
-//   attn_partial_kernel : workgroup = (chunk of pages, kv head, batch entry[, group of row blocks]); each of
+//   attn_plan_kernel    : once per forward pass (the contexts do not change between layers): the work list.  Every
+//                         sequence's pages are cut into chunks of (nearly) equal length, the length chosen on the
+//                         device, from the contexts the batch actually has, as the shortest for which the whole list
+//                         still fits the number of workgroups the chip holds in the rounds asked for - so a small
+//                         batch of ragged contexts fills every CU about equally instead of leaving a tail of
+//                         half-empty rounds;
+//   attn_partial_kernel : workgroup = (work item = chunk of a sequence's pages, kv head[, group of row blocks]); each of
 //                         its 4 wavefronts walks every 4th page of the chunk with its own online softmax,
 //                         reading K and V blocks straight into MFMA operand registers (the cache's
 //                         in-block layout is the operand order, so every load is a contiguous
@@ -33,7 +39,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int ATT_CP_MIN = 32;               // shortest chunk (pages per workgroup) the launch policy picks; longest: 256
+constexpr int ATT_CP_MAX = 256;              // longest chunk (pages per workgroup): a wavefront's page ids sit in one register
+constexpr int KV_ERR_BOUND = 8;              // error bit: more work items than the launch was sized for
 constexpr int ATT_WAVES = 4;
 constexpr int ATT_DEPTH = 3;                 // pages in flight per wavefront
 constexpr int DH = 128;
@@ -62,14 +69,102 @@ __device__ inline float quad_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// part_o : [item][rows][128] fp32, part_ml : [item][rows][2] (reference point in log2 domain, sum relative to it)
-// item = (b * Hkv + kvh) * max_chunks + chunk;  rows = attn_rows_padded(R)
+// One work item: pages [page0, page_end) of batch entry b (sequence seq, cached length ctx, `total` keys visible to the
+// last row; b = -1: unused slot of the list).  32 bytes, read with two 16-byte loads.
+struct AttnItem { int32_t b, seq, page0, page_end, ctx, total, chunk, pad; };
+
+// The work list of one forward pass.  One workgroup of 256.  pages(b) = pages holding the keys batch entry b may see
+// (0 for a dropped entry).  Chunk length L: the smallest multiple of 4 in [min_pages, 256] with sum_b ceil(pages(b) / L)
+// <= budget (256 if none; `forced` > 0 fixes L instead); entry b then has n = ceil(pages / L) items of
+// ceil(pages / n) pages rounded up to a multiple of 4 (the 4 wavefronts take every 4th page).  Items are listed in batch
+// order; entry_items[b] = (first item, number of items).  Slots of the list beyond the last item get b = -1.  More
+// items than max_items (contexts beyond the bound the launch was sized for) set KV_ERR_BOUND and are dropped.
+__global__ __launch_bounds__(256) void attn_plan_kernel(int B, int T, KvView kv, int budget, int min_pages, int forced, int max_items,
+                                                        AttnItem* __restrict__ items, int2* __restrict__ entry_items)
+{
+    __shared__ int s_cnt[256];
+    __shared__ int s_len, s_carry;
+    auto pages_of = [&](int b, int* seq_o, int* ctx_o, int* total_o) {
+        const int seq = kv.entry_seq[b];
+        int ctx = 0, total = 0;
+        if (seq >= 0) {
+            ctx = kv.ctx_len[seq];
+            total = ctx + T;
+            const int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
+            if (total > cap) total = cap;
+        }
+        if (seq_o) { *seq_o = seq; *ctx_o = ctx; *total_o = total; }
+        return (total + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
+    };
+    {
+        // candidate j: chunks of 4 (j + 1) pages; thread t counts candidate t % 64 over the entries t / 64, t / 64 + 4, ...
+        const int j = threadIdx.x & 63, len = 4 * (j + 1);
+        int cnt = 0;
+        for (int b = threadIdx.x >> 6; b < B; b += 4) cnt += (pages_of(b, nullptr, nullptr, nullptr) + len - 1) / len;
+        s_cnt[threadIdx.x] = cnt;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int best = ATT_CP_MAX;
+            for (int c = 63; c >= 0; --c) {
+                const int l = 4 * (c + 1);
+                if (l >= min_pages && s_cnt[c] + s_cnt[c + 64] + s_cnt[c + 128] + s_cnt[c + 192] <= budget) best = l;
+            }
+            s_len = forced > 0 ? forced : best;
+            s_carry = 0;
+        }
+        __syncthreads();
+    }
+    const int L = s_len;
+    for (int base = 0; base < B; base += 256) {
+        const int b = base + threadIdx.x;
+        int seq = -1, ctx = 0, total = 0;
+        const int p = b < B ? pages_of(b, &seq, &ctx, &total) : 0;
+        const int n = (p + L - 1) / L;
+        // exclusive scan of n over the workgroup
+        s_cnt[threadIdx.x] = n;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const int add = (int)threadIdx.x >= off ? s_cnt[threadIdx.x - off] : 0;
+            __syncthreads();
+            s_cnt[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int first = s_carry + s_cnt[threadIdx.x] - n, group_total = s_cnt[255];
+        __syncthreads();
+        if (b < B) {
+            const int len = n > 0 ? ((p + n - 1) / n + ATT_WAVES - 1) / ATT_WAVES * ATT_WAVES : 0;
+            int wrote = 0;
+            for (int c = 0; c < n; ++c) {
+                const int it = first + c;
+                if (it >= max_items) break;
+                AttnItem a;
+                a.b = b; a.seq = seq; a.page0 = c * len; a.page_end = (c + 1) * len < p ? (c + 1) * len : p;
+                a.ctx = ctx; a.total = total; a.chunk = c; a.pad = 0;
+                items[it] = a;
+                ++wrote;
+            }
+            entry_items[b] = make_int2(first < max_items ? first : 0, wrote);
+            if (wrote < n) atomicOr(kv.error, KV_ERR_BOUND);
+        }
+        if (threadIdx.x == 0) s_carry += group_total;
+        __syncthreads();
+    }
+    const int n_items = s_carry < max_items ? s_carry : max_items;
+    for (int it = n_items + threadIdx.x; it < max_items; it += 256) {
+        AttnItem a;
+        a.b = -1; a.seq = -1; a.page0 = 0; a.page_end = 0; a.ctx = 0; a.total = 0; a.chunk = 0; a.pad = 0;
+        items[it] = a;
+    }
+}
+
+// part_o : [item * Hkv + kv head][rows][128] fp32, part_ml : [..][rows][2] (reference point in log2 domain, sum relative
+// to it); rows = attn_rows_padded(R)
 // A workgroup takes NRB (1..4) blocks of 16 query rows.  What does not fit in registers for 4 of them moves: the
 // queries (hi + lo) sit in LDS in operand order and are re-read per page (double buffered, one row block ahead),
 // the accumulators of all row blocks stay in registers.  More than 64 query rows per kv head (deep drafts with many
 // query heads per kv head) are split into RG groups of NRB row blocks, one workgroup each; the groups of a (batch
 // entry, kv head, chunk) re-read the same pages, so they are placed on the same XCD (workgroups go to XCDs
-// round-robin by linear id: blockIdx.x spans a multiple of 8 values - kv head and the low bits of the batch index -
+// round-robin by linear id: blockIdx.x spans a multiple of 8 values - kv head and the low bits of the item index -
 // and the row group sits in blockIdx.y, 8 ids apart) and next to each other in dispatch order: the repeated reads
 // hit that XCD's L2.
 // The page loop is a run-time loop over groups of ATT_DEPTH pages (the register ring needs compile-time slots,
@@ -82,28 +177,19 @@ __device__ inline float quad_sum(float x)
 // folded into the score scale here, the value scale into the final normalisation (attn_reduce_kernel).
 template <int NRB, bool KV8>
 __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
-    const float* __restrict__ q, int T, int G, int Hq, const int32_t* __restrict__ seq_ids, KvView kv,
-    int layer_pool, int layer, float scale_log2_in, int max_chunks, int chunk_pages, int RG, int rows, int Hkv, int BP, int B,
+    const float* __restrict__ q, int T, int G, int Hq, const AttnItem* __restrict__ items, int max_items, KvView kv,
+    int layer_pool, int layer, float scale_log2_in, int RG, int rows, int Hkv, int IP,
     float* __restrict__ part_o, float* __restrict__ part_ml)
 {
-    const int kvh = blockIdx.x % Hkv, rb0 = (blockIdx.y % RG) * NRB, chunk = blockIdx.z;
-    const int b = (blockIdx.y / RG) * BP + blockIdx.x / Hkv;
-    if (b >= B) return;
-    const int seq = seq_ids[b];
-    const int ctx = kv.ctx_len[seq];
-    int total = ctx + T;
-    const int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
-    if (total > cap) total = cap;
-    const int n_pages_seq = (total + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
-    // the sequence's pages go over its ceil(pages / chunk_pages) chunks in equal shares (a multiple of the wavefront
-    // count each), so that no workgroup is left with a short tail chunk that is mostly prologue and merge
-    const int n_chunks_seq = (n_pages_seq + chunk_pages - 1) / chunk_pages;
-    if (chunk >= n_chunks_seq) return;
-    chunk_pages = ((n_pages_seq + n_chunks_seq - 1) / n_chunks_seq + ATT_WAVES - 1) / ATT_WAVES * ATT_WAVES;
-    const int page0 = chunk * chunk_pages;
-    if (page0 >= n_pages_seq) return;
-    int page_end = page0 + chunk_pages;
-    if (page_end > n_pages_seq) page_end = n_pages_seq;
+    const int kvh = blockIdx.x % Hkv, rb0 = (blockIdx.y % RG) * NRB;
+    const int it = (blockIdx.y / RG) * IP + blockIdx.x / Hkv;
+    if (it >= max_items) return;
+    int b, seq, page0, page_end, ctx, total;
+    {
+        const int4 i0 = ((const int4*)items)[2 * it], i1 = ((const int4*)items)[2 * it + 1];
+        b = i0.x; seq = i0.y; page0 = i0.z; page_end = i0.w; ctx = i1.x; total = i1.y;
+    }
+    if (b < 0 || seq < 0 || page0 >= page_end) return;
     int plain_end = ctx / SPEC_PAGE_SIZE;          // pages before this one are visible to every row, every slot valid
     if (plain_end > page_end) plain_end = page_end;
 
@@ -359,7 +445,7 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
     for (int rb = 0; rb < NRB; ++rb) lrow[rb] = quad_sum(lrow[rb]);
 
     // merge the 4 wavefronts through LDS, one row block at a time
-    const int64_t item = ((int64_t)b * Hkv + kvh) * max_chunks + chunk;
+    const int64_t item = (int64_t)it * Hkv + kvh;
     float* po = part_o + item * rows * DH;
     float* pml = part_ml + item * rows * 2;
 #pragma unroll
@@ -395,7 +481,7 @@ __global__ __launch_bounds__(256, NRB <= 2 ? 2 : 1) void attn_partial_kernel(
 // one thread per (batch entry, kv head, row, 8 channels): merge chunks, normalise, write the bf16
 // operand of the O projection: xp[k-step][m-block][lane][8] with k = head*128 + channel
 __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int B, int T,
-                                   int G, int Hkv, int RBrows, int max_chunks, int chunk_pages, const int32_t* __restrict__ seq_ids,
+                                   int G, int Hkv, int RBrows, const int2* __restrict__ entry_items,
                                    KvView kv, int layer, int mb_pad, int xf, uint4* __restrict__ xp)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -406,20 +492,17 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
     int r = (int)((idx / (DH / 8)) % R);
     int kvh = (int)((idx / (DH / 8) / R) % Hkv);
     int b = (int)(idx / (DH / 8) / R / Hkv);
-    int seq = seq_ids[b];
-    int totalk = kv.ctx_len[seq] + T;
-    int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
-    if (totalk > cap) totalk = cap;
-    int n_chunks = ((totalk + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE + chunk_pages - 1) / chunk_pages;
-    int64_t item0 = ((int64_t)b * Hkv + kvh) * max_chunks;
+    const int2 mine = entry_items[b];                        // (first item, number of items) of this batch entry
+    const int n_chunks = mine.y;
+    auto slot = [&](int c) { return ((int64_t)(mine.x + c) * Hkv + kvh) * RBrows + r; };
     float M = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part_ml[((item0 + c) * RBrows + r) * 2]);
+    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part_ml[slot(c) * 2]);
     float L = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < n_chunks; ++c) {
-        float mc = part_ml[((item0 + c) * RBrows + r) * 2];
+        float mc = part_ml[slot(c) * 2];
         float f = mc > -INFINITY ? exp2f(mc - M) : 0.f;      // branch-free: the loads of all chunks overlap
-        L += f * part_ml[((item0 + c) * RBrows + r) * 2 + 1];
-        const float4* src = (const float4*)(part_o + ((item0 + c) * RBrows + r) * DH + c8 * 8);
+        L += f * part_ml[slot(c) * 2 + 1];
+        const float4* src = (const float4*)(part_o + slot(c) * DH + c8 * 8);
         float4 a = src[0], d = src[1];
         o[0] += f * a.x; o[1] += f * a.y; o[2] += f * a.z; o[3] += f * a.w;
         o[4] += f * d.x; o[5] += f * d.y; o[6] += f * d.z; o[7] += f * d.w;
@@ -432,39 +515,38 @@ __global__ void attn_reduce_kernel(const float* __restrict__ part_o, const float
 }
 
 // How R query rows per kv head are laid over workgroups: RG groups of NRB row blocks, NRB <= 4 and as equal as
-// possible (tuning parameter attn_row_blocks = 1..4 caps NRB instead), and the chunk length: the longest of 32, 64,
-// 128, 256 pages that still leaves about two rounds of workgroups for the chip - longer chunks mean fewer
-// prologues, merges and partial results per byte.  The contexts are only known on the device; the host's bound on
-// the longest one stands in for all of them.  attn_chunk_pages overrides (a multiple of 4, at most 256).
-struct AttnPlan { int RB, RG, chunk_pages; };
+// possible (tuning parameter attn_row_blocks = 1..4 caps NRB instead).  How the contexts are cut into work items is
+// decided on the device (attn_plan_kernel); the host only gives the budget - the workgroups the chip holds at once
+// times attn_rounds, per kv head and row group - and sizes the list: at most max(budget, B * ceil(longest context /
+// 256 pages)) items, the host's bound on the longest context standing in for all of them.  attn_chunk_pages (a multiple
+// of 4, at most 256) fixes the chunk length instead.
+struct AttnPlan { int RB, RG, budget, forced, max_items; };
 static AttnPlan attn_plan(int R, int B, int Hkv, int pages_bound)
 {
     const int blocks = (int)cdiv(R, 16);
-    const int forced = tune("attn_row_blocks");
+    const int forced_rb = tune("attn_row_blocks");
     AttnPlan p;
-    if (forced >= 1 && forced <= 4) {
-        p.RB = forced < blocks ? forced : blocks;
+    if (forced_rb >= 1 && forced_rb <= 4) {
+        p.RB = forced_rb < blocks ? forced_rb : blocks;
         p.RG = (int)cdiv(blocks, p.RB);
     } else {
         p.RG = (int)cdiv(blocks, 4);
         p.RB = (int)cdiv(blocks, p.RG);
     }
     const int64_t slots = 256 * (p.RB <= 2 ? 2 : 1);         // workgroups resident at once
-    p.chunk_pages = ATT_CP_MIN;
-    for (int c = 2 * ATT_CP_MIN; c <= 256; c *= 2)
-        if ((int64_t)B * Hkv * p.RG * cdiv(pages_bound, c) >= 2 * slots) p.chunk_pages = c;
+    int rounds = tune("attn_rounds");
+    if (rounds < 1) rounds = 1;
+    p.budget = (int)std::max<int64_t>(1, slots * rounds / ((int64_t)Hkv * p.RG));
     const int cp = tune("attn_chunk_pages");
-    if (cp >= 4 && cp <= 256 && cp % ATT_WAVES == 0) p.chunk_pages = cp;
+    p.forced = (cp >= ATT_WAVES && cp <= ATT_CP_MAX && cp % ATT_WAVES == 0) ? cp : 0;
+    const int64_t by_length = (int64_t)B * cdiv(pages_bound, p.forced ? p.forced : ATT_CP_MAX);
+    p.max_items = (int)(p.forced ? by_length : std::max<int64_t>(p.budget, by_length));
     return p;
 }
 
-// the shortest chunk any launch of R query rows per kv head may use: sizes the partial-result buffers
-int attn_min_chunk_pages(int R)
-{
-    const int cp = tune("attn_chunk_pages");
-    if (cp >= 4 && cp <= 256 && cp % ATT_WAVES == 0 && cp < ATT_CP_MIN) return cp;
-    return ATT_CP_MIN;
-}
+// the most work items a forward pass over B entries of at most pages_bound pages may have: sizes the item list and the
+// partial-result buffers
+int attn_max_items(int R, int B, int Hkv, int pages_bound) { return attn_plan(R, B, Hkv, pages_bound).max_items; }
 
 // rows of a partial tile for R query rows per kv head: enough for every layout above (the workspace is sized before
 // the tuning parameters are final)
@@ -476,24 +558,36 @@ int attn_rows_padded(int R)
     return most * 16;
 }
 
-spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
-                                  const KvView& kv, int layer_pool, int layer, int pages_bound, float* part_o, float* part_ml,
+size_t attn_item_bytes() { return sizeof(AttnItem); }
+
+// once per forward pass, after the page reservation: the work list of all its attention launches
+spec_status launch_attention_plan(int B, int T, int G, int Hkv, const KvView& kv, int pages_bound, void* items, void* entry_items, hipStream_t s)
+{
+    const AttnPlan pl = attn_plan(T * G, B, Hkv, pages_bound);
+    int min_pages = tune("attn_min_pages");
+    if (min_pages < ATT_WAVES) min_pages = ATT_WAVES;
+    attn_plan_kernel<<<1, 256, 0, s>>>(B, T, kv, pl.budget, min_pages, pl.forced, pl.max_items, (AttnItem*)items, (int2*)entry_items);
+    SPEC_LAUNCH_CHECK("attn_plan_kernel");
+    return SPEC_OK;
+}
+
+spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const KvView& kv, int layer_pool, int layer,
+                                  int pages_bound, const void* items, const void* entry_items, float* part_o, float* part_ml,
                                   int mb_pad, int xf_out, bf16_t* xp_out, hipStream_t s)
 {
     int R = T * G;
     if (R > 256) { set_error("attention: (k+1) * (query heads per kv head) = %d rows exceeds 256", R); return SPEC_EUNSUPPORTED; }
     const int rows = attn_rows_padded(R);
     const AttnPlan pl = attn_plan(R, B, Hkv, pages_bound);
-    const int RG = pl.RG, cp = pl.chunk_pages;
-    const int max_chunks = (int)cdiv(pages_bound, cp);
+    const int RG = pl.RG;
     float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-    int BP = 1;                                   // batch entries folded into blockIdx.x so that it spans a multiple of 8
-    while ((Hkv * BP) % 8 != 0) BP *= 2;
-    dim3 grid((unsigned)(Hkv * BP), (unsigned)(RG * cdiv(B, BP)), (unsigned)max_chunks);
-    const float* qq = q;
+    int IP = 1;                                   // items folded into blockIdx.x so that it spans a multiple of 8
+    while ((Hkv * IP) % 8 != 0) IP *= 2;
+    dim3 grid((unsigned)(Hkv * IP), (unsigned)(RG * cdiv(pl.max_items, IP)));
+    const AttnItem* it = (const AttnItem*)items;
 #define SPEC_ATTN_LAUNCH(NRBV) do { \
-        if (kv.fp8) attn_partial_kernel<NRBV, true><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, layer, scale_log2, max_chunks, cp, RG, rows, Hkv, BP, B, part_o, part_ml); \
-        else attn_partial_kernel<NRBV, false><<<grid, 256, 0, s>>>(qq, T, G, Hq, seq_ids, kv, layer_pool, layer, scale_log2, max_chunks, cp, RG, rows, Hkv, BP, B, part_o, part_ml); \
+        if (kv.fp8) attn_partial_kernel<NRBV, true><<<grid, 256, 0, s>>>(q, T, G, Hq, it, pl.max_items, kv, layer_pool, layer, scale_log2, RG, rows, Hkv, IP, part_o, part_ml); \
+        else attn_partial_kernel<NRBV, false><<<grid, 256, 0, s>>>(q, T, G, Hq, it, pl.max_items, kv, layer_pool, layer, scale_log2, RG, rows, Hkv, IP, part_o, part_ml); \
     } while (0)
     switch (pl.RB) {
     case 1: SPEC_ATTN_LAUNCH(1); break;
@@ -505,7 +599,7 @@ spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, i
     SPEC_LAUNCH_CHECK("attn_partial_kernel");
     prof_mark(PC_ATTN, s);
     int64_t total = (int64_t)B * Hkv * R * (DH / 8);
-    attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, rows, max_chunks, cp, seq_ids, kv,
+    attn_reduce_kernel<<<(unsigned)cdiv(total, 256), 256, 0, s>>>(part_o, part_ml, B, T, G, Hkv, rows, (const int2*)entry_items, kv,
                                                                   layer, mb_pad, xf_out, (uint4*)xp_out);
     SPEC_LAUNCH_CHECK("attn_reduce_kernel");
     prof_mark(PC_ATTN_REDUCE, s);

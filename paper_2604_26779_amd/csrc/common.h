@@ -50,6 +50,9 @@ typedef uint16_t bf16_t;   // raw bfloat16 bits in host-side signatures
 // ---- device-resident KV bookkeeping, shared by all kernels that touch the cache ----
 struct KvView {
     void* pool;                // base of the pool
+    const int32_t* entry_seq;  // [B] the step's batch entries as sequence ids, -1 where the caller's id was out of range or a
+                               // duplicate (written by the page reservation that opens every forward pass)
+    int32_t* error;            // sticky error bits of the cache (reported by spec_kv_get_state)
     const int32_t* ctx_len;    // [max_seqs]
     const int32_t* n_held;     // [max_seqs] pages held
     const int32_t* page_table; // [max_seqs, max_pages]
@@ -113,6 +116,8 @@ struct spec_kv {
     int32_t* d_state = nullptr;
     int32_t *d_ctx_len = nullptr, *d_n_held = nullptr, *d_page_table = nullptr, *d_free_stack = nullptr,
             *d_free_count = nullptr, *d_error = nullptr;
+    // behind the bookkeeping (not part of a snapshot): scratch of the id check, and the checked ids of the current step
+    int32_t *d_owner = nullptr, *d_entry_seq = nullptr, *d_entry_tmp = nullptr;
     size_t state_ints = 0;
     // host mirror, valid when !device_ahead
     std::vector<int32_t> h_ctx_len, h_n_held, h_page_table, h_free_stack;

@@ -21,8 +21,10 @@ int gemm_mb_pad(int M);
 int gemm_pick_splits(const PackedW& W, int M, int forced);
 spec_status launch_gemm_bf16(const PackedW& W, const bf16_t* Xp, int M, float* out, int ldo, int splits, bool swiglu, hipStream_t s);
 bool gemm_can_fuse_swiglu(const PackedW& W, int M, int splits);
-int attn_min_chunk_pages(int R);
+int attn_max_items(int R, int B, int Hkv, int pages_bound);
+size_t attn_item_bytes();
 int attn_rows_padded(int R);
+spec_status launch_attention_plan(int B, int T, int G, int Hkv, const KvView& kv, int pages_bound, void* items, void* entry_items, hipStream_t s);
 int moe_rows_bound(int M, int top_k, int E);
 spec_status launch_gemm_bf16_grouped(const PackedW& W0, int64_t group_stride, const bf16_t* Xp, int rows_pad, int max_tiles,
                                      const int32_t* tiles, float* out, int ldo, bool swiglu, hipStream_t s);
@@ -32,8 +34,8 @@ spec_status launch_moe_gather(const bf16_t* xp_src, int mb_pad_src, const int32_
                               int rows_bound, int xf_dst, bf16_t* xp_dst, hipStream_t s);
 spec_status launch_moe_combine_norm(float* x, const float* y, const int32_t* pair_row, const float* wts, int M, int top_k,
                                     const void* gain, int d, float eps, int mb_pad, int xf, bf16_t* xp, hipStream_t s);
-spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const int32_t* seq_ids,
-                                  const KvView& kv, int layer_pool, int layer, int pages_bound, float* part_o, float* part_ml,
+spec_status launch_attention_bf16(const float* q, int B, int T, int G, int Hq, int Hkv, const KvView& kv, int layer_pool, int layer,
+                                  int pages_bound, const void* items, const void* entry_items, float* part_o, float* part_ml,
                                   int mb_pad, int xf_out, bf16_t* xp_out, hipStream_t s);
 
 // sum over the workgroup (blockDim.x a multiple of 64, at most 1024)
@@ -161,16 +163,28 @@ __global__ __launch_bounds__(512) void fuse_input_kernel(
     }
 }
 
-// cos/sin of pos * theta^(-2j/dh) per input row, in fp64 (the angle reaches thousands of radians)
-__global__ void rope_table_kernel(int M, int T, const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ ctx_len,
-                                  int half, double theta, float2* __restrict__ table)
+// Once per forward pass, per input row: cos/sin of pos * theta^(-2j/dh) in fp64 (the angle reaches thousands of radians),
+// and where the row's key and value go: row_slot[m] = page * SPEC_PAGE_SIZE + position in the page, or -1 (the batch entry
+// was dropped, or its sequence holds no page for that position).  The per-layer kernels then need no walk through the
+// bookkeeping (batch entry -> sequence -> length -> page list), three dependent loads each.
+__global__ void rope_table_kernel(int M, int T, KvView kv, int half, double theta, float2* __restrict__ table,
+                                  int32_t* __restrict__ row_slot)
 {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= M * half) return;
     int m = idx / half, j = idx % half;
-    int pos = ctx_len[seq_ids[m / T]] + m % T;
+    const int seq = kv.entry_seq[m / T];
+    const int pos = seq >= 0 ? kv.ctx_len[seq] + m % T : 0;
     double ang = (double)pos * pow(theta, -2.0 * (double)j / (double)(2 * half));
     table[idx] = make_float2((float)cos(ang), (float)sin(ang));
+    if (j == 0) {
+        int slot = -1;
+        if (seq >= 0) {
+            const int lp = pos / SPEC_PAGE_SIZE;
+            if (lp < kv.n_held[seq]) slot = kv.page_table[(int64_t)seq * kv.max_pages + lp] * SPEC_PAGE_SIZE + pos % SPEC_PAGE_SIZE;
+        }
+        row_slot[m] = slot;
+    }
 }
 
 // sums the split-K slices of the QKV projection, rotates q and k, writes q as bf16 rows and the
@@ -179,17 +193,15 @@ __global__ void rope_table_kernel(int M, int T, const int32_t* __restrict__ seq_
 template <bool KV8>
 __global__ __launch_bounds__(256) void qkv_rope_kernel(
     const float* __restrict__ part, int splits, int64_t split_stride, int T, int Hq, int Hkv,
-    const float2* __restrict__ rope, const int32_t* __restrict__ seq_ids, KvView kv, int layer_pool, int layer,
+    const float2* __restrict__ rope, const int32_t* __restrict__ row_slot, KvView kv, int layer_pool, int layer,
     float* __restrict__ q_out)
 {
     constexpr int DHc = 128, HALF = 64;
     const int m = blockIdx.x;
-    const int b = m / T, i = m % T;
-    const int seq = seq_ids[b];
-    const int pos = kv.ctx_len[seq] + i;
-    const int lp = pos / SPEC_PAGE_SIZE, t = pos % SPEC_PAGE_SIZE;
-    const bool writable = lp < kv.n_held[seq];
-    const int64_t page = writable ? kv.page_table[(int64_t)seq * kv.max_pages + lp] : 0;
+    const int slot = row_slot[m];
+    const bool writable = slot >= 0;
+    const int64_t page = writable ? slot / SPEC_PAGE_SIZE : 0;
+    const int t = writable ? slot % SPEC_PAGE_SIZE : 0;
     const int nqkv = (Hq + 2 * Hkv) * DHc;
     const float* row = part + (int64_t)m * nqkv;
     unsigned short* pool = (unsigned short*)kv.pool;
@@ -305,6 +317,8 @@ struct Bf16Plan {
     bool fuse_swiglu;
     int s_qkv, s_o, s_gu, s_down, s_head, s_fuse;
     size_t off_x, off_xp_h, off_xp_a, off_xp_f, off_part, off_q, off_rope, off_att_o, off_att_ml, total;
+    int max_items;                          // attention work items the buffers hold
+    size_t off_row_slot, off_items, off_entry_items;
     // mixture of experts: padded-row bound, router splits, routing tables, permuted activations, expert outputs
     int moe_rows, s_router;
     size_t off_ids, off_wts, off_row0, off_tiles, off_src_row, off_pair_row, off_xp_e, off_y_e;
@@ -319,8 +333,8 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.mb_pad = gemm_mb_pad(p.M);
     int G = d.n_q_heads / d.n_kv_heads;
     p.RBrows = attn_rows_padded(T * G);
-    p.max_chunks = (int)cdiv(cdiv(max_ctx_plus, SPEC_PAGE_SIZE), attn_min_chunk_pages(T * G));   // the most any launch may use
-    if (p.max_chunks < 1) p.max_chunks = 1;
+    p.max_chunks = 0;
+    p.max_items = attn_max_items(T * G, B, d.n_kv_heads, (int)cdiv(max_ctx_plus, SPEC_PAGE_SIZE));   // the most any launch may use
     p.s_qkv = gemm_pick_splits(m->wqkv[0], p.M, tune("splits_qkv"));
     p.s_o = gemm_pick_splits(m->wo[0], p.M, tune("splits_o"));
     const bool moe = m->moe();
@@ -356,7 +370,10 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     }
     p.off_q = take((size_t)p.M * nq * 4);
     p.off_rope = take((size_t)p.M * (d.head_dim / 2) * 8);
-    size_t items = (size_t)B * d.n_kv_heads * p.max_chunks;
+    p.off_row_slot = take((size_t)p.M * 4);
+    p.off_items = take((size_t)p.max_items * attn_item_bytes());
+    p.off_entry_items = take((size_t)B * 8);
+    size_t items = (size_t)p.max_items * d.n_kv_heads;
     p.off_att_o = take(items * p.RBrows * d.head_dim * 4);
     p.off_att_ml = take(items * p.RBrows * 2 * 4);
     p.total = off;
@@ -380,7 +397,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     if (p.total > ws_bytes) { set_error("spec_verify_forward: workspace too small for the current split settings (%zu < %zu)", ws_bytes, p.total); return SPEC_EINVAL; }
     // pages of the longest live context (the host's bound), capped by what the buffers were sized for
     int live_pages = (int)cdiv(kv->ub.max_ctx + T, SPEC_PAGE_SIZE);
-    if (live_pages > p.max_chunks * attn_min_chunk_pages(T * G)) live_pages = p.max_chunks * attn_min_chunk_pages(T * G);
+    if (live_pages > kv->max_pages) live_pages = kv->max_pages;
     if (live_pages < 1) live_pages = 1;
 
     char* base = (char*)ws;
@@ -393,6 +410,9 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     float2* rope = (float2*)(base + p.off_rope);
     float* att_o = (float*)(base + p.off_att_o);
     float* att_ml = (float*)(base + p.off_att_ml);
+    int32_t* row_slot = (int32_t*)(base + p.off_row_slot);
+    void* att_items = base + p.off_items;
+    void* att_entry_items = base + p.off_entry_items;
 
     const int M = p.M, D = d.d_model, F = d.ffn_dim, Hq = d.n_q_heads, Hkv = d.n_kv_heads;
     const int nqkv = (Hq + 2 * Hkv) * d.head_dim;
@@ -403,7 +423,8 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     auto xf_of = [](const PackedW& W) { return W.f16 ? XF_F16 : XF_HILO; };
     if (!mdl->moe() && mdl->wgu[0].f16 != mdl->wd[0].f16) { set_error("bf16 forward: gate/up and down projection must take the same activation format"); return SPEC_ESTATE; }
 
-    rope_table_kernel<<<(unsigned)cdiv((int64_t)M * 64, 256), 256, 0, s>>>(M, T, dev_seq_ids, kv->d_ctx_len, 64, (double)d.rope_theta, rope);
+    rope_table_kernel<<<(unsigned)cdiv((int64_t)M * 64, 256), 256, 0, s>>>(M, T, view, 64, (double)d.rope_theta, rope, row_slot);
+    if ((st = launch_attention_plan(B, T, G, Hkv, view, live_pages, att_items, att_entry_items, s)) != SPEC_OK) return st;
     if (d.fuse_hidden) {
         // hidden-state input: x = w_fuse . [RMSNorm(embed) ; RMSNorm(hidden_in)] (the feed-forward operand buffer is free here)
         fuse_input_kernel<<<M, norm_threads, 0, s>>>(dev_tokens, (const unsigned short*)mdl->embed(), d.vocab, dev_hidden_in,
@@ -422,11 +443,11 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_QKV, s);
         if (view.fp8)
-            qkv_rope_kernel<true><<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, l, qbuf);
+            qkv_rope_kernel<true><<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, row_slot, view, lp, l, qbuf);
         else
-            qkv_rope_kernel<false><<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, dev_seq_ids, view, lp, l, qbuf);
+            qkv_rope_kernel<false><<<dim3(M, 4), 256, 0, s>>>(part, p.s_qkv, (int64_t)M * nqkv, T, Hq, Hkv, rope, row_slot, view, lp, l, qbuf);
         prof_mark(PC_QKV_ROPE, s);
-        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, dev_seq_ids, view, lp, l, live_pages, att_o, att_ml, p.mb_pad, xf_of(mdl->wo[l]), xp_a, s)) != SPEC_OK) return st;
+        if ((st = launch_attention_bf16(qbuf, B, T, G, Hq, Hkv, view, lp, l, live_pages, att_items, att_entry_items, att_o, att_ml, p.mb_pad, xf_of(mdl->wo[l]), xp_a, s)) != SPEC_OK) return st;
         if ((st = launch_gemm_bf16(mdl->wo[l], xp_a, M, part, D, p.s_o, false, s)) != SPEC_OK) return st;
         prof_mark(PC_GEMM_O, s);
         // (mixture of experts: the router reads this buffer and stays hi + lo; the gather below converts for the experts)

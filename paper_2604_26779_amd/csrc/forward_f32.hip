@@ -74,12 +74,12 @@ __global__ void f32_rope_kv_write_kernel(float* __restrict__ qkv, int T, const i
 {
     int m = blockIdx.x;
     int b = m / T, i = m % T;
-    int seq = seq_ids[b];
-    int pos = kv.ctx_len[seq] + i;
+    int seq = kv.entry_seq[b];                     // -1: the entry was dropped (id out of range or named twice)
+    int pos = seq >= 0 ? kv.ctx_len[seq] + i : 0;
     int half = dh >> 1;
     float* row = qkv + (int64_t)m * (Hq + 2 * Hkv) * dh;
     int lp = pos / SPEC_PAGE_SIZE, t = pos % SPEC_PAGE_SIZE;
-    bool writable = lp < kv.n_held[seq];
+    bool writable = seq >= 0 && lp < kv.n_held[seq];
     int64_t page = writable ? kv.page_table[(int64_t)seq * kv.max_pages + lp] : 0;
     float* pool = (float*)kv.pool;
     int64_t block = (int64_t)SPEC_PAGE_SIZE * dh;
@@ -115,9 +115,9 @@ __global__ __launch_bounds__(64) void f32_attention_kernel(const float* __restri
 {
     int m = blockIdx.x, j = blockIdx.y;
     int b = m / T, i = m % T;
-    int seq = seq_ids[b];
-    int visible = kv.ctx_len[seq] + i + 1;
-    int cap = kv.n_held[seq] * SPEC_PAGE_SIZE;
+    int seq = kv.entry_seq[b];
+    int visible = seq >= 0 ? kv.ctx_len[seq] + i + 1 : 0;
+    int cap = seq >= 0 ? kv.n_held[seq] * SPEC_PAGE_SIZE : 0;
     if (visible > cap) visible = cap;
     int g = j / (Hq / Hkv);
     const float* q = qkv + (int64_t)m * (Hq + 2 * Hkv) * dh + (int64_t)j * dh;

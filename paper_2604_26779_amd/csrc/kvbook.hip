@@ -28,22 +28,46 @@ __device__ inline int block_exclusive_scan(int v, int* lds, int* total)
 // error bits
 constexpr int KV_ERR_NOMEM = 1, KV_ERR_SEQ = 2, KV_ERR_LEN = 4;
 
+// Batch entries as the kernels may use them: clean[b] = seq_ids[b] if that id is inside [0, max_seqs) and no earlier
+// batch entry names it, else -1 (flagged with KV_ERR_SEQ): an entry that would index the bookkeeping out of bounds,
+// or write the same cache slots as another, is dropped from the step instead.  owner[max_seqs] is scratch that holds
+// INT_MAX between calls.  One workgroup; ends with a barrier.
+__device__ inline void sanitise_ids(int B, const int32_t* __restrict__ seq_ids, int max_seqs, int32_t* __restrict__ owner,
+                                    int32_t* __restrict__ clean, int32_t* __restrict__ error)
+{
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int seq = seq_ids[b];
+        if (seq >= 0 && seq < max_seqs) atomicMin(&owner[seq], b);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int seq = seq_ids[b];
+        const bool ok = seq >= 0 && seq < max_seqs && __hip_atomic_load(&owner[seq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == b;
+        clean[b] = ok ? seq : -1;
+        if (!ok) atomicOr(error, KV_ERR_SEQ);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int seq = seq_ids[b];
+        if (seq >= 0 && seq < max_seqs) __hip_atomic_store(&owner[seq], 0x7fffffff, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+}
+
 __global__ __launch_bounds__(KVB_THREADS) void kv_reserve_kernel(
     int B, int k, const int32_t* __restrict__ seq_ids, int max_seqs, int max_pages,
     const int32_t* __restrict__ ctx_len, int32_t* __restrict__ n_held, int32_t* __restrict__ page_table,
-    const int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count, int32_t* __restrict__ error)
+    const int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count, int32_t* __restrict__ error,
+    int32_t* __restrict__ owner, int32_t* __restrict__ entry_seq)
 {
     __shared__ int lds[KVB_THREADS];
     __shared__ int s_free;
     if (threadIdx.x == 0) s_free = *free_count;
-    __syncthreads();
+    sanitise_ids(B, seq_ids, max_seqs, owner, entry_seq, error);     // entry_seq: what the forward pass's kernels index by
     for (int base = 0; base < B; base += KVB_THREADS) {
         int b = base + threadIdx.x;
         int seq = -1, held = 0, want = 0;
-        if (b < B) {
-            seq = seq_ids[b];
-            if (seq < 0 || seq >= max_seqs) { atomicOr(error, KV_ERR_SEQ); seq = -1; }
-        }
+        if (b < B) seq = entry_seq[b];
         if (seq >= 0) {
             held = n_held[seq];
             int need = (ctx_len[seq] + k + 1 + SPEC_PAGE_SIZE - 1) / SPEC_PAGE_SIZE;
@@ -72,19 +96,17 @@ __global__ __launch_bounds__(KVB_THREADS) void kv_commit_kernel(
     int B, int k, const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ accept_len, int max_seqs,
     int max_pages, int32_t* __restrict__ ctx_len, int32_t* __restrict__ n_held,
     int32_t* __restrict__ page_table, int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count,
-    int32_t* __restrict__ error, int32_t* __restrict__ new_ctx_len, int32_t* __restrict__ commit_slots)
+    int32_t* __restrict__ error, int32_t* __restrict__ new_ctx_len, int32_t* __restrict__ commit_slots,
+    int32_t* __restrict__ owner, int32_t* __restrict__ clean)
 {
     __shared__ int lds[KVB_THREADS];
     __shared__ int s_free;
     if (threadIdx.x == 0) s_free = *free_count;
-    __syncthreads();
+    sanitise_ids(B, seq_ids, max_seqs, owner, clean, error);
     for (int base = 0; base < B; base += KVB_THREADS) {
         int b = base + threadIdx.x;
         int seq = -1, held = 0, keep = 0, release = 0;
-        if (b < B) {
-            seq = seq_ids[b];
-            if (seq < 0 || seq >= max_seqs) { atomicOr(error, KV_ERR_SEQ); seq = -1; }
-        }
+        if (b < B) seq = clean[b];
         if (seq >= 0) {
             held = n_held[seq];
             int ctx = ctx_len[seq];
@@ -132,19 +154,16 @@ __global__ __launch_bounds__(KVB_THREADS) void kv_truncate_kernel(
     int B, const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ len, int delta, int max_seqs, int max_pages,
     int32_t* __restrict__ ctx_len, int32_t* __restrict__ n_held, int32_t* __restrict__ page_table,
     int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count, int32_t* __restrict__ error,
-    int32_t* __restrict__ new_len)
+    int32_t* __restrict__ new_len, int32_t* __restrict__ owner, int32_t* __restrict__ clean)
 {
     __shared__ int lds[KVB_THREADS];
     __shared__ int s_free;
     if (threadIdx.x == 0) s_free = *free_count;
-    __syncthreads();
+    sanitise_ids(B, seq_ids, max_seqs, owner, clean, error);
     for (int base = 0; base < B; base += KVB_THREADS) {
         int b = base + threadIdx.x;
         int seq = -1, held = 0, keep = 0, release = 0;
-        if (b < B) {
-            seq = seq_ids[b];
-            if (seq < 0 || seq >= max_seqs) { atomicOr(error, KV_ERR_SEQ); seq = -1; }
-        }
+        if (b < B) seq = clean[b];
         if (seq >= 0) {
             held = n_held[seq];
             int ctx = ctx_len[seq];
@@ -323,7 +342,7 @@ spec_status launch_kv_truncate(spec_kv* kv, int B, const int32_t* dev_seq_ids, c
 {
     kv_truncate_kernel<<<1, KVB_THREADS, 0, s>>>(B, dev_seq_ids, dev_len, delta, kv->max_seqs, kv->max_pages, kv->d_ctx_len,
                                                  kv->d_n_held, kv->d_page_table, kv->d_free_stack, kv->d_free_count,
-                                                 kv->d_error, dev_new_len);
+                                                 kv->d_error, dev_new_len, kv->d_owner, kv->d_entry_tmp);
     SPEC_LAUNCH_CHECK("kv_truncate_kernel");
     return SPEC_OK;
 }
@@ -332,7 +351,7 @@ spec_status launch_kv_reserve(spec_kv* kv, int B, int k, const int32_t* dev_seq_
 {
     kv_reserve_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, dev_seq_ids, kv->max_seqs, kv->max_pages, kv->d_ctx_len,
                                                 kv->d_n_held, kv->d_page_table, kv->d_free_stack,
-                                                kv->d_free_count, kv->d_error);
+                                                kv->d_free_count, kv->d_error, kv->d_owner, kv->d_entry_seq);
     SPEC_LAUNCH_CHECK("kv_reserve_kernel");
     return SPEC_OK;
 }
@@ -342,7 +361,8 @@ spec_status launch_kv_commit(spec_kv* kv, int B, int k, const int32_t* dev_seq_i
 {
     kv_commit_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, dev_seq_ids, dev_accept_len, kv->max_seqs, kv->max_pages,
                                                kv->d_ctx_len, kv->d_n_held, kv->d_page_table, kv->d_free_stack,
-                                               kv->d_free_count, kv->d_error, dev_new_ctx_len, dev_commit_slots);
+                                               kv->d_free_count, kv->d_error, dev_new_ctx_len, dev_commit_slots, kv->d_owner,
+                                               kv->d_entry_tmp);
     SPEC_LAUNCH_CHECK("kv_commit_kernel");
     return SPEC_OK;
 }

@@ -1,11 +1,14 @@
 // Fused vocabulary-wide softmax + lossless rejection sampling (the rejection procedure the
 // paper's Section 2.1 relies on; acceptance length as defined in its Section 2.2).
 //
-// Two launches per step:
-//   1. row_stats_kernel: one workgroup per logits row -> (max, sum of exp) of logits / T.
-//   2. reject_sample_kernel: one workgroup per sequence -> accept tests in order, then one
-//      exponential-race draw over the single row that decides the emitted token
-//      (residual row at the first rejection, bonus row after k acceptances).
+// Three launches per step, the vocabulary cut into SAMP_PARTS ranges so that a batch of a few dozen
+// sequences still occupies the whole chip (one workgroup per row or sequence left 7/8 of the CUs idle):
+//   1. row_stats_kernel: workgroup = (logits row, range) -> (max, sum of exp) of logits / T over the range;
+//   2. reject_scan_kernel: workgroup = (sequence, range): the accept tests in order (every range's workgroup
+//      repeats these few scalar steps and arrives at the same n), then the exponential race over its range of
+//      the single row that decides the emitted token (residual row at the first rejection, bonus row after k
+//      acceptances) -> the range's best key;
+//   3. reject_merge_kernel: the best key over the ranges, ties to the lowest token -> outputs.
 // Only the rows' statistics, the k probed q entries and one q row are read: (k+1+2) V floats
 // per sequence at most.
 #include <mutex>
@@ -42,12 +45,25 @@ __device__ inline void online_merge(float& m, float& s, float m2, float s2)
     m = mm;
 }
 
+constexpr int SAMP_PARTS = 8;                 // ranges the vocabulary is cut into (whole groups of 4 entries: one Philox call each)
+
+// groups of 4 vocabulary entries of range `part`: [g0, g1)
+__device__ inline void part_groups(int V, int part, int* g0, int* g1)
+{
+    const int groups = (V + 3) >> 2, per = (groups + SAMP_PARTS - 1) / SAMP_PARTS;
+    *g0 = part * per < groups ? part * per : groups;
+    *g1 = (part + 1) * per < groups ? (part + 1) * per : groups;
+}
+
 __global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __restrict__ logits, int V, float inv_t,
                                                                   float2* __restrict__ stats)
 {
     const float* row = logits + (int64_t)blockIdx.x * V;
+    int g0, g1;
+    part_groups(V, blockIdx.y, &g0, &g1);
+    const int v1 = g1 * 4 < V ? g1 * 4 : V;
     float m = -INFINITY, s = 0.f;
-    for (int v = threadIdx.x; v < V; v += SAMP_THREADS) {
+    for (int v = g0 * 4 + threadIdx.x; v < v1; v += SAMP_THREADS) {
         float z = row[v] * inv_t;
         if (z > m) { s = s * expf(m - z) + 1.f; m = z; }
         else if (z > -INFINITY) s += expf(z - m);
@@ -64,18 +80,30 @@ __global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __
     if (threadIdx.x == 0) {
         float M = lm[0], S = ls[0];
         for (int w = 1; w < SAMP_THREADS / 64; ++w) online_merge(M, S, lm[w], ls[w]);
-        stats[blockIdx.x] = make_float2(M, S);
+        stats[(int64_t)blockIdx.x * SAMP_PARTS + blockIdx.y] = make_float2(M, S);
     }
 }
 
-// mode 0: w = max(0, e/S - q); mode 1: w = e; mode 2: w = e except 0 at the drafted token  (e = exp(z - m))
-template <int MODE>
-__device__ inline void race_scan(const float* __restrict__ lrow, const float* __restrict__ qrow, int V, float inv_t,
-                                 float m, float inv_s, uint32_t k0, uint32_t k1, uint32_t c1, uint32_t c2, uint32_t c3,
-                                 float& best, int& best_v, int hot = -1)
+// a row's statistics from those of its ranges, merged in range order
+__device__ inline float2 row_stat(const float2* __restrict__ stats, int64_t row)
 {
-    int groups = (V + 3) >> 2;
-    for (int g = threadIdx.x; g < groups; g += SAMP_THREADS) {
+    float2 a = stats[row * SAMP_PARTS];
+    for (int p = 1; p < SAMP_PARTS; ++p) {
+        const float2 c = stats[row * SAMP_PARTS + p];
+        online_merge(a.x, a.y, c.x, c.y);
+    }
+    return a;
+}
+
+// Exponential race over the groups [g0, g1) of one row.  Two races share the scan: the residual one (RES: weights
+// max(0, e/S - q); HOT: e except 0 at the drafted token `hot`, the residual of a one-hot draft distribution) and the
+// plain one over e = exp(z - m), which decides the bonus row and stands in where a residual is identically zero.
+template <bool RES, bool HOT>
+__device__ inline void race_scan(const float* __restrict__ lrow, const float* __restrict__ qrow, int V, int g0, int g1, float inv_t,
+                                 float m, float inv_s, uint32_t k0, uint32_t k1, uint32_t c1, uint32_t c2, uint32_t c3,
+                                 float& best, int& best_v, float& best_res, int& best_res_v, int hot = -1)
+{
+    for (int g = g0 + threadIdx.x; g < g1; g += SAMP_THREADS) {
         Philox4 r = philox4x32_10((uint32_t)g, c1, c2, c3, k0, k1);
         uint32_t words[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
@@ -83,12 +111,18 @@ __device__ inline void race_scan(const float* __restrict__ lrow, const float* __
             int v = g * 4 + j;
             if (v >= V) break;
             float e = expf(lrow[v] * inv_t - m);
-            // MODE 2: one-hot draft distribution on token `hot`: the residual is p with that entry removed
-            float w = (MODE == 0) ? fmaxf(0.f, e * inv_s - qrow[v]) : ((MODE == 2 && v == hot) ? 0.f : e);
-            if (!(w > 0.f)) continue;
+            if (!(e > 0.f)) continue;
             float u = ((float)(words[j] >> 9) + 0.5f) * (1.0f / 8388608.0f);
-            float key = w / (-logf(u));
+            float nl = -logf(u);
+            float key = e / nl;
             if (key > best) { best = key; best_v = v; }     // v ascends inside a thread: ties keep the lowest
+            if (RES || HOT) {
+                float w = RES ? fmaxf(0.f, e * inv_s - qrow[v]) : (v == hot ? 0.f : e);
+                if (w > 0.f) {
+                    float kr = w / nl;
+                    if (kr > best_res) { best_res = kr; best_res_v = v; }
+                }
+            }
         }
     }
 }
@@ -113,61 +147,84 @@ __device__ inline void block_argmax(float& key, int& v, float* lk, int* lv)
     for (int w = 1; w < SAMP_THREADS / 64; ++w) argmax_merge(key, v, lk[w], lv[w]);
 }
 
-__global__ __launch_bounds__(SAMP_THREADS) void reject_sample_kernel(
+// what a range's workgroup hands to the merge: n, and its best (key, token) of the residual race and of the plain race
+struct RacePart { int32_t n; float key_res; int32_t v_res; float key; int32_t v; int32_t pad[3]; };
+
+__global__ __launch_bounds__(SAMP_THREADS) void reject_scan_kernel(
     int k, int V, const float* __restrict__ logits, const float* __restrict__ q, const int32_t* __restrict__ draft,
     float inv_t, uint32_t seed_lo, uint32_t seed_hi, uint32_t step4, const float2* __restrict__ stats,
-    int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens, float* __restrict__ dbg)
+    RacePart* __restrict__ parts, float* __restrict__ dbg)
 {
-    const int b = blockIdx.x;
+    const int b = blockIdx.x, part = blockIdx.y;
     const float* L = logits + (int64_t)b * (k + 1) * V;
     const float* Qb = q ? q + (int64_t)b * k * V : nullptr;
     __shared__ int s_n;
+    __shared__ float2 s_st;
     __shared__ float lk[SAMP_THREADS / 64];
     __shared__ int lv[SAMP_THREADS / 64];
 
     if (threadIdx.x == 0) {
         int n = 0;
+        const bool log_it = dbg && part == 0;
         for (int i = 0; i < k; ++i) {
-            if (dbg) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = d[1] = d[2] = NAN; }
+            if (log_it) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = d[1] = d[2] = NAN; }
         }
         for (int i = 0; i < k; ++i) {
             int x = draft[(int64_t)b * k + i];
             if (x < 0 || x >= V) break;
-            float2 st = stats[(int64_t)b * (k + 1) + i];
+            float2 st = row_stat(stats, (int64_t)b * (k + 1) + i);
             float P = expf(L[(int64_t)i * V + x] * inv_t - st.x) / st.y;
             float Q = Qb ? Qb[(int64_t)i * V + x] : 1.0f;          // no q array: one-hot drafts (a deterministic drafter)
             Philox4 r = philox4x32_10(0u, (uint32_t)i, (uint32_t)b, step4 + 0u, seed_lo, seed_hi);
             float u = (float)(r.x >> 8) * (1.0f / 16777216.0f);
-            if (dbg) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = P; d[1] = Q; d[2] = u; }
+            if (log_it) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = P; d[1] = Q; d[2] = u; }
             if ((double)u * (double)Q < (double)P) n += 1; else break;
         }
         s_n = n;
+        s_st = row_stat(stats, (int64_t)b * (k + 1) + n);
     }
     __syncthreads();
     const int n = s_n;
-
+    const float2 st = s_st;
     const float* lrow = L + (int64_t)n * V;
-    float2 st = stats[(int64_t)b * (k + 1) + n];
-    float best = -1.f;
-    int best_v = -1;
+    int g0, g1;
+    part_groups(V, part, &g0, &g1);
+    float best = -1.f, best_res = -1.f;
+    int best_v = -1, best_res_v = -1;
     const uint32_t c1 = (uint32_t)n, c2 = (uint32_t)b, c3 = step4 + 1u;
-    if (n < k) {
-        if (Qb) race_scan<0>(lrow, Qb + (int64_t)n * V, V, inv_t, st.x, 1.0f / st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v);
-        else race_scan<2>(lrow, nullptr, V, inv_t, st.x, 1.0f, seed_lo, seed_hi, c1, c2, c3, best, best_v, draft[(int64_t)b * k + n]);
-        block_argmax(best, best_v, lk, lv);
-    }
-    if (best_v < 0) {                                // bonus row, or a residual that is identically zero
-        best = -1.f;
-        race_scan<1>(lrow, nullptr, V, inv_t, st.x, 1.0f, seed_lo, seed_hi, c1, c2, c3, best, best_v);
-        block_argmax(best, best_v, lk, lv);
-    }
+    if (n < k && Qb) race_scan<true, false>(lrow, Qb + (int64_t)n * V, V, g0, g1, inv_t, st.x, 1.0f / st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v);
+    else if (n < k) race_scan<false, true>(lrow, nullptr, V, g0, g1, inv_t, st.x, 1.0f, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v, draft[(int64_t)b * k + n]);
+    else race_scan<false, false>(lrow, nullptr, V, g0, g1, inv_t, st.x, 1.0f, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v);
+    block_argmax(best, best_v, lk, lv);
+    block_argmax(best_res, best_res_v, lk, lv);
     if (threadIdx.x == 0) {
-        accept_len[b] = n;
-        int32_t* o = out_tokens + (int64_t)b * (k + 1);
-        for (int i = 0; i < n; ++i) o[i] = draft[(int64_t)b * k + i];
-        o[n] = best_v;
-        for (int i = n + 1; i <= k; ++i) o[i] = -1;
+        RacePart r;
+        r.n = n; r.key_res = best_res; r.v_res = best_res_v; r.key = best; r.v = best_v; r.pad[0] = r.pad[1] = r.pad[2] = 0;
+        parts[(int64_t)b * SAMP_PARTS + part] = r;
     }
+}
+
+// one thread per sequence: the winner over the ranges (which ascend in token id, so an equal key never replaces an
+// earlier one), the residual race's if it has one (n < k and a residual that is not identically zero), else the plain one's
+__global__ void reject_merge_kernel(int B, int k, const RacePart* __restrict__ parts, const int32_t* __restrict__ draft,
+                                    int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const RacePart* p = parts + (int64_t)b * SAMP_PARTS;
+    const int n = p[0].n;
+    float key = -1.f, key_res = -1.f;
+    int v = -1, v_res = -1;
+    for (int i = 0; i < SAMP_PARTS; ++i) {
+        argmax_merge(key, v, p[i].key, p[i].v);
+        argmax_merge(key_res, v_res, p[i].key_res, p[i].v_res);
+    }
+    const int y = (n < k && v_res >= 0) ? v_res : v;
+    accept_len[b] = n;
+    int32_t* o = out_tokens + (int64_t)b * (k + 1);
+    for (int i = 0; i < n; ++i) o[i] = draft[(int64_t)b * k + i];
+    o[n] = y;
+    for (int i = n + 1; i <= k; ++i) o[i] = -1;
 }
 
 // The draft model's own draw (one workgroup per sequence): q = softmax(logits / T) written out for
@@ -228,48 +285,56 @@ __global__ __launch_bounds__(SAMP_THREADS) void draft_sample_kernel(
 
 }  // namespace specv
 
+// workspace: the ranges' row statistics [B * (k + 1)][SAMP_PARTS] float2, then the ranges' race results [B][SAMP_PARTS]
+static size_t sample_stats_bytes(int64_t rows) { return specv::align_up((size_t)rows * specv::SAMP_PARTS * sizeof(float2), 256); }
+static size_t sample_parts_bytes(int64_t B) { return specv::align_up((size_t)B * specv::SAMP_PARTS * sizeof(specv::RacePart), 256); }
+
 extern "C" size_t spec_sample_workspace_bytes(int32_t B, int32_t k)
 {
     if (B < 1 || k < 0) return 0;
-    return specv::align_up((size_t)B * (size_t)(k + 1) * sizeof(float2), 256);
+    return sample_stats_bytes((int64_t)B * (k + 1)) + sample_parts_bytes(B);
 }
 
 namespace specv {
 
-// argument checks and the two launches shared by both entry points; stats: B * (k + 1) float2 of device memory
+// argument checks and the launches shared by both entry points; ws: spec_sample_workspace_bytes(B, k) bytes of device memory
 static spec_status reject_sample_launch(const char* who, int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
                                         const int32_t* dev_draft_tokens, float temperature, uint64_t seed, uint64_t step,
-                                        int32_t* dev_accept_len, int32_t* dev_out_tokens, float* dev_dbg, float2* stats, hipStream_t s)
+                                        int32_t* dev_accept_len, int32_t* dev_out_tokens, float* dev_dbg, void* ws, hipStream_t s)
 {
+    float2* stats = (float2*)ws;
     if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT || V < 1) { set_error("%s: B, k or V out of range", who); return SPEC_EINVAL; }
     if (!(temperature > 0.f)) { set_error("%s: temperature must be > 0", who); return SPEC_EINVAL; }
     if (step >= (1ull << 30)) { set_error("%s: step must be < 2^30", who); return SPEC_EINVAL; }
-    if (!dev_logits || !dev_accept_len || !dev_out_tokens || !stats || (k > 0 && !dev_draft_tokens)) {
+    if (!dev_logits || !dev_accept_len || !dev_out_tokens || !ws || (k > 0 && !dev_draft_tokens)) {
         set_error("%s: null pointer", who); return SPEC_EINVAL;
     }
     float inv_t = 1.0f / temperature;
+    RacePart* parts = (RacePart*)((char*)ws + sample_stats_bytes((int64_t)B * (k + 1)));
     prof_mark(PC_OTHER, s);
-    row_stats_kernel<<<B * (k + 1), SAMP_THREADS, 0, s>>>(dev_logits, V, inv_t, stats);
+    row_stats_kernel<<<dim3((unsigned)(B * (k + 1)), SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, V, inv_t, stats);
     SPEC_LAUNCH_CHECK("row_stats_kernel");
     prof_mark(PC_SAMPLE_STATS, s);
-    reject_sample_kernel<<<B, SAMP_THREADS, 0, s>>>(k, V, dev_logits, dev_q, dev_draft_tokens, inv_t, (uint32_t)seed,
-                                                    (uint32_t)(seed >> 32), (uint32_t)(step * 4u), stats,
-                                                    dev_accept_len, dev_out_tokens, dev_dbg);
-    SPEC_LAUNCH_CHECK("reject_sample_kernel");
+    reject_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(k, V, dev_logits, dev_q, dev_draft_tokens, inv_t, (uint32_t)seed,
+                                                                             (uint32_t)(seed >> 32), (uint32_t)(step * 4u), stats, parts, dev_dbg);
+    SPEC_LAUNCH_CHECK("reject_scan_kernel");
+    reject_merge_kernel<<<(unsigned)cdiv(B, 256), 256, 0, s>>>(B, k, parts, dev_draft_tokens, dev_accept_len, dev_out_tokens);
+    SPEC_LAUNCH_CHECK("reject_merge_kernel");
     prof_mark(PC_SAMPLE_DRAW, s);
     return SPEC_OK;
 }
 
-// Row statistics of spec_reject_sample_static: device memory that exists from the moment the library is loaded, so
+// Workspace of spec_reject_sample_static: device memory that exists from the moment the library is loaded, so
 // that entry point never allocates.  Every GPU holds its own copy at its own address; the array's name is only a
 // host-side handle, the address kernels are given comes from hipGetSymbolAddress with that GPU current.
-constexpr int SAMP_STATIC_ROWS = 16384;                 // B * (k + 1) at most: 128 KiB per GPU
-static __device__ __align__(256) float2 scratch[SAMP_STATIC_ROWS];
+constexpr int SAMP_STATIC_ROWS = 4096;                  // B * (k + 1) at most: 256 KiB of row statistics + at most 128 KiB of race results per GPU
+constexpr size_t SAMP_STATIC_BYTES = (size_t)SAMP_STATIC_ROWS * SAMP_PARTS * (sizeof(float2) + sizeof(RacePart)) + 512;
+static __device__ __align__(256) unsigned char scratch[SAMP_STATIC_BYTES];
 constexpr int SAMP_MAX_DEVICES = 64;
-static float2* g_scratch_ptr[SAMP_MAX_DEVICES];
+static void* g_scratch_ptr[SAMP_MAX_DEVICES];
 static std::mutex g_scratch_mutex;
 
-static spec_status static_scratch(float2** out)
+static spec_status static_scratch(void** out)
 {
     int dev = -1;
     SPEC_HIP_TRY(hipGetDevice(&dev));
@@ -279,7 +344,7 @@ static spec_status static_scratch(float2** out)
         void* p = nullptr;
         hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
         if (e != hipSuccess || !p) { set_error("spec_reject_sample_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e)); return SPEC_EHIP; }
-        g_scratch_ptr[dev] = (float2*)p;
+        g_scratch_ptr[dev] = p;
     }
     *out = g_scratch_ptr[dev];
     return SPEC_OK;
@@ -295,7 +360,7 @@ extern "C" spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const
     using namespace specv;
     if (B >= 1 && k >= 0 && dev_workspace && workspace_bytes < spec_sample_workspace_bytes(B, k)) { set_error("spec_reject_sample: workspace too small"); return SPEC_EINVAL; }
     return reject_sample_launch("spec_reject_sample", B, k, V, dev_logits, dev_q, dev_draft_tokens, temperature, seed, step, dev_accept_len,
-                                dev_out_tokens, dev_dbg, (float2*)dev_workspace, (hipStream_t)stream);
+                                dev_out_tokens, dev_dbg, dev_workspace, (hipStream_t)stream);
 }
 
 extern "C" spec_status spec_reject_sample_static(int32_t B, int32_t k, int32_t V, const float* dev_logits, const float* dev_q,
@@ -309,7 +374,7 @@ extern "C" spec_status spec_reject_sample_static(int32_t B, int32_t k, int32_t V
                   (long long)B * (k + 1), SAMP_STATIC_ROWS);
         return SPEC_EINVAL;
     }
-    float2* stats = nullptr;
+    void* stats = nullptr;
     spec_status st = static_scratch(&stats);
     if (st != SPEC_OK) return st;
     return reject_sample_launch("spec_reject_sample_static", B, k, V, dev_logits, dev_q, dev_draft_tokens, temperature, seed, step,

@@ -53,11 +53,11 @@ def test_static_scratch_entry_point_equals_the_workspace_one():
 
 def test_static_scratch_entry_point_refuses_what_does_not_fit():
     from paper_2604_26779_amd import binding as sv
-    B, k, V = 2048, 7, 8                                  # 16384 rows: the limit, accepted
+    B, k, V = 512, 7, 8                                   # 4096 rows: the limit, accepted
     logits, q, draft = si.make_sampler_case(B, k, V, seed=5, noise_std=1.0, temperature=1.0)
     (n_ws, out_ws, _), (n_st, out_st, _) = _both(sv, logits, q, draft, 1.0, 1, 0)
     assert np.array_equal(n_st, n_ws) and np.array_equal(out_st, out_ws)
     one = torch.zeros(16, dtype=torch.int32, device="cuda")
-    status = sv.lib().spec_reject_sample_static(2049, 7, 8, one.data_ptr(), one.data_ptr(), one.data_ptr(), 1.0, 0, 0,
+    status = sv.lib().spec_reject_sample_static(513, 7, 8, one.data_ptr(), one.data_ptr(), one.data_ptr(), 1.0, 0, 0,
                                                 one.data_ptr(), one.data_ptr(), None, None)
-    assert status == sv.SPEC_EINVAL and "16384" in sv.spec_last_error()
+    assert status == sv.SPEC_EINVAL and "4096" in sv.spec_last_error()
