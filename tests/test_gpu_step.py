@@ -511,3 +511,88 @@ def test_bf16_activation_formats_per_projection(mask, B, k, w8):
         sv.spec_tune_set("gemm_f16_inputs", before)
     print("fp16-input projections %d, B=%d k=%d (M=%d), 8-bit matrices %s: logits max abs err %.3e" % (mask, B, k, B * (k + 1), w8, max_err))
     assert ok, (max_err, worst)
+
+
+@pytest.mark.parametrize("workload", ["small_bf16_b5_k3", "tiny_fp32_b4_ctx128_k3"])
+def test_bad_and_repeated_sequence_ids_are_dropped_and_the_rest_is_untouched(workload):
+    """Batch entries whose sequence id (device memory, invisible to the host's checks) is out of range or names a
+    sequence an earlier entry already names are left out of the step: the valid entries' logits still match the
+    oracle, their pages and lengths move exactly as the oracle's book says, nothing else changes, and the cache reports
+    the fault at the next state query."""
+    from paper_2604_26779_amd import binding as sv
+    wl, cfg, w_or, kv_or, batch, sess, seq_ids = _setup(workload, prefill="synthetic")
+    k, ctx_len = wl["k"], batch["ctx_len"]
+    rng = np.random.default_rng(3)
+    ids = np.array([seq_ids[0], sess.max_seqs + 50, seq_ids[2], seq_ids[0], -4], dtype=np.int32)      # entries 1, 3, 4 are bad
+    good = [0, 2]
+    tokens = rng.integers(0, cfg["vocab"], size=(len(ids), k + 1)).astype(np.int32)
+    before = sess.state()
+    logits = sess.forward(torch.from_numpy(ids).cuda(), torch.from_numpy(tokens).cuda())
+    torch.cuda.synchronize()
+    assert torch.isfinite(logits[good]).all()
+    want, _ = of.verify_forward(cfg, w_or, [[per[b] for b in good] for per in kv_or], tokens[good], ctx_len[good])
+    ok, max_err, worst = logits_close(logits[good].cpu().numpy(), want, *TOL[cfg["dtype"]])
+    assert ok, (max_err, worst)
+    n = np.array([1, 2, 0, 3, 1], dtype=np.int32)
+    new_len, slots = sess.commit(torch.from_numpy(ids).cuda(), torch.from_numpy(n).cuda(), k)
+    book = _book(batch, sess, seq_ids, ctx_len)
+    book.reserve([int(ids[b]) for b in good], k)
+    want_len, want_slots = book.commit([int(ids[b]) for b in good], n[good], k)
+    got_len, got_slots = new_len.cpu().numpy(), slots.cpu().numpy()
+    for j, b in enumerate(good):
+        assert got_len[b] == want_len[j] and list(got_slots[b]) == want_slots[j]
+    for b in (1, 3, 4):
+        assert got_len[b] == -1 and np.all(got_slots[b] == -1)
+    with pytest.raises(sv.SpecError) as e:
+        sess.state()
+    assert e.value.status == sv.SPEC_EINVAL
+    _check_state(sess, book, seq_ids)                      # the flag is cleared by the query; every sequence is where the book says
+    after = sess.state()
+    for s in [s for s in seq_ids if s not in (seq_ids[0], seq_ids[2])]:      # sequences no valid entry named: untouched
+        assert after["ctx_len"][s] == before["ctx_len"][s] and after["n_pages"][s] == before["n_pages"][s]
+    sess.close()
+
+
+def test_replay_from_a_longer_cache_state_than_recorded_is_reported():
+    """A recorded forward pass is sized for the longest context the host knew at recording time.  Replayed over
+    longer contexts it cannot cover them: the cache must say so at the next state query instead of returning logits
+    of truncated contexts unmarked."""
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = si.MODELS["small_bf16"]
+    weights = {n: t.cuda() for n, t in si.make_weights(cfg, seed=5).items()}
+    sess = VerifySession(cfg, weights, max_seqs=2, max_ctx_len=512, n_pages=80)
+    before = sv.spec_tune_get("attn_chunk_pages")
+    sv.spec_tune_set("attn_chunk_pages", 4)               # one work item per 4 pages: the list is sized from the recorded lengths
+    try:
+        sess.pool.zero_()
+        sess.assign(0, 40, [0, 1, 2])
+        sess.assign(1, 20, [3, 4])
+        ids = torch.arange(2, dtype=torch.int32, device="cuda")
+        tok = torch.zeros((2, 4), dtype=torch.int32, device="cuda")
+        snap = torch.empty(sv.spec_kv_state_bytes(sess.kv), dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+        sess.step_buffers(2, 3)
+        with torch.cuda.stream(side):
+            sv.spec_kv_snapshot(sess.kv, snap, side)
+            sv.spec_graph_capture_begin(side)
+            sv.spec_kv_restore(sess.kv, snap, side)
+            sess.forward(ids, tok, stream=side)
+            graph = sv.spec_graph_capture_end(side)
+        torch.cuda.synchronize()
+        sv.spec_graph_launch(graph, side)
+        side.synchronize()
+        sess.state()                                       # replay from the recorded state: no complaint
+        sess.assign(0, 300, list(range(10, 29)))           # a much longer context under the same recording
+        with torch.cuda.stream(side):
+            sv.spec_kv_snapshot(sess.kv, snap, side)
+        side.synchronize()
+        sv.spec_graph_launch(graph, side)
+        side.synchronize()
+        with pytest.raises(sv.SpecError) as e:
+            sess.state()
+        assert e.value.status == sv.SPEC_ESTATE
+        sv.spec_graph_destroy(graph)
+    finally:
+        sv.spec_tune_set("attn_chunk_pages", before)
+        sess.close()
