@@ -106,23 +106,28 @@ def cpu_baseline(wl, torch, n_seqs):
     book = oracle_commit.KVBook(wl.sess.n_pages, si.PAGE_SIZE)
     for b in range(n_seqs):
         book.assign(b, int(ctx[b]), wl.batch["page_lists"][b])
-    t0 = time.perf_counter()
+    t0, c0 = time.perf_counter(), time.process_time()
     logits, _ = of.verify_forward(cfg, w_or, kv_or, tokens, ctx)
     n, _ = oracle_sampler.reject_sample(logits.astype(np.float32), q, tokens[:, 1:], wl.wl["temperature"], wl.seed, 0)
     book.reserve(list(range(n_seqs)), wl.k)
     book.commit(list(range(n_seqs)), n, wl.k)
-    dt = time.perf_counter() - t0
+    dt, cpu = time.perf_counter() - t0, time.process_time() - c0
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        pool = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        cores = 1
+        pool = 1
     produced = float((n + 1).sum())
-    return dict(value=produced / dt, unit="accepted tokens/s", cores=int(cores), kind="oracle",
-                sample="%d of %d sequences of the same batch at full depth (%d layers, full vocabulary): forward + "
-                       "rejection sampling + commit took %.1f s; weights are converted to fp64 per layer inside the timed region; not scaled"
-                       % (n_seqs, wl.B, cfg["n_layers"], dt),
-                seconds=dt), logits
+    # threads the oracle actually kept busy: CPU seconds over wall seconds (its matrix products run on the BLAS pool,
+    # its attention loops and everything else on one thread)
+    busy = max(1, int(round(cpu / dt)))
+    return dict(value=produced / dt, unit="accepted tokens/s", cores=busy, kind="oracle",
+                sample="%d of %d sequences of the same batch at full depth (%d layers, full vocabulary): forward + rejection "
+                       "sampling + commit took %.1f s of wall time and %.1f s of CPU time (BLAS pool of %d threads, the rest "
+                       "single-threaded; fp64 conversion of the weights per layer included).  Sequences are independent, so "
+                       "the rate stands for the whole batch, which would take about %.0f s"
+                       % (n_seqs, wl.B, cfg["n_layers"], dt, cpu, pool, dt * wl.B / n_seqs),
+                seconds=dt, blas_threads=int(pool)), logits
 
 
 def run_continuous(args, wl, sv, torch):
@@ -263,7 +268,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=6)
+    ap.add_argument("--cpu-seqs", type=int, default=8)
     ap.add_argument("--rollout-steps", type=int, default=8, help="draft+target pair: consecutive steps of the sustained run")
     ap.add_argument("--graph", action="store_true", help="record the K timed steps into a HIP graph and time its replay (the default for the single-model workloads)")
     ap.add_argument("--no-graph", action="store_true", help="one host launch per kernel in the timed region")
@@ -353,10 +358,13 @@ def main():
         "attn_partial_kernel": dict(ms=per_step["attn"], launches=launches["attn"], bytes=alg["attn"], flops=0.0),
     }
     dom = max(classes, key=lambda n: classes[n]["ms"])
-    traffic = None
+    # HBM bytes per launch of the dominant kernel by hardware counters: not measured in this run (counters need the
+    # profiler); taken from the committed summary of an earlier counter run of the same command, named in traffic_source
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+        entry = json.load(open(tpath)).get(args.workload, {})
+        traffic, traffic_source = entry.get(dom), entry.get("_source")
 
     def roof(c):
         gbs = c["bytes"] / (c["ms"] / 1e3) / 1e9 if c["ms"] > 0 else 0.0
@@ -368,7 +376,7 @@ def main():
         return dict(bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4),
                     avg_launch_us=round(1e3 * c["ms"] / max(c["launches"], 1), 2),
                     bytes_per_launch=int(c["bytes"] / max(c["launches"], 1)))
-    roofline = dict(kernel=dom, **roof(classes[dom]), traffic=traffic)
+    roofline = dict(kernel=dom, **roof(classes[dom]), traffic=traffic, traffic_source=traffic_source)
     total_bytes = alg["gemm"] + alg["attn"] + alg["sampler"] + alg["logits_write"]
 
     out = {

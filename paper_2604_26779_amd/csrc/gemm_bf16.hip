@@ -243,7 +243,6 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
     // (row tile fastest, then column tile, then k-split).  The workgroups that share a weight tile then share an L2,
     // and an XCD reads the activations of one or two k-splits instead of all of them.
     int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
-#ifndef SPEC_GEMM_NO_XCD_MAP
     if constexpr (!GROUPED) {
         const int nx = gridDim.x, ny = gridDim.y, nz = gridDim.z;
         const int total = nx * ny * nz, lin = bx + nx * (by + ny * bz);
@@ -253,7 +252,6 @@ __global__ __launch_bounds__(GEMM_THREADS, (MB >= 6 || (MB >= 3 && WM == 1 && NB
         bx = (v / nz) % nx;
         by = v / (nz * nx);
     }
-#endif
     const int nb0 = bx * TILE_NB + np * NBW;
     const int ks0 = by * ksteps_per_split;
     int ks1 = ks0 + ksteps_per_split;

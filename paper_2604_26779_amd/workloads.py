@@ -76,11 +76,7 @@ class DeviceWorkload:
         std = (self.wl["noise_std"] * torch.from_numpy(self.batch["noise_scale"]).to(self.device, torch.float32))[:, None]
         for i in range(1, self.k + 1):
             logits = self.sess.forward(self.seq_ids, self.tokens)
-            row = logits[:, i - 1, :]
-            noise = torch.randn(row.shape, generator=g, device=self.device, dtype=torch.float32) * std
-            qi = torch.softmax((row + noise) / T, dim=-1)
-            self.q[:, i - 1, :] = qi
-            self.tokens[:, i] = torch.multinomial(qi, 1, generator=g)[:, 0].to(torch.int32)
+            self.q[:, i - 1, :], self.tokens[:, i] = si.device_draft_step(logits[:, i - 1, :], std, T, g)
         torch.cuda.synchronize()
 
     def logical_kv(self, layer, b):

@@ -181,23 +181,26 @@ def make_weights(cfg, seed=DEFAULT_SEED, device="cpu", std=0.02):
 W8_MATRICES = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "head")
 
 
-def weights_for_oracle(cfg, weights, library_decode=False):
+def weights_for_oracle(cfg, weights, library_decode=False, own_decode_layers=(0,)):
     """The same values as nested fp32 numpy arrays in the layout the oracle's forward takes.  8-bit matrices go as
     bytes plus scales and the oracle decodes them itself; with library_decode (the full-size shapes, where the oracle's
     elementwise decode of 8e9 codes would take minutes) they go as the library's cast of the codes times the scale, which
-    the oracle's decode is pinned against code by code."""
+    the oracle's decode is pinned against code by code - except the layers in own_decode_layers, which still go as codes
+    and scales, so that the oracle's own decoder is on the full-size path too."""
     def f(name):
-        if name + ".scale" in weights and library_decode:
+        # (stacked expert matrices stay with the library's cast: a layer of them is billions of codes)
+        own = any(name.startswith("l%d." % l) for l in own_decode_layers) and not (cfg.get("n_experts", 0) > 0 and name.split(".")[-1] in ("wg", "wu", "wd"))
+        if name + ".scale" in weights and library_decode and not own:
             return (weights[name].detach().to("cpu", torch.float32) * weights[name + ".scale"].detach().to("cpu", torch.float32)[..., None]).numpy()
         if name + ".scale" in weights:                # 8-bit matrix: the oracle gets the codes (bytes) and the scales
             return weights[name].detach().to("cpu").view(torch.uint8).numpy()
         return weights[name].detach().to("cpu", torch.float32).numpy()
 
     def scales_of(prefix, keys):
-        if library_decode:
+        if library_decode and not any(prefix == "l%d." % l for l in own_decode_layers):
             return {}
         return {k + "_scale": weights[prefix + k + ".scale"].detach().to("cpu", torch.float32).numpy()
-                for k in keys if prefix + k + ".scale" in weights}
+                for k in keys if prefix + k + ".scale" in weights and not (library_decode and cfg.get("n_experts", 0) > 0 and k in ("wg", "wu", "wd"))}
     layers = []
     names = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd") + (("router",) if cfg.get("n_experts", 0) > 0 else ())
     for l in range(cfg["n_layers"]):
@@ -314,6 +317,14 @@ def noisy_draft_distribution(logits_row, noise, temperature):
     z = z - z.max(axis=-1, keepdims=True)
     e = np.exp(z)
     return (e / e.sum(axis=-1, keepdims=True)).astype(np.float32)
+
+
+def device_draft_step(logits_row, std, temperature, generator):
+    """The draft stand-in on the device, for the full-size workloads: q = softmax((logits + N(0, std)) / T) and one token
+    drawn from it per row.  logits_row [B, V] fp32 device tensor, std [B, 1]; torch library calls only."""
+    noise = torch.randn(logits_row.shape, generator=generator, device=logits_row.device, dtype=torch.float32) * std
+    q = torch.softmax((logits_row + noise) / temperature, dim=-1)
+    return q, torch.multinomial(q, 1, generator=generator)[:, 0].to(torch.int32)
 
 
 def ceil_div(a, b):

@@ -23,16 +23,22 @@ from tests.helpers import logits_close
 
 pytestmark = pytest.mark.gpu
 
+import os as _os
+_REAL_STDERR = _os.dup(2)              # taken at import, before pytest redirects the descriptors of a test
+
 def _one_per_tile(B, rows_per_seq, tile_rows=128):
     """One batch entry inside every run of tile_rows GEMM rows, at varying places inside the run."""
     per = max(1, tile_rows // rows_per_seq)
     return {min(B - 1, t * per + (5 * t + 3) % per) for t in range(-(-B // per))}
 
 
-def _picks_per_draft_length(B, ks, tile_rows=128):
+def _picks_per_draft_length(workload_name, ks, tile_rows=128):
     """For every k: one batch entry inside every run of tile_rows GEMM rows (rows b (k+1) .. b (k+1) + k belong to
-    entry b), re-using entries already picked for another k where one falls into the run: the oracle's copy of the
-    picked sequences' caches is what limits how many there can be."""
+    entry b), re-using entries already picked for another k where one falls into the run (the oracle's copy of the
+    picked sequences' caches is what limits how many there can be), else the entry of the run with the shortest context
+    (the oracle's attention loops cost rows x context; the longest context of the batch is always compared as well)."""
+    wl = si.WORKLOADS[workload_name]
+    ctx_len, B = si.make_batch(wl)["ctx_len"], wl["B"]
     chosen, out = set(), {}
     for k in sorted(ks, reverse=True):
         T = k + 1
@@ -40,10 +46,17 @@ def _picks_per_draft_length(B, ks, tile_rows=128):
         for t in range(-(-B * T // tile_rows)):
             lo, hi = -(-t * tile_rows // T), min(B, -(-(t + 1) * tile_rows // T))      # entries that start inside the run
             inside = sorted(b for b in chosen if lo <= b < hi)
-            mine.add(inside[0] if inside else min(B - 1, lo + (5 * t + 3) % max(1, hi - lo)))
+            mine.add(inside[0] if inside else lo + int(np.argmin(ctx_len[lo:hi])))
         chosen |= mine
         out[k] = mine
     return out
+
+
+def _say(*args):
+    """A line on the real stderr even under pytest's capture: these tests run for minutes, and a run that prints nothing
+    for long is taken to be hung."""
+    import os
+    os.write(_REAL_STDERR, (" ".join(str(a) for a in args) + "\n").encode())
 
 
 def _check_workload(name, ks, moe_margin=None, more_picks=(), max_exempt_frac=0.25, picks_for_k=None):
@@ -94,6 +107,7 @@ def _check_workload(name, ks, moe_margin=None, more_picks=(), max_exempt_frac=0.
         ok, max_err, worst = logits_close(got, want, 2e-2, 1e-2)
         ratio = float((np.abs(got - want) / (2e-2 + 1e-2 * np.abs(want))).max())
         print("  logits max abs err %.3e, |logit| max %.2f, largest error / tolerance %.2f over %d logits" % (max_err, np.abs(want).max(), ratio, want.size), flush=True)
+        _say("[%s k=%d] %d sequences compared: max abs err %.3e, error / tolerance %.2f" % (name, k, len(picks), max_err, ratio))
         assert ok, (max_err, worst)
 
         # new cache entries of the sampled sequences (last layer) sit where the page table says
@@ -151,7 +165,7 @@ def test_llama8b_logits_on_sampled_sequences_and_commit():
 
 def test_llama8b_large_batch_aliased_pool_all_draft_lengths():
     """k = 7, 5, 3, 1 on the aliased bf16 pools; at every k the sampled sequences cover every 128 rows of the GEMMs."""
-    _check_workload("llama8b_b256_ctx2k-16k_k7", [7, 5, 3, 1], picks_for_k=_picks_per_draft_length(256, (7, 5, 3, 1)))
+    _check_workload("llama8b_b256_ctx2k-16k_k7", [7, 5, 3, 1], picks_for_k=_picks_per_draft_length("llama8b_b256_ctx2k-16k_k7", (7, 5, 3, 1)))
 
 
 def test_llama8b_8bit_cache_full_size():
@@ -168,7 +182,7 @@ def test_llama8b_8bit_matrices_and_cache_full_size():
 def test_llama8b_8bit_cache_large_batch_all_layers_distinct():
     """B = 256, contexts 2048..16384: with one byte per entry the cache of 32 distinct layers (155 GB) fits one GPU,
     so no layer pools are shared here."""
-    _check_workload("llama8b_kv8_b256_ctx2k-16k_k3", [3], more_picks=_one_per_tile(256, 4))
+    _check_workload("llama8b_kv8_b256_ctx2k-16k_k3", [3], picks_for_k=_picks_per_draft_length("llama8b_kv8_b256_ctx2k-16k_k3", (3,)))
 
 
 MOE_PICKS = (3, 17, 29, 40, 55, 64, 78, 99, 110, 127)
