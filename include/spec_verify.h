@@ -421,6 +421,18 @@ spec_status spec_rollout_pending(int32_t B, int32_t n_seqs, const int32_t* dev_s
                                  int32_t* dev_pending, void* stream);
 
 /*
+ * The same for a draft model that takes the verifier's hidden states (Section 2.3; spec_verify_forward_hidden,
+ * spec_next_step_hidden): every slot also carries the hidden states of the positions before its two pending tokens,
+ * dev_pending_hidden [B, 2, d] fp32.  A waiting sequence brings its own, dev_seq_hidden [n_seqs, 2, d] fp32, left by
+ * whatever prefilled it (the verifier's hidden state of the position before its last prompt token, and of that token's
+ * own position); the live slots whose sequence changed in spec_rollout_retire get them, the others are left alone.
+ * Call it with the same dev_slot_seq_before as spec_rollout_pending.  Plain copies.  Asynchronous on `stream`.
+ */
+spec_status spec_rollout_pending_hidden(int32_t B, int32_t n_seqs, int32_t d, const int32_t* dev_slot_seq_before,
+                                        const int32_t* dev_slot_seq, const int32_t* dev_active, const float* dev_seq_hidden,
+                                        float* dev_pending_hidden, void* stream);
+
+/*
  * Replay of a recorded sequence of step calls (for callers whose steps are short enough that launching ~350 small
  * kernels per step costs more than running them).  Between spec_graph_capture_begin and spec_graph_capture_end every
  * call of this library on `stream` (which must not be the default stream) is recorded instead of executed; the

@@ -84,3 +84,20 @@ def backfill_pending(pending, slot_seq_before, slot_seq, active, prev_token, fir
             pending[b, 1] = first_token[s]
             changed.append(b)
     return changed
+
+
+def backfill_pending_hidden(pending_hidden, slot_seq_before, slot_seq, active, seq_hidden):
+    """A draft model that takes the verifier's hidden states (the paper's Section 2.3 drafting paths) also carries, per
+    slot, the hidden states of the positions before its two pending tokens (``oracle/draft.py: next_pending_hidden``).
+    A waiting sequence brings its own: seq_hidden[s] [2, d], left by whatever prefilled it - the verifier's hidden state
+    of the position before the last prompt token and of the last prompt token's own position.  A slot that sequence s
+    has just taken over gets them; every other slot is left alone.  pending_hidden [B, 2, d] is updated in place.
+    Returns the slots that changed (the same ones ``backfill_pending`` changes)."""
+    changed = []
+    for b in range(len(slot_seq)):
+        s = int(slot_seq[b])
+        if active[b] and s != int(slot_seq_before[b]):
+            pending_hidden[b, 0, :] = seq_hidden[s, 0, :]
+            pending_hidden[b, 1, :] = seq_hidden[s, 1, :]
+            changed.append(b)
+    return changed

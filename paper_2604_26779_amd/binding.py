@@ -24,7 +24,7 @@ EXPORTS = [
     "spec_kv_alloc", "spec_kv_free", "spec_kv_set_scales", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample", "spec_reject_sample_static",
-    "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_rollout_pending", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
+    "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_rollout_pending", "spec_rollout_pending_hidden", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_graph_capture_begin", "spec_graph_capture_end", "spec_graph_launch",
     "spec_graph_destroy", "spec_calib_read", "spec_calib_copy",
 ]
@@ -90,6 +90,7 @@ def lib():
             "spec_rollout_retire": (i32, [i32, i32, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]),
             "spec_rollout_compact": (i32, [i32, i32, vp, vp, vp, vp, vp, vp]),
             "spec_rollout_pending": (i32, [i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+            "spec_rollout_pending_hidden": (i32, [i32, i32, i32, vp, vp, vp, vp, vp, vp]),
             "spec_tune_set": (i32, [ctypes.c_char_p, i32]),
             "spec_tune_get": (i32, [ctypes.c_char_p]),
             "spec_profile_class_count": (i32, []),
@@ -314,6 +315,13 @@ def spec_rollout_retire(B, k, slot_seq, active, accept_len, gen_len, target_len,
 def spec_rollout_pending(B, slot_seq_before, slot_seq, active, prev_token, first_token, pending, stream=None):
     _check(lib().spec_rollout_pending(B, int(prev_token.shape[0]), _ptr(slot_seq_before), _ptr(slot_seq), _ptr(active),
                                       _ptr(prev_token), _ptr(first_token), _ptr(pending), _stream(stream)))
+
+
+def spec_rollout_pending_hidden(B, slot_seq_before, slot_seq, active, seq_hidden, pending_hidden, stream=None):
+    """seq_hidden [n_seqs, 2, d], pending_hidden [B, 2, d]: contiguous fp32 device tensors."""
+    assert seq_hidden.is_contiguous() and pending_hidden.is_contiguous() and seq_hidden.shape[1:] == pending_hidden.shape[1:]
+    _check(lib().spec_rollout_pending_hidden(B, int(seq_hidden.shape[0]), int(seq_hidden.shape[2]), _ptr(slot_seq_before), _ptr(slot_seq),
+                                             _ptr(active), _ptr(seq_hidden), _ptr(pending_hidden), _stream(stream)))
 
 
 def spec_rollout_compact(B, k, slot_seq, active, tokens, n_live, scratch, stream=None):

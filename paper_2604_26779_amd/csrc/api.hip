@@ -671,6 +671,22 @@ extern "C" spec_status spec_rollout_pending(int32_t B, int32_t n_seqs, const int
     return SPEC_OK;
 }
 
+extern "C" spec_status spec_rollout_pending_hidden(int32_t B, int32_t n_seqs, int32_t d, const int32_t* dev_slot_seq_before,
+                                                   const int32_t* dev_slot_seq, const int32_t* dev_active, const float* dev_seq_hidden,
+                                                   float* dev_pending_hidden, void* stream)
+{
+    if (B < 1 || n_seqs < 1 || d < 1) { set_error("spec_rollout_pending_hidden: B, n_seqs or d out of range"); return SPEC_EINVAL; }
+    if (!dev_slot_seq_before || !dev_slot_seq || !dev_active || !dev_seq_hidden || !dev_pending_hidden) {
+        set_error("spec_rollout_pending_hidden: null pointer");
+        return SPEC_EINVAL;
+    }
+    spec_status st = launch_rollout_pending_hidden(B, n_seqs, d, dev_slot_seq_before, dev_slot_seq, dev_active, dev_seq_hidden,
+                                                   dev_pending_hidden, (hipStream_t)stream);
+    if (st != SPEC_OK) return st;
+    prof_mark(PC_OTHER, (hipStream_t)stream);
+    return SPEC_OK;
+}
+
 extern "C" size_t spec_kv_state_bytes(const spec_kv* kv) { return kv ? kv->state_ints * sizeof(int32_t) : 0; }
 
 extern "C" spec_status spec_kv_snapshot(spec_kv* kv, void* dev_buf, void* stream)

@@ -149,6 +149,8 @@ spec_status launch_rollout_retire(int B, int k, int n_seqs, int32_t* slot_seq, i
                                   int32_t* keep_len, int64_t* produced, hipStream_t s);
 spec_status launch_rollout_pending(int B, int n_seqs, const int32_t* slot_seq_before, const int32_t* slot_seq, const int32_t* active,
                                    const int32_t* prev_token, const int32_t* first_token, int32_t* pending, hipStream_t s);
+spec_status launch_rollout_pending_hidden(int B, int n_seqs, int d, const int32_t* slot_seq_before, const int32_t* slot_seq,
+                                          const int32_t* active, const float* seq_hidden, float* pending_hidden, hipStream_t s);
 spec_status launch_rollout_compact(int B, int k, int32_t* slot_seq, int32_t* active, int32_t* tokens, int32_t* n_live,
                                    int32_t* scratch, hipStream_t s);
 spec_status launch_kv_truncate(spec_kv* kv, int B, const int32_t* dev_seq_ids, const int32_t* dev_len, int delta,

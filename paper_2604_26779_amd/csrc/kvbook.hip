@@ -329,6 +329,27 @@ __global__ void rollout_pending_kernel(int B, int n_seqs, const int32_t* __restr
     pending[2 * b + 1] = first_token[s];
 }
 
+// pending_hidden[b] = seq_hidden[s] (two rows of d floats) for the live slots whose sequence s changed in the retire step
+__global__ void rollout_pending_hidden_kernel(int B, int n_seqs, int d, const int32_t* __restrict__ slot_seq_before,
+                                              const int32_t* __restrict__ slot_seq, const int32_t* __restrict__ active,
+                                              const float* __restrict__ seq_hidden, float* __restrict__ pending_hidden)
+{
+    const int b = blockIdx.x;
+    const int s = slot_seq[b];
+    if (!active[b] || s == slot_seq_before[b] || s < 0 || s >= n_seqs) return;
+    const float* src = seq_hidden + (int64_t)s * 2 * d;
+    float* dst = pending_hidden + (int64_t)b * 2 * d;
+    for (int i = threadIdx.x; i < 2 * d; i += blockDim.x) dst[i] = src[i];
+}
+
+spec_status launch_rollout_pending_hidden(int B, int n_seqs, int d, const int32_t* slot_seq_before, const int32_t* slot_seq,
+                                          const int32_t* active, const float* seq_hidden, float* pending_hidden, hipStream_t s)
+{
+    rollout_pending_hidden_kernel<<<(unsigned)B, 256, 0, s>>>(B, n_seqs, d, slot_seq_before, slot_seq, active, seq_hidden, pending_hidden);
+    SPEC_LAUNCH_CHECK("rollout_pending_hidden_kernel");
+    return SPEC_OK;
+}
+
 spec_status launch_rollout_pending(int B, int n_seqs, const int32_t* slot_seq_before, const int32_t* slot_seq, const int32_t* active,
                                    const int32_t* prev_token, const int32_t* first_token, int32_t* pending, hipStream_t s)
 {

@@ -231,12 +231,15 @@ class ContinuousPairRollout:
     array; waiting sequences are prefilled in both caches (the draft's one position behind the verifier's).  Only call
     order and buffers are handled here."""
 
-    def __init__(self, target_session, draft_session, B, k, slot_seq, target_len, queue, prev_token, first_token):
+    def __init__(self, target_session, draft_session, B, k, slot_seq, target_len, queue, prev_token, first_token, seq_hidden=None):
+        """seq_hidden [n_seqs, 2, d] fp32: for a draft with hidden-state input, every sequence's own pair of verifier
+        hidden states (the positions before its last prompt token and before its first input)."""
         self.t, self.d, self.B, self.k = target_session, draft_session, int(B), int(k)
         dev = target_session.device
         n_seqs = int(target_len.shape[0])
         self.loop = DraftLoop(draft_session, B, k)
-        assert not self.loop.fused, "a draft with hidden-state input would also need the waiting sequences' hidden states"
+        self.fused = self.loop.fused
+        assert not self.fused or seq_hidden is not None, "a draft with hidden-state input needs every sequence's own pair of hidden states"
         self.slot_seq = slot_seq.to(dev, torch.int32).clone()
         self.slot_seq_before = self.slot_seq.clone()
         self.target_len = target_len.to(dev, torch.int32)
@@ -256,6 +259,11 @@ class ContinuousPairRollout:
         self.tokens[:, 0] = self.first_token[idx]
         self.pending[:, 0] = self.prev_token[idx]
         self.pending[:, 1] = self.first_token[idx]
+        if self.fused:
+            d = target_session.cfg["d_model"]
+            self.seq_hidden = seq_hidden.to(dev, torch.float32).contiguous()
+            self.pending_hidden = self.seq_hidden[idx].contiguous()
+            self.target_hidden = torch.zeros((B, k + 1, d), dtype=torch.float32, device=dev)
 
     def run(self, n_steps, temperature, seed, step0=0, live_out=None, accept_out=None, stream=None):
         """live_out [n_steps] int32, accept_out [n_steps, B] int32 (device, optional): live slots after and accept
@@ -269,20 +277,30 @@ class ContinuousPairRollout:
         out = buf["out_tokens"]
         for s in range(n_steps):
             acc = accept_out[s] if accept_out is not None else buf["accept_len"]
-            drafts = self.loop.run(self.slot_seq, self.pending, self.q, temperature, seed, step0 + s, stream)
+            drafts = self.loop.run(self.slot_seq, self.pending, self.q, temperature, seed, step0 + s, stream,
+                                   self.pending_hidden if self.fused else None)
             self.tokens[:, 1:] = drafts
-            sv.spec_verify_forward(t.model, t.kv, B, k, self.slot_seq, self.tokens, buf["logits"], ws, stream)
+            if self.fused:
+                sv.spec_verify_forward_hidden(t.model, t.kv, B, k, self.slot_seq, self.tokens, None, buf["logits"], self.target_hidden,
+                                              ws, stream)
+            else:
+                sv.spec_verify_forward(t.model, t.kv, B, k, self.slot_seq, self.tokens, buf["logits"], ws, stream)
             sv.spec_reject_sample(B, k, V, buf["logits"], self.q, drafts, temperature, seed, step0 + s, acc, out, None,
                                   buf["sample_ws"], stream)
             sv.spec_commit_kv(t.kv, B, k, self.slot_seq, acc, buf["new_ctx_len"], None, stream)
             self.loop.roll_back(self.slot_seq, buf["new_ctx_len"], stream)
             sv.spec_next_step_inputs(B, k, self.tokens, out, acc, self.pending, stream)
+            if self.fused:
+                sv.spec_next_step_hidden(B, k, t.cfg["d_model"], self.target_hidden, acc, self.pending_hidden, stream)
             self.slot_seq_before.copy_(self.slot_seq)
             sv.spec_rollout_retire(B, k, self.slot_seq, self.active, acc, self.gen_len, self.target_len, self.queue,
                                    self.queue_head, self.first_token, self.tokens, self.release_seq, self.keep_len,
                                    self.produced, stream)
             sv.spec_rollout_pending(B, self.slot_seq_before, self.slot_seq, self.active, self.prev_token, self.first_token,
                                     self.pending, stream)
+            if self.fused:
+                sv.spec_rollout_pending_hidden(B, self.slot_seq_before, self.slot_seq, self.active, self.seq_hidden,
+                                               self.pending_hidden, stream)
             sv.spec_kv_truncate(t.kv, B, self.release_seq, self.keep_len, 0, None, stream)
             sv.spec_kv_truncate(self.d.kv, B, self.release_seq, self.keep_len, 0, None, stream)
             if live_out is not None:

@@ -241,3 +241,84 @@ def test_backfilled_slots_get_their_own_pending_pair_and_a_pair_rollout_drains()
     print("pair rollout: %d slots, %d sequences, drained in %d steps, %d tokens" % (slots, n_seqs, steps, int(roll.produced.item())))
     tsess.close()
     dsess.close()
+
+
+def test_hidden_state_pairs_follow_taken_over_slots_and_a_fused_pair_rollout_drains():
+    """spec_rollout_pending_hidden bit for bit against the oracle on random slot tables, and a whole continuous rollout
+    whose draft model takes the verifier's hidden states (small bf16 pair, slots taken over several times): every
+    sequence produces exactly its response length, both caches end empty, at every step a live slot's draft cache is one
+    position behind its verifier cache, and a slot that was just taken over carries its new sequence's own hidden states."""
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.draft import ContinuousPairRollout
+    from paper_2604_26779_amd.session import VerifySession
+    rng = np.random.default_rng(31)
+    for B, n_seqs, d, p_change, p_live in ((1, 3, 8, 1.0, 1.0), (7, 40, 512, 0.5, 0.7), (300, 900, 64, 0.3, 0.5)):
+        before = rng.permutation(n_seqs)[:B].astype(np.int32)
+        after = before.copy()
+        spare = [s for s in range(n_seqs) if s not in set(before.tolist())]
+        for b in range(B):
+            if spare and rng.random() < p_change:
+                after[b] = spare.pop()
+        active = (rng.random(B) < p_live).astype(np.int32)
+        seq_hidden = rng.standard_normal((n_seqs, 2, d)).astype(np.float32)
+        ph = rng.standard_normal((B, 2, d)).astype(np.float32)
+        want = ph.copy()
+        oro.backfill_pending_hidden(want, before, after, active, seq_hidden)
+        dv = lambda a: torch.from_numpy(a).cuda()
+        d_ph = dv(ph)
+        sv.spec_rollout_pending_hidden(B, dv(before), dv(after), dv(active), dv(seq_hidden), d_ph)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_ph.cpu().numpy(), want)
+
+    cfg_t, cfg_d = si.MODELS["small_bf16"], si.MODELS["draft_fused_small_bf16"]
+    slots, n_seqs, k = 4, 10, 3
+    ctx0 = rng.integers(2, 60, size=n_seqs).astype(np.int64)
+    n_pages = 160
+    tsess = VerifySession(cfg_t, {n: t.cuda() for n, t in si.make_weights(cfg_t, seed=5).items()}, max_seqs=n_seqs, max_ctx_len=256,
+                          n_pages=n_pages)
+    dsess = VerifySession(cfg_d, {n: t.cuda() for n, t in si.make_weights(cfg_d, seed=6).items()}, max_seqs=n_seqs, max_ctx_len=256,
+                          n_pages=n_pages)
+    tsess.pool.normal_()
+    dsess.pool.normal_()
+    at = dat = 0
+    for s in range(n_seqs):                               # prompts cached: the draft's cache one position behind
+        need, dneed = -(-int(ctx0[s]) // si.PAGE_SIZE), -(-int(ctx0[s] - 1) // si.PAGE_SIZE)
+        tsess.assign(s, int(ctx0[s]), list(range(at, at + need)))
+        dsess.assign(s, int(ctx0[s]) - 1, list(range(dat, dat + dneed)))
+        at += need
+        dat += dneed
+    target = rng.integers(1, 14, size=n_seqs).astype(np.int32)
+    prev = torch.from_numpy(rng.integers(0, cfg_t["vocab"], size=n_seqs).astype(np.int32))
+    first = torch.from_numpy(rng.integers(0, cfg_t["vocab"], size=n_seqs).astype(np.int32))
+    seq_hidden = torch.from_numpy(rng.standard_normal((n_seqs, 2, cfg_t["d_model"])).astype(np.float32))
+    roll = ContinuousPairRollout(tsess, dsess, slots, k, torch.arange(slots, dtype=torch.int32), torch.from_numpy(target),
+                                 torch.arange(slots, n_seqs, dtype=torch.int32), prev, first, seq_hidden=seq_hidden)
+    live = torch.zeros(1, dtype=torch.int32, device="cuda")
+    steps, taken_over = 0, 0
+    while steps < 200:
+        seq_before = roll.slot_seq.cpu().numpy().copy()
+        roll.run(1, 1.0, 78, steps, live_out=live)
+        steps += 1
+        torch.cuda.synchronize()
+        ts, ds = tsess.state(), dsess.state()
+        slot_seq, active = roll.slot_seq.cpu().numpy(), roll.active.cpu().numpy()
+        for b in range(slots):
+            s = int(slot_seq[b])
+            if active[b]:
+                assert ds["ctx_len"][s] == ts["ctx_len"][s] - 1, (steps, b, s)
+                assert int(roll.pending[b, 1].item()) == int(roll.tokens[b, 0].item())
+                if s != int(seq_before[b]):
+                    assert torch.equal(roll.pending_hidden[b].cpu(), seq_hidden[s])
+                    taken_over += 1
+                assert torch.isfinite(roll.pending_hidden[b]).all()
+            else:
+                assert ts["ctx_len"][s] == 0 and ds["ctx_len"][s] == 0
+        if int(live.item()) == 0:
+            break
+    assert int(live.item()) == 0 and int(roll.produced.item()) == int(target.sum()) and taken_over == n_seqs - slots
+    assert np.array_equal(roll.gen_len.cpu().numpy(), target) and int(roll.queue_head.item()) == n_seqs - slots
+    for st in (tsess.state(), dsess.state()):
+        assert np.all(st["ctx_len"][:n_seqs] == 0) and np.all(st["n_pages"][:n_seqs] == 0) and len(st["free_stack"]) == n_pages
+    print("fused pair rollout: %d slots, %d sequences, drained in %d steps, %d tokens" % (slots, n_seqs, steps, int(roll.produced.item())))
+    tsess.close()
+    dsess.close()

@@ -125,3 +125,35 @@ def test_backfill_pending_touches_only_slots_taken_over():
             assert pending[b, 1] == tokens[b, 0]                        # the same first input the verifier gets
         else:
             assert list(pending[b]) == list(old_pending[b])
+
+
+def test_backfill_pending_hidden_follows_the_token_pairs():
+    """The hidden-state pairs change for exactly the slots whose token pairs change, and to the new sequence's own two
+    states; checked against the definition spelled out per slot on the same retire step as above, plus random tables."""
+    rng = np.random.default_rng(4)
+    B, n_seqs, d = 5, 8, 6
+    before = np.arange(B, dtype=np.int32)
+    after = np.array([5, 1, 6, 3, 4], dtype=np.int32)
+    active = np.array([1, 1, 1, 0, 0], dtype=np.int32)
+    seq_hidden = rng.standard_normal((n_seqs, 2, d)).astype(np.float32)
+    ph = rng.standard_normal((B, 2, d)).astype(np.float32)
+    old = ph.copy()
+    pend = np.zeros((B, 2), dtype=np.int32)
+    assert oro.backfill_pending_hidden(ph, before, after, active, seq_hidden) == [0, 2] == \
+        oro.backfill_pending(pend, before, after, active, np.zeros(n_seqs, np.int32), np.zeros(n_seqs, np.int32))
+    for b in range(B):
+        want = seq_hidden[after[b]] if b in (0, 2) else old[b]
+        assert np.array_equal(ph[b], want)
+    for trial in range(50):                                            # idle slots and kept slots never change
+        B, n_seqs = int(rng.integers(1, 40)), 60
+        before = rng.permutation(n_seqs)[:B].astype(np.int32)
+        after = np.where(rng.random(B) < 0.4, rng.permutation(n_seqs)[:B], before).astype(np.int32)
+        active = (rng.random(B) < 0.6).astype(np.int32)
+        seq_hidden = rng.standard_normal((n_seqs, 2, d)).astype(np.float32)
+        ph = rng.standard_normal((B, 2, d)).astype(np.float32)
+        old = ph.copy()
+        changed = oro.backfill_pending_hidden(ph, before, after, active, seq_hidden)
+        for b in range(B):
+            moved = bool(active[b]) and after[b] != before[b]
+            assert (b in changed) == moved
+            assert np.array_equal(ph[b], seq_hidden[after[b]] if moved else old[b])
