@@ -276,12 +276,15 @@ spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const int32_t* dev
  * Draw: exponential race argmax_v q_v / (-ln u_v), ties to the lowest v, Philox4x32-10 with the key and
  * counter layout of spec_reject_sample on stream 2: counter = (v >> 2, row, b, step*4 + 2), word v & 3,
  * u_v = ((word >> 9) + 0.5) * 2^-23; `row` is the index of the draft position (0 .. SPEC_MAX_DRAFT).
- * Errors: SPEC_EINVAL (sizes, strides below V, temperature <= 0, step >= 2^30, null).  Asynchronous on `stream`.
+ * dev_workspace: at least spec_draft_sample_workspace_bytes(B) bytes of device memory (contents irrelevant).
+ * Errors: SPEC_EINVAL (sizes, strides below V, temperature <= 0, step >= 2^30, null, workspace too small).
+ * Asynchronous on `stream`.
  */
+size_t spec_draft_sample_workspace_bytes(int32_t B);
 spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int64_t logits_row_stride,
                               float temperature, uint64_t seed, uint64_t step, int32_t row,
                               int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
-                              float* dev_q, int64_t q_row_stride, void* stream);
+                              float* dev_q, int64_t q_row_stride, void* dev_workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Roll a cache back (the draft's cache after verification keeps only what the verifier kept): batch entry b

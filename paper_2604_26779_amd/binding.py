@@ -24,7 +24,7 @@ EXPORTS = [
     "spec_kv_alloc", "spec_kv_free", "spec_kv_set_scales", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample", "spec_reject_sample_static",
-    "spec_commit_kv", "spec_draft_sample", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_rollout_pending", "spec_rollout_pending_hidden", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
+    "spec_commit_kv", "spec_draft_sample", "spec_draft_sample_workspace_bytes", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_rollout_pending", "spec_rollout_pending_hidden", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_graph_capture_begin", "spec_graph_capture_end", "spec_graph_launch",
     "spec_graph_destroy", "spec_calib_read", "spec_calib_copy",
 ]
@@ -82,7 +82,8 @@ def lib():
             "spec_reject_sample": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp, sz, vp]),
             "spec_reject_sample_static": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp]),
             "spec_commit_kv": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
-            "spec_draft_sample": (i32, [i32, i32, vp, i64, f32, u64, u64, i32, vp, i32, vp, i32, vp, i64, vp]),
+            "spec_draft_sample": (i32, [i32, i32, vp, i64, f32, u64, u64, i32, vp, i32, vp, i32, vp, i64, vp, sz, vp]),
+            "spec_draft_sample_workspace_bytes": (sz, [i32]),
             "spec_kv_truncate": (i32, [vp, i32, vp, vp, i32, vp, vp]),
             "spec_next_step_inputs": (i32, [i32, i32, vp, vp, vp, vp, vp]),
             "spec_ngram_draft": (i32, [i32, i32, i32, i32, vp, i64, i32, vp, vp, vp, vp, vp]),
@@ -276,12 +277,24 @@ def spec_commit_kv(kv, B, k, seq_ids, accept_len, new_ctx_len, commit_slots, str
                                 _stream(stream)))
 
 
+def spec_draft_sample_workspace_bytes(B):
+    return int(lib().spec_draft_sample_workspace_bytes(int(B)))
+
+
+_draft_ws = {}
+
+
 def spec_draft_sample(B, V, logits, logits_row_stride, temperature, seed, step, row, tokens_a, stride_a, tokens_b, stride_b,
-                      q, q_row_stride, stream=None):
-    """logits, tokens_a, tokens_b, q: device tensors or raw addresses (ints) of the first row / element."""
+                      q, q_row_stride, stream=None, workspace=None):
+    """logits, tokens_a, tokens_b, q: device tensors or raw addresses (ints) of the first row / element.
+    workspace: uint8 device tensor of spec_draft_sample_workspace_bytes(B) bytes (one per batch size is kept here if none is given)."""
+    if workspace is None:
+        if B not in _draft_ws:
+            _draft_ws[B] = torch.empty(spec_draft_sample_workspace_bytes(B), dtype=torch.uint8, device="cuda")
+        workspace = _draft_ws[B]
     _check(lib().spec_draft_sample(B, V, _addr(logits), int(logits_row_stride), float(temperature), int(seed), int(step),
                                    int(row), _addr(tokens_a), int(stride_a), _addr(tokens_b), int(stride_b), _addr(q),
-                                   int(q_row_stride), _stream(stream)))
+                                   int(q_row_stride), _ptr(workspace), workspace.numel(), _stream(stream)))
 
 
 def spec_kv_truncate(kv, B, seq_ids, lengths, delta, new_len, stream=None):

@@ -55,10 +55,10 @@ __device__ inline void part_groups(int V, int part, int* g0, int* g1)
     *g1 = (part + 1) * per < groups ? (part + 1) * per : groups;
 }
 
-__global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __restrict__ logits, int V, float inv_t,
+__global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __restrict__ logits, int64_t row_stride, int V, float inv_t,
                                                                   float2* __restrict__ stats)
 {
-    const float* row = logits + (int64_t)blockIdx.x * V;
+    const float* row = logits + (int64_t)blockIdx.x * row_stride;
     int g0, g1;
     part_groups(V, blockIdx.y, &g0, &g1);
     const int v1 = g1 * 4 < V ? g1 * 4 : V;
@@ -227,41 +227,29 @@ __global__ void reject_merge_kernel(int B, int k, const RacePart* __restrict__ p
     for (int i = n + 1; i <= k; ++i) o[i] = -1;
 }
 
-// The draft model's own draw (one workgroup per sequence): q = softmax(logits / T) written out for
-// the verifier, and x = argmax_v e_v / (-ln u_v) on random stream 2 (e = exp(z - max): the argmax
-// does not need the normalisation).  Two passes over the row; the second one hits the cache.
-__global__ __launch_bounds__(SAMP_THREADS) void draft_sample_kernel(
+// The draft model's own draw, over the same SAMP_PARTS vocabulary ranges as the verifier's: q = softmax(logits / T)
+// written out for the verifier, and x = argmax_v e_v / (-ln u_v) on random stream 2 (e = exp(z - max): the argmax does
+// not need the normalisation).  row_stats_kernel gives the ranges' (max, sum); draft_scan_kernel (workgroup = sequence,
+// range) merges them, writes its range of q and finds its range's best key; draft_merge_kernel picks the token.
+struct DraftPart { float key; int32_t v; };
+
+__global__ __launch_bounds__(SAMP_THREADS) void draft_scan_kernel(
     int V, const float* __restrict__ logits, int64_t logits_stride, float inv_t, uint32_t seed_lo, uint32_t seed_hi,
-    uint32_t step4, uint32_t row, int32_t* __restrict__ tok_a, int stride_a, int32_t* __restrict__ tok_b, int stride_b,
-    float* __restrict__ q, int64_t q_stride)
+    uint32_t step4, uint32_t row, const float2* __restrict__ stats, float* __restrict__ q, int64_t q_stride,
+    DraftPart* __restrict__ parts)
 {
-    const int b = blockIdx.x;
+    const int b = blockIdx.x, part = blockIdx.y;
     const float* lrow = logits + (int64_t)b * logits_stride;
     float* qrow = q + (int64_t)b * q_stride;
-    __shared__ float lm[SAMP_THREADS / 64], ls[SAMP_THREADS / 64];
     __shared__ float lk[SAMP_THREADS / 64];
     __shared__ int lv[SAMP_THREADS / 64];
-    float m = -INFINITY, s = 0.f;
-    for (int v = threadIdx.x; v < V; v += SAMP_THREADS) {
-        float z = lrow[v] * inv_t;
-        if (z > m) { s = s * expf(m - z) + 1.f; m = z; }
-        else if (z > -INFINITY) s += expf(z - m);
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
-        online_merge(m, s, m2, s2);
-    }
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (lane == 0) { lm[wave] = m; ls[wave] = s; }
-    __syncthreads();
-    m = lm[0]; s = ls[0];
-    for (int w = 1; w < SAMP_THREADS / 64; ++w) online_merge(m, s, lm[w], ls[w]);
-    const float inv_s = 1.0f / s;
-
+    const float2 st = row_stat(stats, b);                      // every thread merges the 8 ranges itself (cached loads)
+    const float m = st.x, inv_s = 1.0f / st.y;
+    int g0, g1;
+    part_groups(V, part, &g0, &g1);
     float best = -1.f;
     int best_v = -1;
-    const int groups = (V + 3) >> 2;
-    for (int g = threadIdx.x; g < groups; g += SAMP_THREADS) {
+    for (int g = g0 + threadIdx.x; g < g1; g += SAMP_THREADS) {
         Philox4 r = philox4x32_10((uint32_t)g, row, (uint32_t)b, step4 + 2u, seed_lo, seed_hi);
         uint32_t words[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
@@ -277,10 +265,19 @@ __global__ __launch_bounds__(SAMP_THREADS) void draft_sample_kernel(
         }
     }
     block_argmax(best, best_v, lk, lv);
-    if (threadIdx.x == 0) {
-        if (tok_a) tok_a[(int64_t)b * stride_a] = best_v;
-        if (tok_b) tok_b[(int64_t)b * stride_b] = best_v;
-    }
+    if (threadIdx.x == 0) { parts[(int64_t)b * SAMP_PARTS + part].key = best; parts[(int64_t)b * SAMP_PARTS + part].v = best_v; }
+}
+
+__global__ void draft_merge_kernel(int B, const DraftPart* __restrict__ parts, int32_t* __restrict__ tok_a, int stride_a,
+                                   int32_t* __restrict__ tok_b, int stride_b)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    float key = -1.f;
+    int v = -1;
+    for (int i = 0; i < SAMP_PARTS; ++i) argmax_merge(key, v, parts[(int64_t)b * SAMP_PARTS + i].key, parts[(int64_t)b * SAMP_PARTS + i].v);
+    if (tok_a) tok_a[(int64_t)b * stride_a] = v;
+    if (tok_b) tok_b[(int64_t)b * stride_b] = v;
 }
 
 }  // namespace specv
@@ -312,7 +309,7 @@ static spec_status reject_sample_launch(const char* who, int32_t B, int32_t k, i
     float inv_t = 1.0f / temperature;
     RacePart* parts = (RacePart*)((char*)ws + sample_stats_bytes((int64_t)B * (k + 1)));
     prof_mark(PC_OTHER, s);
-    row_stats_kernel<<<dim3((unsigned)(B * (k + 1)), SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, V, inv_t, stats);
+    row_stats_kernel<<<dim3((unsigned)(B * (k + 1)), SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, (int64_t)V, V, inv_t, stats);
     SPEC_LAUNCH_CHECK("row_stats_kernel");
     prof_mark(PC_SAMPLE_STATS, s);
     reject_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(k, V, dev_logits, dev_q, dev_draft_tokens, inv_t, (uint32_t)seed,
@@ -381,10 +378,16 @@ extern "C" spec_status spec_reject_sample_static(int32_t B, int32_t k, int32_t V
                                 dev_accept_len, dev_out_tokens, dev_dbg, stats, (hipStream_t)stream);
 }
 
+extern "C" size_t spec_draft_sample_workspace_bytes(int32_t B)
+{
+    if (B < 1) return 0;
+    return sample_stats_bytes(B) + specv::align_up((size_t)B * specv::SAMP_PARTS * sizeof(specv::DraftPart), 256);
+}
+
 extern "C" spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int64_t logits_row_stride,
                                          float temperature, uint64_t seed, uint64_t step, int32_t row,
                                          int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
-                                         float* dev_q, int64_t q_row_stride, void* stream)
+                                         float* dev_q, int64_t q_row_stride, void* dev_workspace, size_t workspace_bytes, void* stream)
 {
     using namespace specv;
     if (B < 1 || V < 1 || row < 0 || row > SPEC_MAX_DRAFT) { set_error("spec_draft_sample: B, V or row out of range"); return SPEC_EINVAL; }
@@ -394,12 +397,18 @@ extern "C" spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_
     if (logits_row_stride < V || q_row_stride < V || (dev_tokens_a && stride_a < 1) || (dev_tokens_b && stride_b < 1)) {
         set_error("spec_draft_sample: a row stride is smaller than the row"); return SPEC_EINVAL;
     }
+    if (!dev_workspace || workspace_bytes < spec_draft_sample_workspace_bytes(B)) { set_error("spec_draft_sample: workspace missing or too small"); return SPEC_EINVAL; }
     hipStream_t s = (hipStream_t)stream;
     prof_mark(PC_OTHER, s);
-    draft_sample_kernel<<<B, SAMP_THREADS, 0, s>>>(V, dev_logits, logits_row_stride, 1.0f / temperature, (uint32_t)seed,
-                                                   (uint32_t)(seed >> 32), (uint32_t)(step * 4u), (uint32_t)row,
-                                                   dev_tokens_a, stride_a, dev_tokens_b, stride_b, dev_q, q_row_stride);
-    SPEC_LAUNCH_CHECK("draft_sample_kernel");
+    float2* stats = (float2*)dev_workspace;
+    DraftPart* parts = (DraftPart*)((char*)dev_workspace + sample_stats_bytes(B));
+    const float inv_t = 1.0f / temperature;
+    row_stats_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, logits_row_stride, V, inv_t, stats);
+    draft_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(V, dev_logits, logits_row_stride, inv_t, (uint32_t)seed,
+                                                                            (uint32_t)(seed >> 32), (uint32_t)(step * 4u), (uint32_t)row, stats,
+                                                                            dev_q, q_row_stride, parts);
+    draft_merge_kernel<<<(unsigned)cdiv(B, 256), 256, 0, s>>>(B, parts, dev_tokens_a, stride_a, dev_tokens_b, stride_b);
+    SPEC_LAUNCH_CHECK("draft sampling kernels");
     prof_mark(PC_DRAFT_SAMPLE, s);
     return SPEC_OK;
 }

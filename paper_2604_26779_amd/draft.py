@@ -17,6 +17,7 @@ class DraftLoop:
         self.zeros = torch.zeros(B, dtype=torch.int32, device=dev)
         self.drafts = torch.zeros((B, k), dtype=torch.int32, device=dev)
         self.new_len = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.sample_ws = torch.empty(sv.spec_draft_sample_workspace_bytes(B), dtype=torch.uint8, device=dev)
         # a draft that takes hidden states chains its own: the last row of a pass feeds the next pass
         self.fused = bool(draft_session.cfg.get("fuse_hidden", 0))
         d = draft_session.cfg["d_model"]
@@ -55,7 +56,7 @@ class DraftLoop:
                 last, stride = logits.data_ptr(), V
             sv.spec_draft_sample(B, V, last, stride, temperature, seed, step, i,
                                  self.drafts.data_ptr() + 4 * i, k, self.feed, 1,
-                                 q_out.data_ptr() + 4 * i * V, k * V, stream)
+                                 q_out.data_ptr() + 4 * i * V, k * V, stream, self.sample_ws)
             fed = P if i == 0 else 1
             sv.spec_commit_kv(sess.kv, B, fed - 1, seq_ids, self.ones if fed == 2 else self._full(fed - 1), None, None, stream)
         return self.drafts

@@ -64,9 +64,10 @@ def test_argument_checks_of_the_draft_side_calls(sv):
     def draft(**kw):
         a = dict(ok, **kw)
         return L.spec_draft_sample(a["B"], a["V"], a["logits"], a["lstride"], a["T"], a["seed"], a["step"], a["row"], a["ta"], a["sa"],
-                                   a["tb"], a["sb"], a["q"], a["qstride"], None)
+                                   a["tb"], a["sb"], a["q"], a["qstride"], a.get("ws", 1), a.get("ws_bytes", 1 << 20), None)
+    assert sv.spec_draft_sample_workspace_bytes(2) > 0 and sv.spec_draft_sample_workspace_bytes(0) == 0
     for bad in (dict(B=0), dict(V=0), dict(row=-1), dict(row=16), dict(T=0.0), dict(step=1 << 30), dict(logits=None), dict(q=None),
-                dict(ta=None), dict(lstride=9), dict(qstride=9), dict(sa=0)):
+                dict(ta=None), dict(lstride=9), dict(qstride=9), dict(sa=0), dict(ws=None), dict(ws_bytes=8)):
         assert draft(**bad) == sv.SPEC_EINVAL, bad
         assert "spec_draft_sample" in sv.spec_last_error()
     assert L.spec_kv_truncate(None, 1, None, None, -1, None, None) == sv.SPEC_EINVAL
