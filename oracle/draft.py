@@ -25,7 +25,8 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
     A draft that takes hidden states (cfg fuse_hidden) gets pending_hidden [B, P, d]: for each pending token the
     verifier's hidden state of the position before it.  Iterations after the first pair the drafted token with the
     draft's own hidden state of the position before it (the last row of the previous iteration), as EAGLE- and
-    MTP-style drafters chain their predictions.
+    MTP-style drafters chain their predictions.  A draft with cfg fuse_taps = n takes pending_hidden [B, P, n*d], the
+    verifier's multi-layer features, through its w_fc in the first iteration; the chained ones are d wide as before.
 
     Returns (drafts [B, k] int32, q [B, k, V] fp32, kv_ctx grown by the fed positions, new_len [B],
     keys [B, k, 2] = winning and runner-up key of every draw).
@@ -40,8 +41,12 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
     feed = pending
     fused = bool(cfg.get("fuse_hidden", 0))
     feed_hidden = np.asarray(pending_hidden, dtype=np.float64) if fused else None
+    taps = int(cfg.get("fuse_taps", 0)) if fused else 0
     for i in range(k):
-        if fused:
+        if fused and taps and i == 0:
+            logits, new_kv, hid = _forward.verify_forward(cfg, weights, kv, feed, ctx_len, features_in=feed_hidden, return_hidden=True)
+            feed_hidden = hid[:, -1:, :]
+        elif fused:
             logits, new_kv, hid = _forward.verify_forward(cfg, weights, kv, feed, ctx_len, hidden_in=feed_hidden, return_hidden=True)
             feed_hidden = hid[:, -1:, :]
         else:
@@ -72,14 +77,16 @@ def next_pending_hidden(pending_hidden, target_hidden, accept_len):
     return out
 
 
-def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperature, seed, n_steps, pending_hidden=None):
+def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperature, seed, n_steps, pending_hidden=None,
+            tap_layers=None):
     """Several speculation steps in a row (the decode phase of a rollout, Section 2.1-2.2): every step drafts k
     tokens with the draft model, verifies them with the target, keeps the accepted prefix and emits one more
     token, which is the first input of the next step.
 
     kv_t / kv_d: cached context of target (ctx_len[b] positions) and draft (ctx_len[b] - 1 positions: it lacks
     `prev`, the last input the target has cached); t0 [B]: the last emitted token (cached by neither).
-    Random numbers: step s uses counter word `step = s`.
+    Random numbers: step s uses counter word `step = s`.  A draft with fuse_taps is fed the target's features at
+    tap_layers in place of its last hidden state; pending_hidden is then [B, 2, n*d].
 
     Returns (history, kv_t, kv_d, ctx_len) with history[s] = dict(drafts [B,k], accept_len [B], out_tokens [B,k+1]);
     the caches hold what each model keeps after the last step (target: ctx_len positions, draft: ctx_len - 1).
@@ -98,7 +105,9 @@ def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperatur
         drafts, q, kv_d_grown, _, _ = draft_loop(cfg_d, w_d, kv_d, pending, ctx_len - 1, k, temperature, seed, s,
                                                  pending_hidden if fused else None)
         tokens = np.concatenate([t0[:, None], drafts], axis=1).astype(np.int32)
-        if fused:
+        if fused and tap_layers is not None:
+            logits, new_kv, hid_t = _forward.verify_forward(cfg_t, w_t, kv_t, tokens, ctx_len, tap_layers=tap_layers)
+        elif fused:
             logits, new_kv, hid_t = _forward.verify_forward(cfg_t, w_t, kv_t, tokens, ctx_len, return_hidden=True)
         else:
             logits, new_kv = _forward.verify_forward(cfg_t, w_t, kv_t, tokens, ctx_len)

@@ -128,7 +128,7 @@ def matrix(w, key, expert=None):
 
 
 def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden_in=None, return_hidden=False,
-                   kv_scales=None):
+                   kv_scales=None, features_in=None, tap_layers=None):
     """One verify forward.
 
     cfg      dict: n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab,
@@ -147,12 +147,19 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden
     w_fuse . [RMSNorm(embedding) * norm_e ; RMSNorm(hidden_in) * norm_h], hidden_in[b][i] being the hidden state
     of the position before input i.
 
+    Multi-layer features (the EAGLE-3 drafting path, Section 2.3: the draft sees the target's state at several depths,
+    not only the last): tap_layers = (l_1, .., l_n), 1 <= l_i <= n_layers, makes the target also return the residual
+    stream after l_i layers, side by side, [B, k+1, n*d].  A draft with cfg fuse_taps = n holds one more matrix,
+    weights['fuse']['w_fc'] [d, n*d]; given features_in [B, k+1, n*d] it takes hidden_in = w_fc . features_in (no
+    norm before it; the fusion above normalises the product).  Chained draft passes feed hidden_in directly.
+
     8-bit cache (cfg kv_dtype "fp8_e4m3"): kv_scales = (k_scale [L, Hkv], v_scale [L, Hkv]); kv_ctx then holds the
     values the cache returns (decode(code) * scale), and so does new_kv.
 
     Returns (logits [B,k+1,V] fp64, new_kv) with new_kv[layer] = (K [B,k+1,Hkv,dh], V [...]),
     the keys (after rotation) and values of the k+1 input positions as the cache stores them; with return_hidden
-    also the residual stream after the last layer, before the final norm, [B,k+1,d].
+    also the residual stream after the last layer, before the final norm, [B,k+1,d]; with tap_layers, last of
+    all, the features [B,k+1,n*d].
     """
     tokens = np.asarray(tokens)
     B, T = tokens.shape
@@ -165,12 +172,18 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden
     x = embed[tokens.reshape(-1)]                                   # [B*T, d]
     if cfg.get("fuse_hidden", 0):
         f = weights["fuse"]
-        h_in = np.asarray(hidden_in, dtype=np.float64).reshape(B * T, -1)
+        if features_in is not None:
+            assert hidden_in is None and cfg.get("fuse_taps", 0) > 0
+            feats = np.asarray(features_in, dtype=np.float64).reshape(B * T, cfg["fuse_taps"] * cfg["d_model"])
+            h_in = feats @ np.asarray(f["w_fc"], dtype=np.float64).T
+        else:
+            h_in = np.asarray(hidden_in, dtype=np.float64).reshape(B * T, -1)
         both = np.concatenate([rmsnorm(x, f["norm_e"], eps), rmsnorm(h_in, f["norm_h"], eps)], axis=1)
         x = both @ np.asarray(f["w_fuse"], dtype=np.float64).T
     pos = (np.asarray(ctx_len)[:, None] + np.arange(T)[None, :]).reshape(-1)
 
     new_kv = []
+    taps = {}
     for layer in range(cfg["n_layers"]):
         w = weights["layers"][layer]
         h = rmsnorm(x, w["attn_norm"], eps)
@@ -206,13 +219,17 @@ def verify_forward(cfg, weights, kv_ctx, tokens, ctx_len, route_log=None, hidden
             gate = h @ matrix(w, "wg").T
             up = h @ matrix(w, "wu").T
             x = x + (silu(gate) * up) @ matrix(w, "wd").T
+        taps[layer + 1] = x                                         # x is rebound, never updated in place
 
     head = weights.get("head")
     head = embed if head is None else matrix(weights, "head")
     logits = rmsnorm(x, weights["final_norm"], eps) @ head.T
+    out = (logits.reshape(B, T, -1), new_kv)
     if return_hidden:
-        return logits.reshape(B, T, -1), new_kv, x.reshape(B, T, -1).copy()
-    return logits.reshape(B, T, -1), new_kv
+        out += (x.reshape(B, T, -1).copy(),)
+    if tap_layers is not None:
+        out += (np.concatenate([taps[int(l)] for l in tap_layers], axis=1).reshape(B, T, -1),)
+    return out
 
 
 def prefill(cfg, weights, tokens, kv_scales=None):

@@ -51,6 +51,16 @@ MODELS = {
                                    vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1, fuse_hidden=1),
     "draft1l_fused_8b_bf16": dict(n_layers=1, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
                                   vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1, fuse_hidden=1),
+    # The EAGLE-3 input: the verifier's residual stream at three depths, side by side, through w_fc [d, 3d] first.
+    "draft_eagle3_small_bf16": dict(n_layers=1, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1792,
+                                    vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1, fuse_hidden=1,
+                                    fuse_taps=3),
+    "draft1l_eagle3_8b_bf16": dict(n_layers=1, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
+                                   vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1, fuse_hidden=1,
+                                   fuse_taps=3),
+    # A four-layer target for it at the small widths (taps after layers 1, 2 and 4).
+    "small4_bf16": dict(n_layers=4, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1280,
+                        vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0),
     "draft1l_8b_bf16": dict(n_layers=1, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
                             vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1),
 }
@@ -75,6 +85,11 @@ WORKLOADS["draft_pair_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model=
                                               ctx_hi=4096, noise_std=0.0, temperature=1.0)
 WORKLOADS["draft_pair_fused_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model="draft1l_fused_8b_bf16", B=64, k=5,
                                                     ctx_lo=4096, ctx_hi=4096, noise_std=0.0, temperature=1.0)
+WORKLOADS["draft_pair_eagle3_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model="draft1l_eagle3_8b_bf16", B=64, k=5,
+                                                     ctx_lo=4096, ctx_hi=4096, noise_std=0.0, temperature=1.0,
+                                                     tap_layers=(2, 16, 29))
+WORKLOADS["draft_pair_eagle3_small_b5_k4"] = dict(model="small4_bf16", draft_model="draft_eagle3_small_bf16", B=5, k=4, ctx_lo=20,
+                                                  ctx_hi=600, noise_std=0.0, temperature=0.9, tap_layers=(1, 2, 4))
 WORKLOADS["draft_pair_fused_small_b5_k4"] = dict(model="small_bf16", draft_model="draft_fused_small_bf16", B=5, k=4, ctx_lo=20,
                                                  ctx_hi=600, noise_std=0.0, temperature=0.9)
 WORKLOADS["draft_pair_small_b5_k4"] = dict(model="small_bf16", draft_model="draft_small_bf16", B=5, k=4, ctx_lo=20,
@@ -149,6 +164,8 @@ def weight_shapes(cfg):
         out.append(("head", (V, d)))
     if cfg.get("fuse_hidden", 0):      # a draft model that also takes the verifier's hidden states
         out += [("w_fuse", (d, 2 * d)), ("fuse_e_norm", (d,)), ("fuse_h_norm", (d,))]
+        if cfg.get("fuse_taps", 0):    # ... at several depths: their projection down to d channels
+            out += [("w_fc", (d, cfg["fuse_taps"] * d))]
     return out
 
 
@@ -211,6 +228,8 @@ def weights_for_oracle(cfg, weights, library_decode=False, own_decode_layers=(0,
     out.update(scales_of("", ("head",)))
     if cfg.get("fuse_hidden", 0):
         out["fuse"] = {"w_fuse": f("w_fuse"), "norm_e": f("fuse_e_norm"), "norm_h": f("fuse_h_norm")}
+        if cfg.get("fuse_taps", 0):
+            out["fuse"]["w_fc"] = f("w_fc")
     return out
 
 

@@ -37,6 +37,8 @@ def _weights(cfg, seed=0, std=0.3):
     if cfg.get("fuse_hidden", 0):
         out["fuse"] = dict(w_fuse=rng.standard_normal((d, 2 * d)) * std, norm_e=1 + 0.1 * rng.standard_normal(d),
                            norm_h=1 + 0.1 * rng.standard_normal(d))
+        if cfg.get("fuse_taps", 0):
+            out["fuse"]["w_fc"] = rng.standard_normal((d, cfg["fuse_taps"] * d)) * std
     return out
 
 
@@ -230,3 +232,53 @@ def test_fused_draft_loop_chains_its_own_hidden_states():
     assert np.array_equal(new[0, 0], old[0, 1]) and np.array_equal(new[0, 1], H[0, 0])
     assert np.array_equal(new[1, 0], H[1, 1]) and np.array_equal(new[1, 1], H[1, 2])
     assert np.array_equal(new[2, 0], H[2, 2]) and np.array_equal(new[2, 1], H[2, 3])
+
+
+def test_feature_draft_loop_projects_the_first_pass_only_and_the_rollout_carries_features():
+    """The multi-layer-feature draft (EAGLE-3 input): iteration 1 sends the pending tokens' features through w_fc,
+    the chained iterations feed the draft's own d-wide state unprojected.  Checked against the single-state loop fed
+    the projected features by hand (numpy matmul), and the two-model rollout against a step-by-step recomputation
+    that collects the target's taps with separate cut-down models."""
+    cfg = dict(CFG, fuse_hidden=1, fuse_taps=3)
+    w = _weights(cfg, seed=8)
+    d = cfg["d_model"]
+    rng = np.random.default_rng(12)
+    B, C, k, T = 2, 4, 3, 0.8
+    kv = [[(rng.standard_normal((C, 2, 16)), rng.standard_normal((C, 2, 16))) for _ in range(B)] for _ in range(cfg["n_layers"])]
+    pending = rng.integers(0, cfg["vocab"], size=(B, 2)).astype(np.int32)
+    feats = rng.standard_normal((B, 2, 3 * d))
+    drafts, q, _, new_len, _ = od.draft_loop(cfg, w, kv, pending, np.full(B, C), k, T, 31, 2, feats)
+    by_hand = feats @ w["fuse"]["w_fc"].T
+    drafts1, q1, _, new_len1, _ = od.draft_loop(dict(cfg, fuse_taps=0), w, kv, pending, np.full(B, C), k, T, 31, 2, by_hand)
+    assert np.array_equal(drafts, drafts1) and np.max(np.abs(q - q1)) < 1e-7 and list(new_len) == list(new_len1)
+    # two-model rollout: target with 3 layers, taps after layers 1, 3, 2
+    cfg_t = dict(CFG, n_layers=3)
+    w_t = _weights(cfg_t, seed=3)
+    taps = (1, 3, 2)
+    string = rng.integers(0, cfg["vocab"], size=(B, C + 1)).astype(np.int32)
+    _, kv_t0, = of.verify_forward(cfg_t, w_t, [[(np.zeros((0, 2, 16)), np.zeros((0, 2, 16))) for _ in range(B)] for _ in range(3)],
+                                  string[:, :C], np.zeros(B, dtype=int))
+    kv_t = [[(kv_t0[l][0][b], kv_t0[l][1][b]) for b in range(B)] for l in range(3)]
+    kv_d = [[(K[:C - 1], V[:C - 1]) for (K, V) in per] for per in kv]
+    pend = rng.standard_normal((B, 2, 3 * d))
+    hist, _, _, ctx = od.rollout(cfg_t, w_t, cfg, w, kv_t, kv_d, string[:, C - 1], string[:, C], np.full(B, C), k, T, 5, 2,
+                                 pending_hidden=pend, tap_layers=taps)
+    # recomputation of step 0's verify features and step 1's drafts
+    tokens0 = hist[0]["tokens"]
+    cols = []
+    for l in taps:
+        _, _, h = of.verify_forward(dict(cfg_t, n_layers=l), dict(w_t, layers=w_t["layers"][:l]), kv_t[:l], tokens0, np.full(B, C), return_hidden=True)
+        cols.append(h)
+    pend1 = od.next_pending_hidden(pend, np.concatenate(cols, axis=2), hist[0]["accept_len"])
+    n0 = hist[0]["accept_len"]
+    d0, _, kv_d_grown, _, _ = od.draft_loop(cfg, w, kv_d, np.stack([string[:, C - 1], string[:, C]], axis=1), np.full(B, C - 1), k, T, 5, 0, pend)
+    assert np.array_equal(d0, hist[0]["drafts"])
+    kv_d1 = [[(K[:C + int(n0[b])], V[:C + int(n0[b])]) for b, (K, V) in enumerate(per)] for per in kv_d_grown]
+    # (per-sequence lengths differ: one sequence at a time)
+    for b in range(B):
+        one = [[per[b]] for per in kv_d1]
+        pending1 = np.array([[tokens0[b, n0[b]], hist[0]["out_tokens"][b, n0[b]]]])
+        d1, _, _, _, _ = od.draft_loop(cfg, w, one, pending1, np.array([C + int(n0[b])]), k, T, 5, 1, pend1[b:b + 1])
+        # rows of one-sequence calls use random-stream row 0: only sequence 0 is comparable draw for draw
+        if b == 0:
+            assert np.array_equal(d1[0], hist[1]["drafts"][0])

@@ -283,3 +283,49 @@ def test_hidden_state_input_against_torch_composition_and_special_cases():
     assert np.max(np.abs(b1 - b2)) < 1e-10
     c1, _ = of.verify_forward(cfg, w, kv, tokens, ctx_len, hidden_in=hid * 7.0)
     assert np.max(np.abs(c1 - logits)) < 1e-4            # up to the epsilon inside the norm
+
+
+def test_multi_layer_features_taps_and_their_projection():
+    """Features at several depths (the EAGLE-3 input).  Target side: the tap after l layers is the last hidden state
+    of the model cut to l layers (a prefix of a decoder does not see what follows), the tap after all layers is the
+    returned hidden state, and the taps stand side by side in the order asked for.  Draft side: w_fc = [0 | I | 0]
+    picks the middle tap, so the pass equals the single-state one fed that tap; a general w_fc equals the
+    single-state pass fed torch's linear(features, w_fc)."""
+    cfg = dict(CFG, n_layers=3)
+    d = cfg["d_model"]
+    w = _weights(cfg, seed=6)
+    rng = np.random.default_rng(3)
+    ctx_len = np.array([4, 1])
+    kv = _random_ctx(cfg, ctx_len)
+    tokens = rng.integers(0, cfg["vocab"], size=(2, 3)).astype(np.int32)
+    logits, _, hid, feats = of.verify_forward(cfg, w, kv, tokens, ctx_len, return_hidden=True, tap_layers=(1, 3, 2))
+    assert feats.shape == (2, 3, 3 * d)
+    assert np.array_equal(feats[..., d:2 * d], hid)
+    for col, l in ((0, 1), (2, 2)):
+        cut_w = dict(w, layers=w["layers"][:l])
+        _, _, h_cut = of.verify_forward(dict(cfg, n_layers=l), cut_w, kv[:l], tokens, ctx_len, return_hidden=True)
+        assert np.array_equal(feats[..., col * d:(col + 1) * d], h_cut)
+    assert np.max(np.abs(feats[..., :d] - feats[..., 2 * d:])) > 1e-3          # the depths differ
+    logits2, _ = of.verify_forward(cfg, w, kv, tokens, ctx_len)
+    assert np.array_equal(logits, logits2)                                       # asking for taps changes nothing else
+    # draft side
+    cfg_d = dict(CFG, n_layers=1, tied_head=1, fuse_hidden=1, fuse_taps=3)
+    wd_ = _weights(cfg_d, seed=7)
+    assert wd_["fuse"]["w_fc"].shape == (d, 3 * d)
+    kv_d = _random_ctx(cfg_d, ctx_len, seed=5)
+    scaled = feats * 3.0
+    pick = dict(wd_, fuse=dict(wd_["fuse"], w_fc=np.concatenate([np.zeros((d, d)), np.eye(d), np.zeros((d, d))], axis=1)))
+    a, _ = of.verify_forward(cfg_d, pick, kv_d, tokens, ctx_len, features_in=scaled)
+    b, _ = of.verify_forward(cfg_d, pick, kv_d, tokens, ctx_len, hidden_in=scaled[..., d:2 * d])
+    assert np.max(np.abs(a - b)) < 1e-12
+    T64 = lambda x: torch.from_numpy(np.asarray(x, dtype=np.float64))
+    g = F.linear(T64(scaled.reshape(-1, 3 * d)), T64(wd_["fuse"]["w_fc"])).numpy().reshape(2, 3, d)
+    c, _, hc = of.verify_forward(cfg_d, wd_, kv_d, tokens, ctx_len, features_in=scaled, return_hidden=True)
+    e, _, he = of.verify_forward(cfg_d, wd_, kv_d, tokens, ctx_len, hidden_in=g, return_hidden=True)
+    assert np.max(np.abs(c - e)) < 1e-10 and np.max(np.abs(hc - he)) < 1e-10 and np.max(np.abs(c - a)) > 1e-3
+    # every tap reaches the result: zeroing one third of the features changes the logits
+    for col in range(3):
+        z = scaled.copy()
+        z[..., col * d:(col + 1) * d] = 0.0
+        zl, _ = of.verify_forward(cfg_d, wd_, kv_d, tokens, ctx_len, features_in=z)
+        assert np.max(np.abs(zl - c)) > 1e-4
