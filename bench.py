@@ -47,7 +47,9 @@ def run_steps(wl, sv, torch, n_steps, accept_out, step0, marks=None):
             wl.tokens[:, 1:] = draft                             # drafted tokens into the verify input rows
             if ev:
                 ev[1].record()
-        if pair and wl.pending_hidden is not None:            # the draft consumes the target's hidden states: export them
+        if pair and wl.tap_layers:                             # ... at several depths (features)
+            sv.spec_verify_forward_taps(sess.model, sess.kv, B, k, wl.seq_ids, wl.tokens, buf["logits"], wl.tap_layers, wl.target_hidden, ws)
+        elif pair and wl.pending_hidden is not None:          # the draft consumes the target's hidden states: export them
             sv.spec_verify_forward_hidden(sess.model, sess.kv, B, k, wl.seq_ids, wl.tokens, None, buf["logits"], wl.target_hidden, ws)
         else:
             sv.spec_verify_forward(sess.model, sess.kv, B, k, wl.seq_ids, wl.tokens, buf["logits"], ws)
@@ -409,7 +411,7 @@ def main():
         # sustained rollout: consecutive steps, each feeding the next on the device (no cache restore, no host sync)
         from paper_2604_26779_amd.draft import RolloutLoop
         S = args.rollout_steps
-        roll = RolloutLoop(wl.sess, wl.dsess, B, k)
+        roll = RolloutLoop(wl.sess, wl.dsess, B, k, tap_layers=wl.tap_layers)
         acc_s = torch.zeros((S, B), dtype=torch.int32, device="cuda")
         times = []
         for rep in range(2):                      # first repetition warms up

@@ -78,6 +78,8 @@ typedef struct {
     int32_t fuse_hidden;       /* 1: a draft model whose input also takes hidden states (bf16, dense, ffn_dim >= 2 d_model) */
     int32_t kv_dtype;          /* 0: the cache stores `dtype`; SPEC_FP8_E4M3: 8-bit cache with scales (bf16 models) */
     int32_t w_dtype;           /* 0: the matrices are `dtype`; SPEC_FP8_E4M3: 8-bit matrices with one scale per output row */
+    int32_t fuse_taps;         /* 0, or 1..SPEC_MAX_TAPS with fuse_hidden: the hidden-state input can also come as that many
+                                  hidden states side by side (spec_verify_forward_features), projected by w_fc */
 } spec_model_desc;
 
 typedef struct spec_model spec_model;
@@ -85,7 +87,7 @@ typedef struct spec_kv spec_kv;
 typedef struct spec_graph spec_graph;
 
 /* Number of weight pointers spec_model_create expects:
- * 1 + (9 + (n_experts ? 1 : 0))*n_layers + 1 + (tied_head ? 0 : 1) + (fuse_hidden ? 3 : 0)
+ * 1 + (9 + (n_experts ? 1 : 0))*n_layers + 1 + (tied_head ? 0 : 1) + (fuse_hidden ? 3 : 0) + (fuse_taps ? 1 : 0)
  * + (w_dtype == SPEC_FP8_E4M3 ? 7*n_layers + 1 : 0). */
 int32_t spec_model_weight_count(const spec_model_desc* desc);
 
@@ -98,6 +100,7 @@ int32_t spec_model_weight_count(const spec_model_desc* desc);
  *              Fe = expert_ffn_dim), then router [E, d];
  *   final_norm [d]; head [vocab, d] unless tied_head;
  *   with fuse_hidden: w_fuse [d, 2d] (columns 0..d-1 meet the embedding half), fuse_e_norm [d], fuse_h_norm [d];
+ *   with fuse_taps = n: w_fc [d, n*d] (columns j*d .. (j+1)*d-1 meet the j-th hidden state);
  *   with w_dtype = SPEC_FP8_E4M3, after all of the above: the fp32 scales [out_features] of wq, wk, wv, wo, wg, wu, wd
  *   of layer 0, then of layer 1, ..., then of head (the matrices themselves then hold codes, 8-byte aligned).
  * SPEC_F32: the pointers are borrowed for the model's lifetime (kernels read them in place).
@@ -205,6 +208,31 @@ spec_status spec_verify_forward(spec_model* model, spec_kv* kv, int32_t B, int32
 spec_status spec_verify_forward_hidden(spec_model* model, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
                                        const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits,
                                        float* dev_hidden_out, void* dev_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Multi-layer features (the EAGLE-3 drafting path of Section 2.3: the draft is fed the target's state at several
+ * depths instead of the last one only).
+ *
+ * spec_verify_forward_taps: the verify forward of a bf16 model without hidden-state input that also writes
+ * dev_taps_out [B, k+1, n_taps * d_model] fp32: columns j*d .. (j+1)*d-1 of row (b, i) = the residual stream after
+ * host_tap_layers[j] layers (1 .. n_layers; n_layers is what spec_verify_forward_hidden returns; repeats allowed),
+ * 1 <= n_taps <= SPEC_MAX_TAPS.  The array of layers is read during the call only.
+ *
+ * spec_verify_forward_features: the pass of a draft model created with fuse_taps = n whose hidden-state input comes
+ * as features, dev_features_in [B, k+1, n * d_model] fp32 (row i: the target's taps of the position before input
+ * row i, as spec_verify_forward_taps wrote them): the hidden state the fusion sees is w_fc . features (no norm before
+ * it).  Everything else as spec_verify_forward_hidden, which the same model still takes for passes that chain its own
+ * d_model-wide state.  spec_next_step_hidden and spec_rollout_pending_hidden carry features when given d = n * d_model.
+ * Errors as spec_verify_forward; SPEC_EINVAL for a tap out of range or a model of the wrong kind.
+ */
+#define SPEC_MAX_TAPS 4
+spec_status spec_verify_forward_taps(spec_model* model, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                     const int32_t* dev_tokens, float* dev_logits, int32_t n_taps,
+                                     const int32_t* host_tap_layers, float* dev_taps_out, void* dev_workspace,
+                                     size_t workspace_bytes, void* stream);
+spec_status spec_verify_forward_features(spec_model* model, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                         const int32_t* dev_tokens, const float* dev_features_in, float* dev_logits,
+                                         float* dev_hidden_out, void* dev_workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Lossless rejection sampling (the rejection procedure of Section 2.1; acceptance length as in

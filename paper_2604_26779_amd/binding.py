@@ -23,7 +23,7 @@ EXPORTS = [
     "spec_last_error", "spec_model_weight_count", "spec_model_create", "spec_model_destroy", "spec_kv_pool_bytes",
     "spec_kv_alloc", "spec_kv_free", "spec_kv_set_scales", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
-    "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample", "spec_reject_sample_static",
+    "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_verify_forward_taps", "spec_verify_forward_features", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample", "spec_reject_sample_static",
     "spec_commit_kv", "spec_draft_sample", "spec_draft_sample_workspace_bytes", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_rollout_pending", "spec_rollout_pending_hidden", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_graph_capture_begin", "spec_graph_capture_end", "spec_graph_launch",
     "spec_graph_destroy", "spec_calib_read", "spec_calib_copy",
@@ -41,7 +41,8 @@ class spec_model_desc(ctypes.Structure):
                                               "ffn_dim", "vocab")] + \
                [("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("dtype", ctypes.c_int32),
                 ("tied_head", ctypes.c_int32), ("n_experts", ctypes.c_int32), ("top_k", ctypes.c_int32),
-                ("expert_ffn_dim", ctypes.c_int32), ("fuse_hidden", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("w_dtype", ctypes.c_int32)]
+                ("expert_ffn_dim", ctypes.c_int32), ("fuse_hidden", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("w_dtype", ctypes.c_int32),
+                ("fuse_taps", ctypes.c_int32)]
 
 
 _lib = None
@@ -77,6 +78,8 @@ def lib():
             "spec_verify_workspace_bytes": (sz, [vp, vp, i32, i32]),
             "spec_verify_forward": (i32, [vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]),
             "spec_verify_forward_hidden": (i32, [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]),
+            "spec_verify_forward_taps": (i32, [vp, vp, i32, i32, vp, vp, vp, i32, vp, vp, vp, sz, vp]),
+            "spec_verify_forward_features": (i32, [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]),
             "spec_next_step_hidden": (i32, [i32, i32, i32, vp, vp, vp, vp]),
             "spec_sample_workspace_bytes": (sz, [i32, i32]),
             "spec_reject_sample": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp, sz, vp]),
@@ -152,6 +155,7 @@ def make_desc(cfg):
     d.tied_head = int(cfg.get("tied_head", 0))
     d.n_experts, d.top_k, d.expert_ffn_dim = (int(cfg.get(n, 0)) for n in ("n_experts", "top_k", "expert_ffn_dim"))
     d.fuse_hidden = int(cfg.get("fuse_hidden", 0))
+    d.fuse_taps = int(cfg.get("fuse_taps", 0))
     d.kv_dtype = {None: 0, "fp8_e4m3": SPEC_FP8_E4M3}[cfg.get("kv_dtype")]
     d.w_dtype = {None: 0, "fp8_e4m3": SPEC_FP8_E4M3}[cfg.get("w_dtype")]
     return d
@@ -250,6 +254,21 @@ def spec_verify_forward_hidden(model, kv, B, k, seq_ids, tokens, hidden_in, logi
     _check(lib().spec_verify_forward_hidden(model, kv, B, k, _ptr(seq_ids), _ptr(tokens), _ptr(hidden_in), _ptr(logits),
                                             _ptr(hidden_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _stream(stream)))
+
+
+def spec_verify_forward_taps(model, kv, B, k, seq_ids, tokens, logits, tap_layers, taps_out, workspace, stream=None):
+    """tap_layers: host sequence of layer counts; taps_out [B, k+1, len(tap_layers) * d] fp32 device tensor."""
+    layers = (ctypes.c_int32 * len(tap_layers))(*[int(l) for l in tap_layers])
+    _check(lib().spec_verify_forward_taps(model, kv, B, k, _ptr(seq_ids), _ptr(tokens), _ptr(logits), len(tap_layers),
+                                          ctypes.cast(layers, ctypes.c_void_p), _ptr(taps_out), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def spec_verify_forward_features(model, kv, B, k, seq_ids, tokens, features_in, logits, hidden_out, workspace, stream=None):
+    """features_in [B, k+1, fuse_taps * d], hidden_out [B, k+1, d] or None: fp32 device tensors."""
+    _check(lib().spec_verify_forward_features(model, kv, B, k, _ptr(seq_ids), _ptr(tokens), _ptr(features_in), _ptr(logits),
+                                              _ptr(hidden_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                              _stream(stream)))
 
 
 def spec_next_step_hidden(B, k, d, target_hidden, accept_len, pending_hidden, stream=None):

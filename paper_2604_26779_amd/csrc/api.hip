@@ -138,7 +138,7 @@ extern "C" int32_t spec_tune_get(const char* name)
 extern "C" int32_t spec_model_weight_count(const spec_model_desc* d)
 {
     if (!d || d->n_layers < 0) return -1;
-    return 1 + (9 + (d->n_experts > 0 ? 1 : 0)) * d->n_layers + 1 + (d->tied_head ? 0 : 1) + (d->fuse_hidden ? 3 : 0) +
+    return 1 + (9 + (d->n_experts > 0 ? 1 : 0)) * d->n_layers + 1 + (d->tied_head ? 0 : 1) + (d->fuse_hidden ? 3 : 0) + (d->fuse_taps ? 1 : 0) +
            (d->w_dtype == SPEC_FP8_E4M3 ? 7 * d->n_layers + 1 : 0);
 }
 
@@ -172,6 +172,10 @@ static spec_status check_desc(const spec_model_desc& d)
             set_error("spec_model_create: a model with hidden-state input must be bf16, dense, with ffn_dim >= 2 * d_model");
             return SPEC_EUNSUPPORTED;
         }
+    }
+    if (d.fuse_taps < 0 || d.fuse_taps > SPEC_MAX_TAPS || (d.fuse_taps && !d.fuse_hidden)) {
+        set_error("spec_model_create: fuse_taps must be 0 .. %d and needs fuse_hidden", SPEC_MAX_TAPS);
+        return SPEC_EINVAL;
     }
     if (d.dtype == SPEC_BF16) {
         if (d.head_dim != 128 || d.d_model % 256 || d.ffn_dim % 256) {
@@ -274,6 +278,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         else elems += (size_t)L * (bf16_packed_elems(2 * F, D) + bf16_packed_elems(D, F));
         elems += bf16_packed_elems(d.vocab, D);
         if (d.fuse_hidden) elems += bf16_packed_elems(D, 2 * D);
+        if (d.fuse_taps) elems += bf16_packed_elems(D, d.fuse_taps * D);
         m->arena_bytes = elems * sizeof(bf16_t);
         hipError_t e = hipMalloc(&m->arena, m->arena_bytes);
         if (e != hipSuccess) {
@@ -315,6 +320,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         }
         if (st == SPEC_OK) st = pack({m->head_w()}, {d.vocab}, D, &m->head, f16_mask & 8);
         if (st == SPEC_OK && d.fuse_hidden) st = pack({m->fuse_w(0)}, {D}, 2 * D, &m->wfuse, false);
+        if (st == SPEC_OK && d.fuse_taps) st = pack({m->fuse_w(3)}, {D}, d.fuse_taps * D, &m->wfc, false);
         if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }
         if (st != SPEC_OK) { (void)hipFree(m->arena); delete m; return st; }
     }
@@ -547,10 +553,12 @@ extern "C" size_t spec_verify_workspace_bytes(const spec_model* m, const spec_kv
     return m->desc.dtype == SPEC_F32 ? f32_workspace_bytes(m->desc, B, k) : bf16_workspace_bytes(m, kv, B, k);
 }
 
-extern "C" spec_status spec_verify_forward_hidden(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
-                                                  const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits,
-                                                  float* dev_hidden_out, void* ws, size_t ws_bytes, void* stream)
+static spec_status verify_forward_any(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                      const int32_t* dev_tokens, const Bf16Extras& io, float* dev_logits,
+                                      void* ws, size_t ws_bytes, void* stream)
 {
+    const float* dev_hidden_in = io.dev_hidden_in ? io.dev_hidden_in : io.dev_features_in;
+    float* dev_hidden_out = io.dev_hidden_out ? io.dev_hidden_out : io.dev_taps_out;
     if (!m || !kv || !dev_seq_ids || !dev_tokens || !dev_logits || !ws) { set_error("spec_verify_forward: null pointer"); return SPEC_EINVAL; }
     if (kv->model != m) { set_error("spec_verify_forward: the cache belongs to another model"); return SPEC_EINVAL; }
     if ((m->desc.fuse_hidden != 0) != (dev_hidden_in != nullptr)) {
@@ -585,8 +593,50 @@ extern "C" spec_status spec_verify_forward_hidden(spec_model* m, spec_kv* kv, in
     prof_mark(PC_KV_RESERVE, s);
     kv->device_ahead = true;
     st = m->desc.dtype == SPEC_F32 ? f32_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_logits, ws, s)
-                                   : bf16_forward(m, kv, B, k, dev_seq_ids, dev_tokens, dev_hidden_in, dev_logits, dev_hidden_out, ws, ws_bytes, s);
+                                   : bf16_forward(m, kv, B, k, dev_seq_ids, dev_tokens, io, dev_logits, ws, ws_bytes, s);
     return st;
+}
+
+extern "C" spec_status spec_verify_forward_hidden(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                                  const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits,
+                                                  float* dev_hidden_out, void* ws, size_t ws_bytes, void* stream)
+{
+    Bf16Extras io;
+    io.dev_hidden_in = dev_hidden_in;
+    io.dev_hidden_out = dev_hidden_out;
+    return verify_forward_any(m, kv, B, k, dev_seq_ids, dev_tokens, io, dev_logits, ws, ws_bytes, stream);
+}
+
+extern "C" spec_status spec_verify_forward_taps(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                                const int32_t* dev_tokens, float* dev_logits, int32_t n_taps,
+                                                const int32_t* host_tap_layers, float* dev_taps_out, void* ws, size_t ws_bytes,
+                                                void* stream)
+{
+    if (!m || !host_tap_layers || !dev_taps_out) { set_error("spec_verify_forward_taps: null pointer"); return SPEC_EINVAL; }
+    if (n_taps < 1 || n_taps > SPEC_MAX_TAPS) { set_error("spec_verify_forward_taps: n_taps must be 1 .. %d", SPEC_MAX_TAPS); return SPEC_EINVAL; }
+    Bf16Extras io;
+    io.n_taps = n_taps;
+    for (int j = 0; j < n_taps; ++j) {
+        if (host_tap_layers[j] < 1 || host_tap_layers[j] > m->desc.n_layers) {
+            set_error("spec_verify_forward_taps: tap %d asks for the state after %d layers; the model has %d", j, host_tap_layers[j], m->desc.n_layers);
+            return SPEC_EINVAL;
+        }
+        io.tap_layers[j] = host_tap_layers[j];
+    }
+    io.dev_taps_out = dev_taps_out;
+    return verify_forward_any(m, kv, B, k, dev_seq_ids, dev_tokens, io, dev_logits, ws, ws_bytes, stream);
+}
+
+extern "C" spec_status spec_verify_forward_features(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
+                                                    const int32_t* dev_tokens, const float* dev_features_in, float* dev_logits,
+                                                    float* dev_hidden_out, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!m || !dev_features_in) { set_error("spec_verify_forward_features: null pointer"); return SPEC_EINVAL; }
+    if (!m->desc.fuse_taps) { set_error("spec_verify_forward_features: the model was not created with fuse_taps"); return SPEC_EINVAL; }
+    Bf16Extras io;
+    io.dev_features_in = dev_features_in;
+    io.dev_hidden_out = dev_hidden_out;
+    return verify_forward_any(m, kv, B, k, dev_seq_ids, dev_tokens, io, dev_logits, ws, ws_bytes, stream);
 }
 
 extern "C" spec_status spec_verify_forward(spec_model* m, spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,

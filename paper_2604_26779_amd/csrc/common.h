@@ -90,14 +90,14 @@ struct spec_model {
     std::vector<specv::PackedW> wqkv, wo, wgu, wd;   // mixture of experts: wgu / wd describe expert 0, the
     std::vector<specv::PackedW> router;              // others follow at moe_gu_stride / moe_d_stride elements
     int64_t moe_gu_stride = 0, moe_d_stride = 0;
-    specv::PackedW head, wfuse;
+    specv::PackedW head, wfuse, wfc;
     bool moe() const { return desc.n_experts > 0; }
     int per_layer() const { return moe() ? 10 : 9; }
     const void* embed() const { return w[0]; }
     const void* layer_w(int l, int i) const { return w[1 + per_layer() * l + i]; }   // i: 0 attn_norm .. 8 wd, 9 router
     const void* final_norm() const { return w[1 + per_layer() * desc.n_layers]; }
     const void* head_w() const { return desc.tied_head ? w[0] : w[2 + per_layer() * desc.n_layers]; }
-    // fuse_hidden: w_fuse, fuse_e_norm, fuse_h_norm follow the head
+    // fuse_hidden: w_fuse, fuse_e_norm, fuse_h_norm follow the head; fuse_taps: then w_fc
     const void* fuse_w(int i) const { return w[2 + per_layer() * desc.n_layers + (desc.tied_head ? 0 : 1) + i]; }
     // 8-bit weights (dense, untied head): the scales follow everything else, 7 per layer in matrix order
     // (wq wk wv wo wg wu wd), then the head's
@@ -169,8 +169,18 @@ size_t w8_packed_bytes(int N, int K);
 spec_status w8_pack_matrix(const unsigned char* const* dev_parts, const float* const* dev_scales, const int* part_rows, int n_parts,
                            int K, void* dev_out, PackedW* out, bool interleave, bool x_f16, hipStream_t s);
 size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k);
+// hidden-state input: dev_hidden_in [M, d], or dev_features_in [M, fuse_taps * d] (one of them, models with fuse_hidden);
+// outputs besides the logits: dev_hidden_out [M, d] and/or dev_taps_out [M, n_taps * d] after tap_layers[j] layers
+struct Bf16Extras {
+    const float* dev_hidden_in = nullptr;
+    const float* dev_features_in = nullptr;
+    float* dev_hidden_out = nullptr;
+    int n_taps = 0;
+    int tap_layers[SPEC_MAX_TAPS] = {0, 0, 0, 0};
+    float* dev_taps_out = nullptr;
+};
 spec_status bf16_forward(spec_model* m, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids,
-                         const int32_t* dev_tokens, const float* dev_hidden_in, float* dev_logits, float* dev_hidden_out,
+                         const int32_t* dev_tokens, const Bf16Extras& io, float* dev_logits,
                          void* ws, size_t ws_bytes, hipStream_t s);
 
 // in-block layouts of the cache, by storage type (host + device)

@@ -122,8 +122,10 @@ __global__ __launch_bounds__(512) void residual_rmsnorm_kernel(
 
 // Input of a draft model that also takes hidden states: the operand of the fusion projection,
 // [RMSNorm(embed[token]) * g_e ; RMSNorm(hidden_in[m]) * g_h] (2d channels), as hi + lo bf16.  One workgroup per row.
+// hidden_in may come as h_splits partial sums h_split_stride floats apart (the K-split output of the feature projection).
 __global__ __launch_bounds__(512) void fuse_input_kernel(
     const int32_t* __restrict__ tokens, const unsigned short* __restrict__ embed, int vocab, const float* __restrict__ hidden_in,
+    int h_splits, int64_t h_split_stride,
     const unsigned short* __restrict__ gain_e, const unsigned short* __restrict__ gain_h, int d, float eps, int mb_pad,
     uint4* __restrict__ xp)
 {
@@ -141,6 +143,11 @@ __global__ __launch_bounds__(512) void fuse_input_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) { float lo = from_bf16(w[j] & 0xffff), hi = from_bf16(w[j] >> 16); ss_e += lo * lo + hi * hi; }
         float4 a = *(const float4*)(hr + c), b = *(const float4*)(hr + c + 4);
+        for (int sp = 1; sp < h_splits; ++sp) {
+            float4 a2 = *(const float4*)(hr + sp * h_split_stride + c), b2 = *(const float4*)(hr + sp * h_split_stride + c + 4);
+            a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+            b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
+        }
         ss_h += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
     }
     const float re = 1.0f / sqrtf(block_sum(ss_e, lds16) / (float)d + eps);
@@ -149,6 +156,11 @@ __global__ __launch_bounds__(512) void fuse_input_kernel(
         uint4 e = *(const uint4*)(er + c), ge = *(const uint4*)(gain_e + c), gh = *(const uint4*)(gain_h + c);
         unsigned int w[4] = {e.x, e.y, e.z, e.w}, g1[4] = {ge.x, ge.y, ge.z, ge.w}, g2[4] = {gh.x, gh.y, gh.z, gh.w};
         float4 a = *(const float4*)(hr + c), b = *(const float4*)(hr + c + 4);
+        for (int sp = 1; sp < h_splits; ++sp) {               // the same sums, in the same order, as in the first sweep
+            float4 a2 = *(const float4*)(hr + sp * h_split_stride + c), b2 = *(const float4*)(hr + sp * h_split_stride + c + 4);
+            a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+            b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
+        }
         float hv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
         float ve[8], vh[8];
 #pragma unroll
@@ -311,11 +323,33 @@ __global__ void swiglu_pack_kernel(const float* __restrict__ part, int splits, i
     xp_store8_rt(xp, xf, m, f, mb_pad, v);
 }
 
+// fp32 rows [M, K] -> the hi + lo operand of a projection, unchanged in value (the multi-layer features before w_fc)
+__global__ __launch_bounds__(256) void pack_rows_kernel(const float* __restrict__ src, int M, int K, int mb_pad, uint4* __restrict__ xp)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int per_row = K / 8;
+    if (i >= (int64_t)M * per_row) return;
+    const int m = (int)(i / per_row), c = (int)(i % per_row) * 8;
+    const float4 a = *(const float4*)(src + (int64_t)m * K + c), b = *(const float4*)(src + (int64_t)m * K + c + 4);
+    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    xp_store8(xp, m, c, mb_pad, v);
+}
+
+// the residual stream [M, d] into columns col0 .. col0+d-1 of the feature rows [M, width]
+__global__ __launch_bounds__(256) void tap_copy_kernel(const float* __restrict__ x, int M, int d, float* __restrict__ taps, int width, int col0)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int per_row = d / 4;
+    if (i >= (int64_t)M * per_row) return;
+    const int m = (int)(i / per_row), c = (int)(i % per_row) * 4;
+    *(float4*)(taps + (int64_t)m * width + col0 + c) = *(const float4*)(x + (int64_t)m * d + c);
+}
+
 // ------------------------------------------------------------------ host side
 struct Bf16Plan {
     int M, mb_pad, max_chunks, RBrows;
     bool fuse_swiglu;
-    int s_qkv, s_o, s_gu, s_down, s_head, s_fuse;
+    int s_qkv, s_o, s_gu, s_down, s_head, s_fuse, s_fc;
     size_t off_x, off_xp_h, off_xp_a, off_xp_f, off_part, off_q, off_rope, off_att_o, off_att_ml, total;
     int max_items;                          // attention work items the buffers hold
     size_t off_row_slot, off_items, off_entry_items;
@@ -343,6 +377,7 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.s_down = moe ? 1 : gemm_pick_splits(m->wd[0], p.M, tune("splits_down"));
     p.s_head = 1;
     p.s_fuse = d.fuse_hidden ? gemm_pick_splits(m->wfuse, p.M, 0) : 0;
+    p.s_fc = d.fuse_taps ? gemm_pick_splits(m->wfc, p.M, 0) : 0;
     p.s_router = moe ? gemm_pick_splits(m->router[0], p.M, 0) : 0;
     p.moe_rows = moe ? moe_rows_bound(p.M, d.top_k, d.n_experts) : 0;
     int D = d.d_model, F = moe ? d.expert_ffn_dim : d.ffn_dim, nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
@@ -352,10 +387,11 @@ static Bf16Plan make_plan(const spec_model* m, int B, int k, int64_t max_ctx_plu
     p.off_x = take((size_t)p.M * D * 4);
     p.off_xp_h = take(rows * D * 4);          // hi + lo
     p.off_xp_a = take(rows * nq * 4);
-    p.off_xp_f = take((moe ? (size_t)p.moe_rows : rows) * F * 4);     // mixture: the permuted rows' silu(gate)*up
+    // (mixture: the permuted rows' silu(gate)*up; a feature-fed draft stages its features here first)
+    p.off_xp_f = take((moe ? (size_t)p.moe_rows : rows) * (size_t)std::max(F, d.fuse_taps * D) * 4);
     size_t part = std::max(std::max((size_t)p.s_qkv * nqkv, (size_t)p.s_o * D), std::max((size_t)p.s_gu * 2 * F, (size_t)p.s_down * D));
     if (moe) part = std::max(std::max((size_t)p.s_qkv * nqkv, (size_t)p.s_o * D), (size_t)p.s_router * d.n_experts);
-    part = std::max(part, (size_t)p.s_fuse * D);
+    part = std::max(part, (size_t)std::max(p.s_fuse, p.s_fc) * D);
     p.off_part = take(part * p.M * 4);
     if (moe) {
         size_t pairs = (size_t)p.M * d.top_k;
@@ -386,9 +422,10 @@ size_t bf16_workspace_bytes(const spec_model* m, const spec_kv* kv, int B, int k
 }
 
 spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32_t* dev_seq_ids, const int32_t* dev_tokens,
-                         const float* dev_hidden_in, float* dev_logits, float* dev_hidden_out, void* ws, size_t ws_bytes, hipStream_t s)
+                         const Bf16Extras& io, float* dev_logits, void* ws, size_t ws_bytes, hipStream_t s)
 {
     const spec_model_desc& d = mdl->desc;
+    float* const dev_hidden_out = io.dev_hidden_out;
     const int T = k + 1, G = d.n_q_heads / d.n_kv_heads;
     if (T * G > 256) { set_error("bf16 path: (k+1) * (query heads per kv head) = %d exceeds 256", T * G); return SPEC_EUNSUPPORTED; }
     // the workspace is laid out for the longest context the cache allows; the launch only spans
@@ -427,7 +464,17 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
     if ((st = launch_attention_plan(B, T, G, Hkv, view, live_pages, att_items, att_entry_items, s)) != SPEC_OK) return st;
     if (d.fuse_hidden) {
         // hidden-state input: x = w_fuse . [RMSNorm(embed) ; RMSNorm(hidden_in)] (the feed-forward operand buffer is free here)
-        fuse_input_kernel<<<M, norm_threads, 0, s>>>(dev_tokens, (const unsigned short*)mdl->embed(), d.vocab, dev_hidden_in,
+        const float* hidden = io.dev_hidden_in;
+        int h_splits = 1;
+        if (io.dev_features_in) {
+            // multi-layer features: hidden = w_fc . features, left as K-split partial sums for the kernel below
+            const int Kf = d.fuse_taps * D;
+            pack_rows_kernel<<<(unsigned)cdiv((int64_t)M * (Kf / 8), 256), 256, 0, s>>>(io.dev_features_in, M, Kf, p.mb_pad, (uint4*)xp_f);
+            if ((st = launch_gemm_bf16(mdl->wfc, xp_f, M, part, D, p.s_fc, false, s)) != SPEC_OK) return st;
+            hidden = part;
+            h_splits = p.s_fc;
+        }
+        fuse_input_kernel<<<M, norm_threads, 0, s>>>(dev_tokens, (const unsigned short*)mdl->embed(), d.vocab, hidden, h_splits, (int64_t)M * D,
                                                      (const unsigned short*)mdl->fuse_w(1), (const unsigned short*)mdl->fuse_w(2), D, d.rms_eps,
                                                      p.mb_pad, (uint4*)xp_f);
         if ((st = launch_gemm_bf16(mdl->wfuse, xp_f, M, part, D, p.s_fuse, false, s)) != SPEC_OK) return st;
@@ -438,6 +485,12 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
                                                         (const unsigned short*)mdl->layer_w(0, 0), D, d.rms_eps, p.mb_pad, xf_of(mdl->wqkv[0]), (uint4*)xp_h);
     }
     prof_mark(PC_EMBED_NORM, s);
+    // the residual stream after `done` layers into every feature column block that asks for it
+    auto write_taps = [&](int done) {
+        for (int j = 0; j < io.n_taps; ++j)
+            if (io.tap_layers[j] == done)
+                tap_copy_kernel<<<(unsigned)cdiv((int64_t)M * (D / 4), 256), 256, 0, s>>>(x, M, D, io.dev_taps_out, io.n_taps * D, j * D);
+    };
     for (int l = 0; l < d.n_layers; ++l) {
         int lp = kv->alias_mod > 0 ? l % kv->alias_mod : l;
         if ((st = launch_gemm_bf16(mdl->wqkv[l], xp_h, M, part, nqkv, p.s_qkv, false, s)) != SPEC_OK) return st;
@@ -480,6 +533,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
             prof_mark(PC_GEMM_DOWN, s);
             if ((st = launch_moe_combine_norm(x, y_e, pair_row, wts, M, d.top_k, next_gain, D, d.rms_eps, p.mb_pad, next_xf, xp_h, s)) != SPEC_OK) return st;
             prof_mark(PC_RESID_NORM, s);
+            write_taps(l + 1);
             continue;
         }
         if (p.fuse_swiglu) {
@@ -497,6 +551,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
         residual_rmsnorm_kernel<RES_ADD><<<M, norm_threads, 0, s>>>(x, part, p.s_down, (int64_t)M * D, nullptr, nullptr, 0,
                                                          (const unsigned short*)next_gain, D, d.rms_eps, p.mb_pad, next_xf, (uint4*)xp_h);
         prof_mark(PC_RESID_NORM, s);
+        write_taps(l + 1);
     }
     if (dev_hidden_out) {
         // the residual stream after the last layer: what a hidden-state-consuming draft model is fed

@@ -20,6 +20,8 @@ class DraftLoop:
         self.sample_ws = torch.empty(sv.spec_draft_sample_workspace_bytes(B), dtype=torch.uint8, device=dev)
         # a draft that takes hidden states chains its own: the last row of a pass feeds the next pass
         self.fused = bool(draft_session.cfg.get("fuse_hidden", 0))
+        # ... and may take the verifier's states at several depths (features, n * d wide) on the first pass of a step
+        self.taps = int(draft_session.cfg.get("fuse_taps", 0)) if self.fused else 0
         d = draft_session.cfg["d_model"]
         self.hid_first = None                                               # [B, P, d], allocated on first use
         self.hid = [torch.zeros((B, 1, d), dtype=torch.float32, device=dev) for _ in range(2)] if self.fused else None
@@ -27,7 +29,7 @@ class DraftLoop:
     def run(self, seq_ids, pending, q_out, temperature, seed, step, stream=None, pending_hidden=None):
         """pending [B, P] int32 (tokens the draft's cache lacks; P = 2 in steady state), q_out [B, k, V] fp32;
         pending_hidden [B, P, d] fp32 for a draft with hidden-state input (the verifier's hidden state of the position
-        before each pending token).
+        before each pending token; [B, P, n * d] features for a draft with fuse_taps = n).
 
         Fills self.drafts [B, k] and q_out; the draft's cache grows by P + k - 1 positions."""
         sess, B, k = self.sess, self.B, self.k
@@ -41,7 +43,10 @@ class DraftLoop:
         for i in range(k):
             if i == 0:
                 if self.fused:
-                    logits = sess.forward(seq_ids, pending, stream, hidden_in=pending_hidden, hidden_out=self.hid_first)
+                    if self.taps:
+                        logits = sess.forward(seq_ids, pending, stream, features_in=pending_hidden, hidden_out=self.hid_first)
+                    else:
+                        logits = sess.forward(seq_ids, pending, stream, hidden_in=pending_hidden, hidden_out=self.hid_first)
                     self.hid[0].copy_(self.hid_first[:, P - 1:P, :])
                 else:
                     logits = sess.forward(seq_ids, pending, stream)                      # [B, P, V]
@@ -79,7 +84,8 @@ class RolloutLoop:
     rejection sampling -> commit -> roll-back of the draft's cache -> next step's inputs.  Only call order and
     buffers are handled here."""
 
-    def __init__(self, target_session, draft_session, B, k):
+    def __init__(self, target_session, draft_session, B, k, tap_layers=None):
+        """tap_layers: for a draft with fuse_taps, the target layers whose output it is fed."""
         self.t, self.B, self.k = target_session, int(B), int(k)
         self.loop = DraftLoop(draft_session, B, k)
         dev = target_session.device
@@ -88,8 +94,11 @@ class RolloutLoop:
         self.pending = torch.zeros((B, 2), dtype=torch.int32, device=dev)
         self.q = torch.zeros((B, k, V), dtype=torch.float32, device=dev)
         self.fused = self.loop.fused
+        self.tap_layers = tuple(int(l) for l in tap_layers) if self.loop.taps else None
+        assert not self.loop.taps or len(self.tap_layers) == self.loop.taps
         if self.fused:
-            d = target_session.cfg["d_model"]
+            d = target_session.cfg["d_model"] * max(1, self.loop.taps)
+            self.hidden_width = d
             self.pending_hidden = torch.zeros((B, 2, d), dtype=torch.float32, device=dev)
             self.target_hidden = torch.zeros((B, k + 1, d), dtype=torch.float32, device=dev)
 
@@ -117,7 +126,10 @@ class RolloutLoop:
             self.tokens[:, 1:] = drafts
             acc = accept_out[s] if accept_out is not None else buf["accept_len"]
             out = tokens_out[s] if tokens_out is not None else buf["out_tokens"]
-            if self.fused:
+            if self.tap_layers:
+                sv.spec_verify_forward_taps(t.model, t.kv, B, k, seq_ids, self.tokens, buf["logits"], self.tap_layers,
+                                            self.target_hidden, ws, stream)
+            elif self.fused:
                 sv.spec_verify_forward_hidden(t.model, t.kv, B, k, seq_ids, self.tokens, None, buf["logits"], self.target_hidden,
                                               ws, stream)
             else:
@@ -128,7 +140,7 @@ class RolloutLoop:
             self.loop.roll_back(seq_ids, buf["new_ctx_len"], stream)
             sv.spec_next_step_inputs(B, k, self.tokens, out, acc, self.pending, stream)
             if self.fused:
-                sv.spec_next_step_hidden(B, k, t.cfg["d_model"], self.target_hidden, acc, self.pending_hidden, stream)
+                sv.spec_next_step_hidden(B, k, self.hidden_width, self.target_hidden, acc, self.pending_hidden, stream)
 
 
 class NgramRollout:
@@ -232,15 +244,19 @@ class ContinuousPairRollout:
     array; waiting sequences are prefilled in both caches (the draft's one position behind the verifier's).  Only call
     order and buffers are handled here."""
 
-    def __init__(self, target_session, draft_session, B, k, slot_seq, target_len, queue, prev_token, first_token, seq_hidden=None):
+    def __init__(self, target_session, draft_session, B, k, slot_seq, target_len, queue, prev_token, first_token, seq_hidden=None,
+                 tap_layers=None):
         """seq_hidden [n_seqs, 2, d] fp32: for a draft with hidden-state input, every sequence's own pair of verifier
-        hidden states (the positions before its last prompt token and before its first input)."""
+        hidden states (the positions before its last prompt token and before its first input); for a draft with
+        fuse_taps = n they are features, [n_seqs, 2, n * d], and tap_layers names the n target layers."""
         self.t, self.d, self.B, self.k = target_session, draft_session, int(B), int(k)
         dev = target_session.device
         n_seqs = int(target_len.shape[0])
         self.loop = DraftLoop(draft_session, B, k)
         self.fused = self.loop.fused
         assert not self.fused or seq_hidden is not None, "a draft with hidden-state input needs every sequence's own pair of hidden states"
+        self.tap_layers = tuple(int(l) for l in tap_layers) if self.loop.taps else None
+        assert not self.loop.taps or len(self.tap_layers) == self.loop.taps
         self.slot_seq = slot_seq.to(dev, torch.int32).clone()
         self.slot_seq_before = self.slot_seq.clone()
         self.target_len = target_len.to(dev, torch.int32)
@@ -261,7 +277,8 @@ class ContinuousPairRollout:
         self.pending[:, 0] = self.prev_token[idx]
         self.pending[:, 1] = self.first_token[idx]
         if self.fused:
-            d = target_session.cfg["d_model"]
+            d = target_session.cfg["d_model"] * max(1, self.loop.taps)
+            self.hidden_width = d
             self.seq_hidden = seq_hidden.to(dev, torch.float32).contiguous()
             self.pending_hidden = self.seq_hidden[idx].contiguous()
             self.target_hidden = torch.zeros((B, k + 1, d), dtype=torch.float32, device=dev)
@@ -281,7 +298,10 @@ class ContinuousPairRollout:
             drafts = self.loop.run(self.slot_seq, self.pending, self.q, temperature, seed, step0 + s, stream,
                                    self.pending_hidden if self.fused else None)
             self.tokens[:, 1:] = drafts
-            if self.fused:
+            if self.tap_layers:
+                sv.spec_verify_forward_taps(t.model, t.kv, B, k, self.slot_seq, self.tokens, buf["logits"], self.tap_layers,
+                                            self.target_hidden, ws, stream)
+            elif self.fused:
                 sv.spec_verify_forward_hidden(t.model, t.kv, B, k, self.slot_seq, self.tokens, None, buf["logits"], self.target_hidden,
                                               ws, stream)
             else:
@@ -292,7 +312,7 @@ class ContinuousPairRollout:
             self.loop.roll_back(self.slot_seq, buf["new_ctx_len"], stream)
             sv.spec_next_step_inputs(B, k, self.tokens, out, acc, self.pending, stream)
             if self.fused:
-                sv.spec_next_step_hidden(B, k, t.cfg["d_model"], self.target_hidden, acc, self.pending_hidden, stream)
+                sv.spec_next_step_hidden(B, k, self.hidden_width, self.target_hidden, acc, self.pending_hidden, stream)
             self.slot_seq_before.copy_(self.slot_seq)
             sv.spec_rollout_retire(B, k, self.slot_seq, self.active, acc, self.gen_len, self.target_len, self.queue,
                                    self.queue_head, self.first_token, self.tokens, self.release_seq, self.keep_len,

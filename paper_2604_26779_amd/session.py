@@ -110,14 +110,23 @@ class VerifySession:
             )
         return self._bufs[key]
 
-    def forward(self, seq_ids, tokens, stream=None, hidden_in=None, hidden_out=None):
+    def forward(self, seq_ids, tokens, stream=None, hidden_in=None, hidden_out=None, features_in=None, tap_layers=None,
+                taps_out=None):
         """seq_ids [B] int32, tokens [B, k+1] int32 device tensors -> logits [B, k+1, V] (device, fp32).
-        hidden_in / hidden_out [B, k+1, d] fp32: hidden-state input of a fuse_hidden model / hidden states out."""
+        hidden_in / hidden_out [B, k+1, d] fp32: hidden-state input of a fuse_hidden model / hidden states out;
+        features_in [B, k+1, n*d]: the same input as multi-layer features (a fuse_taps model);
+        tap_layers + taps_out [B, k+1, n*d]: the residual stream after those layers, side by side."""
         B, T = tokens.shape
         buf = self.step_buffers(B, T - 1)
         ws = buf["workspace"]
         off = (-ws.data_ptr()) % 256
-        if hidden_in is None and hidden_out is None:
+        if features_in is not None:
+            sv.spec_verify_forward_features(self.model, self.kv, B, T - 1, seq_ids, tokens, features_in, buf["logits"], hidden_out,
+                                            ws[off:off + ws.numel() - 256], stream)
+        elif tap_layers is not None:
+            sv.spec_verify_forward_taps(self.model, self.kv, B, T - 1, seq_ids, tokens, buf["logits"], tap_layers, taps_out,
+                                        ws[off:off + ws.numel() - 256], stream)
+        elif hidden_in is None and hidden_out is None:
             sv.spec_verify_forward(self.model, self.kv, B, T - 1, seq_ids, tokens, buf["logits"], ws[off:off + ws.numel() - 256],
                                    stream)
         else:

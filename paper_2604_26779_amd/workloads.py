@@ -157,9 +157,11 @@ class DraftPairWorkload(DeviceWorkload):
         self.loop = DraftLoop(self.dsess, B, k)
         # a draft with hidden-state input: the target's hidden states before the two pending tokens (synthetic)
         self.pending_hidden = None
+        self.tap_layers = tuple(self.wl["tap_layers"]) if self.draft_cfg.get("fuse_taps", 0) else None
         if self.draft_cfg.get("fuse_hidden", 0):
-            self.pending_hidden = torch.randn((B, 2, self.cfg["d_model"]), generator=g, device=device, dtype=torch.float32)
-            self.target_hidden = torch.zeros((B, k + 1, self.cfg["d_model"]), dtype=torch.float32, device=device)
+            width = self.cfg["d_model"] * max(1, int(self.draft_cfg.get("fuse_taps", 0)))     # features: several states side by side
+            self.pending_hidden = torch.randn((B, 2, width), generator=g, device=device, dtype=torch.float32)
+            self.target_hidden = torch.zeros((B, k + 1, width), dtype=torch.float32, device=device)
         self.dsnapshot = torch.empty(sv.spec_kv_state_bytes(self.dsess.kv), dtype=torch.uint8, device=device)
         sv.spec_kv_snapshot(self.dsess.kv, self.dsnapshot)
 

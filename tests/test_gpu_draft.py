@@ -96,7 +96,9 @@ def _setup_pair(name, seed=7):
     rng = np.random.default_rng(seed)
     out["prev"] = rng.integers(0, cfg_t["vocab"], size=B).astype(np.int32)
     # a draft with hidden-state input also gets the target's hidden states before its two pending tokens (inputs here)
-    out["pend_hidden"] = (rng.standard_normal((B, 2, cfg_t["d_model"])) * 1.5).astype(np.float32) if cfg_d.get("fuse_hidden", 0) else None
+    # (a draft fed multi-layer features: that many states side by side)
+    width = cfg_t["d_model"] * max(1, int(cfg_d.get("fuse_taps", 0)))
+    out["pend_hidden"] = (rng.standard_normal((B, 2, width)) * 1.5).astype(np.float32) if cfg_d.get("fuse_hidden", 0) else None
     for tag, cfg, clen, s in (("t", cfg_t, ctx, seed), ("d", cfg_d, ctx - 1, seed + 17)):
         weights = random_norm_gains(si.make_weights(cfg, seed=s), s)
         kv = si.make_logical_kv(cfg, clen, seed=s)
@@ -140,7 +142,8 @@ def _compare_drafts(x_gpu, q_gpu, x_or, q_or, keys, tol):
     return valid, exempt
 
 
-@pytest.mark.parametrize("name", ["draft_pair_tiny_b4_k3", "draft_pair_small_b5_k4", "draft_pair_fused_small_b5_k4"])
+@pytest.mark.parametrize("name", ["draft_pair_tiny_b4_k3", "draft_pair_small_b5_k4", "draft_pair_fused_small_b5_k4",
+                                  "draft_pair_eagle3_small_b5_k4"])
 def test_draft_loop_and_pair_step_parity(name):
     from paper_2604_26779_amd.draft import DraftLoop
     S = _setup_pair(name)
@@ -211,7 +214,8 @@ def test_draft_loop_and_pair_step_parity(name):
     d["sess"].close()
 
 
-@pytest.mark.parametrize("name,n_steps", [("draft_pair_tiny_b4_k3", 4), ("draft_pair_small_b5_k4", 3), ("draft_pair_fused_small_b5_k4", 3)])
+@pytest.mark.parametrize("name,n_steps", [("draft_pair_tiny_b4_k3", 4), ("draft_pair_small_b5_k4", 3), ("draft_pair_fused_small_b5_k4", 3),
+                                          ("draft_pair_eagle3_small_b5_k4", 3)])
 def test_rollout_of_several_steps_against_oracle(name, n_steps):
     """Consecutive steps with no host round trip: per step and sequence, accept length and emitted tokens equal the
     oracle's until the first decision the oracle marks as fragile (then that sequence is left out from there on);
@@ -223,8 +227,8 @@ def test_rollout_of_several_steps_against_oracle(name, n_steps):
     seed = 0x0123456789ABCDEF
     t0 = S["batch"]["tokens0"]
     hist, _, _, ctx_or = oracle_draft.rollout(t["cfg"], t["w_or"], d["cfg"], d["w_or"], t["kv_or"], d["kv_or"], S["prev"], t0, t["ctx"],
-                                              k, T, seed, n_steps, pending_hidden=S["pend_hidden"])
-    roll = RolloutLoop(t["sess"], d["sess"], B, k)
+                                              k, T, seed, n_steps, pending_hidden=S["pend_hidden"], tap_layers=S["wl"].get("tap_layers"))
+    roll = RolloutLoop(t["sess"], d["sess"], B, k, tap_layers=S["wl"].get("tap_layers"))
     roll.start(torch.from_numpy(S["prev"]).cuda(), torch.from_numpy(t0).cuda(),
                None if S["pend_hidden"] is None else torch.from_numpy(S["pend_hidden"]).cuda())
     acc = torch.full((n_steps, B), -9, dtype=torch.int32, device="cuda")
@@ -303,3 +307,82 @@ def test_hidden_state_output_input_and_next_step_copy():
     sv.spec_next_step_hidden(B, k, d, torch.from_numpy(H).cuda(), torch.from_numpy(n).cuda(), pend)
     torch.cuda.synchronize()
     assert np.array_equal(pend.cpu().numpy(), want)
+
+
+def test_multi_layer_feature_taps_and_feature_fed_draft_pass():
+    """spec_verify_forward_taps: the residual stream after chosen layers of a 4-layer target, side by side, against the
+    oracle (several tap lists, one with a repeat; the logits are unchanged by asking).  spec_verify_forward_features:
+    a draft's logits and hidden states from features through w_fc against the oracle; the same model still takes its own
+    d-wide state through spec_verify_forward_hidden.  Wrong uses are refused on the host."""
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    rng = np.random.default_rng(8)
+
+    def session(cfg, B, k, ctx, seed):
+        weights = random_norm_gains(si.make_weights(cfg, seed=seed), seed)
+        kv = si.make_logical_kv(cfg, ctx, seed=seed)
+        n_pages = sum(-(-(int(c) + k + 1) // si.PAGE_SIZE) for c in ctx) + 8
+        sess = VerifySession(cfg, {n: t.cuda() for n, t in weights.items()}, max_seqs=B, max_ctx_len=int(ctx.max()) + 64, n_pages=n_pages)
+        at = 0
+        for b in range(B):
+            need = -(-int(ctx[b]) // si.PAGE_SIZE)
+            pages = list(range(at, at + need))
+            at += need
+            sess.assign(b, int(ctx[b]), pages)
+            for l in range(cfg["n_layers"]):
+                sess.write_logical_kv(l, pages, kv[l][b][0], kv[l][b][1])
+        return sess, si.weights_for_oracle(cfg, weights), si.kv_for_oracle(kv)
+
+    B, k = 9, 3
+    ctx = rng.integers(0, 200, size=B).astype(np.int64)
+    seq = torch.arange(B, dtype=torch.int32, device="cuda")
+    cfg_t = dict(si.MODELS["small4_bf16"], vocab=1000)
+    d = cfg_t["d_model"]
+    sess, w_or, kv_or = session(cfg_t, B, k, ctx, 5)
+    tokens = rng.integers(0, cfg_t["vocab"], size=(B, k + 1)).astype(np.int32)
+    d_tokens = torch.from_numpy(tokens).cuda()
+    plain = sess.forward(seq, d_tokens).clone()
+    for taps in ((1, 2, 4), (4, 4, 3), (2,), (3, 1, 2, 4)):
+        want, _, want_f = of.verify_forward(cfg_t, w_or, kv_or, tokens, ctx, tap_layers=taps)
+        feats = torch.full((B, k + 1, len(taps) * d), float("nan"), dtype=torch.float32, device="cuda")
+        got = sess.forward(seq, d_tokens, tap_layers=taps, taps_out=feats)
+        torch.cuda.synchronize()
+        assert torch.equal(got, plain)
+        ok, max_err, worst = logits_close(got.cpu().numpy(), want, *TOL["bf16"])
+        assert ok, (taps, max_err, worst)
+        okf, max_err_f, worst_f = logits_close(feats.cpu().numpy(), want_f, *TOL["bf16"])
+        assert okf, (taps, max_err_f, worst_f)
+        print("taps", taps, "features max abs err %.3e (|x| up to %.2f)" % (max_err_f, np.abs(want_f).max()))
+    last = torch.zeros((B, k + 1, d), dtype=torch.float32, device="cuda")
+    sess.forward(seq, d_tokens, hidden_out=last)
+    torch.cuda.synchronize()
+    assert torch.equal(last, feats[..., 3 * d:])                     # the tap after all layers is the hidden-state output
+    for bad in ((0, 1, 2), (1, 5), (1, 2, 3, 4, 4)):
+        with pytest.raises(sv.SpecError):
+            sess.forward(seq, d_tokens, tap_layers=bad, taps_out=torch.zeros((B, k + 1, len(bad) * d), dtype=torch.float32, device="cuda"))
+    with pytest.raises(sv.SpecError):                                # features into a model that takes none
+        sess.forward(seq, d_tokens, features_in=feats)
+    sess.close()
+
+    cfg_d = dict(si.MODELS["draft_eagle3_small_bf16"], vocab=1000)
+    dsess, wd_or, kvd_or = session(cfg_d, B, k, ctx, 6)
+    f_in = (np.asarray(want_f[..., :3 * d]) * 1.0).astype(np.float32)          # real target states, as they would arrive
+    want, _, want_h = of.verify_forward(cfg_d, wd_or, kvd_or, tokens, ctx, features_in=f_in, return_hidden=True)
+    hid = torch.full((B, k + 1, d), float("nan"), dtype=torch.float32, device="cuda")
+    got = dsess.forward(seq, d_tokens, features_in=torch.from_numpy(f_in).cuda(), hidden_out=hid)
+    torch.cuda.synchronize()
+    ok, max_err, worst = logits_close(got.cpu().numpy(), want, *TOL["bf16"])
+    assert ok, (max_err, worst)
+    okh, max_err_h, worst_h = logits_close(hid.cpu().numpy(), want_h, *TOL["bf16"])
+    assert okh, (max_err_h, worst_h)
+    print("feature-fed draft: logits max abs err %.3e, hidden states max abs err %.3e" % (max_err, max_err_h))
+    # the chained form of the same model: its own d-wide state, no projection
+    h_in = (rng.standard_normal((B, k + 1, d)) * 2.0).astype(np.float32)
+    want2, _ = of.verify_forward(cfg_d, wd_or, kvd_or, tokens, ctx, hidden_in=h_in)
+    got2 = dsess.forward(seq, d_tokens, hidden_in=torch.from_numpy(h_in).cuda())
+    torch.cuda.synchronize()
+    ok2, max_err2, worst2 = logits_close(got2.cpu().numpy(), want2, *TOL["bf16"])
+    assert ok2, (max_err2, worst2)
+    with pytest.raises(sv.SpecError):                                # taps from a model that itself needs a hidden-state input
+        dsess.forward(seq, d_tokens, tap_layers=(1,), taps_out=hid)
+    dsess.close()

@@ -112,3 +112,4 @@ def test_argument_checks_of_the_rollout_side_calls(sv):
     fused = dict(n_layers=1, d_model=256, n_q_heads=2, n_kv_heads=2, head_dim=128, ffn_dim=512, vocab=10, rope_theta=1e4, rms_eps=1e-5,
                  dtype="bf16", tied_head=1, fuse_hidden=1)
     assert sv.spec_model_weight_count(fused) == 1 + 9 + 1 + 3
+    assert sv.spec_model_weight_count(dict(fused, fuse_taps=3)) == 1 + 9 + 1 + 3 + 1
