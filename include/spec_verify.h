@@ -241,7 +241,8 @@ spec_status spec_verify_forward_features(spec_model* model, spec_kv* kv, int32_t
  * q = dev_q[b][i][:] are the probabilities the draft was sampled from; stop at the first failure.
  * With n kept: if n < k the next token is drawn from norm(max(0, p_n - q_n)) (from p_n if that
  * residual is identically zero), else from p_k (bonus).  The draw is an exponential race,
- * argmax_v w_v / (-ln u_v), ties to the lowest v.
+ * argmax_v w_v / (-ln u_v), ties to the lowest v.  Every quantity a decision hangs on - logit / temperature,
+ * the softmax, the accept test, the residual and the race keys - is computed in fp64.
  * Random numbers: Philox4x32-10, key = (seed low word, seed high word), counter =
  * (c0, i, b, step*4 + stream); accept: stream 0, c0 = 0, u = (word0 >> 8) * 2^-24;
  * vocabulary entry v: stream 1, c0 = v >> 2, word v & 3, u_v = ((word >> 9) + 0.5) * 2^-23.
@@ -264,7 +265,7 @@ spec_status spec_reject_sample(int32_t B, int32_t k, int32_t V, const float* dev
  * spec_reject_sample for callers that cannot allocate device memory or carry a workspace along: code recorded under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic, random
  * streams and outputs as spec_reject_sample, minus the workspace: the row statistics and per-range race results live
- * in a buffer that is part of the loaded library (384 KiB of device memory per GPU, held until the process ends).
+ * in a buffer that is part of the loaded library (1.5 MiB of device memory per GPU, held until the process ends).
  * The call allocates and frees nothing.  Limit: B * (k + 1) <= 4096 logits rows, SPEC_EINVAL beyond (use
  * spec_reject_sample then).
  * All calls on one GPU share that buffer: calls whose work may overlap on one GPU (different streams, or graphs

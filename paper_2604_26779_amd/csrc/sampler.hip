@@ -37,14 +37,6 @@ __device__ inline Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, u
     return Philox4{c0, c1, c2, c3};
 }
 
-__device__ inline void online_merge(float& m, float& s, float m2, float s2)
-{
-    float mm = fmaxf(m, m2);
-    if (mm == -INFINITY) { m = mm; s = 0.f; return; }
-    s = s * expf(m - mm) + s2 * expf(m2 - mm);
-    m = mm;
-}
-
 constexpr int SAMP_PARTS = 8;                 // ranges the vocabulary is cut into (whole groups of 4 entries: one Philox call each)
 
 // groups of 4 vocabulary entries of range `part`: [g0, g1)
@@ -55,53 +47,72 @@ __device__ inline void part_groups(int V, int part, int* g0, int* g1)
     *g1 = (part + 1) * per < groups ? (part + 1) * per : groups;
 }
 
-__global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __restrict__ logits, int64_t row_stride, int V, float inv_t,
-                                                                  float2* __restrict__ stats)
+// Everything a decision hangs on is fp64, as the definition has it: z = logit / T (a division, not a product with
+// 1 / T), e = exp(z - max), p = e / sum, the accept test u * q < p, the race keys w / (-ln u).  With fp32 keys two
+// candidates closer than 1e-6 relative could swap, and a residual p - q that cancels to a few ulps was noise; in fp64
+// the choice differs from an fp64 reference's only where its own keys agree to 15 digits.  The cost is small: about 140
+// fp64 instructions per vocabulary entry of the B rows that draw, 50 per entry of the statistics.
+
+// (max, sum of exp) of one range of a row; the maximum of z is taken over the raw fp32 logits (z is monotone in them)
+__global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __restrict__ logits, int64_t row_stride, int V, double T,
+                                                                  double2* __restrict__ stats)
 {
     const float* row = logits + (int64_t)blockIdx.x * row_stride;
     int g0, g1;
     part_groups(V, blockIdx.y, &g0, &g1);
     const int v1 = g1 * 4 < V ? g1 * 4 : V;
-    float m = -INFINITY, s = 0.f;
+    __shared__ float lmax[SAMP_THREADS / 64];
+    __shared__ double lsum[SAMP_THREADS / 64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float mx = -INFINITY;
     for (int v = g0 * 4 + threadIdx.x; v < v1; v += SAMP_THREADS) {
-        float z = row[v] * inv_t;
-        if (z > m) { s = s * expf(m - z) + 1.f; m = z; }
-        else if (z > -INFINITY) s += expf(z - m);
+        const float l = row[v];
+        if (l > mx) mx = l;                                      // NaN compares false: left out, as below
     }
-    // wavefront reduction, then across the 16 wavefronts through LDS
-    for (int off = 32; off > 0; off >>= 1) {
-        float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
-        online_merge(m, s, m2, s2);
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if (lane == 0) lmax[wave] = mx;
+    __syncthreads();
+    mx = lmax[0];
+    for (int w = 1; w < SAMP_THREADS / 64; ++w) mx = fmaxf(mx, lmax[w]);
+    const double m = (double)mx / T;
+    double sum = 0.0;
+    if (mx > -INFINITY) {
+        for (int v = g0 * 4 + threadIdx.x; v < v1; v += SAMP_THREADS) {
+            const float l = row[v];
+            if (l > -INFINITY) sum += exp((double)l / T - m);
+        }
     }
-    __shared__ float lm[SAMP_THREADS / 64], ls[SAMP_THREADS / 64];
-    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (lane == 0) { lm[wave] = m; ls[wave] = s; }
+    // fixed order: butterfly inside a wavefront, then the 16 wavefronts one after the other
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) lsum[wave] = sum;
     __syncthreads();
     if (threadIdx.x == 0) {
-        float M = lm[0], S = ls[0];
-        for (int w = 1; w < SAMP_THREADS / 64; ++w) online_merge(M, S, lm[w], ls[w]);
-        stats[(int64_t)blockIdx.x * SAMP_PARTS + blockIdx.y] = make_float2(M, S);
+        double S = lsum[0];
+        for (int w = 1; w < SAMP_THREADS / 64; ++w) S += lsum[w];
+        stats[(int64_t)blockIdx.x * SAMP_PARTS + blockIdx.y] = make_double2(m, S);
     }
 }
 
-// a row's statistics from those of its ranges, merged in range order
-__device__ inline float2 row_stat(const float2* __restrict__ stats, int64_t row)
+// a row's statistics from those of its ranges, in range order: M = max m_p, S = sum_p s_p exp(m_p - M)
+__device__ inline double2 row_stat(const double2* __restrict__ stats, int64_t row)
 {
-    float2 a = stats[row * SAMP_PARTS];
-    for (int p = 1; p < SAMP_PARTS; ++p) {
-        const float2 c = stats[row * SAMP_PARTS + p];
-        online_merge(a.x, a.y, c.x, c.y);
+    double M = -INFINITY;
+    for (int p = 0; p < SAMP_PARTS; ++p) M = fmax(M, stats[row * SAMP_PARTS + p].x);
+    double S = 0.0;
+    for (int p = 0; p < SAMP_PARTS; ++p) {
+        const double2 c = stats[row * SAMP_PARTS + p];
+        if (c.y > 0.0) S += c.y * exp(c.x - M);
     }
-    return a;
+    return make_double2(M, S);
 }
 
 // Exponential race over the groups [g0, g1) of one row.  Two races share the scan: the residual one (RES: weights
-// max(0, e/S - q); HOT: e except 0 at the drafted token `hot`, the residual of a one-hot draft distribution) and the
-// plain one over e = exp(z - m), which decides the bonus row and stands in where a residual is identically zero.
+// max(0, p - q); HOT: p except 0 at the drafted token `hot`, the residual of a one-hot draft distribution) and the
+// plain one over p = exp(z - m) / S, which decides the bonus row and stands in where a residual is identically zero.
 template <bool RES, bool HOT>
-__device__ inline void race_scan(const float* __restrict__ lrow, const float* __restrict__ qrow, int V, int g0, int g1, float inv_t,
-                                 float m, float inv_s, uint32_t k0, uint32_t k1, uint32_t c1, uint32_t c2, uint32_t c3,
-                                 float& best, int& best_v, float& best_res, int& best_res_v, int hot = -1)
+__device__ inline void race_scan(const float* __restrict__ lrow, const float* __restrict__ qrow, int V, int g0, int g1, double T,
+                                 double m, double S, uint32_t k0, uint32_t k1, uint32_t c1, uint32_t c2, uint32_t c3,
+                                 double& best, int& best_v, double& best_res, int& best_res_v, int hot = -1)
 {
     for (int g = g0 + threadIdx.x; g < g1; g += SAMP_THREADS) {
         Philox4 r = philox4x32_10((uint32_t)g, c1, c2, c3, k0, k1);
@@ -110,16 +121,16 @@ __device__ inline void race_scan(const float* __restrict__ lrow, const float* __
         for (int j = 0; j < 4; ++j) {
             int v = g * 4 + j;
             if (v >= V) break;
-            float e = expf(lrow[v] * inv_t - m);
-            if (!(e > 0.f)) continue;
-            float u = ((float)(words[j] >> 9) + 0.5f) * (1.0f / 8388608.0f);
-            float nl = -logf(u);
-            float key = e / nl;
+            const double pv = exp((double)lrow[v] / T - m) / S;
+            if (!(pv > 0.0)) continue;
+            const double u = ((double)(words[j] >> 9) + 0.5) * (1.0 / 8388608.0);
+            const double nl = -log(u);
+            const double key = pv / nl;
             if (key > best) { best = key; best_v = v; }     // v ascends inside a thread: ties keep the lowest
             if (RES || HOT) {
-                float w = RES ? fmaxf(0.f, e * inv_s - qrow[v]) : (v == hot ? 0.f : e);
-                if (w > 0.f) {
-                    float kr = w / nl;
+                const double w = RES ? fmax(0.0, pv - (double)qrow[v]) : (v == hot ? 0.0 : pv);
+                if (w > 0.0) {
+                    const double kr = w / nl;
                     if (kr > best_res) { best_res = kr; best_res_v = v; }
                 }
             }
@@ -127,15 +138,15 @@ __device__ inline void race_scan(const float* __restrict__ lrow, const float* __
     }
 }
 
-__device__ inline void argmax_merge(float& key, int& v, float key2, int v2)
+__device__ inline void argmax_merge(double& key, int& v, double key2, int v2)
 {
     if (key2 > key || (key2 == key && v2 >= 0 && (v < 0 || v2 < v))) { key = key2; v = v2; }
 }
 
-__device__ inline void block_argmax(float& key, int& v, float* lk, int* lv)
+__device__ inline void block_argmax(double& key, int& v, double* lk, int* lv)
 {
     for (int off = 32; off > 0; off >>= 1) {
-        float k2 = __shfl_xor(key, off);
+        double k2 = __shfl_xor(key, off);
         int v2 = __shfl_xor(v, off);
         argmax_merge(key, v, k2, v2);
     }
@@ -148,19 +159,19 @@ __device__ inline void block_argmax(float& key, int& v, float* lk, int* lv)
 }
 
 // what a range's workgroup hands to the merge: n, and its best (key, token) of the residual race and of the plain race
-struct RacePart { int32_t n; float key_res; int32_t v_res; float key; int32_t v; int32_t pad[3]; };
+struct RacePart { int32_t n, v_res, v, pad; double key_res, key; };
 
 __global__ __launch_bounds__(SAMP_THREADS) void reject_scan_kernel(
     int k, int V, const float* __restrict__ logits, const float* __restrict__ q, const int32_t* __restrict__ draft,
-    float inv_t, uint32_t seed_lo, uint32_t seed_hi, uint32_t step4, const float2* __restrict__ stats,
+    double T, uint32_t seed_lo, uint32_t seed_hi, uint32_t step4, const double2* __restrict__ stats,
     RacePart* __restrict__ parts, float* __restrict__ dbg)
 {
     const int b = blockIdx.x, part = blockIdx.y;
     const float* L = logits + (int64_t)b * (k + 1) * V;
     const float* Qb = q ? q + (int64_t)b * k * V : nullptr;
     __shared__ int s_n;
-    __shared__ float2 s_st;
-    __shared__ float lk[SAMP_THREADS / 64];
+    __shared__ double2 s_st;
+    __shared__ double lk[SAMP_THREADS / 64];
     __shared__ int lv[SAMP_THREADS / 64];
 
     if (threadIdx.x == 0) {
@@ -172,34 +183,34 @@ __global__ __launch_bounds__(SAMP_THREADS) void reject_scan_kernel(
         for (int i = 0; i < k; ++i) {
             int x = draft[(int64_t)b * k + i];
             if (x < 0 || x >= V) break;
-            float2 st = row_stat(stats, (int64_t)b * (k + 1) + i);
-            float P = expf(L[(int64_t)i * V + x] * inv_t - st.x) / st.y;
-            float Q = Qb ? Qb[(int64_t)i * V + x] : 1.0f;          // no q array: one-hot drafts (a deterministic drafter)
+            const double2 st = row_stat(stats, (int64_t)b * (k + 1) + i);
+            const double P = exp((double)L[(int64_t)i * V + x] / T - st.x) / st.y;
+            const double Q = Qb ? (double)Qb[(int64_t)i * V + x] : 1.0;     // no q array: one-hot drafts (a deterministic drafter)
             Philox4 r = philox4x32_10(0u, (uint32_t)i, (uint32_t)b, step4 + 0u, seed_lo, seed_hi);
-            float u = (float)(r.x >> 8) * (1.0f / 16777216.0f);
-            if (log_it) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = P; d[1] = Q; d[2] = u; }
-            if ((double)u * (double)Q < (double)P) n += 1; else break;
+            const double u = (double)(r.x >> 8) * (1.0 / 16777216.0);
+            if (log_it) { float* d = dbg + ((int64_t)b * k + i) * 3; d[0] = (float)P; d[1] = (float)Q; d[2] = (float)u; }
+            if (u * Q < P) n += 1; else break;
         }
         s_n = n;
         s_st = row_stat(stats, (int64_t)b * (k + 1) + n);
     }
     __syncthreads();
     const int n = s_n;
-    const float2 st = s_st;
+    const double2 st = s_st;
     const float* lrow = L + (int64_t)n * V;
     int g0, g1;
     part_groups(V, part, &g0, &g1);
-    float best = -1.f, best_res = -1.f;
+    double best = -1.0, best_res = -1.0;
     int best_v = -1, best_res_v = -1;
     const uint32_t c1 = (uint32_t)n, c2 = (uint32_t)b, c3 = step4 + 1u;
-    if (n < k && Qb) race_scan<true, false>(lrow, Qb + (int64_t)n * V, V, g0, g1, inv_t, st.x, 1.0f / st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v);
-    else if (n < k) race_scan<false, true>(lrow, nullptr, V, g0, g1, inv_t, st.x, 1.0f, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v, draft[(int64_t)b * k + n]);
-    else race_scan<false, false>(lrow, nullptr, V, g0, g1, inv_t, st.x, 1.0f, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v);
+    if (n < k && Qb) race_scan<true, false>(lrow, Qb + (int64_t)n * V, V, g0, g1, T, st.x, st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v);
+    else if (n < k) race_scan<false, true>(lrow, nullptr, V, g0, g1, T, st.x, st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v, draft[(int64_t)b * k + n]);
+    else race_scan<false, false>(lrow, nullptr, V, g0, g1, T, st.x, st.y, seed_lo, seed_hi, c1, c2, c3, best, best_v, best_res, best_res_v);
     block_argmax(best, best_v, lk, lv);
     block_argmax(best_res, best_res_v, lk, lv);
     if (threadIdx.x == 0) {
         RacePart r;
-        r.n = n; r.key_res = best_res; r.v_res = best_res_v; r.key = best; r.v = best_v; r.pad[0] = r.pad[1] = r.pad[2] = 0;
+        r.n = n; r.key_res = best_res; r.v_res = best_res_v; r.key = best; r.v = best_v; r.pad = 0;
         parts[(int64_t)b * SAMP_PARTS + part] = r;
     }
 }
@@ -213,7 +224,7 @@ __global__ void reject_merge_kernel(int B, int k, const RacePart* __restrict__ p
     if (b >= B) return;
     const RacePart* p = parts + (int64_t)b * SAMP_PARTS;
     const int n = p[0].n;
-    float key = -1.f, key_res = -1.f;
+    double key = -1.0, key_res = -1.0;
     int v = -1, v_res = -1;
     for (int i = 0; i < SAMP_PARTS; ++i) {
         argmax_merge(key, v, p[i].key, p[i].v);
@@ -228,26 +239,28 @@ __global__ void reject_merge_kernel(int B, int k, const RacePart* __restrict__ p
 }
 
 // The draft model's own draw, over the same SAMP_PARTS vocabulary ranges as the verifier's: q = softmax(logits / T)
-// written out for the verifier, and x = argmax_v e_v / (-ln u_v) on random stream 2 (e = exp(z - max): the argmax does
-// not need the normalisation).  row_stats_kernel gives the ranges' (max, sum); draft_scan_kernel (workgroup = sequence,
-// range) merges them, writes its range of q and finds its range's best key; draft_merge_kernel picks the token.
-struct DraftPart { float key; int32_t v; };
+// written out for the verifier (rounded to fp32 from the fp64 value), and x = argmax_v q_v / (-ln u_v) on random
+// stream 2.  row_stats_kernel gives the ranges' (max, sum); draft_scan_kernel (workgroup = sequence, range) merges them,
+// writes its range of q and finds its range's best key; draft_merge_kernel picks the token.
+struct DraftPart { double key; int32_t v, pad; };
 
 __global__ __launch_bounds__(SAMP_THREADS) void draft_scan_kernel(
-    int V, const float* __restrict__ logits, int64_t logits_stride, float inv_t, uint32_t seed_lo, uint32_t seed_hi,
-    uint32_t step4, uint32_t row, const float2* __restrict__ stats, float* __restrict__ q, int64_t q_stride,
+    int V, const float* __restrict__ logits, int64_t logits_stride, double T, uint32_t seed_lo, uint32_t seed_hi,
+    uint32_t step4, uint32_t row, const double2* __restrict__ stats, float* __restrict__ q, int64_t q_stride,
     DraftPart* __restrict__ parts)
 {
     const int b = blockIdx.x, part = blockIdx.y;
     const float* lrow = logits + (int64_t)b * logits_stride;
     float* qrow = q + (int64_t)b * q_stride;
-    __shared__ float lk[SAMP_THREADS / 64];
+    __shared__ double lk[SAMP_THREADS / 64];
     __shared__ int lv[SAMP_THREADS / 64];
-    const float2 st = row_stat(stats, b);                      // every thread merges the 8 ranges itself (cached loads)
-    const float m = st.x, inv_s = 1.0f / st.y;
+    __shared__ double2 s_st;
+    if (threadIdx.x == 0) s_st = row_stat(stats, b);
+    __syncthreads();
+    const double m = s_st.x, S = s_st.y;
     int g0, g1;
     part_groups(V, part, &g0, &g1);
-    float best = -1.f;
+    double best = -1.0;
     int best_v = -1;
     for (int g = g0 + threadIdx.x; g < g1; g += SAMP_THREADS) {
         Philox4 r = philox4x32_10((uint32_t)g, row, (uint32_t)b, step4 + 2u, seed_lo, seed_hi);
@@ -256,16 +269,16 @@ __global__ __launch_bounds__(SAMP_THREADS) void draft_scan_kernel(
         for (int j = 0; j < 4; ++j) {
             int v = g * 4 + j;
             if (v >= V) break;
-            float e = expf(lrow[v] * inv_t - m);
-            qrow[v] = e * inv_s;
-            if (!(e > 0.f)) continue;
-            float u = ((float)(words[j] >> 9) + 0.5f) * (1.0f / 8388608.0f);
-            float key = e / (-logf(u));
+            const double pv = exp((double)lrow[v] / T - m) / S;
+            qrow[v] = (float)pv;
+            if (!(pv > 0.0)) continue;
+            const double u = ((double)(words[j] >> 9) + 0.5) * (1.0 / 8388608.0);
+            const double key = pv / (-log(u));
             if (key > best) { best = key; best_v = v; }
         }
     }
     block_argmax(best, best_v, lk, lv);
-    if (threadIdx.x == 0) { parts[(int64_t)b * SAMP_PARTS + part].key = best; parts[(int64_t)b * SAMP_PARTS + part].v = best_v; }
+    if (threadIdx.x == 0) { DraftPart d; d.key = best; d.v = best_v; d.pad = 0; parts[(int64_t)b * SAMP_PARTS + part] = d; }
 }
 
 __global__ void draft_merge_kernel(int B, const DraftPart* __restrict__ parts, int32_t* __restrict__ tok_a, int stride_a,
@@ -273,7 +286,7 @@ __global__ void draft_merge_kernel(int B, const DraftPart* __restrict__ parts, i
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    float key = -1.f;
+    double key = -1.0;
     int v = -1;
     for (int i = 0; i < SAMP_PARTS; ++i) argmax_merge(key, v, parts[(int64_t)b * SAMP_PARTS + i].key, parts[(int64_t)b * SAMP_PARTS + i].v);
     if (tok_a) tok_a[(int64_t)b * stride_a] = v;
@@ -282,8 +295,8 @@ __global__ void draft_merge_kernel(int B, const DraftPart* __restrict__ parts, i
 
 }  // namespace specv
 
-// workspace: the ranges' row statistics [B * (k + 1)][SAMP_PARTS] float2, then the ranges' race results [B][SAMP_PARTS]
-static size_t sample_stats_bytes(int64_t rows) { return specv::align_up((size_t)rows * specv::SAMP_PARTS * sizeof(float2), 256); }
+// workspace: the ranges' row statistics [B * (k + 1)][SAMP_PARTS] double2, then the ranges' race results [B][SAMP_PARTS]
+static size_t sample_stats_bytes(int64_t rows) { return specv::align_up((size_t)rows * specv::SAMP_PARTS * sizeof(double2), 256); }
 static size_t sample_parts_bytes(int64_t B) { return specv::align_up((size_t)B * specv::SAMP_PARTS * sizeof(specv::RacePart), 256); }
 
 extern "C" size_t spec_sample_workspace_bytes(int32_t B, int32_t k)
@@ -299,20 +312,20 @@ static spec_status reject_sample_launch(const char* who, int32_t B, int32_t k, i
                                         const int32_t* dev_draft_tokens, float temperature, uint64_t seed, uint64_t step,
                                         int32_t* dev_accept_len, int32_t* dev_out_tokens, float* dev_dbg, void* ws, hipStream_t s)
 {
-    float2* stats = (float2*)ws;
+    double2* stats = (double2*)ws;
     if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT || V < 1) { set_error("%s: B, k or V out of range", who); return SPEC_EINVAL; }
     if (!(temperature > 0.f)) { set_error("%s: temperature must be > 0", who); return SPEC_EINVAL; }
     if (step >= (1ull << 30)) { set_error("%s: step must be < 2^30", who); return SPEC_EINVAL; }
     if (!dev_logits || !dev_accept_len || !dev_out_tokens || !ws || (k > 0 && !dev_draft_tokens)) {
         set_error("%s: null pointer", who); return SPEC_EINVAL;
     }
-    float inv_t = 1.0f / temperature;
+    const double T = (double)temperature;
     RacePart* parts = (RacePart*)((char*)ws + sample_stats_bytes((int64_t)B * (k + 1)));
     prof_mark(PC_OTHER, s);
-    row_stats_kernel<<<dim3((unsigned)(B * (k + 1)), SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, (int64_t)V, V, inv_t, stats);
+    row_stats_kernel<<<dim3((unsigned)(B * (k + 1)), SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, (int64_t)V, V, T, stats);
     SPEC_LAUNCH_CHECK("row_stats_kernel");
     prof_mark(PC_SAMPLE_STATS, s);
-    reject_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(k, V, dev_logits, dev_q, dev_draft_tokens, inv_t, (uint32_t)seed,
+    reject_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(k, V, dev_logits, dev_q, dev_draft_tokens, T, (uint32_t)seed,
                                                                              (uint32_t)(seed >> 32), (uint32_t)(step * 4u), stats, parts, dev_dbg);
     SPEC_LAUNCH_CHECK("reject_scan_kernel");
     reject_merge_kernel<<<(unsigned)cdiv(B, 256), 256, 0, s>>>(B, k, parts, dev_draft_tokens, dev_accept_len, dev_out_tokens);
@@ -324,8 +337,8 @@ static spec_status reject_sample_launch(const char* who, int32_t B, int32_t k, i
 // Workspace of spec_reject_sample_static: device memory that exists from the moment the library is loaded, so
 // that entry point never allocates.  Every GPU holds its own copy at its own address; the array's name is only a
 // host-side handle, the address kernels are given comes from hipGetSymbolAddress with that GPU current.
-constexpr int SAMP_STATIC_ROWS = 4096;                  // B * (k + 1) at most: 256 KiB of row statistics + at most 128 KiB of race results per GPU
-constexpr size_t SAMP_STATIC_BYTES = (size_t)SAMP_STATIC_ROWS * SAMP_PARTS * (sizeof(float2) + sizeof(RacePart)) + 512;
+constexpr int SAMP_STATIC_ROWS = 4096;                  // B * (k + 1) at most: 512 KiB of row statistics + 1 MiB of race results (sized for k = 0, B = 4096) per GPU
+constexpr size_t SAMP_STATIC_BYTES = (size_t)SAMP_STATIC_ROWS * SAMP_PARTS * (sizeof(double2) + sizeof(RacePart)) + 512;
 static __device__ __align__(256) unsigned char scratch[SAMP_STATIC_BYTES];
 constexpr int SAMP_MAX_DEVICES = 64;
 static void* g_scratch_ptr[SAMP_MAX_DEVICES];
@@ -400,11 +413,11 @@ extern "C" spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_
     if (!dev_workspace || workspace_bytes < spec_draft_sample_workspace_bytes(B)) { set_error("spec_draft_sample: workspace missing or too small"); return SPEC_EINVAL; }
     hipStream_t s = (hipStream_t)stream;
     prof_mark(PC_OTHER, s);
-    float2* stats = (float2*)dev_workspace;
+    double2* stats = (double2*)dev_workspace;
     DraftPart* parts = (DraftPart*)((char*)dev_workspace + sample_stats_bytes(B));
-    const float inv_t = 1.0f / temperature;
-    row_stats_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, logits_row_stride, V, inv_t, stats);
-    draft_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(V, dev_logits, logits_row_stride, inv_t, (uint32_t)seed,
+    const double T = (double)temperature;
+    row_stats_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, logits_row_stride, V, T, stats);
+    draft_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(V, dev_logits, logits_row_stride, T, (uint32_t)seed,
                                                                             (uint32_t)(seed >> 32), (uint32_t)(step * 4u), (uint32_t)row, stats,
                                                                             dev_q, q_row_stride, parts);
     draft_merge_kernel<<<(unsigned)cdiv(B, 256), 256, 0, s>>>(B, parts, dev_tokens_a, stride_a, dev_tokens_b, stride_b);

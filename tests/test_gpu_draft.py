@@ -39,7 +39,7 @@ def test_draft_sample_parity(B, V, temperature, pad):
     torch.cuda.synchronize()
     q_gpu = q[:, row, :].cpu().numpy()
     assert np.all(q[:, [i for i in range(k) if i != row], :].cpu().numpy() == -1.0)      # other rows untouched
-    assert np.max(np.abs(q_gpu - q_or) / (q_or + 1e-30)) < 2e-5
+    assert np.max(np.abs(q_gpu - q_or) / (q_or + 1e-30)) < 1.3e-7          # fp64 on both sides, rounded to fp32 once
     assert np.max(np.abs(q_gpu.sum(-1) - 1)) < 1e-4
     x_gpu = tok_b.cpu().numpy()
     assert np.array_equal(tok_a[:, row + 1].cpu().numpy(), x_gpu)
@@ -47,8 +47,7 @@ def test_draft_sample_parity(B, V, temperature, pad):
     near = (keys[:, 0] - keys[:, 1]) <= 1e-4 * keys[:, 0]
     diff = x_gpu != x_or
     print("draft sample", dict(B=B, V=V), "mismatches %d (near ties %d)" % (diff.sum(), near.sum()))
-    assert not np.any(diff & ~near)
-    assert diff.sum() <= max(1, B // 20)
+    assert diff.sum() == 0                                  # the draw is decided in fp64 on both sides: no exemption
 
 
 def test_kv_truncate_against_oracle_book():
