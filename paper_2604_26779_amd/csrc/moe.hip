@@ -27,6 +27,10 @@ __global__ __launch_bounds__(64) void moe_route_kernel(const float* __restrict__
         if (e < E) {
             v = 0.f;
             for (int s = 0; s < splits; ++s) v += part[s * split_stride + (int64_t)m * E + e];
+            // a logit that is not finite (overflowed or corrupt router weights) must not poison the row: NaN counts as the
+            // lowest finite value, infinities as the largest, so that top_k distinct experts inside [0, E) are always found
+            // (-INFINITY is reserved for "taken" and "beyond E") and the weights stay finite with a sum >= 1
+            v = v == v ? fminf(fmaxf(v, -3.0e38f), 3.0e38f) : -3.0e38f;
         }
         r[j] = v;
     }
@@ -46,7 +50,7 @@ __global__ __launch_bounds__(64) void moe_route_kernel(const float* __restrict__
             if (b2 > best || (b2 == best && e2 < be)) { best = b2; be = e2; }
         }
         float p = expf(best - mx);
-        if (be >= E) { be = t; p = 0.f; }                 // non-finite logits: stay inside the expert range
+        if (be >= E) { be = t; p = 0.f; }                 // cannot happen with top_k <= E (kept so that an id is never out of range)
         sum += p;
         if (lane == t) { chosen_p = p; chosen_e = be; }
 #pragma unroll

@@ -126,3 +126,33 @@ def test_moe_with_8bit_matrices_and_cache(B, k, changes):
     max_err, n_exempt, n_rows, loads = _run(cfg, ctx, k, seed=B * 7 + k)
     print("moe, 8-bit matrices and cache, B=%d k=%d %s: max abs err %.3e on %d rows, %d exempted" % (B, k, changes, max_err, n_rows - n_exempt, n_exempt))
     assert n_exempt <= max(2, n_rows // 10), (n_exempt, n_rows)
+
+
+def test_router_weights_that_overflow_do_not_poison_the_step():
+    """A router whose matrix holds infinities gives logits that are +inf, -inf or NaN (inf - inf).  The routing must
+    still pick top_k distinct experts inside the range with finite weights: the logits of the step are finite, and a second session with healthy weights in the same process still matches the oracle."""
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = si.MODELS["small_moe_bf16"]
+    B, k = 5, 2
+    weights = si.make_weights(cfg, seed=3)
+    bad = {n: t.clone() for n, t in weights.items()}
+    bad["l0.router"][2, :] = float("inf")                  # expert 2: +-inf or NaN on every row
+    bad["l1.router"][5, ::2] = float("-inf")
+    bad["l1.router"][7, 0] = float("nan")
+    ctx = np.array([40, 3, 90, 17, 64])
+    n_pages = sum(-(-(int(c) + k + 1) // si.PAGE_SIZE) for c in ctx) + 8
+    sess = VerifySession(cfg, {n: t.cuda() for n, t in bad.items()}, max_seqs=B, max_ctx_len=160, n_pages=n_pages)
+    sess.pool.zero_()
+    at = 0
+    for b in range(B):
+        need = -(-int(ctx[b]) // si.PAGE_SIZE)
+        sess.assign(b, int(ctx[b]), list(range(at, at + need)))
+        at += need
+    tokens = torch.randint(0, cfg["vocab"], (B, k + 1), dtype=torch.int32, device="cuda")
+    seq = torch.arange(B, dtype=torch.int32, device="cuda")
+    a = sess.forward(seq, tokens).clone()
+    torch.cuda.synchronize()
+    assert torch.isfinite(a).all()
+    sess.close()
+    max_err, n_exempt, n_rows, _ = _run(cfg, [30, 70, 5], 2, seed=14)
+    assert max_err < 2e-2 and n_exempt <= n_rows // 3
