@@ -59,7 +59,7 @@ def _say(*args):
     os.write(_REAL_STDERR, (" ".join(str(a) for a in args) + "\n").encode())
 
 
-def _check_workload(name, ks, moe_margin=None, more_picks=(), max_exempt_frac=0.25, picks_for_k=None):
+def _check_workload(name, ks, moe_margin=None, more_picks=(), max_exempt_frac=0.25, picks_for_k=None, tap_layers=None):
     from paper_2604_26779_amd.workloads import DeviceWorkload
     wl = DeviceWorkload(name)
     cfg, B = wl.cfg, wl.B
@@ -86,12 +86,35 @@ def _check_workload(name, ks, moe_margin=None, more_picks=(), max_exempt_frac=0.
         kv_or = [[per[all_picks.index(b)] for b in picks] for per in kv_all]
         wl.restore()
         tokens = np.concatenate([wl.batch["tokens0"][:, None], rng.integers(0, cfg["vocab"], size=(B, k))], axis=1).astype(np.int32)
-        logits = wl.sess.forward(seq_ids, torch.from_numpy(tokens).cuda())
+        if tap_layers:               # the same pass, also writing the residual stream after the tapped layers (multi-layer features)
+            feats = torch.full((B, k + 1, len(tap_layers) * cfg["d_model"]), float("nan"), dtype=torch.float32, device="cuda")
+            logits = wl.sess.forward(seq_ids, torch.from_numpy(tokens).cuda(), tap_layers=tap_layers, taps_out=feats)
+        else:
+            logits = wl.sess.forward(seq_ids, torch.from_numpy(tokens).cuda())
         torch.cuda.synchronize()
         assert torch.isfinite(logits).all()
         print(name, "k=%d: oracle on sequences" % k, picks, "contexts", [int(wl.ctx_len[b]) for b in picks], flush=True)
         log = []
-        want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks], route_log=log, kv_scales=scales)
+        if tap_layers:
+            want, new_kv, want_f = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks], route_log=log, kv_scales=scales,
+                                                     tap_layers=tap_layers)
+            assert torch.isfinite(feats).all()
+            got_f = feats[picks].cpu().numpy()
+            # a feature is a linear image of the same accumulated rounding noise as a logit, but of another size: the
+            # residual stream grows with depth (rms 2.4 after 2 layers, 13 after 29 here) while the logits have rms 1.3.
+            # The tolerance's absolute term, stated for the logits, is scaled by that ratio; the relative term is kept.
+            d_model = cfg["d_model"]
+            rms_logits = float(np.sqrt((want * want).mean()))
+            for j, l in enumerate(tap_layers):
+                w = want_f[..., j * d_model:(j + 1) * d_model]
+                e = np.abs(got_f[..., j * d_model:(j + 1) * d_model] - w)
+                rms_x = float(np.sqrt((w * w).mean()))
+                ratio_f = float((e / (2e-2 * rms_x / rms_logits + 1e-2 * np.abs(w))).max())
+                print("  features after %d layers: rms %.2f, rms err %.3e, max err %.3e, largest error / tolerance %.2f" %
+                      (l, rms_x, np.sqrt((e * e).mean()), e.max(), ratio_f), flush=True)
+                assert ratio_f <= 1.0, (l, ratio_f)
+        else:
+            want, new_kv = of.verify_forward(cfg, w_or, kv_or, tokens[picks], wl.ctx_len[picks], route_log=log, kv_scales=scales)
         got = logits[picks].cpu().numpy()
         if moe_margin is not None:
             # rows whose expert choice the oracle decides by less than the margin (and the rows after them in the
@@ -160,7 +183,8 @@ B32_BLOCK_PICKS = (0, 7, 8, 15, 16, 23, 24, 31)        # first and last batch en
 
 
 def test_llama8b_logits_on_sampled_sequences_and_commit():
-    _check_workload("llama8b_b32_ctx1k-8k_k3", [3], more_picks=B32_BLOCK_PICKS)
+    """...and the multi-layer features a feature-fed draft would be given (the residual stream after layers 2, 16 and 29)."""
+    _check_workload("llama8b_b32_ctx1k-8k_k3", [3], more_picks=B32_BLOCK_PICKS, tap_layers=(2, 16, 29))
 
 
 def test_llama8b_large_batch_aliased_pool_all_draft_lengths():
