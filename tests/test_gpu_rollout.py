@@ -270,7 +270,15 @@ def test_hidden_state_pairs_follow_taken_over_slots_and_a_fused_pair_rollout_dra
         torch.cuda.synchronize()
         assert np.array_equal(d_ph.cpu().numpy(), want)
 
-    cfg_t, cfg_d = si.MODELS["small_bf16"], si.MODELS["draft_fused_small_bf16"]
+    for target_name, draft_name, taps in (("small_bf16", "draft_fused_small_bf16", None), ("small4_bf16", "draft_eagle3_small_bf16", (1, 2, 4))):
+        _drain_fused_pair(rng, target_name, draft_name, taps)
+
+
+def _drain_fused_pair(rng, target_name, draft_name, taps):
+    """taps: the target layers a feature-fed draft is given (then every hidden-state pair is len(taps) * d wide)."""
+    from paper_2604_26779_amd.draft import ContinuousPairRollout
+    from paper_2604_26779_amd.session import VerifySession
+    cfg_t, cfg_d = si.MODELS[target_name], si.MODELS[draft_name]
     slots, n_seqs, k = 4, 10, 3
     ctx0 = rng.integers(2, 60, size=n_seqs).astype(np.int64)
     n_pages = 160
@@ -290,9 +298,9 @@ def test_hidden_state_pairs_follow_taken_over_slots_and_a_fused_pair_rollout_dra
     target = rng.integers(1, 14, size=n_seqs).astype(np.int32)
     prev = torch.from_numpy(rng.integers(0, cfg_t["vocab"], size=n_seqs).astype(np.int32))
     first = torch.from_numpy(rng.integers(0, cfg_t["vocab"], size=n_seqs).astype(np.int32))
-    seq_hidden = torch.from_numpy(rng.standard_normal((n_seqs, 2, cfg_t["d_model"])).astype(np.float32))
+    seq_hidden = torch.from_numpy(rng.standard_normal((n_seqs, 2, cfg_t["d_model"] * (len(taps) if taps else 1))).astype(np.float32))
     roll = ContinuousPairRollout(tsess, dsess, slots, k, torch.arange(slots, dtype=torch.int32), torch.from_numpy(target),
-                                 torch.arange(slots, n_seqs, dtype=torch.int32), prev, first, seq_hidden=seq_hidden)
+                                 torch.arange(slots, n_seqs, dtype=torch.int32), prev, first, seq_hidden=seq_hidden, tap_layers=taps)
     live = torch.zeros(1, dtype=torch.int32, device="cuda")
     steps, taken_over = 0, 0
     while steps < 200:
@@ -319,6 +327,6 @@ def test_hidden_state_pairs_follow_taken_over_slots_and_a_fused_pair_rollout_dra
     assert np.array_equal(roll.gen_len.cpu().numpy(), target) and int(roll.queue_head.item()) == n_seqs - slots
     for st in (tsess.state(), dsess.state()):
         assert np.all(st["ctx_len"][:n_seqs] == 0) and np.all(st["n_pages"][:n_seqs] == 0) and len(st["free_stack"]) == n_pages
-    print("fused pair rollout: %d slots, %d sequences, drained in %d steps, %d tokens" % (slots, n_seqs, steps, int(roll.produced.item())))
+    print("fused pair rollout (%s): %d slots, %d sequences, drained in %d steps, %d tokens" % (draft_name, slots, n_seqs, steps, int(roll.produced.item())))
     tsess.close()
     dsess.close()
