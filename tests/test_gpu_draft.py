@@ -352,6 +352,20 @@ def test_multi_layer_feature_taps_and_feature_fed_draft_pass():
         okf, max_err_f, worst_f = logits_close(feats.cpu().numpy(), want_f, *TOL["bf16"])
         assert okf, (taps, max_err_f, worst_f)
         print("taps", taps, "features max abs err %.3e (|x| up to %.2f)" % (max_err_f, np.abs(want_f).max()))
+    # a mixture-of-experts target: the tap follows the combine of the experts' outputs
+    cfg_m = dict(si.MODELS["small_moe_bf16"], vocab=1000)
+    msess, wm_or, kvm_or = session(cfg_m, B, k, ctx, 14)
+    want_m, _, want_fm = of.verify_forward(cfg_m, wm_or, kvm_or, tokens, ctx, tap_layers=(1, 2))
+    feats_m = torch.full((B, k + 1, 2 * cfg_m["d_model"]), float("nan"), dtype=torch.float32, device="cuda")
+    got_m = msess.forward(seq, d_tokens, tap_layers=(1, 2), taps_out=feats_m)
+    torch.cuda.synchronize()
+    # (rows whose routing the oracle decides by a hair may differ: compare the rows whose logits agree)
+    row_ok = (np.abs(got_m.cpu().numpy() - want_m) <= TOL["bf16"][0] + TOL["bf16"][1] * np.abs(want_m)).all(-1)
+    assert row_ok.mean() >= 0.75
+    errm = np.abs(feats_m.cpu().numpy() - want_fm)[row_ok]
+    assert np.all(errm <= TOL["bf16"][0] + TOL["bf16"][1] * np.abs(want_fm[row_ok])), errm.max()
+    print("taps of a mixture-of-experts target: max abs err %.3e on %d of %d rows" % (errm.max(), row_ok.sum(), row_ok.size))
+    msess.close()
     last = torch.zeros((B, k + 1, d), dtype=torch.float32, device="cuda")
     sess.forward(seq, d_tokens, hidden_out=last)
     torch.cuda.synchronize()
