@@ -194,7 +194,10 @@ spec_status spec_kv_restore(spec_kv* kv, const void* dev_buf, void* stream);
  * aligned; contents need not be preserved between calls.  Query the size again after spec_tune_set.
  * Errors: SPEC_EINVAL (null, B < 1, k < 0, k > SPEC_MAX_DRAFT, workspace too small, kv of another
  * model), SPEC_ENOMEM (the pool cannot hold k+1 more positions for every batch entry),
- * SPEC_EHIP.  Asynchronous on `stream`.
+ * SPEC_EHIP.  Asynchronous on `stream`, with one exception: when the host's bounds on the cache state (kept
+ * without reading the device) no longer show that the new positions fit, the call reads the exact state back once,
+ * which synchronises; under stream capture it returns SPEC_ESTATE instead, with nothing launched (call
+ * spec_kv_get_state before recording, so that the bounds are exact).
  *
  * spec_verify_forward_hidden is the same pass with the hidden states exposed (bf16 models): dev_hidden_out
  * [B, k+1, d_model] fp32 (may be NULL) receives the residual stream after the last layer, before the final norm -

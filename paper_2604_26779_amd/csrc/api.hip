@@ -574,6 +574,12 @@ static spec_status verify_forward_any(spec_model* m, spec_kv* kv, int32_t B, int
     int64_t grow = (int64_t)B * (cdiv(k + 1, SPEC_PAGE_SIZE) + 1);
     if (kv->ub.pages() + grow > kv->n_pages || kv->ub.max_ctx + k + 1 > (int64_t)kv->max_pages * SPEC_PAGE_SIZE) {
         if (kv->device_ahead) {                           // bounds may be stale: refresh them exactly once
+            // ... which reads the device state back and synchronises: not under stream capture (it would end the recording)
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing((hipStream_t)stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) {
+                set_error("spec_verify_forward: the host's bounds on the cache state no longer show that %d more positions fit, and the exact state cannot be read while the stream is being captured: call spec_kv_get_state before recording", k + 1);
+                return SPEC_ESTATE;
+            }
             spec_status st = kv_download(kv, nullptr);
             if (st != SPEC_OK) return st;
         }

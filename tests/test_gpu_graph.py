@@ -64,3 +64,50 @@ def test_replayed_step_equals_eager_step(name):
     with pytest.raises(sv.SpecError):
         sv.spec_graph_capture_begin(None)                                 # the default stream cannot record
     wl.close()
+
+
+def test_forward_under_capture_never_synchronises():
+    """When the host's bounds cannot show that the step fits, an eager call reads the cache state back (a
+    synchronisation); a call on a stream that is being captured must not - it reports SPEC_ESTATE with nothing recorded,
+    the capture stays valid, and after spec_kv_get_state the same step records and replays."""
+    import synth_inputs as si
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = si.MODELS["tiny_fp32"]
+    B, k = 2, 3
+    sess = VerifySession(cfg, si.make_weights(cfg, seed=1, device="cuda"), max_seqs=B, max_ctx_len=64, n_pages=8)
+    sess.pool.normal_()
+    for b in range(B):
+        sess.assign(b, 5, [b])
+    seq = torch.arange(B, dtype=torch.int32, device="cuda")
+    tokens = torch.randint(0, cfg["vocab"], (B, k + 1), dtype=torch.int32, device="cuda")
+    zero = torch.zeros(B, dtype=torch.int32, device="cuda")
+    for _ in range(3):                                  # eager steps that keep one position each: the bounds drift upwards
+        sess.forward(seq, tokens)
+        sess.commit(seq, zero, k)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        sv.spec_graph_capture_begin(side)
+        with pytest.raises(sv.SpecError) as e:
+            sess.forward(seq, tokens, stream=side)
+        assert e.value.status == sv.SPEC_ESTATE
+        graph = sv.spec_graph_capture_end(side)         # the recording is still alive (and empty)
+        sv.spec_graph_destroy(graph)
+    st = sess.state()                                   # exact bounds again
+    assert list(st["ctx_len"][:B]) == [8, 8]
+    with torch.cuda.stream(side):
+        sv.spec_graph_capture_begin(side)
+        logits = sess.forward(seq, tokens, stream=side)
+        graph = sv.spec_graph_capture_end(side)
+        sv.spec_graph_launch(graph, side)
+        side.synchronize()
+    a = logits.clone()
+    sess.commit(seq, zero, k)
+    sess.state()
+    sv.spec_kv_truncate(sess.kv, B, seq, torch.full((B,), 8, dtype=torch.int32, device="cuda"), 0, None)   # back to 8 positions
+    b2 = sess.forward(seq, tokens).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b2)
+    sv.spec_graph_destroy(graph)
+    sess.close()
