@@ -287,7 +287,11 @@ spec_status spec_reject_sample_static(int32_t B, int32_t k, int32_t V, const flo
  * has no entry yet); pages wholly beyond the new length return to the free stack, a sequence's
  * last page first, batch entries in order.  k must be the k of the preceding spec_verify_forward.
  * Outputs (either may be NULL): dev_new_ctx_len [B]; dev_commit_slots [B, k+1] = pool slot of each
- * kept position, -1 for dropped ones.  Asynchronous on `stream`.
+ * kept position, -1 for dropped ones.  A batch entry the step left out - its sequence id out of range or named
+ * twice, or (only possible when a recorded step is replayed over a cache state with fewer free pages than the host
+ * had checked) no page left for its new positions - is not committed: its sequence stays as it was, and it gets
+ * dev_new_ctx_len[b] = -1 and slots of -1; spec_kv_get_state then reports SPEC_EINVAL or SPEC_ENOMEM.
+ * Asynchronous on `stream`.
  */
 spec_status spec_commit_kv(spec_kv* kv, int32_t B, int32_t k, const int32_t* dev_seq_ids,
                            const int32_t* dev_accept_len, int32_t* dev_new_ctx_len, int32_t* dev_commit_slots,

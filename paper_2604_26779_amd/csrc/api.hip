@@ -397,7 +397,7 @@ extern "C" spec_status spec_kv_alloc(const spec_model* m, int32_t max_seqs, int3
     kv->n_pages = n_pages;
     kv->pool = dev_pool;
     kv->state_ints = (size_t)max_seqs * 2 + (size_t)max_seqs * kv->max_pages + (size_t)n_pages + 2;
-    hipError_t e = hipMalloc((void**)&kv->d_state, (kv->state_ints + 3 * (size_t)max_seqs) * sizeof(int32_t));
+    hipError_t e = hipMalloc((void**)&kv->d_state, (kv->state_ints + 4 * (size_t)max_seqs) * sizeof(int32_t));
     if (e != hipSuccess) { set_error("spec_kv_alloc: hipMalloc failed: %s", hipGetErrorString(e)); delete kv; return SPEC_ENOMEM; }
     int32_t* p = kv->d_state;
     kv->d_ctx_len = p; p += max_seqs;
@@ -408,7 +408,8 @@ extern "C" spec_status spec_kv_alloc(const spec_model* m, int32_t max_seqs, int3
     kv->d_error = p; p += 1;
     kv->d_owner = p; p += max_seqs;
     kv->d_entry_seq = p; p += max_seqs;
-    kv->d_entry_tmp = p;
+    kv->d_entry_tmp = p; p += max_seqs;
+    kv->d_starved = p;
     kv->h_ctx_len.assign(max_seqs, 0);
     kv->h_n_held.assign(max_seqs, 0);
     kv->h_page_table.assign((size_t)max_seqs * kv->max_pages, -1);
@@ -417,9 +418,9 @@ extern "C" spec_status spec_kv_alloc(const spec_model* m, int32_t max_seqs, int3
     kv->h_free_count = n_pages;
     kv->device_ahead = false;
     // upload
-    std::vector<int32_t> img(kv->state_ints + 3 * (size_t)max_seqs, 0);
+    std::vector<int32_t> img(kv->state_ints + 4 * (size_t)max_seqs, 0);
     std::fill(img.begin() + kv->state_ints, img.begin() + kv->state_ints + max_seqs, 0x7fffffff);       // d_owner
-    std::fill(img.begin() + kv->state_ints + max_seqs, img.end(), -1);
+    std::fill(img.begin() + kv->state_ints + max_seqs, img.begin() + kv->state_ints + 3 * (size_t)max_seqs, -1);   // entry ids; d_starved stays 0
     std::fill(img.begin() + 2 * max_seqs, img.begin() + 2 * max_seqs + (size_t)max_seqs * kv->max_pages, -1);
     std::copy(kv->h_free_stack.begin(), kv->h_free_stack.end(), img.begin() + 2 * max_seqs + (size_t)max_seqs * kv->max_pages);
     img[kv->state_ints - 2] = (int32_t)n_pages;

@@ -118,6 +118,7 @@ struct spec_kv {
             *d_free_count = nullptr, *d_error = nullptr;
     // behind the bookkeeping (not part of a snapshot): scratch of the id check, and the checked ids of the current step
     int32_t *d_owner = nullptr, *d_entry_seq = nullptr, *d_entry_tmp = nullptr;
+    int32_t* d_starved = nullptr;          // per sequence: its last reservation found no page (cleared by the commit that follows)
     size_t state_ints = 0;
     // host mirror, valid when !device_ahead
     std::vector<int32_t> h_ctx_len, h_n_held, h_page_table, h_free_stack;

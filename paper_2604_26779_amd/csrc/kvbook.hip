@@ -58,7 +58,7 @@ __global__ __launch_bounds__(KVB_THREADS) void kv_reserve_kernel(
     int B, int k, const int32_t* __restrict__ seq_ids, int max_seqs, int max_pages,
     const int32_t* __restrict__ ctx_len, int32_t* __restrict__ n_held, int32_t* __restrict__ page_table,
     const int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count, int32_t* __restrict__ error,
-    int32_t* __restrict__ owner, int32_t* __restrict__ entry_seq)
+    int32_t* __restrict__ owner, int32_t* __restrict__ entry_seq, int32_t* __restrict__ starved)
 {
     __shared__ int lds[KVB_THREADS];
     __shared__ int s_free;
@@ -79,12 +79,19 @@ __global__ __launch_bounds__(KVB_THREADS) void kv_reserve_kernel(
         int avail = s_free;
         __syncthreads();
         if (total > avail) {
-            // not enough pages for this group of entries: nobody grows, the step is flagged
+            // not enough pages for this group of entries: nobody grows, the step is flagged.  An entry that needed a page is
+            // left out of the step like one with a bad id - its rows are not computed, nothing of it is written to the cache
+            // - and its sequence is marked, so that the commit leaves it as it is and reports -1 for it.
             if (threadIdx.x == 0) atomicOr(error, KV_ERR_NOMEM);
+            if (seq >= 0) {
+                starved[seq] = want > 0 ? 1 : 0;
+                if (want > 0) entry_seq[b] = -1;
+            }
         } else {
             for (int j = 0; j < want; ++j)
                 page_table[(int64_t)seq * max_pages + held + j] = free_stack[avail - 1 - off - j];
             if (want > 0) n_held[seq] = held + want;
+            if (seq >= 0) starved[seq] = 0;
             if (threadIdx.x == 0) s_free = avail - total;
         }
         __syncthreads();
@@ -97,7 +104,7 @@ __global__ __launch_bounds__(KVB_THREADS) void kv_commit_kernel(
     int max_pages, int32_t* __restrict__ ctx_len, int32_t* __restrict__ n_held,
     int32_t* __restrict__ page_table, int32_t* __restrict__ free_stack, int32_t* __restrict__ free_count,
     int32_t* __restrict__ error, int32_t* __restrict__ new_ctx_len, int32_t* __restrict__ commit_slots,
-    int32_t* __restrict__ owner, int32_t* __restrict__ clean)
+    int32_t* __restrict__ owner, int32_t* __restrict__ clean, int32_t* __restrict__ starved)
 {
     __shared__ int lds[KVB_THREADS];
     __shared__ int s_free;
@@ -107,6 +114,10 @@ __global__ __launch_bounds__(KVB_THREADS) void kv_commit_kernel(
         int b = base + threadIdx.x;
         int seq = -1, held = 0, keep = 0, release = 0;
         if (b < B) seq = clean[b];
+        if (seq >= 0 && starved[seq]) {                  // its step found no page: nothing was computed for it, nothing is kept
+            starved[seq] = 0;
+            seq = -1;
+        }
         if (seq >= 0) {
             held = n_held[seq];
             int ctx = ctx_len[seq];
@@ -372,7 +383,7 @@ spec_status launch_kv_reserve(spec_kv* kv, int B, int k, const int32_t* dev_seq_
 {
     kv_reserve_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, dev_seq_ids, kv->max_seqs, kv->max_pages, kv->d_ctx_len,
                                                 kv->d_n_held, kv->d_page_table, kv->d_free_stack,
-                                                kv->d_free_count, kv->d_error, kv->d_owner, kv->d_entry_seq);
+                                                kv->d_free_count, kv->d_error, kv->d_owner, kv->d_entry_seq, kv->d_starved);
     SPEC_LAUNCH_CHECK("kv_reserve_kernel");
     return SPEC_OK;
 }
@@ -383,7 +394,7 @@ spec_status launch_kv_commit(spec_kv* kv, int B, int k, const int32_t* dev_seq_i
     kv_commit_kernel<<<1, KVB_THREADS, 0, s>>>(B, k, dev_seq_ids, dev_accept_len, kv->max_seqs, kv->max_pages,
                                                kv->d_ctx_len, kv->d_n_held, kv->d_page_table, kv->d_free_stack,
                                                kv->d_free_count, kv->d_error, dev_new_ctx_len, dev_commit_slots, kv->d_owner,
-                                               kv->d_entry_tmp);
+                                               kv->d_entry_tmp, kv->d_starved);
     SPEC_LAUNCH_CHECK("kv_commit_kernel");
     return SPEC_OK;
 }

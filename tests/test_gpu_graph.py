@@ -111,3 +111,65 @@ def test_forward_under_capture_never_synchronises():
     assert torch.equal(a, b2)
     sv.spec_graph_destroy(graph)
     sess.close()
+
+
+@pytest.mark.parametrize("model", ["tiny_fp32", "small_bf16"])
+def test_replay_over_a_pool_with_too_few_free_pages_leaves_the_starved_sequences_alone(model):
+    """The host checks the page budget when a step is launched; a recorded step replayed after other sequences took the
+    free pages meets the shortage on the device.  The entries that needed a page are then left out of the step like
+    entries with a bad id (rows not computed, nothing written, commit reports -1 and changes nothing), the others step as
+    usual and still equal the eager step, and spec_kv_get_state reports SPEC_ENOMEM once."""
+    import synth_inputs as si
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = si.MODELS[model]
+    B, k = 3, 3
+    sess = VerifySession(cfg, si.make_weights(cfg, seed=2, device="cuda"), max_seqs=4, max_ctx_len=64, n_pages=6)
+    sess.pool.normal_()
+    ctx = [14, 3, 15]                                   # entries 0 and 2 need a second page for 4 more positions, entry 1 does not
+    for b in range(B):
+        sess.assign(b, ctx[b], [b])
+    seq = torch.arange(B, dtype=torch.int32, device="cuda")
+    tokens = torch.randint(0, cfg["vocab"], (B, k + 1), dtype=torch.int32, device="cuda")
+    acc = torch.full((B,), k, dtype=torch.int32, device="cuda")
+    snap = torch.empty(sv.spec_kv_state_bytes(sess.kv), dtype=torch.uint8, device="cuda")
+    sv.spec_kv_snapshot(sess.kv, snap)
+    ref = sess.forward(seq, tokens).clone()             # eager, with pages to spare
+    torch.cuda.synchronize()
+    sv.spec_kv_restore(sess.kv, snap)
+    sess.state()                                        # exact bounds on the host: the recording below must not need the device
+    side = torch.cuda.Stream()
+    buf = sess.step_buffers(B, k)
+    with torch.cuda.stream(side):
+        sv.spec_graph_capture_begin(side)
+        sess.forward(seq, tokens, stream=side)
+        sess.commit(seq, acc, k, stream=side)
+        graph = sv.spec_graph_capture_end(side)
+    free = list(sess.state()["free_stack"])
+    assert len(free) == 3
+    sess.assign(3, 40, free)                            # another sequence takes every free page
+    buf["logits"].fill_(-5.0)
+    sv.spec_graph_launch(graph, side)
+    side.synchronize()
+    with pytest.raises(sv.SpecError) as e:
+        sess.state()
+    assert e.value.status == sv.SPEC_ENOMEM
+    st = sess.state()                                   # the flag is reported once
+    assert list(st["ctx_len"][:4]) == [14, 3 + k + 1, 15, 40] and list(st["n_pages"][:4]) == [1, 1, 1, 3]
+    assert len(st["free_stack"]) == 0
+    assert buf["new_ctx_len"].cpu().tolist() == [-1, 3 + k + 1, -1]
+    slots = buf["commit_slots"].cpu().numpy()
+    assert np.all(slots[0] == -1) and np.all(slots[2] == -1) and np.all(slots[1] >= 0)
+    got = buf["logits"]
+    assert torch.equal(got[1], ref[1]) and torch.isfinite(got).all()
+    # with pages back, the same recording steps every entry again
+    sv.spec_kv_truncate(sess.kv, 1, torch.tensor([3], dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda"), 0, None)
+    sv.spec_kv_truncate(sess.kv, 1, torch.tensor([1], dtype=torch.int32, device="cuda"), torch.full((1,), 3, dtype=torch.int32, device="cuda"), 0, None)
+    sess.state()
+    sv.spec_graph_launch(graph, side)
+    side.synchronize()
+    st = sess.state()
+    assert list(st["ctx_len"][:3]) == [c + k + 1 for c in ctx]
+    assert torch.equal(buf["logits"], ref)
+    sv.spec_graph_destroy(graph)
+    sess.close()
