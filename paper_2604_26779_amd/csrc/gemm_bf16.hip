@@ -654,8 +654,8 @@ static GemmShape gemm_shape(const PackedW& W, int M, bool fused_swiglu)
     // 64 - 2 x 112 workgroups fit the chip at once, 3 x 112 and 4 x 112 do not.
     // 97..128 rows with fp16 activations: one tile of 128 rows x 128 columns with the wavefronts 1 x 4, each its own column
     // block over all four row blocks.  Every weight fragment is then fetched by exactly one wavefront of one workgroup
-    // (the pair of 64-row tiles fetches each twice, which takes up half of a CU's outstanding-request window with
-    // duplicates), at the price of one LDS read per MFMA, which the single fp16 MFMA per fragment leaves room for:
+    // (the pair of 64-row tiles fetches each twice: the second time as an L2 hit, but through the same L1 and memory
+    // pipeline as the weight stream), at the price of one LDS read per MFMA, which the single fp16 MFMA per fragment leaves room for:
     // gate/up 56 -> 50 us, down 31 -> 26 us at the 8B shape.  With hi + lo operands the pair stays ahead.
     if (g.mb == 4 && g.m_tiles == 1 && W.f16 && tune("gemm_one_block") != 0 && W.n_blocks % 4 == 0) {
         g.one_block = true; g.tile_nb = 4; g.n_tiles = W.n_blocks / 4; g.kunit = GEMM_KS * 2;
