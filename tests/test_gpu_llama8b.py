@@ -209,6 +209,12 @@ def test_llama8b_8bit_cache_large_batch_all_layers_distinct():
     _check_workload("llama8b_kv8_b256_ctx2k-16k_k3", [3], picks_for_k=_picks_per_draft_length("llama8b_kv8_b256_ctx2k-16k_k3", (3,)))
 
 
+def test_llama8b_8bit_matrices_and_cache_large_batch():
+    """B = 256 with E4M3 matrices and the E4M3 cache: the 256-row x 256-column tiles with 8-bit weights at the full K and
+    N of the 8B shape (the small-shape tests cover every tile shape, this one the sizes the benchmark runs)."""
+    _check_workload("llama8b_w8kv8_b256_ctx2k-16k_k3", [3], picks_for_k=_picks_per_draft_length("llama8b_w8kv8_b256_ctx2k-16k_k3", (3,)))
+
+
 MOE_PICKS = (3, 17, 29, 40, 55, 64, 78, 99, 110, 127)
 
 
