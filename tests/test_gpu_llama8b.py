@@ -228,19 +228,22 @@ def test_moe_slice_full_size_8bit_matrices_and_cache():
     _check_workload("moe235b_slice_w8kv8_b128_ctx4k-32k_k3", [3], moe_margin=1e-3, more_picks=MOE_PICKS)
 
 
-def test_draft_pair_full_size_on_sampled_sequences():
+@pytest.mark.parametrize("name", ["draft_pair_b64_ctx4096_k5", "draft_pair_eagle3_b64_ctx4096_k5"])
+def test_draft_pair_full_size_on_sampled_sequences(name):
     """Single-layer draft (8B widths, tied 128256-token head) run 5 times + 8B-shaped verify, B = 64, contexts 4096:
     the whole step on the GPU, then for two sampled sequences the oracle's draft loop, verify forward and rejection
     sampling on the same inputs (a sequence's results depend only on its own rows, cache and random-counter index b,
-    so the oracle is given the sequence's batch index through a padded batch)."""
+    so the oracle is given the sequence's batch index through a padded batch).  The second workload's draft is fed
+    multi-layer features: its first pass projects them, the chained passes take its own state."""
     from oracle import draft as oracle_draft
     from oracle import sampler as oracle_sampler
     from paper_2604_26779_amd.workloads import DraftPairWorkload
-    wl = DraftPairWorkload("draft_pair_b64_ctx4096_k5")
+    wl = DraftPairWorkload(name)
     cfg_t, cfg_d, B, k, T = wl.cfg, wl.draft_cfg, wl.B, wl.k, wl.wl["temperature"]
     V = cfg_t["vocab"]
     seed, step = wl.seed, 2
-    drafts = wl.loop.run(wl.seq_ids, wl.pending, wl.q, T, seed, step)
+    feats = None if wl.pending_hidden is None else wl.pending_hidden.cpu().numpy()
+    drafts = wl.loop.run(wl.seq_ids, wl.pending, wl.q, T, seed, step, pending_hidden=wl.pending_hidden)
     wl.tokens[:, 1:] = drafts
     logits, n, out = wl.sess.step(wl.seq_ids, wl.tokens, wl.q, drafts, T, seed, step)
     torch.cuda.synchronize()
@@ -261,8 +264,16 @@ def test_draft_pair_full_size_on_sampled_sequences():
         x_or = np.zeros(k, dtype=np.int32)
         q_or = np.zeros((k, V), dtype=np.float32)
         feed, kv_run, clen, fragile = pending[b:b + 1], kv_d, np.array([ctx - 1]), False
+        own = None
         for i in range(k):
-            lg, new_kv = of.verify_forward(cfg_d, w_d, kv_run, feed, clen)
+            if feats is None:
+                lg, new_kv = of.verify_forward(cfg_d, w_d, kv_run, feed, clen)
+            elif i == 0:
+                lg, new_kv, hid = of.verify_forward(cfg_d, w_d, kv_run, feed, clen, features_in=feats[b:b + 1], return_hidden=True)
+                own = hid[:, -1:, :]
+            else:
+                lg, new_kv, hid = of.verify_forward(cfg_d, w_d, kv_run, feed, clen, hidden_in=own, return_hidden=True)
+                own = hid[:, -1:, :]
             kv_run = [[(np.concatenate([kv_run[0][0][0], new_kv[0][0][0]]), np.concatenate([kv_run[0][0][1], new_kv[0][1][0]]))]]
             clen = clen + feed.shape[1]
             pad = np.zeros((b + 1, V), dtype=np.float32)
