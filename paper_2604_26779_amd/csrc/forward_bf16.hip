@@ -1,6 +1,7 @@
 // bf16 verify forward: orchestration and the small kernels between the GEMMs and the attention.
 //
-// Per layer (residual stream x in fp32, every GEMM input as hi + lo bf16 pairs in operand order "xp"):
+// Per layer (residual stream x in fp32; every GEMM input in operand order "xp", as hi + lo bf16 pairs or as one fp16
+// value, whichever its matrix was tiled for, see operand.h):
 //   xp_h  = RMSNorm(x) * g                         (fused into the kernel that last touched x)
 //   part  = xp_h W_qkv^T                           gemm, split-K slices
 //   q, K, V = rotary(sum part)                     qkv_rope_kernel: q -> bf16 rows, K/V -> paged cache
@@ -8,7 +9,11 @@
 //   part  = xp_a W_o^T ; x += sum part ; xp_h = RMSNorm(x) * g2        residual_rmsnorm_kernel
 //   part  = xp_h [W_g; W_u]^T ; xp_f = silu(gate) * up                  swiglu_pack_kernel
 //   part  = xp_f W_d^T ; x += sum part ; xp_h = RMSNorm(x) * g_next     residual_rmsnorm_kernel
+//   (gate/up normally ends in the fused SwiGLU epilogue of the GEMM instead of swiglu_pack_kernel)
 // logits = xp_h W_head^T (fp32, written in place by the GEMM).
+// Around that: a draft model's input fusion (fuse_input_kernel; with multi-layer features pack_rows_kernel and the
+// w_fc GEMM before it), the hidden-state and feature outputs (a copy of x after the last layer, tap_copy_kernel after
+// the tapped ones), and the mixture-of-experts feed-forward (moe.hip) in place of the dense one.
 #include <algorithm>
 
 #include "common.h"
