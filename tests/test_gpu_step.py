@@ -596,3 +596,57 @@ def test_replay_from_a_longer_cache_state_than_recorded_is_reported():
     finally:
         sv.spec_tune_set("attn_chunk_pages", before)
         sess.close()
+
+
+def test_long_random_walk_of_the_bookkeeping_against_the_oracle_book():
+    """Sixty steps over 300 sequences with a different random subset, order, draft length and accept lengths each
+    time, roll-backs to shorter lengths and to zero in between: after every call the lengths and slots the kernels
+    report equal the oracle book's, and the whole state (page lists and the free stack, entry by entry) is compared
+    every few steps.  More than 256 entries per call take the bookkeeping workgroup through several passes."""
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.session import VerifySession
+    cfg = si.MODELS["tiny_fp32"]
+    S, max_ctx, n_pages = 300, 160, 2600
+    rng = np.random.default_rng(2024)
+    sess = VerifySession(cfg, si.make_weights(cfg, seed=1, device="cuda"), max_seqs=S, max_ctx_len=max_ctx, n_pages=n_pages)
+    sess.pool.normal_()
+    book = oracle_commit.KVBook(n_pages, si.PAGE_SIZE)
+    order = rng.permutation(n_pages)
+    at = 0
+    for s in range(S):
+        c = int(rng.integers(0, 40))
+        need = -(-c // si.PAGE_SIZE)
+        pages = [int(p) for p in order[at:at + need]]
+        at += need
+        sess.assign(s, c, pages)
+        book.assign(s, c, pages)
+    all_ids = np.arange(S)
+    for step in range(60):
+        k = int(rng.integers(0, 4))
+        room = np.array([s for s in range(S) if book.ctx_len[s] + k + 1 <= max_ctx])
+        B = int(rng.integers(1, len(room) + 1))
+        ids = rng.permutation(room)[:B].astype(np.int32)
+        tokens = torch.randint(0, cfg["vocab"], (B, k + 1), dtype=torch.int32, device="cuda")
+        d_ids = torch.from_numpy(ids).cuda()
+        logits = sess.forward(d_ids, tokens)
+        n = rng.integers(0, k + 1, size=B).astype(np.int32)
+        book.reserve([int(s) for s in ids], k)
+        new_len, slots = sess.commit(d_ids, torch.from_numpy(n).cuda(), k)
+        want_len, want_slots = book.commit([int(s) for s in ids], n, k)
+        assert new_len.cpu().numpy().tolist() == want_len and slots.cpu().numpy().tolist() == want_slots, step
+        if step % 3 == 2:                                   # roll some back: a little, a lot, or to nothing
+            Bt = int(rng.integers(1, S + 1))
+            tids = rng.permutation(S)[:Bt].astype(np.int32)
+            cur = np.array([book.ctx_len[int(s)] for s in tids])
+            kind = rng.integers(0, 3, size=Bt)
+            target = np.where(kind == 0, np.maximum(cur - rng.integers(0, 5, size=Bt), 0), np.where(kind == 1, cur // 2, 0)).astype(np.int32)
+            out = torch.zeros(Bt, dtype=torch.int32, device="cuda")
+            sv.spec_kv_truncate(sess.kv, Bt, torch.from_numpy(tids).cuda(), torch.from_numpy(target).cuda(), 0, out)
+            assert out.cpu().numpy().tolist() == book.truncate([int(s) for s in tids], target), step
+        if step % 5 == 4 or step == 59:
+            assert torch.isfinite(logits).all()
+            _check_state(sess, book, all_ids)
+    held = sum(len(book.pages[s]) for s in range(S))
+    assert held + len(book.free) == n_pages
+    print("bookkeeping walk: %d pages held, %d free after 60 steps; longest sequence %d" % (held, len(book.free), max(book.ctx_len[s] for s in range(S))))
+    sess.close()
