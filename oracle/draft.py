@@ -19,7 +19,8 @@ from . import forward as _forward
 from . import sampler as _sampler
 
 
-def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, step, pending_hidden=None):
+def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, step, pending_hidden=None, token_map=None,
+               v_full=None):
     """pending [B, P] int tokens not yet in the draft's cache, ctx_len [B] its cached length.
 
     A draft that takes hidden states (cfg fuse_hidden) gets pending_hidden [B, P, d]: for each pending token the
@@ -27,6 +28,10 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
     draft's own hidden state of the position before it (the last row of the previous iteration), as EAGLE- and
     MTP-style drafters chain their predictions.  A draft with cfg fuse_taps = n takes pending_hidden [B, P, n*d], the
     verifier's multi-layer features, through its w_fc in the first iteration; the chained ones are d wide as before.
+
+    token_map [V_d] + v_full: a draft whose head covers a subset of the target's vocabulary (cfg head_vocab = V_d; its
+    embedding still covers all of it, its inputs being target tokens): drafts are target ids and q is laid out over
+    the target's v_full entries (``sampler.draft_sample_mapped``).
 
     Returns (drafts [B, k] int32, q [B, k, V] fp32, kv_ctx grown by the fed positions, new_len [B],
     keys [B, k, 2] = winning and runner-up key of every draw).
@@ -36,7 +41,7 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
     ctx_len = np.asarray(ctx_len, dtype=np.int64).copy()
     kv = [[(np.asarray(K, dtype=np.float64), np.asarray(V, dtype=np.float64)) for (K, V) in per_seq] for per_seq in kv_ctx]
     drafts = np.zeros((B, k), dtype=np.int32)
-    q = np.zeros((B, k, cfg["vocab"]), dtype=np.float32)
+    q = np.zeros((B, k, int(v_full) if token_map is not None else cfg["vocab"]), dtype=np.float32)
     keys = np.zeros((B, k, 2), dtype=np.float64)
     feed = pending
     fused = bool(cfg.get("fuse_hidden", 0))
@@ -56,7 +61,10 @@ def draft_loop(cfg, weights, kv_ctx, pending, ctx_len, k, temperature, seed, ste
                 K, V = kv[layer][b]
                 kv[layer][b] = (np.concatenate([K, new_kv[layer][0][b]]), np.concatenate([V, new_kv[layer][1][b]]))
         ctx_len += feed.shape[1]
-        x, qi, keys[:, i, :] = _sampler.draft_sample(logits[:, -1, :].astype(np.float32), temperature, seed, step, i, debug=True)
+        if token_map is not None:
+            x, qi, keys[:, i, :] = _sampler.draft_sample_mapped(logits[:, -1, :].astype(np.float32), token_map, v_full, temperature, seed, step, i, debug=True)
+        else:
+            x, qi, keys[:, i, :] = _sampler.draft_sample(logits[:, -1, :].astype(np.float32), temperature, seed, step, i, debug=True)
         drafts[:, i] = x
         q[:, i, :] = qi
         feed = x.reshape(B, 1)
@@ -78,7 +86,7 @@ def next_pending_hidden(pending_hidden, target_hidden, accept_len):
 
 
 def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperature, seed, n_steps, pending_hidden=None,
-            tap_layers=None):
+            tap_layers=None, token_map=None):
     """Several speculation steps in a row (the decode phase of a rollout, Section 2.1-2.2): every step drafts k
     tokens with the draft model, verifies them with the target, keeps the accepted prefix and emits one more
     token, which is the first input of the next step.
@@ -103,7 +111,7 @@ def rollout(cfg_t, w_t, cfg_d, w_d, kv_t, kv_d, prev, t0, ctx_len, k, temperatur
         pending = np.stack([prev, t0], axis=1)
         fused = bool(cfg_d.get("fuse_hidden", 0))
         drafts, q, kv_d_grown, _, _ = draft_loop(cfg_d, w_d, kv_d, pending, ctx_len - 1, k, temperature, seed, s,
-                                                 pending_hidden if fused else None)
+                                                 pending_hidden if fused else None, token_map=token_map, v_full=cfg_t["vocab"])
         tokens = np.concatenate([t0[:, None], drafts], axis=1).astype(np.int32)
         if fused and tap_layers is not None:
             logits, new_kv, hid_t = _forward.verify_forward(cfg_t, w_t, kv_t, tokens, ctx_len, tap_layers=tap_layers)

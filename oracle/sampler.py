@@ -113,3 +113,20 @@ def draft_sample(logits, temperature, seed, step, row, debug=False):
     if debug:
         return tokens, q, keys
     return tokens, q
+
+
+def draft_sample_mapped(logits, token_map, v_full, temperature, seed, step, row, debug=False):
+    """The proposal of a draft model whose output head covers a subset of the target's vocabulary (the reduced draft
+    vocabulary of the EAGLE-3 design: the head holds the V_d most useful tokens, token_map [V_d] gives their ids in the
+    target's vocabulary, strictly increasing).  logits [B, V_d] -> (tokens [B] as target ids, q [B, v_full] fp32): the
+    draft's own softmax and draw (``draft_sample``), q laid out over the target's vocabulary with zeros outside the
+    subset - the form the verifier takes."""
+    token_map = np.asarray(token_map, dtype=np.int64)
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    assert logits.shape[1] == token_map.shape[0] and np.all(np.diff(token_map) > 0) and 0 <= token_map[0] and token_map[-1] < v_full
+    out = draft_sample(logits, temperature, seed, step, row, debug=debug)
+    x_d, q_d = out[0], out[1]
+    q = np.zeros((logits.shape[0], int(v_full)), dtype=np.float32)
+    q[:, token_map] = q_d
+    tokens = token_map[x_d].astype(np.int32)
+    return (tokens, q, out[2]) if debug else (tokens, q)

@@ -282,3 +282,50 @@ def test_feature_draft_loop_projects_the_first_pass_only_and_the_rollout_carries
         # rows of one-sequence calls use random-stream row 0: only sequence 0 is comparable draw for draw
         if b == 0:
             assert np.array_equal(d1[0], hist[1]["drafts"][0])
+
+
+def test_reduced_draft_vocabulary_is_still_lossless():
+    """A draft head over a subset of the target's vocabulary (the EAGLE-3 design's reduced draft vocabulary): with the
+    identity map the mapped draw is the plain one; otherwise q lives on the subset (zeros elsewhere, sums to 1), the
+    drafted tokens are target ids inside the subset and follow q (chi-square), and drafts verified by the rejection
+    oracle still give a first emitted token distributed as the target's p over the WHOLE vocabulary - tokens the draft
+    can never propose come out of the residual - with the closed-form mean accept length."""
+    V, Vd, k, N = 14, 6, 3, 400_000
+    rng = np.random.default_rng(18)
+    tmap = np.sort(rng.permutation(V)[:Vd])
+    target = (rng.standard_normal((k + 1, V)) * 1.2).astype(np.float32)
+    draft_logits = (target[:k][:, tmap] + rng.standard_normal((k, Vd)) * 0.7).astype(np.float32)
+    # identity map
+    lg = (rng.standard_normal((5, V)) * 2).astype(np.float32)
+    x0, q0 = sampler.draft_sample(lg, 0.8, 3, 1, 2)
+    x1, q1 = sampler.draft_sample_mapped(lg, np.arange(V), V, 0.8, 3, 1, 2)
+    assert np.array_equal(x0, x1) and np.array_equal(q0, q1)
+    drafts = np.zeros((N, k), dtype=np.int32)
+    q = np.zeros((N, k, V), dtype=np.float32)
+    for i in range(k):
+        drafts[:, i], q[:, i, :] = sampler.draft_sample_mapped(np.broadcast_to(draft_logits[i], (N, Vd)).copy(), tmap, V, 1.0, 21, 9, i)
+    outside = np.setdiff1d(np.arange(V), tmap)
+    assert np.all(q[:, :, outside] == 0) and np.max(np.abs(q.sum(-1) - 1)) < 1e-6 and np.all(np.isin(drafts, tmap))
+    qd = scipy_softmax(draft_logits.astype(np.float64), axis=-1)
+    obs = np.bincount(drafts[:, 0], minlength=V)[tmap].astype(np.float64)
+    chi2 = float(((obs - qd[0] * N) ** 2 / (qd[0] * N)).sum())
+    assert stats.chi2.sf(chi2, df=Vd - 1) > 1e-4
+    n, out = sampler.reject_sample(np.broadcast_to(target, (N, k + 1, V)).copy(), q, drafts, 1.0, 21, 9)
+    p = scipy_softmax(target.astype(np.float64), axis=-1)
+    obs = np.bincount(out[:, 0], minlength=V).astype(np.float64)
+    chi2 = float(((obs - p[0] * N) ** 2 / (p[0] * N)).sum())
+    assert stats.chi2.sf(chi2, df=V - 1) > 1e-4
+    assert obs[outside].sum() > 0.5 * N * p[0][outside].sum()                      # tokens outside the subset do get emitted
+    beta = np.minimum(p[:k], q[0].astype(np.float64)).sum(axis=-1)
+    alpha = 1 + beta[0] + beta[0] * beta[1] + beta[0] * beta[1] * beta[2]
+    assert abs((n + 1).mean() - alpha) < 0.01
+    # the loop with a reduced head: drafts are target ids, q is as wide as the target's vocabulary
+    cfg = dict(CFG, tied_head=0, head_vocab=Vd)
+    w = _weights(cfg, seed=5)
+    w["head"] = np.random.default_rng(1).standard_normal((Vd, cfg["d_model"])) * 0.3
+    tm = np.sort(np.random.default_rng(2).permutation(cfg["vocab"])[:Vd])
+    B, C = 2, 4
+    kv = [[(rng.standard_normal((C, 2, 16)), rng.standard_normal((C, 2, 16))) for _ in range(B)] for _ in range(cfg["n_layers"])]
+    pending = rng.integers(0, cfg["vocab"], size=(B, 2)).astype(np.int32)
+    d_, q_, _, _, _ = od.draft_loop(cfg, w, kv, pending, np.full(B, C), 3, 0.9, 5, 0, token_map=tm, v_full=cfg["vocab"])
+    assert q_.shape == (B, 3, cfg["vocab"]) and np.all(np.isin(d_, tm)) and np.max(np.abs(q_.sum(-1) - 1)) < 1e-6
