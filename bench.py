@@ -411,7 +411,7 @@ def main():
         # sustained rollout: consecutive steps, each feeding the next on the device (no cache restore, no host sync)
         from paper_2604_26779_amd.draft import RolloutLoop
         S = args.rollout_steps
-        roll = RolloutLoop(wl.sess, wl.dsess, B, k, tap_layers=wl.tap_layers)
+        roll = RolloutLoop(wl.sess, wl.dsess, B, k, tap_layers=wl.tap_layers, token_map=wl.token_map)
         acc_s = torch.zeros((S, B), dtype=torch.int32, device="cuda")
         times = []
         for rep in range(2):                      # first repetition warms up

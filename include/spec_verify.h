@@ -80,6 +80,9 @@ typedef struct {
     int32_t w_dtype;           /* 0: the matrices are `dtype`; SPEC_FP8_E4M3: 8-bit matrices with one scale per output row */
     int32_t fuse_taps;         /* 0, or 1..SPEC_MAX_TAPS with fuse_hidden: the hidden-state input can also come as that many
                                   hidden states side by side (spec_verify_forward_features), projected by w_fc */
+    int32_t head_vocab;        /* 0: the output head has `vocab` rows; else its number of rows (untied heads only): a draft
+                                  model that proposes from a subset of the vocabulary (spec_draft_sample_mapped); the
+                                  embedding still has `vocab` rows and the logits are [B, k+1, head_vocab] */
 } spec_model_desc;
 
 typedef struct spec_model spec_model;
@@ -98,7 +101,7 @@ int32_t spec_model_weight_count(const spec_model_desc* desc);
  *              ffn_norm [d], wg [ffn, d], wu [ffn, d], wd [d, ffn];
  *              with n_experts > 0 instead: wg [E, Fe, d], wu [E, Fe, d], wd [E, d, Fe] (the experts stacked,
  *              Fe = expert_ffn_dim), then router [E, d];
- *   final_norm [d]; head [vocab, d] unless tied_head;
+ *   final_norm [d]; head [vocab, d] ([head_vocab, d] if that is set) unless tied_head;
  *   with fuse_hidden: w_fuse [d, 2d] (columns 0..d-1 meet the embedding half), fuse_e_norm [d], fuse_h_norm [d];
  *   with fuse_taps = n: w_fc [d, n*d] (columns j*d .. (j+1)*d-1 meet the j-th hidden state);
  *   with w_dtype = SPEC_FP8_E4M3, after all of the above: the fp32 scales [out_features] of wq, wk, wv, wo, wg, wu, wd
@@ -321,6 +324,23 @@ spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int
                               float temperature, uint64_t seed, uint64_t step, int32_t row,
                               int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
                               float* dev_q, int64_t q_row_stride, void* dev_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same for a draft model whose head covers a subset of the target's vocabulary (the reduced draft vocabulary of the
+ * EAGLE-3 design, Section 2.3: a head of the V_d most useful tokens is a quarter of the bytes and of the sampling work
+ * of a 128k one).  dev_logits rows have V_d entries; dev_token_map [V_d] holds their ids in the target's vocabulary,
+ * strictly increasing, all below V_full.  q = softmax over the V_d entries, written into rows of V_full entries
+ * (q_row_stride >= V_full) at the mapped positions with zeros everywhere else - the [B, k, V_full] array
+ * spec_reject_sample takes, which then resamples tokens outside the subset from the target's own probabilities; the
+ * tokens written are target ids.  Draw and random numbers as spec_draft_sample, v counting draft entries.
+ * Errors as spec_draft_sample; the map's contents are not checked (an id outside [0, V_full) would be written out of
+ * the row).
+ */
+spec_status spec_draft_sample_mapped(int32_t B, int32_t V_d, const float* dev_logits, int64_t logits_row_stride,
+                                     float temperature, uint64_t seed, uint64_t step, int32_t row,
+                                     int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
+                                     float* dev_q, int64_t q_row_stride, const int32_t* dev_token_map, int32_t V_full,
+                                     void* dev_workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Roll a cache back (the draft's cache after verification keeps only what the verifier kept): batch entry b

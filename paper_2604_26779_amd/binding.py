@@ -24,7 +24,7 @@ EXPORTS = [
     "spec_kv_alloc", "spec_kv_free", "spec_kv_set_scales", "spec_kv_block_offset", "spec_kv_block_base", "spec_kv_seq_assign",
     "spec_kv_get_state", "spec_kv_max_pages_per_seq", "spec_kv_state_bytes", "spec_kv_snapshot", "spec_kv_restore",
     "spec_verify_workspace_bytes", "spec_verify_forward", "spec_verify_forward_hidden", "spec_verify_forward_taps", "spec_verify_forward_features", "spec_next_step_hidden", "spec_sample_workspace_bytes", "spec_reject_sample", "spec_reject_sample_static",
-    "spec_commit_kv", "spec_draft_sample", "spec_draft_sample_workspace_bytes", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_rollout_pending", "spec_rollout_pending_hidden", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
+    "spec_commit_kv", "spec_draft_sample", "spec_draft_sample_mapped", "spec_draft_sample_workspace_bytes", "spec_kv_truncate", "spec_next_step_inputs", "spec_ngram_draft", "spec_ngram_append", "spec_rollout_retire", "spec_rollout_compact", "spec_rollout_pending", "spec_rollout_pending_hidden", "spec_tune_set", "spec_tune_get", "spec_profile_class_count", "spec_profile_class_name",
     "spec_profile_begin", "spec_profile_end", "spec_graph_capture_begin", "spec_graph_capture_end", "spec_graph_launch",
     "spec_graph_destroy", "spec_calib_read", "spec_calib_copy",
 ]
@@ -42,7 +42,7 @@ class spec_model_desc(ctypes.Structure):
                [("rope_theta", ctypes.c_float), ("rms_eps", ctypes.c_float), ("dtype", ctypes.c_int32),
                 ("tied_head", ctypes.c_int32), ("n_experts", ctypes.c_int32), ("top_k", ctypes.c_int32),
                 ("expert_ffn_dim", ctypes.c_int32), ("fuse_hidden", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("w_dtype", ctypes.c_int32),
-                ("fuse_taps", ctypes.c_int32)]
+                ("fuse_taps", ctypes.c_int32), ("head_vocab", ctypes.c_int32)]
 
 
 _lib = None
@@ -86,6 +86,7 @@ def lib():
             "spec_reject_sample_static": (i32, [i32, i32, i32, vp, vp, vp, f32, u64, u64, vp, vp, vp, vp]),
             "spec_commit_kv": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
             "spec_draft_sample": (i32, [i32, i32, vp, i64, f32, u64, u64, i32, vp, i32, vp, i32, vp, i64, vp, sz, vp]),
+            "spec_draft_sample_mapped": (i32, [i32, i32, vp, i64, f32, u64, u64, i32, vp, i32, vp, i32, vp, i64, vp, i32, vp, sz, vp]),
             "spec_draft_sample_workspace_bytes": (sz, [i32]),
             "spec_kv_truncate": (i32, [vp, i32, vp, vp, i32, vp, vp]),
             "spec_next_step_inputs": (i32, [i32, i32, vp, vp, vp, vp, vp]),
@@ -156,6 +157,7 @@ def make_desc(cfg):
     d.n_experts, d.top_k, d.expert_ffn_dim = (int(cfg.get(n, 0)) for n in ("n_experts", "top_k", "expert_ffn_dim"))
     d.fuse_hidden = int(cfg.get("fuse_hidden", 0))
     d.fuse_taps = int(cfg.get("fuse_taps", 0))
+    d.head_vocab = int(cfg.get("head_vocab", 0))
     d.kv_dtype = {None: 0, "fp8_e4m3": SPEC_FP8_E4M3}[cfg.get("kv_dtype")]
     d.w_dtype = {None: 0, "fp8_e4m3": SPEC_FP8_E4M3}[cfg.get("w_dtype")]
     return d
@@ -314,6 +316,20 @@ def spec_draft_sample(B, V, logits, logits_row_stride, temperature, seed, step, 
     _check(lib().spec_draft_sample(B, V, _addr(logits), int(logits_row_stride), float(temperature), int(seed), int(step),
                                    int(row), _addr(tokens_a), int(stride_a), _addr(tokens_b), int(stride_b), _addr(q),
                                    int(q_row_stride), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def spec_draft_sample_mapped(B, V_d, logits, logits_row_stride, temperature, seed, step, row, tokens_a, stride_a, tokens_b, stride_b,
+                             q, q_row_stride, token_map, V_full, stream=None, workspace=None):
+    """As spec_draft_sample for a draft head over a subset of the vocabulary: token_map [V_d] int32 device tensor of
+    target ids, q rows V_full wide."""
+    if workspace is None:
+        if B not in _draft_ws:
+            _draft_ws[B] = torch.empty(spec_draft_sample_workspace_bytes(B), dtype=torch.uint8, device="cuda")
+        workspace = _draft_ws[B]
+    _check(lib().spec_draft_sample_mapped(B, V_d, _addr(logits), int(logits_row_stride), float(temperature), int(seed), int(step),
+                                          int(row), _addr(tokens_a), int(stride_a), _addr(tokens_b), int(stride_b), _addr(q),
+                                          int(q_row_stride), _ptr(token_map), int(V_full), _ptr(workspace), workspace.numel(),
+                                          _stream(stream)))
 
 
 def spec_kv_truncate(kv, B, seq_ids, lengths, delta, new_len, stream=None):

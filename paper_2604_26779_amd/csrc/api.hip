@@ -173,6 +173,10 @@ static spec_status check_desc(const spec_model_desc& d)
             return SPEC_EUNSUPPORTED;
         }
     }
+    if (d.head_vocab < 0 || (d.head_vocab > 0 && d.tied_head)) {
+        set_error("spec_model_create: head_vocab must be 0 or the row count of an untied head");
+        return SPEC_EINVAL;
+    }
     if (d.fuse_taps < 0 || d.fuse_taps > SPEC_MAX_TAPS || (d.fuse_taps && !d.fuse_hidden)) {
         set_error("spec_model_create: fuse_taps must be 0 .. %d and needs fuse_hidden", SPEC_MAX_TAPS);
         return SPEC_EINVAL;
@@ -212,7 +216,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         const int L = d.n_layers, D = d.d_model, F = d.ffn_dim;
         const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim;
         const int E = d.n_experts, Fe = d.expert_ffn_dim;
-        m->arena_bytes = (size_t)L * (w8_packed_bytes(nq + 2 * nkv, D) + w8_packed_bytes(D, nq)) + w8_packed_bytes(d.vocab, D);
+        m->arena_bytes = (size_t)L * (w8_packed_bytes(nq + 2 * nkv, D) + w8_packed_bytes(D, nq)) + w8_packed_bytes(head_rows(d), D);
         if (E > 0)       // every expert's region (codes, then scales) on its own; the router stays a bf16 matrix
             m->arena_bytes += (size_t)L * ((size_t)E * (w8_packed_bytes(2 * Fe, D) + w8_packed_bytes(D, Fe)) + align_up(bf16_packed_elems(E, D) * sizeof(bf16_t), 256));
         else
@@ -264,7 +268,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
                 if (st == SPEC_OK) st = pack8({m->layer_w(l, 8)}, {m->w_scale(l, 6)}, {D}, F, &m->wd[l], f16_mask & 4);
             }
         }
-        if (st == SPEC_OK) st = pack8({m->head_w()}, {m->head_scale()}, {d.vocab}, D, &m->head, f16_mask & 8);
+        if (st == SPEC_OK) st = pack8({m->head_w()}, {m->head_scale()}, {head_rows(d)}, D, &m->head, f16_mask & 8);
         if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }
         if (st != SPEC_OK) { (void)hipFree(m->arena); delete m; return st; }
     } else if (desc->dtype == SPEC_BF16) {
@@ -276,7 +280,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
         elems += (size_t)L * (bf16_packed_elems(nq + 2 * nkv, D) + bf16_packed_elems(D, nq));
         if (E > 0) elems += (size_t)L * ((size_t)E * (bf16_packed_elems(2 * Fe, D) + bf16_packed_elems(D, Fe)) + bf16_packed_elems(E, D));
         else elems += (size_t)L * (bf16_packed_elems(2 * F, D) + bf16_packed_elems(D, F));
-        elems += bf16_packed_elems(d.vocab, D);
+        elems += bf16_packed_elems(head_rows(d), D);
         if (d.fuse_hidden) elems += bf16_packed_elems(D, 2 * D);
         if (d.fuse_taps) elems += bf16_packed_elems(D, d.fuse_taps * D);
         m->arena_bytes = elems * sizeof(bf16_t);
@@ -318,7 +322,7 @@ extern "C" spec_status spec_model_create(const spec_model_desc* desc, const void
                 if (st == SPEC_OK) st = pack({m->layer_w(l, 8)}, {D}, F, &m->wd[l], f16_mask & 4);
             }
         }
-        if (st == SPEC_OK) st = pack({m->head_w()}, {d.vocab}, D, &m->head, f16_mask & 8);
+        if (st == SPEC_OK) st = pack({m->head_w()}, {head_rows(d)}, D, &m->head, f16_mask & 8);
         if (st == SPEC_OK && d.fuse_hidden) st = pack({m->fuse_w(0)}, {D}, 2 * D, &m->wfuse, false);
         if (st == SPEC_OK && d.fuse_taps) st = pack({m->fuse_w(3)}, {D}, d.fuse_taps * D, &m->wfc, false);
         if (st == SPEC_OK && hipDeviceSynchronize() != hipSuccess) { set_error("spec_model_create: weight tiling failed on the device"); st = SPEC_EHIP; }

@@ -80,6 +80,9 @@ struct PackedW {
 
 }  // namespace specv
 
+// rows of the output head (and entries of a logits row)
+inline int head_rows(const spec_model_desc& d) { return d.head_vocab > 0 ? d.head_vocab : d.vocab; }
+
 struct spec_model {
     spec_model_desc desc;
     int device = 0;

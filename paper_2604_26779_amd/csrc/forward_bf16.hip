@@ -565,7 +565,7 @@ spec_status bf16_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32
             return SPEC_EHIP;
         }
     }
-    if ((st = launch_gemm_bf16(mdl->head, xp_h, M, dev_logits, d.vocab, 1, false, s)) != SPEC_OK) return st;
+    if ((st = launch_gemm_bf16(mdl->head, xp_h, M, dev_logits, head_rows(d), 1, false, s)) != SPEC_OK) return st;
     prof_mark(PC_GEMM_HEAD, s);
     SPEC_LAUNCH_CHECK("bf16 forward");
     return SPEC_OK;

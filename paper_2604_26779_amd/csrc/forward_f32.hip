@@ -243,7 +243,7 @@ spec_status f32_forward(spec_model* mdl, spec_kv* kv, int B, int k, const int32_
         gemm(w.act, W(8), M, D, F, w.x, D, true, s);
     }
     f32_rmsnorm_kernel<<<M, 256, 0, s>>>(w.x, (const float*)mdl->final_norm(), D, d.rms_eps, w.h);
-    gemm(w.h, (const float*)mdl->head_w(), M, d.vocab, D, dev_logits, d.vocab, false, s);
+    gemm(w.h, (const float*)mdl->head_w(), M, head_rows(d), D, dev_logits, head_rows(d), false, s);
     SPEC_LAUNCH_CHECK("fp32 forward");
     return SPEC_OK;
 }

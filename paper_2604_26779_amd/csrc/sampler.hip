@@ -54,9 +54,18 @@ __device__ inline void part_groups(int V, int part, int* g0, int* g1)
 // fp64 instructions per vocabulary entry of the B rows that draw, 50 per entry of the statistics.
 
 // (max, sum of exp) of one range of a row; the maximum of z is taken over the raw fp32 logits (z is monotone in them)
+// (zero_rows != null: the workgroup also clears its eighth of row blockIdx.x of that array, zero_width entries wide - the
+// q rows a mapped draft draw then fills at scattered positions)
 __global__ __launch_bounds__(SAMP_THREADS) void row_stats_kernel(const float* __restrict__ logits, int64_t row_stride, int V, double T,
-                                                                  double2* __restrict__ stats)
+                                                                  double2* __restrict__ stats, float* __restrict__ zero_rows = nullptr,
+                                                                  int64_t zero_stride = 0, int zero_width = 0)
 {
+    if (zero_rows) {
+        const int per = (zero_width + SAMP_PARTS - 1) / SAMP_PARTS;
+        const int z0 = blockIdx.y * per, z1 = z0 + per < zero_width ? z0 + per : zero_width;
+        float* zr = zero_rows + (int64_t)blockIdx.x * zero_stride;
+        for (int v = z0 + threadIdx.x; v < z1; v += SAMP_THREADS) zr[v] = 0.f;
+    }
     const float* row = logits + (int64_t)blockIdx.x * row_stride;
     int g0, g1;
     part_groups(V, blockIdx.y, &g0, &g1);
@@ -247,7 +256,7 @@ struct DraftPart { double key; int32_t v, pad; };
 __global__ __launch_bounds__(SAMP_THREADS) void draft_scan_kernel(
     int V, const float* __restrict__ logits, int64_t logits_stride, double T, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t step4, uint32_t row, const double2* __restrict__ stats, float* __restrict__ q, int64_t q_stride,
-    DraftPart* __restrict__ parts)
+    DraftPart* __restrict__ parts, const int32_t* __restrict__ token_map)
 {
     const int b = blockIdx.x, part = blockIdx.y;
     const float* lrow = logits + (int64_t)b * logits_stride;
@@ -270,7 +279,7 @@ __global__ __launch_bounds__(SAMP_THREADS) void draft_scan_kernel(
             int v = g * 4 + j;
             if (v >= V) break;
             const double pv = exp((double)lrow[v] / T - m) / S;
-            qrow[v] = (float)pv;
+            qrow[token_map ? token_map[v] : v] = (float)pv;     // (a mapped row was cleared by the statistics kernel)
             if (!(pv > 0.0)) continue;
             const double u = ((double)(words[j] >> 9) + 0.5) * (1.0 / 8388608.0);
             const double key = pv / (-log(u));
@@ -282,13 +291,14 @@ __global__ __launch_bounds__(SAMP_THREADS) void draft_scan_kernel(
 }
 
 __global__ void draft_merge_kernel(int B, const DraftPart* __restrict__ parts, int32_t* __restrict__ tok_a, int stride_a,
-                                   int32_t* __restrict__ tok_b, int stride_b)
+                                   int32_t* __restrict__ tok_b, int stride_b, const int32_t* __restrict__ token_map)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     double key = -1.0;
     int v = -1;
     for (int i = 0; i < SAMP_PARTS; ++i) argmax_merge(key, v, parts[(int64_t)b * SAMP_PARTS + i].key, parts[(int64_t)b * SAMP_PARTS + i].v);
+    if (token_map && v >= 0) v = token_map[v];
     if (tok_a) tok_a[(int64_t)b * stride_a] = v;
     if (tok_b) tok_b[(int64_t)b * stride_b] = v;
 }
@@ -397,33 +407,55 @@ extern "C" size_t spec_draft_sample_workspace_bytes(int32_t B)
     return sample_stats_bytes(B) + specv::align_up((size_t)B * specv::SAMP_PARTS * sizeof(specv::DraftPart), 256);
 }
 
-extern "C" spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int64_t logits_row_stride,
-                                         float temperature, uint64_t seed, uint64_t step, int32_t row,
-                                         int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
-                                         float* dev_q, int64_t q_row_stride, void* dev_workspace, size_t workspace_bytes, void* stream)
+static spec_status draft_sample_launch(const char* who, int32_t B, int32_t V, const float* dev_logits, int64_t logits_row_stride,
+                                       float temperature, uint64_t seed, uint64_t step, int32_t row,
+                                       int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
+                                       float* dev_q, int64_t q_row_stride, const int32_t* dev_token_map, int32_t q_width,
+                                       void* dev_workspace, size_t workspace_bytes, void* stream)
 {
     using namespace specv;
-    if (B < 1 || V < 1 || row < 0 || row > SPEC_MAX_DRAFT) { set_error("spec_draft_sample: B, V or row out of range"); return SPEC_EINVAL; }
-    if (!(temperature > 0.f)) { set_error("spec_draft_sample: temperature must be > 0"); return SPEC_EINVAL; }
-    if (step >= (1ull << 30)) { set_error("spec_draft_sample: step must be < 2^30"); return SPEC_EINVAL; }
-    if (!dev_logits || !dev_q || (!dev_tokens_a && !dev_tokens_b)) { set_error("spec_draft_sample: null pointer"); return SPEC_EINVAL; }
-    if (logits_row_stride < V || q_row_stride < V || (dev_tokens_a && stride_a < 1) || (dev_tokens_b && stride_b < 1)) {
-        set_error("spec_draft_sample: a row stride is smaller than the row"); return SPEC_EINVAL;
+    if (B < 1 || V < 1 || row < 0 || row > SPEC_MAX_DRAFT) { set_error("%s: B, V or row out of range", who); return SPEC_EINVAL; }
+    if (!(temperature > 0.f)) { set_error("%s: temperature must be > 0", who); return SPEC_EINVAL; }
+    if (step >= (1ull << 30)) { set_error("%s: step must be < 2^30", who); return SPEC_EINVAL; }
+    if (!dev_logits || !dev_q || (!dev_tokens_a && !dev_tokens_b)) { set_error("%s: null pointer", who); return SPEC_EINVAL; }
+    if (logits_row_stride < V || q_row_stride < q_width || (dev_tokens_a && stride_a < 1) || (dev_tokens_b && stride_b < 1)) {
+        set_error("%s: a row stride is smaller than the row", who); return SPEC_EINVAL;
     }
-    if (!dev_workspace || workspace_bytes < spec_draft_sample_workspace_bytes(B)) { set_error("spec_draft_sample: workspace missing or too small"); return SPEC_EINVAL; }
+    if (!dev_workspace || workspace_bytes < spec_draft_sample_workspace_bytes(B)) { set_error("%s: workspace missing or too small", who); return SPEC_EINVAL; }
     hipStream_t s = (hipStream_t)stream;
     prof_mark(PC_OTHER, s);
     double2* stats = (double2*)dev_workspace;
     DraftPart* parts = (DraftPart*)((char*)dev_workspace + sample_stats_bytes(B));
     const double T = (double)temperature;
-    row_stats_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, logits_row_stride, V, T, stats);
+    row_stats_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(dev_logits, logits_row_stride, V, T, stats,
+                                                                           dev_token_map ? dev_q : nullptr, q_row_stride, q_width);
     draft_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(V, dev_logits, logits_row_stride, T, (uint32_t)seed,
                                                                             (uint32_t)(seed >> 32), (uint32_t)(step * 4u), (uint32_t)row, stats,
-                                                                            dev_q, q_row_stride, parts);
-    draft_merge_kernel<<<(unsigned)cdiv(B, 256), 256, 0, s>>>(B, parts, dev_tokens_a, stride_a, dev_tokens_b, stride_b);
+                                                                            dev_q, q_row_stride, parts, dev_token_map);
+    draft_merge_kernel<<<(unsigned)cdiv(B, 256), 256, 0, s>>>(B, parts, dev_tokens_a, stride_a, dev_tokens_b, stride_b, dev_token_map);
     SPEC_LAUNCH_CHECK("draft sampling kernels");
     prof_mark(PC_DRAFT_SAMPLE, s);
     return SPEC_OK;
+}
+
+extern "C" spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int64_t logits_row_stride,
+                                         float temperature, uint64_t seed, uint64_t step, int32_t row,
+                                         int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
+                                         float* dev_q, int64_t q_row_stride, void* dev_workspace, size_t workspace_bytes, void* stream)
+{
+    return draft_sample_launch("spec_draft_sample", B, V, dev_logits, logits_row_stride, temperature, seed, step, row, dev_tokens_a, stride_a,
+                               dev_tokens_b, stride_b, dev_q, q_row_stride, nullptr, V, dev_workspace, workspace_bytes, stream);
+}
+
+extern "C" spec_status spec_draft_sample_mapped(int32_t B, int32_t V_d, const float* dev_logits, int64_t logits_row_stride,
+                                                float temperature, uint64_t seed, uint64_t step, int32_t row,
+                                                int32_t* dev_tokens_a, int32_t stride_a, int32_t* dev_tokens_b, int32_t stride_b,
+                                                float* dev_q, int64_t q_row_stride, const int32_t* dev_token_map, int32_t V_full,
+                                                void* dev_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!dev_token_map || V_full < V_d) { specv::set_error("spec_draft_sample_mapped: no token map, or V_full below V_d"); return SPEC_EINVAL; }
+    return draft_sample_launch("spec_draft_sample_mapped", B, V_d, dev_logits, logits_row_stride, temperature, seed, step, row, dev_tokens_a,
+                               stride_a, dev_tokens_b, stride_b, dev_q, q_row_stride, dev_token_map, V_full, dev_workspace, workspace_bytes, stream);
 }
 
 namespace specv {

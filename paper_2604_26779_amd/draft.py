@@ -9,8 +9,14 @@ from . import binding as sv
 
 
 class DraftLoop:
-    def __init__(self, draft_session, B, k):
+    def __init__(self, draft_session, B, k, token_map=None, target_vocab=None):
+        """token_map [head_vocab] int32 device tensor + target_vocab: for a draft whose head covers a subset of the target's
+        vocabulary (cfg head_vocab): its drafts are written as target ids and q over the target's vocabulary."""
         self.sess, self.B, self.k = draft_session, int(B), int(k)
+        self.token_map = token_map
+        self.head_vocab = int(draft_session.cfg.get("head_vocab", 0))
+        assert (self.head_vocab > 0) == (token_map is not None), "a draft with a reduced head needs its token map (and only such a draft)"
+        self.q_width = int(target_vocab) if token_map is not None else draft_session.cfg["vocab"]
         dev = draft_session.device
         self.feed = torch.zeros(B, dtype=torch.int32, device=dev)          # the single token of passes 2..k
         self.ones = torch.ones(B, dtype=torch.int32, device=dev)
@@ -33,9 +39,10 @@ class DraftLoop:
 
         Fills self.drafts [B, k] and q_out; the draft's cache grows by P + k - 1 positions."""
         sess, B, k = self.sess, self.B, self.k
-        V = sess.cfg["vocab"]
+        V = self.head_vocab or sess.cfg["vocab"]                      # entries of the draft's logits rows
+        W = self.q_width                                              # entries of a q row
         P = pending.shape[1]
-        assert q_out.shape == (B, k, V) and q_out.is_contiguous() and pending.is_contiguous()
+        assert q_out.shape == (B, k, W) and q_out.is_contiguous() and pending.is_contiguous()
         if self.fused:
             assert pending_hidden is not None and pending_hidden.is_contiguous()
             if self.hid_first is None or self.hid_first.shape[1] != P:
@@ -59,9 +66,14 @@ class DraftLoop:
                 else:
                     logits = sess.forward(seq_ids, self.feed.view(B, 1), stream)        # [B, 1, V]
                 last, stride = logits.data_ptr(), V
-            sv.spec_draft_sample(B, V, last, stride, temperature, seed, step, i,
-                                 self.drafts.data_ptr() + 4 * i, k, self.feed, 1,
-                                 q_out.data_ptr() + 4 * i * V, k * V, stream, self.sample_ws)
+            if self.token_map is not None:
+                sv.spec_draft_sample_mapped(B, V, last, stride, temperature, seed, step, i,
+                                            self.drafts.data_ptr() + 4 * i, k, self.feed, 1,
+                                            q_out.data_ptr() + 4 * i * W, k * W, self.token_map, W, stream, self.sample_ws)
+            else:
+                sv.spec_draft_sample(B, V, last, stride, temperature, seed, step, i,
+                                     self.drafts.data_ptr() + 4 * i, k, self.feed, 1,
+                                     q_out.data_ptr() + 4 * i * V, k * V, stream, self.sample_ws)
             fed = P if i == 0 else 1
             sv.spec_commit_kv(sess.kv, B, fed - 1, seq_ids, self.ones if fed == 2 else self._full(fed - 1), None, None, stream)
         return self.drafts
@@ -84,10 +96,11 @@ class RolloutLoop:
     rejection sampling -> commit -> roll-back of the draft's cache -> next step's inputs.  Only call order and
     buffers are handled here."""
 
-    def __init__(self, target_session, draft_session, B, k, tap_layers=None):
-        """tap_layers: for a draft with fuse_taps, the target layers whose output it is fed."""
+    def __init__(self, target_session, draft_session, B, k, tap_layers=None, token_map=None):
+        """tap_layers: for a draft with fuse_taps, the target layers whose output it is fed; token_map: for a draft with a
+        reduced head, its entries' ids in the target's vocabulary."""
         self.t, self.B, self.k = target_session, int(B), int(k)
-        self.loop = DraftLoop(draft_session, B, k)
+        self.loop = DraftLoop(draft_session, B, k, token_map=token_map, target_vocab=target_session.cfg["vocab"])
         dev = target_session.device
         V = target_session.cfg["vocab"]
         self.tokens = torch.zeros((B, k + 1), dtype=torch.int32, device=dev)
@@ -245,14 +258,14 @@ class ContinuousPairRollout:
     order and buffers are handled here."""
 
     def __init__(self, target_session, draft_session, B, k, slot_seq, target_len, queue, prev_token, first_token, seq_hidden=None,
-                 tap_layers=None):
+                 tap_layers=None, token_map=None):
         """seq_hidden [n_seqs, 2, d] fp32: for a draft with hidden-state input, every sequence's own pair of verifier
         hidden states (the positions before its last prompt token and before its first input); for a draft with
         fuse_taps = n they are features, [n_seqs, 2, n * d], and tap_layers names the n target layers."""
         self.t, self.d, self.B, self.k = target_session, draft_session, int(B), int(k)
         dev = target_session.device
         n_seqs = int(target_len.shape[0])
-        self.loop = DraftLoop(draft_session, B, k)
+        self.loop = DraftLoop(draft_session, B, k, token_map=token_map, target_vocab=target_session.cfg["vocab"])
         self.fused = self.loop.fused
         assert not self.fused or seq_hidden is not None, "a draft with hidden-state input needs every sequence's own pair of hidden states"
         self.tap_layers = tuple(int(l) for l in tap_layers) if self.loop.taps else None

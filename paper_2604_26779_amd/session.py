@@ -94,7 +94,7 @@ class VerifySession:
     def step_buffers(self, B, k):
         key = (B, k)
         if key not in self._bufs:
-            V, dev = self.cfg["vocab"], self.device
+            V, dev = self.cfg.get("head_vocab", 0) or self.cfg["vocab"], self.device      # entries of a logits row
             ws_bytes = sv.spec_verify_workspace_bytes(self.model, self.kv, B, k)
             if ws_bytes == 0:
                 raise ValueError("spec_verify_workspace_bytes rejected B=%d k=%d" % (B, k))

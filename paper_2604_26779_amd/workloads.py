@@ -154,7 +154,11 @@ class DraftPairWorkload(DeviceWorkload):
             at += need
         prev = torch.from_numpy(rng.integers(0, self.cfg["vocab"], size=B).astype(np.int32)).to(device)
         self.pending = torch.stack([prev, self.tokens[:, 0]], dim=1).contiguous()
-        self.loop = DraftLoop(self.dsess, B, k)
+        # a draft with a reduced head: which target tokens its entries are
+        self.token_map = None
+        if self.draft_cfg.get("head_vocab", 0):
+            self.token_map = torch.from_numpy(si.make_token_map(self.draft_cfg, seed=seed + 29)).to(device)
+        self.loop = DraftLoop(self.dsess, B, k, token_map=self.token_map, target_vocab=self.cfg["vocab"])
         # a draft with hidden-state input: the target's hidden states before the two pending tokens (synthetic)
         self.pending_hidden = None
         self.tap_layers = tuple(self.wl["tap_layers"]) if self.draft_cfg.get("fuse_taps", 0) else None

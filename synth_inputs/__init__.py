@@ -58,6 +58,13 @@ MODELS = {
     "draft1l_eagle3_8b_bf16": dict(n_layers=1, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
                                    vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=1, fuse_hidden=1,
                                    fuse_taps=3),
+    # The same with the reduced draft vocabulary of that design: an untied head over a subset of the target's tokens.
+    "draft_eagle3r_small_bf16": dict(n_layers=1, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1792,
+                                     vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0, fuse_hidden=1,
+                                     fuse_taps=3, head_vocab=992),
+    "draft1l_eagle3r_8b_bf16": dict(n_layers=1, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=14336,
+                                    vocab=128256, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0, fuse_hidden=1,
+                                    fuse_taps=3, head_vocab=32000),
     # A four-layer target for it at the small widths (taps after layers 1, 2 and 4).
     "small4_bf16": dict(n_layers=4, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=1280,
                         vocab=4000, rope_theta=5.0e5, rms_eps=1.0e-5, dtype="bf16", tied_head=0),
@@ -88,8 +95,10 @@ WORKLOADS["draft_pair_fused_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_
 WORKLOADS["draft_pair_eagle3_b64_ctx4096_k5"] = dict(model="llama8b_bf16", draft_model="draft1l_eagle3_8b_bf16", B=64, k=5,
                                                      ctx_lo=4096, ctx_hi=4096, noise_std=0.0, temperature=1.0,
                                                      tap_layers=(2, 16, 29))
+WORKLOADS["draft_pair_eagle3r_b64_ctx4096_k5"] = dict(WORKLOADS["draft_pair_eagle3_b64_ctx4096_k5"], draft_model="draft1l_eagle3r_8b_bf16")
 WORKLOADS["draft_pair_eagle3_small_b5_k4"] = dict(model="small4_bf16", draft_model="draft_eagle3_small_bf16", B=5, k=4, ctx_lo=20,
                                                   ctx_hi=600, noise_std=0.0, temperature=0.9, tap_layers=(1, 2, 4))
+WORKLOADS["draft_pair_eagle3r_small_b5_k4"] = dict(WORKLOADS["draft_pair_eagle3_small_b5_k4"], draft_model="draft_eagle3r_small_bf16")
 WORKLOADS["draft_pair_fused_small_b5_k4"] = dict(model="small_bf16", draft_model="draft_fused_small_bf16", B=5, k=4, ctx_lo=20,
                                                  ctx_hi=600, noise_std=0.0, temperature=0.9)
 WORKLOADS["draft_pair_small_b5_k4"] = dict(model="small_bf16", draft_model="draft_small_bf16", B=5, k=4, ctx_lo=20,
@@ -161,7 +170,7 @@ def weight_shapes(cfg):
             out += [(f"l{l}.wg", (F, d)), (f"l{l}.wu", (F, d)), (f"l{l}.wd", (d, F))]
     out.append(("final_norm", (d,)))
     if not cfg.get("tied_head", 0):
-        out.append(("head", (V, d)))
+        out.append(("head", (cfg.get("head_vocab", 0) or V, d)))
     if cfg.get("fuse_hidden", 0):      # a draft model that also takes the verifier's hidden states
         out += [("w_fuse", (d, 2 * d)), ("fuse_e_norm", (d,)), ("fuse_h_norm", (d,))]
         if cfg.get("fuse_taps", 0):    # ... at several depths: their projection down to d channels
@@ -336,6 +345,12 @@ def noisy_draft_distribution(logits_row, noise, temperature):
     z = z - z.max(axis=-1, keepdims=True)
     e = np.exp(z)
     return (e / e.sum(axis=-1, keepdims=True)).astype(np.float32)
+
+
+def make_token_map(cfg, seed=DEFAULT_SEED):
+    """Which tokens of the vocabulary a reduced draft head (cfg head_vocab) covers: a seeded subset, increasing, int32."""
+    rng = np.random.Generator(np.random.Philox(int(seed)))
+    return np.sort(rng.permutation(cfg["vocab"])[:cfg["head_vocab"]]).astype(np.int32)
 
 
 def device_draft_step(logits_row, std, temperature, generator):

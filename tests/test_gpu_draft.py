@@ -98,6 +98,8 @@ def _setup_pair(name, seed=7):
     # (a draft fed multi-layer features: that many states side by side)
     width = cfg_t["d_model"] * max(1, int(cfg_d.get("fuse_taps", 0)))
     out["pend_hidden"] = (rng.standard_normal((B, 2, width)) * 1.5).astype(np.float32) if cfg_d.get("fuse_hidden", 0) else None
+    # (a draft with a reduced head: which target tokens its entries are)
+    out["token_map"] = si.make_token_map(cfg_d, seed=seed + 29) if cfg_d.get("head_vocab", 0) else None
     for tag, cfg, clen, s in (("t", cfg_t, ctx, seed), ("d", cfg_d, ctx - 1, seed + 17)):
         weights = random_norm_gains(si.make_weights(cfg, seed=s), s)
         kv = si.make_logical_kv(cfg, clen, seed=s)
@@ -142,7 +144,7 @@ def _compare_drafts(x_gpu, q_gpu, x_or, q_or, keys, tol):
 
 
 @pytest.mark.parametrize("name", ["draft_pair_tiny_b4_k3", "draft_pair_small_b5_k4", "draft_pair_fused_small_b5_k4",
-                                  "draft_pair_eagle3_small_b5_k4"])
+                                  "draft_pair_eagle3_small_b5_k4", "draft_pair_eagle3r_small_b5_k4"])
 def test_draft_loop_and_pair_step_parity(name):
     from paper_2604_26779_amd.draft import DraftLoop
     S = _setup_pair(name)
@@ -157,7 +159,7 @@ def test_draft_loop_and_pair_step_parity(name):
 
     # ---- oracle: draft loop, verify forward on its drafts, rejection sampling, commit, roll-back
     x_or, q_or, _, dlen_or, keys = oracle_draft.draft_loop(d["cfg"], d["w_or"], d["kv_or"], pending, d["ctx"], k, T, seed, step,
-                                                           S["pend_hidden"])
+                                                           S["pend_hidden"], token_map=S["token_map"], v_full=V)
     tokens_or = np.concatenate([t0[:, None], x_or], axis=1).astype(np.int32)
     logits_or, _ = of.verify_forward(t["cfg"], t["w_or"], t["kv_or"], tokens_or, t["ctx"])
     n_or, out_or, pqu, rkeys = oracle_sampler.reject_sample(logits_or.astype(np.float32), q_or, x_or, T, seed, step, debug=True)
@@ -173,8 +175,8 @@ def test_draft_loop_and_pair_step_parity(name):
     d["book"].truncate(ids, np.array(tlen_or) - 1)
 
     # ---- HIP path
-    loop = DraftLoop(d["sess"], B, k)
-    q = torch.zeros((B, k, V), dtype=torch.float32, device="cuda")
+    loop = DraftLoop(d["sess"], B, k, token_map=None if S["token_map"] is None else torch.from_numpy(S["token_map"]).cuda(), target_vocab=V)
+    q = torch.full((B, k, V), 0.5, dtype=torch.float32, device="cuda")        # stale values: a mapped draw must clear its rows
     drafts = loop.run(seq_ids, torch.from_numpy(pending).cuda(), q, T, seed, step,
                       pending_hidden=None if S["pend_hidden"] is None else torch.from_numpy(S["pend_hidden"]).cuda())
     tokens = torch.cat([torch.from_numpy(t0).cuda().view(B, 1), drafts], dim=1).contiguous()
@@ -214,7 +216,7 @@ def test_draft_loop_and_pair_step_parity(name):
 
 
 @pytest.mark.parametrize("name,n_steps", [("draft_pair_tiny_b4_k3", 4), ("draft_pair_small_b5_k4", 3), ("draft_pair_fused_small_b5_k4", 3),
-                                          ("draft_pair_eagle3_small_b5_k4", 3)])
+                                          ("draft_pair_eagle3_small_b5_k4", 3), ("draft_pair_eagle3r_small_b5_k4", 3)])
 def test_rollout_of_several_steps_against_oracle(name, n_steps):
     """Consecutive steps with no host round trip: per step and sequence, accept length and emitted tokens equal the
     oracle's until the first decision the oracle marks as fragile (then that sequence is left out from there on);
@@ -226,8 +228,10 @@ def test_rollout_of_several_steps_against_oracle(name, n_steps):
     seed = 0x0123456789ABCDEF
     t0 = S["batch"]["tokens0"]
     hist, _, _, ctx_or = oracle_draft.rollout(t["cfg"], t["w_or"], d["cfg"], d["w_or"], t["kv_or"], d["kv_or"], S["prev"], t0, t["ctx"],
-                                              k, T, seed, n_steps, pending_hidden=S["pend_hidden"], tap_layers=S["wl"].get("tap_layers"))
-    roll = RolloutLoop(t["sess"], d["sess"], B, k, tap_layers=S["wl"].get("tap_layers"))
+                                              k, T, seed, n_steps, pending_hidden=S["pend_hidden"], tap_layers=S["wl"].get("tap_layers"),
+                                              token_map=S["token_map"])
+    roll = RolloutLoop(t["sess"], d["sess"], B, k, tap_layers=S["wl"].get("tap_layers"),
+                       token_map=None if S["token_map"] is None else torch.from_numpy(S["token_map"]).cuda())
     roll.start(torch.from_numpy(S["prev"]).cuda(), torch.from_numpy(t0).cuda(),
                None if S["pend_hidden"] is None else torch.from_numpy(S["pend_hidden"]).cuda())
     acc = torch.full((n_steps, B), -9, dtype=torch.int32, device="cuda")
@@ -399,3 +403,31 @@ def test_multi_layer_feature_taps_and_feature_fed_draft_pass():
     with pytest.raises(sv.SpecError):                                # taps from a model that itself needs a hidden-state input
         dsess.forward(seq, d_tokens, tap_layers=(1,), taps_out=hid)
     dsess.close()
+
+
+@pytest.mark.parametrize("B,Vd,V,temperature", [(7, 1000, 4001, 0.8), (64, 32000, 128256, 1.0), (3, 5, 5, 1.3)])
+def test_mapped_draft_sample_parity(B, Vd, V, temperature):
+    """spec_draft_sample_mapped (a draft head over a subset of the vocabulary) against the oracle: tokens as target ids and q
+    over the whole vocabulary, exact - the rows are cleared by the call itself (they start out holding stale values) and
+    only the row of this draft position is touched."""
+    from paper_2604_26779_amd import binding as sv
+    rng = np.random.Generator(np.random.Philox(B + V))
+    logits = (rng.standard_normal((B, Vd)) * 2.5).astype(np.float32)
+    tmap = np.sort(rng.permutation(V)[:Vd]).astype(np.int32)
+    seed, step, row, k = 0x0F1E2D3C4B5A6978, 6, 1, 3
+    x_or, q_or = oracle_sampler.draft_sample_mapped(logits, tmap, V, temperature, seed, step, row)
+    q = torch.full((B, k, V), 0.25, dtype=torch.float32, device="cuda")
+    tok_a = torch.full((B, k + 1), -7, dtype=torch.int32, device="cuda")
+    tok_b = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    sv.spec_draft_sample_mapped(B, Vd, torch.from_numpy(logits).cuda(), Vd, temperature, seed, step, row, tok_a.data_ptr() + 4 * (row + 1), k + 1,
+                                tok_b, 1, q.data_ptr() + 4 * row * V, k * V, torch.from_numpy(tmap).cuda(), V)
+    torch.cuda.synchronize()
+    assert np.array_equal(tok_b.cpu().numpy(), x_or) and np.array_equal(tok_a[:, row + 1].cpu().numpy(), x_or)
+    q_gpu = q[:, row, :].cpu().numpy()
+    assert np.all(q[:, [i for i in range(k) if i != row], :].cpu().numpy() == 0.25)
+    outside = np.setdiff1d(np.arange(V), tmap)
+    assert np.all(q_gpu[:, outside] == 0)
+    assert np.max(np.abs(q_gpu[:, tmap] - q_or[:, tmap]) / (q_or[:, tmap] + 1e-30)) < 1.3e-7
+    with pytest.raises(sv.SpecError):                       # q rows narrower than the target's vocabulary
+        sv.spec_draft_sample_mapped(B, Vd, torch.from_numpy(logits).cuda(), Vd, temperature, seed, step, row, None, 1, tok_b, 1, q, V - 1,
+                                    torch.from_numpy(tmap).cuda(), V)
