@@ -228,13 +228,14 @@ def test_moe_slice_full_size_8bit_matrices_and_cache():
     _check_workload("moe235b_slice_w8kv8_b128_ctx4k-32k_k3", [3], moe_margin=1e-3, more_picks=MOE_PICKS)
 
 
-@pytest.mark.parametrize("name", ["draft_pair_b64_ctx4096_k5", "draft_pair_eagle3_b64_ctx4096_k5"])
+@pytest.mark.parametrize("name", ["draft_pair_b64_ctx4096_k5", "draft_pair_eagle3_b64_ctx4096_k5", "draft_pair_eagle3r_b64_ctx4096_k5"])
 def test_draft_pair_full_size_on_sampled_sequences(name):
     """Single-layer draft (8B widths, tied 128256-token head) run 5 times + 8B-shaped verify, B = 64, contexts 4096:
     the whole step on the GPU, then for two sampled sequences the oracle's draft loop, verify forward and rejection
     sampling on the same inputs (a sequence's results depend only on its own rows, cache and random-counter index b,
     so the oracle is given the sequence's batch index through a padded batch).  The second workload's draft is fed
-    multi-layer features: its first pass projects them, the chained passes take its own state."""
+    multi-layer features: its first pass projects them, the chained passes take its own state.  The third's head covers
+    32000 of the tokens: the draw runs over the head's rows and q is laid out over the target's vocabulary."""
     from oracle import draft as oracle_draft
     from oracle import sampler as oracle_sampler
     from paper_2604_26779_amd.workloads import DraftPairWorkload
@@ -243,6 +244,7 @@ def test_draft_pair_full_size_on_sampled_sequences(name):
     V = cfg_t["vocab"]
     seed, step = wl.seed, 2
     feats = None if wl.pending_hidden is None else wl.pending_hidden.cpu().numpy()
+    tmap = None if wl.token_map is None else wl.token_map.cpu().numpy()
     drafts = wl.loop.run(wl.seq_ids, wl.pending, wl.q, T, seed, step, pending_hidden=wl.pending_hidden)
     wl.tokens[:, 1:] = drafts
     logits, n, out = wl.sess.step(wl.seq_ids, wl.tokens, wl.q, drafts, T, seed, step)
@@ -276,12 +278,20 @@ def test_draft_pair_full_size_on_sampled_sequences(name):
                 own = hid[:, -1:, :]
             kv_run = [[(np.concatenate([kv_run[0][0][0], new_kv[0][0][0]]), np.concatenate([kv_run[0][0][1], new_kv[0][1][0]]))]]
             clen = clen + feed.shape[1]
-            pad = np.zeros((b + 1, V), dtype=np.float32)
+            pad = np.zeros((b + 1, lg.shape[-1]), dtype=np.float32)
             pad[b] = lg[0, -1].astype(np.float32)
-            xs, qs, keys = oracle_sampler.draft_sample(pad, T, seed, step, i, debug=True)
+            if tmap is None:
+                xs, qs, keys = oracle_sampler.draft_sample(pad, T, seed, step, i, debug=True)
+                on = slice(None)
+            else:
+                xs, qs, keys = oracle_sampler.draft_sample_mapped(pad, tmap, V, T, seed, step, i, debug=True)
+                on = tmap
+                off = np.ones(V, dtype=bool)
+                off[tmap] = False
+                assert not got_q[b, i].cpu().numpy()[off].any() and not qs[b][off].any(), (b, i)
             x_or[i], q_or[i] = xs[b], qs[b]
-            lq_g = torch.log(got_q[b, i]).cpu().numpy().astype(np.float64)
-            lq_o = np.log(q_or[i].astype(np.float64))
+            lq_g = torch.log(got_q[b, i].cpu()[on]).numpy().astype(np.float64)
+            lq_o = np.log(q_or[i][on].astype(np.float64))
             assert np.max(np.abs(lq_g - lq_o) - 2 * (2e-2 + 1e-2 * np.abs(lq_o))) <= 0, (b, i)
             if got_drafts[b, i] != x_or[i]:
                 assert keys[b, 0] - keys[b, 1] <= 1e-3 * keys[b, 0], ("draft token differs", b, i)

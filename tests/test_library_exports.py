@@ -70,6 +70,17 @@ def test_argument_checks_of_the_draft_side_calls(sv):
                 dict(ta=None), dict(lstride=9), dict(qstride=9), dict(sa=0), dict(ws=None), dict(ws_bytes=8)):
         assert draft(**bad) == sv.SPEC_EINVAL, bad
         assert "spec_draft_sample" in sv.spec_last_error()
+    # the draw of a head over a subset of the vocabulary: the same checks, and a map and a full width that fit
+    okm = dict(ok, V=6, lstride=6, tmap=1, vfull=10)
+
+    def mapped(**kw):
+        a = dict(okm, **kw)
+        return L.spec_draft_sample_mapped(a["B"], a["V"], a["logits"], a["lstride"], a["T"], a["seed"], a["step"], a["row"], a["ta"], a["sa"],
+                                          a["tb"], a["sb"], a["q"], a["qstride"], a["tmap"], a["vfull"], a.get("ws", 1), a.get("ws_bytes", 1 << 20), None)
+    for bad in (dict(B=0), dict(V=0), dict(T=0.0), dict(logits=None), dict(q=None), dict(tmap=None), dict(vfull=5), dict(qstride=9),
+                dict(lstride=5), dict(ws=None), dict(ws_bytes=8)):
+        assert mapped(**bad) == sv.SPEC_EINVAL, bad
+        assert "spec_draft_sample_mapped" in sv.spec_last_error()
     assert L.spec_kv_truncate(None, 1, None, None, -1, None, None) == sv.SPEC_EINVAL
     assert L.spec_next_step_inputs(0, 3, 1, 1, 1, None, None) == sv.SPEC_EINVAL
     assert L.spec_next_step_inputs(2, 16, 1, 1, 1, None, None) == sv.SPEC_EINVAL
@@ -113,3 +124,5 @@ def test_argument_checks_of_the_rollout_side_calls(sv):
                  dtype="bf16", tied_head=1, fuse_hidden=1)
     assert sv.spec_model_weight_count(fused) == 1 + 9 + 1 + 3
     assert sv.spec_model_weight_count(dict(fused, fuse_taps=3)) == 1 + 9 + 1 + 3 + 1
+    # a head over a subset of the vocabulary is a matrix of its own
+    assert sv.spec_model_weight_count(dict(fused, fuse_taps=3, tied_head=0, head_vocab=6)) == 1 + 9 + 1 + 1 + 3 + 1
