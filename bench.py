@@ -63,6 +63,26 @@ def run_steps(wl, sv, torch, n_steps, accept_out, step0, marks=None):
                 marks.append(ev)
 
 
+def replay_ms(sv, torch, record, reps=3):
+    """Record what `record()` launches into a HIP graph on a side stream, replay it once untimed, then time `reps` replays."""
+    side = torch.cuda.Stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(side):
+        sv.spec_graph_capture_begin(side)
+        record()
+        graph = sv.spec_graph_capture_end(side)
+        sv.spec_graph_launch(graph, side)
+        side.synchronize()
+        e0.record(side)
+        for _ in range(reps):
+            sv.spec_graph_launch(graph, side)
+        e1.record(side)
+        side.synchronize()
+    torch.cuda.synchronize()
+    sv.spec_graph_destroy(graph)
+    return e0.elapsed_time(e1) / reps
+
+
 def hbm_ceiling(sv, torch, nbytes=1 << 30, reps=5):
     """Measured streaming ceiling: the library's plain read and copy kernels over a buffer of known size."""
     src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -344,10 +364,25 @@ def main():
     accepted_drafts = float(accept[:K].sum().item())
     tokens_per_s = produced / (ms_per_step * K / 1e3)
 
-    # instrumented run of the same K steps: HIP events around every kernel class
+    # draft / verify split of a pair: events between the two halves of every step, launched kernel by kernel, and the
+    # draft loop alone replayed from a HIP graph (K x (cache restore + draft loop) minus K x cache restore)
     marks = [] if pair else None
+    draft_loop_graph_ms = None
+    if pair:
+        run_steps(wl, sv, torch, K, accept, 1000, marks)
+        torch.cuda.synchronize()
+
+        def draft_only(with_loop):
+            for i in range(K):
+                wl.restore()
+                if with_loop:
+                    wl.loop.run(wl.seq_ids, wl.pending, wl.q, wl.wl["temperature"], wl.seed, 1000 + i, pending_hidden=wl.pending_hidden)
+                    wl.tokens[:, 1:] = wl.loop.drafts
+        draft_loop_graph_ms = (replay_ms(sv, torch, lambda: draft_only(True)) - replay_ms(sv, torch, lambda: draft_only(False))) / K
+
+    # instrumented run of the same K steps: HIP events around every kernel class
     sv.spec_profile_begin(K * (400 + (200 if pair else 0)) + 64)
-    run_steps(wl, sv, torch, K, accept, 1000, marks)
+    run_steps(wl, sv, torch, K, accept, 1000)
     prof = sv.spec_profile_end()
     per_step = {name: ms / K for name, (ms, cnt) in prof.items()}
     launches = {name: cnt / K for name, (ms, cnt) in prof.items()}
@@ -407,6 +442,7 @@ def main():
         out["draft_verify_split_ms"] = {
             "draft_loop": round(sum(e[0].elapsed_time(e[1]) for e in marks) / K, 4),
             "verify_sample_commit_rollback": round(sum(e[1].elapsed_time(e[2]) for e in marks) / K, 4),
+            "draft_loop_replayed_from_a_graph": round(draft_loop_graph_ms, 4),
             "draft_model": wl.wl["draft_model"], "draft_passes": k}
         # sustained rollout: consecutive steps, each feeding the next on the device (no cache restore, no host sync)
         from paper_2604_26779_amd.draft import RolloutLoop
