@@ -333,8 +333,9 @@ spec_status spec_draft_sample(int32_t B, int32_t V, const float* dev_logits, int
  * (q_row_stride >= V_full) at the mapped positions with zeros everywhere else - the [B, k, V_full] array
  * spec_reject_sample takes, which then resamples tokens outside the subset from the target's own probabilities; the
  * tokens written are target ids.  Draw and random numbers as spec_draft_sample, v counting draft entries.
- * Errors as spec_draft_sample; the map's contents are not checked (an id outside [0, V_full) would be written out of
- * the row).
+ * Errors as spec_draft_sample.  The map's contents live on the device and are not validated by the call: an entry
+ * outside [0, V_full) is skipped by the kernel (its probability is written nowhere, so the row of q then sums to
+ * less than 1, and it is never drawn); repeated ids are not detected.
  */
 spec_status spec_draft_sample_mapped(int32_t B, int32_t V_d, const float* dev_logits, int64_t logits_row_stride,
                                      float temperature, uint64_t seed, uint64_t step, int32_t row,

@@ -256,7 +256,7 @@ struct DraftPart { double key; int32_t v, pad; };
 __global__ __launch_bounds__(SAMP_THREADS) void draft_scan_kernel(
     int V, const float* __restrict__ logits, int64_t logits_stride, double T, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t step4, uint32_t row, const double2* __restrict__ stats, float* __restrict__ q, int64_t q_stride,
-    DraftPart* __restrict__ parts, const int32_t* __restrict__ token_map)
+    DraftPart* __restrict__ parts, const int32_t* __restrict__ token_map, int q_width)
 {
     const int b = blockIdx.x, part = blockIdx.y;
     const float* lrow = logits + (int64_t)b * logits_stride;
@@ -279,7 +279,9 @@ __global__ __launch_bounds__(SAMP_THREADS) void draft_scan_kernel(
             int v = g * 4 + j;
             if (v >= V) break;
             const double pv = exp((double)lrow[v] / T - m) / S;
-            qrow[token_map ? token_map[v] : v] = (float)pv;     // (a mapped row was cleared by the statistics kernel)
+            const int at = token_map ? token_map[v] : v;         // (a mapped row was cleared by the statistics kernel)
+            if ((unsigned)at >= (unsigned)q_width) continue;     // a map entry outside the target's vocabulary: never written, never drawn
+            qrow[at] = (float)pv;
             if (!(pv > 0.0)) continue;
             const double u = ((double)(words[j] >> 9) + 0.5) * (1.0 / 8388608.0);
             const double key = pv / (-log(u));
@@ -431,7 +433,7 @@ static spec_status draft_sample_launch(const char* who, int32_t B, int32_t V, co
                                                                            dev_token_map ? dev_q : nullptr, q_row_stride, q_width);
     draft_scan_kernel<<<dim3((unsigned)B, SAMP_PARTS), SAMP_THREADS, 0, s>>>(V, dev_logits, logits_row_stride, T, (uint32_t)seed,
                                                                             (uint32_t)(seed >> 32), (uint32_t)(step * 4u), (uint32_t)row, stats,
-                                                                            dev_q, q_row_stride, parts, dev_token_map);
+                                                                            dev_q, q_row_stride, parts, dev_token_map, dev_token_map ? q_width : V);
     draft_merge_kernel<<<(unsigned)cdiv(B, 256), 256, 0, s>>>(B, parts, dev_tokens_a, stride_a, dev_tokens_b, stride_b, dev_token_map);
     SPEC_LAUNCH_CHECK("draft sampling kernels");
     prof_mark(PC_DRAFT_SAMPLE, s);

@@ -431,3 +431,19 @@ def test_mapped_draft_sample_parity(B, Vd, V, temperature):
     with pytest.raises(sv.SpecError):                       # q rows narrower than the target's vocabulary
         sv.spec_draft_sample_mapped(B, Vd, torch.from_numpy(logits).cuda(), Vd, temperature, seed, step, row, None, 1, tok_b, 1, q, V - 1,
                                     torch.from_numpy(tmap).cuda(), V)
+    # map entries outside the target's vocabulary are skipped by the kernel: nothing is written for them, they are never
+    # drawn, and the other entries keep the probabilities of the softmax over all the head's rows
+    bad = tmap.copy()
+    bad[[1, Vd // 2, Vd - 1]] = [-5, V, V + 12345]
+    valid = (bad >= 0) & (bad < V)
+    _, q_d = oracle_sampler.draft_sample(logits, temperature, seed, step, row)
+    guard = torch.full((B * k * V + 64,), 0.25, dtype=torch.float32, device="cuda")
+    q2 = guard[:B * k * V].view(B, k, V)
+    sv.spec_draft_sample_mapped(B, Vd, torch.from_numpy(logits).cuda(), Vd, temperature, seed, step, row, None, 1, tok_b, 1,
+                                q2.data_ptr() + 4 * row * V, k * V, torch.from_numpy(bad).cuda(), V)
+    torch.cuda.synchronize()
+    q2_gpu = q2[:, row, :].cpu().numpy()
+    assert np.max(np.abs(q2_gpu[:, bad[valid]] - q_d[:, valid]) / (q_d[:, valid] + 1e-30)) < 1.3e-7
+    assert np.all(q2_gpu[:, np.setdiff1d(np.arange(V), bad[valid])] == 0)
+    assert np.all(guard[B * k * V:].cpu().numpy() == 0.25) and np.all(q2[:, [i for i in range(k) if i != row], :].cpu().numpy() == 0.25)
+    assert np.all(np.isin(tok_b.cpu().numpy(), bad[valid]))
