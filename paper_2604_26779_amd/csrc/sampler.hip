@@ -480,7 +480,7 @@ __global__ void next_inputs_kernel(int B, int k, int32_t* __restrict__ tokens, c
 
 namespace specv {
 
-// pending_hidden[b] = (H[b][n-1] or its own old row 1 if n = 0, H[b][n]); one workgroup per batch entry
+// pending_hidden[b] = (H[b][n-1] or its own old row 1 if n = 0, H[b][n]); workgroup = (batch entry, 1024 channels)
 __global__ void next_hidden_kernel(int k, int d, const float* __restrict__ target_hidden, const int32_t* __restrict__ accept_len,
                                    float* __restrict__ pending_hidden)
 {
@@ -489,7 +489,8 @@ __global__ void next_hidden_kernel(int k, int d, const float* __restrict__ targe
     n = n < 0 ? 0 : (n > k ? k : n);
     const float* H = target_hidden + (int64_t)b * (k + 1) * d;
     float* p = pending_hidden + (int64_t)b * 2 * d;
-    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    const int c_end = min(d, (int)(blockIdx.y + 1) * 1024);
+    for (int c = blockIdx.y * 1024 + threadIdx.x; c < c_end; c += blockDim.x) {
         const float before_kept = n >= 1 ? H[(int64_t)(n - 1) * d + c] : p[d + c];     // read row 1 before it is overwritten
         const float before_emitted = H[(int64_t)n * d + c];
         p[c] = before_kept;
@@ -505,7 +506,7 @@ extern "C" spec_status spec_next_step_hidden(int32_t B, int32_t k, int32_t d, co
     using namespace specv;
     if (B < 1 || k < 0 || k > SPEC_MAX_DRAFT || d < 1) { set_error("spec_next_step_hidden: B, k or d out of range"); return SPEC_EINVAL; }
     if (!dev_target_hidden || !dev_accept_len || !dev_pending_hidden) { set_error("spec_next_step_hidden: null pointer"); return SPEC_EINVAL; }
-    next_hidden_kernel<<<(unsigned)B, 256, 0, (hipStream_t)stream>>>(k, d, dev_target_hidden, dev_accept_len, dev_pending_hidden);
+    next_hidden_kernel<<<dim3((unsigned)B, (unsigned)cdiv(d, 1024)), 256, 0, (hipStream_t)stream>>>(k, d, dev_target_hidden, dev_accept_len, dev_pending_hidden);
     SPEC_LAUNCH_CHECK("next_hidden_kernel");
     return SPEC_OK;
 }
