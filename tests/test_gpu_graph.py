@@ -66,6 +66,63 @@ def test_replayed_step_equals_eager_step(name):
     wl.close()
 
 
+@pytest.mark.parametrize("name", ["draft_pair_small_b5_k4", "draft_pair_fused_small_b5_k4", "draft_pair_eagle3_small_b5_k4",
+                                  "draft_pair_eagle3r_small_b5_k4"])
+def test_replayed_pair_rollout_equals_the_eager_one(name):
+    """Three consecutive steps of a draft + verify pair (draft loop, verify forward, rejection sampling, commit, roll-back of
+    the draft's cache, next inputs - with the draft's hidden-state or feature input and its reduced vocabulary where the
+    workload has them) recorded once: every replay, with eager work and synchronisations in between, gives the accept
+    lengths, emitted tokens and cache lengths of the same calls launched one by one."""
+    from paper_2604_26779_amd import binding as sv
+    from paper_2604_26779_amd.draft import RolloutLoop
+    from paper_2604_26779_amd.workloads import DraftPairWorkload
+    wl = DraftPairWorkload(name)
+    B, k, T, S = wl.B, wl.k, wl.wl["temperature"], 3
+    roll = RolloutLoop(wl.sess, wl.dsess, B, k, tap_layers=wl.tap_layers, token_map=wl.token_map)
+    acc = torch.zeros((S, B), dtype=torch.int32, device="cuda")
+    out = torch.zeros((S, B, k + 1), dtype=torch.int32, device="cuda")
+
+    def begin(stream=None):
+        wl.restore(stream)
+        roll.start(wl.pending[:, 0].contiguous(), wl.pending[:, 1].contiguous(), wl.pending_hidden)
+
+    def outputs():
+        torch.cuda.synchronize()
+        return (acc.clone(), out.clone(), wl.sess.state()["ctx_len"].copy(), wl.dsess.state()["ctx_len"].copy(),
+                wl.dsess.state()["free_stack"].copy(), roll.pending.clone())
+
+    begin()
+    roll.run(wl.seq_ids, S, T, wl.seed, 40, acc, out)
+    want = outputs()
+    assert int(want[0].sum()) > 0                                         # some drafts were accepted
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        begin(side)
+        side.synchronize()
+        wl.sess.state(), wl.dsess.state()                                 # the host mirrors are current: no read-back while recording
+        sv.spec_graph_capture_begin(side)
+        roll.run(wl.seq_ids, S, T, wl.seed, 40, acc, out, stream=side)
+        graph = sv.spec_graph_capture_end(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        acc.fill_(-3)
+        out.fill_(-3)
+        with torch.cuda.stream(side):
+            begin(side)
+            sv.spec_graph_launch(graph, side)
+            side.synchronize()
+        got = outputs()
+        for a, b in zip(got, want):
+            same = torch.equal(a, b) if isinstance(a, torch.Tensor) else np.array_equal(a, b)
+            assert same, "replay %d differs from the eager rollout" % rep
+        begin()                                                           # eager work between the replays
+        roll.run(wl.seq_ids, 1, T, wl.seed, 77)
+        torch.cuda.synchronize()
+    sv.spec_graph_destroy(graph)
+    wl.close()
+
+
 def test_forward_under_capture_never_synchronises():
     """When the host's bounds cannot show that the step fits, an eager call reads the cache state back (a
     synchronisation); a call on a stream that is being captured must not - it reports SPEC_ESTATE with nothing recorded,
