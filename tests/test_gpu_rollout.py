@@ -270,7 +270,8 @@ def test_hidden_state_pairs_follow_taken_over_slots_and_a_fused_pair_rollout_dra
         torch.cuda.synchronize()
         assert np.array_equal(d_ph.cpu().numpy(), want)
 
-    for target_name, draft_name, taps in (("small_bf16", "draft_fused_small_bf16", None), ("small4_bf16", "draft_eagle3_small_bf16", (1, 2, 4))):
+    for target_name, draft_name, taps in (("small_bf16", "draft_fused_small_bf16", None), ("small4_bf16", "draft_eagle3_small_bf16", (1, 2, 4)),
+                                          ("small4_bf16", "draft_eagle3r_small_bf16", (1, 2, 4))):       # the last: a head over a subset of the tokens
         _drain_fused_pair(rng, target_name, draft_name, taps)
 
 
@@ -300,7 +301,8 @@ def _drain_fused_pair(rng, target_name, draft_name, taps):
     first = torch.from_numpy(rng.integers(0, cfg_t["vocab"], size=n_seqs).astype(np.int32))
     seq_hidden = torch.from_numpy(rng.standard_normal((n_seqs, 2, cfg_t["d_model"] * (len(taps) if taps else 1))).astype(np.float32))
     roll = ContinuousPairRollout(tsess, dsess, slots, k, torch.arange(slots, dtype=torch.int32), torch.from_numpy(target),
-                                 torch.arange(slots, n_seqs, dtype=torch.int32), prev, first, seq_hidden=seq_hidden, tap_layers=taps)
+                                 torch.arange(slots, n_seqs, dtype=torch.int32), prev, first, seq_hidden=seq_hidden, tap_layers=taps,
+                                 token_map=torch.from_numpy(si.make_token_map(cfg_d, seed=7)).cuda() if cfg_d.get("head_vocab", 0) else None)
     live = torch.zeros(1, dtype=torch.int32, device="cuda")
     steps, taken_over = 0, 0
     while steps < 200:
@@ -319,6 +321,7 @@ def _drain_fused_pair(rng, target_name, draft_name, taps):
                     assert torch.equal(roll.pending_hidden[b].cpu(), seq_hidden[s])
                     taken_over += 1
                 assert torch.isfinite(roll.pending_hidden[b]).all()
+                assert 0 <= int(roll.tokens[b, 0].item()) < cfg_t["vocab"]
             else:
                 assert ts["ctx_len"][s] == 0 and ds["ctx_len"][s] == 0
         if int(live.item()) == 0:
